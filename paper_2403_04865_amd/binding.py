@@ -1,0 +1,203 @@
+"""ctypes binding of libslide.so: same names as include/slide.h, argument marshalling only.
+
+torch is used for device memory and streams; every step of the path runs in the library's
+HIP kernels.  Missing library => ImportError-like failure at load (no fallback).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libslide.so")
+
+
+class SlideError(RuntimeError):
+    CODES = {-1: "SLIDE_EINVAL", -2: "SLIDE_EARENA", -3: "SLIDE_EUNSUPPORTED", -4: "SLIDE_ESTATE", -5: "SLIDE_EHIP"}
+
+    def __init__(self, code, what, hip=0):
+        self.code = code
+        super().__init__(f"{what}: {self.CODES.get(code, code)}" + (f" (hipError {hip})" if code == -5 else ""))
+
+
+class _CConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("tile", "patch", "dim", "layers", "heads", "mlp_ratio", "mil_hidden",
+                                         "n_classes", "dtype", "recompute")] + \
+               [("ln_eps", C.c_float), ("want_pixel_grad", C.c_int32)]
+
+
+@dataclass
+class SlideConfig:
+    tile: int
+    patch: int
+    dim: int
+    layers: int
+    heads: int
+    mlp_ratio: int
+    mil_hidden: int
+    n_classes: int
+    dtype: int = 0          # 0 float32, 1 bfloat16
+    recompute: int = 0
+    ln_eps: float = 1e-6
+    want_pixel_grad: int = 0
+
+
+_SYMS = {
+    "slide_ctx_create": (C.c_int, [C.POINTER(_CConfig), C.POINTER(C.c_void_p)]),
+    "slide_ctx_destroy": (None, [C.c_void_p]),
+    "slide_param_count": (C.c_size_t, [C.c_void_p]),
+    "slide_param_tensors": (C.c_int, [C.c_void_p]),
+    "slide_param_name": (C.c_int, [C.c_void_p, C.c_int, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+    "slide_param_offset": (C.c_int, [C.c_void_p, C.c_char_p, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+    "slide_arena_bytes": (C.c_size_t, [C.c_void_p, C.c_int64]),
+    "slide_pool_arena_bytes": (C.c_size_t, [C.c_void_p, C.c_int64]),
+    "slide_bind": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
+    "encoder_fwd_tiles": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_void_p]),
+    "encoder_bwd_tiles": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]),
+    "mil_pool_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mil_pool_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int, C.c_void_p]),
+    "slide_step_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "slide_step_bwd": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
+    "slide_features": (C.c_void_p, [C.c_void_p]),
+    "slide_feature_grads": (C.c_void_p, [C.c_void_p]),
+    "slide_last_hip_error": (C.c_int, []),
+    "slide_prof_begin": (C.c_int, [C.c_void_p, C.c_int]),
+    "slide_prof_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "slide_kernel_name": (C.c_char_p, [C.c_int]),
+}
+
+
+def load_cdll():
+    p = lib_path()
+    if not os.path.exists(p):
+        raise OSError(f"{p} is not built: run `python -m paper_2403_04865_amd.build` (there is no fallback path)")
+    lib = C.CDLL(p)
+    for name, (res, args) in _SYMS.items():
+        f = getattr(lib, name)
+        f.restype = res
+        f.argtypes = args
+    return lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
+    return C.c_void_p(stream.cuda_stream)
+
+
+class SlideLib:
+    """One slide_ctx.  Methods carry the C ABI's names and pass torch tensors' device pointers."""
+
+    def __init__(self, cfg: SlideConfig):
+        self.lib = load_cdll()
+        self.cfg = cfg
+        cc = _CConfig(cfg.tile, cfg.patch, cfg.dim, cfg.layers, cfg.heads, cfg.mlp_ratio, cfg.mil_hidden,
+                      cfg.n_classes, cfg.dtype, cfg.recompute, cfg.ln_eps, cfg.want_pixel_grad)
+        h = C.c_void_p()
+        self._check(self.lib.slide_ctx_create(C.byref(cc), C.byref(h)), "slide_ctx_create")
+        self.ctx = h
+        self._keep = []
+
+    def __del__(self):
+        try:
+            if getattr(self, "ctx", None):
+                self.lib.slide_ctx_destroy(self.ctx)
+                self.ctx = None
+        except Exception:
+            pass
+
+    def _check(self, rc, what):
+        if rc != 0:
+            raise SlideError(rc, what, self.lib.slide_last_hip_error())
+
+    # ---- layout queries
+    def slide_param_count(self):
+        return int(self.lib.slide_param_count(self.ctx))
+
+    def param_layout(self):
+        """[(name, offset, length)] in layout order."""
+        out = []
+        buf = C.create_string_buffer(64)
+        off, ln = C.c_size_t(), C.c_size_t()
+        for i in range(self.lib.slide_param_tensors(self.ctx)):
+            self._check(self.lib.slide_param_name(self.ctx, i, buf, 64, C.byref(off), C.byref(ln)), "slide_param_name")
+            out.append((buf.value.decode(), off.value, ln.value))
+        return out
+
+    def slide_param_offset(self, name):
+        off, ln = C.c_size_t(), C.c_size_t()
+        self._check(self.lib.slide_param_offset(self.ctx, name.encode(), C.byref(off), C.byref(ln)), "slide_param_offset")
+        return off.value, ln.value
+
+    def slide_arena_bytes(self, n_tiles):
+        return int(self.lib.slide_arena_bytes(self.ctx, n_tiles))
+
+    def slide_pool_arena_bytes(self, n):
+        return int(self.lib.slide_pool_arena_bytes(self.ctx, n))
+
+    # ---- calls
+    def slide_bind(self, params, grads, arena):
+        self._keep = [params, grads, arena]
+        self._check(self.lib.slide_bind(self.ctx, _ptr(params), _ptr(grads), _ptr(arena), arena.numel() * arena.element_size()),
+                    "slide_bind")
+
+    def encoder_fwd_tiles(self, pixels, n_tiles, feats_out, save_for_bwd, stream=None):
+        self._check(self.lib.encoder_fwd_tiles(self.ctx, _ptr(pixels), n_tiles, _ptr(feats_out), int(save_for_bwd),
+                                               _stream(stream)), "encoder_fwd_tiles")
+
+    def encoder_bwd_tiles(self, dfeats, n_tiles, accumulate, pixel_grad=None, stream=None):
+        self._check(self.lib.encoder_bwd_tiles(self.ctx, _ptr(dfeats), n_tiles, int(accumulate), _ptr(pixel_grad),
+                                               _stream(stream)), "encoder_bwd_tiles")
+
+    def mil_pool_fwd(self, feats, N, label, loss=None, logits=None, alpha=None, stream=None):
+        self._check(self.lib.mil_pool_fwd(self.ctx, _ptr(feats), N, label, _ptr(loss), _ptr(logits), _ptr(alpha),
+                                          _stream(stream)), "mil_pool_fwd")
+
+    def mil_pool_bwd(self, feats, N, label, dfeats_out, accumulate, stream=None):
+        self._check(self.lib.mil_pool_bwd(self.ctx, _ptr(feats), N, label, _ptr(dfeats_out), int(accumulate),
+                                          _stream(stream)), "mil_pool_bwd")
+
+    def slide_step_fwd(self, pixels, N, label, loss=None, logits=None, alpha=None, stream=None):
+        self._check(self.lib.slide_step_fwd(self.ctx, _ptr(pixels), N, label, _ptr(loss), _ptr(logits), _ptr(alpha),
+                                            _stream(stream)), "slide_step_fwd")
+
+    def slide_step_bwd(self, accumulate, pixel_grad=None, stream=None):
+        self._check(self.lib.slide_step_bwd(self.ctx, int(accumulate), _ptr(pixel_grad), _stream(stream)), "slide_step_bwd")
+
+    def slide_features(self):
+        return self.lib.slide_features(self.ctx)
+
+    def slide_feature_grads(self):
+        return self.lib.slide_feature_grads(self.ctx)
+
+    def slide_prof_begin(self, kernel_id):
+        self._check(self.lib.slide_prof_begin(self.ctx, kernel_id), "slide_prof_begin")
+
+    def slide_prof_end(self):
+        ms, n, fl, by = C.c_double(), C.c_int(), C.c_double(), C.c_double()
+        self._check(self.lib.slide_prof_end(self.ctx, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)), "slide_prof_end")
+        return ms.value, n.value, fl.value, by.value
+
+    def kernel_names(self):
+        out, i = [], 0
+        while True:
+            s = self.lib.slide_kernel_name(i)
+            if s is None:
+                return out
+            out.append(s.decode())
+            i += 1

@@ -1,0 +1,37 @@
+// Epilogue shared by the NT GEMM kernels: what happens to one accumulator element.
+#pragma once
+#include "slide_internal.h"
+
+namespace sl {
+
+template <typename T, typename RS>
+__device__ __forceinline__ void epi_store(const GemmNT& g, long long m, int n, float acc) {
+  switch (g.epi) {
+    case EPI_PLAIN:
+      ((T*)g.out)[m * g.ldc + n] = from_f<T>(acc);
+      break;
+    case EPI_BIAS:
+      ((T*)g.out)[m * g.ldc + n] = from_f<T>(acc + g.bias[n]);
+      break;
+    case EPI_BIAS_RESID:
+      ((RS*)g.out)[m * g.ldc + n] = from_f<RS>(acc + g.bias[n] + to_f(((const RS*)g.resid)[m * g.ldr + n]));
+      break;
+    case EPI_BIAS_GELU: {
+      T pre = from_f<T>(acc + g.bias[n]);
+      ((T*)g.out)[m * g.ldc + n] = pre;
+      ((T*)g.out2)[m * g.ldc2 + n] = from_f<T>(gelu_f(to_f(pre)));  // GELU of the stored (rounded) value
+      break;
+    }
+    case EPI_DGELU:
+      ((T*)g.out)[m * g.ldc + n] = from_f<T>(acc * gelu_grad_f(to_f(((const T*)g.pre)[m * g.ldpre + n])));
+      break;
+    case EPI_PATCH: {
+      long long mm = g.cmap(m);
+      int tok = 1 + (int)(m % g.cmap.g2);
+      ((RS*)g.out)[mm * g.ldc + n] = from_f<RS>(acc + g.bias[n] + g.pos[(size_t)tok * g.N + n]);
+      break;
+    }
+  }
+}
+
+}  // namespace sl

@@ -1,0 +1,197 @@
+// Element-wise, layout and reduction kernels of the slide step (gfx950).
+#include "slide_internal.h"
+
+namespace sl {
+
+// ---------------------------------------------------------------------------------------
+// fp32 master weight [R,C] -> T copy [R,C] (optional) and T transpose [C,R] (optional)
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) cast_transpose_k(const float* __restrict__ src, int R, int C,
+                                                        T* __restrict__ dstW, T* __restrict__ dstWT) {
+  __shared__ float tile[32][33];
+  int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  for (int i = ty; i < 32; i += 8) {
+    int r = r0 + i, c = c0 + tx;
+    float v = (r < R && c < C) ? src[(size_t)r * C + c] : 0.f;
+    tile[i][tx] = v;
+    if (dstW && r < R && c < C) dstW[(size_t)r * C + c] = from_f<T>(v);
+  }
+  __syncthreads();
+  if (dstWT) {
+    for (int i = ty; i < 32; i += 8) {
+      int c = c0 + i, r = r0 + tx;
+      if (r < R && c < C) dstWT[(size_t)c * R + r] = from_f<T>(tile[tx][i]);
+    }
+  }
+}
+
+hipError_t launch_cast_transpose(int dt, const float* src, int R, int C, void* dstW, void* dstWT, hipStream_t s) {
+  dim3 grid((C + 31) / 32, (R + 31) / 32);
+  if (dt == DT_F32)
+    hipLaunchKernelGGL(cast_transpose_k<float>, grid, dim3(256), 0, s, src, R, C, (float*)dstW, (float*)dstWT);
+  else
+    hipLaunchKernelGGL(cast_transpose_k<bf16>, grid, dim3(256), 0, s, src, R, C, (bf16*)dstW, (bf16*)dstWT);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// pixels [n,3,S,S] <-> patches [n*g*g, 3*P*P]   (patch order (gy,gx), flatten order (c,py,px))
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) patchify_k(const T* __restrict__ pix, T* __restrict__ pat, long long total,
+                                                  int S, int P) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  int g = S / P, Kp = 3 * P * P;
+  int col = (int)(i % Kp);
+  long long row = i / Kp;
+  int px = col % P, py = (col / P) % P, c = col / (P * P);
+  int gx = (int)(row % g), gy = (int)((row / g) % g);
+  long long n = row / (g * g);
+  pat[i] = pix[((n * 3 + c) * S + gy * P + py) * S + gx * P + px];
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) unpatchify_k(const T* __restrict__ dpat, T* __restrict__ dpix, long long total,
+                                                    int S, int P) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;  // index into dpix
+  if (i >= total) return;
+  int g = S / P, Kp = 3 * P * P;
+  int x = (int)(i % S), y = (int)((i / S) % S), c = (int)((i / ((long long)S * S)) % 3);
+  long long n = i / (3LL * S * S);
+  long long row = (n * g + y / P) * g + x / P;
+  int col = c * P * P + (y % P) * P + (x % P);
+  dpix[i] = dpat[row * Kp + col];
+}
+
+hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long n, int S, int P, hipStream_t s) {
+  long long total = n * 3LL * S * S;
+  unsigned grid = (unsigned)((total + 255) / 256);
+  if (dt == DT_F32)
+    hipLaunchKernelGGL(patchify_k<float>, dim3(grid), dim3(256), 0, s, (const float*)pixels, (float*)patches, total, S, P);
+  else
+    hipLaunchKernelGGL(patchify_k<bf16>, dim3(grid), dim3(256), 0, s, (const bf16*)pixels, (bf16*)patches, total, S, P);
+  return hipGetLastError();
+}
+
+hipError_t launch_unpatchify(int dt, const void* dpatches, void* dpix, long long n, int S, int P, hipStream_t s) {
+  long long total = n * 3LL * S * S;
+  unsigned grid = (unsigned)((total + 255) / 256);
+  if (dt == DT_F32)
+    hipLaunchKernelGGL(unpatchify_k<float>, dim3(grid), dim3(256), 0, s, (const float*)dpatches, (float*)dpix, total, S, P);
+  else
+    hipLaunchKernelGGL(unpatchify_k<bf16>, dim3(grid), dim3(256), 0, s, (const bf16*)dpatches, (bf16*)dpix, total, S, P);
+  return hipGetLastError();
+}
+
+// x[n, 0, :] = cls + pos[0]
+template <typename RS>
+__global__ void __launch_bounds__(256) cls_rows_k(RS* __restrict__ x, const float* __restrict__ cls,
+                                                  const float* __restrict__ pos, long long n, int T, int D) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n * D) return;
+  int d = (int)(i % D);
+  long long t = i / D;
+  x[t * T * D + d] = from_f<RS>(cls[d] + pos[d]);
+}
+
+hipError_t launch_cls_rows(int dt, void* x, const float* cls, const float* pos, long long n, int T, int D, hipStream_t s) {
+  unsigned grid = (unsigned)((n * D + 255) / 256);
+  if (dt == DT_F32)
+    hipLaunchKernelGGL(cls_rows_k<float>, dim3(grid), dim3(256), 0, s, (float*)x, cls, pos, n, T, D);
+  else
+    hipLaunchKernelGGL(cls_rows_k<rs_bf16path_t>, dim3(grid), dim3(256), 0, s, (rs_bf16path_t*)x, cls, pos, n, T, D);
+  return hipGetLastError();
+}
+
+// zero fill in 16-byte words (bytes must be a multiple of 16; all arena regions are)
+__global__ void __launch_bounds__(256) fill_zero_k(uint4* __restrict__ p, size_t words) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * 256;
+  for (; i < words; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  size_t words = bytes / 16;
+  if (words == 0) return hipSuccess;
+  size_t blocks = (words + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(fill_zero_k, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)p, words);
+  return hipGetLastError();
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) gelu_k(const T* __restrict__ m, T* __restrict__ a, long long count) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  long long stride = (long long)gridDim.x * 256;
+  for (; i < count; i += stride) a[i] = from_f<T>(gelu_f(to_f(m[i])));
+}
+
+hipError_t launch_gelu(int dt, const void* m, void* a, long long count, hipStream_t s) {
+  long long blocks = (count + 255) / 256;
+  if (blocks > 262144) blocks = 262144;
+  if (blocks == 0) return hipSuccess;
+  if (dt == DT_F32)
+    hipLaunchKernelGGL(gelu_k<float>, dim3((unsigned)blocks), dim3(256), 0, s, (const float*)m, (float*)a, count);
+  else
+    hipLaunchKernelGGL(gelu_k<bf16>, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16*)m, (bf16*)a, count);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// column sums, two-stage and deterministic: part[s][c] = sum over rows of slab s
+// ---------------------------------------------------------------------------------------
+template <typename E>
+__global__ void __launch_bounds__(256) colsum_k(const E* __restrict__ A, long long lda, RowMap map, long long M, int N,
+                                                float* __restrict__ part, int slabs) {
+  __shared__ float red[4][64];
+  int cl = threadIdx.x & 63, q = threadIdx.x >> 6;
+  int c = blockIdx.x * 64 + cl;
+  int s = blockIdx.y;
+  long long per = (M + slabs - 1) / slabs;
+  long long lo = (long long)s * per, hi = lo + per < M ? lo + per : M;
+  float acc = 0.f;
+  if (c < N)
+    for (long long r = lo + q; r < hi; r += 4) acc += to_f(A[map(r) * lda + c]);
+  red[q][cl] = acc;
+  __syncthreads();
+  if (q == 0 && c < N) part[(size_t)s * N + c] = (red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl]);
+}
+
+int colsum_slabs(long long M) {
+  long long s = (M + 511) / 512;
+  if (s < 1) s = 1;
+  if (s > 128) s = 128;
+  return (int)s;
+}
+
+__global__ void __launch_bounds__(256) reduce_partials_k(const float* __restrict__ part, int slabs, long long stride,
+                                                         long long len, float* __restrict__ out, int accumulate) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= len) return;
+  float acc = 0.f;
+  for (int s = 0; s < slabs; ++s) acc += part[(size_t)s * stride + i];
+  out[i] = accumulate ? out[i] + acc : acc;
+}
+
+hipError_t launch_reduce_partials(const float* part, int slabs, long long stride, long long len, float* out,
+                                  int accumulate, hipStream_t s) {
+  if (len <= 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_partials_k, dim3((unsigned)((len + 255) / 256)), dim3(256), 0, s, part, slabs, stride, len,
+                     out, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum_part(int elem, const void* A, long long lda, RowMap map, long long M, int N, float* part,
+                              int slabs, hipStream_t s) {
+  dim3 grid((N + 63) / 64, slabs);
+  if (elem == DT_F32)
+    hipLaunchKernelGGL(colsum_k<float>, grid, dim3(256), 0, s, (const float*)A, lda, map, M, N, part, slabs);
+  else
+    hipLaunchKernelGGL(colsum_k<bf16>, grid, dim3(256), 0, s, (const bf16*)A, lda, map, M, N, part, slabs);
+  return hipGetLastError();
+}
+
+}  // namespace sl

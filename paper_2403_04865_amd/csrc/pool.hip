@@ -1,0 +1,342 @@
+// Gated-attention MIL pooling over the tile features of a slide, forward and backward.
+//   t_n = tanh(V h_n + b_V), s_n = sigmoid(U h_n + b_U), a_n = w . (t_n * s_n),
+//   alpha = softmax_n(a), z = sum_n alpha_n h_n, y = W_c z + b_c, loss = BCE / CE(y, label).
+// The softmax over tiles is a two-level online reduction: every workgroup keeps a running
+// (max, sum, weighted feature sum) over its row groups, one workgroup combines them.
+#include "slide_internal.h"
+
+namespace sl {
+
+constexpr int PR = 16;  // rows per group
+
+// Gate activations of PR feature rows held in LDS (hs [PR][D] fp32):
+// tl[r][j] = tanh(V_j.h_r + bV_j), sg[r][j] = sigmoid(U_j.h_r + bU_j).  One wave per gate unit j.
+__device__ __forceinline__ void gate_rows(const float* hs, int D, int Mh, const float* __restrict__ VW,
+                                          const float* __restrict__ Vb, const float* __restrict__ UW,
+                                          const float* __restrict__ Ub, float* tl, float* sg) {
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int j = w; j < Mh; j += 4) {
+    float av[PR], au[PR];
+#pragma unroll
+    for (int r = 0; r < PR; ++r) { av[r] = 0.f; au[r] = 0.f; }
+    for (int d = lane; d < D; d += 64) {
+      float v = VW[(size_t)j * D + d], u = UW[(size_t)j * D + d];
+#pragma unroll
+      for (int r = 0; r < PR; ++r) {
+        float h = hs[r * D + d];
+        av[r] += v * h;
+        au[r] += u * h;
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < PR; ++r) {
+      av[r] = wave_sum(av[r]);
+      au[r] = wave_sum(au[r]);
+    }
+    if (lane == 0) {
+      float bv = Vb[j], bu = Ub[j];
+#pragma unroll
+      for (int r = 0; r < PR; ++r) {
+        tl[r * Mh + j] = tanhf(av[r] + bv);
+        sg[r * Mh + j] = 1.0f / (1.0f + __expf(-(au[r] + bu)));
+      }
+    }
+  }
+}
+
+__device__ __forceinline__ void load_rows(const float* __restrict__ H, long long n0, long long N, int D, float* hs) {
+  for (int i = threadIdx.x; i < PR * D; i += 256) {
+    long long n = n0 + i / D;
+    hs[i] = n < N ? H[n * D + i % D] : 0.f;
+  }
+}
+
+// forward, stage 1: attention logits a[n] and per-workgroup partials part[b] = {max, sum, zsum[D]}
+__global__ void __launch_bounds__(256) pool_gate_part_k(PoolArgs p) {
+  extern __shared__ float lds[];
+  int D = p.D, Mh = p.Mh;
+  float* hs = lds;                // [PR][D]
+  float* tl = hs + PR * D;        // [PR][Mh]
+  float* sg = tl + PR * Mh;       // [PR][Mh]
+  float* ar = sg + PR * Mh;       // [PR] logits of the group
+  float* er = ar + PR;            // [PR] exp weights
+  double* zb = (double*)(er + PR);  // [D] running weighted sum (fp64: z feeds a cancelling difference later)
+  __shared__ float run_m, resc;
+  __shared__ double run_l;
+  const float* H = p.H;
+  for (int d = threadIdx.x; d < D; d += 256) zb[d] = 0.0;
+  if (threadIdx.x == 0) { run_m = -INFINITY; run_l = 0.0; }
+  long long groups = (p.N + PR - 1) / PR;
+  for (long long gi = blockIdx.x; gi < groups; gi += gridDim.x) {
+    long long n0 = gi * PR;
+    __syncthreads();
+    load_rows(H, n0, p.N, D, hs);
+    __syncthreads();
+    gate_rows(hs, D, Mh, p.VW, p.Vb, p.UW, p.Ub, tl, sg);
+    __syncthreads();
+    if (threadIdx.x < PR) {
+      int r = threadIdx.x;
+      float a = 0.f;
+      for (int j = 0; j < Mh; ++j) a += p.w[j] * tl[r * Mh + j] * sg[r * Mh + j];
+      bool ok = n0 + r < p.N;
+      ar[r] = ok ? a : -INFINITY;
+      if (ok) p.a[n0 + r] = a;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      float m = run_m;
+      for (int r = 0; r < PR; ++r) m = fmaxf(m, ar[r]);
+      float sc = __expf(run_m - m);  // exp(-inf) = 0 on the first group
+      double l = run_l * (double)sc;
+      for (int r = 0; r < PR; ++r) {
+        float e = __expf(ar[r] - m);
+        er[r] = e;
+        l += (double)e;
+      }
+      run_m = m; run_l = l; resc = sc;
+    }
+    __syncthreads();
+    for (int d = threadIdx.x; d < D; d += 256) {
+      double z = zb[d] * (double)resc;
+#pragma unroll
+      for (int r = 0; r < PR; ++r) z += (double)er[r] * (double)hs[r * D + d];
+      zb[d] = z;
+    }
+  }
+  __syncthreads();
+  double* out = p.part + (size_t)blockIdx.x * (2 + D);
+  if (threadIdx.x == 0) { out[0] = (double)run_m; out[1] = run_l; }
+  for (int d = threadIdx.x; d < D; d += 256) out[2 + d] = zb[d];
+}
+
+// forward, stage 2 (one workgroup): combine partials -> m, Z, z, logits, loss, dy, dz, z.dz
+__global__ void __launch_bounds__(256) pool_combine_k(PoolArgs p) {
+  __shared__ float sm[256];
+  __shared__ double smd[256];
+  __shared__ float gm;
+  __shared__ double gZ;
+  int D = p.D, C = p.C, B = p.blocks;
+  float* scal = p.scal;
+  float* y = scal + 4;
+  float* dy = y + C;
+  float* z = dy + C;
+  float* dz = z + D;
+  float* zlo = dz + D;  // z = z[d] + zlo[d] to fp64 accuracy
+  float m = -INFINITY;
+  for (int b = threadIdx.x; b < B; b += 256) m = fmaxf(m, (float)p.part[(size_t)b * (2 + D)]);
+  sm[threadIdx.x] = m;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) sm[threadIdx.x] = fmaxf(sm[threadIdx.x], sm[threadIdx.x + o]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) gm = sm[0];
+  __syncthreads();
+  m = gm;
+  double l = 0.0;
+  for (int b = threadIdx.x; b < B; b += 256) {
+    const double* q = p.part + (size_t)b * (2 + D);
+    l += q[1] * (double)__expf((float)q[0] - m);
+  }
+  smd[threadIdx.x] = l;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) smd[threadIdx.x] += smd[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) gZ = smd[0];
+  __syncthreads();
+  double Z = gZ;
+  for (int d = threadIdx.x; d < D; d += 256) {
+    double acc = 0.0;
+    for (int b = 0; b < B; ++b) {
+      const double* q = p.part + (size_t)b * (2 + D);
+      acc += q[2 + d] * (double)__expf((float)q[0] - m);
+    }
+    acc /= Z;
+    float hi = (float)acc;
+    z[d] = hi;
+    zlo[d] = (float)(acc - (double)hi);
+  }
+  __syncthreads();
+  // logits: one wave per class round-robin
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int c = w; c < C; c += 4) {
+    float acc = 0.f;
+    for (int d = lane; d < D; d += 64) acc += p.cW[(size_t)c * D + d] * z[d];
+    acc = wave_sum(acc);
+    if (lane == 0) y[c] = acc + p.cb[c];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float loss;
+    if (C == 1) {
+      float v = y[0];
+      loss = fmaxf(v, 0.f) - v * (float)p.label + log1pf(__expf(-fabsf(v)));
+      dy[0] = 1.0f / (1.0f + __expf(-v)) - (float)p.label;
+    } else {
+      float mx = y[0];
+      for (int c = 1; c < C; ++c) mx = fmaxf(mx, y[c]);
+      float se = 0.f;
+      for (int c = 0; c < C; ++c) se += __expf(y[c] - mx);
+      float lse = mx + logf(se);
+      loss = lse - y[p.label];
+      for (int c = 0; c < C; ++c) dy[c] = __expf(y[c] - lse) - (c == p.label ? 1.f : 0.f);
+    }
+    scal[0] = m; scal[1] = (float)Z; scal[2] = loss;
+    if (p.loss) p.loss[0] = loss;
+    if (p.logits) for (int c = 0; c < C; ++c) p.logits[c] = y[c];
+  }
+  __syncthreads();
+  float part = 0.f;
+  for (int d = threadIdx.x; d < D; d += 256) {
+    float acc = 0.f;
+    for (int c = 0; c < C; ++c) acc += p.cW[(size_t)c * D + d] * dy[c];
+    dz[d] = acc;
+    part += acc * z[d];
+  }
+  sm[threadIdx.x] = part;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) sm[threadIdx.x] += sm[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) scal[3] = sm[0];
+}
+
+__global__ void __launch_bounds__(256) pool_alpha_k(const float* __restrict__ a, const float* __restrict__ scal,
+                                                    float* __restrict__ alpha, long long N) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < N) alpha[i] = __expf(a[i] - scal[0]) / scal[1];
+}
+
+// backward rows: G and the per-row gate gradients Dp [N, 3*Mh] (fp32: their column sums cancel
+// almost completely because sum_n da_n = 0, so they are not rounded to the storage type):
+//   [0,Mh)   dpV = da * w * s * (1 - t^2)     (gradient at V's pre-activation)
+//   [Mh,2Mh) dpU = da * w * t * s * (1 - s)   (gradient at U's pre-activation)
+//   [2Mh,3Mh) da * t * s                      (summed over rows this is dw)
+__global__ void __launch_bounds__(256) pool_bwd_rows_k(PoolArgs p, float* __restrict__ Dp) {
+  extern __shared__ float lds[];
+  int D = p.D, Mh = p.Mh, C = p.C;
+  float* hs = lds;                // [PR][D]
+  float* tl = hs + PR * D;        // [PR][Mh] -> reused as dpV
+  float* sg = tl + PR * Mh;       // [PR][Mh] -> reused as dpU
+  float* al = sg + PR * Mh;       // [PR] alpha
+  float* da = al + PR;            // [PR]
+  const float* H = p.H;
+  float* G = p.G;
+  const float* scal = p.scal;
+  const float* zv = scal + 4 + 2 * C;
+  const float* dz = zv + D;
+  const float* zlo = dz + D;
+  float m = scal[0], Z = scal[1];
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  long long groups = (p.N + PR - 1) / PR;
+  for (long long gi = blockIdx.x; gi < groups; gi += gridDim.x) {
+    long long n0 = gi * PR;
+    __syncthreads();
+    load_rows(H, n0, p.N, D, hs);
+    __syncthreads();
+    gate_rows(hs, D, Mh, p.VW, p.Vb, p.UW, p.Ub, tl, sg);
+    for (int r = w; r < PR; r += 4) {  // softmax backward: da_n = alpha_n (h_n - z) . dz
+      float acc = 0.f;
+      for (int d = lane; d < D; d += 64) acc += ((hs[r * D + d] - zv[d]) - zlo[d]) * dz[d];
+      acc = wave_sum(acc);
+      if (lane == 0) {
+        bool ok = n0 + r < p.N;
+        float a = ok ? __expf(p.a[n0 + r] - m) / Z : 0.f;
+        al[r] = a;
+        da[r] = a * acc;
+      }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < PR * Mh; i += 256) {
+      int r = i / Mh, j = i % Mh;
+      float t = tl[i], s = sg[i], g = da[r], wj = p.w[j];
+      float dv = g * wj * s * (1.f - t * t);
+      float du = g * wj * t * s * (1.f - s);
+      tl[i] = dv;
+      sg[i] = du;
+      if (n0 + r < p.N) {
+        float* row = Dp + (n0 + r) * 3LL * Mh;
+        row[j] = dv;
+        row[Mh + j] = du;
+        row[2 * Mh + j] = g * t * s;
+      }
+    }
+    __syncthreads();
+    for (int d = threadIdx.x; d < D; d += 256) {
+      float acc[PR];
+      float dzd = dz[d];
+#pragma unroll
+      for (int r = 0; r < PR; ++r) acc[r] = al[r] * dzd;
+      for (int j = 0; j < Mh; ++j) {
+        float v = p.VW[(size_t)j * D + d], u = p.UW[(size_t)j * D + d];
+#pragma unroll
+        for (int r = 0; r < PR; ++r) acc[r] += tl[r * Mh + j] * v + sg[r * Mh + j] * u;
+      }
+#pragma unroll
+      for (int r = 0; r < PR; ++r)
+        if (n0 + r < p.N) G[(n0 + r) * D + d] = acc[r];
+    }
+  }
+}
+
+// head.W grad = dy z^T, head.b grad = dy
+__global__ void __launch_bounds__(256) pool_head_grads_k(PoolArgs p) {
+  int D = p.D, C = p.C;
+  const float* dy = p.scal + 4 + C;
+  const float* z = dy + C;
+  float* gW = p.grads + p.ocW;
+  float* gb = p.grads + p.ocb;
+  for (int i = threadIdx.x + blockIdx.x * 256; i < C * D; i += 256 * gridDim.x) {
+    float v = dy[i / D] * z[i % D];
+    gW[i] = p.accumulate ? gW[i] + v : v;
+  }
+  if (blockIdx.x == 0 && threadIdx.x < C) {
+    float v = dy[threadIdx.x];
+    gb[threadIdx.x] = p.accumulate ? gb[threadIdx.x] + v : v;
+  }
+}
+
+int pool_blocks(long long N) {
+  long long g = (N + PR - 1) / PR;
+  if (g > 1024) g = 1024;
+  if (g < 1) g = 1;
+  return (int)g;
+}
+
+static size_t pool_lds(int D, int Mh) { return ((size_t)PR * D + 2 * PR * Mh + 2 * PR + 2 * D) * sizeof(float); }
+
+template <typename K>
+static hipError_t set_lds(K kernel, size_t bytes) {
+  if (bytes <= 65536) return hipSuccess;
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+hipError_t launch_pool_fwd(const PoolArgs& p, hipStream_t s) {
+  size_t lds = pool_lds(p.D, p.Mh);
+  hipError_t e;
+  if ((e = set_lds(pool_gate_part_k, lds)) != hipSuccess) return e;
+  hipLaunchKernelGGL(pool_gate_part_k, dim3(p.blocks), dim3(256), lds, s, p);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(pool_combine_k, dim3(1), dim3(256), 0, s, p);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (p.alpha) {
+    hipLaunchKernelGGL(pool_alpha_k, dim3((unsigned)((p.N + 255) / 256)), dim3(256), 0, s, p.a, p.scal, p.alpha, p.N);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+hipError_t launch_pool_bwd_rows(const PoolArgs& p, float* Dp, hipStream_t s) {
+  size_t lds = pool_lds(p.D, p.Mh);
+  hipError_t e;
+  if ((e = set_lds(pool_bwd_rows_k, lds)) != hipSuccess) return e;
+  hipLaunchKernelGGL(pool_bwd_rows_k, dim3(p.blocks), dim3(256), lds, s, p, Dp);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(pool_head_grads_k, dim3(4), dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace sl

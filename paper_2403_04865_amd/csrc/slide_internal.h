@@ -1,0 +1,154 @@
+// Internal declarations shared by the translation units of libslide (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace sl {
+
+// ---- element types -------------------------------------------------------------------
+typedef __bf16 bf16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Residual-stream element type of the bf16 path (activations that are summed layer after
+// layer, forward x and backward dx).  float keeps the running sums exact to fp32; every
+// other saved activation is bf16.
+#ifndef SLIDE_BF16_STREAM_IS_BF16
+typedef float rs_bf16path_t;
+#else
+typedef bf16 rs_bf16path_t;
+#endif
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+__host__ __device__ inline size_t elem_size(int dt) { return dt == DT_F32 ? 4 : 2; }
+inline size_t rs_size(int dt) { return dt == DT_F32 ? 4 : sizeof(rs_bf16path_t); }
+
+__device__ __forceinline__ float to_f(float v) { return v; }
+__device__ __forceinline__ float to_f(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f(float v);
+template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f<bf16>(float v) { return (bf16)v; }  // RNE
+
+// ---- wave / block reductions (wave = 64 lanes) ------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+__device__ __forceinline__ float gelu_f(float m) {
+  return 0.5f * m * (1.0f + erff(m * 0.70710678118654752f));
+}
+__device__ __forceinline__ float gelu_grad_f(float m) {
+  return 0.5f * (1.0f + erff(m * 0.70710678118654752f)) +
+         m * __expf(-0.5f * m * m) * 0.39894228040143268f;
+}
+
+// Row map used where a GEMM operand lives in the token matrix but only patch-token rows
+// take part: logical row r (tile r / g2, patch r % g2) -> token row (r / g2) * T + 1 + r % g2.
+// g2 == 0 means identity.
+struct RowMap {
+  int g2, T;
+  __host__ __device__ __forceinline__ long long operator()(long long r) const {
+    return g2 ? (r / g2) * T + 1 + (r % g2) : r;
+  }
+};
+
+// ---- GEMM epilogues (C = A * B^T, A [M,K], B [N,K], both K-contiguous) ------------------
+enum {
+  EPI_PLAIN = 0,       // out(T)  = acc
+  EPI_BIAS = 1,        // out(T)  = acc + bias[n]
+  EPI_BIAS_RESID = 2,  // out(RS) = acc + bias[n] + resid(RS)[m][n]
+  EPI_BIAS_GELU = 3,   // out(T)  = m = acc + bias[n];  out2(T) = gelu(m)
+  EPI_DGELU = 4,       // out(T)  = acc * gelu'(pre(T)[m][n])
+  EPI_PATCH = 5,       // out(RS)[rowmap(m)] = acc + bias[n] + pos[1 + m % g2][n]
+};
+
+struct GemmNT {
+  const void* A; long long lda;  // T
+  RowMap amap;                   // row map applied to A rows
+  const void* B; long long ldb;  // T (weights, [N,K])
+  long long M; int N, K;
+  int epi;
+  const float* bias;
+  const void* resid; long long ldr;
+  void* out; long long ldc;
+  void* out2; long long ldc2;
+  const void* pre; long long ldpre;
+  const float* pos;  // [T, N] position table (EPI_PATCH)
+  RowMap cmap;       // EPI_PATCH output rows
+};
+
+// C[N1,N2] (fp32) = sum_m A[m,N1]^T B[m,N2]; split over `slabs` ranges of m, partial s is
+// written to part + s*N1*N2.  A rows go through amap.
+struct GemmTN {
+  const void* A; long long lda; RowMap amap;  // T [M, N1]
+  const void* B; long long ldb; RowMap bmap;  // T [M, N2]
+  long long M; int N1, N2;
+  float* part; int slabs;
+};
+
+// All launchers enqueue on `s` and return the launch status.
+hipError_t launch_gemm_nt(int dt, const GemmNT& g, bool use_mfma, hipStream_t s);
+hipError_t launch_gemm_tn(int dt, const GemmTN& g, bool use_mfma, hipStream_t s);
+int gemm_tn_pick_slabs(long long M, int N1, int N2, int max_slabs);
+
+hipError_t launch_cast_transpose(int dt, const float* src, int R, int C, void* dstW, void* dstWT, hipStream_t s);
+hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long n, int S, int P, hipStream_t s);
+hipError_t launch_unpatchify(int dt, const void* dpatches, void* dpix, long long n, int S, int P, hipStream_t s);
+hipError_t launch_cls_rows(int dt, void* x, const float* cls, const float* pos, long long n, int T, int D, hipStream_t s);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_gelu(int dt, const void* m, void* a, long long count, hipStream_t s);
+// part[s][c] = sum over rows of slab s of A[map(r)][c]; elem: DT_F32 / DT_BF16 element type of A
+int colsum_slabs(long long M);
+hipError_t launch_colsum_part(int elem, const void* A, long long lda, RowMap map, long long M, int N, float* part,
+                              int slabs, hipStream_t s);
+// out[i] = (accumulate ? out[i] : 0) + sum_s part[s*stride + i], i < len
+hipError_t launch_reduce_partials(const float* part, int slabs, long long stride, long long len, float* out,
+                                  int accumulate, hipStream_t s);
+
+// LayerNorm.  x rows at x + r*x_stride (RS), out rows at out + r*out_stride (T, or fp32 when out_f32).
+hipError_t launch_ln_fwd(int dt, const void* x, long long x_stride, const float* gam, const float* bet, void* out,
+                         long long out_stride, long long rows, int D, float eps, bool out_f32, hipStream_t s);
+// dx_out[r] (RS) = (dres ? dres[r] : 0) + LN-backward(dy[r] (T, or fp32 when dy_f32); x[r] (RS)); optional T copy of dx_out
+// (only written when RS and T differ); dgamma/dbeta partials -> part[slab][2][D], ln_bwd_slabs(rows) slabs.
+int ln_bwd_slabs(long long rows);
+hipError_t launch_ln_bwd(int dt, const void* x, long long x_stride, const void* dy, long long dy_stride,
+                         const float* gam, const void* dres, void* dx_out, void* dx_out_t, long long o_stride,
+                         long long rows, int D, float eps, float* part, bool dy_f32, hipStream_t s);
+
+// Attention over qkv [n*T, 3D] (T): O [n*T, D] (T), lse [n,H,T] fp32.
+hipError_t launch_attn_fwd(int dt, const void* qkv, void* O, float* lse, long long n, int T, int H, int dh,
+                           bool use_mfma, hipStream_t s);
+hipError_t launch_attn_bwd(int dt, const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
+                           long long n, int T, int H, int dh, bool use_mfma, hipStream_t s);
+size_t attn_lds_bytes(int T, int dh);
+
+// Gated-attention MIL pool.
+struct PoolArgs {
+  const float* H; long long N; int D, Mh, C; int label;  // features are fp32 in both paths
+  const float *VW, *Vb, *UW, *Ub, *w, *cW, *cb;
+  float* a;     // [N] attention logits
+  double* part; // [blocks][2 + D] forward partials {max, sum, weighted feature sum}
+  float* scal;  // [4 + 2C + 3D]: m, Z, loss, z.dz, logits[C], dy[C], z[D], dz[D], zlo[D]
+  int blocks;
+  float *loss, *logits, *alpha;  // outputs, may be null
+  float* G;                      // [N,D]
+  float* grads;                  // flat gradient vector
+  size_t ocW, ocb;               // offsets of head.W / head.b in it
+  int accumulate;
+};
+int pool_blocks(long long N);
+hipError_t launch_pool_fwd(const PoolArgs& p, hipStream_t s);
+hipError_t launch_pool_bwd_rows(const PoolArgs& p, float* Dp, hipStream_t s);
+
+}  // namespace sl

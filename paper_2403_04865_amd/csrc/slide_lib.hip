@@ -1,0 +1,737 @@
+// libslide: C ABI, parameter layout, arena carving and the launch sequence of one slide step.
+#include "../../include/slide.h"
+#include "slide_internal.h"
+
+#include <string>
+#include <vector>
+#include <cstring>
+#include <cstdio>
+
+using namespace sl;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+enum KernelId {
+  K_GEMM_NT = 0, K_GEMM_TN, K_ATTN_FWD, K_ATTN_BWD, K_LN_FWD, K_LN_BWD, K_COLSUM, K_POOL_FWD, K_POOL_BWD,
+  K_ELEMWISE, K_COUNT
+};
+const char* const kKernelNames[K_COUNT] = {
+  "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "pool_fwd", "pool_bwd", "elementwise"};
+
+struct Prof {
+  bool active = false;
+  int id = -1;
+  int count = 0;
+  double flops = 0, bytes = 0;
+  std::vector<hipEvent_t> ev;  // 2 per launch
+};
+
+struct Tensor { std::string name; size_t off, len; };
+
+struct LayerOff { size_t ln1g, ln1b, qkvW, qkvb, projW, projb, ln2g, ln2b, fc1W, fc1b, fc2W, fc2b; };
+
+// shadow copies (element offsets inside the shadow region, in T elements)
+struct ShadowMat { size_t w, wt; int R, C; size_t poff; };
+
+struct Layout {
+  size_t total = 0;
+  // pool
+  size_t p_a, p_part, p_scal, p_Dp, p_tn, p_cs, p_H, p_G, pool_end;
+  // shared reduction work space
+  size_t w_wpart, w_cpart, w_lnpart;
+  // encoder
+  size_t enc_begin;
+  size_t e_patches, e_x, e_qkv, e_O, e_lse, e_xmid, e_m;              // first instance
+  size_t s_x, s_qkv, s_O, s_lse, s_xmid, s_m;                         // per-layer strides (0 when not saved)
+  size_t e_u, e_a, e_dxA, e_dxB, e_dxAt, e_dxBt, e_du, e_dqkv;
+};
+
+}  // namespace
+
+struct slide_ctx {
+  slide_config cfg;
+  int g, g2, T, D, F, Kp, dh, L, H, Mh, C, dt;
+  std::vector<Tensor> tensors;
+  size_t n_params = 0;
+  size_t o_peW, o_peb, o_cls, o_pos, o_lnfg, o_lnfb, o_VW, o_Vb, o_UW, o_Ub, o_w, o_cW, o_cb;
+  std::vector<LayerOff> lo;
+  std::vector<ShadowMat> sh;  // 0 = pe.W, then per layer qkv, proj, fc1, fc2
+  size_t shadow_bytes = 0;
+  size_t max_w = 0;  // largest weight matrix (elements)
+  const float* params = nullptr;
+  float* grads = nullptr;
+  char* arena = nullptr;
+  size_t arena_bytes = 0;
+  // state
+  bool enc_saved = false;     // activations of enc_n tiles are in the arena
+  long long enc_n = 0;
+  Layout enc_layout;
+  bool step_saved = false;    // slide_step_fwd state (features in arena, label)
+  int step_label = 0;
+  bool use_mfma = true;
+  Prof prof;
+};
+
+namespace {
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t add_tensor(slide_ctx* c, const std::string& name, size_t len) {
+  size_t off = c->n_params;
+  c->tensors.push_back({name, off, len});
+  c->n_params += len;
+  return off;
+}
+
+void add_shadow(slide_ctx* c, size_t poff, int R, int Cc) {
+  ShadowMat m;
+  m.R = R; m.C = Cc; m.poff = poff;
+  size_t e = elem_size(c->dt);
+  size_t n = (size_t)R * Cc;
+  m.w = c->shadow_bytes;
+  if (c->dt == DT_BF16) c->shadow_bytes += align256(n * e);
+  m.wt = c->shadow_bytes;
+  c->shadow_bytes += align256(n * e);
+  c->sh.push_back(m);
+  if (n > c->max_w) c->max_w = n;
+}
+
+// Carve the arena for an encoder call on n tiles (with or without saved activations) and a
+// pool over pool_N rows.  Pure arithmetic; the same inputs always give the same layout.
+Layout make_layout(const slide_ctx* c, long long n, long long pool_N, bool save) {
+  Layout y;
+  size_t cur = align256(c->shadow_bytes);
+  auto take = [&](size_t bytes) { size_t o = cur; cur = align256(cur + bytes); return o; };
+  size_t e = elem_size(c->dt), rs = rs_size(c->dt);
+  long long PN = pool_N > 0 ? pool_N : 0;
+  int D = c->D, Mh = c->Mh, C = c->C;
+  y.p_a = take((size_t)PN * 4);
+  y.p_part = take((size_t)1024 * (2 + D) * 8);
+  y.p_scal = take((size_t)(4 + 2 * C + 3 * D) * 4);
+  y.p_Dp = take((size_t)PN * 3 * Mh * 4);
+  y.p_tn = take((size_t)32 * Mh * D * 4);
+  y.p_cs = take((size_t)128 * 3 * Mh * 4);
+  y.p_H = take((size_t)PN * D * 4);
+  y.p_G = take((size_t)PN * D * 4);
+  y.pool_end = cur;
+  long long nn = n > 0 ? n : 0;
+  size_t M = (size_t)nn * c->T;
+  size_t maxcols = (size_t)(c->F > 3 * D ? c->F : 3 * D);
+  size_t tokcols = (size_t)c->T * D;
+  y.w_wpart = take((size_t)32 * c->max_w * 4);
+  y.w_cpart = take((size_t)128 * (maxcols > tokcols ? maxcols : tokcols) * 4);
+  y.w_lnpart = take((size_t)1024 * 2 * D * 4);
+  y.enc_begin = cur;
+  int inst = save ? c->L : (c->L > 0 ? 1 : 0);
+  y.e_patches = take((size_t)nn * c->g2 * c->Kp * e);
+  y.s_x = save ? align256(M * D * rs) : 0;
+  y.e_x = take(0);
+  cur += (save ? (size_t)(c->L + 1) : 1) * align256(M * D * rs);
+  y.s_qkv = save ? align256(M * 3 * D * e) : 0;
+  y.e_qkv = take(0); cur += (size_t)inst * align256(M * 3 * D * e);
+  y.s_O = save ? align256(M * D * e) : 0;
+  y.e_O = take(0); cur += (size_t)inst * align256(M * D * e);
+  y.s_lse = save ? align256((size_t)nn * c->H * c->T * 4) : 0;
+  y.e_lse = take(0); cur += (size_t)inst * align256((size_t)nn * c->H * c->T * 4);
+  if (save) {
+    y.s_xmid = align256(M * D * rs);
+    y.e_xmid = take(0); cur += (size_t)inst * y.s_xmid;
+  } else {
+    y.s_xmid = 0; y.e_xmid = y.e_x;  // residual adds run in place
+  }
+  y.s_m = save ? align256(M * c->F * e) : 0;
+  y.e_m = take(0); cur += (size_t)inst * align256(M * c->F * e);
+  y.e_u = take(M * D * e);
+  size_t abytes = M * c->F * e, pbytes = (size_t)nn * c->g2 * c->Kp * e;
+  y.e_a = take(abytes > pbytes ? abytes : pbytes);
+  if (save) {
+    y.e_dxA = take(M * D * rs);
+    y.e_dxB = take(M * D * rs);
+    if (rs != e) { y.e_dxAt = take(M * D * e); y.e_dxBt = take(M * D * e); }
+    else { y.e_dxAt = y.e_dxA; y.e_dxBt = y.e_dxB; }
+    y.e_du = take(M * D * e);
+    y.e_dqkv = take(M * 3 * D * e);
+  } else {
+    y.e_dxA = y.e_dxB = y.e_dxAt = y.e_dxBt = y.e_du = y.e_dqkv = 0;
+  }
+  y.total = cur;
+  return y;
+}
+
+struct Run {
+  slide_ctx* c;
+  hipStream_t s;
+  hipError_t err = hipSuccess;
+  bool ok() const { return err == hipSuccess; }
+};
+
+// Launch wrapper: skips work after the first failure and records profiling events.
+template <typename F>
+void launch(Run& r, int id, double flops, double bytes, F f) {
+  if (!r.ok()) return;
+  Prof& p = r.c->prof;
+  bool rec = p.active && p.id == id && p.count < SLIDE_PROF_MAX;
+  if (rec) {
+    while ((int)p.ev.size() < 2 * (p.count + 1)) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) { rec = false; break; }
+      p.ev.push_back(e);
+    }
+  }
+  if (rec) (void)hipEventRecord(p.ev[2 * p.count], r.s);
+  hipError_t e = f();
+  if (rec) {
+    (void)hipEventRecord(p.ev[2 * p.count + 1], r.s);
+    p.count++;
+    p.flops += flops;
+    p.bytes += bytes;
+  }
+  if (e != hipSuccess) { r.err = e; g_last_hip = (int)e; }
+}
+
+int finish(Run& r) { return r.ok() ? SLIDE_OK : SLIDE_EHIP; }
+
+const void* weight(const slide_ctx* c, int idx) {  // [out][in] in T
+  const ShadowMat& m = c->sh[idx];
+  return c->dt == DT_F32 ? (const void*)(c->params + m.poff) : (const void*)(c->arena + m.w);
+}
+const void* weight_t(const slide_ctx* c, int idx) { return c->arena + c->sh[idx].wt; }  // [in][out] in T
+
+void cast_weights(Run& r) {
+  slide_ctx* c = r.c;
+  for (size_t i = 0; i < c->sh.size(); ++i) {
+    const ShadowMat& m = c->sh[i];
+    void* w = c->dt == DT_BF16 ? (void*)(c->arena + m.w) : nullptr;
+    void* wt = c->arena + m.wt;
+    launch(r, K_ELEMWISE, 0, (double)m.R * m.C * (4 + 2 * elem_size(c->dt)),
+           [&] { return launch_cast_transpose(c->dt, c->params + m.poff, m.R, m.C, w, wt, r.s); });
+  }
+}
+
+void gemm_nt(Run& r, const GemmNT& g) {
+  size_t e = elem_size(r.c->dt);
+  double bytes = (double)g.M * g.K * e + (double)g.N * g.K * e + (double)g.M * g.N * e;
+  launch(r, K_GEMM_NT, 2.0 * g.M * g.N * g.K, bytes, [&] { return launch_gemm_nt(r.c->dt, g, r.c->use_mfma, r.s); });
+}
+
+// dW (+)= A^T B through split partials
+void gemm_tn(Run& r, const void* A, long long lda, RowMap amap, const void* B, long long ldb, RowMap bmap, long long M,
+             int N1, int N2, float* part, float* out, int accumulate, int dt_override = -1) {
+  GemmTN g;
+  int dt = dt_override >= 0 ? dt_override : r.c->dt;
+  g.A = A; g.lda = lda; g.amap = amap; g.B = B; g.ldb = ldb; g.bmap = bmap; g.M = M; g.N1 = N1; g.N2 = N2;
+  g.part = part;
+  g.slabs = gemm_tn_pick_slabs(M, N1, N2, 32);
+  size_t e = elem_size(dt);
+  launch(r, K_GEMM_TN, 2.0 * M * N1 * N2, (double)M * (N1 + N2) * e + (double)g.slabs * N1 * N2 * 4,
+         [&] { return launch_gemm_tn(dt, g, r.c->use_mfma, r.s); });
+  launch(r, K_ELEMWISE, 0, (double)(g.slabs + 1) * N1 * N2 * 4, [&] {
+    return launch_reduce_partials(part, g.slabs, (long long)N1 * N2, (long long)N1 * N2, out, accumulate, r.s);
+  });
+}
+
+void colsum(Run& r, int elem, const void* A, long long lda, RowMap map, long long M, int N, float* part, float* out,
+            int accumulate) {
+  int slabs = colsum_slabs(M);
+  launch(r, K_COLSUM, 0, (double)M * N * elem_size(elem),
+         [&] { return launch_colsum_part(elem, A, lda, map, M, N, part, slabs, r.s); });
+  launch(r, K_ELEMWISE, 0, (double)slabs * N * 4,
+         [&] { return launch_reduce_partials(part, slabs, N, N, out, accumulate, r.s); });
+}
+
+void ln_fwd(Run& r, const void* x, long long xs, const float* g, const float* b, void* out, long long os, long long rows,
+            bool out_f32 = false) {
+  slide_ctx* c = r.c;
+  launch(r, K_LN_FWD, 0, (double)rows * c->D * (rs_size(c->dt) + elem_size(c->dt)),
+         [&] { return launch_ln_fwd(c->dt, x, xs, g, b, out, os, rows, c->D, c->cfg.ln_eps, out_f32, r.s); });
+}
+
+void ln_bwd(Run& r, const void* x, long long xs, const void* dy, long long dys, size_t o_gam, size_t o_bet,
+            const void* dres, void* dxo, void* dxo_t, long long os, long long rows, float* part, int accumulate,
+            bool dy_f32 = false) {
+  slide_ctx* c = r.c;
+  size_t rs = rs_size(c->dt), e = elem_size(c->dt);
+  double bytes = (double)rows * c->D * (rs + e + (dres ? rs : 0) + rs + (rs != e ? e : 0));
+  launch(r, K_LN_BWD, 0, bytes, [&] {
+    return launch_ln_bwd(c->dt, x, xs, dy, dys, c->params + o_gam, dres, dxo, dxo_t, os, rows, c->D, c->cfg.ln_eps, part,
+                         dy_f32, r.s);
+  });
+  int slabs = ln_bwd_slabs(rows);
+  launch(r, K_ELEMWISE, 0, 0, [&] {
+    return launch_reduce_partials(part, slabs, 2LL * c->D, c->D, c->grads + o_gam, accumulate, r.s);
+  });
+  launch(r, K_ELEMWISE, 0, 0, [&] {
+    return launch_reduce_partials(part + c->D, slabs, 2LL * c->D, c->D, c->grads + o_bet, accumulate, r.s);
+  });
+}
+
+int check_bound(const slide_ctx* c) {
+  if (!c) return SLIDE_EINVAL;
+  if (!c->params || !c->grads || !c->arena) return SLIDE_ESTATE;
+  return SLIDE_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// encoder forward
+// ------------------------------------------------------------------------------------------
+int enc_fwd(slide_ctx* c, const void* pixels, long long n, void* feats_out, bool save, long long pool_N,
+            hipStream_t s) {
+  Layout y = make_layout(c, n, pool_N, save);
+  if (y.total > c->arena_bytes) return SLIDE_EARENA;
+  c->enc_saved = false;
+  c->step_saved = false;
+  Run r{c, s};
+  char* ar = c->arena;
+  int D = c->D, T = c->T, F = c->F, dt = c->dt;
+  long long M = n * T;
+  cast_weights(r);
+  launch(r, K_ELEMWISE, 0, 2.0 * n * 3 * c->cfg.tile * c->cfg.tile * elem_size(dt),
+         [&] { return launch_patchify(dt, pixels, ar + y.e_patches, n, c->cfg.tile, c->cfg.patch, s); });
+  {
+    GemmNT g{};
+    g.A = ar + y.e_patches; g.lda = c->Kp; g.amap = RowMap{0, 0};
+    g.B = weight(c, 0); g.ldb = c->Kp;
+    g.M = n * c->g2; g.N = D; g.K = c->Kp;
+    g.epi = EPI_PATCH; g.bias = c->params + c->o_peb; g.pos = c->params + c->o_pos;
+    g.out = ar + y.e_x; g.ldc = D; g.cmap = RowMap{c->g2, T};
+    gemm_nt(r, g);
+  }
+  launch(r, K_ELEMWISE, 0, 0,
+         [&] { return launch_cls_rows(dt, ar + y.e_x, c->params + c->o_cls, c->params + c->o_pos, n, T, D, s); });
+  for (int l = 0; l < c->L; ++l) {
+    const LayerOff& o = c->lo[l];
+    char* xin = ar + y.e_x + (size_t)l * y.s_x;
+    char* xout = ar + y.e_x + (size_t)(l + 1) * y.s_x;
+    char* xmid = ar + y.e_xmid + (size_t)l * y.s_xmid;
+    char* qkv = ar + y.e_qkv + (size_t)l * y.s_qkv;
+    char* O = ar + y.e_O + (size_t)l * y.s_O;
+    float* lse = (float*)(ar + y.e_lse + (size_t)l * y.s_lse);
+    char* m = ar + y.e_m + (size_t)l * y.s_m;
+    char* u = ar + y.e_u;
+    char* a = ar + y.e_a;
+    int wi = 1 + 4 * l;
+    ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
+    {
+      GemmNT g{};
+      g.A = u; g.lda = D; g.B = weight(c, wi + 0); g.ldb = D; g.M = M; g.N = 3 * D; g.K = D;
+      g.epi = EPI_BIAS; g.bias = c->params + o.qkvb; g.out = qkv; g.ldc = 3 * D;
+      gemm_nt(r, g);
+    }
+    launch(r, K_ATTN_FWD, 4.0 * n * c->H * (double)T * T * c->dh, (double)M * 4 * D * elem_size(dt),
+           [&] { return launch_attn_fwd(dt, qkv, O, lse, n, T, c->H, c->dh, c->use_mfma, s); });
+    {
+      GemmNT g{};
+      g.A = O; g.lda = D; g.B = weight(c, wi + 1); g.ldb = D; g.M = M; g.N = D; g.K = D;
+      g.epi = EPI_BIAS_RESID; g.bias = c->params + o.projb; g.resid = xin; g.ldr = D; g.out = xmid; g.ldc = D;
+      gemm_nt(r, g);
+    }
+    ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u, D, M);
+    {
+      GemmNT g{};
+      g.A = u; g.lda = D; g.B = weight(c, wi + 2); g.ldb = D; g.M = M; g.N = F; g.K = D;
+      g.epi = EPI_BIAS_GELU; g.bias = c->params + o.fc1b; g.out = m; g.ldc = F; g.out2 = a; g.ldc2 = F;
+      gemm_nt(r, g);
+    }
+    {
+      GemmNT g{};
+      g.A = a; g.lda = F; g.B = weight(c, wi + 3); g.ldb = F; g.M = M; g.N = D; g.K = F;
+      g.epi = EPI_BIAS_RESID; g.bias = c->params + o.fc2b; g.resid = xmid; g.ldr = D; g.out = xout; g.ldc = D;
+      gemm_nt(r, g);
+    }
+  }
+  char* xL = ar + y.e_x + (size_t)c->L * y.s_x;
+  ln_fwd(r, xL, (long long)T * D, c->params + c->o_lnfg, c->params + c->o_lnfb, feats_out, D, n, true);
+  if (r.ok() && save) { c->enc_saved = true; c->enc_n = n; c->enc_layout = y; }
+  return finish(r);
+}
+
+// ------------------------------------------------------------------------------------------
+// encoder backward
+// ------------------------------------------------------------------------------------------
+int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void* pixel_grad, hipStream_t s) {
+  if (!c->enc_saved || c->enc_n != n) return SLIDE_ESTATE;
+  const Layout& y = c->enc_layout;
+  Run r{c, s};
+  char* ar = c->arena;
+  int D = c->D, T = c->T, F = c->F, dt = c->dt;
+  long long M = n * T;
+  size_t rs = rs_size(dt), e = elem_size(dt);
+  bool dual = rs != e;
+  int rs_elem = rs == 4 ? DT_F32 : DT_BF16;
+  float* wpart = (float*)(ar + y.w_wpart);
+  float* cpart = (float*)(ar + y.w_cpart);
+  float* lnpart = (float*)(ar + y.w_lnpart);
+  char *dxA = ar + y.e_dxA, *dxB = ar + y.e_dxB, *dxAt = ar + y.e_dxAt, *dxBt = ar + y.e_dxBt;
+  char *du = ar + y.e_du, *dqkv = ar + y.e_dqkv, *u = ar + y.e_u, *a = ar + y.e_a;
+  RowMap id{0, 0};
+  float* G = c->grads;
+  launch(r, K_ELEMWISE, 0, (double)M * D * rs, [&] { return launch_fill_zero(dxA, (size_t)M * D * rs, s); });
+  if (dual) launch(r, K_ELEMWISE, 0, (double)M * D * e, [&] { return launch_fill_zero(dxAt, (size_t)M * D * e, s); });
+  char* xL = ar + y.e_x + (size_t)c->L * y.s_x;
+  ln_bwd(r, xL, (long long)T * D, dfeats, D, c->o_lnfg, c->o_lnfb, nullptr, dxA, dxAt, (long long)T * D, n, lnpart,
+         accumulate, true);
+  for (int l = c->L - 1; l >= 0; --l) {
+    const LayerOff& o = c->lo[l];
+    char* xin = ar + y.e_x + (size_t)l * y.s_x;
+    char* xmid = ar + y.e_xmid + (size_t)l * y.s_xmid;
+    char* qkv = ar + y.e_qkv + (size_t)l * y.s_qkv;
+    char* O = ar + y.e_O + (size_t)l * y.s_O;
+    float* lse = (float*)(ar + y.e_lse + (size_t)l * y.s_lse);
+    char* m = ar + y.e_m + (size_t)l * y.s_m;
+    int wi = 1 + 4 * l;
+    // ---- MLP half: x_out = x_mid + gelu(LN2(x_mid) W1^T + b1) W2^T + b2
+    colsum(r, dt, dxAt, D, id, M, D, cpart, G + o.fc2b, accumulate);
+    launch(r, K_ELEMWISE, 0, 2.0 * M * F * e, [&] { return launch_gelu(dt, m, a, M * F, s); });
+    gemm_tn(r, dxAt, D, id, a, F, id, M, D, F, wpart, G + o.fc2W, accumulate);
+    {
+      GemmNT g{};
+      g.A = dxAt; g.lda = D; g.B = weight_t(c, wi + 3); g.ldb = D; g.M = M; g.N = F; g.K = D;
+      g.epi = EPI_DGELU; g.pre = m; g.ldpre = F; g.out = a; g.ldc = F;  // dm overwrites the GELU output
+      gemm_nt(r, g);
+    }
+    colsum(r, dt, a, F, id, M, F, cpart, G + o.fc1b, accumulate);
+    ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u, D, M);
+    gemm_tn(r, a, F, id, u, D, id, M, F, D, wpart, G + o.fc1W, accumulate);
+    {
+      GemmNT g{};
+      g.A = a; g.lda = F; g.B = weight_t(c, wi + 2); g.ldb = F; g.M = M; g.N = D; g.K = F;
+      g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
+      gemm_nt(r, g);
+    }
+    ln_bwd(r, xmid, D, du, D, o.ln2g, o.ln2b, dxA, dxB, dxBt, D, M, lnpart, accumulate);
+    // ---- attention half: x_mid = x_in + attn(LN1(x_in)) Wo^T + bo
+    colsum(r, dt, dxBt, D, id, M, D, cpart, G + o.projb, accumulate);
+    gemm_tn(r, dxBt, D, id, O, D, id, M, D, D, wpart, G + o.projW, accumulate);
+    {
+      GemmNT g{};
+      g.A = dxBt; g.lda = D; g.B = weight_t(c, wi + 1); g.ldb = D; g.M = M; g.N = D; g.K = D;
+      g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
+      gemm_nt(r, g);
+    }
+    launch(r, K_ATTN_BWD, 10.0 * n * c->H * (double)T * T * c->dh, (double)M * 9 * D * e,
+           [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s); });
+    colsum(r, dt, dqkv, 3 * D, id, M, 3 * D, cpart, G + o.qkvb, accumulate);
+    ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
+    gemm_tn(r, dqkv, 3 * D, id, u, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate);
+    {
+      GemmNT g{};
+      g.A = dqkv; g.lda = 3 * D; g.B = weight_t(c, wi + 0); g.ldb = 3 * D; g.M = M; g.N = D; g.K = 3 * D;
+      g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
+      gemm_nt(r, g);
+    }
+    ln_bwd(r, xin, D, du, D, o.ln1g, o.ln1b, dxB, dxA, dxAt, D, M, lnpart, accumulate);
+  }
+  // ---- token assembly: x0[n,0] = cls + pos[0]; x0[n,1+j] = patch_j W_pe^T + b_pe + pos[1+j]
+  {
+    long long cols = (long long)T * D;
+    int slabs = colsum_slabs(n);
+    launch(r, K_COLSUM, 0, (double)M * D * rs,
+           [&] { return launch_colsum_part(rs_elem, dxA, cols, id, n, (int)cols, cpart, slabs, s); });
+    launch(r, K_ELEMWISE, 0, 0,
+           [&] { return launch_reduce_partials(cpart, slabs, cols, cols, G + c->o_pos, accumulate, s); });
+    launch(r, K_ELEMWISE, 0, 0,
+           [&] { return launch_reduce_partials(cpart, slabs, cols, D, G + c->o_cls, accumulate, s); });
+  }
+  RowMap pm{c->g2, T};
+  long long Mp = n * c->g2;
+  colsum(r, dt, dxAt, D, pm, Mp, D, cpart, G + c->o_peb, accumulate);
+  gemm_tn(r, dxAt, D, pm, ar + y.e_patches, c->Kp, id, Mp, D, c->Kp, wpart, G + c->o_peW, accumulate);
+  if (pixel_grad) {
+    GemmNT g{};
+    g.A = dxAt; g.lda = D; g.amap = pm; g.B = weight_t(c, 0); g.ldb = D; g.M = Mp; g.N = c->Kp; g.K = D;
+    g.epi = EPI_PLAIN; g.out = a; g.ldc = c->Kp;
+    gemm_nt(r, g);
+    launch(r, K_ELEMWISE, 0, 2.0 * Mp * c->Kp * e,
+           [&] { return launch_unpatchify(dt, a, pixel_grad, n, c->cfg.tile, c->cfg.patch, s); });
+  }
+  return finish(r);
+}
+
+// ------------------------------------------------------------------------------------------
+// pool
+// ------------------------------------------------------------------------------------------
+PoolArgs pool_args(slide_ctx* c, const Layout& y, const void* feats, long long N, int label) {
+  PoolArgs p{};
+  char* ar = c->arena;
+  p.H = (const float*)feats; p.N = N; p.D = c->D; p.Mh = c->Mh; p.C = c->C; p.label = label;
+  p.VW = c->params + c->o_VW; p.Vb = c->params + c->o_Vb; p.UW = c->params + c->o_UW; p.Ub = c->params + c->o_Ub;
+  p.w = c->params + c->o_w; p.cW = c->params + c->o_cW; p.cb = c->params + c->o_cb;
+  p.a = (float*)(ar + y.p_a); p.part = (double*)(ar + y.p_part); p.scal = (float*)(ar + y.p_scal);
+  p.blocks = pool_blocks(N);
+  p.grads = c->grads; p.ocW = c->o_cW; p.ocb = c->o_cb;
+  return p;
+}
+
+int pool_fwd(slide_ctx* c, const Layout& y, const void* feats, long long N, int label, float* loss, float* logits,
+             float* alpha, hipStream_t s) {
+  Run r{c, s};
+  PoolArgs p = pool_args(c, y, feats, N, label);
+  p.loss = loss; p.logits = logits; p.alpha = alpha;
+  launch(r, K_POOL_FWD, 4.0 * N * c->D * c->Mh, (double)N * c->D * 4, [&] { return launch_pool_fwd(p, s); });
+  return finish(r);
+}
+
+int pool_bwd(slide_ctx* c, const Layout& y, const void* feats, long long N, int label, void* G, int accumulate,
+             hipStream_t s) {
+  Run r{c, s};
+  char* ar = c->arena;
+  PoolArgs p = pool_args(c, y, feats, N, label);
+  p.G = (float*)G; p.accumulate = accumulate;
+  int D = c->D, Mh = c->Mh;
+  launch(r, K_POOL_FWD, 4.0 * N * D * Mh, (double)N * D * 4, [&] { return launch_pool_fwd(p, s); });
+  char* Dp = ar + y.p_Dp;
+  launch(r, K_POOL_BWD, 8.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_rows(p, (float*)Dp, s); });
+  RowMap id{0, 0};
+  float* tn = (float*)(ar + y.p_tn);
+  float* cs = (float*)(ar + y.p_cs);
+  gemm_tn(r, Dp, 3 * Mh, id, feats, D, id, N, Mh, D, tn, c->grads + c->o_VW, accumulate, DT_F32);
+  gemm_tn(r, Dp + (size_t)Mh * 4, 3 * Mh, id, feats, D, id, N, Mh, D, tn, c->grads + c->o_UW, accumulate, DT_F32);
+  int slabs = colsum_slabs(N);
+  launch(r, K_COLSUM, 0, (double)N * 3 * Mh * 4,
+         [&] { return launch_colsum_part(DT_F32, Dp, 3 * Mh, id, N, 3 * Mh, cs, slabs, s); });
+  launch(r, K_ELEMWISE, 0, 0,
+         [&] { return launch_reduce_partials(cs, slabs, 3 * Mh, Mh, c->grads + c->o_Vb, accumulate, s); });
+  launch(r, K_ELEMWISE, 0, 0,
+         [&] { return launch_reduce_partials(cs + Mh, slabs, 3 * Mh, Mh, c->grads + c->o_Ub, accumulate, s); });
+  launch(r, K_ELEMWISE, 0, 0,
+         [&] { return launch_reduce_partials(cs + 2 * Mh, slabs, 3 * Mh, Mh, c->grads + c->o_w, accumulate, s); });
+  return finish(r);
+}
+
+}  // namespace
+
+// ============================================================================================
+// C ABI
+// ============================================================================================
+extern "C" {
+
+int slide_ctx_create(const slide_config* cfg, slide_ctx** out) {
+  if (!cfg || !out) return SLIDE_EINVAL;
+  *out = nullptr;
+  if (cfg->tile <= 0 || cfg->patch <= 0 || cfg->tile % cfg->patch) return SLIDE_EINVAL;
+  if (cfg->dim <= 0 || cfg->heads <= 0 || cfg->dim % cfg->heads) return SLIDE_EINVAL;
+  if (cfg->layers < 0 || cfg->mlp_ratio <= 0 || cfg->mil_hidden <= 0 || cfg->n_classes <= 0) return SLIDE_EINVAL;
+  if (cfg->dtype != DT_F32 && cfg->dtype != DT_BF16) return SLIDE_EINVAL;
+  if (!(cfg->ln_eps > 0.f)) return SLIDE_EINVAL;
+  int dh = cfg->dim / cfg->heads;
+  int g = cfg->tile / cfg->patch;
+  int T = g * g + 1;
+  if (dh != 8 && dh != 32 && dh != 64) return SLIDE_EUNSUPPORTED;
+  if (cfg->dim > 1024 || cfg->n_classes > 64 || cfg->mil_hidden > 1024) return SLIDE_EUNSUPPORTED;
+  if (attn_lds_bytes(T, dh) > 160 * 1024) return SLIDE_EUNSUPPORTED;
+  if (cfg->recompute != 0) return SLIDE_EUNSUPPORTED;
+  slide_ctx* c = new (std::nothrow) slide_ctx();
+  if (!c) return SLIDE_EINVAL;
+  c->cfg = *cfg;
+  c->g = g; c->g2 = g * g; c->T = T; c->D = cfg->dim; c->F = cfg->mlp_ratio * cfg->dim;
+  c->Kp = 3 * cfg->patch * cfg->patch; c->dh = dh; c->L = cfg->layers; c->H = cfg->heads;
+  c->Mh = cfg->mil_hidden; c->C = cfg->n_classes; c->dt = cfg->dtype;
+  size_t D = c->D, F = c->F;
+  c->o_peW = add_tensor(c, "pe.W", D * c->Kp);
+  c->o_peb = add_tensor(c, "pe.b", D);
+  c->o_cls = add_tensor(c, "cls", D);
+  c->o_pos = add_tensor(c, "pos", (size_t)T * D);
+  add_shadow(c, c->o_peW, (int)D, c->Kp);
+  for (int l = 0; l < c->L; ++l) {
+    std::string p = "l" + std::to_string(l) + ".";
+    LayerOff o;
+    o.ln1g = add_tensor(c, p + "ln1.g", D);
+    o.ln1b = add_tensor(c, p + "ln1.b", D);
+    o.qkvW = add_tensor(c, p + "qkv.W", 3 * D * D);
+    o.qkvb = add_tensor(c, p + "qkv.b", 3 * D);
+    o.projW = add_tensor(c, p + "proj.W", D * D);
+    o.projb = add_tensor(c, p + "proj.b", D);
+    o.ln2g = add_tensor(c, p + "ln2.g", D);
+    o.ln2b = add_tensor(c, p + "ln2.b", D);
+    o.fc1W = add_tensor(c, p + "fc1.W", F * D);
+    o.fc1b = add_tensor(c, p + "fc1.b", F);
+    o.fc2W = add_tensor(c, p + "fc2.W", D * F);
+    o.fc2b = add_tensor(c, p + "fc2.b", D);
+    c->lo.push_back(o);
+    add_shadow(c, o.qkvW, (int)(3 * D), (int)D);
+    add_shadow(c, o.projW, (int)D, (int)D);
+    add_shadow(c, o.fc1W, (int)F, (int)D);
+    add_shadow(c, o.fc2W, (int)D, (int)F);
+  }
+  c->o_lnfg = add_tensor(c, "lnf.g", D);
+  c->o_lnfb = add_tensor(c, "lnf.b", D);
+  c->o_VW = add_tensor(c, "mil.V.W", (size_t)c->Mh * D);
+  c->o_Vb = add_tensor(c, "mil.V.b", c->Mh);
+  c->o_UW = add_tensor(c, "mil.U.W", (size_t)c->Mh * D);
+  c->o_Ub = add_tensor(c, "mil.U.b", c->Mh);
+  c->o_w = add_tensor(c, "mil.w", c->Mh);
+  c->o_cW = add_tensor(c, "head.W", (size_t)c->C * D);
+  c->o_cb = add_tensor(c, "head.b", c->C);
+  if ((size_t)c->Mh * D > c->max_w) c->max_w = (size_t)c->Mh * D;
+  const char* env = getenv("SLIDE_NO_MFMA");
+  c->use_mfma = !(env && env[0] == '1');
+  *out = c;
+  return SLIDE_OK;
+}
+
+void slide_ctx_destroy(slide_ctx* c) {
+  if (!c) return;
+  for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
+  delete c;
+}
+
+size_t slide_param_count(const slide_ctx* c) { return c ? c->n_params : 0; }
+int slide_param_tensors(const slide_ctx* c) { return c ? (int)c->tensors.size() : 0; }
+
+int slide_param_name(const slide_ctx* c, int index, char* name_out, size_t name_cap, size_t* offset, size_t* length) {
+  if (!c || index < 0 || index >= (int)c->tensors.size()) return SLIDE_EINVAL;
+  const Tensor& t = c->tensors[index];
+  if (name_out) {
+    if (name_cap < t.name.size() + 1) return SLIDE_EINVAL;
+    memcpy(name_out, t.name.c_str(), t.name.size() + 1);
+  }
+  if (offset) *offset = t.off;
+  if (length) *length = t.len;
+  return SLIDE_OK;
+}
+
+int slide_param_offset(const slide_ctx* c, const char* name, size_t* offset, size_t* length) {
+  if (!c || !name) return SLIDE_EINVAL;
+  for (const Tensor& t : c->tensors)
+    if (t.name == name) {
+      if (offset) *offset = t.off;
+      if (length) *length = t.len;
+      return SLIDE_OK;
+    }
+  return SLIDE_EINVAL;
+}
+
+size_t slide_arena_bytes(const slide_ctx* c, int64_t n_tiles) {
+  if (!c || n_tiles <= 0) return 0;
+  return make_layout(c, n_tiles, n_tiles, true).total;
+}
+
+size_t slide_pool_arena_bytes(const slide_ctx* c, int64_t N) {
+  if (!c || N <= 0) return 0;
+  return make_layout(c, 0, N, false).pool_end;
+}
+
+int slide_bind(slide_ctx* c, const float* params, float* grads, void* arena, size_t arena_bytes) {
+  if (!c || !params || !grads || !arena) return SLIDE_EINVAL;
+  if (((uintptr_t)arena & 255) != 0) return SLIDE_EINVAL;
+  c->params = params; c->grads = grads; c->arena = (char*)arena; c->arena_bytes = arena_bytes;
+  c->enc_saved = false; c->step_saved = false;
+  return SLIDE_OK;
+}
+
+int encoder_fwd_tiles(slide_ctx* c, const void* pixels, int64_t n, void* feats_out, int save, void* stream) {
+  int rc = check_bound(c);
+  if (rc) return rc;
+  if (!pixels || !feats_out || n <= 0) return SLIDE_EINVAL;
+  return enc_fwd(c, pixels, n, feats_out, save != 0, n, (hipStream_t)stream);
+}
+
+int encoder_bwd_tiles(slide_ctx* c, const void* dfeats, int64_t n, int accumulate, void* pixel_grad, void* stream) {
+  int rc = check_bound(c);
+  if (rc) return rc;
+  if (!dfeats || n <= 0) return SLIDE_EINVAL;
+  return enc_bwd(c, dfeats, n, accumulate, pixel_grad, (hipStream_t)stream);
+}
+
+static int pool_check(slide_ctx* c, const void* feats, int64_t N, int32_t label, Layout* y) {
+  int rc = check_bound(c);
+  if (rc) return rc;
+  if (!feats || N <= 0) return SLIDE_EINVAL;
+  if (label < 0 || label >= (c->C == 1 ? 2 : c->C)) return SLIDE_EINVAL;
+  *y = make_layout(c, 0, N, false);
+  if (y->pool_end > c->arena_bytes) return SLIDE_EARENA;
+  // a pool over more rows than the saved encoder state was laid out for would overwrite it
+  if (c->enc_saved && y->pool_end > c->enc_layout.enc_begin) { c->enc_saved = false; c->step_saved = false; }
+  return SLIDE_OK;
+}
+
+int mil_pool_fwd(slide_ctx* c, const void* feats, int64_t N, int32_t label, float* loss, float* logits, float* alpha,
+                 void* stream) {
+  Layout y;
+  int rc = pool_check(c, feats, N, label, &y);
+  if (rc) return rc;
+  return pool_fwd(c, y, feats, N, label, loss, logits, alpha, (hipStream_t)stream);
+}
+
+int mil_pool_bwd(slide_ctx* c, const void* feats, int64_t N, int32_t label, void* dfeats_out, int accumulate,
+                 void* stream) {
+  Layout y;
+  int rc = pool_check(c, feats, N, label, &y);
+  if (rc) return rc;
+  if (!dfeats_out) return SLIDE_EINVAL;
+  return pool_bwd(c, y, feats, N, label, dfeats_out, accumulate, (hipStream_t)stream);
+}
+
+int slide_step_fwd(slide_ctx* c, const void* pixels, int64_t N, int32_t label, float* loss, float* logits,
+                   float* alpha, void* stream) {
+  int rc = check_bound(c);
+  if (rc) return rc;
+  if (!pixels || N <= 0) return SLIDE_EINVAL;
+  if (label < 0 || label >= (c->C == 1 ? 2 : c->C)) return SLIDE_EINVAL;
+  Layout y = make_layout(c, N, N, true);
+  if (y.total > c->arena_bytes) return SLIDE_EARENA;
+  rc = enc_fwd(c, pixels, N, c->arena + y.p_H, true, N, (hipStream_t)stream);
+  if (rc) return rc;
+  rc = pool_fwd(c, y, c->arena + y.p_H, N, label, loss, logits, alpha, (hipStream_t)stream);
+  if (rc) { c->enc_saved = false; return rc; }
+  c->step_saved = true;
+  c->step_label = label;
+  return SLIDE_OK;
+}
+
+int slide_step_bwd(slide_ctx* c, int accumulate, void* pixel_grad, void* stream) {
+  int rc = check_bound(c);
+  if (rc) return rc;
+  if (!c->step_saved || !c->enc_saved) return SLIDE_ESTATE;
+  const Layout y = c->enc_layout;
+  long long N = c->enc_n;
+  rc = pool_bwd(c, y, c->arena + y.p_H, N, c->step_label, c->arena + y.p_G, accumulate, (hipStream_t)stream);
+  if (rc) return rc;
+  rc = enc_bwd(c, c->arena + y.p_G, N, accumulate, pixel_grad, (hipStream_t)stream);
+  c->step_saved = false;  // activations are consumed (work buffers were overwritten)
+  c->enc_saved = false;
+  return rc;
+}
+
+const void* slide_features(const slide_ctx* c) {
+  if (!c || !c->arena) return nullptr;
+  return c->arena + c->enc_layout.p_H;
+}
+const void* slide_feature_grads(const slide_ctx* c) {
+  if (!c || !c->arena) return nullptr;
+  return c->arena + c->enc_layout.p_G;
+}
+
+int slide_last_hip_error(void) { return g_last_hip; }
+
+int slide_prof_begin(slide_ctx* c, int kernel_id) {
+  if (!c || kernel_id < 0 || kernel_id >= K_COUNT) return SLIDE_EINVAL;
+  c->prof.active = true; c->prof.id = kernel_id; c->prof.count = 0; c->prof.flops = 0; c->prof.bytes = 0;
+  return SLIDE_OK;
+}
+
+int slide_prof_end(slide_ctx* c, double* total_ms, int* launches, double* flops, double* bytes) {
+  if (!c) return SLIDE_EINVAL;
+  Prof& p = c->prof;
+  double tot = 0;
+  int rc = SLIDE_OK;
+  for (int i = 0; i < p.count; ++i) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(p.ev[2 * i + 1]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]);
+    if (e != hipSuccess) { g_last_hip = (int)e; rc = SLIDE_EHIP; break; }
+    tot += ms;
+  }
+  if (total_ms) *total_ms = tot;
+  if (launches) *launches = p.count;
+  if (flops) *flops = p.flops;
+  if (bytes) *bytes = p.bytes;
+  p.active = false;
+  return rc;
+}
+
+const char* slide_kernel_name(int id) { return (id >= 0 && id < K_COUNT) ? kKernelNames[id] : nullptr; }
+
+}  // extern "C"

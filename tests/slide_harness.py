@@ -1,0 +1,131 @@
+"""Test-side glue between the seeded generators, the ctypes binding and the CPU oracle."""
+from __future__ import annotations
+
+import numpy as np
+
+import gen
+
+
+def lib_config(cfg: gen.SlideConfig, dtype: int, recompute: int = 0):
+    from paper_2403_04865_amd import SlideConfig
+    return SlideConfig(cfg.tile, cfg.patch, cfg.dim, cfg.layers, cfg.heads, cfg.mlp_ratio, cfg.mil_hidden,
+                       cfg.n_classes, dtype=dtype, recompute=recompute, ln_eps=cfg.ln_eps)
+
+
+class GpuSlide:
+    """A bound library context on cuda:0 with flat parameter / gradient vectors."""
+
+    def __init__(self, cfg: gen.SlideConfig, prm: dict, dtype: int, n_tiles: int, recompute: int = 0):
+        import torch
+        from paper_2403_04865_amd import SlideLib
+        self.torch = torch
+        self.cfg = cfg
+        self.dtype = dtype
+        self.tt = torch.float32 if dtype == 0 else torch.bfloat16
+        self.dev = torch.device("cuda:0")
+        self.lib = SlideLib(lib_config(cfg, dtype, recompute))
+        self.layout = self.lib.param_layout()
+        flat = np.zeros(self.lib.slide_param_count(), dtype=np.float32)
+        shapes = dict(gen.param_shapes(cfg))
+        assert [n for n, _, _ in self.layout] == [n for n, _ in gen.param_shapes(cfg)]
+        for name, off, ln in self.layout:
+            assert int(np.prod(shapes[name])) == ln, name
+            flat[off:off + ln] = np.asarray(prm[name], dtype=np.float32).reshape(-1)
+        self.shapes = shapes
+        self.params = torch.from_numpy(flat).to(self.dev)
+        self.grads = torch.zeros_like(self.params)
+        self.arena = torch.empty(self.lib.slide_arena_bytes(n_tiles) + 256, dtype=torch.uint8, device=self.dev)
+        off = (-self.arena.data_ptr()) % 256
+        self.arena = self.arena[off:off + self.lib.slide_arena_bytes(n_tiles)]
+        self.lib.slide_bind(self.params, self.grads, self.arena)
+
+    def to_dev(self, x):
+        return self.torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(self.dev).to(self.tt).contiguous()
+
+    def grads_dict(self):
+        g = self.grads.cpu().numpy()
+        return {name: g[off:off + ln].reshape(self.shapes[name]).astype(np.float64) for name, off, ln in self.layout}
+
+    def view(self, ptr, shape):
+        """Copy a [*shape] float32 tensor out of the arena at device pointer `ptr`."""
+        torch = self.torch
+        off = ptr - self.arena.data_ptr()
+        n = int(np.prod(shape)) * 4
+        return self.arena[off:off + n].view(torch.float32).reshape(shape).cpu().numpy().astype(np.float64)
+
+    def step(self, X, label, want_pixel_grad=True, accumulate=False):
+        torch = self.torch
+        N = X.shape[0]
+        px = self.to_dev(X)
+        loss = torch.zeros(1, device=self.dev)
+        logits = torch.zeros(self.cfg.n_classes, device=self.dev)
+        alpha = torch.zeros(N, device=self.dev)
+        dX = torch.zeros_like(px) if want_pixel_grad else None
+        self.lib.slide_step_fwd(px, N, label, loss, logits, alpha)
+        H = self.view(self.lib.slide_features(), (N, self.cfg.dim))
+        self.lib.slide_step_bwd(accumulate, dX)
+        torch.cuda.synchronize()
+        G = self.view(self.lib.slide_feature_grads(), (N, self.cfg.dim))
+        return {"loss": float(loss.item()), "logits": logits.cpu().numpy().astype(np.float64),
+                "alpha": alpha.cpu().numpy().astype(np.float64), "H": H, "G": G, "grads": self.grads_dict(),
+                "dX": None if dX is None else dX.float().cpu().numpy().astype(np.float64)}
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64).reshape(-1)
+    b = np.asarray(b, dtype=np.float64).reshape(-1)
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / nb) if nb > 0 else float(np.linalg.norm(a - b))
+
+
+GATE = ("mil.V.W", "mil.V.b", "mil.U.W", "mil.U.b", "mil.w")
+
+
+def feature_spread(H):
+    """kappa = |H| / |H - mean row|: how much a relative perturbation of the feature rows is
+    amplified in quantities that depend only on differences between rows."""
+    H = np.asarray(H, dtype=np.float64)
+    return float(np.linalg.norm(H) / max(np.linalg.norm(H - H.mean(axis=0, keepdims=True)), 1e-300))
+
+
+def compare_step(gpu, ref, tol, cfg, grad_tol=None, pool_same_input=None):
+    """Relative-L2 comparison of every output.
+
+    * The key-bias third of each qkv.b is analytically zero (a per-key constant shift is
+      softmax-invariant): checked absolutely against the norm of the whole tensor.
+    * The gate tensors of the pool (mil.V.*, mil.U.*, mil.w) depend on the features only
+      through differences between rows (sum_n da_n = 0), so a relative error eps in the
+      features appears amplified by kappa = |H| / |H - mean row|.  They are therefore held
+      to `grad_tol` against the oracle's pool evaluated on the SAME feature matrix the GPU
+      produced (`pool_same_input`: dict of oracle pool gradients on gpu["H"]), and end to
+      end to kappa * tol.
+    """
+    grad_tol = tol if grad_tol is None else grad_tol
+    errs, lim = {}, {}
+    errs["loss"] = abs(gpu["loss"] - ref["loss"]) / max(abs(ref["loss"]), 1e-12)
+    for k in ("logits", "alpha", "H", "G"):
+        errs[k] = rel_l2(gpu[k], ref[k])
+    if gpu.get("dX") is not None and ref.get("dX") is not None:
+        errs["dX"] = rel_l2(gpu["dX"], ref["dX"])
+    for k in errs:
+        lim[k] = tol
+    D = cfg.dim
+    kappa = feature_spread(ref["H"])
+    for name, g in ref["grads"].items():
+        a = gpu["grads"][name]
+        if name.endswith("qkv.b"):
+            full = np.linalg.norm(g)
+            errs[name + "[q,v]"] = float(np.linalg.norm(np.concatenate([a[:D] - g[:D], a[2 * D:] - g[2 * D:]])) /
+                                         np.linalg.norm(np.concatenate([g[:D], g[2 * D:]])))
+            errs[name + "[k]abs"] = float(np.linalg.norm(a[D:2 * D]) / full)
+            lim[name + "[q,v]"] = lim[name + "[k]abs"] = grad_tol
+        elif name in GATE and pool_same_input is not None:
+            errs[name + "@sameH"] = rel_l2(a, pool_same_input[name])
+            lim[name + "@sameH"] = grad_tol
+            errs[name + "@e2e"] = rel_l2(a, g)
+            lim[name + "@e2e"] = max(grad_tol, kappa * tol)
+        else:
+            errs[name] = rel_l2(a, g)
+            lim[name] = grad_tol
+    bad = {k: (v, lim[k]) for k, v in errs.items() if not v <= lim[k]}
+    return errs, bad, kappa
