@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the slide step on one MI355X.
+
+A "step" is one whole slide step (slide_step_fwd + slide_step_bwd: encoder forward and backward
+over every tile, gated-attention pool forward and backward, all parameter gradients) on one
+synthetic slide that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|medium|small|full]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+# model FLOPs per tile, forward + backward (2mnk per GEMM, both attention GEMMs, dgrad + wgrad,
+# no pixel gradient)
+def model_flops_per_tile(cfg):
+    T, D, F, H = cfg.tokens, cfg.dim, cfg.ffn, cfg.heads
+    dh = D // H
+    g2 = T - 1
+    per_layer = 2 * T * D * 3 * D + 2 * T * D * D + 2 * 2 * T * D * F + 2 * 2 * H * T * T * dh
+    fwd = 2 * g2 * cfg.patch_dim * D + cfg.layers * per_layer
+    bwd = 2 * g2 * cfg.patch_dim * D + 2 * cfg.layers * per_layer   # patch embed: wgrad only
+    return fwd + bwd
+
+
+PEAK = {"mfma_bf16": 2.5e15, "hbm": 8e12}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--tiles", type=int, default=0, help="override the tile count (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tiles", type=int, default=16)
+    ap.add_argument("--prof-kernel", default="gemm_nt")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import gen
+    from slide_harness import lib_config
+    from paper_2403_04865_amd import SlideLib
+
+    cfg, N = gen.CONFIGS[a.workload]
+    if a.tiles:
+        N = a.tiles
+    ds, ws, ls = gen.SEEDS[a.workload]
+    dev = torch.device("cuda:0")
+    dtype = 1  # bf16 storage / fp32 accumulate
+    lib = SlideLib(lib_config(cfg, dtype))
+    layout = lib.param_layout()
+    prm = gen.make_params(cfg, ws)
+    flat = np.zeros(lib.slide_param_count(), dtype=np.float32)
+    for name, off, ln in layout:
+        flat[off:off + ln] = prm[name].reshape(-1)
+    params = torch.from_numpy(flat).to(dev)
+    grads = torch.zeros_like(params)
+    nbytes = lib.slide_arena_bytes(N)
+    arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    o = (-arena.data_ptr()) % 256
+    arena = arena[o:o + nbytes]
+    lib.slide_bind(params, grads, arena)
+
+    # synthetic slide -> HBM (bf16), generated and uploaded in chunks
+    t0 = time.time()
+    px = torch.empty((N, 3, cfg.tile, cfg.tile), dtype=torch.bfloat16, device=dev)
+    step = 512
+    workers = min(16, os.cpu_count() or 1)
+    for lo in range(0, N, step):
+        hi = min(N, lo + step)
+        x = gen.make_pixels(cfg, hi - lo, ds, first_tile=lo, workers=workers)
+        px[lo:hi] = torch.from_numpy(x).to(dev).to(torch.bfloat16)
+    label = gen.make_label(cfg, ls)
+    gen_s = time.time() - t0
+
+    loss = torch.zeros(1, device=dev)
+    logits = torch.zeros(cfg.n_classes, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def one_step():
+        lib.slide_step_fwd(px, N, label, loss, logits, None, stream)
+        lib.slide_step_bwd(0, None, stream)
+
+    for _ in range(a.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    kid = lib.kernel_names().index(a.prof_kernel)
+    lib.slide_prof_begin(kid)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    k_ms, k_n, k_flops, k_bytes = lib.slide_prof_end()
+    peak_alloc = torch.cuda.max_memory_allocated() / 1e9
+
+    ms_per_step = dt / a.steps * 1e3
+    tiles_per_s = N * a.steps / dt
+    mflops = model_flops_per_tile(cfg)
+    mfu = tiles_per_s * mflops / PEAK["mfma_bf16"]
+    achieved = (k_flops / (k_ms * 1e-3)) / 1e12 if k_ms > 0 else 0.0   # TFLOP/s of the profiled kernel family
+    roof = {"bound": "mfma", "kernel": a.prof_kernel, "achieved": round(achieved, 2), "peak": 2500.0,
+            "unit": "TFLOP/s", "frac": round(achieved / 2500.0, 4), "traffic": None,
+            "launches": k_n, "avg_launch_ms": round(k_ms / max(k_n, 1), 4),
+            "share_of_step": round(k_ms / (dt * 1e3), 4)}
+
+    cpu = None
+    if not a.no_cpu_baseline:
+        from oracle import slide_oracle as so
+        from threadpoolctl import threadpool_info
+        nt = a.cpu_tiles
+        Xc = px[:nt].float().cpu().numpy().astype(np.float64)
+        prm_b = {k: gen.to_bf16_grid(v) for k, v in prm.items()}
+        t0 = time.perf_counter()
+        so.slide_step(prm_b, Xc, label, cfg, want_pixel_grad=False)
+        cs = time.perf_counter() - t0
+        cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+        cpu = {"value": round(nt / cs, 3), "unit": "tiles/s", "cores": cores, "kind": "oracle",
+               "sample": f"{nt} tiles of the same slide, fp64 numpy oracle, full fwd+bwd step"}
+
+    out = {
+        "metric": "tiles/sec fwd+bwd per slide step (1 MI355X); MFMA util % of bf16 peak",
+        "value": round(tiles_per_s, 2), "unit": "tiles/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: {N} tiles {cfg.tile}x{cfg.tile}x3, ViT dim {cfg.dim} x {cfg.layers} layers "
+                               f"x {cfg.heads} heads, gated-attention MIL hidden {cfg.mil_hidden}, {cfg.n_classes} classes",
+                   "tiles": N, "slide_steps_per_s": round(a.steps / dt, 4),
+                   "model_gflop_per_tile": round(mflops / 1e9, 3), "mfu_bf16_peak": round(mfu, 4),
+                   "arena_gb": round(nbytes / 1e9, 2), "peak_alloc_gb_of_288": round(peak_alloc, 2),
+                   "loss": float(loss.item()), "input_gen_s": round(gen_s, 1)},
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

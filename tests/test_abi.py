@@ -1,0 +1,83 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol slide.h declares,
+and its pure-host calls (validation, layout, arena arithmetic) behave as documented."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import gen
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2403_04865_amd.binding import lib_path, load_cdll
+    if not os.path.exists(lib_path()):
+        from paper_2403_04865_amd.build import build
+        build()
+    return load_cdll()
+
+
+def test_header_symbols_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "slide.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b([a-z_0-9]+)\s*\(", hdr)) - {"defined"}
+    names = {n for n in names if n.startswith(("slide_", "encoder_", "mil_"))}
+    assert {"slide_step_fwd", "slide_step_bwd", "encoder_fwd_tiles", "mil_pool_fwd", "mil_pool_bwd"} <= names
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_layout_matches_generator_names():
+    from paper_2403_04865_amd import SlideLib
+    from slide_harness import lib_config
+    for name in ("tiny", "small", "full"):
+        cfg, _ = gen.CONFIGS[name]
+        L = SlideLib(lib_config(cfg, 1))
+        lay = L.param_layout()
+        shapes = gen.param_shapes(cfg)
+        assert [n for n, _, _ in lay] == [n for n, _ in shapes]
+        off = 0
+        for (n, o, ln), (_, shp) in zip(lay, shapes):
+            size = 1
+            for s in shp:
+                size *= s
+            assert o == off and ln == size, n
+            off += ln
+        assert off == L.slide_param_count()
+        assert L.slide_param_offset("mil.w") == (lay[-3][1], cfg.mil_hidden)
+
+
+def test_config_validation():
+    from paper_2403_04865_amd import SlideLib, SlideConfig, SlideError
+    ok = dict(tile=32, patch=8, dim=64, layers=2, heads=2, mlp_ratio=4, mil_hidden=32, n_classes=1)
+    SlideLib(SlideConfig(**ok))
+    for bad in (dict(tile=30), dict(heads=3), dict(n_classes=0), dict(dtype=2), dict(layers=-1), dict(ln_eps=0.0)):
+        with pytest.raises(SlideError) as e:
+            SlideLib(SlideConfig(**{**ok, **bad}))
+        assert e.value.code == -1
+    with pytest.raises(SlideError) as e:
+        SlideLib(SlideConfig(**{**ok, "heads": 4}))     # head width 16 is not built
+    assert e.value.code == -3
+
+
+def test_arena_arithmetic_and_unbound_calls(lib):
+    from paper_2403_04865_amd import SlideLib, SlideError
+    from slide_harness import lib_config
+    cfg, _ = gen.CONFIGS["large"]
+    L = SlideLib(lib_config(cfg, 1))
+    assert L.slide_arena_bytes(0) == 0
+    sizes = [L.slide_arena_bytes(n) for n in (1, 16, 256, 8192)]
+    assert sizes == sorted(sizes) and sizes[-1] < 288e9
+    assert all(s % 256 == 0 for s in sizes)
+    assert L.slide_pool_arena_bytes(8192) < sizes[2]
+    # nothing bound yet: compute calls refuse without touching the GPU
+    with pytest.raises(SlideError) as e:
+        L._check(L.lib.slide_step_bwd(L.ctx, 0, None, None), "slide_step_bwd")
+    assert e.value.code == -4
+    with pytest.raises(SlideError) as e:
+        L._check(L.lib.encoder_fwd_tiles(L.ctx, None, 4, None, 0, None), "encoder_fwd_tiles")
+    assert e.value.code == -4
+    assert L.kernel_names()[0] == "gemm_nt"
