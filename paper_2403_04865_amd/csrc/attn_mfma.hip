@@ -1,13 +1,447 @@
-// bf16 MFMA attention for gfx950 (placeholder until the tiled kernels land: reports "not available").
+// bf16 MFMA softmax attention inside one tile for gfx950 (v_mfma_f32_32x32x16_bf16).
+//
+// One workgroup (4 wavefronts) per (tile, head); all keys/values of the head sit in LDS.
+// Scores are produced TRANSPOSED (keys x queries): a 32x32 accumulator block then holds one
+// query per lane column and the keys down the registers, so the softmax over keys is a
+// reduction inside each lane plus one exchange between the two lane halves, and the
+// probabilities are already in the lane layout the next MFMA wants as its B operand.
+// Operands whose contraction index is the row index of a row-major matrix (V in P.V, K in
+// dS.K, Q and dO in the key-owned backward) are transposed 8x8 in registers while being
+// copied into LDS.
+//
+// Backward is two deterministic passes, both recomputing P from the saved row log-sum-exp:
+//   pass Q (query blocks owned by a wave): dQ = scale * dS K
+//   pass K (key blocks owned by a wave):   dV = P^T dO,  dK = scale * dS^T Q
+// with dS = P * (dP - delta), dP = dO V^T, delta_i = dO_i . O_i.  No atomics.
 #include "slide_internal.h"
 
 namespace sl {
-bool attn_mfma_ok(int, int) { return false; }
-hipError_t launch_attn_fwd_mfma(const void*, void*, float*, long long, int, int, int, hipStream_t) {
-  return hipErrorNotSupported;
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ u32x4 ldg16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+__device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    int w = c >> 1;
+    unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
+    u32x4 o;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) o[p] = __builtin_amdgcn_perm(in[2 * p + 1][w], in[2 * p][w], sel);
+    out[c] = o;
+  }
 }
-hipError_t launch_attn_bwd_mfma(const void*, const void*, const float*, const void*, void*, long long, int, int, int,
-                                hipStream_t) {
-  return hipErrorNotSupported;
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// pack 8 floats into the bf16x8 B operand
+__device__ __forceinline__ bf16x8 pack8(const float* p) {
+  bf16x8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) o[i] = (bf16)p[i];
+  return o;
 }
+
+// A operand from a transposed LDS image Xt[d][j] (row stride ldt): 8 contraction indices
+// j0 + 4*h2 + {0..3} and j0 + 8 + 4*h2 + {0..3}, matching accumulator registers 8t..8t+7.
+__device__ __forceinline__ bf16x8 frag_t(const bf16* Xt, int ldt, int d, int j0, int h2) {
+  const bf16* p = Xt + d * ldt + j0 + 4 * h2;
+  u32x2 a = *reinterpret_cast<const u32x2*>(p);
+  u32x2 b = *reinterpret_cast<const u32x2*>(p + 8);
+  u32x4 v = {a[0], a[1], b[0], b[1]};
+  return as_bf16x8(v);
+}
+
+// copy rows [0,T) x DH of a row-major global matrix (row stride gs) into LDS row-major [TP][DH+8]
+template <int DH>
+__device__ __forceinline__ void load_rm(const bf16* __restrict__ g, long long gs, int T, int TP, bf16* dst) {
+  constexpr int CH = DH / 8;
+  for (int c = threadIdx.x; c < TP * CH; c += blockDim.x) {
+    int row = c / CH, kc = c % CH;
+    u32x4 v = {0, 0, 0, 0};
+    if (row < T) v = ldg16(g + row * gs + kc * 8);
+    *reinterpret_cast<u32x4*>(dst + row * (DH + 8) + kc * 8) = v;
+  }
+}
+
+// same source, transposed into LDS [DH][TP+8]
+template <int DH>
+__device__ __forceinline__ void load_tr(const bf16* __restrict__ g, long long gs, int T, int TP, bf16* dst) {
+  constexpr int NDB = DH / 8;
+  int nblk = (TP / 8) * NDB;
+  for (int b = threadIdx.x; b < nblk; b += blockDim.x) {
+    int jb = b / NDB, db = b % NDB;
+    u32x4 v[8], o[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      int j = jb * 8 + r;
+      v[r] = u32x4{0, 0, 0, 0};
+      if (j < T) v[r] = ldg16(g + j * gs + db * 8);
+    }
+    transpose8x8(v, o);
+#pragma unroll
+    for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4*>(dst + (db * 8 + c) * (TP + 8) + jb * 8) = o[c];
+  }
+}
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+// --------------------------------------------------------------------------------------------
+// forward
+// --------------------------------------------------------------------------------------------
+template <int DH, int NB>
+__global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict__ qkv, bf16* __restrict__ O,
+                                                       float* __restrict__ lse, int T, int H) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
+  bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
+  bf16* Vt = Ks + TP * LDR;                  // [DH][LDT]
+  int h = blockIdx.x % H;
+  long long tile = blockIdx.x / H;
+  int D = H * DH;
+  long long gs = 3LL * D;
+  const bf16* base = qkv + tile * T * gs + h * DH;
+  load_rm<DH>(base + D, gs, T, TP, Ks);
+  load_tr<DH>(base + 2 * D, gs, T, TP, Vt);
+  __syncthreads();
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int li = lane & 31, h2 = lane >> 5;
+  float sl2 = LOG2E / sqrtf((float)DH);
+  for (int qb = wave; qb < NB; qb += 4) {
+    int q = qb * 32 + li;
+    int qc = q < T ? q : T - 1;
+    bf16x8 fq[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fq[ks] = as_bf16x8(ldg16(base + qc * gs + ks * 16 + h2 * 8));
+    f32x16 s[NB];
+#pragma unroll
+    for (int kb = 0; kb < NB; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fq[ks], s[kb], 0, 0, 0);
+      }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int key = kb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
+        if (key >= T) s[kb][r] = -INFINITY;
+        mx = fmaxf(mx, s[kb][r]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    float l = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_amdgcn_exp2f((s[kb][r] - mx) * sl2);
+        s[kb][r] = p;
+        l += p;
+      }
+    l += __shfl_xor(l, 32, 64);
+    f32x16 o[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < NB; ++kb)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        float pv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pv[i] = s[kb][8 * t + i];
+        bf16x8 pb = pack8(pv);
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+          bf16x8 a = frag_t(Vt, LDT, d * 32 + li, kb * 32 + 16 * t, h2);
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[d], 0, 0, 0);
+        }
+      }
+    if (q < T) {
+      float inv = 1.0f / l;
+      bf16* orow = O + (tile * T + q) * D + h * DH;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          bf16x4 v;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = (bf16)(o[d][g4 * 4 + i] * inv);
+          *reinterpret_cast<bf16x4*>(orow + d * 32 + g4 * 8 + h2 * 4) = v;
+        }
+      if (h2 == 0) lse[(tile * H + h) * T + q] = mx * (sl2 / LOG2E) + logf(l);
+    }
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// backward, pass Q: dQ
+// --------------------------------------------------------------------------------------------
+template <int DH, int NB>
+__global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
+                                                         const float* __restrict__ lse, const bf16* __restrict__ dO,
+                                                         bf16* __restrict__ dqkv, int T, int H) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
+  bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
+  bf16* Vs = Ks + TP * LDR;                  // [TP][LDR]
+  bf16* Kt = Vs + TP * LDR;                  // [DH][LDT]
+  int h = blockIdx.x % H;
+  long long tile = blockIdx.x / H;
+  int D = H * DH;
+  long long gs = 3LL * D;
+  const bf16* base = qkv + tile * T * gs + h * DH;
+  load_rm<DH>(base + D, gs, T, TP, Ks);
+  load_rm<DH>(base + 2 * D, gs, T, TP, Vs);
+  load_tr<DH>(base + D, gs, T, TP, Kt);
+  __syncthreads();
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int li = lane & 31, h2 = lane >> 5;
+  float scale = 1.0f / sqrtf((float)DH);
+  float sl2 = LOG2E * scale;
+  for (int qb = wave; qb < NB; qb += 4) {
+    int q = qb * 32 + li;
+    int qc = q < T ? q : T - 1;
+    bf16x8 fq[KS], fdo[KS];
+    float delta = 0.f;
+    const bf16* orow = O + (tile * T + qc) * D + h * DH;
+    const bf16* gor = dO + (tile * T + qc) * D + h * DH;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      fq[ks] = as_bf16x8(ldg16(base + qc * gs + ks * 16 + h2 * 8));
+      fdo[ks] = as_bf16x8(ldg16(gor + ks * 16 + h2 * 8));
+      bf16x8 fo = as_bf16x8(ldg16(orow + ks * 16 + h2 * 8));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) delta += (float)fdo[ks][i] * (float)fo[i];
+    }
+    delta += __shfl_xor(delta, 32, 64);
+    float lq = lse[(tile * H + h) * T + qc] * LOG2E;
+    f32x16 dq[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dq[d][r] = 0.f;
+#pragma unroll 1
+    for (int kb = 0; kb < NB; ++kb) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fq[ks], s, 0, 0, 0);
+        bf16x8 v = *reinterpret_cast<const bf16x8*>(Vs + (kb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v, fdo[ks], dp, 0, 0, 0);
+      }
+      float ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int key = kb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
+        float p = key < T ? __builtin_amdgcn_exp2f(s[r] * sl2 - lq) : 0.f;
+        ds[r] = p * (dp[r] - delta);
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        bf16x8 db = pack8(ds + 8 * t);
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+          bf16x8 a = frag_t(Kt, LDT, d * 32 + li, kb * 32 + 16 * t, h2);
+          dq[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, db, dq[d], 0, 0, 0);
+        }
+      }
+    }
+    if (q < T) {
+      bf16* out = dqkv + (tile * T + q) * gs + h * DH;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          bf16x4 v;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = (bf16)(dq[d][g4 * 4 + i] * scale);
+          *reinterpret_cast<bf16x4*>(out + d * 32 + g4 * 8 + h2 * 4) = v;
+        }
+    }
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// backward, pass K: dK, dV
+// --------------------------------------------------------------------------------------------
+template <int DH, int NB>
+__global__ void __launch_bounds__(256) attn_bwd_k_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
+                                                         const float* __restrict__ lse, const bf16* __restrict__ dO,
+                                                         bf16* __restrict__ dqkv, int T, int H) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
+  bf16* Qs = reinterpret_cast<bf16*>(smem);   // [TP][LDR]
+  bf16* Gs = Qs + TP * LDR;                   // [TP][LDR]  dO
+  bf16* Qt = Gs + TP * LDR;                   // [DH][LDT]
+  bf16* Gt = Qt + DH * LDT;                   // [DH][LDT]
+  float* ls = reinterpret_cast<float*>(Gt + DH * LDT);  // [TP] lse * log2(e), +inf on padding rows
+  float* dl = ls + TP;                                  // [TP] delta
+  int h = blockIdx.x % H;
+  long long tile = blockIdx.x / H;
+  int D = H * DH;
+  long long gs = 3LL * D;
+  const bf16* base = qkv + tile * T * gs + h * DH;
+  const bf16* gbase = dO + tile * T * (long long)D + h * DH;
+  const bf16* obase = O + tile * T * (long long)D + h * DH;
+  load_rm<DH>(base, gs, T, TP, Qs);
+  load_rm<DH>(gbase, D, T, TP, Gs);
+  load_tr<DH>(base, gs, T, TP, Qt);
+  load_tr<DH>(gbase, D, T, TP, Gt);
+  for (int i = threadIdx.x; i < TP; i += blockDim.x) {
+    float d = 0.f, lv = INFINITY;
+    if (i < T) {
+#pragma unroll
+      for (int c = 0; c < DH / 8; ++c) {
+        bf16x8 a = as_bf16x8(ldg16(gbase + (long long)i * D + c * 8));
+        bf16x8 b = as_bf16x8(ldg16(obase + (long long)i * D + c * 8));
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d += (float)a[e] * (float)b[e];
+      }
+      lv = lse[(tile * H + h) * T + i] * LOG2E;
+    }
+    dl[i] = d;
+    ls[i] = lv;
+  }
+  __syncthreads();
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int li = lane & 31, h2 = lane >> 5;
+  float scale = 1.0f / sqrtf((float)DH);
+  float sl2 = LOG2E * scale;
+  for (int kb = wave; kb < NB; kb += 4) {
+    int key = kb * 32 + li;
+    int kc = key < T ? key : T - 1;
+    bf16x8 fk[KS], fv[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      fk[ks] = as_bf16x8(ldg16(base + D + kc * gs + ks * 16 + h2 * 8));
+      fv[ks] = as_bf16x8(ldg16(base + 2 * D + kc * gs + ks * 16 + h2 * 8));
+    }
+    f32x16 dk[DB], dv[DB];
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { dk[d][r] = 0.f; dv[d][r] = 0.f; }
+#pragma unroll 1
+    for (int qb = 0; qb < NB; ++qb) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(Qs + (qb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fk[ks], s, 0, 0, 0);
+        bf16x8 g = *reinterpret_cast<const bf16x8*>(Gs + (qb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g, fv[ks], dp, 0, 0, 0);
+      }
+      float p[16], ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int qi = qb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
+        p[r] = __builtin_amdgcn_exp2f(s[r] * sl2 - ls[qi]);  // padding rows: lse = +inf -> 0
+        ds[r] = p[r] * (dp[r] - dl[qi]);
+      }
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        bf16x8 pb = pack8(p + 8 * t);
+        bf16x8 db = pack8(ds + 8 * t);
+#pragma unroll
+        for (int d = 0; d < DB; ++d) {
+          bf16x8 ag = frag_t(Gt, LDT, d * 32 + li, qb * 32 + 16 * t, h2);
+          dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, pb, dv[d], 0, 0, 0);
+          bf16x8 aq = frag_t(Qt, LDT, d * 32 + li, qb * 32 + 16 * t, h2);
+          dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, db, dk[d], 0, 0, 0);
+        }
+      }
+    }
+    if (key < T) {
+      bf16* outk = dqkv + (tile * T + key) * gs + D + h * DH;
+      bf16* outv = outk + D;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          bf16x4 vk, vv;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            vk[i] = (bf16)(dk[d][g4 * 4 + i] * scale);
+            vv[i] = (bf16)dv[d][g4 * 4 + i];
+          }
+          *reinterpret_cast<bf16x4*>(outk + d * 32 + g4 * 8 + h2 * 4) = vk;
+          *reinterpret_cast<bf16x4*>(outv + d * 32 + g4 * 8 + h2 * 4) = vv;
+        }
+    }
+  }
+}
+
+template <int DH, int NB> constexpr size_t fwd_lds() { return ((size_t)NB * 32 * (DH + 8) + (size_t)DH * (NB * 32 + 8)) * 2; }
+template <int DH, int NB> constexpr size_t bq_lds() { return ((size_t)2 * NB * 32 * (DH + 8) + (size_t)DH * (NB * 32 + 8)) * 2; }
+template <int DH, int NB> constexpr size_t bk_lds() {
+  return ((size_t)2 * NB * 32 * (DH + 8) + (size_t)2 * DH * (NB * 32 + 8)) * 2 + (size_t)2 * NB * 32 * 4;
+}
+
+template <typename K>
+hipError_t set_lds(K kernel, size_t bytes) {
+  if (bytes <= 65536) return hipSuccess;
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <int DH, int NB>
+hipError_t fwd_go(const void* qkv, void* O, float* lse, long long n, int T, int H, hipStream_t s) {
+  size_t lds = fwd_lds<DH, NB>();
+  hipError_t e = set_lds(attn_fwd_mfma_k<DH, NB>, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((attn_fwd_mfma_k<DH, NB>), dim3((unsigned)(n * H)), dim3(256), lds, s,
+                     (const bf16*)qkv, (bf16*)O, lse, T, H);
+  return hipGetLastError();
+}
+
+template <int DH, int NB>
+hipError_t bwd_go(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv, long long n, int T,
+                  int H, hipStream_t s) {
+  size_t lq = bq_lds<DH, NB>(), lk = bk_lds<DH, NB>();
+  hipError_t e = set_lds(attn_bwd_q_mfma_k<DH, NB>, lq);
+  if (e != hipSuccess) return e;
+  e = set_lds(attn_bwd_k_mfma_k<DH, NB>, lk);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((attn_bwd_q_mfma_k<DH, NB>), dim3((unsigned)(n * H)), dim3(256), lq, s,
+                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL((attn_bwd_k_mfma_k<DH, NB>), dim3((unsigned)(n * H)), dim3(256), lk, s,
+                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// built shapes: head width 64 with 193..224 tokens (ViT-*/16 at 224 px), head width 32 with <= 32 tokens
+bool attn_mfma_ok(int T, int dh) {
+  int nb = (T + 31) / 32;
+  return (dh == 64 && nb == 7) || (dh == 32 && nb == 1);
+}
+
+hipError_t launch_attn_fwd_mfma(const void* qkv, void* O, float* lse, long long n, int T, int H, int dh, hipStream_t s) {
+  if (dh == 64) return fwd_go<64, 7>(qkv, O, lse, n, T, H, s);
+  return fwd_go<32, 1>(qkv, O, lse, n, T, H, s);
+}
+
+hipError_t launch_attn_bwd_mfma(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
+                                long long n, int T, int H, int dh, hipStream_t s) {
+  if (dh == 64) return bwd_go<64, 7>(qkv, O, lse, dO, dqkv, n, T, H, s);
+  return bwd_go<32, 1>(qkv, O, lse, dO, dqkv, n, T, H, s);
+}
+
 }  // namespace sl

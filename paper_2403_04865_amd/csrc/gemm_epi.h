@@ -5,8 +5,8 @@
 namespace sl {
 
 template <typename T, typename RS>
-__device__ __forceinline__ void epi_store(const GemmNT& g, long long m, int n, float acc) {
-  switch (g.epi) {
+__device__ __forceinline__ void epi_store_mode(int mode, const GemmNT& g, long long m, int n, float acc) {
+  switch (mode) {
     case EPI_PLAIN:
       ((T*)g.out)[m * g.ldc + n] = from_f<T>(acc);
       break;
@@ -32,6 +32,11 @@ __device__ __forceinline__ void epi_store(const GemmNT& g, long long m, int n, f
       break;
     }
   }
+}
+
+template <typename T, typename RS>
+__device__ __forceinline__ void epi_store(const GemmNT& g, long long m, int n, float acc) {
+  epi_store_mode<T, RS>(g.epi, g, m, n, acc);
 }
 
 }  // namespace sl

@@ -23,6 +23,22 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ u32x4 ldg16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
 
+template <int MODE, typename RS>
+__device__ __forceinline__ void nt_epilogue(const GemmNT& g, const f32x16 (&acc)[2][2], long long mw, int nw, int lane) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      int n = nw + j * 32 + (lane & 31);
+      bool n_ok = n < g.N;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        long long m = mw + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (n_ok && m < g.M) epi_store_mode<bf16, RS>(MODE, g, m, n, acc[i][j][r]);
+      }
+    }
+}
+
 template <typename RS>
 __global__ void __launch_bounds__(256, 2) gemm_nt_mfma_k(GemmNT g, int MT, int NT) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -117,18 +133,14 @@ __global__ void __launch_bounds__(256, 2) gemm_nt_mfma_k(GemmNT g, int MT, int N
   }
 
   // accumulator element r of lane l: row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 block
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      int n = n0 + wn * 64 + j * 32 + (lane & 31);
-      if (n >= g.N) continue;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        long long m = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (m < g.M) epi_store<bf16, RS>(g, m, n, acc[i][j][r]);
-      }
-    }
+  switch (g.epi) {
+    case EPI_PLAIN: nt_epilogue<EPI_PLAIN, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
+    case EPI_BIAS: nt_epilogue<EPI_BIAS, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
+    case EPI_BIAS_RESID: nt_epilogue<EPI_BIAS_RESID, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
+    case EPI_BIAS_GELU: nt_epilogue<EPI_BIAS_GELU, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
+    case EPI_DGELU: nt_epilogue<EPI_DGELU, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
+    default: nt_epilogue<EPI_PATCH, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -241,11 +253,11 @@ __global__ void __launch_bounds__(256, 2) gemm_tn_mfma_k(GemmTN g) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       int c = j0 + wn * 64 + j * 32 + (lane & 31);
-      if (c >= g.N2) continue;
+      bool c_ok = c < g.N2;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         int row = i0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (row < g.N1) P[(size_t)row * g.N2 + c] = acc[i][j][r];
+        if (c_ok && row < g.N1) P[(size_t)row * g.N2 + c] = acc[i][j][r];
       }
     }
 }
