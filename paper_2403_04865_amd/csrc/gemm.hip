@@ -120,6 +120,10 @@ int gemm_tn_pick_slabs(long long M, int N1, int N2, int max_slabs) {
   return (int)s;
 }
 
+bool gemm_tn_fuses_colsum(int dt, const GemmTN& g, bool use_mfma) {
+  return dt == DT_BF16 && use_mfma && gemm_tn_mfma_ok(g);
+}
+
 hipError_t launch_gemm_nt(int dt, const GemmNT& g, bool use_mfma, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
   if (dt == DT_BF16 && use_mfma && gemm_nt_mfma_ok(g)) return launch_gemm_nt_mfma(g, s);

@@ -216,9 +216,25 @@ __global__ void __launch_bounds__(256, 2) gemm_tn_mfma_k(GemmTN g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // column sums of A (bias gradients) ride along in the workgroups of the first tile column
+  bool do_cs = g.cs_part != nullptr && blockIdx.y == 0 && !isB;
+  float cs[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) cs[c] = 0.f;
+  auto add_cs = [&](const u32x4 (&v)[8]) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        cs[2 * w] += __uint_as_float(v[r][w] << 16);
+        cs[2 * w + 1] += __uint_as_float(v[r][w] & 0xffff0000u);
+      }
+  };
+
   u32x4 v[8];
   if (lo < hi) {
     load(lo, v);
+    if (do_cs) add_cs(v);
     store(0, v);
   }
   __syncthreads();
@@ -244,8 +260,25 @@ __global__ void __launch_bounds__(256, 2) gemm_tn_mfma_k(GemmTN g) {
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-    if (more) store(cur ^ 1, v);
+    if (more) {
+      if (do_cs) add_cs(v);
+      store(cur ^ 1, v);
+    }
     __syncthreads();
+  }
+  if (g.cs_part != nullptr && blockIdx.y == 0) {  // uniform per workgroup
+    float* red = reinterpret_cast<float*>(smem);  // [8][128]; all LDS reads are behind the last barrier
+    if (!isB) {
+#pragma unroll
+      for (int c = 0; c < 8; ++c) red[mb * 128 + cb * 8 + c] = cs[c];
+    }
+    __syncthreads();
+    if (tid < 128 && i0 + tid < g.N1) {
+      float a = 0.f;
+#pragma unroll
+      for (int m = 0; m < 8; ++m) a += red[m * 128 + tid];
+      g.cs_part[(size_t)s * g.N1 + i0 + tid] = a;
+    }
   }
   float* P = g.part + (size_t)s * g.N1 * g.N2;
 #pragma unroll

@@ -40,10 +40,172 @@ __global__ void __launch_bounds__(256) ln_fwd_k(const RS* __restrict__ x, long l
   }
 }
 
+
+// ---- fast path: D == 128 * NP, each lane owns NP column pairs {2*(lane + 64*i), +1} -----------
+template <typename E> struct Pair;
+template <> struct Pair<float> { typedef float2 type; };
+template <> struct Pair<bf16> { typedef unsigned int type; };
+
+__device__ __forceinline__ float2 ld2(const float* p) { return *reinterpret_cast<const float2*>(p); }
+__device__ __forceinline__ float2 ld2(const bf16* p) {
+  unsigned int u = *reinterpret_cast<const unsigned int*>(p);
+  return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
+}
+__device__ __forceinline__ void st2(float* p, float a, float b) { *reinterpret_cast<float2*>(p) = make_float2(a, b); }
+__device__ __forceinline__ void st2(bf16* p, float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v = {(bf16)a, (bf16)b};
+  *reinterpret_cast<bf16x2*>(p) = v;
+}
+
+template <typename RS, typename T, int NP>
+__global__ void __launch_bounds__(256) ln_fwd_fast_k(const RS* __restrict__ x, long long xs,
+                                                     const float* __restrict__ gam, const float* __restrict__ bet,
+                                                     T* __restrict__ out, long long os, long long rows, float eps) {
+  constexpr int D = 128 * NP;
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  long long r = (long long)blockIdx.x * 4 + w;
+  if (r >= rows) return;
+  const RS* xr = x + r * xs;
+  float2 v[NP];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    v[i] = ld2(xr + 2 * (lane + 64 * i));
+    sum += v[i].x + v[i].y;
+  }
+  float mean = wave_sum(sum) * (1.0f / D);
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    v[i].x -= mean;
+    v[i].y -= mean;
+    sq += v[i].x * v[i].x + v[i].y * v[i].y;
+  }
+  float rstd = 1.0f / sqrtf(wave_sum(sq) * (1.0f / D) + eps);
+  T* o = out + r * os;
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    int c = 2 * (lane + 64 * i);
+    float2 g = ld2(gam + c), b = ld2(bet + c);
+    st2(o + c, v[i].x * rstd * g.x + b.x, v[i].y * rstd * g.y + b.y);
+  }
+}
+
+template <typename RS, typename TDY, typename T, bool SAME, int NP>
+__global__ void __launch_bounds__(256) ln_bwd_fast_k(const RS* __restrict__ x, long long xs,
+                                                     const TDY* __restrict__ dy, long long dys,
+                                                     const float* __restrict__ gam, const RS* __restrict__ dres,
+                                                     RS* __restrict__ dxo, T* __restrict__ dxo_t, long long os,
+                                                     long long rows, float eps, float* __restrict__ part) {
+  constexpr int D = 128 * NP;
+  __shared__ float red[4 * 2 * D];
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  float2 dg[NP], db[NP], g[NP];
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    dg[i] = make_float2(0.f, 0.f);
+    db[i] = make_float2(0.f, 0.f);
+    g[i] = ld2(gam + 2 * (lane + 64 * i));
+  }
+  for (long long r = (long long)blockIdx.x * 4 + w; r < rows; r += (long long)gridDim.x * 4) {
+    const RS* xr = x + r * xs;
+    const TDY* dyr = dy + r * dys;
+    float2 v[NP], d[NP], rs_[NP];
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      int c = 2 * (lane + 64 * i);
+      v[i] = ld2(xr + c);
+      d[i] = ld2(dyr + c);
+      if (dres) rs_[i] = ld2(dres + r * os + c);
+      sum += v[i].x + v[i].y;
+    }
+    float mean = wave_sum(sum) * (1.0f / D);
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      v[i].x -= mean;
+      v[i].y -= mean;
+      sq += v[i].x * v[i].x + v[i].y * v[i].y;
+    }
+    float rstd = 1.0f / sqrtf(wave_sum(sq) * (1.0f / D) + eps);
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      v[i].x *= rstd;
+      v[i].y *= rstd;
+      dg[i].x += d[i].x * v[i].x;
+      dg[i].y += d[i].y * v[i].y;
+      db[i].x += d[i].x;
+      db[i].y += d[i].y;
+      d[i].x *= g[i].x;
+      d[i].y *= g[i].y;
+      s1 += d[i].x + d[i].y;
+      s2 += d[i].x * v[i].x + d[i].y * v[i].y;
+    }
+    s1 = wave_sum(s1) * (1.0f / D);
+    s2 = wave_sum(s2) * (1.0f / D);
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      int c = 2 * (lane + 64 * i);
+      float a = rstd * (d[i].x - s1 - v[i].x * s2);
+      float b = rstd * (d[i].y - s1 - v[i].y * s2);
+      if (dres) { a += rs_[i].x; b += rs_[i].y; }
+      st2(dxo + r * os + c, a, b);
+      if (!SAME) st2(dxo_t + r * os + c, a, b);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    int c = 2 * (lane + 64 * i);
+    red[(w * 2 + 0) * D + c] = dg[i].x;
+    red[(w * 2 + 0) * D + c + 1] = dg[i].y;
+    red[(w * 2 + 1) * D + c] = db[i].x;
+    red[(w * 2 + 1) * D + c + 1] = db[i].y;
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 2 * D; i += 256) {
+    float a = (red[0 * 2 * D + i] + red[1 * 2 * D + i]) + (red[2 * 2 * D + i] + red[3 * 2 * D + i]);
+    part[(size_t)blockIdx.x * 2 * D + i] = a;
+  }
+}
+
+template <typename RS, typename T>
+bool ln_fwd_fast(const void* x, long long xs, const float* gam, const float* bet, void* out, long long os,
+                 long long rows, int D, float eps, hipStream_t s) {
+  if ((xs & 1) || (os & 1)) return false;
+  dim3 grid((unsigned)((rows + 3) / 4));
+#define GO(NP) hipLaunchKernelGGL((ln_fwd_fast_k<RS, T, NP>), grid, dim3(256), 0, s, (const RS*)x, xs, gam, bet, (T*)out, os, rows, eps)
+  if (D == 384) { GO(3); return true; }
+  if (D == 768) { GO(6); return true; }
+  if (D == 128) { GO(1); return true; }
+#undef GO
+  return false;
+}
+
+template <typename RS, typename TDY, typename T, bool SAME>
+bool ln_bwd_fast(dim3 grid, const void* x, long long xs, const void* dy, long long dys, const float* gam,
+                 const void* dres, void* dxo, void* dxo_t, long long os, long long rows, int D, float eps, float* part,
+                 hipStream_t s) {
+  if ((xs & 1) || (os & 1) || (dys & 1)) return false;
+#define GO(NP) hipLaunchKernelGGL((ln_bwd_fast_k<RS, TDY, T, SAME, NP>), grid, dim3(256), 0, s, (const RS*)x, xs, (const TDY*)dy, dys, gam, (const RS*)dres, (RS*)dxo, (T*)dxo_t, os, rows, eps, part)
+  if (D == 384) { GO(3); return true; }
+  if (D == 768) { GO(6); return true; }
+  if (D == 128) { GO(1); return true; }
+#undef GO
+  return false;
+}
+
 hipError_t launch_ln_fwd(int dt, const void* x, long long x_stride, const float* gam, const float* bet, void* out,
                          long long out_stride, long long rows, int D, float eps, bool out_f32, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   dim3 grid((unsigned)((rows + 3) / 4));
+  bool fast;
+  if (dt != DT_F32 && out_f32) fast = ln_fwd_fast<rs_bf16path_t, float>(x, x_stride, gam, bet, out, out_stride, rows, D, eps, s);
+  else if (dt == DT_F32) fast = ln_fwd_fast<float, float>(x, x_stride, gam, bet, out, out_stride, rows, D, eps, s);
+  else fast = ln_fwd_fast<rs_bf16path_t, bf16>(x, x_stride, gam, bet, out, out_stride, rows, D, eps, s);
+  if (fast) return hipGetLastError();
   if (dt != DT_F32 && out_f32)
     hipLaunchKernelGGL((ln_fwd_k<rs_bf16path_t, float>), grid, dim3(256), 0, s, (const rs_bf16path_t*)x, x_stride, gam,
                        bet, (float*)out, out_stride, rows, D, eps);
@@ -135,7 +297,7 @@ __global__ void __launch_bounds__(256) ln_bwd_k(const RS* __restrict__ x, long l
 
 int ln_bwd_slabs(long long rows) {
   long long s = (rows + 3) / 4;
-  if (s > 1024) s = 1024;
+  if (s > 512) s = 512;
   if (s < 1) s = 1;
   return (int)s;
 }
@@ -146,6 +308,20 @@ hipError_t launch_ln_bwd(int dt, const void* x, long long x_stride, const void* 
   if (rows <= 0) return hipSuccess;
   dim3 grid(ln_bwd_slabs(rows));
   size_t lds = (size_t)4 * 2 * D * sizeof(float);
+  {
+    constexpr bool same = sizeof(rs_bf16path_t) == sizeof(bf16);
+    bool fast;
+    if (dt == DT_F32)
+      fast = ln_bwd_fast<float, float, float, true>(grid, x, x_stride, dy, dy_stride, gam, dres, dx_out, nullptr,
+                                                    o_stride, rows, D, eps, part, s);
+    else if (dy_f32)
+      fast = ln_bwd_fast<rs_bf16path_t, float, bf16, same>(grid, x, x_stride, dy, dy_stride, gam, dres, dx_out,
+                                                           dx_out_t, o_stride, rows, D, eps, part, s);
+    else
+      fast = ln_bwd_fast<rs_bf16path_t, bf16, bf16, same>(grid, x, x_stride, dy, dy_stride, gam, dres, dx_out,
+                                                          dx_out_t, o_stride, rows, D, eps, part, s);
+    if (fast) return hipGetLastError();
+  }
   if (dt == DT_F32) {
     hipLaunchKernelGGL((ln_bwd_k<float, float, float, true>), grid, dim3(256), lds, s, (const float*)x, x_stride,
                        (const float*)dy, dy_stride, gam, (const float*)dres, (float*)dx_out, (float*)nullptr, o_stride,

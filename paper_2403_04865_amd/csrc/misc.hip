@@ -167,19 +167,28 @@ int colsum_slabs(long long M) {
   return (int)s;
 }
 
+// 64 outputs per workgroup; the slabs are dealt to 4 quarter-groups whose sums are then added
+// in a fixed order, so the result does not depend on scheduling.
 __global__ void __launch_bounds__(256) reduce_partials_k(const float* __restrict__ part, int slabs, long long stride,
                                                          long long len, float* __restrict__ out, int accumulate) {
-  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= len) return;
+  __shared__ float red[4][64];
+  int cl = threadIdx.x & 63, q = threadIdx.x >> 6;
+  long long i = (long long)blockIdx.x * 64 + cl;
   float acc = 0.f;
-  for (int s = 0; s < slabs; ++s) acc += part[(size_t)s * stride + i];
-  out[i] = accumulate ? out[i] + acc : acc;
+  if (i < len)
+    for (int s = q; s < slabs; s += 4) acc += part[(size_t)s * stride + i];
+  red[q][cl] = acc;
+  __syncthreads();
+  if (q == 0 && i < len) {
+    float v = (red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl]);
+    out[i] = accumulate ? out[i] + v : v;
+  }
 }
 
 hipError_t launch_reduce_partials(const float* part, int slabs, long long stride, long long len, float* out,
                                   int accumulate, hipStream_t s) {
   if (len <= 0) return hipSuccess;
-  hipLaunchKernelGGL(reduce_partials_k, dim3((unsigned)((len + 255) / 256)), dim3(256), 0, s, part, slabs, stride, len,
+  hipLaunchKernelGGL(reduce_partials_k, dim3((unsigned)((len + 63) / 64)), dim3(256), 0, s, part, slabs, stride, len,
                      out, accumulate);
   return hipGetLastError();
 }

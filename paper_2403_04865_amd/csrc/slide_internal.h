@@ -95,12 +95,14 @@ struct GemmTN {
   const void* B; long long ldb; RowMap bmap;  // T [M, N2]
   long long M; int N1, N2;
   float* part; int slabs;
+  float* cs_part;  // optional: column sums of A per slab, [slabs][N1] (only the MFMA kernel fills it)
 };
 
 // All launchers enqueue on `s` and return the launch status.
 hipError_t launch_gemm_nt(int dt, const GemmNT& g, bool use_mfma, hipStream_t s);
 hipError_t launch_gemm_tn(int dt, const GemmTN& g, bool use_mfma, hipStream_t s);
 int gemm_tn_pick_slabs(long long M, int N1, int N2, int max_slabs);
+bool gemm_tn_fuses_colsum(int dt, const GemmTN& g, bool use_mfma);  // will launch_gemm_tn fill cs_part?
 
 hipError_t launch_cast_transpose(int dt, const float* src, int R, int C, void* dstW, void* dstWT, hipStream_t s);
 hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long n, int S, int P, hipStream_t s);

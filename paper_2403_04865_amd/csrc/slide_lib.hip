@@ -216,20 +216,31 @@ void gemm_nt(Run& r, const GemmNT& g) {
   launch(r, K_GEMM_NT, 2.0 * g.M * g.N * g.K, bytes, [&] { return launch_gemm_nt(r.c->dt, g, r.c->use_mfma, r.s); });
 }
 
-// dW (+)= A^T B through split partials
+void colsum(Run& r, int elem, const void* A, long long lda, RowMap map, long long M, int N, float* part, float* out,
+            int accumulate);
+
+// dW (+)= A^T B through split partials; optionally also db (+)= column sums of A
 void gemm_tn(Run& r, const void* A, long long lda, RowMap amap, const void* B, long long ldb, RowMap bmap, long long M,
-             int N1, int N2, float* part, float* out, int accumulate, int dt_override = -1) {
+             int N1, int N2, float* part, float* out, int accumulate, int dt_override = -1, float* bias_out = nullptr,
+             float* cpart = nullptr) {
   GemmTN g;
   int dt = dt_override >= 0 ? dt_override : r.c->dt;
   g.A = A; g.lda = lda; g.amap = amap; g.B = B; g.ldb = ldb; g.bmap = bmap; g.M = M; g.N1 = N1; g.N2 = N2;
   g.part = part;
   g.slabs = gemm_tn_pick_slabs(M, N1, N2, 32);
+  g.cs_part = nullptr;
+  bool fused = bias_out && gemm_tn_fuses_colsum(dt, g, r.c->use_mfma);
+  if (fused) g.cs_part = cpart;
+  if (bias_out && !fused) colsum(r, dt, A, lda, amap, M, N1, cpart, bias_out, accumulate);
   size_t e = elem_size(dt);
   launch(r, K_GEMM_TN, 2.0 * M * N1 * N2, (double)M * (N1 + N2) * e + (double)g.slabs * N1 * N2 * 4,
          [&] { return launch_gemm_tn(dt, g, r.c->use_mfma, r.s); });
   launch(r, K_ELEMWISE, 0, (double)(g.slabs + 1) * N1 * N2 * 4, [&] {
     return launch_reduce_partials(part, g.slabs, (long long)N1 * N2, (long long)N1 * N2, out, accumulate, r.s);
   });
+  if (fused)
+    launch(r, K_ELEMWISE, 0, 0,
+           [&] { return launch_reduce_partials(cpart, g.slabs, N1, N1, bias_out, accumulate, r.s); });
 }
 
 void colsum(Run& r, int elem, const void* A, long long lda, RowMap map, long long M, int N, float* part, float* out,
@@ -382,18 +393,16 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
     char* m = ar + y.e_m + (size_t)l * y.s_m;
     int wi = 1 + 4 * l;
     // ---- MLP half: x_out = x_mid + gelu(LN2(x_mid) W1^T + b1) W2^T + b2
-    colsum(r, dt, dxAt, D, id, M, D, cpart, G + o.fc2b, accumulate);
     launch(r, K_ELEMWISE, 0, 2.0 * M * F * e, [&] { return launch_gelu(dt, m, a, M * F, s); });
-    gemm_tn(r, dxAt, D, id, a, F, id, M, D, F, wpart, G + o.fc2W, accumulate);
+    gemm_tn(r, dxAt, D, id, a, F, id, M, D, F, wpart, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
     {
       GemmNT g{};
       g.A = dxAt; g.lda = D; g.B = weight_t(c, wi + 3); g.ldb = D; g.M = M; g.N = F; g.K = D;
       g.epi = EPI_DGELU; g.pre = m; g.ldpre = F; g.out = a; g.ldc = F;  // dm overwrites the GELU output
       gemm_nt(r, g);
     }
-    colsum(r, dt, a, F, id, M, F, cpart, G + o.fc1b, accumulate);
     ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u, D, M);
-    gemm_tn(r, a, F, id, u, D, id, M, F, D, wpart, G + o.fc1W, accumulate);
+    gemm_tn(r, a, F, id, u, D, id, M, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
     {
       GemmNT g{};
       g.A = a; g.lda = F; g.B = weight_t(c, wi + 2); g.ldb = F; g.M = M; g.N = D; g.K = F;
@@ -402,8 +411,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
     }
     ln_bwd(r, xmid, D, du, D, o.ln2g, o.ln2b, dxA, dxB, dxBt, D, M, lnpart, accumulate);
     // ---- attention half: x_mid = x_in + attn(LN1(x_in)) Wo^T + bo
-    colsum(r, dt, dxBt, D, id, M, D, cpart, G + o.projb, accumulate);
-    gemm_tn(r, dxBt, D, id, O, D, id, M, D, D, wpart, G + o.projW, accumulate);
+    gemm_tn(r, dxBt, D, id, O, D, id, M, D, D, wpart, G + o.projW, accumulate, -1, G + o.projb, cpart);
     {
       GemmNT g{};
       g.A = dxBt; g.lda = D; g.B = weight_t(c, wi + 1); g.ldb = D; g.M = M; g.N = D; g.K = D;
@@ -412,9 +420,8 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
     }
     launch(r, K_ATTN_BWD, 10.0 * n * c->H * (double)T * T * c->dh, (double)M * 9 * D * e,
            [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s); });
-    colsum(r, dt, dqkv, 3 * D, id, M, 3 * D, cpart, G + o.qkvb, accumulate);
     ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
-    gemm_tn(r, dqkv, 3 * D, id, u, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate);
+    gemm_tn(r, dqkv, 3 * D, id, u, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
     {
       GemmNT g{};
       g.A = dqkv; g.lda = 3 * D; g.B = weight_t(c, wi + 0); g.ldb = 3 * D; g.M = M; g.N = D; g.K = 3 * D;
@@ -436,8 +443,8 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
   }
   RowMap pm{c->g2, T};
   long long Mp = n * c->g2;
-  colsum(r, dt, dxAt, D, pm, Mp, D, cpart, G + c->o_peb, accumulate);
-  gemm_tn(r, dxAt, D, pm, ar + y.e_patches, c->Kp, id, Mp, D, c->Kp, wpart, G + c->o_peW, accumulate);
+  gemm_tn(r, dxAt, D, pm, ar + y.e_patches, c->Kp, id, Mp, D, c->Kp, wpart, G + c->o_peW, accumulate, -1,
+          G + c->o_peb, cpart);
   if (pixel_grad) {
     GemmNT g{};
     g.A = dxAt; g.lda = D; g.amap = pm; g.B = weight_t(c, 0); g.ldb = D; g.M = Mp; g.N = c->Kp; g.K = D;
