@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libslide.so")
-SOURCES = ["slide_lib.hip", "misc.hip", "ln.hip", "gemm.hip", "gemm_mfma.hip", "attn.hip", "attn_mfma.hip", "pool.hip"]
+SOURCES = ["slide_lib.hip", "misc.hip", "ln.hip", "gemm.hip", "gemm_mfma.hip", "gemm_nt_mfma.hip", "attn.hip", "attn_mfma.hip", "pool.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -47,7 +47,7 @@ def build(force: bool = False, verbose: bool = True, extra_flags=()):
 
     def compile_one(job):
         s, o = job
-        cmd = [hipcc, *FLAGS, *extra_flags, "-c", s, "-o", o]
+        cmd = [hipcc, *FLAGS, *extra_flags, *os.environ.get("SLIDE_HIPCC_FLAGS", "").split(), "-c", s, "-o", o]
         p = subprocess.run(cmd, capture_output=True, text=True)
         # the host pass does not know the gfx-only feature flag and says so: not an error
         err = "\n".join(l for l in p.stderr.splitlines() if "packed-fp32-ops" not in l)

@@ -22,9 +22,13 @@ __device__ __forceinline__ void epi_store_mode(int mode, const GemmNT& g, long l
       ((T*)g.out2)[m * g.ldc2 + n] = from_f<T>(gelu_f(to_f(pre)));  // GELU of the stored (rounded) value
       break;
     }
-    case EPI_DGELU:
-      ((T*)g.out)[m * g.ldc + n] = from_f<T>(acc * gelu_grad_f(to_f(((const T*)g.pre)[m * g.ldpre + n])));
+    case EPI_DGELU: {
+      float gl, dg;
+      gelu_both(to_f(((const T*)g.pre)[m * g.ldpre + n]), &gl, &dg);
+      ((T*)g.out)[m * g.ldc + n] = from_f<T>(acc * dg);
+      if (g.out2) ((T*)g.out2)[m * g.ldc2 + n] = from_f<T>(gl);
       break;
+    }
     case EPI_PATCH: {
       long long mm = g.cmap(m);
       int tok = 1 + (int)(m % g.cmap.g2);

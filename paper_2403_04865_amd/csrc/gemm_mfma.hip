@@ -1,147 +1,18 @@
-// bf16 MFMA GEMMs for gfx950 (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
+// bf16 MFMA weight-gradient GEMM for gfx950 (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
 //
-// NT: C[M,N] = A[M,K] * B[N,K]^T, both operands K-contiguous.  128x128 output tile per
-//     workgroup of 4 wavefronts (2x2, 64x64 each = 2x2 MFMA blocks), K step 64, LDS double
-//     buffered, global loads for step k+1 issued before the MFMAs of step k.
 // TN: C[N1,N2] = A[M,N1]^T * B[M,N2], contraction over the slow (row) index.  Each thread
 //     transposes 8x8 bf16 blocks in registers on the way into LDS, so the LDS image is
 //     [column][row-chunk] and MFMA operands are again 16-byte contiguous reads.
-//
-// Workgroup ids are mapped so that the output tiles that share an A row panel run on the
-// same XCD (ids are dealt round-robin to the 8 XCDs, each with its own L2).
 #include "gemm_epi.h"
 
 namespace sl {
 
 namespace {
 
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int LDT = BK + 8;  // padded LDS row (elements): 144 B stride -> conflict-free 16 B reads
-constexpr int NXCD = 8;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ u32x4 ldg16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
-
-template <int MODE, typename RS>
-__device__ __forceinline__ void nt_epilogue(const GemmNT& g, const f32x16 (&acc)[2][2], long long mw, int nw, int lane) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      int n = nw + j * 32 + (lane & 31);
-      bool n_ok = n < g.N;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        long long m = mw + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (n_ok && m < g.M) epi_store_mode<bf16, RS>(MODE, g, m, n, acc[i][j][r]);
-      }
-    }
-}
-
-template <typename RS>
-__global__ void __launch_bounds__(256, 2) gemm_nt_mfma_k(GemmNT g, int MT, int NT) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16* As = reinterpret_cast<bf16*>(smem);       // [2][BM][LDT]
-  bf16* Bs = As + 2 * BM * LDT;                   // [2][BN][LDT]
-  // XCD-aware tile id
-  int id = blockIdx.x;
-  int xcd = id % NXCD, slot = id / NXCD;
-  int mt = (slot / NT) * NXCD + xcd, nt = slot % NT;
-  if (mt >= MT) return;
-  long long m0 = (long long)mt * BM;
-  int n0 = nt * BN;
-  const bf16* A = (const bf16*)g.A;
-  const bf16* B = (const bf16*)g.B;
-  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  int wm = wave >> 1, wn = wave & 1;
-
-  // loader: 4 x 16-byte chunks of A and of B per thread per K step
-  const bf16* ap[4];
-  const bf16* bp[4];
-  int soff[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int c = tid + 256 * i;
-    int row = c >> 3, kc = c & 7;
-    long long am = m0 + row;
-    if (am > g.M - 1) am = g.M - 1;  // clamp: rows past the end are loaded but never stored
-    int bn = n0 + row;
-    if (bn > g.N - 1) bn = g.N - 1;
-    ap[i] = A + g.amap(am) * g.lda + kc * 8;
-    bp[i] = B + (long long)bn * g.ldb + kc * 8;
-    soff[i] = row * LDT + kc * 8;
-  }
-  u32x4 ra[4], rb[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    ra[i] = ldg16(ap[i]);
-    rb[i] = ldg16(bp[i]);
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    *reinterpret_cast<u32x4*>(As + soff[i]) = ra[i];
-    *reinterpret_cast<u32x4*>(Bs + soff[i]) = rb[i];
-  }
-  __syncthreads();
-
-  f32x16 acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  int nk = g.K / BK;
-  int frow = lane & 31, fk = (lane >> 5) * 8;
-  for (int kt = 0; kt < nk; ++kt) {
-    int cur = kt & 1;
-    bool more = kt + 1 < nk;
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        ra[i] = ldg16(ap[i] + (kt + 1) * BK);
-        rb[i] = ldg16(bp[i] + (kt + 1) * BK);
-      }
-    }
-    const bf16* as = As + cur * BM * LDT + (wm * 64 + frow) * LDT + fk;
-    const bf16* bs = Bs + cur * BN * LDT + (wn * 64 + frow) * LDT + fk;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[2], fb[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        fa[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDT + ks * 16);
-        fb[i] = *reinterpret_cast<const bf16x8*>(bs + i * 32 * LDT + ks * 16);
-      }
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (more) {
-      int nxt = cur ^ 1;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<u32x4*>(As + nxt * BM * LDT + soff[i]) = ra[i];
-        *reinterpret_cast<u32x4*>(Bs + nxt * BN * LDT + soff[i]) = rb[i];
-      }
-    }
-    __syncthreads();
-  }
-
-  // accumulator element r of lane l: row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 block
-  switch (g.epi) {
-    case EPI_PLAIN: nt_epilogue<EPI_PLAIN, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
-    case EPI_BIAS: nt_epilogue<EPI_BIAS, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
-    case EPI_BIAS_RESID: nt_epilogue<EPI_BIAS_RESID, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
-    case EPI_BIAS_GELU: nt_epilogue<EPI_BIAS_GELU, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
-    case EPI_DGELU: nt_epilogue<EPI_DGELU, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
-    default: nt_epilogue<EPI_PATCH, RS>(g, acc, m0 + wm * 64, n0 + wn * 64, lane); break;
-  }
-}
 
 // ---------------------------------------------------------------------------------------
 // TN: part[s][i][j] = sum_{m in slab s} A[amap(m)][i] * B[bmap(m)][j]
@@ -299,27 +170,8 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 }  // namespace
 
-bool gemm_nt_mfma_ok(const GemmNT& g) {
-  return g.K % BK == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && aligned16(g.A) && aligned16(g.B) && g.M > 0 && g.N > 0;
-}
-
 bool gemm_tn_mfma_ok(const GemmTN& g) {
   return g.N1 % 8 == 0 && g.N2 % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && aligned16(g.A) && aligned16(g.B);
-}
-
-hipError_t launch_gemm_nt_mfma(const GemmNT& g, hipStream_t s) {
-  static bool attr_done = false;
-  size_t lds = (size_t)2 * (BM + BN) * LDT * sizeof(bf16);
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_nt_mfma_k<rs_bf16path_t>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  int MT = (int)((g.M + BM - 1) / BM), NT = (g.N + BN - 1) / BN;
-  long long wgs = (long long)((MT + NXCD - 1) / NXCD) * NXCD * NT;
-  hipLaunchKernelGGL(gemm_nt_mfma_k<rs_bf16path_t>, dim3((unsigned)wgs), dim3(256), lds, s, g, MT, NT);
-  return hipGetLastError();
 }
 
 hipError_t launch_gemm_tn_mfma(const GemmTN& g, hipStream_t s) {

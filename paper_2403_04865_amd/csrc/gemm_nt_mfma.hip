@@ -1,0 +1,300 @@
+// bf16 MFMA "NT" GEMM for gfx950: C[M,N] = A[M,K] * B[N,K]^T (+ fused epilogue), fp32 accumulate.
+//
+// Every activation-side GEMM of the encoder is this kernel (forward GEMMs use W [out][in];
+// input-gradient GEMMs use the pre-transposed copy W^T, so both operands are always
+// K-contiguous).  K is short here (384..1536), so the output tile is made large instead: one
+// workgroup of WVM x WVN wavefronts owns a (WVM*WBM*32) x (WVN*WBN*32) tile, each wavefront a
+// WBM x WBN grid of 32x32 MFMA accumulators.  A large tile is what keeps the bytes moved
+// global->LDS per MFMA clock under what one CU's vector memory path delivers.
+//   * LDS: two stages of [BM + BN][BK + 8] bf16 (144-byte rows: conflict-free 16-byte reads);
+//     global loads of K step k+1 are issued before the MFMAs of step k and parked in registers.
+//   * Epilogue: each wave passes its accumulators through a private LDS patch and gets them back
+//     as 8-column row segments, so bias / residual / GELU / position terms are applied with
+//     16-byte loads and stores and every output row of the strip is one contiguous run
+//     (partial-line stores straight from the MFMA register layout measured 25 % slower).
+//   * Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the id -> tile map puts
+//     the tiles that share an A row panel on the same XCD (same L2).
+#include "gemm_epi.h"
+
+namespace sl {
+
+namespace {
+
+constexpr int NXCD = 8;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32x4 ldg16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+// ---- 8-wide row segment helpers ----------------------------------------------------------------
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    float4 t = reinterpret_cast<const float4*>(p)[i];
+    v[4 * i] = t.x; v[4 * i + 1] = t.y; v[4 * i + 2] = t.z; v[4 * i + 3] = t.w;
+  }
+}
+__device__ __forceinline__ void load8(const bf16* p, float (&v)[8]) {
+  u32x4 t = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    v[2 * w] = __uint_as_float(t[w] << 16);
+    v[2 * w + 1] = __uint_as_float(t[w] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) reinterpret_cast<float4*>(p)[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+}
+__device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
+  bf16x8 t;
+#pragma unroll
+  for (int w = 0; w < 8; ++w) t[w] = (bf16)v[w];
+  *reinterpret_cast<bf16x8*>(p) = t;
+}
+
+// one row segment: columns n..n+7 of row m
+template <int MODE, typename RS>
+__device__ __forceinline__ void epi_seg8(const GemmNT& g, long long m, int n, float (&v)[8]) {
+  float t[8];
+  if (MODE != EPI_PLAIN && MODE != EPI_DGELU) {
+    load8(g.bias + n, t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] += t[i];
+  }
+  if (MODE == EPI_PLAIN || MODE == EPI_BIAS) {
+    store8((bf16*)g.out + m * g.ldc + n, v);
+  } else if (MODE == EPI_BIAS_RESID) {
+    load8((const RS*)g.resid + m * g.ldr + n, t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] += t[i];
+    store8((RS*)g.out + m * g.ldc + n, v);
+  } else if (MODE == EPI_BIAS_GELU) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      v[i] = (float)(bf16)v[i];  // GELU of the stored (rounded) pre-activation
+      t[i] = gelu_f(v[i]);
+    }
+    store8((bf16*)g.out + m * g.ldc + n, v);
+    store8((bf16*)g.out2 + m * g.ldc2 + n, t);
+  } else if (MODE == EPI_DGELU) {
+    load8((const bf16*)g.pre + m * g.ldpre + n, t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float gl, dg;
+      gelu_both(t[i], &gl, &dg);
+      v[i] *= dg;
+      t[i] = gl;
+    }
+    store8((bf16*)g.out + m * g.ldc + n, v);
+    if (g.out2) store8((bf16*)g.out2 + m * g.ldc2 + n, t);
+  } else {  // EPI_PATCH
+    int tok = 1 + (int)(m % g.cmap.g2);
+    load8(g.pos + (size_t)tok * g.N + n, t);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] += t[i];
+    store8((RS*)g.out + g.cmap(m) * g.ldc + n, v);
+  }
+}
+
+template <int WBM, int WBN, int WVM, int WVN, int BK>
+struct Cfg {
+  static constexpr int BM = WVM * WBM * 32, BN = WVN * WBN * 32;
+  static constexpr int NT = 64 * WVM * WVN;
+  static constexpr int LDT = BK + 8;
+  static constexpr int CPR = BK / 8;                 // 16-byte chunks per tile row
+  static constexpr int CA = BM * CPR / NT, CB = BN * CPR / NT;
+  static constexpr int RSTEP = NT / CPR;             // rows between successive chunks of one thread
+  static constexpr size_t LDS = (size_t)2 * (BM + BN) * LDT * sizeof(bf16);
+  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "loader split");
+  static_assert(WBN == 2 || WBN == 4, "epilogue row split");
+  static_assert(LDS >= (size_t)WVM * WVN * 32 * (WBN * 32 + 4) * 4, "epilogue patches fit");
+};
+
+// Epilogue: the wave's 32 x (WBN*32) strip of accumulators goes through a wave-private LDS patch
+// (row stride padded to WBN*32 + 4 floats) and comes back as 8-column row segments, 4*WBN
+// neighbouring lanes covering one full output row of the strip: every global load and store of
+// the epilogue is a 16-byte access and each row is written as one contiguous run.
+// Accumulator element r of lane l sits at row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its block.
+template <int MODE, typename RS, int WBM, int WBN>
+__device__ __forceinline__ void nt_epilogue(const GemmNT& g, f32x16 (&acc)[WBM][WBN], long long mw, int nw, int lane,
+                                            float* patch) {
+  constexpr int PS = WBN * 32 + 4;      // patch row stride (floats)
+  constexpr int SEG = WBN * 4;          // 8-column segments per row
+  constexpr int RPP = 64 / SEG;         // rows per pass
+  int li = lane & 31, h2 = lane >> 5;
+  int prow = lane / SEG, pseg = lane % SEG;
+#pragma unroll
+  for (int i = 0; i < WBM; ++i) {
+#pragma unroll
+    for (int j = 0; j < WBN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) patch[((r >> 2) * 8 + h2 * 4 + (r & 3)) * PS + j * 32 + li] = acc[i][j][r];
+#pragma unroll
+    for (int ps = 0; ps < 32 / RPP; ++ps) {
+      int row = ps * RPP + prow;
+      float v[8];
+      const float4* src = reinterpret_cast<const float4*>(patch + row * PS + pseg * 8);
+      float4 a = src[0], b = src[1];
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+      long long m = mw + i * 32 + row;
+      int n = nw + pseg * 8;
+      if (m < g.M && n < g.N) epi_seg8<MODE, RS>(g, m, n, v);
+    }
+  }
+}
+
+template <typename RS, int WBM, int WBN, int WVM, int WVN, int BK>
+__global__ void __launch_bounds__(64 * WVM * WVN) gemm_nt_tile_k(GemmNT g, int MT, int NTL) {
+  using C = Cfg<WBM, WBN, WVM, WVN, BK>;
+  constexpr int BM = C::BM, BN = C::BN, LDT = C::LDT, CA = C::CA, CB = C::CB;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* As = reinterpret_cast<bf16*>(smem);  // [2][BM][LDT]
+  bf16* Bs = As + 2 * BM * LDT;              // [2][BN][LDT]
+  int id = blockIdx.x;
+  int xcd = id % NXCD, slot = id / NXCD;
+  int mt = (slot / NTL) * NXCD + xcd, nt = slot % NTL;
+  if (mt >= MT) return;
+  long long m0 = (long long)mt * BM;
+  int n0 = nt * BN;
+  const bf16* A = (const bf16*)g.A;
+  const bf16* B = (const bf16*)g.B;
+  int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int wm = wave / WVN, wn = wave % WVN;
+
+  int row0 = tid / C::CPR, kc = tid % C::CPR;
+  long long aoff[CA], boff[CB];
+#pragma unroll
+  for (int i = 0; i < CA; ++i) {
+    long long am = m0 + row0 + i * C::RSTEP;
+    if (am > g.M - 1) am = g.M - 1;  // rows past the end are loaded (valid memory) but never stored
+    aoff[i] = g.amap(am) * g.lda + kc * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < CB; ++i) {
+    int bn = n0 + row0 + i * C::RSTEP;
+    if (bn > g.N - 1) bn = g.N - 1;
+    boff[i] = (long long)bn * g.ldb + kc * 8;
+  }
+  int soff = row0 * LDT + kc * 8;
+  u32x4 ra[CA], rb[CB];
+#pragma unroll
+  for (int i = 0; i < CA; ++i) ra[i] = ldg16(A + aoff[i]);
+#pragma unroll
+  for (int i = 0; i < CB; ++i) rb[i] = ldg16(B + boff[i]);
+#pragma unroll
+  for (int i = 0; i < CA; ++i) *reinterpret_cast<u32x4*>(As + soff + i * C::RSTEP * LDT) = ra[i];
+#pragma unroll
+  for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(Bs + soff + i * C::RSTEP * LDT) = rb[i];
+  __syncthreads();
+
+  f32x16 acc[WBM][WBN];
+#pragma unroll
+  for (int i = 0; i < WBM; ++i)
+#pragma unroll
+    for (int j = 0; j < WBN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  int nk = g.K / BK;
+  int frow = lane & 31, fk = (lane >> 5) * 8;
+  for (int kt = 0; kt < nk; ++kt) {
+    int cur = kt & 1;
+    bool more = kt + 1 < nk;
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < CA; ++i) ra[i] = ldg16(A + aoff[i] + (kt + 1) * BK);
+#pragma unroll
+      for (int i = 0; i < CB; ++i) rb[i] = ldg16(B + boff[i] + (kt + 1) * BK);
+    }
+    const bf16* as = As + cur * BM * LDT + (wm * WBM * 32 + frow) * LDT + fk;
+    const bf16* bs = Bs + cur * BN * LDT + (wn * WBN * 32 + frow) * LDT + fk;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[WBM], fb[WBN];
+#pragma unroll
+      for (int i = 0; i < WBM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDT + ks * 16);
+#pragma unroll
+      for (int j = 0; j < WBN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDT + ks * 16);
+#pragma unroll
+      for (int i = 0; i < WBM; ++i)
+#pragma unroll
+        for (int j = 0; j < WBN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (more) {
+      int nxt = cur ^ 1;
+#pragma unroll
+      for (int i = 0; i < CA; ++i) *reinterpret_cast<u32x4*>(As + nxt * BM * LDT + soff + i * C::RSTEP * LDT) = ra[i];
+#pragma unroll
+      for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(Bs + nxt * BN * LDT + soff + i * C::RSTEP * LDT) = rb[i];
+    }
+    __syncthreads();
+  }
+
+  // operand tiles are dead past the last barrier: the patches reuse their LDS
+  float* patch = reinterpret_cast<float*>(smem) + wave * 32 * (WBN * 32 + 4);
+  long long mw = m0 + wm * WBM * 32;
+  int nw = n0 + wn * WBN * 32;
+  switch (g.epi) {
+    case EPI_PLAIN: nt_epilogue<EPI_PLAIN, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+    case EPI_BIAS: nt_epilogue<EPI_BIAS, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+    case EPI_BIAS_RESID: nt_epilogue<EPI_BIAS_RESID, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+    case EPI_BIAS_GELU: nt_epilogue<EPI_BIAS_GELU, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+    case EPI_DGELU: nt_epilogue<EPI_DGELU, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+    default: nt_epilogue<EPI_PATCH, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+  }
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+template <int WBM, int WBN, int WVM, int WVN, int BK>
+hipError_t go(const GemmNT& g, hipStream_t s) {
+  using C = Cfg<WBM, WBN, WVM, WVN, BK>;
+  static bool attr_done = false;
+  auto kern = gemm_nt_tile_k<rs_bf16path_t, WBM, WBN, WVM, WVN, BK>;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  int MT = (int)((g.M + C::BM - 1) / C::BM), NTL = (g.N + C::BN - 1) / C::BN;
+  long long wgs = (long long)((MT + NXCD - 1) / NXCD) * NXCD * NTL;
+  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(C::NT), C::LDS, s, g, MT, NTL);
+  return hipGetLastError();
+}
+
+int g_variant = -1;
+
+}  // namespace
+
+bool gemm_nt_mfma_ok(const GemmNT& g) {
+  bool ok = g.K % 64 == 0 && g.N % 16 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && aligned16(g.A) && aligned16(g.B) &&
+            g.M > 0 && g.ldc % 8 == 0 && aligned16(g.out) && g.N % 8 == 0;
+  if (g.epi == EPI_BIAS_RESID) ok = ok && g.ldr % 8 == 0 && aligned16(g.resid);
+  if (g.epi == EPI_BIAS_GELU || (g.epi == EPI_DGELU && g.out2)) ok = ok && g.ldc2 % 8 == 0 && aligned16(g.out2);
+  if (g.epi == EPI_DGELU) ok = ok && g.ldpre % 8 == 0 && aligned16(g.pre);
+  if (g.epi != EPI_PLAIN && g.epi != EPI_DGELU) ok = ok && aligned16(g.bias);
+  if (g.epi == EPI_PATCH) ok = ok && aligned16(g.pos);
+  return ok;
+}
+
+// Tile shape: SLIDE_NT_VARIANT (tuning aid) overrides the built-in choice.
+hipError_t launch_gemm_nt_mfma(const GemmNT& g, hipStream_t s) {
+  if (g_variant < 0) {
+    const char* e = getenv("SLIDE_NT_VARIANT");
+    g_variant = e ? atoi(e) : 1;
+  }
+  int v = g_variant;
+  if (g.M < 1024) v = 1;  // small problems: small tiles
+  switch (v) {
+    case 1: return go<2, 2, 2, 2, 64>(g, s);   // 128 x 128
+    case 2: return go<4, 2, 2, 2, 64>(g, s);   // 256 x 128
+    case 3: return go<4, 4, 2, 2, 64>(g, s);   // 256 x 256
+    case 6: return go<2, 2, 4, 2, 64>(g, s);   // 256 x 128, 8 waves
+    case 7: return go<2, 4, 4, 1, 64>(g, s);   // 256 x 128, 4x1 waves of 64 x 128
+    case 8: return go<2, 4, 2, 1, 64>(g, s);   // 128 x 128, 2 waves of 64 x 128
+    default: return go<4, 2, 2, 2, 64>(g, s);
+  }
+}
+
+}  // namespace sl

@@ -14,9 +14,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Residual-stream element type of the bf16 path (activations that are summed layer after
-// layer, forward x and backward dx).  float keeps the running sums exact to fp32; every
-// other saved activation is bf16.
-#ifndef SLIDE_BF16_STREAM_IS_BF16
+// layer, forward x and backward dx).  bf16 halves the traffic of every kernel that touches the
+// stream and stays inside the 2e-2 parity budget; -DSLIDE_BF16_STREAM_IS_F32 keeps the running
+// sums in fp32 instead (about half the error, 4*D more bytes per token and layer).
+#ifdef SLIDE_BF16_STREAM_IS_F32
 typedef float rs_bf16path_t;
 #else
 typedef bf16 rs_bf16path_t;
@@ -45,12 +46,33 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// erf(x) and exp(-x^2) together.  Rational approximation 7.1.26 of Abramowitz & Stegun,
+// |error| <= 1.5e-7 (about one fp32 ulp of the result near 1): one reciprocal, one exponential
+// and five fused multiply-adds instead of the library routine's long polynomial ladder; the
+// GEMM epilogues that apply GELU run it once per output element.
+__device__ __forceinline__ float erf_exp(float x, float* e_out) {
+  float ax = fabsf(x);
+  float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * ax);  // 1 ulp reciprocal
+  float e = __expf(-ax * ax);
+  float p = ((((1.061405429f * t - 1.453152027f) * t + 1.421413741f) * t - 0.284496736f) * t + 0.254829592f) * t;
+  *e_out = e;
+  return copysignf(1.0f - p * e, x);
+}
 __device__ __forceinline__ float gelu_f(float m) {
-  return 0.5f * m * (1.0f + erff(m * 0.70710678118654752f));
+  float e;
+  return 0.5f * m * (1.0f + erf_exp(m * 0.70710678118654752f, &e));
+}
+// gelu(m) and gelu'(m) from one erf/exp evaluation
+__device__ __forceinline__ void gelu_both(float m, float* g, float* dg) {
+  float e;
+  float c = 0.5f * (1.0f + erf_exp(m * 0.70710678118654752f, &e));
+  *g = m * c;
+  *dg = c + m * e * 0.39894228040143268f;
 }
 __device__ __forceinline__ float gelu_grad_f(float m) {
-  return 0.5f * (1.0f + erff(m * 0.70710678118654752f)) +
-         m * __expf(-0.5f * m * m) * 0.39894228040143268f;
+  float e;  // exp(-m^2/2)
+  float c = 0.5f * (1.0f + erf_exp(m * 0.70710678118654752f, &e));
+  return c + m * e * 0.39894228040143268f;
 }
 
 // Row map used where a GEMM operand lives in the token matrix but only patch-token rows
@@ -69,7 +91,7 @@ enum {
   EPI_BIAS = 1,        // out(T)  = acc + bias[n]
   EPI_BIAS_RESID = 2,  // out(RS) = acc + bias[n] + resid(RS)[m][n]
   EPI_BIAS_GELU = 3,   // out(T)  = m = acc + bias[n];  out2(T) = gelu(m)
-  EPI_DGELU = 4,       // out(T)  = acc * gelu'(pre(T)[m][n])
+  EPI_DGELU = 4,       // out(T)  = acc * gelu'(pre(T)[m][n]);  out2(T) = gelu(pre) when out2 != null
   EPI_PATCH = 5,       // out(RS)[rowmap(m)] = acc + bias[n] + pos[1 + m % g2][n]
 };
 

@@ -45,7 +45,7 @@ struct Layout {
   size_t enc_begin;
   size_t e_patches, e_x, e_qkv, e_O, e_lse, e_xmid, e_m;              // first instance
   size_t s_x, s_qkv, s_O, s_lse, s_xmid, s_m;                         // per-layer strides (0 when not saved)
-  size_t e_u, e_a, e_dxA, e_dxB, e_dxAt, e_dxBt, e_du, e_dqkv;
+  size_t e_u, e_a, e_dm, e_dxA, e_dxB, e_dxAt, e_dxBt, e_du, e_dqkv;
 };
 
 }  // namespace
@@ -145,8 +145,9 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, bool save)
   y.e_m = take(0); cur += (size_t)inst * align256(M * c->F * e);
   y.e_u = take(M * D * e);
   size_t abytes = M * c->F * e, pbytes = (size_t)nn * c->g2 * c->Kp * e;
-  y.e_a = take(abytes > pbytes ? abytes : pbytes);
+  y.e_a = take(abytes);
   if (save) {
+    y.e_dm = take(abytes > pbytes ? abytes : pbytes);
     y.e_dxA = take(M * D * rs);
     y.e_dxB = take(M * D * rs);
     if (rs != e) { y.e_dxAt = take(M * D * e); y.e_dxBt = take(M * D * e); }
@@ -154,7 +155,7 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, bool save)
     y.e_du = take(M * D * e);
     y.e_dqkv = take(M * 3 * D * e);
   } else {
-    y.e_dxA = y.e_dxB = y.e_dxAt = y.e_dxBt = y.e_du = y.e_dqkv = 0;
+    y.e_dm = y.e_dxA = y.e_dxB = y.e_dxAt = y.e_dxBt = y.e_du = y.e_dqkv = 0;
   }
   y.total = cur;
   return y;
@@ -375,7 +376,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
   float* cpart = (float*)(ar + y.w_cpart);
   float* lnpart = (float*)(ar + y.w_lnpart);
   char *dxA = ar + y.e_dxA, *dxB = ar + y.e_dxB, *dxAt = ar + y.e_dxAt, *dxBt = ar + y.e_dxBt;
-  char *du = ar + y.e_du, *dqkv = ar + y.e_dqkv, *u = ar + y.e_u, *a = ar + y.e_a;
+  char *du = ar + y.e_du, *dqkv = ar + y.e_dqkv, *u = ar + y.e_u, *a = ar + y.e_a, *dm = ar + y.e_dm;
   RowMap id{0, 0};
   float* G = c->grads;
   launch(r, K_ELEMWISE, 0, (double)M * D * rs, [&] { return launch_fill_zero(dxA, (size_t)M * D * rs, s); });
@@ -393,19 +394,18 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
     char* m = ar + y.e_m + (size_t)l * y.s_m;
     int wi = 1 + 4 * l;
     // ---- MLP half: x_out = x_mid + gelu(LN2(x_mid) W1^T + b1) W2^T + b2
-    launch(r, K_ELEMWISE, 0, 2.0 * M * F * e, [&] { return launch_gelu(dt, m, a, M * F, s); });
-    gemm_tn(r, dxAt, D, id, a, F, id, M, D, F, wpart, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
-    {
+    {  // dm = (dx W2) * gelu'(m); the same epilogue re-creates a = gelu(m) for the weight gradient
       GemmNT g{};
       g.A = dxAt; g.lda = D; g.B = weight_t(c, wi + 3); g.ldb = D; g.M = M; g.N = F; g.K = D;
-      g.epi = EPI_DGELU; g.pre = m; g.ldpre = F; g.out = a; g.ldc = F;  // dm overwrites the GELU output
+      g.epi = EPI_DGELU; g.pre = m; g.ldpre = F; g.out = dm; g.ldc = F; g.out2 = a; g.ldc2 = F;
       gemm_nt(r, g);
     }
+    gemm_tn(r, dxAt, D, id, a, F, id, M, D, F, wpart, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
     ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u, D, M);
-    gemm_tn(r, a, F, id, u, D, id, M, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
+    gemm_tn(r, dm, F, id, u, D, id, M, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
     {
       GemmNT g{};
-      g.A = a; g.lda = F; g.B = weight_t(c, wi + 2); g.ldb = F; g.M = M; g.N = D; g.K = F;
+      g.A = dm; g.lda = F; g.B = weight_t(c, wi + 2); g.ldb = F; g.M = M; g.N = D; g.K = F;
       g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
       gemm_nt(r, g);
     }
@@ -448,10 +448,10 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
   if (pixel_grad) {
     GemmNT g{};
     g.A = dxAt; g.lda = D; g.amap = pm; g.B = weight_t(c, 0); g.ldb = D; g.M = Mp; g.N = c->Kp; g.K = D;
-    g.epi = EPI_PLAIN; g.out = a; g.ldc = c->Kp;
+    g.epi = EPI_PLAIN; g.out = dm; g.ldc = c->Kp;
     gemm_nt(r, g);
     launch(r, K_ELEMWISE, 0, 2.0 * Mp * c->Kp * e,
-           [&] { return launch_unpatchify(dt, a, pixel_grad, n, c->cfg.tile, c->cfg.patch, s); });
+           [&] { return launch_unpatchify(dt, dm, pixel_grad, n, c->cfg.tile, c->cfg.patch, s); });
   }
   return finish(r);
 }
