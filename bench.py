@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tiles", type=int, default=16)
     ap.add_argument("--prof-kernel", default="gemm_nt")
+    ap.add_argument("--recompute", type=int, default=-1,
+                    help="1 = keep block inputs only and re-run blocks in the backward (default: only for 'full')")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -61,7 +63,8 @@ def main():
     ds, ws, ls = gen.SEEDS[a.workload]
     dev = torch.device("cuda:0")
     dtype = 1  # bf16 storage / fp32 accumulate
-    lib = SlideLib(lib_config(cfg, dtype))
+    recompute = a.recompute if a.recompute >= 0 else int(a.workload == "full")
+    lib = SlideLib(lib_config(cfg, dtype, recompute))
     layout = lib.param_layout()
     prm = gen.make_params(cfg, ws)
     flat = np.zeros(lib.slide_param_count(), dtype=np.float32)
@@ -142,6 +145,7 @@ def main():
                                f"x {cfg.heads} heads, gated-attention MIL hidden {cfg.mil_hidden}, {cfg.n_classes} classes",
                    "tiles": N, "slide_steps_per_s": round(a.steps / dt, 4),
                    "model_gflop_per_tile": round(mflops / 1e9, 3), "mfu_bf16_peak": round(mfu, 4),
+                   "activation_policy": "block inputs + re-run blocks in backward" if recompute else "all block activations kept",
                    "arena_gb": round(nbytes / 1e9, 2), "peak_alloc_gb_of_288": round(peak_alloc, 2),
                    "loss": float(loss.item()), "input_gen_s": round(gen_s, 1)},
         "roofline": roof,

@@ -12,6 +12,10 @@
 //     as 8-column row segments, so bias / residual / GELU / position terms are applied with
 //     16-byte loads and stores and every output row of the strip is one contiguous run
 //     (partial-line stores straight from the MFMA register layout measured 25 % slower).
+//   * Persistent workgroups: the grid is what fits on the chip at once and every workgroup walks
+//     over tiles.  Identical tiles otherwise march in lockstep (all CUs load and multiply, then
+//     all CUs store), leaving HBM idle in one phase and the MFMAs idle in the other; here a
+//     tile's stores drain under the next tile's loads and MFMAs.
 //   * Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the id -> tile map puts
 //     the tiles that share an A row panel on the same XCD (same L2).
 #include "gemm_epi.h"
@@ -52,19 +56,26 @@ __device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
   *reinterpret_cast<bf16x8*>(p) = t;
 }
 
-// one row segment: columns n..n+7 of row m
+// Auxiliary operand of one 8-column row segment (residual / saved pre-activation / position
+// row), fetched ahead of the arithmetic so that its latency overlaps the LDS round trip.
 template <int MODE, typename RS>
-__device__ __forceinline__ void epi_seg8(const GemmNT& g, long long m, int n, float (&v)[8]) {
-  float t[8];
+__device__ __forceinline__ void epi_aux8(const GemmNT& g, long long m, int n, float (&t)[8]) {
+  if (MODE == EPI_BIAS_RESID) load8((const RS*)g.resid + m * g.ldr + n, t);
+  else if (MODE == EPI_DGELU) load8((const bf16*)g.pre + m * g.ldpre + n, t);
+  else if (MODE == EPI_PATCH) load8(g.pos + (size_t)(1 + (int)(m % g.cmap.g2)) * g.N + n, t);
+}
+
+// one row segment: columns n..n+7 of row m; `bias` and `t` (aux) were loaded by the caller
+template <int MODE, typename RS>
+__device__ __forceinline__ void epi_seg8(const GemmNT& g, long long m, int n, float (&v)[8], const float (&bias)[8],
+                                         float (&t)[8]) {
   if (MODE != EPI_PLAIN && MODE != EPI_DGELU) {
-    load8(g.bias + n, t);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] += t[i];
+    for (int i = 0; i < 8; ++i) v[i] += bias[i];
   }
   if (MODE == EPI_PLAIN || MODE == EPI_BIAS) {
     store8((bf16*)g.out + m * g.ldc + n, v);
   } else if (MODE == EPI_BIAS_RESID) {
-    load8((const RS*)g.resid + m * g.ldr + n, t);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] += t[i];
     store8((RS*)g.out + m * g.ldc + n, v);
@@ -77,7 +88,6 @@ __device__ __forceinline__ void epi_seg8(const GemmNT& g, long long m, int n, fl
     store8((bf16*)g.out + m * g.ldc + n, v);
     store8((bf16*)g.out2 + m * g.ldc2 + n, t);
   } else if (MODE == EPI_DGELU) {
-    load8((const bf16*)g.pre + m * g.ldpre + n, t);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       float gl, dg;
@@ -88,8 +98,6 @@ __device__ __forceinline__ void epi_seg8(const GemmNT& g, long long m, int n, fl
     store8((bf16*)g.out + m * g.ldc + n, v);
     if (g.out2) store8((bf16*)g.out2 + m * g.ldc2 + n, t);
   } else {  // EPI_PATCH
-    int tok = 1 + (int)(m % g.cmap.g2);
-    load8(g.pos + (size_t)tok * g.N + n, t);
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] += t[i];
     store8((RS*)g.out + g.cmap(m) * g.ldc + n, v);
@@ -121,24 +129,34 @@ __device__ __forceinline__ void nt_epilogue(const GemmNT& g, f32x16 (&acc)[WBM][
   constexpr int PS = WBN * 32 + 4;      // patch row stride (floats)
   constexpr int SEG = WBN * 4;          // 8-column segments per row
   constexpr int RPP = 64 / SEG;         // rows per pass
+  constexpr int NP = 32 / RPP;          // passes per strip
   int li = lane & 31, h2 = lane >> 5;
   int prow = lane / SEG, pseg = lane % SEG;
+  int n = nw + pseg * 8;
+  bool n_ok = n < g.N;
+  float bias[8];
+  if (MODE != EPI_PLAIN && MODE != EPI_DGELU && n_ok) load8(g.bias + n, bias);
 #pragma unroll
   for (int i = 0; i < WBM; ++i) {
+    float aux[NP][8];
+#pragma unroll
+    for (int ps = 0; ps < NP; ++ps) {
+      long long m = mw + i * 32 + ps * RPP + prow;
+      if (n_ok && m < g.M) epi_aux8<MODE, RS>(g, m, n, aux[ps]);
+    }
 #pragma unroll
     for (int j = 0; j < WBN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) patch[((r >> 2) * 8 + h2 * 4 + (r & 3)) * PS + j * 32 + li] = acc[i][j][r];
 #pragma unroll
-    for (int ps = 0; ps < 32 / RPP; ++ps) {
+    for (int ps = 0; ps < NP; ++ps) {
       int row = ps * RPP + prow;
       float v[8];
       const float4* src = reinterpret_cast<const float4*>(patch + row * PS + pseg * 8);
       float4 a = src[0], b = src[1];
       v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
       long long m = mw + i * 32 + row;
-      int n = nw + pseg * 8;
-      if (m < g.M && n < g.N) epi_seg8<MODE, RS>(g, m, n, v);
+      if (n_ok && m < g.M) epi_seg8<MODE, RS>(g, m, n, v, bias, aux[ps]);
     }
   }
 }
@@ -150,98 +168,147 @@ __global__ void __launch_bounds__(64 * WVM * WVN) gemm_nt_tile_k(GemmNT g, int M
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* As = reinterpret_cast<bf16*>(smem);  // [2][BM][LDT]
   bf16* Bs = As + 2 * BM * LDT;              // [2][BN][LDT]
-  int id = blockIdx.x;
-  int xcd = id % NXCD, slot = id / NXCD;
-  int mt = (slot / NTL) * NXCD + xcd, nt = slot % NTL;
-  if (mt >= MT) return;
-  long long m0 = (long long)mt * BM;
-  int n0 = nt * BN;
   const bf16* A = (const bf16*)g.A;
   const bf16* B = (const bf16*)g.B;
   int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   int wm = wave / WVN, wn = wave % WVN;
-
   int row0 = tid / C::CPR, kc = tid % C::CPR;
-  long long aoff[CA], boff[CB];
-#pragma unroll
-  for (int i = 0; i < CA; ++i) {
-    long long am = m0 + row0 + i * C::RSTEP;
-    if (am > g.M - 1) am = g.M - 1;  // rows past the end are loaded (valid memory) but never stored
-    aoff[i] = g.amap(am) * g.lda + kc * 8;
-  }
-#pragma unroll
-  for (int i = 0; i < CB; ++i) {
-    int bn = n0 + row0 + i * C::RSTEP;
-    if (bn > g.N - 1) bn = g.N - 1;
-    boff[i] = (long long)bn * g.ldb + kc * 8;
-  }
   int soff = row0 * LDT + kc * 8;
-  u32x4 ra[CA], rb[CB];
-#pragma unroll
-  for (int i = 0; i < CA; ++i) ra[i] = ldg16(A + aoff[i]);
-#pragma unroll
-  for (int i = 0; i < CB; ++i) rb[i] = ldg16(B + boff[i]);
-#pragma unroll
-  for (int i = 0; i < CA; ++i) *reinterpret_cast<u32x4*>(As + soff + i * C::RSTEP * LDT) = ra[i];
-#pragma unroll
-  for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(Bs + soff + i * C::RSTEP * LDT) = rb[i];
-  __syncthreads();
-
-  f32x16 acc[WBM][WBN];
-#pragma unroll
-  for (int i = 0; i < WBM; ++i)
-#pragma unroll
-    for (int j = 0; j < WBN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  int nk = g.K / BK;
   int frow = lane & 31, fk = (lane >> 5) * 8;
-  for (int kt = 0; kt < nk; ++kt) {
-    int cur = kt & 1;
-    bool more = kt + 1 < nk;
-    if (more) {
-#pragma unroll
-      for (int i = 0; i < CA; ++i) ra[i] = ldg16(A + aoff[i] + (kt + 1) * BK);
-#pragma unroll
-      for (int i = 0; i < CB; ++i) rb[i] = ldg16(B + boff[i] + (kt + 1) * BK);
-    }
-    const bf16* as = As + cur * BM * LDT + (wm * WBM * 32 + frow) * LDT + fk;
-    const bf16* bs = Bs + cur * BN * LDT + (wn * WBN * 32 + frow) * LDT + fk;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[WBM], fb[WBN];
-#pragma unroll
-      for (int i = 0; i < WBM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDT + ks * 16);
-#pragma unroll
-      for (int j = 0; j < WBN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDT + ks * 16);
-#pragma unroll
-      for (int i = 0; i < WBM; ++i)
-#pragma unroll
-        for (int j = 0; j < WBN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (more) {
-      int nxt = cur ^ 1;
-#pragma unroll
-      for (int i = 0; i < CA; ++i) *reinterpret_cast<u32x4*>(As + nxt * BM * LDT + soff + i * C::RSTEP * LDT) = ra[i];
-#pragma unroll
-      for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(Bs + nxt * BN * LDT + soff + i * C::RSTEP * LDT) = rb[i];
-    }
-    __syncthreads();
-  }
+  int nk = g.K / BK;
+  int total = (MT + NXCD - 1) / NXCD * NXCD * NTL;
 
-  // operand tiles are dead past the last barrier: the patches reuse their LDS
-  float* patch = reinterpret_cast<float*>(smem) + wave * 32 * (WBN * 32 + 4);
-  long long mw = m0 + wm * WBM * 32;
-  int nw = n0 + wn * WBN * 32;
-  switch (g.epi) {
-    case EPI_PLAIN: nt_epilogue<EPI_PLAIN, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
-    case EPI_BIAS: nt_epilogue<EPI_BIAS, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
-    case EPI_BIAS_RESID: nt_epilogue<EPI_BIAS_RESID, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
-    case EPI_BIAS_GELU: nt_epilogue<EPI_BIAS_GELU, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
-    case EPI_DGELU: nt_epilogue<EPI_DGELU, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
-    default: nt_epilogue<EPI_PATCH, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+  long long aoff[CA], boff[CB];
+  u32x4 ra[CA], rb[CB];
+  // tile id -> (row tile, column tile); ids are dealt round-robin to the XCDs, and the tiles of one
+  // row panel get consecutive slots of one XCD.  The grid size is a multiple of 8, so a persistent
+  // workgroup keeps meeting tiles of its own XCD.
+  auto tile_of = [&](int id, long long& m0, int& n0) {
+    int xcd = id % NXCD, slot = id / NXCD;
+    int mt = (slot / NTL) * NXCD + xcd;
+    m0 = (long long)mt * BM;
+    n0 = (slot % NTL) * BN;
+    return mt < MT;
+  };
+  auto fetch0 = [&](long long m0, int n0) {  // operand offsets of a tile + global loads of its first K step
+#pragma unroll
+    for (int i = 0; i < CA; ++i) {
+      long long am = m0 + row0 + i * C::RSTEP;
+      if (am > g.M - 1) am = g.M - 1;  // rows past the end are loaded (valid memory) but never stored
+      aoff[i] = g.amap(am) * g.lda + kc * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < CB; ++i) {
+      int bn = n0 + row0 + i * C::RSTEP;
+      if (bn > g.N - 1) bn = g.N - 1;
+      boff[i] = (long long)bn * g.ldb + kc * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < CA; ++i) ra[i] = ldg16(A + aoff[i]);
+#pragma unroll
+    for (int i = 0; i < CB; ++i) rb[i] = ldg16(B + boff[i]);
+  };
+
+  bool have = false;  // ra/rb already hold the first K step of the tile about to be processed
+  for (int id = blockIdx.x; id < total; id += gridDim.x) {
+    long long m0;
+    int n0;
+    if (!tile_of(id, m0, n0)) { have = false; continue; }  // uniform for the workgroup
+    if (!have) fetch0(m0, n0);
+#pragma unroll
+    for (int i = 0; i < CA; ++i) *reinterpret_cast<u32x4*>(As + soff + i * C::RSTEP * LDT) = ra[i];
+#pragma unroll
+    for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(Bs + soff + i * C::RSTEP * LDT) = rb[i];
+    __syncthreads();
+
+    f32x16 acc[WBM][WBN];
+#pragma unroll
+    for (int i = 0; i < WBM; ++i)
+#pragma unroll
+      for (int j = 0; j < WBN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    for (int kt = 0; kt < nk; ++kt) {
+      int cur = kt & 1;
+      bool more = kt + 1 < nk;
+#ifdef SLIDE_DEBUG_HOOKS
+      if (more && !(g.dbg & 4)) {
+#else
+      if (more) {
+#endif
+#pragma unroll
+        for (int i = 0; i < CA; ++i) ra[i] = ldg16(A + aoff[i] + (kt + 1) * BK);
+#pragma unroll
+        for (int i = 0; i < CB; ++i) rb[i] = ldg16(B + boff[i] + (kt + 1) * BK);
+      }
+      const bf16* as = As + cur * BM * LDT + (wm * WBM * 32 + frow) * LDT + fk;
+      const bf16* bs = Bs + cur * BN * LDT + (wn * WBN * 32 + frow) * LDT + fk;
+      // fragments of k-slice ks+1 are read from LDS before the MFMAs of slice ks are issued
+      bf16x8 fa[2][WBM], fb[2][WBN];
+#pragma unroll
+      for (int i = 0; i < WBM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDT);
+#pragma unroll
+      for (int j = 0; j < WBN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDT);
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        if (ks + 1 < BK / 16) {
+#pragma unroll
+          for (int i = 0; i < WBM; ++i)
+            fa[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDT + (ks + 1) * 16);
+#pragma unroll
+          for (int j = 0; j < WBN; ++j)
+            fb[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDT + (ks + 1) * 16);
+        }
+#ifdef SLIDE_DEBUG_HOOKS
+        if (!(g.dbg & 1))
+#endif
+#pragma unroll
+        for (int i = 0; i < WBM; ++i)
+#pragma unroll
+          for (int j = 0; j < WBN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+      }
+      if (more) {
+        int nxt = cur ^ 1;
+#pragma unroll
+        for (int i = 0; i < CA; ++i)
+          *reinterpret_cast<u32x4*>(As + nxt * BM * LDT + soff + i * C::RSTEP * LDT) = ra[i];
+#pragma unroll
+        for (int i = 0; i < CB; ++i)
+          *reinterpret_cast<u32x4*>(Bs + nxt * BN * LDT + soff + i * C::RSTEP * LDT) = rb[i];
+      }
+      __syncthreads();
+    }
+
+    // the next tile's first loads go out now: they and this tile's stores drain while the epilogue
+    // arithmetic runs, and the stores keep draining under the next tile's MFMAs
+    {
+      long long m1;
+      int n1;
+      int nid = id + gridDim.x;
+      have = nid < total && tile_of(nid, m1, n1);
+      if (have) fetch0(m1, n1);
+    }
+
+    // operand tiles are dead past the last barrier: the patches reuse their LDS
+    float* patch = reinterpret_cast<float*>(smem) + wave * 32 * (WBN * 32 + 4);
+    long long mw = m0 + wm * WBM * 32;
+    int nw = n0 + wn * WBN * 32;
+#ifdef SLIDE_DEBUG_HOOKS
+    if (g.dbg & 2) {
+      if (acc[0][0][0] == 12345.678f) ((float*)g.out)[0] = 1.f;  // keeps the accumulators alive
+    } else
+#endif
+    switch (g.epi) {
+      case EPI_PLAIN: nt_epilogue<EPI_PLAIN, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+      case EPI_BIAS: nt_epilogue<EPI_BIAS, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+      case EPI_BIAS_RESID: nt_epilogue<EPI_BIAS_RESID, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+      case EPI_BIAS_GELU: nt_epilogue<EPI_BIAS_GELU, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+      case EPI_DGELU: nt_epilogue<EPI_DGELU, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+      default: nt_epilogue<EPI_PATCH, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
+    }
+    __syncthreads();  // patches are read before the next tile's operands overwrite them
   }
 }
 
@@ -250,15 +317,23 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 template <int WBM, int WBN, int WVM, int WVN, int BK>
 hipError_t go(const GemmNT& g, hipStream_t s) {
   using C = Cfg<WBM, WBN, WVM, WVN, BK>;
-  static bool attr_done = false;
+  static int resident = 0;  // workgroups that fit on the chip at once (persistent grid size)
   auto kern = gemm_nt_tile_k<rs_bf16path_t, WBM, WBN, WVM, WVN, BK>;
-  if (!attr_done) {
+  if (!resident) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    int per_cu = 0, dev = 0;
+    hipDeviceProp_t prop;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
+    if ((e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, C::NT, C::LDS)) != hipSuccess) return e;
+    if (per_cu < 1) per_cu = 1;
+    resident = per_cu * prop.multiProcessorCount / NXCD * NXCD;
+    if (resident < NXCD) resident = NXCD;
   }
   int MT = (int)((g.M + C::BM - 1) / C::BM), NTL = (g.N + C::BN - 1) / C::BN;
-  long long wgs = (long long)((MT + NXCD - 1) / NXCD) * NXCD * NTL;
+  long long total = (long long)((MT + NXCD - 1) / NXCD) * NXCD * NTL;
+  long long wgs = total < resident ? total : resident;
   hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(C::NT), C::LDS, s, g, MT, NTL);
   return hipGetLastError();
 }
@@ -293,6 +368,9 @@ hipError_t launch_gemm_nt_mfma(const GemmNT& g, hipStream_t s) {
     case 6: return go<2, 2, 4, 2, 64>(g, s);   // 256 x 128, 8 waves
     case 7: return go<2, 4, 4, 1, 64>(g, s);   // 256 x 128, 4x1 waves of 64 x 128
     case 8: return go<2, 4, 2, 1, 64>(g, s);   // 128 x 128, 2 waves of 64 x 128
+    case 9: return go<2, 2, 2, 2, 32>(g, s);   // 128 x 128, K step 32
+    case 10: return go<4, 2, 2, 2, 32>(g, s);  // 256 x 128, K step 32
+    case 11: return go<4, 4, 2, 2, 32>(g, s);  // 256 x 256, K step 32
     default: return go<4, 2, 2, 2, 64>(g, s);
   }
 }

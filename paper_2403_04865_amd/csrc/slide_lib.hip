@@ -100,8 +100,14 @@ void add_shadow(slide_ctx* c, size_t poff, int R, int Cc) {
 
 // Carve the arena for an encoder call on n tiles (with or without saved activations) and a
 // pool over pool_N rows.  Pure arithmetic; the same inputs always give the same layout.
-Layout make_layout(const slide_ctx* c, long long n, long long pool_N, bool save) {
+// keep: 0 = nothing is saved (feature extraction), 1 = every block's activations, 2 = block inputs only
+// (one set of block activations is shared by all blocks and re-created in the backward).
+enum { KEEP_NONE = 0, KEEP_ALL = 1, KEEP_INPUTS = 2 };
+
+Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) {
   Layout y;
+  bool save = keep == KEEP_ALL;      // per-block instances of every saved activation
+  bool bwd = keep != KEEP_NONE;      // backward work buffers
   size_t cur = align256(c->shadow_bytes);
   auto take = [&](size_t bytes) { size_t o = cur; cur = align256(cur + bytes); return o; };
   size_t e = elem_size(c->dt), rs = rs_size(c->dt);
@@ -126,18 +132,18 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, bool save)
   y.enc_begin = cur;
   int inst = save ? c->L : (c->L > 0 ? 1 : 0);
   y.e_patches = take((size_t)nn * c->g2 * c->Kp * e);
-  y.s_x = save ? align256(M * D * rs) : 0;
+  y.s_x = bwd ? align256(M * D * rs) : 0;
   y.e_x = take(0);
-  cur += (save ? (size_t)(c->L + 1) : 1) * align256(M * D * rs);
+  cur += (bwd ? (size_t)(c->L + 1) : 1) * align256(M * D * rs);
   y.s_qkv = save ? align256(M * 3 * D * e) : 0;
   y.e_qkv = take(0); cur += (size_t)inst * align256(M * 3 * D * e);
   y.s_O = save ? align256(M * D * e) : 0;
   y.e_O = take(0); cur += (size_t)inst * align256(M * D * e);
   y.s_lse = save ? align256((size_t)nn * c->H * c->T * 4) : 0;
   y.e_lse = take(0); cur += (size_t)inst * align256((size_t)nn * c->H * c->T * 4);
-  if (save) {
-    y.s_xmid = align256(M * D * rs);
-    y.e_xmid = take(0); cur += (size_t)inst * y.s_xmid;
+  if (bwd) {
+    y.s_xmid = save ? align256(M * D * rs) : 0;
+    y.e_xmid = take(0); cur += (size_t)inst * align256(M * D * rs);
   } else {
     y.s_xmid = 0; y.e_xmid = y.e_x;  // residual adds run in place
   }
@@ -146,7 +152,7 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, bool save)
   y.e_u = take(M * D * e);
   size_t abytes = M * c->F * e, pbytes = (size_t)nn * c->g2 * c->Kp * e;
   y.e_a = take(abytes);
-  if (save) {
+  if (bwd) {
     y.e_dm = take(abytes > pbytes ? abytes : pbytes);
     y.e_dxA = take(M * D * rs);
     y.e_dxB = take(M * D * rs);
@@ -285,19 +291,70 @@ int check_bound(const slide_ctx* c) {
   return SLIDE_OK;
 }
 
+// One transformer block forward: x_in(l) -> x_in(l+1), leaving qkv, O, lse, x_mid and the fc1
+// pre-activation of block l in their (per-block or shared) arena slots.  `replay` (backward of the
+// block-inputs-only policy): x_in(l+1) is already stored, so the GELU output and the fc2 GEMM are skipped.
+void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
+  slide_ctx* c = r.c;
+  hipStream_t s = r.s;
+  char* ar = c->arena;
+  int D = c->D, T = c->T, F = c->F, dt = c->dt;
+  long long M = n * T;
+  const LayerOff& o = c->lo[l];
+  char* xin = ar + y.e_x + (size_t)l * y.s_x;
+  char* xout = ar + y.e_x + (size_t)(l + 1) * y.s_x;
+  char* xmid = ar + y.e_xmid + (size_t)l * y.s_xmid;
+  char* qkv = ar + y.e_qkv + (size_t)l * y.s_qkv;
+  char* O = ar + y.e_O + (size_t)l * y.s_O;
+  float* lse = (float*)(ar + y.e_lse + (size_t)l * y.s_lse);
+  char* m = ar + y.e_m + (size_t)l * y.s_m;
+  char* u = ar + y.e_u;
+  char* a = ar + y.e_a;
+  int wi = 1 + 4 * l;
+  ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
+  {
+    GemmNT g{};
+    g.A = u; g.lda = D; g.B = weight(c, wi + 0); g.ldb = D; g.M = M; g.N = 3 * D; g.K = D;
+    g.epi = EPI_BIAS; g.bias = c->params + o.qkvb; g.out = qkv; g.ldc = 3 * D;
+    gemm_nt(r, g);
+  }
+  launch(r, K_ATTN_FWD, 4.0 * n * c->H * (double)T * T * c->dh, (double)M * 4 * D * elem_size(dt),
+         [&] { return launch_attn_fwd(dt, qkv, O, lse, n, T, c->H, c->dh, c->use_mfma, s); });
+  {
+    GemmNT g{};
+    g.A = O; g.lda = D; g.B = weight(c, wi + 1); g.ldb = D; g.M = M; g.N = D; g.K = D;
+    g.epi = EPI_BIAS_RESID; g.bias = c->params + o.projb; g.resid = xin; g.ldr = D; g.out = xmid; g.ldc = D;
+    gemm_nt(r, g);
+  }
+  ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u, D, M);
+  {
+    GemmNT g{};
+    g.A = u; g.lda = D; g.B = weight(c, wi + 2); g.ldb = D; g.M = M; g.N = F; g.K = D;
+    g.epi = replay ? EPI_BIAS : EPI_BIAS_GELU; g.bias = c->params + o.fc1b; g.out = m; g.ldc = F;
+    g.out2 = a; g.ldc2 = F;
+    gemm_nt(r, g);
+  }
+  if (!replay) {
+    GemmNT g{};
+    g.A = a; g.lda = F; g.B = weight(c, wi + 3); g.ldb = F; g.M = M; g.N = D; g.K = F;
+    g.epi = EPI_BIAS_RESID; g.bias = c->params + o.fc2b; g.resid = xmid; g.ldr = D; g.out = xout; g.ldc = D;
+    gemm_nt(r, g);
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // encoder forward
 // ------------------------------------------------------------------------------------------
 int enc_fwd(slide_ctx* c, const void* pixels, long long n, void* feats_out, bool save, long long pool_N,
             hipStream_t s) {
-  Layout y = make_layout(c, n, pool_N, save);
+  int keep = !save ? KEEP_NONE : (c->cfg.recompute ? KEEP_INPUTS : KEEP_ALL);
+  Layout y = make_layout(c, n, pool_N, keep);
   if (y.total > c->arena_bytes) return SLIDE_EARENA;
   c->enc_saved = false;
   c->step_saved = false;
   Run r{c, s};
   char* ar = c->arena;
-  int D = c->D, T = c->T, F = c->F, dt = c->dt;
-  long long M = n * T;
+  int D = c->D, T = c->T, dt = c->dt;
   cast_weights(r);
   launch(r, K_ELEMWISE, 0, 2.0 * n * 3 * c->cfg.tile * c->cfg.tile * elem_size(dt),
          [&] { return launch_patchify(dt, pixels, ar + y.e_patches, n, c->cfg.tile, c->cfg.patch, s); });
@@ -312,47 +369,7 @@ int enc_fwd(slide_ctx* c, const void* pixels, long long n, void* feats_out, bool
   }
   launch(r, K_ELEMWISE, 0, 0,
          [&] { return launch_cls_rows(dt, ar + y.e_x, c->params + c->o_cls, c->params + c->o_pos, n, T, D, s); });
-  for (int l = 0; l < c->L; ++l) {
-    const LayerOff& o = c->lo[l];
-    char* xin = ar + y.e_x + (size_t)l * y.s_x;
-    char* xout = ar + y.e_x + (size_t)(l + 1) * y.s_x;
-    char* xmid = ar + y.e_xmid + (size_t)l * y.s_xmid;
-    char* qkv = ar + y.e_qkv + (size_t)l * y.s_qkv;
-    char* O = ar + y.e_O + (size_t)l * y.s_O;
-    float* lse = (float*)(ar + y.e_lse + (size_t)l * y.s_lse);
-    char* m = ar + y.e_m + (size_t)l * y.s_m;
-    char* u = ar + y.e_u;
-    char* a = ar + y.e_a;
-    int wi = 1 + 4 * l;
-    ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
-    {
-      GemmNT g{};
-      g.A = u; g.lda = D; g.B = weight(c, wi + 0); g.ldb = D; g.M = M; g.N = 3 * D; g.K = D;
-      g.epi = EPI_BIAS; g.bias = c->params + o.qkvb; g.out = qkv; g.ldc = 3 * D;
-      gemm_nt(r, g);
-    }
-    launch(r, K_ATTN_FWD, 4.0 * n * c->H * (double)T * T * c->dh, (double)M * 4 * D * elem_size(dt),
-           [&] { return launch_attn_fwd(dt, qkv, O, lse, n, T, c->H, c->dh, c->use_mfma, s); });
-    {
-      GemmNT g{};
-      g.A = O; g.lda = D; g.B = weight(c, wi + 1); g.ldb = D; g.M = M; g.N = D; g.K = D;
-      g.epi = EPI_BIAS_RESID; g.bias = c->params + o.projb; g.resid = xin; g.ldr = D; g.out = xmid; g.ldc = D;
-      gemm_nt(r, g);
-    }
-    ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u, D, M);
-    {
-      GemmNT g{};
-      g.A = u; g.lda = D; g.B = weight(c, wi + 2); g.ldb = D; g.M = M; g.N = F; g.K = D;
-      g.epi = EPI_BIAS_GELU; g.bias = c->params + o.fc1b; g.out = m; g.ldc = F; g.out2 = a; g.ldc2 = F;
-      gemm_nt(r, g);
-    }
-    {
-      GemmNT g{};
-      g.A = a; g.lda = F; g.B = weight(c, wi + 3); g.ldb = F; g.M = M; g.N = D; g.K = F;
-      g.epi = EPI_BIAS_RESID; g.bias = c->params + o.fc2b; g.resid = xmid; g.ldr = D; g.out = xout; g.ldc = D;
-      gemm_nt(r, g);
-    }
-  }
+  for (int l = 0; l < c->L; ++l) block_fwd(r, y, l, n, false);
   char* xL = ar + y.e_x + (size_t)c->L * y.s_x;
   ln_fwd(r, xL, (long long)T * D, c->params + c->o_lnfg, c->params + c->o_lnfb, feats_out, D, n, true);
   if (r.ok() && save) { c->enc_saved = true; c->enc_n = n; c->enc_layout = y; }
@@ -393,6 +410,9 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
     float* lse = (float*)(ar + y.e_lse + (size_t)l * y.s_lse);
     char* m = ar + y.e_m + (size_t)l * y.s_m;
     int wi = 1 + 4 * l;
+    // block inputs only were kept: re-create this block's activations in the shared slots (the
+    // last block's are still there from the forward)
+    if (c->cfg.recompute && l != c->L - 1) block_fwd(r, y, l, n, true);
     // ---- MLP half: x_out = x_mid + gelu(LN2(x_mid) W1^T + b1) W2^T + b2
     {  // dm = (dx W2) * gelu'(m); the same epilogue re-creates a = gelu(m) for the weight gradient
       GemmNT g{};
@@ -528,7 +548,7 @@ int slide_ctx_create(const slide_config* cfg, slide_ctx** out) {
   if (dh != 8 && dh != 32 && dh != 64) return SLIDE_EUNSUPPORTED;
   if (cfg->dim > 1024 || cfg->n_classes > 64 || cfg->mil_hidden > 1024) return SLIDE_EUNSUPPORTED;
   if (attn_lds_bytes(T, dh) > 160 * 1024) return SLIDE_EUNSUPPORTED;
-  if (cfg->recompute != 0) return SLIDE_EUNSUPPORTED;
+  if (cfg->recompute != 0 && cfg->recompute != 1) return SLIDE_EINVAL;
   slide_ctx* c = new (std::nothrow) slide_ctx();
   if (!c) return SLIDE_EINVAL;
   c->cfg = *cfg;
@@ -612,12 +632,12 @@ int slide_param_offset(const slide_ctx* c, const char* name, size_t* offset, siz
 
 size_t slide_arena_bytes(const slide_ctx* c, int64_t n_tiles) {
   if (!c || n_tiles <= 0) return 0;
-  return make_layout(c, n_tiles, n_tiles, true).total;
+  return make_layout(c, n_tiles, n_tiles, c->cfg.recompute ? KEEP_INPUTS : KEEP_ALL).total;
 }
 
 size_t slide_pool_arena_bytes(const slide_ctx* c, int64_t N) {
   if (!c || N <= 0) return 0;
-  return make_layout(c, 0, N, false).pool_end;
+  return make_layout(c, 0, N, KEEP_NONE).pool_end;
 }
 
 int slide_bind(slide_ctx* c, const float* params, float* grads, void* arena, size_t arena_bytes) {
@@ -647,7 +667,7 @@ static int pool_check(slide_ctx* c, const void* feats, int64_t N, int32_t label,
   if (rc) return rc;
   if (!feats || N <= 0) return SLIDE_EINVAL;
   if (label < 0 || label >= (c->C == 1 ? 2 : c->C)) return SLIDE_EINVAL;
-  *y = make_layout(c, 0, N, false);
+  *y = make_layout(c, 0, N, KEEP_NONE);
   if (y->pool_end > c->arena_bytes) return SLIDE_EARENA;
   // a pool over more rows than the saved encoder state was laid out for would overwrite it
   if (c->enc_saved && y->pool_end > c->enc_layout.enc_begin) { c->enc_saved = false; c->step_saved = false; }
@@ -677,7 +697,7 @@ int slide_step_fwd(slide_ctx* c, const void* pixels, int64_t N, int32_t label, f
   if (rc) return rc;
   if (!pixels || N <= 0) return SLIDE_EINVAL;
   if (label < 0 || label >= (c->C == 1 ? 2 : c->C)) return SLIDE_EINVAL;
-  Layout y = make_layout(c, N, N, true);
+  Layout y = make_layout(c, N, N, c->cfg.recompute ? KEEP_INPUTS : KEEP_ALL);
   if (y.total > c->arena_bytes) return SLIDE_EARENA;
   rc = enc_fwd(c, pixels, N, c->arena + y.p_H, true, N, (hipStream_t)stream);
   if (rc) return rc;
@@ -738,6 +758,18 @@ int slide_prof_end(slide_ctx* c, double* total_ms, int* launches, double* flops,
   p.active = false;
   return rc;
 }
+
+#ifdef SLIDE_DEBUG_HOOKS
+// Tuning aid (not part of the ABI, not built by default): one NT GEMM on caller-provided buffers.
+int slide_debug_gemm_nt(long long M, int N, int K, const void* A, const void* B, const float* bias, const void* aux,
+                        void* out, void* out2, int epi, int dbg, void* stream) {
+  GemmNT g{};
+  g.A = A; g.lda = K; g.B = B; g.ldb = K; g.M = M; g.N = N; g.K = K; g.epi = epi; g.bias = bias;
+  g.resid = aux; g.ldr = N; g.pre = aux; g.ldpre = N; g.out = out; g.ldc = N; g.out2 = out2; g.ldc2 = N; g.dbg = dbg;
+  hipError_t e = launch_gemm_nt(DT_BF16, g, true, (hipStream_t)stream);
+  return e == hipSuccess ? 0 : SLIDE_EHIP;
+}
+#endif
 
 const char* slide_kernel_name(int id) { return (id >= 0 && id < K_COUNT) ? kKernelNames[id] : nullptr; }
 

@@ -54,7 +54,8 @@ def test_config_validation():
     from paper_2403_04865_amd import SlideLib, SlideConfig, SlideError
     ok = dict(tile=32, patch=8, dim=64, layers=2, heads=2, mlp_ratio=4, mil_hidden=32, n_classes=1)
     SlideLib(SlideConfig(**ok))
-    for bad in (dict(tile=30), dict(heads=3), dict(n_classes=0), dict(dtype=2), dict(layers=-1), dict(ln_eps=0.0)):
+    for bad in (dict(tile=30), dict(heads=3), dict(n_classes=0), dict(dtype=2), dict(layers=-1), dict(ln_eps=0.0),
+                dict(recompute=2)):
         with pytest.raises(SlideError) as e:
             SlideLib(SlideConfig(**{**ok, **bad}))
         assert e.value.code == -1
@@ -73,6 +74,12 @@ def test_arena_arithmetic_and_unbound_calls(lib):
     assert sizes == sorted(sizes) and sizes[-1] < 288e9
     assert all(s % 256 == 0 for s in sizes)
     assert L.slide_pool_arena_bytes(8192) < sizes[2]
+    # block-inputs-only policy: much smaller arena; the 16384-tile ViT-B slide fits one device with it only
+    R = SlideLib(lib_config(cfg, 1, recompute=1))
+    assert R.slide_arena_bytes(8192) < 0.5 * sizes[-1]
+    fcfg, fn = gen.CONFIGS["full"]
+    assert SlideLib(lib_config(fcfg, 1, recompute=0)).slide_arena_bytes(fn) > 288e9
+    assert SlideLib(lib_config(fcfg, 1, recompute=1)).slide_arena_bytes(fn) + fn * 3 * 224 * 224 * 2 < 270e9
     # nothing bound yet: compute calls refuse without touching the GPU
     with pytest.raises(SlideError) as e:
         L._check(L.lib.slide_step_bwd(L.ctx, 0, None, None), "slide_step_bwd")

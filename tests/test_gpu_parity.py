@@ -26,11 +26,11 @@ def _inputs(name, n=None, perturbed=True, n_classes=None, bf16=False, std=0.02):
     return cfg, prm, X, gen.make_label(cfg, ls)
 
 
-def _run(cfg, prm, X, label, dtype, tol, grad_tol=None):
+def _run(cfg, prm, X, label, dtype, tol, grad_tol=None, recompute=0):
     from oracle import slide_oracle as so
     from slide_harness import GpuSlide, compare_step
-    print(f"case cfg={cfg} n={X.shape[0]} dtype={dtype} label={label}", flush=True)
-    g = GpuSlide(cfg, prm, dtype, X.shape[0])
+    print(f"case cfg={cfg} n={X.shape[0]} dtype={dtype} label={label} recompute={recompute}", flush=True)
+    g = GpuSlide(cfg, prm, dtype, X.shape[0], recompute)
     out = g.step(X, label)
     ref = so.slide_step(prm, X.astype(np.float64), label, cfg)
     _, pool_same = so.pool_bwd(so.pool_fwd(prm, out["H"], label, cfg)[4])
@@ -72,3 +72,36 @@ def test_vit_s_fp32_21_tiles():
 def test_vit_s_bf16_21_tiles():
     cfg, prm, X, lab = _inputs("small", n=21, bf16=True)
     _run(cfg, prm, X, lab, 1, BF16_TOL)
+
+
+# ---- block-inputs-only activation policy (blocks are re-run inside the backward) ----------------
+def test_tiny_fp32_recompute():
+    cfg, prm, X, lab = _inputs("tiny")
+    _run(cfg, prm, X, lab, 0, FP32_TOL, recompute=1)
+
+
+def test_vit_s_bf16_21_tiles_recompute():
+    cfg, prm, X, lab = _inputs("small", n=21, bf16=True)
+    _run(cfg, prm, X, lab, 1, BF16_TOL, recompute=1)
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+def test_recompute_is_bit_identical_to_keeping_everything(dtype):
+    # same kernels on the same inputs in the same order: re-running a block reproduces its activations exactly
+    from slide_harness import GpuSlide
+    cfg, prm, X, lab = _inputs("small", n=5, bf16=bool(dtype))
+    cfg = replace(cfg, layers=3)
+    prm = gen.make_params(cfg, 77, perturbed=True)
+    outs = []
+    for rc in (0, 1):
+        print(f"case small/3 layers n=5 dtype={dtype} recompute={rc}", flush=True)
+        g = GpuSlide(cfg, prm, dtype, X.shape[0], rc)
+        outs.append(g.step(X, lab))
+        if rc == 1:
+            assert g.lib.slide_arena_bytes(5) < GpuSlide(cfg, prm, dtype, 5, 0).lib.slide_arena_bytes(5)
+    a, b = outs
+    assert a["loss"] == b["loss"]
+    for k in ("H", "G", "alpha", "dX"):
+        assert np.array_equal(a[k], b[k]), k
+    for k in a["grads"]:
+        assert np.array_equal(a["grads"][k], b["grads"][k]), k
