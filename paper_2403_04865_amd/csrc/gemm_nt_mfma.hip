@@ -353,13 +353,18 @@ bool gemm_nt_mfma_ok(const GemmNT& g) {
   return ok;
 }
 
-// Tile shape: SLIDE_NT_VARIANT (tuning aid) overrides the built-in choice.
+bool gemm_nt_big_ok(const GemmNT& g);
+hipError_t launch_gemm_nt_big(const GemmNT& g, hipStream_t s);
+
+// Large problems go to the 256 x 192 persistent kernel; the rest to the small-tile kernel below, whose
+// tile shape SLIDE_NT_VARIANT (tuning aid; 0 = never use the large kernel) overrides.
 hipError_t launch_gemm_nt_mfma(const GemmNT& g, hipStream_t s) {
   if (g_variant < 0) {
     const char* e = getenv("SLIDE_NT_VARIANT");
-    g_variant = e ? atoi(e) : 1;
+    g_variant = e ? atoi(e) : 100;
   }
-  int v = g_variant;
+  if (g_variant >= 100 && gemm_nt_big_ok(g)) return launch_gemm_nt_big(g, s);
+  int v = g_variant >= 100 ? 1 : g_variant;
   if (g.M < 1024) v = 1;  // small problems: small tiles
   switch (v) {
     case 1: return go<2, 2, 2, 2, 64>(g, s);   // 128 x 128

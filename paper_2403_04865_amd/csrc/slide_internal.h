@@ -83,6 +83,12 @@ struct RowMap {
   __host__ __device__ __forceinline__ long long operator()(long long r) const {
     return g2 ? (r / g2) * T + 1 + (r % g2) : r;
   }
+  // same for row indices below 2^31 (32-bit division)
+  __host__ __device__ __forceinline__ long long map32(unsigned r) const {
+    if (!g2) return r;
+    unsigned q = r / (unsigned)g2;
+    return (long long)q * T + 1 + (r - q * (unsigned)g2);
+  }
 };
 
 // ---- GEMM epilogues (C = A * B^T, A [M,K], B [N,K], both K-contiguous) ------------------
