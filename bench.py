@@ -34,6 +34,70 @@ def model_flops_per_tile(cfg):
 PEAK = {"mfma_bf16": 2.5e15, "hbm": 8e12}
 
 
+def pool_sweep(a):
+    """Achieved HBM bandwidth of the pool kernels alone (mil_pool_fwd / mil_pool_bwd through the C ABI) over feature
+    matrices far larger than the caches: N = 2^13 .. 2^22 rows of 384 floats, M_h = 128, one logit.  Algorithmic
+    bytes: forward N*D*4 (every feature row read once), backward 2*N*D*4 (rows read once, gradient rows written
+    once).  Times are HIP events around the kernels of each call, on the launch stream."""
+    import numpy as np
+    import torch
+    import gen
+    from dataclasses import replace
+    from slide_harness import lib_config
+    from paper_2403_04865_amd import SlideLib
+    cfg, _ = gen.CONFIGS["medium"]
+    cfg = replace(cfg, mil_hidden=a.pool_hidden)
+    dev = torch.device("cuda:0")
+    lib = SlideLib(lib_config(cfg, 1))
+    prm = gen.make_params(cfg, gen.SEEDS["medium"][1])
+    flat = np.zeros(lib.slide_param_count(), dtype=np.float32)
+    for name, off, ln in lib.param_layout():
+        flat[off:off + ln] = prm[name].reshape(-1)
+    params = torch.from_numpy(flat).to(dev)
+    grads = torch.zeros_like(params)
+    names = lib.kernel_names()
+    rows = []
+    for lg in range(13, a.pool_max_log2 + 1):
+        N = 1 << lg
+        nbytes = lib.slide_pool_arena_bytes(N)
+        arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        o = (-arena.data_ptr()) % 256
+        lib.slide_bind(params, grads, arena[o:o + nbytes])
+        H = torch.from_numpy(gen.make_features(cfg, min(N, 1 << 16), 9)).to(dev)
+        if N > H.shape[0]:
+            H = H.repeat(N // H.shape[0], 1).contiguous()
+        G = torch.empty_like(H)
+        loss = torch.zeros(1, device=dev)
+        res = {"N": N, "feature_MB": round(N * cfg.dim * 4 / 1e6, 1)}
+        for which, kid in (("fwd", names.index("pool_fwd")), ("bwd", names.index("pool_bwd"))):
+            reps = 5
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for it in range(reps + 1):
+                if it == 1:
+                    torch.cuda.synchronize()
+                    lib.slide_prof_begin(kid)
+                    e0.record()
+                if which == "fwd":
+                    lib.mil_pool_fwd(H, N, 1, loss, None, None)
+                else:
+                    lib.mil_pool_bwd(H, N, 1, G, 0)
+            e1.record()
+            torch.cuda.synchronize()
+            ms, n, _, by = lib.slide_prof_end()
+            ms /= max(n, 1)
+            # the whole ABI call (backward: forward recomputation + row kernel + weight-gradient reductions)
+            res[which + "_call_us"] = round(e0.elapsed_time(e1) / reps * 1e3, 1)
+            alg = N * cfg.dim * 4 * (1 if which == "fwd" else 2)
+            res[which + "_us"] = round(ms * 1e3, 1)
+            res[which + "_GBps"] = round(alg / (ms * 1e-3) / 1e9, 1)
+            res[which + "_frac_hbm"] = round(alg / (ms * 1e-3) / PEAK["hbm"], 4)
+        rows.append(res)
+        print(json.dumps(res), flush=True)
+        del arena, H, G
+        torch.cuda.empty_cache()
+    print(json.dumps({"pool_sweep": rows, "D": cfg.dim, "mil_hidden": cfg.mil_hidden, "peak_GBps": PEAK["hbm"] / 1e9}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,10 +110,16 @@ def main():
     ap.add_argument("--prof-kernel", default="gemm_nt")
     ap.add_argument("--recompute", type=int, default=-1,
                     help="1 = keep block inputs only and re-run blocks in the backward (default: only for 'full')")
+    ap.add_argument("--pool-sweep", action="store_true", help="bandwidth sweep of the pool kernels instead of the step")
+    ap.add_argument("--pool-hidden", type=int, default=128)
+    ap.add_argument("--pool-max-log2", type=int, default=22)
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if a.pool_sweep:
+        return pool_sweep(a)
 
     import numpy as np
     import torch

@@ -5,5 +5,5 @@ method's arithmetic (no encoder, pool, loss or gradient code) lives here.
 """
 from .slide_inputs import (  # noqa: F401
     SlideConfig, CONFIGS, SEEDS, param_shapes, make_params, make_pixels,
-    make_label, to_bf16_grid,
+    make_label, make_features, to_bf16_grid,
 )

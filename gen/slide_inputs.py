@@ -183,6 +183,20 @@ def make_pixels(cfg: SlideConfig, n_tiles: int, seed: int, kind: str = "blur",
     return out
 
 
+def make_features(cfg: SlideConfig, n_rows: int, seed: int, spread: float = 0.25):
+    """Synthetic [n_rows, D] tile-feature matrix with the statistics of final-LayerNorm CLS rows: a
+    common component shared by all tiles plus a per-tile component (spread = their ratio, so that
+    |H| / |H - mean row| is about 1 / spread), float32."""
+    rng = np.random.Generator(np.random.PCG64([seed, 77]))
+    mu = rng.standard_normal(cfg.dim)
+    out = np.empty((n_rows, cfg.dim), dtype=np.float32)
+    step = 65536
+    for lo in range(0, n_rows, step):
+        hi = min(n_rows, lo + step)
+        out[lo:hi] = mu + spread * rng.standard_normal((hi - lo, cfg.dim))
+    return out
+
+
 def make_label(cfg: SlideConfig, seed: int) -> int:
     rng = np.random.Generator(np.random.PCG64(seed))
     if cfg.n_classes == 1:

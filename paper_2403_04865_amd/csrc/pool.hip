@@ -314,12 +314,30 @@ static hipError_t set_lds(K kernel, size_t bytes) {
   return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-hipError_t launch_pool_fwd(const PoolArgs& p, hipStream_t s) {
+hipError_t launch_pool_fwd(const PoolArgs& p0, hipStream_t s) {
+  PoolArgs p = p0;
   size_t lds = pool_lds(p.D, p.Mh);
   hipError_t e;
-  if ((e = set_lds(pool_gate_part_k, lds)) != hipSuccess) return e;
-  hipLaunchKernelGGL(pool_gate_part_k, dim3(p.blocks), dim3(256), lds, s, p);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
+  if (p.use_mfma && pool_mfma_ok(p)) {
+    // persistent grid: one workgroup per compute unit (it owns almost all of the unit's LDS)
+    static int cus = 0;
+    if (!cus) {
+      int dev = 0;
+      hipDeviceProp_t prop;
+      if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+      if ((e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
+      cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+    }
+    int rb = pool_mfma_rows(p);
+    long long groups = (p.N + rb - 1) / rb;
+    p.blocks = (int)(groups < cus ? groups : cus);
+    if (p.blocks > 1024) p.blocks = 1024;
+    if ((e = launch_pool_gate_part_mfma(p, s)) != hipSuccess) return e;
+  } else {
+    if ((e = set_lds(pool_gate_part_k, lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL(pool_gate_part_k, dim3(p.blocks), dim3(256), lds, s, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(pool_combine_k, dim3(1), dim3(256), 0, s, p);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (p.alpha) {

@@ -1,0 +1,247 @@
+// Gated-attention MIL pooling, forward stage 1 on the matrix cores (gfx950, bf16 path).
+//
+// a_n = w . (tanh(V h_n + b_V) * sigmoid(U h_n + b_U)) needs 4 * M_h * D flop per feature row of D * 4 bytes:
+// 128 flop/byte at M_h = 128, far more than the vector ALUs deliver at HBM speed, so the two projections are one
+// bf16 MFMA GEMM [rows] x [V;U]^T with fp32 accumulation.  Everything else stays fp32 / fp64 on the
+// unrounded features: the softmax over tiles is a two-level online reduction (every workgroup keeps a running
+// max, sum and weighted feature sum over its row blocks; one workgroup combines them afterwards).
+//   * One persistent workgroup (4 wavefronts) per compute unit walks over blocks of RB feature rows.
+//   * The block's rows sit in LDS as fp32 (they are needed again, exactly, for the weighted sum); MFMA operands
+//     are converted to bf16 on the way from LDS to the registers.  The next block is in flight from HBM, in
+//     registers, while the current one is processed: each feature row is read from HBM exactly once.
+//   * [V;U] (bf16 copy, 2 M_h x D) streams from L2 through a double-buffered LDS ring, BK columns per step.
+//   * Operands are passed swapped (weights first): a lane then owns one feature row and 16 gate units per
+//     accumulator, so the sum over gate units is in-lane plus one exchange between the lane halves.
+#include "slide_internal.h"
+
+namespace sl {
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ bf16x8 cvt8(float4 a, float4 b) {
+  f32x2 p0 = {a.x, a.y}, p1 = {a.z, a.w}, p2 = {b.x, b.y}, p3 = {b.z, b.w};
+  bf16x2 h0 = __builtin_convertvector(p0, bf16x2), h1 = __builtin_convertvector(p1, bf16x2);
+  bf16x2 h2 = __builtin_convertvector(p2, bf16x2), h3 = __builtin_convertvector(p3, bf16x2);
+  bf16x8 r = {h0[0], h0[1], h1[0], h1[1], h2[0], h2[1], h3[0], h3[1]};
+  return r;
+}
+
+// [V;U] fp32 -> bf16, rows 0..Mh-1 = V, Mh..2Mh-1 = U
+__global__ void __launch_bounds__(256) pool_cast_vu_k(const float* __restrict__ V, const float* __restrict__ U,
+                                                      bf16* __restrict__ out, long long n) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) { out[i] = (bf16)V[i]; out[n + i] = (bf16)U[i]; }
+}
+
+template <int RB, int MH, int BK>
+struct PoolCfg {
+  static constexpr int RG = RB / 32;          // row groups of 32 (wavefronts along the rows)
+  static constexpr int JG = 4 / RG;           // wavefronts along the gate units
+  static constexpr int JW = MH / JG;          // gate units per wavefront
+  static constexpr int NBK = JW / 32;         // 32 x 32 accumulators per wavefront for V (and as many for U)
+  static constexpr int LDW = BK + 8;          // LDS row stride of the weight ring (bf16)
+  static constexpr int WCH = 2 * MH * (BK / 8) / 256;  // 16-byte weight chunks per thread and step
+  static_assert(JW % 32 == 0 && WCH >= 1, "shape");
+  static size_t lds_bytes(int D) {
+    return (size_t)RB * (D + 4) * 4 + (size_t)2 * 2 * MH * LDW * 2 + (size_t)D * 8 + (size_t)3 * MH * 4 +
+           (size_t)JG * RB * 4 + (size_t)RB * 4 + 64;
+  }
+};
+
+template <int RB, int MH, int BK, int HCH>   // HCH: float4 chunks of the row block per thread (RB * D / 1024)
+__global__ void __launch_bounds__(256) pool_gate_part_mfma_k(PoolArgs p, const bf16* __restrict__ VU) {
+  using C = PoolCfg<RB, MH, BK>;
+  constexpr int LDW = C::LDW, NBK = C::NBK, JW = C::JW;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int D = p.D, LDH = D + 4;
+  float* Hs = reinterpret_cast<float*>(smem);                          // [RB][LDH]
+  bf16* Ws = reinterpret_cast<bf16*>(Hs + RB * LDH);                   // [2][2 MH][LDW]
+  double* zb = reinterpret_cast<double*>(Ws + 2 * 2 * MH * LDW);       // [D]
+  float* gb = reinterpret_cast<float*>(zb + D);                        // bV[MH], bU[MH], w[MH]
+  float* apart = gb + 3 * MH;                                          // [JG][RB]
+  float* er = apart + C::JG * RB;                                      // [RB]
+  float* misc = er + RB;                                               // run_m, resc; run_l as double behind
+  double* run_l = reinterpret_cast<double*>(misc + 2);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int rg = wave % C::RG, jg = wave / C::RG;
+  const int li = lane & 31, h2 = lane >> 5;
+  const int nk = D / BK;
+  const float* H = p.H;
+  const long long total = p.N * (long long)D;   // feature elements
+
+  for (int d = tid; d < D; d += 256) zb[d] = 0.0;
+  for (int j = tid; j < MH; j += 256) { gb[j] = p.Vb[j]; gb[MH + j] = p.Ub[j]; gb[2 * MH + j] = p.w[j]; }
+  if (tid == 0) { misc[0] = -INFINITY; misc[1] = 0.f; *run_l = 0.0; }
+
+  const long long groups = (p.N + RB - 1) / RB;
+  // weight ring loader: chunk c = tid + i * 256 -> row c / (BK / 8), 16-byte column c % (BK / 8)
+  u32x4 rw[C::WCH];
+  auto issue_w = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < C::WCH; ++i) {
+      int c = tid + i * 256;
+      int row = c / (BK / 8), kc = c % (BK / 8);
+      rw[i] = *reinterpret_cast<const u32x4*>(VU + (size_t)row * D + kt * BK + kc * 8);
+    }
+  };
+  auto stash_w = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < C::WCH; ++i) {
+      int c = tid + i * 256;
+      int row = c / (BK / 8), kc = c % (BK / 8);
+      *reinterpret_cast<u32x4*>(Ws + ((size_t)buf * 2 * MH + row) * LDW + kc * 8) = rw[i];
+    }
+  };
+  // feature block loader: the block is one contiguous span of RB * D floats
+  float4 rh[HCH];
+  auto issue_h = [&](long long g) {
+    long long e0 = g * RB * (long long)D;
+#pragma unroll
+    for (int i = 0; i < HCH; ++i) {
+      long long e = e0 + (long long)(tid + i * 256) * 4;
+      rh[i] = e < total ? *reinterpret_cast<const float4*>(H + e) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto stash_h = [&]() {
+    int q4 = D / 4;
+#pragma unroll
+    for (int i = 0; i < HCH; ++i) {
+      int c = tid + i * 256;
+      int row = c / q4, col = (c - row * q4) * 4;
+      *reinterpret_cast<float4*>(Hs + row * LDH + col) = rh[i];
+    }
+  };
+
+  long long gi = blockIdx.x;
+  if (gi < groups) issue_h(gi);
+  issue_w(0);
+  __syncthreads();
+  for (; gi < groups; gi += gridDim.x) {
+    const long long n0 = gi * RB;
+    stash_h();
+    long long gnext = gi + gridDim.x;
+    if (gnext < groups) issue_h(gnext);   // in flight during the whole block
+
+    f32x16 acc[2 * NBK];
+#pragma unroll
+    for (int b = 0; b < 2 * NBK; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[b][r] = 0.f;
+
+    for (int kt = 0; kt < nk; ++kt) {
+      int buf = kt & 1;
+      stash_w(buf);
+      issue_w(kt + 1 < nk ? kt + 1 : 0);
+      __syncthreads();   // ring stage (and, at kt == 0, the feature block) visible; the other stage is free
+      const float* hrow = Hs + (rg * 32 + li) * LDH + kt * BK + h2 * 8;
+      const bf16* wbase = Ws + (size_t)buf * 2 * MH * LDW + h2 * 8;
+#pragma unroll
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        float4 a = *reinterpret_cast<const float4*>(hrow + ks * 16);
+        float4 b4 = *reinterpret_cast<const float4*>(hrow + ks * 16 + 4);
+        bf16x8 hf = cvt8(a, b4);
+#pragma unroll
+        for (int b = 0; b < 2 * NBK; ++b) {
+          int row = (b < NBK ? 0 : MH) + jg * JW + (b % NBK) * 32 + li;
+          bf16x8 wf = *reinterpret_cast<const bf16x8*>(wbase + row * LDW + ks * 16);
+          acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, hf, acc[b], 0, 0, 0);
+        }
+      }
+    }
+    // gate: lane = feature row rg * 32 + li; accumulator register r = gate unit (r / 4) * 8 + h2 * 4 + r % 4 of its block
+    float part = 0.f;
+#pragma unroll
+    for (int b = 0; b < NBK; ++b)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        int j = jg * JW + b * 32 + q * 8 + h2 * 4;
+        float4 bv = *reinterpret_cast<const float4*>(gb + j);
+        float4 bu = *reinterpret_cast<const float4*>(gb + MH + j);
+        float4 wj = *reinterpret_cast<const float4*>(gb + 2 * MH + j);
+        float bvv[4] = {bv.x, bv.y, bv.z, bv.w}, buu[4] = {bu.x, bu.y, bu.z, bu.w}, ww[4] = {wj.x, wj.y, wj.z, wj.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float xv = acc[b][4 * q + e] + bvv[e], xu = acc[NBK + b][4 * q + e] + buu[e];
+          // tanh(xv) * sigmoid(xu) = (1 - e1) / ((1 + e1) (1 + e2)), e1 = exp(-2 xv), e2 = exp(-xu)
+          float e1 = __expf(fminf(-2.0f * xv, 40.f)), e2 = __expf(fminf(-xu, 40.f));
+          part += ww[e] * ((1.0f - e1) * __builtin_amdgcn_rcpf((1.0f + e1) * (1.0f + e2)));
+        }
+      }
+    part += __shfl_xor(part, 32, 64);
+    if (h2 == 0) apart[jg * RB + rg * 32 + li] = part;
+    __syncthreads();
+    if (tid < 64) {   // wavefront 0: logits of the block, online softmax state
+      float a = 0.f;
+      if (tid < RB) {
+#pragma unroll
+        for (int j = 0; j < C::JG; ++j) a += apart[j * RB + tid];
+      }
+      bool ok = tid < RB && n0 + tid < p.N;
+      if (ok) p.a[n0 + tid] = a;
+      a = ok ? a : -INFINITY;
+      float m_old = misc[0];
+      float m = fmaxf(m_old, wave_max(a));   // finite: the block has at least one row
+      float e = __expf(a - m);
+      if (tid < RB) er[tid] = e;
+      float es = wave_sum(e);
+      if (tid == 0) {
+        float sc = __expf(m_old - m);   // exp(-inf) = 0 on the first block
+        misc[0] = m; misc[1] = sc;
+        *run_l = *run_l * (double)sc + (double)es;
+      }
+    }
+    __syncthreads();
+    {
+      float sc = misc[1];
+      for (int d = tid; d < D; d += 256) {
+        double z = zb[d] * (double)sc;
+#pragma unroll 8
+        for (int r = 0; r < RB; ++r) z += (double)er[r] * (double)Hs[r * LDH + d];
+        zb[d] = z;
+      }
+    }
+    __syncthreads();   // the feature block and er are free again
+  }
+  double* out = p.part + (size_t)blockIdx.x * (2 + D);
+  if (tid == 0) { out[0] = (double)misc[0]; out[1] = *run_l; }
+  for (int d = tid; d < D; d += 256) out[2 + d] = zb[d];
+}
+
+template <int RB, int MH, int BK, int HCH>
+hipError_t go(const PoolArgs& p, hipStream_t s) {
+  using C = PoolCfg<RB, MH, BK>;
+  auto kern = pool_gate_part_mfma_k<RB, MH, BK, HCH>;
+  size_t lds = C::lds_bytes(p.D);
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  long long n = (long long)p.Mh * p.D;
+  hipLaunchKernelGGL(pool_cast_vu_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.VW, p.UW, (bf16*)p.vub, n);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(256), lds, s, p, (const bf16*)p.vub);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// shapes built: (D, M_h) in {384, 768} x {128, 256}
+bool pool_mfma_ok(const PoolArgs& p) {
+  return p.vub && p.N >= 512 && (p.D == 384 || p.D == 768) && (p.Mh == 128 || p.Mh == 256) &&
+         ((uintptr_t)p.H & 15) == 0 && ((uintptr_t)p.vub & 15) == 0;
+}
+
+int pool_mfma_rows(const PoolArgs& p) { return p.D == 384 ? 64 : 32; }
+
+hipError_t launch_pool_gate_part_mfma(const PoolArgs& p, hipStream_t s) {
+  if (p.D == 384 && p.Mh == 128) return go<64, 128, 32, 24>(p, s);
+  if (p.D == 384 && p.Mh == 256) return go<64, 256, 16, 24>(p, s);
+  if (p.D == 768 && p.Mh == 128) return go<32, 128, 32, 24>(p, s);
+  if (p.D == 768 && p.Mh == 256) return go<32, 256, 16, 24>(p, s);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace sl

@@ -177,8 +177,13 @@ struct PoolArgs {
   float* grads;                  // flat gradient vector
   size_t ocW, ocb;               // offsets of head.W / head.b in it
   int accumulate;
+  void* vub;     // [2 Mh][D] bf16 copy of [V;U] (scratch; only the matrix-core forward uses it), may be null
+  int use_mfma;  // bf16 path: gate projections on the matrix cores where the shape is built
 };
 int pool_blocks(long long N);
+bool pool_mfma_ok(const PoolArgs& p);
+int pool_mfma_rows(const PoolArgs& p);
+hipError_t launch_pool_gate_part_mfma(const PoolArgs& p, hipStream_t s);
 hipError_t launch_pool_fwd(const PoolArgs& p, hipStream_t s);
 hipError_t launch_pool_bwd_rows(const PoolArgs& p, float* Dp, hipStream_t s);
 

@@ -38,7 +38,7 @@ struct ShadowMat { size_t w, wt; int R, C; size_t poff; };
 struct Layout {
   size_t total = 0;
   // pool
-  size_t p_a, p_part, p_scal, p_Dp, p_tn, p_cs, p_H, p_G, pool_end;
+  size_t p_a, p_part, p_scal, p_Dp, p_tn, p_cs, p_vub, p_H, p_G, pool_end;
   // shared reduction work space
   size_t w_wpart, w_cpart, w_lnpart;
   // encoder
@@ -119,6 +119,7 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   y.p_Dp = take((size_t)PN * 3 * Mh * 4);
   y.p_tn = take((size_t)32 * Mh * D * 4);
   y.p_cs = take((size_t)128 * 3 * Mh * 4);
+  y.p_vub = take((size_t)2 * Mh * D * 2);
   y.p_H = take((size_t)PN * D * 4);
   y.p_G = take((size_t)PN * D * 4);
   y.pool_end = cur;
@@ -488,6 +489,7 @@ PoolArgs pool_args(slide_ctx* c, const Layout& y, const void* feats, long long N
   p.a = (float*)(ar + y.p_a); p.part = (double*)(ar + y.p_part); p.scal = (float*)(ar + y.p_scal);
   p.blocks = pool_blocks(N);
   p.grads = c->grads; p.ocW = c->o_cW; p.ocb = c->o_cb;
+  p.vub = ar + y.p_vub; p.use_mfma = c->use_mfma && c->dt == DT_BF16;
   return p;
 }
 
