@@ -98,6 +98,33 @@ def pool_sweep(a):
     print(json.dumps({"pool_sweep": rows, "D": cfg.dim, "mil_hidden": cfg.mil_hidden, "peak_GBps": PEAK["hbm"] / 1e9}))
 
 
+def calib_copy(a):
+    """One warm-up and three launches of the library's plain copy kernel over --calib-copy bytes: the known-size
+    kernel whose FETCH_SIZE / WRITE_SIZE readings give the scale of those counters."""
+    import torch
+    from paper_2403_04865_amd import SlideLib, SlideConfig
+    lib = SlideLib(SlideConfig(32, 8, 64, 2, 2, 4, 32, 1))
+    n = a.calib_copy // 16 * 16
+    src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros(n, dtype=torch.uint8, device="cuda:0")
+    for _ in range(4):
+        lib.slide_calib_copy(dst, src, n)
+    torch.cuda.synchronize()
+    assert bool((dst[:4096] == 1).all())
+    print(json.dumps({"calib_copy_bytes": n, "launches": 4}))
+
+
+def load_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` measured with rocprofv3 --pmc (profiles/traffic_<workload>.json, written by
+    `python -m paper_2403_04865_amd.pmc_traffic`); None when no measurement of this workload is stored."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        d = json.load(f)
+    return d.get(kernel)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +137,7 @@ def main():
     ap.add_argument("--prof-kernel", default="gemm_nt")
     ap.add_argument("--recompute", type=int, default=-1,
                     help="1 = keep block inputs only and re-run blocks in the backward (default: only for 'full')")
+    ap.add_argument("--calib-copy", type=int, default=0, help="run the plain copy kernel over this many bytes and exit")
     ap.add_argument("--pool-sweep", action="store_true", help="bandwidth sweep of the pool kernels instead of the step")
     ap.add_argument("--pool-hidden", type=int, default=128)
     ap.add_argument("--pool-max-log2", type=int, default=22)
@@ -120,6 +148,8 @@ def main():
 
     if a.pool_sweep:
         return pool_sweep(a)
+    if a.calib_copy:
+        return calib_copy(a)
 
     import numpy as np
     import torch
@@ -187,8 +217,11 @@ def main():
     mflops = model_flops_per_tile(cfg)
     mfu = tiles_per_s * mflops / PEAK["mfma_bf16"]
     achieved = (k_flops / (k_ms * 1e-3)) / 1e12 if k_ms > 0 else 0.0   # TFLOP/s of the profiled kernel family
+    tr = load_traffic(a.workload, a.prof_kernel) if not a.tiles else None
     roof = {"bound": "mfma", "kernel": a.prof_kernel, "achieved": round(achieved, 2), "peak": 2500.0,
-            "unit": "TFLOP/s", "frac": round(achieved / 2500.0, 4), "traffic": None,
+            "unit": "TFLOP/s", "frac": round(achieved / 2500.0, 4),
+            "traffic": None if tr is None else tr["hbm_bytes_per_launch"],
+            "algorithmic_bytes_per_launch": round(k_bytes / max(k_n, 1)),
             "launches": k_n, "avg_launch_ms": round(k_ms / max(k_n, 1), 4),
             "share_of_step": round(k_ms / (dt * 1e3), 4)}
 

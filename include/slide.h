@@ -157,6 +157,11 @@ int         slide_prof_end(slide_ctx* ctx, double* total_ms, int* launches,
                            double* flops, double* bytes);
 const char* slide_kernel_name(int kernel_id);  /* NULL past the last id */
 
+/* Measurement aid: a plain device-to-device copy kernel (calib_copy_k) of `bytes` bytes (a multiple
+ * of 16; dst and src 16-byte aligned device pointers, not overlapping).  It moves a known number of
+ * bytes, which is what the hardware traffic counters of the other kernels are scaled with. */
+int  slide_calib_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

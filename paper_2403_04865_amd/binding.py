@@ -68,6 +68,7 @@ _SYMS = {
     "slide_prof_begin": (C.c_int, [C.c_void_p, C.c_int]),
     "slide_prof_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "slide_kernel_name": (C.c_char_p, [C.c_int]),
+    "slide_calib_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
 
 
@@ -192,6 +193,9 @@ class SlideLib:
         ms, n, fl, by = C.c_double(), C.c_int(), C.c_double(), C.c_double()
         self._check(self.lib.slide_prof_end(self.ctx, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)), "slide_prof_end")
         return ms.value, n.value, fl.value, by.value
+
+    def slide_calib_copy(self, dst, src, nbytes, stream=None):
+        self._check(self.lib.slide_calib_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream(stream)), "slide_calib_copy")
 
     def kernel_names(self):
         out, i = [], 0

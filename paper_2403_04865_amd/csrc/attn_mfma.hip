@@ -95,13 +95,16 @@ constexpr float LOG2E = 1.4426950408889634f;
 // --------------------------------------------------------------------------------------------
 template <int DH, int NB>
 __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict__ qkv, bf16* __restrict__ O,
-                                                       float* __restrict__ lse, int T, int H) {
+                                                       float* __restrict__ lse, int T, int H, long long ntiles) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
   bf16* Vt = Ks + TP * LDR;                  // [DH][LDT]
-  int h = blockIdx.x % H;
-  long long tile = blockIdx.x / H;
+  // workgroup ids are dealt round-robin to the 8 XCDs: the heads of one tile go to one XCD, next to each other
+  // in time, so the neighbouring 128-byte head slices of its token rows meet in one L2
+  int h = (blockIdx.x / 8) % H;
+  long long tile = (long long)(blockIdx.x / 8 / H) * 8 + blockIdx.x % 8;
+  if (tile >= ntiles) return;
   int D = H * DH;
   long long gs = 3LL * D;
   const bf16* base = qkv + tile * T * gs + h * DH;
@@ -117,49 +120,55 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict
     bf16x8 fq[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) fq[ks] = as_bf16x8(ldg16(base + qc * gs + ks * 16 + h2 * 8));
-    f32x16 s[NB];
-#pragma unroll
-    for (int kb = 0; kb < NB; ++kb) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + li) * LDR + ks * 16 + h2 * 8);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fq[ks], s[kb], 0, 0, 0);
-      }
-    }
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kb = 0; kb < NB; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        int key = kb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
-        if (key >= T) s[kb][r] = -INFINITY;
-        mx = fmaxf(mx, s[kb][r]);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    float l = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < NB; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f((s[kb][r] - mx) * sl2);
-        s[kb][r] = p;
-        l += p;
-      }
-    l += __shfl_xor(l, 32, 64);
+    // keys are taken one block of 32 at a time with a running maximum and sum (the whole row of
+    // scores never sits in registers); o is rescaled when the maximum moves
     f32x16 o[DB];
 #pragma unroll
     for (int d = 0; d < DB; ++d)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
+    float mx = -INFINITY, l = 0.f;
+#pragma unroll 1
+    for (int kb = 0; kb < NB; ++kb) {
+      f32x16 sc;
 #pragma unroll
-    for (int kb = 0; kb < NB; ++kb)
+      for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fq[ks], sc, 0, 0, 0);
+      }
+      float bm = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (kb == NB - 1) {   // only the last block holds padded keys
+          int key = kb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
+          if (key >= T) sc[r] = -INFINITY;
+        }
+        bm = fmaxf(bm, sc[r]);
+      }
+      bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+      float mn = fmaxf(mx, bm);                                  // finite: every block has a real key
+      float resc = __builtin_amdgcn_exp2f((mx - mn) * sl2);       // 0 at the first block
+      float ms = mn * sl2;
+      float ls = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float pe = __builtin_amdgcn_exp2f(sc[r] * sl2 - ms);
+        sc[r] = pe;
+        ls += pe;
+      }
+      l = l * resc + ls;
+      mx = mn;
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[d][r] *= resc;
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         float pv[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) pv[i] = s[kb][8 * t + i];
+        for (int i = 0; i < 8; ++i) pv[i] = sc[8 * t + i];
         bf16x8 pb = pack8(pv);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
@@ -167,6 +176,8 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict
           o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[d], 0, 0, 0);
         }
       }
+    }
+    l += __shfl_xor(l, 32, 64);
     if (q < T) {
       float inv = 1.0f / l;
       bf16* orow = O + (tile * T + q) * D + h * DH;
@@ -190,14 +201,17 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict
 template <int DH, int NB>
 __global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
-                                                         bf16* __restrict__ dqkv, int T, int H) {
+                                                         bf16* __restrict__ dqkv, int T, int H, long long ntiles) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
   bf16* Vs = Ks + TP * LDR;                  // [TP][LDR]
   bf16* Kt = Vs + TP * LDR;                  // [DH][LDT]
-  int h = blockIdx.x % H;
-  long long tile = blockIdx.x / H;
+  // workgroup ids are dealt round-robin to the 8 XCDs: the heads of one tile go to one XCD, next to each other
+  // in time, so the neighbouring 128-byte head slices of its token rows meet in one L2
+  int h = (blockIdx.x / 8) % H;
+  long long tile = (long long)(blockIdx.x / 8 / H) * 8 + blockIdx.x % 8;
+  if (tile >= ntiles) return;
   int D = H * DH;
   long long gs = 3LL * D;
   const bf16* base = qkv + tile * T * gs + h * DH;
@@ -281,7 +295,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restri
 template <int DH, int NB>
 __global__ void __launch_bounds__(256) attn_bwd_k_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
-                                                         bf16* __restrict__ dqkv, int T, int H) {
+                                                         bf16* __restrict__ dqkv, int T, int H, long long ntiles) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Qs = reinterpret_cast<bf16*>(smem);   // [TP][LDR]
@@ -290,8 +304,11 @@ __global__ void __launch_bounds__(256) attn_bwd_k_mfma_k(const bf16* __restrict_
   bf16* Gt = Qt + DH * LDT;                   // [DH][LDT]
   float* ls = reinterpret_cast<float*>(Gt + DH * LDT);  // [TP] lse * log2(e), +inf on padding rows
   float* dl = ls + TP;                                  // [TP] delta
-  int h = blockIdx.x % H;
-  long long tile = blockIdx.x / H;
+  // workgroup ids are dealt round-robin to the 8 XCDs: the heads of one tile go to one XCD, next to each other
+  // in time, so the neighbouring 128-byte head slices of its token rows meet in one L2
+  int h = (blockIdx.x / 8) % H;
+  long long tile = (long long)(blockIdx.x / 8 / H) * 8 + blockIdx.x % 8;
+  if (tile >= ntiles) return;
   int D = H * DH;
   long long gs = 3LL * D;
   const bf16* base = qkv + tile * T * gs + h * DH;
@@ -404,8 +421,8 @@ hipError_t fwd_go(const void* qkv, void* O, float* lse, long long n, int T, int 
   size_t lds = fwd_lds<DH, NB>();
   hipError_t e = set_lds(attn_fwd_mfma_k<DH, NB>, lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_fwd_mfma_k<DH, NB>), dim3((unsigned)(n * H)), dim3(256), lds, s,
-                     (const bf16*)qkv, (bf16*)O, lse, T, H);
+  hipLaunchKernelGGL((attn_fwd_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(256), lds, s,
+                     (const bf16*)qkv, (bf16*)O, lse, T, H, n);
   return hipGetLastError();
 }
 
@@ -417,11 +434,11 @@ hipError_t bwd_go(const void* qkv, const void* O, const float* lse, const void* 
   if (e != hipSuccess) return e;
   e = set_lds(attn_bwd_k_mfma_k<DH, NB>, lk);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_bwd_q_mfma_k<DH, NB>), dim3((unsigned)(n * H)), dim3(256), lq, s,
-                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H);
+  hipLaunchKernelGGL((attn_bwd_q_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(256), lq, s,
+                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_bwd_k_mfma_k<DH, NB>), dim3((unsigned)(n * H)), dim3(256), lk, s,
-                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H);
+  hipLaunchKernelGGL((attn_bwd_k_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(256), lk, s,
+                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n);
   return hipGetLastError();
 }
 

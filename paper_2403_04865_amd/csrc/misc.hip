@@ -113,6 +113,21 @@ __global__ void __launch_bounds__(256) fill_zero_k(uint4* __restrict__ p, size_t
   for (; i < words; i += stride) p[i] = make_uint4(0, 0, 0, 0);
 }
 
+// plain copy, 16 bytes per lane, grid-stride: the known-size kernel that hardware traffic counters are scaled with
+__global__ void __launch_bounds__(256) calib_copy_k(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t words) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x, step = (size_t)gridDim.x * 256;
+  for (; i < words; i += step) dst[i] = src[i];
+}
+
+hipError_t launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  size_t words = bytes / 16;
+  if (!words) return hipSuccess;
+  size_t blocks = (words + 255) / 256;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(calib_copy_k, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, words);
+  return hipGetLastError();
+}
+
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   size_t words = bytes / 16;
   if (words == 0) return hipSuccess;

@@ -138,6 +138,7 @@ hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long 
 hipError_t launch_unpatchify(int dt, const void* dpatches, void* dpix, long long n, int S, int P, hipStream_t s);
 hipError_t launch_cls_rows(int dt, void* x, const float* cls, const float* pos, long long n, int T, int D, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_gelu(int dt, const void* m, void* a, long long count, hipStream_t s);
 // part[s][c] = sum over rows of slab s of A[map(r)][c]; elem: DT_F32 / DT_BF16 element type of A
 int colsum_slabs(long long M);

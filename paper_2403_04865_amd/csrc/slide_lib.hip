@@ -220,7 +220,11 @@ void cast_weights(Run& r) {
 
 void gemm_nt(Run& r, const GemmNT& g) {
   size_t e = elem_size(r.c->dt);
+  // every operand once: A, B, the output(s), and the residual / saved pre-activation the epilogue reads
   double bytes = (double)g.M * g.K * e + (double)g.N * g.K * e + (double)g.M * g.N * e;
+  if (g.epi == EPI_BIAS_RESID) bytes += (double)g.M * g.N * rs_size(r.c->dt);
+  if (g.epi == EPI_BIAS_GELU || (g.epi == EPI_DGELU && g.out2)) bytes += (double)g.M * g.N * e;
+  if (g.epi == EPI_DGELU) bytes += (double)g.M * g.N * e;
   launch(r, K_GEMM_NT, 2.0 * g.M * g.N * g.K, bytes, [&] { return launch_gemm_nt(r.c->dt, g, r.c->use_mfma, r.s); });
 }
 
@@ -772,6 +776,13 @@ int slide_debug_gemm_nt(long long M, int N, int K, const void* A, const void* B,
   return e == hipSuccess ? 0 : SLIDE_EHIP;
 }
 #endif
+
+int slide_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return SLIDE_EINVAL;
+  hipError_t e = launch_calib_copy(dst, src, bytes, (hipStream_t)stream);
+  if (e != hipSuccess) { g_last_hip = (int)e; return SLIDE_EHIP; }
+  return SLIDE_OK;
+}
 
 const char* slide_kernel_name(int id) { return (id >= 0 && id < K_COUNT) ? kKernelNames[id] : nullptr; }
 
