@@ -137,6 +137,7 @@ hipError_t launch_gemm_nt(int dt, const GemmNT& g, bool use_mfma, hipStream_t s)
 
 hipError_t launch_gemm_tn(int dt, const GemmTN& g, bool use_mfma, hipStream_t s) {
   if (g.N1 <= 0 || g.N2 <= 0 || g.slabs <= 0) return hipSuccess;
+  if (dt == DT_BF16 && use_mfma && g.big) return launch_gemm_tn_big(g, s);
   if (dt == DT_BF16 && use_mfma && gemm_tn_mfma_ok(g)) return launch_gemm_tn_mfma(g, s);
   dim3 grid((g.N1 + 63) / 64, (g.N2 + 63) / 64, g.slabs);
   if (dt == DT_F32)

@@ -1,0 +1,324 @@
+// bf16 MFMA weight-gradient GEMM for gfx950, large-M variant: C[N1,N2] = sum_m A[m,N1]^T B[m,N2] (fp32 partials).
+//
+// Same machine balance as the activation GEMMs (what a compute unit can pull out of its L2 bounds the tile from
+// below), so the same shape: one persistent workgroup of 4 wavefronts per compute unit, a 256 x 192 output tile
+// (wavefront: 128 x 96), 64 rows of m per step, operands global -> registers -> LDS with the loads of A two steps
+// and of B one step ahead, MFMA / LDS / global instructions dealt out by hand.  What differs:
+//   * The contraction runs over the ROW index of both operands.  Each thread takes 8 x 8 blocks, transposes them in
+//     registers and writes them to LDS as [column][row chunk], after which fragments are the same 16-byte reads
+//     as in the activation GEMM.
+//   * M (all tokens of the slide) is split into slabs; a work item is (slab, output tile) and writes its partial
+//     tile once, a second kernel adds the slabs in a fixed order (no atomics: results are run-to-run identical).
+//     All tiles of a slab run on ONE XCD at about the same time, so the slab's rows come from HBM once and the
+//     other tiles find them in that XCD's L2 (with tiles spread over XCDs the rows were fetched several times).
+//   * Either operand can play the 256-wide side ("X"), whichever leaves fewer empty tile columns; the output
+//     strides follow.  Column sums of A (the bias gradient) are taken from the registers of the loads.
+#include "slide_internal.h"
+
+#include <type_traits>
+
+namespace sl {
+
+namespace {
+
+constexpr int NXCD = 8;
+constexpr int BX = 256, BY = 192, BK = 64, LDT = BK + 8, NTH = 256;
+constexpr int BYP = 256;                            // Y rows in LDS (wave 3 parks its duplicate block behind the tile)
+constexpr int STAGE = (BX + BYP) * LDT;             // bf16 elements per LDS stage
+constexpr int WBM = 4, WBN = 3;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ u32x4 ldg16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+__device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    int w = c >> 1;
+    unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
+    u32x4 o;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) o[p] = __builtin_amdgcn_perm(in[2 * p + 1][w], in[2 * p][w], sel);
+    out[c] = o;
+  }
+}
+
+// a row of zeros that loads of rows past a slab's end (and of columns past the matrix) are pointed at, so that
+// the loads need no branches (a branch would cut the step into several scheduling regions)
+__device__ __attribute__((aligned(16))) unsigned int g_zero_row[64];
+
+struct TnBig {
+  const bf16* X; long long ldx; int NX;   // 256-wide side
+  const bf16* Y; long long ldy; int NY;   // 192-wide side
+  long long M;
+  float* part; long long sx, sy;          // partial of slab s: part[s * NX * NY + x * sx + y * sy]
+  float* cs_part; int cs_on_x;            // column sums of X (1) or Y (0) per slab, [slabs][N of that side]; may be null
+  int slabs, spx;                         // slabs = 8 * spx: slabs xcd * spx .. xcd * spx + spx - 1 run on XCD xcd
+  int TX, TY;
+};
+
+template <bool LANE_IS_X>
+__global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
+  __shared__ __attribute__((aligned(16))) bf16 ring0[STAGE];
+  __shared__ __attribute__((aligned(16))) bf16 ring1[STAGE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  // loader block: rows mb * 8 .. + 8, columns cb * 8 .. + 8.  The 4 lanes of a quad read 64 contiguous bytes of one
+  // row (the texture path works quad by quad: four rows per quad cost four cache-line accesses); the row
+  // blocks vary next, which keeps the 16-byte LDS stores of neighbouring lanes on different banks.
+  const int mb = (tid >> 2) & 7, cbx = (tid >> 5) * 4 + (tid & 3);
+  const int cby = cbx < BY / 8 ? cbx : cbx - 8;            // wave 3 re-loads blocks of wave 2 (never used)
+  const int yrow = cbx * 8;                                // LDS row of the Y block (>= BY for wave 3)
+  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  const int xcd = blockIdx.x % NXCD, wg = blockIdx.x / NXCD, wgs = gridDim.x / NXCD;
+  const int tiles = g.TX * g.TY;
+  const int items = g.spx * tiles;
+  long long per = (g.M + g.slabs - 1) / g.slabs;
+  per = (per + 2 * BK - 1) / (2 * BK) * (2 * BK);          // whole double steps
+
+  u32x4 rx[2][8], ry[8];
+  for (int idx = wg; idx < items; idx += wgs) {            // uniform for the workgroup
+    const int s = xcd * g.spx + idx / tiles;
+    const int tile = idx % tiles;
+    const int x0 = (tile / g.TY) * BX, y0 = (tile % g.TY) * BY;
+    const long long lo = (long long)s * per;
+    const long long hi = lo + per < g.M ? lo + per : g.M;
+    const int nk = lo < hi ? (int)((hi - lo + 2 * BK - 1) / (2 * BK)) * 2 : 0;
+    // this thread's columns exist?  (N % 8 == 0: a block is inside or outside as a whole)
+    const bool xok = x0 + cbx * 8 < g.NX, yok = y0 + cby * 8 < g.NY;
+    const bf16* zero = reinterpret_cast<const bf16*>(g_zero_row);
+    const bf16* xp = xok ? g.X + (x0 + cbx * 8) : zero;
+    const bf16* yp = yok ? g.Y + (y0 + cby * 8) : zero;
+    const long long ldx = xok ? g.ldx : 0, ldy = yok ? g.ldy : 0;
+    auto issue_x = [&](auto slot, int kt) {
+      constexpr int S = decltype(slot)::value;
+      long long m = lo + (long long)kt * BK + mb * 8;
+      int nv = (int)(hi - m < 8 ? (hi - m < 0 ? 0 : hi - m) : 8);   // rows of this block inside the slab
+      const bf16* p = xp + m * ldx;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) rx[S][r] = ldg16(r < nv ? p + r * ldx : zero);
+    };
+    auto issue_y = [&](int kt) {
+      long long m = lo + (long long)kt * BK + mb * 8;
+      int nv = (int)(hi - m < 8 ? (hi - m < 0 ? 0 : hi - m) : 8);
+      const bf16* p = yp + m * ldy;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) ry[r] = ldg16(r < nv ? p + r * ldy : zero);
+    };
+    const bool cs_x = g.cs_part != nullptr && g.cs_on_x && y0 == 0;
+    const bool cs_y = g.cs_part != nullptr && !g.cs_on_x && x0 == 0;
+    float cs[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) cs[c] = 0.f;
+    auto add_cs_row = [&](const u32x4& v) {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        cs[2 * w] += __uint_as_float(v[w] << 16);
+        cs[2 * w + 1] += __uint_as_float(v[w] & 0xffff0000u);
+      }
+    };
+    // column c of the transposed 8 x 8 block -> one 16-byte LDS row segment
+    auto tr_col = [&](const u32x4 (&in)[8], int c) {
+      int w = c >> 1;
+      unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
+      u32x4 o;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) o[p] = __builtin_amdgcn_perm(in[2 * p + 1][w], in[2 * p][w], sel);
+      return o;
+    };
+    auto stash = [&](auto slot, auto csm) {   // prologue only; the steps below do the same piecewise
+      constexpr int S = decltype(slot)::value;
+      constexpr int CSM = decltype(csm)::value;
+      bf16* st = S ? ring1 : ring0;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        if (CSM == 1) add_cs_row(rx[S][c]);
+        if (CSM == 2) add_cs_row(ry[c]);
+        *reinterpret_cast<u32x4*>(st + (cbx * 8 + c) * LDT + mb * 8) = tr_col(rx[S], c);
+        *reinterpret_cast<u32x4*>(st + (BX + yrow + c) * LDT + mb * 8) = tr_col(ry, c);
+      }
+    };
+
+    f32x16 acc[WBM][WBN];
+#pragma unroll
+    for (int i = 0; i < WBM; ++i)
+#pragma unroll
+      for (int j = 0; j < WBN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // One step, written out in issue order (one wavefront per SIMD: everything that is not an MFMA has to be
+    // issued in the shadow of the 48 MFMAs, and the scheduler is kept from regrouping by a barrier after each
+    // MFMA).  Step kt multiplies out of stage S = kt & 1.  Between the MFMAs: fragment reads of the next slice;
+    // the next step's operands (X: register slot S^1, loaded two steps ago; Y: loaded one step ago) are
+    // transposed column by column and written to stage S^1, which every wave left before the last barrier;
+    // then the registers are re-used for the loads of X three steps and Y two steps ahead.
+    auto step = [&](auto slot, int kt, auto csm) {
+      constexpr int S = decltype(slot)::value;
+      constexpr int N = S ^ 1;
+      constexpr int CSM = decltype(csm)::value;   // 0: no column sums in this item, 1: of X, 2: of Y
+      const bf16* st = S ? ring1 : ring0;
+      bf16* sn = N ? ring1 : ring0;
+      const bf16* xs = st + (wm * (WBM * 32) + frow) * LDT + fk;
+      const bf16* ys = st + BX * LDT + (wn * (WBN * 32) + frow) * LDT + fk;
+      bf16x8 fx[2][WBM], fy[2][WBN];
+#pragma unroll
+      for (int i = 0; i < WBM; ++i) fx[0][i] = *reinterpret_cast<const bf16x8*>(xs + i * 32 * LDT);
+#pragma unroll
+      for (int j = 0; j < WBN; ++j) fy[0][j] = *reinterpret_cast<const bf16x8*>(ys + j * 32 * LDT);
+      const bf16* px = nullptr;
+      const bf16* py = nullptr;
+      int nvx = 0, nvy = 0;
+#pragma unroll
+      for (int n = 0; n < 4 * WBM * WBN; ++n) {
+        constexpr int PER = WBM * WBN;
+        const int ks = n / PER, t = n % PER, i = t / WBN, j = t % WBN;
+        if (ks < 3 && t < WBM + WBN) {   // fragments of slice ks + 1
+          if (t < WBM) fx[(ks + 1) & 1][t] = *reinterpret_cast<const bf16x8*>(xs + t * 32 * LDT + (ks + 1) * 16);
+          else fy[(ks + 1) & 1][t - WBM] = *reinterpret_cast<const bf16x8*>(ys + (t - WBM) * 32 * LDT + (ks + 1) * 16);
+        }
+        acc[i][j] = LANE_IS_X
+                        ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[ks & 1][j], fx[ks & 1][i], acc[i][j], 0, 0, 0)
+                        : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[ks & 1][i], fy[ks & 1][j], acc[i][j], 0, 0, 0);
+        // pieces: 0..7 transpose + store X; 8..15 column sums; 16..23 transpose + store Y; 24..31 load Y (it is
+        // needed again 40 pieces later); 32..39 load X (needed two steps later)
+        if (n < 8) {
+          *reinterpret_cast<u32x4*>(sn + (cbx * 8 + n) * LDT + mb * 8) = tr_col(rx[N], n);
+        } else if (n < 16) {
+          if (CSM == 1) add_cs_row(rx[N][n - 8]);
+          if (CSM == 2) add_cs_row(ry[n - 8]);
+          if (n == 14) {
+            long long m = lo + (long long)(kt + 2) * BK + mb * 8;
+            nvy = (int)(hi - m < 8 ? (hi - m < 0 ? 0 : hi - m) : 8);
+            py = yp + m * ldy;
+          }
+          if (n == 15) {
+            long long m = lo + (long long)(kt + 3) * BK + mb * 8;
+            nvx = (int)(hi - m < 8 ? (hi - m < 0 ? 0 : hi - m) : 8);
+            px = xp + m * ldx;
+          }
+        } else if (n < 24) {
+          *reinterpret_cast<u32x4*>(sn + (BX + yrow + (n - 16)) * LDT + mb * 8) = tr_col(ry, n - 16);
+        } else if (n < 32) {
+          int r = n - 24;
+          ry[r] = ldg16(r < nvy ? py + r * ldy : zero);
+        } else if (n < 40) {
+          int r = n - 32;
+          rx[N][r] = ldg16(r < nvx ? px + r * ldx : zero);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      __syncthreads();
+    };
+
+    auto run = [&](auto csm) {   // one instance per column-sum mode: the step stays free of branches
+      issue_x(std::integral_constant<int, 0>{}, 0);
+      issue_y(0);
+      issue_x(std::integral_constant<int, 1>{}, 1);
+      stash(std::integral_constant<int, 0>{}, csm);
+      issue_x(std::integral_constant<int, 0>{}, 2);
+      issue_y(1);
+      __syncthreads();
+      for (int kt = 0; kt < nk; kt += 2) {       // loads past the slab's end read the zero row
+        step(std::integral_constant<int, 0>{}, kt, csm);
+        step(std::integral_constant<int, 1>{}, kt + 1, csm);
+      }
+    };
+    if (nk > 0) {
+      if (cs_x) run(std::integral_constant<int, 1>{});
+      else if (cs_y) run(std::integral_constant<int, 2>{});
+      else run(std::integral_constant<int, 0>{});
+    }
+    // (the last step stashed zero rows into stage 0 and passed the barrier: both stages are free again)
+
+    // column sums: 8 row blocks per column block -> one value per column
+    if (cs_x || cs_y) {
+      float* red = reinterpret_cast<float*>(ring1);   // [8][256]
+      int cb = cs_x ? cbx : cby;
+      bool mine = cs_x || tid < BY;                   // wave 3 holds duplicates of Y blocks
+      if (mine) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) red[mb * 256 + cb * 8 + c] = cs[c];
+      }
+      __syncthreads();
+      int ncol = cs_x ? BX : BY, c0 = cs_x ? x0 : y0, nn = cs_x ? g.NX : g.NY;
+      if (tid < ncol && c0 + tid < nn) {
+        float a = 0.f;
+#pragma unroll
+        for (int m = 0; m < 8; ++m) a += red[m * 256 + tid];
+        g.cs_part[(size_t)s * nn + c0 + tid] = a;
+      }
+      __syncthreads();
+    }
+
+    float* P = g.part + (size_t)s * g.NX * g.NY;
+#pragma unroll
+    for (int i = 0; i < WBM; ++i)
+#pragma unroll
+      for (int j = 0; j < WBN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int inner = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), outer = lane & 31;
+          int x = x0 + wm * (WBM * 32) + i * 32 + (LANE_IS_X ? outer : inner);
+          int y = y0 + wn * (WBN * 32) + j * 32 + (LANE_IS_X ? inner : outer);
+          if (x < g.NX && y < g.NY) P[x * g.sx + y * g.sy] = acc[i][j][r];
+        }
+  }
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+long long padded(int n1, int n2) {   // cells of the tile grid with n1 on the 256 side
+  return (long long)((n1 + BX - 1) / BX * BX) * ((n2 + BY - 1) / BY * BY);
+}
+
+}  // namespace
+
+// Shapes this kernel takes: identity row maps, enough rows.  Returns the number of slabs it will use (0: not taken).
+int gemm_tn_big_slabs(const GemmTN& g, int max_slabs) {
+  if (g.amap.g2 != 0 || g.bmap.g2 != 0 || g.M < 65536) return 0;
+  if (g.N1 % 8 || g.N2 % 8 || g.lda % 8 || g.ldb % 8 || !aligned16(g.A) || !aligned16(g.B)) return 0;
+  if ((long long)g.N1 * g.N2 >= (1LL << 31)) return 0;
+  bool a_is_x = padded(g.N1, g.N2) <= padded(g.N2, g.N1);
+  int nx = a_is_x ? g.N1 : g.N2, ny = a_is_x ? g.N2 : g.N1;
+  int tiles = ((nx + BX - 1) / BX) * ((ny + BY - 1) / BY);
+  // per XCD: spx slabs x tiles items over 32 workgroups; prefer a whole number of rounds
+  int spx = 8;
+  for (int c = 4; c <= 8; ++c)
+    if ((c * tiles) % 32 == 0) { spx = c; break; }
+  while (spx > 1 && 8 * spx > max_slabs) --spx;
+  return 8 * spx;
+}
+
+hipError_t launch_gemm_tn_big(const GemmTN& g, hipStream_t s) {
+  static int cus = 0;
+  if (!cus) {
+    hipError_t e;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+    if ((e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
+    cus = prop.multiProcessorCount / NXCD * NXCD;
+    if (cus < NXCD) cus = NXCD;
+  }
+  bool a_is_x = padded(g.N1, g.N2) <= padded(g.N2, g.N1);
+  TnBig t{};
+  t.M = g.M; t.part = g.part; t.cs_part = g.cs_part; t.slabs = g.slabs; t.spx = g.slabs / NXCD;
+  if (a_is_x) {
+    t.X = (const bf16*)g.A; t.ldx = g.lda; t.NX = g.N1; t.Y = (const bf16*)g.B; t.ldy = g.ldb; t.NY = g.N2;
+    t.sx = g.N2; t.sy = 1; t.cs_on_x = 1;
+  } else {
+    t.X = (const bf16*)g.B; t.ldx = g.ldb; t.NX = g.N2; t.Y = (const bf16*)g.A; t.ldy = g.lda; t.NY = g.N1;
+    t.sx = 1; t.sy = g.N2; t.cs_on_x = 0;
+  }
+  t.TX = (t.NX + BX - 1) / BX; t.TY = (t.NY + BY - 1) / BY;
+  int items_per_xcd = t.spx * t.TX * t.TY;
+  int per_xcd = cus / NXCD < items_per_xcd ? cus / NXCD : items_per_xcd;
+  dim3 grid((unsigned)(per_xcd * NXCD));
+  // the lanes of a store run along the output's contiguous index: y when X = A (row-major [N1][N2]), x otherwise
+  if (a_is_x) hipLaunchKernelGGL(gemm_tn_big_k<false>, grid, dim3(NTH), 0, s, t);
+  else hipLaunchKernelGGL(gemm_tn_big_k<true>, grid, dim3(NTH), 0, s, t);
+  return hipGetLastError();
+}
+
+}  // namespace sl

@@ -124,8 +124,11 @@ struct GemmTN {
   const void* B; long long ldb; RowMap bmap;  // T [M, N2]
   long long M; int N1, N2;
   float* part; int slabs;
-  float* cs_part;  // optional: column sums of A per slab, [slabs][N1] (only the MFMA kernel fills it)
+  float* cs_part;  // optional: column sums of A per slab, [slabs][N1] (only the MFMA kernels fill it)
+  int big;         // use the large-M kernel (slabs was chosen by gemm_tn_big_slabs)
 };
+int gemm_tn_big_slabs(const GemmTN& g, int max_slabs);   // 0: the large-M kernel does not take this problem
+hipError_t launch_gemm_tn_big(const GemmTN& g, hipStream_t s);
 
 // All launchers enqueue on `s` and return the launch status.
 hipError_t launch_gemm_nt(int dt, const GemmNT& g, bool use_mfma, hipStream_t s);

@@ -127,7 +127,7 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   size_t M = (size_t)nn * c->T;
   size_t maxcols = (size_t)(c->F > 3 * D ? c->F : 3 * D);
   size_t tokcols = (size_t)c->T * D;
-  y.w_wpart = take((size_t)32 * c->max_w * 4);
+  y.w_wpart = take((size_t)64 * c->max_w * 4);
   y.w_cpart = take((size_t)128 * (maxcols > tokcols ? maxcols : tokcols) * 4);
   y.w_lnpart = take((size_t)1024 * 2 * D * 4);
   y.enc_begin = cur;
@@ -239,8 +239,11 @@ void gemm_tn(Run& r, const void* A, long long lda, RowMap amap, const void* B, l
   int dt = dt_override >= 0 ? dt_override : r.c->dt;
   g.A = A; g.lda = lda; g.amap = amap; g.B = B; g.ldb = ldb; g.bmap = bmap; g.M = M; g.N1 = N1; g.N2 = N2;
   g.part = part;
-  g.slabs = gemm_tn_pick_slabs(M, N1, N2, 32);
   g.cs_part = nullptr;
+  g.big = 0;
+  int bs = (dt == DT_BF16 && r.c->use_mfma && !getenv("SLIDE_TN_SMALL")) ? gemm_tn_big_slabs(g, 64) : 0;
+  if (bs) { g.slabs = bs; g.big = 1; }
+  else g.slabs = gemm_tn_pick_slabs(M, N1, N2, 32);
   bool fused = bias_out && gemm_tn_fuses_colsum(dt, g, r.c->use_mfma);
   if (fused) g.cs_part = cpart;
   if (bias_out && !fused) colsum(r, dt, A, lda, amap, M, N1, cpart, bias_out, accumulate);

@@ -32,7 +32,7 @@ def _upload_pixels(torch, cfg, N, seed, dev):
     return px
 
 
-@pytest.mark.parametrize("name,n_sample,n_chunks", [("medium", 6, 4), ("large", 6, 4), ("full", 3, 2)])
+@pytest.mark.parametrize("name,n_sample,n_chunks", [("medium", 6, 8), ("large", 6, 4), ("full", 3, 2)])
 def test_fullsize_links(name, n_sample, n_chunks):
     import torch
     from oracle import slide_oracle as so
@@ -125,7 +125,9 @@ def test_fullsize_links(name, n_sample, n_chunks):
     print("link 3 (chunk backward):", sorted(e3.items(), key=lambda kv: -kv[1])[:5], flush=True)
     assert all(v <= BF16_TOL for v in e3.values()), {k: v for k, v in e3.items() if v > BF16_TOL}
 
-    # ---- link 4: whole-slide encoder gradients == sum over tile chunks (GPU vs GPU, same G rows)
+    # ---- link 4: whole-slide encoder gradients == sum over tile chunks (GPU vs GPU, same G rows).
+    # At the medium workload a chunk has fewer token rows than the large-M weight-gradient kernel takes, so
+    # this also holds that kernel (whole slide) against the small-tile one (chunks; oracle-checked in link 3).
     per = N // n_chunks
     for c in range(n_chunks):
         lo, hi = c * per, (N if c == n_chunks - 1 else (c + 1) * per)
