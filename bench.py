@@ -216,10 +216,16 @@ def main():
     tiles_per_s = N * a.steps / dt
     mflops = model_flops_per_tile(cfg)
     mfu = tiles_per_s * mflops / PEAK["mfma_bf16"]
-    achieved = (k_flops / (k_ms * 1e-3)) / 1e12 if k_ms > 0 else 0.0   # TFLOP/s of the profiled kernel family
     tr = load_traffic(a.workload, a.prof_kernel) if not a.tiles else None
-    roof = {"bound": "mfma", "kernel": a.prof_kernel, "achieved": round(achieved, 2), "peak": 2500.0,
-            "unit": "TFLOP/s", "frac": round(achieved / 2500.0, 4),
+    hbm_bound = a.prof_kernel in ("ln_fwd", "ln_bwd", "pool_fwd", "pool_bwd", "colsum", "elementwise")
+    if hbm_bound:   # streaming kernels: algorithmic bytes over time against the HBM peak
+        achieved = (k_bytes / (k_ms * 1e-3)) / 1e9 if k_ms > 0 else 0.0
+        peak, unit = PEAK["hbm"] / 1e9, "GB/s"
+    else:           # contractions: FLOP/s of the kernel family against the dense bf16 MFMA peak
+        achieved = (k_flops / (k_ms * 1e-3)) / 1e12 if k_ms > 0 else 0.0
+        peak, unit = PEAK["mfma_bf16"] / 1e12, "TFLOP/s"
+    roof = {"bound": "hbm" if hbm_bound else "mfma", "kernel": a.prof_kernel, "achieved": round(achieved, 2), "peak": peak,
+            "unit": unit, "frac": round(achieved / peak, 4),
             "traffic": None if tr is None else tr["hbm_bytes_per_launch"],
             "algorithmic_bytes_per_launch": round(k_bytes / max(k_n, 1)),
             "launches": k_n, "avg_launch_ms": round(k_ms / max(k_n, 1), 4),

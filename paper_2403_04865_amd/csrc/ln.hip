@@ -197,9 +197,201 @@ bool ln_bwd_fast(dim3 grid, const void* x, long long xs, const void* dy, long lo
   return false;
 }
 
+
+// ---- bf16 rows, 16 lanes per row: D == 128 * NP, every lane owns NP chunks of 8 columns (16-byte accesses), a
+// wavefront works on four rows at a time.  LayerNorm is pure streaming: what matters is how many bytes a
+// wavefront keeps in flight, and one row of 2 * D bytes per wavefront (4-byte accesses) left HBM mostly idle.
+typedef unsigned int lnu4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void ln_ld8(const bf16* p, float (&v)[8]) {
+  lnu4 t = *reinterpret_cast<const lnu4*>(p);
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    v[2 * w] = __uint_as_float(t[w] << 16);
+    v[2 * w + 1] = __uint_as_float(t[w] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void ln_st8(bf16* p, const float (&v)[8]) {
+  typedef float lnf2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 lnb2 __attribute__((ext_vector_type(2)));
+  lnu4 r;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    lnf2 f = {v[2 * w], v[2 * w + 1]};
+    lnb2 h = __builtin_convertvector(f, lnb2);
+    r[w] = __builtin_bit_cast(unsigned, h);
+  }
+  *reinterpret_cast<lnu4*>(p) = r;
+}
+__device__ __forceinline__ float sum16(float v) {   // over the 16 lanes of a row group
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <int NP>
+__global__ void __launch_bounds__(256) ln_fwd_row16_k(const bf16* __restrict__ x, long long xs,
+                                                      const float* __restrict__ gam, const float* __restrict__ bet,
+                                                      bf16* __restrict__ out, long long os, long long rows, float eps) {
+  constexpr int D = 128 * NP;
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l16 = lane & 15, grp = lane >> 4;
+  long long r = ((long long)blockIdx.x * 4 + w) * 4 + grp;
+  bool ok = r < rows;
+  const bf16* xr = x + (ok ? r : rows - 1) * xs;
+  float v[NP][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int k = 0; k < NP; ++k) {
+    ln_ld8(xr + (l16 + 16 * k) * 8, v[k]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sum += v[k][e];
+  }
+  float mean = sum16(sum) * (1.0f / D);
+  float sq = 0.f;
+#pragma unroll
+  for (int k = 0; k < NP; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      v[k][e] -= mean;
+      sq += v[k][e] * v[k][e];
+    }
+  float rstd = 1.0f / sqrtf(sum16(sq) * (1.0f / D) + eps);
+  if (!ok) return;
+  bf16* o = out + r * os;
+#pragma unroll
+  for (int k = 0; k < NP; ++k) {
+    int c = (l16 + 16 * k) * 8;
+    float4 g0 = *reinterpret_cast<const float4*>(gam + c), g1 = *reinterpret_cast<const float4*>(gam + c + 4);
+    float4 b0 = *reinterpret_cast<const float4*>(bet + c), b1 = *reinterpret_cast<const float4*>(bet + c + 4);
+    float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w}, bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+    float y[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) y[e] = v[k][e] * rstd * gg[e] + bb[e];
+    ln_st8(o + c, y);
+  }
+}
+
+// dx = (dres ? dres : 0) + rstd * (dxh - mean(dxh) - xh * mean(dxh * xh)), dxh = dy * gamma;
+// dgamma / dbeta partials of the workgroup -> part[block][0][D], part[block][1][D]
+template <int NP>
+__global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x, long long xs,
+                                                      const bf16* __restrict__ dy, long long dys,
+                                                      const float* __restrict__ gam, const bf16* __restrict__ dres,
+                                                      bf16* __restrict__ dxo, long long os, long long rows, float eps,
+                                                      float* __restrict__ part) {
+  constexpr int D = 128 * NP;
+  __shared__ float red[4 * 2 * D];
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l16 = lane & 15, grp = lane >> 4;
+  float dg[NP][8], db[NP][8], g[NP][8];
+#pragma unroll
+  for (int k = 0; k < NP; ++k) {
+    int c = (l16 + 16 * k) * 8;
+    float4 g0 = *reinterpret_cast<const float4*>(gam + c), g1 = *reinterpret_cast<const float4*>(gam + c + 4);
+    g[k][0] = g0.x; g[k][1] = g0.y; g[k][2] = g0.z; g[k][3] = g0.w; g[k][4] = g1.x; g[k][5] = g1.y; g[k][6] = g1.z; g[k][7] = g1.w;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { dg[k][e] = 0.f; db[k][e] = 0.f; }
+  }
+  long long nsets = (rows + 3) / 4;   // sets of four rows; a wavefront takes every (gridDim * 4)-th set
+  for (long long set = (long long)blockIdx.x * 4 + w; set < nsets; set += (long long)gridDim.x * 4) {
+    long long r = set * 4 + grp;
+    bool ok = r < rows;
+    float okf = ok ? 1.f : 0.f;
+    long long rc = ok ? r : rows - 1;
+    const bf16* xr = x + rc * xs;
+    const bf16* dyr = dy + rc * dys;
+    float v[NP][8], d[NP][8];
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+      int c = (l16 + 16 * k) * 8;
+      ln_ld8(xr + c, v[k]);
+      ln_ld8(dyr + c, d[k]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += v[k][e];
+    }
+    float mean = sum16(sum) * (1.0f / D);
+    float sq = 0.f;
+#pragma unroll
+    for (int k = 0; k < NP; ++k)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        v[k][e] -= mean;
+        sq += v[k][e] * v[k][e];
+      }
+    float rstd = 1.0f / sqrtf(sum16(sq) * (1.0f / D) + eps);
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int k = 0; k < NP; ++k)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        v[k][e] *= rstd;
+        float dd = d[k][e] * okf;     // rows past the end contribute nothing
+        dg[k][e] += dd * v[k][e];
+        db[k][e] += dd;
+        d[k][e] *= g[k][e];
+        s1 += d[k][e];
+        s2 += d[k][e] * v[k][e];
+      }
+    s1 = sum16(s1) * (1.0f / D);
+    s2 = sum16(s2) * (1.0f / D);
+    if (ok) {
+#pragma unroll
+      for (int k = 0; k < NP; ++k) {
+        int c = (l16 + 16 * k) * 8;
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = rstd * (d[k][e] - s1 - v[k][e] * s2);
+        if (dres) {
+          float t[8];
+          ln_ld8(dres + r * os + c, t);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] += t[e];
+        }
+        ln_st8(dxo + r * os + c, o);
+      }
+    }
+  }
+  // the four row groups of a wavefront, then the four wavefronts
+#pragma unroll
+  for (int k = 0; k < NP; ++k)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      dg[k][e] += __shfl_xor(dg[k][e], 16, 64);
+      dg[k][e] += __shfl_xor(dg[k][e], 32, 64);
+      db[k][e] += __shfl_xor(db[k][e], 16, 64);
+      db[k][e] += __shfl_xor(db[k][e], 32, 64);
+    }
+  if (grp == 0) {
+#pragma unroll
+    for (int k = 0; k < NP; ++k)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        int c = (l16 + 16 * k) * 8 + e;
+        red[(w * 2 + 0) * D + c] = dg[k][e];
+        red[(w * 2 + 1) * D + c] = db[k][e];
+      }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 2 * D; i += 256) {
+    float a = (red[0 * 2 * D + i] + red[1 * 2 * D + i]) + (red[2 * 2 * D + i] + red[3 * 2 * D + i]);
+    part[(size_t)blockIdx.x * 2 * D + i] = a;
+  }
+}
+
+static bool ln_row16_ok(const void* a, const void* b, const void* c, long long s1, long long s2, long long s3, int D) {
+  auto al = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  return sizeof(rs_bf16path_t) == 2 && (D == 384 || D == 768) && al(a) && al(b) && al(c) && s1 % 8 == 0 && s2 % 8 == 0 &&
+         s3 % 8 == 0;
+}
+
 hipError_t launch_ln_fwd(int dt, const void* x, long long x_stride, const float* gam, const float* bet, void* out,
                          long long out_stride, long long rows, int D, float eps, bool out_f32, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
+  if (dt == DT_BF16 && !out_f32 && ln_row16_ok(x, out, gam, x_stride, out_stride, 0, D) && ((uintptr_t)bet & 15) == 0) {
+    dim3 g16((unsigned)((rows + 15) / 16));
+    if (D == 384) hipLaunchKernelGGL(ln_fwd_row16_k<3>, g16, dim3(256), 0, s, (const bf16*)x, x_stride, gam, bet, (bf16*)out, out_stride, rows, eps);
+    else hipLaunchKernelGGL(ln_fwd_row16_k<6>, g16, dim3(256), 0, s, (const bf16*)x, x_stride, gam, bet, (bf16*)out, out_stride, rows, eps);
+    return hipGetLastError();
+  }
   dim3 grid((unsigned)((rows + 3) / 4));
   bool fast;
   if (dt != DT_F32 && out_f32) fast = ln_fwd_fast<rs_bf16path_t, float>(x, x_stride, gam, bet, out, out_stride, rows, D, eps, s);
@@ -308,6 +500,12 @@ hipError_t launch_ln_bwd(int dt, const void* x, long long x_stride, const void* 
   if (rows <= 0) return hipSuccess;
   dim3 grid(ln_bwd_slabs(rows));
   size_t lds = (size_t)4 * 2 * D * sizeof(float);
+  if (dt == DT_BF16 && !dy_f32 && ln_row16_ok(x, dy, dx_out, x_stride, dy_stride, o_stride, D) &&
+      ((uintptr_t)gam & 15) == 0 && ((uintptr_t)dres & 15) == 0) {
+    if (D == 384) hipLaunchKernelGGL(ln_bwd_row16_k<3>, grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part);
+    else hipLaunchKernelGGL(ln_bwd_row16_k<6>, grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part);
+    return hipGetLastError();
+  }
   {
     constexpr bool same = sizeof(rs_bf16path_t) == sizeof(bf16);
     bool fast;
