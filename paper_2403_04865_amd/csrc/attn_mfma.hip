@@ -56,6 +56,22 @@ __device__ __forceinline__ bf16x8 frag_t(const bf16* Xt, int ldt, int d, int j0,
   return as_bf16x8(v);
 }
 
+// A operand whose contraction index runs along the ROWS of a row-major LDS matrix X[row][col] (row stride ld):
+// lane l gets column c0 + l % 32 and the rows j0 + 4*h2 + {0..3}, j0 + 8 + 4*h2 + {0..3} (h2 = l / 32), the order
+// of accumulator registers 8t..8t+7.  Two LDS transpose reads (ds_read_b64_tr_b16): within a group of 16
+// lanes, lane s addresses 4 consecutive columns of row s / 4 and receives, for column s of the group's 16, the
+// four rows.  No transposed copy of X is kept.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x8 frag_tr(const bf16* X, int ld, int c0, int j0, int lane) {
+  int g = lane >> 4, s = lane & 15;
+  const bf16* p = X + (j0 + 4 * (g >> 1) + (s >> 2)) * ld + c0 + 16 * (g & 1) + (s & 3) * 4;
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 8 * ld));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
 // copy rows [0,T) x DH of a row-major global matrix (row stride gs) into LDS row-major [TP][DH+8]
 template <int DH>
 __device__ __forceinline__ void load_rm(const bf16* __restrict__ g, long long gs, int T, int TP, bf16* dst) {
@@ -99,7 +115,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
-  bf16* Vt = Ks + TP * LDR;                  // [DH][LDT]
+  bf16* Vs = Ks + TP * LDR;                  // [TP][LDR]
   // workgroup ids are dealt round-robin to the 8 XCDs: the heads of one tile go to one XCD, next to each other
   // in time, so the neighbouring 128-byte head slices of its token rows meet in one L2
   int h = (blockIdx.x / 8) % H;
@@ -109,7 +125,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict
   long long gs = 3LL * D;
   const bf16* base = qkv + tile * T * gs + h * DH;
   load_rm<DH>(base + D, gs, T, TP, Ks);
-  load_tr<DH>(base + 2 * D, gs, T, TP, Vt);
+  load_rm<DH>(base + 2 * D, gs, T, TP, Vs);
   __syncthreads();
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
@@ -172,7 +188,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict
         bf16x8 pb = pack8(pv);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          bf16x8 a = frag_t(Vt, LDT, d * 32 + li, kb * 32 + 16 * t, h2);
+          bf16x8 a = frag_tr(Vs, LDR, d * 32, kb * 32 + 16 * t, lane);
           o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[d], 0, 0, 0);
         }
       }
@@ -206,7 +222,6 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restri
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
   bf16* Vs = Ks + TP * LDR;                  // [TP][LDR]
-  bf16* Kt = Vs + TP * LDR;                  // [DH][LDT]
   // workgroup ids are dealt round-robin to the 8 XCDs: the heads of one tile go to one XCD, next to each other
   // in time, so the neighbouring 128-byte head slices of its token rows meet in one L2
   int h = (blockIdx.x / 8) % H;
@@ -217,7 +232,6 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restri
   const bf16* base = qkv + tile * T * gs + h * DH;
   load_rm<DH>(base + D, gs, T, TP, Ks);
   load_rm<DH>(base + 2 * D, gs, T, TP, Vs);
-  load_tr<DH>(base + D, gs, T, TP, Kt);
   __syncthreads();
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
@@ -269,7 +283,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restri
         bf16x8 db = pack8(ds + 8 * t);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          bf16x8 a = frag_t(Kt, LDT, d * 32 + li, kb * 32 + 16 * t, h2);
+          bf16x8 a = frag_tr(Ks, LDR, d * 32, kb * 32 + 16 * t, lane);
           dq[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, db, dq[d], 0, 0, 0);
         }
       }
@@ -293,16 +307,14 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restri
 // backward, pass K: dK, dV
 // --------------------------------------------------------------------------------------------
 template <int DH, int NB>
-__global__ void __launch_bounds__(256) attn_bwd_k_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
+__global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
                                                          bf16* __restrict__ dqkv, int T, int H, long long ntiles) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Qs = reinterpret_cast<bf16*>(smem);   // [TP][LDR]
   bf16* Gs = Qs + TP * LDR;                   // [TP][LDR]  dO
-  bf16* Qt = Gs + TP * LDR;                   // [DH][LDT]
-  bf16* Gt = Qt + DH * LDT;                   // [DH][LDT]
-  float* ls = reinterpret_cast<float*>(Gt + DH * LDT);  // [TP] lse * log2(e), +inf on padding rows
+  float* ls = reinterpret_cast<float*>(Gs + TP * LDR);  // [TP] lse * log2(e), +inf on padding rows
   float* dl = ls + TP;                                  // [TP] delta
   // workgroup ids are dealt round-robin to the 8 XCDs: the heads of one tile go to one XCD, next to each other
   // in time, so the neighbouring 128-byte head slices of its token rows meet in one L2
@@ -316,8 +328,6 @@ __global__ void __launch_bounds__(256) attn_bwd_k_mfma_k(const bf16* __restrict_
   const bf16* obase = O + tile * T * (long long)D + h * DH;
   load_rm<DH>(base, gs, T, TP, Qs);
   load_rm<DH>(gbase, D, T, TP, Gs);
-  load_tr<DH>(base, gs, T, TP, Qt);
-  load_tr<DH>(gbase, D, T, TP, Gt);
   for (int i = threadIdx.x; i < TP; i += blockDim.x) {
     float d = 0.f, lv = INFINITY;
     if (i < T) {
@@ -377,9 +387,9 @@ __global__ void __launch_bounds__(256) attn_bwd_k_mfma_k(const bf16* __restrict_
         bf16x8 db = pack8(ds + 8 * t);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          bf16x8 ag = frag_t(Gt, LDT, d * 32 + li, qb * 32 + 16 * t, h2);
+          bf16x8 ag = frag_tr(Gs, LDR, d * 32, qb * 32 + 16 * t, lane);
           dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, pb, dv[d], 0, 0, 0);
-          bf16x8 aq = frag_t(Qt, LDT, d * 32 + li, qb * 32 + 16 * t, h2);
+          bf16x8 aq = frag_tr(Qs, LDR, d * 32, qb * 32 + 16 * t, lane);
           dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, db, dk[d], 0, 0, 0);
         }
       }
@@ -404,10 +414,10 @@ __global__ void __launch_bounds__(256) attn_bwd_k_mfma_k(const bf16* __restrict_
   }
 }
 
-template <int DH, int NB> constexpr size_t fwd_lds() { return ((size_t)NB * 32 * (DH + 8) + (size_t)DH * (NB * 32 + 8)) * 2; }
-template <int DH, int NB> constexpr size_t bq_lds() { return ((size_t)2 * NB * 32 * (DH + 8) + (size_t)DH * (NB * 32 + 8)) * 2; }
+template <int DH, int NB> constexpr size_t fwd_lds() { return (size_t)2 * NB * 32 * (DH + 8) * 2; }
+template <int DH, int NB> constexpr size_t bq_lds() { return (size_t)2 * NB * 32 * (DH + 8) * 2; }
 template <int DH, int NB> constexpr size_t bk_lds() {
-  return ((size_t)2 * NB * 32 * (DH + 8) + (size_t)2 * DH * (NB * 32 + 8)) * 2 + (size_t)2 * NB * 32 * 4;
+  return (size_t)2 * NB * 32 * (DH + 8) * 2 + (size_t)2 * NB * 32 * 4;
 }
 
 template <typename K>
