@@ -4,9 +4,10 @@
 // below), so the same shape: one persistent workgroup of 4 wavefronts per compute unit, a 256 x 192 output tile
 // (wavefront: 128 x 96), 64 rows of m per step, operands global -> registers -> LDS with the loads of A two steps
 // and of B one step ahead, MFMA / LDS / global instructions dealt out by hand.  What differs:
-//   * The contraction runs over the ROW index of both operands.  Each thread takes 8 x 8 blocks, transposes them in
-//     registers and writes them to LDS as [column][row chunk], after which fragments are the same 16-byte reads
-//     as in the activation GEMM.
+//   * The contraction runs over the ROW index of both operands.  The 64-row slices go to LDS as they are
+//     (row-major, 16-byte stores) and the MFMA fragments, which need 8 consecutive contraction indices per
+//     lane, are read with LDS transpose reads (ds_read_b64_tr_b16: a group of 16 lanes addresses a 4-row x
+//     16-column patch and every lane receives one column of it).  No transposition in registers.
 //   * M (all tokens of the slide) is split into slabs; a work item is (slab, output tile) and writes its partial
 //     tile once, a second kernel adds the slabs in a fixed order (no atomics: results are run-to-run identical).
 //     All tiles of a slab run on ONE XCD at about the same time, so the slab's rows come from HBM once and the
@@ -22,25 +23,28 @@ namespace sl {
 namespace {
 
 constexpr int NXCD = 8;
-constexpr int BX = 256, BY = 192, BK = 64, LDT = BK + 8, NTH = 256;
-constexpr int BYP = 256;                            // Y rows in LDS (wave 3 parks its duplicate block behind the tile)
-constexpr int STAGE = (BX + BYP) * LDT;             // bf16 elements per LDS stage
+constexpr int BX = 256, BY = 192, BK = 64, NTH = 256;
+constexpr int BYP = 256;                            // Y columns in LDS (lanes past the tile park duplicates behind it)
+constexpr int LDW = BX + BYP + 8;                   // LDS row: 256 X columns, 256 Y columns, pad
+constexpr int STAGE = BK * LDW;                     // bf16 elements per LDS stage
 constexpr int WBM = 4, WBN = 3;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ u32x4 ldg16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
 
-__device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
-#pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    int w = c >> 1;
-    unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
-    u32x4 o;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) o[p] = __builtin_amdgcn_perm(in[2 * p + 1][w], in[2 * p][w], sel);
-    out[c] = o;
-  }
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// MFMA operand from a row-major LDS slice S[k][col] (row stride LDW): lane l gets column c0 + l % 32 and the
+// contraction indices k0 + 8 * (l / 32) + {0..7}
+__device__ __forceinline__ bf16x8 frag_tr(const bf16* S, int c0, int k0, int lane) {
+  int g = lane >> 4, q = lane & 15;
+  const bf16* p = S + (k0 + 8 * (g >> 1) + (q >> 2)) * LDW + c0 + 16 * (g & 1) + (q & 3) * 4;
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * LDW));
+  s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
 }
 
 // a row of zeros that loads of rows past a slab's end (and of columns past the matrix) are pointed at, so that
@@ -63,13 +67,10 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
   __shared__ __attribute__((aligned(16))) bf16 ring1[STAGE];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
-  // loader block: rows mb * 8 .. + 8, columns cb * 8 .. + 8.  The 4 lanes of a quad read 64 contiguous bytes of one
-  // row (the texture path works quad by quad: four rows per quad cost four cache-line accesses); the row
-  // blocks vary next, which keeps the 16-byte LDS stores of neighbouring lanes on different banks.
-  const int mb = (tid >> 2) & 7, cbx = (tid >> 5) * 4 + (tid & 3);
-  const int cby = cbx < BY / 8 ? cbx : cbx - 8;            // wave 3 re-loads blocks of wave 2 (never used)
-  const int yrow = cbx * 8;                                // LDS row of the Y block (>= BY for wave 3)
-  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  // loader: 32 lanes cover 512 contiguous bytes of one row; thread t takes 16-byte chunk t % 32 of rows t / 32 + 8 i.
+  // Y has 24 chunks per row: lanes 24..31 re-load chunk 23 and park it behind the tile (no divergent code).
+  const int lr = tid >> 5, lc = tid & 31;
+  const int lcy = lc < BY / 8 ? lc : BY / 8 - 1;
   const int xcd = blockIdx.x % NXCD, wg = blockIdx.x / NXCD, wgs = gridDim.x / NXCD;
   const int tiles = g.TX * g.TY;
   const int items = g.spx * tiles;
@@ -84,26 +85,25 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
     const long long lo = (long long)s * per;
     const long long hi = lo + per < g.M ? lo + per : g.M;
     const int nk = lo < hi ? (int)((hi - lo + 2 * BK - 1) / (2 * BK)) * 2 : 0;
-    // this thread's columns exist?  (N % 8 == 0: a block is inside or outside as a whole)
-    const bool xok = x0 + cbx * 8 < g.NX, yok = y0 + cby * 8 < g.NY;
+    // this thread's columns exist?  (N % 8 == 0: a chunk is inside or outside as a whole)
+    const bool xok = x0 + lc * 8 < g.NX, yok = y0 + lcy * 8 < g.NY;
     const bf16* zero = reinterpret_cast<const bf16*>(g_zero_row);
-    const bf16* xp = xok ? g.X + (x0 + cbx * 8) : zero;
-    const bf16* yp = yok ? g.Y + (y0 + cby * 8) : zero;
+    const bf16* xp = xok ? g.X + (x0 + lc * 8) : zero;
+    const bf16* yp = yok ? g.Y + (y0 + lcy * 8) : zero;
     const long long ldx = xok ? g.ldx : 0, ldy = yok ? g.ldy : 0;
+    // rows of step kt this thread loads: lo + kt * 64 + lr + 8 i; rows past the slab's end read the zero row
     auto issue_x = [&](auto slot, int kt) {
       constexpr int S = decltype(slot)::value;
-      long long m = lo + (long long)kt * BK + mb * 8;
-      int nv = (int)(hi - m < 8 ? (hi - m < 0 ? 0 : hi - m) : 8);   // rows of this block inside the slab
+      long long m = lo + (long long)kt * BK + lr;
       const bf16* p = xp + m * ldx;
 #pragma unroll
-      for (int r = 0; r < 8; ++r) rx[S][r] = ldg16(r < nv ? p + r * ldx : zero);
+      for (int i = 0; i < 8; ++i) rx[S][i] = ldg16(m + 8 * i < hi ? p + 8 * i * ldx : zero);
     };
     auto issue_y = [&](int kt) {
-      long long m = lo + (long long)kt * BK + mb * 8;
-      int nv = (int)(hi - m < 8 ? (hi - m < 0 ? 0 : hi - m) : 8);
+      long long m = lo + (long long)kt * BK + lr;
       const bf16* p = yp + m * ldy;
 #pragma unroll
-      for (int r = 0; r < 8; ++r) ry[r] = ldg16(r < nv ? p + r * ldy : zero);
+      for (int i = 0; i < 8; ++i) ry[i] = ldg16(m + 8 * i < hi ? p + 8 * i * ldy : zero);
     };
     const bool cs_x = g.cs_part != nullptr && g.cs_on_x && y0 == 0;
     const bool cs_y = g.cs_part != nullptr && !g.cs_on_x && x0 == 0;
@@ -117,25 +117,17 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
         cs[2 * w + 1] += __uint_as_float(v[w] & 0xffff0000u);
       }
     };
-    // column c of the transposed 8 x 8 block -> one 16-byte LDS row segment
-    auto tr_col = [&](const u32x4 (&in)[8], int c) {
-      int w = c >> 1;
-      unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
-      u32x4 o;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) o[p] = __builtin_amdgcn_perm(in[2 * p + 1][w], in[2 * p][w], sel);
-      return o;
-    };
+    const int sx_off = lr * LDW + lc * 8, sy_off = lr * LDW + BX + lc * 8;
     auto stash = [&](auto slot, auto csm) {   // prologue only; the steps below do the same piecewise
       constexpr int S = decltype(slot)::value;
       constexpr int CSM = decltype(csm)::value;
       bf16* st = S ? ring1 : ring0;
 #pragma unroll
-      for (int c = 0; c < 8; ++c) {
-        if (CSM == 1) add_cs_row(rx[S][c]);
-        if (CSM == 2) add_cs_row(ry[c]);
-        *reinterpret_cast<u32x4*>(st + (cbx * 8 + c) * LDT + mb * 8) = tr_col(rx[S], c);
-        *reinterpret_cast<u32x4*>(st + (BX + yrow + c) * LDT + mb * 8) = tr_col(ry, c);
+      for (int i = 0; i < 8; ++i) {
+        if (CSM == 1) add_cs_row(rx[S][i]);
+        if (CSM == 2) add_cs_row(ry[i]);
+        *reinterpret_cast<u32x4*>(st + sx_off + 8 * i * LDW) = rx[S][i];
+        *reinterpret_cast<u32x4*>(st + sy_off + 8 * i * LDW) = ry[i];
       }
     };
 
@@ -159,52 +151,43 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
       constexpr int CSM = decltype(csm)::value;   // 0: no column sums in this item, 1: of X, 2: of Y
       const bf16* st = S ? ring1 : ring0;
       bf16* sn = N ? ring1 : ring0;
-      const bf16* xs = st + (wm * (WBM * 32) + frow) * LDT + fk;
-      const bf16* ys = st + BX * LDT + (wn * (WBN * 32) + frow) * LDT + fk;
+      const int xc = wm * (WBM * 32), yc = BX + wn * (WBN * 32);
       bf16x8 fx[2][WBM], fy[2][WBN];
 #pragma unroll
-      for (int i = 0; i < WBM; ++i) fx[0][i] = *reinterpret_cast<const bf16x8*>(xs + i * 32 * LDT);
+      for (int i = 0; i < WBM; ++i) fx[0][i] = frag_tr(st, xc + i * 32, 0, lane);
 #pragma unroll
-      for (int j = 0; j < WBN; ++j) fy[0][j] = *reinterpret_cast<const bf16x8*>(ys + j * 32 * LDT);
+      for (int j = 0; j < WBN; ++j) fy[0][j] = frag_tr(st, yc + j * 32, 0, lane);
       const bf16* px = nullptr;
       const bf16* py = nullptr;
-      int nvx = 0, nvy = 0;
+      long long mx = 0, my = 0;
 #pragma unroll
       for (int n = 0; n < 4 * WBM * WBN; ++n) {
         constexpr int PER = WBM * WBN;
         const int ks = n / PER, t = n % PER, i = t / WBN, j = t % WBN;
         if (ks < 3 && t < WBM + WBN) {   // fragments of slice ks + 1
-          if (t < WBM) fx[(ks + 1) & 1][t] = *reinterpret_cast<const bf16x8*>(xs + t * 32 * LDT + (ks + 1) * 16);
-          else fy[(ks + 1) & 1][t - WBM] = *reinterpret_cast<const bf16x8*>(ys + (t - WBM) * 32 * LDT + (ks + 1) * 16);
+          if (t < WBM) fx[(ks + 1) & 1][t] = frag_tr(st, xc + t * 32, (ks + 1) * 16, lane);
+          else fy[(ks + 1) & 1][t - WBM] = frag_tr(st, yc + (t - WBM) * 32, (ks + 1) * 16, lane);
         }
         acc[i][j] = LANE_IS_X
                         ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[ks & 1][j], fx[ks & 1][i], acc[i][j], 0, 0, 0)
                         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[ks & 1][i], fy[ks & 1][j], acc[i][j], 0, 0, 0);
-        // pieces: 0..7 transpose + store X; 8..15 column sums; 16..23 transpose + store Y; 24..31 load Y (it is
-        // needed again 40 pieces later); 32..39 load X (needed two steps later)
+        // pieces: 0..7 store X rows; 8..15 column sums; 16..23 store Y rows; 24..31 load Y (needed again 40
+        // pieces later); 32..39 load X (needed two steps later)
         if (n < 8) {
-          *reinterpret_cast<u32x4*>(sn + (cbx * 8 + n) * LDT + mb * 8) = tr_col(rx[N], n);
+          *reinterpret_cast<u32x4*>(sn + sx_off + 8 * n * LDW) = rx[N][n];
         } else if (n < 16) {
           if (CSM == 1) add_cs_row(rx[N][n - 8]);
           if (CSM == 2) add_cs_row(ry[n - 8]);
-          if (n == 14) {
-            long long m = lo + (long long)(kt + 2) * BK + mb * 8;
-            nvy = (int)(hi - m < 8 ? (hi - m < 0 ? 0 : hi - m) : 8);
-            py = yp + m * ldy;
-          }
-          if (n == 15) {
-            long long m = lo + (long long)(kt + 3) * BK + mb * 8;
-            nvx = (int)(hi - m < 8 ? (hi - m < 0 ? 0 : hi - m) : 8);
-            px = xp + m * ldx;
-          }
+          if (n == 14) { my = lo + (long long)(kt + 2) * BK + lr; py = yp + my * ldy; }
+          if (n == 15) { mx = lo + (long long)(kt + 3) * BK + lr; px = xp + mx * ldx; }
         } else if (n < 24) {
-          *reinterpret_cast<u32x4*>(sn + (BX + yrow + (n - 16)) * LDT + mb * 8) = tr_col(ry, n - 16);
+          *reinterpret_cast<u32x4*>(sn + sy_off + 8 * (n - 16) * LDW) = ry[n - 16];
         } else if (n < 32) {
           int r = n - 24;
-          ry[r] = ldg16(r < nvy ? py + r * ldy : zero);
+          ry[r] = ldg16(my + 8 * r < hi ? py + 8 * r * ldy : zero);
         } else if (n < 40) {
           int r = n - 32;
-          rx[N][r] = ldg16(r < nvx ? px + r * ldx : zero);
+          rx[N][r] = ldg16(mx + 8 * r < hi ? px + 8 * r * ldx : zero);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -231,14 +214,13 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
     }
     // (the last step stashed zero rows into stage 0 and passed the barrier: both stages are free again)
 
-    // column sums: 8 row blocks per column block -> one value per column
+    // column sums: the 8 threads lr = 0..7 that share a 16-byte chunk -> one value per column
     if (cs_x || cs_y) {
       float* red = reinterpret_cast<float*>(ring1);   // [8][256]
-      int cb = cs_x ? cbx : cby;
-      bool mine = cs_x || tid < BY;                   // wave 3 holds duplicates of Y blocks
+      bool mine = cs_x || lc < BY / 8;                // lanes 24..31 hold duplicates of Y chunks
       if (mine) {
 #pragma unroll
-        for (int c = 0; c < 8; ++c) red[mb * 256 + cb * 8 + c] = cs[c];
+        for (int c = 0; c < 8; ++c) red[lr * 256 + lc * 8 + c] = cs[c];
       }
       __syncthreads();
       int ncol = cs_x ? BX : BY, c0 = cs_x ? x0 : y0, nn = cs_x ? g.NX : g.NY;
