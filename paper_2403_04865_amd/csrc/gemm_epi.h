@@ -17,18 +17,15 @@ __device__ __forceinline__ void epi_store_mode(int mode, const GemmNT& g, long l
       ((RS*)g.out)[m * g.ldc + n] = from_f<RS>(acc + g.bias[n] + to_f(((const RS*)g.resid)[m * g.ldr + n]));
       break;
     case EPI_BIAS_GELU: {
-      T pre = from_f<T>(acc + g.bias[n]);
-      ((T*)g.out)[m * g.ldc + n] = pre;
-      ((T*)g.out2)[m * g.ldc2 + n] = from_f<T>(gelu_f(to_f(pre)));  // GELU of the stored (rounded) value
-      break;
-    }
-    case EPI_DGELU: {
       float gl, dg;
-      gelu_both(to_f(((const T*)g.pre)[m * g.ldpre + n]), &gl, &dg);
-      ((T*)g.out)[m * g.ldc + n] = from_f<T>(acc * dg);
-      if (g.out2) ((T*)g.out2)[m * g.ldc2 + n] = from_f<T>(gl);
+      gelu_both(acc + g.bias[n], &gl, &dg);
+      ((T*)g.out)[m * g.ldc + n] = from_f<T>(gl);
+      ((T*)g.out2)[m * g.ldc2 + n] = from_f<T>(dg);
       break;
     }
+    case EPI_DGELU:
+      ((T*)g.out)[m * g.ldc + n] = from_f<T>(acc * to_f(((const T*)g.pre)[m * g.ldpre + n]));
+      break;
     case EPI_PATCH: {
       long long mm = g.cmap(m);
       int tok = 1 + (int)(m % g.cmap.g2);

@@ -231,8 +231,7 @@ struct BigEpilogue {
       }
       if (DBG & 32) {  // tuning: all epilogue arithmetic, no global stores
         float sacc = 0.f;
-        if (MODE == EPI_BIAS_GELU) { for (int e = 0; e < 8; ++e) sacc += gelu_tab(tab, (float)(bf16)v[e]); }
-        else if (MODE == EPI_DGELU) { for (int e = 0; e < 8; ++e) { float gl, dg; gelu_both_tab(tab, t[e], &gl, &dg); sacc += v[e] * dg + gl; } }
+        if (MODE == EPI_BIAS_GELU) { for (int e = 0; e < 8; ++e) { float gl, dg; gelu_both_tab(tab, v[e], &gl, &dg); sacc += dg + gl; } }
         else if (E::HAS_AUX) { for (int e = 0; e < 8; ++e) sacc += v[e] + t[e]; }
         else { for (int e = 0; e < 8; ++e) sacc += v[e]; }
         if (sacc == 12345.678f) ((float*)g.out)[0] = sacc;
@@ -251,21 +250,17 @@ struct BigEpilogue {
         } else if (MODE == EPI_BIAS_GELU) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) {
-            v[e] = (float)(bf16)v[e];  // GELU of the stored (rounded) pre-activation
-            t[e] = gelu_tab(tab, v[e]);
+            float gl, dg;
+            gelu_both_tab(tab, v[e], &gl, &dg);
+            v[e] = gl;
+            t[e] = dg;
           }
           put((bf16*)g.out + (rs * ldc + nw) + oc + vo_c, v);
           put((bf16*)g.out2 + (rs * ldc2 + nw) + oc2 + vo_c2, t);
         } else if (MODE == EPI_DGELU) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            float gl, dg;
-            gelu_both_tab(tab, t[e], &gl, &dg);
-            v[e] *= dg;
-            t[e] = gl;
-          }
+          for (int e = 0; e < 8; ++e) v[e] *= t[e];
           put((bf16*)g.out + (rs * ldc + nw) + oc + vo_c, v);
-          if (g.out2) put((bf16*)g.out2 + (rs * ldc2 + nw) + oc2 + vo_c2, t);
         } else {  // EPI_PATCH: output rows go through the row map
 #pragma unroll
           for (int e = 0; e < 8; ++e) v[e] += t[e];
@@ -324,7 +319,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   const int total = (MT + NXCD - 1) / NXCD * NXCD * NTL;
   constexpr bool has_bias = MODE != EPI_PLAIN && MODE != EPI_DGELU;
 
-  if (MODE == EPI_BIAS_GELU || MODE == EPI_DGELU) {
+  if (MODE == EPI_BIAS_GELU) {
     // filled once per workgroup; the K-loop barriers order it before the first epilogue
     for (int k = tid; k < TAB_N; k += NTH) {
       float x0 = -8.0f + (float)k * (1.0f / 64.0f), x1 = x0 + (1.0f / 64.0f);

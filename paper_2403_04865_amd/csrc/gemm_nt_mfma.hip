@@ -82,21 +82,17 @@ __device__ __forceinline__ void epi_seg8(const GemmNT& g, long long m, int n, fl
   } else if (MODE == EPI_BIAS_GELU) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      v[i] = (float)(bf16)v[i];  // GELU of the stored (rounded) pre-activation
-      t[i] = gelu_f(v[i]);
+      float gl, dg;
+      gelu_both(v[i], &gl, &dg);
+      v[i] = gl;
+      t[i] = dg;
     }
     store8((bf16*)g.out + m * g.ldc + n, v);
     store8((bf16*)g.out2 + m * g.ldc2 + n, t);
   } else if (MODE == EPI_DGELU) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float gl, dg;
-      gelu_both(t[i], &gl, &dg);
-      v[i] *= dg;
-      t[i] = gl;
-    }
+    for (int i = 0; i < 8; ++i) v[i] *= t[i];
     store8((bf16*)g.out + m * g.ldc + n, v);
-    if (g.out2) store8((bf16*)g.out2 + m * g.ldc2 + n, t);
   } else {  // EPI_PATCH
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] += t[i];
@@ -346,7 +342,7 @@ bool gemm_nt_mfma_ok(const GemmNT& g) {
   bool ok = g.K % 64 == 0 && g.N % 16 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && aligned16(g.A) && aligned16(g.B) &&
             g.M > 0 && g.ldc % 8 == 0 && aligned16(g.out) && g.N % 8 == 0;
   if (g.epi == EPI_BIAS_RESID) ok = ok && g.ldr % 8 == 0 && aligned16(g.resid);
-  if (g.epi == EPI_BIAS_GELU || (g.epi == EPI_DGELU && g.out2)) ok = ok && g.ldc2 % 8 == 0 && aligned16(g.out2);
+  if (g.epi == EPI_BIAS_GELU) ok = ok && g.ldc2 % 8 == 0 && aligned16(g.out2);
   if (g.epi == EPI_DGELU) ok = ok && g.ldpre % 8 == 0 && aligned16(g.pre);
   if (g.epi != EPI_PLAIN && g.epi != EPI_DGELU) ok = ok && aligned16(g.bias);
   if (g.epi == EPI_PATCH) ok = ok && aligned16(g.pos);

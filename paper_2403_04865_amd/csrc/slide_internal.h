@@ -96,8 +96,8 @@ enum {
   EPI_PLAIN = 0,       // out(T)  = acc
   EPI_BIAS = 1,        // out(T)  = acc + bias[n]
   EPI_BIAS_RESID = 2,  // out(RS) = acc + bias[n] + resid(RS)[m][n]
-  EPI_BIAS_GELU = 3,   // out(T)  = m = acc + bias[n];  out2(T) = gelu(m)
-  EPI_DGELU = 4,       // out(T)  = acc * gelu'(pre(T)[m][n]);  out2(T) = gelu(pre) when out2 != null
+  EPI_BIAS_GELU = 3,   // m = acc + bias[n];  out(T) = gelu(m);  out2(T) = gelu'(m)
+  EPI_DGELU = 4,       // out(T)  = acc * pre(T)[m][n]   (pre holds the gelu'(m) the forward stored)
   EPI_PATCH = 5,       // out(RS)[rowmap(m)] = acc + bias[n] + pos[1 + m % g2][n]
 };
 

@@ -44,7 +44,7 @@ struct Layout {
   // encoder
   size_t enc_begin;
   size_t e_patches, e_x, e_qkv, e_O, e_lse, e_xmid, e_m;              // first instance
-  size_t s_x, s_qkv, s_O, s_lse, s_xmid, s_m;                         // per-layer strides (0 when not saved)
+  size_t s_x, s_qkv, s_O, s_lse, s_xmid, s_m, s_a;                    // per-layer strides (0 when not saved)
   size_t e_u, e_a, e_dm, e_dxA, e_dxB, e_dxAt, e_dxBt, e_du, e_dqkv;
 };
 
@@ -152,7 +152,8 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   y.e_m = take(0); cur += (size_t)inst * align256(M * c->F * e);
   y.e_u = take(M * D * e);
   size_t abytes = M * c->F * e, pbytes = (size_t)nn * c->g2 * c->Kp * e;
-  y.e_a = take(abytes);
+  y.s_a = save ? align256(abytes) : 0;
+  y.e_a = take(0); cur += (size_t)inst * align256(abytes);
   if (bwd) {
     y.e_dm = take(abytes > pbytes ? abytes : pbytes);
     y.e_dxA = take(M * D * rs);
@@ -223,7 +224,7 @@ void gemm_nt(Run& r, const GemmNT& g) {
   // every operand once: A, B, the output(s), and the residual / saved pre-activation the epilogue reads
   double bytes = (double)g.M * g.K * e + (double)g.N * g.K * e + (double)g.M * g.N * e;
   if (g.epi == EPI_BIAS_RESID) bytes += (double)g.M * g.N * rs_size(r.c->dt);
-  if (g.epi == EPI_BIAS_GELU || (g.epi == EPI_DGELU && g.out2)) bytes += (double)g.M * g.N * e;
+  if (g.epi == EPI_BIAS_GELU) bytes += (double)g.M * g.N * e;
   if (g.epi == EPI_DGELU) bytes += (double)g.M * g.N * e;
   launch(r, K_GEMM_NT, 2.0 * g.M * g.N * g.K, bytes, [&] { return launch_gemm_nt(r.c->dt, g, r.c->use_mfma, r.s); });
 }
@@ -299,9 +300,9 @@ int check_bound(const slide_ctx* c) {
   return SLIDE_OK;
 }
 
-// One transformer block forward: x_in(l) -> x_in(l+1), leaving qkv, O, lse, x_mid and the fc1
-// pre-activation of block l in their (per-block or shared) arena slots.  `replay` (backward of the
-// block-inputs-only policy): x_in(l+1) is already stored, so the GELU output and the fc2 GEMM are skipped.
+// One transformer block forward: x_in(l) -> x_in(l+1), leaving qkv, O, lse, x_mid, the MLP activation
+// a = gelu(m) and gelu'(m) of block l in their (per-block or shared) arena slots.  `replay` (backward of the
+// block-inputs-only policy): x_in(l+1) is already stored, so the fc2 GEMM is skipped.
 void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
   slide_ctx* c = r.c;
   hipStream_t s = r.s;
@@ -317,7 +318,7 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
   float* lse = (float*)(ar + y.e_lse + (size_t)l * y.s_lse);
   char* m = ar + y.e_m + (size_t)l * y.s_m;
   char* u = ar + y.e_u;
-  char* a = ar + y.e_a;
+  char* a = ar + y.e_a + (size_t)l * y.s_a;
   int wi = 1 + 4 * l;
   ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
   {
@@ -338,8 +339,8 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
   {
     GemmNT g{};
     g.A = u; g.lda = D; g.B = weight(c, wi + 2); g.ldb = D; g.M = M; g.N = F; g.K = D;
-    g.epi = replay ? EPI_BIAS : EPI_BIAS_GELU; g.bias = c->params + o.fc1b; g.out = m; g.ldc = F;
-    g.out2 = a; g.ldc2 = F;
+    g.epi = EPI_BIAS_GELU; g.bias = c->params + o.fc1b; g.out = a; g.ldc = F;
+    g.out2 = m; g.ldc2 = F;   // m slot: gelu'(pre-activation), all the backward needs of it
     gemm_nt(r, g);
   }
   if (!replay) {
@@ -401,7 +402,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
   float* cpart = (float*)(ar + y.w_cpart);
   float* lnpart = (float*)(ar + y.w_lnpart);
   char *dxA = ar + y.e_dxA, *dxB = ar + y.e_dxB, *dxAt = ar + y.e_dxAt, *dxBt = ar + y.e_dxBt;
-  char *du = ar + y.e_du, *dqkv = ar + y.e_dqkv, *u = ar + y.e_u, *a = ar + y.e_a, *dm = ar + y.e_dm;
+  char *du = ar + y.e_du, *dqkv = ar + y.e_dqkv, *u = ar + y.e_u, *dm = ar + y.e_dm;
   RowMap id{0, 0};
   float* G = c->grads;
   launch(r, K_ELEMWISE, 0, (double)M * D * rs, [&] { return launch_fill_zero(dxA, (size_t)M * D * rs, s); });
@@ -422,10 +423,11 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
     // last block's are still there from the forward)
     if (c->cfg.recompute && l != c->L - 1) block_fwd(r, y, l, n, true);
     // ---- MLP half: x_out = x_mid + gelu(LN2(x_mid) W1^T + b1) W2^T + b2
-    {  // dm = (dx W2) * gelu'(m); the same epilogue re-creates a = gelu(m) for the weight gradient
+    char* a = ar + y.e_a + (size_t)l * y.s_a;
+    {  // dm = (dx W2) * gelu'(m), gelu'(m) as stored by the forward
       GemmNT g{};
       g.A = dxAt; g.lda = D; g.B = weight_t(c, wi + 3); g.ldb = D; g.M = M; g.N = F; g.K = D;
-      g.epi = EPI_DGELU; g.pre = m; g.ldpre = F; g.out = dm; g.ldc = F; g.out2 = a; g.ldc2 = F;
+      g.epi = EPI_DGELU; g.pre = m; g.ldpre = F; g.out = dm; g.ldc = F;
       gemm_nt(r, g);
     }
     gemm_tn(r, dxAt, D, id, a, F, id, M, D, F, wpart, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
