@@ -5,11 +5,14 @@
 // pull out of its L2 (measured: < 50 bytes per clock) bounds the tile from below: a 256 x 192 tile needs
 // (256 + 192) * 2 bytes per 256 * 192 * 2 flop, about 37 bytes per MFMA clock.  192 divides every N that
 // occurs (D, 3D, 4D for D = 384 and 768), so no column tile is partly empty.
-//   * One persistent workgroup of 8 wavefronts per compute unit; a wavefront owns 64 x 96 of the tile
-//     (2 x 3 accumulators of 32 x 32).  Tiles that share an A row panel run at the same time on one XCD.
-//   * Operands travel global -> registers -> LDS.  The loads of K step k + 2 are issued during step k and
-//     stay in flight (in registers) across two steps and across tile boundaries, which covers an HBM miss
-//     on the A panel; LDS holds two stages of [256 + 192][64 + 8] bf16 and needs one barrier per step.
+//   * One persistent workgroup of 4 wavefronts per compute unit (one per SIMD, the whole register file
+//     each); a wavefront owns 128 x 96 of the tile (4 x 3 accumulators of 32 x 32), so every fragment read
+//     from LDS feeds three or four MFMAs.  Tiles that share an A row panel run at the same time on one XCD.
+//   * Operands travel global -> registers -> LDS.  The A loads of K step k + 2 and the B loads of step
+//     k + 1 are issued during step k and stay in flight (in registers) across steps and across tile
+//     boundaries, which covers an HBM miss on the A panel; LDS holds two stages of [256 + 192][64 + 8]
+//     bf16 (two separate arrays, so that writes to one are free to move past reads of the other) and
+//     needs one barrier per step.  The order of MFMA, LDS and global instructions inside a step is pinned.
 //   * The MFMA operands are passed swapped (B fragment first), so a lane's accumulator registers are runs
 //     of four neighbouring columns of one row: the epilogue moves them through a wave-private LDS patch
 //     with 16-byte writes and gets 8-column row segments back, all global traffic being 16-byte accesses
@@ -32,10 +35,8 @@ constexpr int WBM = 4, WBN = 3;                    // 32 x 32 accumulators per w
 constexpr int RSTEP = NTH / 8;                     // rows per loader pass
 constexpr int CA = BM / RSTEP, CB = BN / RSTEP;    // 16-byte chunks per thread and K step
 constexpr int STAGE = (BM + BN) * LDT;             // bf16 elements per LDS stage
-constexpr int RING_BYTES = 2 * STAGE * 2;          // 129024
 constexpr int TAB_N = 1024;                        // table over [-8, 8) in steps of 1/64
 constexpr int PS = 100;                            // patch row stride in floats (96 + 4)
-constexpr size_t LDS_BYTES = (size_t)RING_BYTES + TAB_N * 16 + BN * 4;
 static_assert((NTH / 64) * 32 * PS * 4 <= STAGE * 2, "epilogue patches alias stage 1 of the operand ring");
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));

@@ -88,3 +88,36 @@ def test_arena_arithmetic_and_unbound_calls(lib):
         L._check(L.lib.encoder_fwd_tiles(L.ctx, None, 4, None, 0, None), "encoder_fwd_tiles")
     assert e.value.code == -4
     assert L.kernel_names()[0] == "gemm_nt"
+
+
+def _paper_capacity():
+    path = os.path.join(os.path.dirname(__file__), "golden", "paper_capacity.txt")
+    out = {}
+    for line in open(path):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            out[k] = int(v)
+    return out
+
+
+def test_paper_capacity_arithmetic_and_arena_accounting():
+    """The paper's device counts follow from its tiles-per-device figure (Method), and the arena accounting of this
+    library (host arithmetic, no GPU) must not need more memory per ViT-B tile than the paper's framework did."""
+    import gen
+    from paper_2403_04865_amd import SlideLib
+    from slide_harness import lib_config
+    cap = _paper_capacity()
+    k = cap["tiles_per_80GB_vit_base_amp"]
+    assert -(-cap["tiles_largest_slide"] // k) == cap["gpus_largest_slide"]
+    assert -(-cap["tiles_p99_slide"] // k) == cap["gpus_p99_slide"]
+    assert (cap["gpus_finetune_experiment"] - 1) * k == cap["tiles_per_step_finetune_experiment"]
+    cfg, _ = gen.CONFIGS["full"]  # ViT-B/16 at 224 px
+    lib = SlideLib(lib_config(cfg, 1, 0))  # bf16 storage, every block activation kept
+    b1, b2 = lib.slide_arena_bytes(1000), lib.slide_arena_bytes(2000)
+    per_tile = (b2 - b1) / 1000.0
+    fixed = b1 - 1000 * per_tile
+    fits_80 = int((80e9 - fixed) // per_tile)
+    assert fits_80 >= k, (fits_80, k)
+    # the same accounting puts the paper's largest slide, with per-block recompute, inside one 288 GB device
+    lib_r = SlideLib(lib_config(cfg, 1, 1))
+    assert lib_r.slide_arena_bytes(16384) < 288e9 < lib.slide_arena_bytes(16384)
