@@ -24,6 +24,7 @@
 #include "gemm_epi.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace sl {
 
@@ -42,6 +43,8 @@ static_assert((NTH / 64) * 32 * PS * 4 <= STAGE * 2, "epilogue patches alias sta
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ u32x4 ldg16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
+// uniform base (scalar registers) + 32-bit per-lane byte offset
+__device__ __forceinline__ u32x4 ldg16(const char* base, unsigned off) { return *reinterpret_cast<const u32x4*>(base + off); }
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -87,29 +90,13 @@ __device__ __forceinline__ void gelu_both_tab(const float4* tab, float x, float*
   *dg = e.z + f * e.w;
 }
 
-// Instruction order of one K step, pinned for the scheduler (one wavefront per SIMD: nothing else hides
-// the LDS and global-memory instructions, so they are dealt out between the 48 MFMAs of the step):
-// fragment reads of slice ks + 1 and the 14 LDS writes of the next step's operands under the MFMAs of
-// slices 0..2, the 14 global loads of the step after next-but-one under those of slices 2..3.
-__device__ __forceinline__ void pin_step_schedule() {
-#define SL_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-  constexpr int MFMA = 0x008, VMEM_RD = 0x020, DS_RD = 0x100, DS_WR = 0x200;
-  SL_SGB(DS_RD, WBM + WBN);
-#pragma unroll
-  for (int ks = 0; ks < 3; ++ks) {
-#pragma unroll
-    for (int t = 0; t < WBM + WBN; ++t) { SL_SGB(MFMA, 1); SL_SGB(DS_RD, 1); }
-#pragma unroll
-    for (int t = 0; t < WBM * WBN - (WBM + WBN); ++t) {
-      SL_SGB(MFMA, 1);
-      if (ks < 2 || t < 4) SL_SGB(DS_WR, 1); else SL_SGB(VMEM_RD, 1);
-    }
-  }
-#pragma unroll
-  for (int t = 0; t < WBM * WBN; ++t) { SL_SGB(MFMA, 1); SL_SGB(VMEM_RD, 1); }
-  SL_SGB(VMEM_RD, 1);
-#undef SL_SGB
+template <class F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
 }
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) { static_for_impl(f, std::make_integer_sequence<int, N>{}); }
 
 // ---- epilogue of one wavefront's 128 x 96 block -------------------------------------------------
 // Accumulator element r of lane l (operands swapped) is row l % 32, column (r / 4) * 8 + (l / 32) * 4 + r % 4
@@ -353,7 +340,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   float rbias = 0.f;
   bool off_special = true;   // aoff must be (re)built
 #pragma unroll
-  for (int i = 0; i < CB; ++i) boff[i] = (unsigned)((row0 + i * RSTEP) * (int)g.ldb + kc * 8);  // N % 96 == 0: no clamp
+  for (int i = 0; i < CB; ++i) boff[i] = 2u * (unsigned)((row0 + i * RSTEP) * (int)g.ldb + kc * 8);  // bytes; N % 96 == 0: no clamp
   auto set_offsets_a = [&](long long m0) {
     if (DBG & 8) m0 = (m0 / BM % 8) * BM;  // tuning: every A load hits L2
     long long base_row = g.amap.map32((unsigned)m0);
@@ -364,9 +351,9 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     if (special || off_special) {
 #pragma unroll
       for (int i = 0; i < CA; ++i) {
-        long long am = m0 + row0 + i * RSTEP;
-        if (am > g.M - 1) am = g.M - 1;  // rows past the end are loaded (valid memory) but never stored
-        aoff[i] = (unsigned)((g.amap.map32((unsigned)am) - base_row) * g.lda + kc * 8);
+        unsigned am = (unsigned)m0 + (unsigned)(row0 + i * RSTEP);  // M < 2^31
+        if (am > (unsigned)g.M - 1u) am = (unsigned)g.M - 1u;  // rows past the end are loaded (valid memory) but never stored
+        aoff[i] = 2u * (unsigned)((g.amap.map32(am) - base_row) * g.lda + kc * 8);  // bytes
       }
     }
     off_special = special;
@@ -379,12 +366,12 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     constexpr int S = decltype(slot)::value;
     if (DBG & 4) return;
 #pragma unroll
-    for (int i = 0; i < CA; ++i) ra[S][i] = ldg16(Ab + (aoff[i] + (unsigned)k0));
+    for (int i = 0; i < CA; ++i) ra[S][i] = ldg16((const char*)(Ab + k0), aoff[i]);
   };
   auto issue_b = [&](int k0) {
     if (DBG & 4) return;
 #pragma unroll
-    for (int i = 0; i < CB; ++i) rb[i] = ldg16(Bb + (boff[i] + (unsigned)k0));
+    for (int i = 0; i < CB; ++i) rb[i] = ldg16((const char*)(Bb + k0), boff[i]);
   };
   auto stash = [&](auto slot) {
     constexpr int S = decltype(slot)::value;
@@ -402,12 +389,19 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   // prologue: step 0 in LDS stage 0, steps 1 and 2 in flight in register slots 1 and 0
   set_offsets_a(m0);
   set_offsets_b(n0);
+  // (the order of these loads is fenced: the waits the compiler places in the K loop are the most
+  // conservative over every way into it, this one included)
   issue_a(std::integral_constant<int, 0>{}, 0);
   issue_b(0);
+  __builtin_amdgcn_sched_barrier(0);
   issue_a(std::integral_constant<int, 1>{}, BK);
+  __builtin_amdgcn_sched_barrier(0);
   stash(std::integral_constant<int, 0>{});
-  issue_a(std::integral_constant<int, 0>{}, 2 * BK);
+  __builtin_amdgcn_sched_barrier(0);
   issue_b(BK);
+  __builtin_amdgcn_sched_barrier(0);
+  issue_a(std::integral_constant<int, 0>{}, 2 * BK);
+  __builtin_amdgcn_sched_barrier(0);
   if (tid < BN) lbias_all[tid] = rbias;
   __syncthreads();
 
@@ -434,57 +428,93 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
         }
       }
 
-    auto compute = [&](auto slot, auto first) {
-      constexpr int S = decltype(slot)::value;
-      constexpr bool FIRST = decltype(first)::value;
+    // MFMA fragments: two buffers of one 16-wide slice each
+    bf16x8 fa[2][WBM], fb[2][WBN];
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    // fragment t (0..3: A row blocks, 4..6: B column blocks) of slice KS of stage S -> buffer BF
+    auto rd_one = [&](auto slot, auto slice, auto buf, auto frag) {
+      constexpr int S = decltype(slot)::value, KS = decltype(slice)::value, BF = decltype(buf)::value;
+      constexpr int T = decltype(frag)::value;
       const bf16* st = S ? ring1 : ring0;
-      const bf16* as = st + (wm * (WBM * 32) + frow) * LDT + fk;
-      const bf16* bs = st + BM * LDT + (wn * (WBN * 32) + frow) * LDT + fk;
-      bf16x8 fa[2][WBM], fb[2][WBN];
-#pragma unroll
-      for (int i = 0; i < WBM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDT);
-#pragma unroll
-      for (int j = 0; j < WBN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDT);
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        if (ks + 1 < BK / 16) {
-#pragma unroll
-          for (int i = 0; i < WBM; ++i)
-            fa[(ks + 1) & 1][i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * LDT + (ks + 1) * 16);
-#pragma unroll
-          for (int j = 0; j < WBN; ++j)
-            fb[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDT + (ks + 1) * 16);
-        }
-#pragma unroll
-        for (int i = 0; i < WBM; ++i)
-#pragma unroll
-          for (int j = 0; j < WBN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i],
-                                                                acc[i][j], 0, 0, 0);
+      if constexpr (T < WBM) {
+        const bf16* as = st + (wm * (WBM * 32) + frow) * LDT + fk + KS * 16;
+        fa[BF][T] = *reinterpret_cast<const bf16x8*>(as + T * 32 * LDT);
+      } else {
+        const bf16* bs = st + BM * LDT + (wn * (WBN * 32) + frow) * LDT + fk + KS * 16;
+        fb[BF][T - WBM] = *reinterpret_cast<const bf16x8*>(bs + (T - WBM) * 32 * LDT);
       }
     };
-    // one K step: multiply out of LDS stage S; move the next step's operands (A: register slot S^1, issued two
-    // steps ago; B: issued one step ago) into stage S^1, which every wave left before the last barrier;
-    // re-use the registers for A three steps and B two steps ahead (element offsets ka, kb).
-    auto step = [&](auto slot, int ka, int kb, auto first) {
+    // LDS write w of the next stage: 0..7 the A chunks of register slot S, 8..13 the B chunks
+    auto wr_one = [&](auto slot, auto idx) {
+      constexpr int S = decltype(slot)::value, W = decltype(idx)::value;
+      bf16* st = S ? ring1 : ring0;
+      if constexpr (W < CA) *reinterpret_cast<u32x4*>(st + soff + W * RSTEP * LDT) = ra[S][W];
+      else *reinterpret_cast<u32x4*>(st + BM * LDT + soff + (W - CA) * RSTEP * LDT) = rb[W - CA];
+    };
+    // global load l of a step: 0..5 the B chunks (they are needed first and hit L2), 6..13 the A chunks.
+    // Loads return in order: the B chunks, issued one step before their LDS writes, do not wait for younger A
+    // loads that may miss to HBM.
+    auto ld_one = [&](auto slot, auto idx, int ka, int kb) {
+      constexpr int S = decltype(slot)::value, Lx = decltype(idx)::value;
+      if (DBG & 4) return;
+      if constexpr (Lx < CB) rb[Lx] = ldg16((const char*)(Bb + kb), boff[Lx]);
+      else ra[S][Lx - CB] = ldg16((const char*)(Ab + ka), aoff[Lx - CB]);
+    };
+    auto mfma_one = [&](auto buf, auto tt) {
+      constexpr int BF = decltype(buf)::value, T = decltype(tt)::value, i = T / WBN, j = T % WBN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[BF][j], fa[BF][i], acc[i][j], 0, 0, 0);
+    };
+    // One K step out of LDS stage S, in explicit issue order: one MFMA and at most two memory instructions per
+    // piece, a scheduling fence after each piece (one wavefront per SIMD: nothing else hides the LDS and
+    // global-memory instructions, so they are dealt out between the 48 MFMAs).  The step's barrier sits
+    // between slices 2 and 3: by then every fragment of this stage has been read and the next stage
+    // (A: register slot S^1, loaded two steps ago; B: loaded one step ago) is completely written, so the
+    // fragments of the next step's slice 0 are fetched under the MFMAs of slice 3 and no wavefront starts a
+    // step with an empty MFMA pipe.  The registers are re-used for A three steps and B two steps ahead
+    // (element offsets ka, kb).  NEXT_FRAGS = 0 for the last step of a tile.
+    auto step_part1 = [&](auto slot, int ka, int kb) {
       constexpr int S = decltype(slot)::value;
-      compute(slot, first);
-      stash(std::integral_constant<int, S ^ 1>{});
-      issue_a(std::integral_constant<int, S ^ 1>{}, ka);
-      issue_b(kb);
-      pin_step_schedule();
+      using SN = std::integral_constant<int, S ^ 1>;
+      static_for<36>([&](auto pc) {
+        constexpr int P = decltype(pc)::value, KS = P / 12, T = P % 12;
+        mfma_one(std::integral_constant<int, KS & 1>{}, std::integral_constant<int, T>{});
+        if constexpr (T < WBM + WBN)
+          rd_one(slot, std::integral_constant<int, KS + 1>{}, std::integral_constant<int, (KS + 1) & 1>{},
+                 std::integral_constant<int, T>{});
+        if constexpr (KS < 2 && T >= 7) wr_one(SN{}, std::integral_constant<int, KS * 5 + T - 7>{});
+        if constexpr (KS == 2 && T < 4) wr_one(SN{}, std::integral_constant<int, 10 + T>{});
+        if constexpr (KS == 2 && T >= 7) ld_one(SN{}, std::integral_constant<int, T - 7>{}, ka, kb);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    };
+    auto step_part2 = [&](auto slot, auto next_frags, int ka, int kb) {
+      constexpr int S = decltype(slot)::value;
+      using SN = std::integral_constant<int, S ^ 1>;
+      static_for<12>([&](auto tc) {
+        constexpr int T = decltype(tc)::value;
+        mfma_one(I1{}, tc);
+        if constexpr (decltype(next_frags)::value && T < WBM + WBN) rd_one(SN{}, I0{}, I0{}, tc);
+        if constexpr (T < 9) ld_one(SN{}, std::integral_constant<int, 5 + T>{}, ka, kb);
+        __builtin_amdgcn_sched_barrier(0);
+      });
+    };
+    auto step = [&](auto slot, int ka, int kb) {
+      step_part1(slot, ka, kb);
       __syncthreads();
+      step_part2(slot, I1{}, ka, kb);
     };
 
+    static_for<WBM + WBN>([&](auto tc) { rd_one(I0{}, I0{}, I0{}, tc); });
     for (int kt = 0; kt < nk - 4; kt += 2) {
-      step(std::integral_constant<int, 0>{}, (kt + 3) * BK, (kt + 2) * BK, std::false_type{});
-      step(std::integral_constant<int, 1>{}, (kt + 4) * BK, (kt + 3) * BK, std::false_type{});
+      step(I0{}, (kt + 3) * BK, (kt + 2) * BK);
+      step(I1{}, (kt + 4) * BK, (kt + 3) * BK);
     }
-    step(std::integral_constant<int, 0>{}, (nk - 1) * BK, (nk - 2) * BK, std::false_type{});   // step nk - 4
+    step(I0{}, (nk - 1) * BK, (nk - 2) * BK);   // step nk - 4
     set_offsets_a(m1);  // this tile needs no further A loads
-    step(std::integral_constant<int, 1>{}, 0, (nk - 1) * BK, std::false_type{});               // step nk - 3
+    step(I1{}, 0, (nk - 1) * BK);               // step nk - 3
     set_offsets_b(n1);
-    step(std::integral_constant<int, 0>{}, BK, 0, std::false_type{});                          // step nk - 2
+    step(I0{}, BK, 0);                          // step nk - 2
     if (DBG & 64) tstamp[1] = clock64();
 
     // last step: the next tile's first operands go to stage 0 and every load up to its third step is in flight
@@ -494,12 +524,9 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     BigEpilogue<MODE, RS, DBG> epi(g, tab, (int)mw, nw, lane);
     {
       typename BigEpilogue<MODE, RS, DBG>::Aux aux;
+      step_part1(I1{}, 2 * BK, BK);
       epi.template fetch<0>(aux);
-      compute(std::integral_constant<int, 1>{}, std::false_type{});
-      stash(std::integral_constant<int, 0>{});
-      issue_a(std::integral_constant<int, 0>{}, 2 * BK);
-      issue_b(BK);
-      pin_step_schedule();
+      step_part2(I1{}, I0{}, 2 * BK, BK);
       if (tid < BN) lbias_all[tid] = rbias;  // next tile's bias; this tile's was consumed at its start
       if (DBG & 64) tstamp[2] = clock64();
       __syncthreads();  // every wave is done with stage 1
@@ -535,7 +562,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
 // Shapes this kernel takes: a contraction that is a whole number of double steps, and enough rows
 // to fill the chip with 256-row tiles.  Alignment requirements are those of gemm_nt_mfma_ok.
 bool gemm_nt_big_ok(const GemmNT& g) { return g.M < (1LL << 31) && g.N % BN == 0 &&
-         g.ldc < (1 << 20) && g.ldc2 < (1 << 20) && g.ldr < (1 << 20) && g.ldpre < (1 << 20) && g.K % (2 * BK) == 0 && g.K >= 4 * BK && g.M >= 4096 && g.N >= 96; }
+         g.lda < (1 << 20) && g.ldb < (1 << 20) && g.ldc < (1 << 20) && g.ldc2 < (1 << 20) && g.ldr < (1 << 20) && g.ldpre < (1 << 20) && g.K % (2 * BK) == 0 && g.K >= 4 * BK && g.M >= 4096 && g.N >= 96; }
 
 template <int MODE, int DBG>
 hipError_t launch_big(const GemmNT& g, hipStream_t s) {
