@@ -106,11 +106,15 @@ __device__ __forceinline__ void load_tr(const bf16* __restrict__ g, long long gs
 
 constexpr float LOG2E = 1.4426950408889634f;
 
+// Workgroup size: one wavefront per block of 32 queries (keys) where a head has seven of them: no
+// wavefront then carries two blocks while another carries one.
+template <int NB> constexpr int attn_threads() { return NB >= 7 ? NB * 64 : 256; }
+
 // --------------------------------------------------------------------------------------------
 // forward
 // --------------------------------------------------------------------------------------------
 template <int DH, int NB>
-__global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict__ qkv, bf16* __restrict__ O,
+__global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const bf16* __restrict__ qkv, bf16* __restrict__ O,
                                                        float* __restrict__ lse, int T, int H, long long ntiles) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
@@ -130,7 +134,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
   float sl2 = LOG2E / sqrtf((float)DH);
-  for (int qb = wave; qb < NB; qb += 4) {
+  for (int qb = wave; qb < NB; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
     int qc = q < T ? q : T - 1;
     bf16x8 fq[KS];
@@ -215,7 +219,7 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_mfma_k(const bf16* __restrict
 // backward, pass Q: dQ
 // --------------------------------------------------------------------------------------------
 template <int DH, int NB>
-__global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
+__global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
                                                          bf16* __restrict__ dqkv, int T, int H, long long ntiles) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -237,7 +241,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restri
   int li = lane & 31, h2 = lane >> 5;
   float scale = 1.0f / sqrtf((float)DH);
   float sl2 = LOG2E * scale;
-  for (int qb = wave; qb < NB; qb += 4) {
+  for (int qb = wave; qb < NB; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
     int qc = q < T ? q : T - 1;
     bf16x8 fq[KS], fdo[KS];
@@ -307,6 +311,8 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_q_mfma_k(const bf16* __restri
 // backward, pass K: dK, dV
 // --------------------------------------------------------------------------------------------
 template <int DH, int NB>
+// (four wavefronts: this kernel needs more registers than seven wavefronts per workgroup, two workgroups per
+// compute unit, would leave it, and measured slower with seven and one workgroup)
 __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
                                                          bf16* __restrict__ dqkv, int T, int H, long long ntiles) {
@@ -431,7 +437,7 @@ hipError_t fwd_go(const void* qkv, void* O, float* lse, long long n, int T, int 
   size_t lds = fwd_lds<DH, NB>();
   hipError_t e = set_lds(attn_fwd_mfma_k<DH, NB>, lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_fwd_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(256), lds, s,
+  hipLaunchKernelGGL((attn_fwd_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(attn_threads<NB>()), lds, s,
                      (const bf16*)qkv, (bf16*)O, lse, T, H, n);
   return hipGetLastError();
 }
@@ -444,7 +450,7 @@ hipError_t bwd_go(const void* qkv, const void* O, const float* lse, const void* 
   if (e != hipSuccess) return e;
   e = set_lds(attn_bwd_k_mfma_k<DH, NB>, lk);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_bwd_q_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(256), lq, s,
+  hipLaunchKernelGGL((attn_bwd_q_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(attn_threads<NB>()), lq, s,
                      (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((attn_bwd_k_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(256), lk, s,
