@@ -140,23 +140,27 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     // One step, written out in issue order (one wavefront per SIMD: everything that is not an MFMA has to be
-    // issued in the shadow of the 48 MFMAs, and the scheduler is kept from regrouping by a barrier after each
+    // issued in the shadow of the 48 MFMAs, and the scheduler is kept from regrouping by a fence after each
     // MFMA).  Step kt multiplies out of stage S = kt & 1.  Between the MFMAs: fragment reads of the next slice;
     // the next step's operands (X: register slot S^1, loaded two steps ago; Y: loaded one step ago) are
-    // transposed column by column and written to stage S^1, which every wave left before the last barrier;
-    // then the registers are re-used for the loads of X three steps and Y two steps ahead.
+    // written to stage S^1, which every wave left before the last barrier; then the registers are re-used
+    // for the loads of X three steps and Y two steps ahead.  The step's barrier sits between slices 2 and
+    // 3: by then this stage has been read and the next one is written, so the fragments of the next step's
+    // slice 0 are fetched under the MFMAs of slice 3 and no wavefront starts a step with an empty MFMA pipe.
+    const int xc = wm * (WBM * 32), yc = BX + wn * (WBN * 32);
+    bf16x8 fx[2][WBM], fy[2][WBN];
+    auto first_frags = [&]() {   // slice 0 of stage 0
+#pragma unroll
+      for (int i = 0; i < WBM; ++i) fx[0][i] = frag_tr(ring0, xc + i * 32, 0, lane);
+#pragma unroll
+      for (int j = 0; j < WBN; ++j) fy[0][j] = frag_tr(ring0, yc + j * 32, 0, lane);
+    };
     auto step = [&](auto slot, int kt, auto csm) {
       constexpr int S = decltype(slot)::value;
       constexpr int N = S ^ 1;
       constexpr int CSM = decltype(csm)::value;   // 0: no column sums in this item, 1: of X, 2: of Y
       const bf16* st = S ? ring1 : ring0;
       bf16* sn = N ? ring1 : ring0;
-      const int xc = wm * (WBM * 32), yc = BX + wn * (WBN * 32);
-      bf16x8 fx[2][WBM], fy[2][WBN];
-#pragma unroll
-      for (int i = 0; i < WBM; ++i) fx[0][i] = frag_tr(st, xc + i * 32, 0, lane);
-#pragma unroll
-      for (int j = 0; j < WBN; ++j) fy[0][j] = frag_tr(st, yc + j * 32, 0, lane);
       const bf16* px = nullptr;
       const bf16* py = nullptr;
       long long mx = 0, my = 0;
@@ -164,9 +168,12 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
       for (int n = 0; n < 4 * WBM * WBN; ++n) {
         constexpr int PER = WBM * WBN;
         const int ks = n / PER, t = n % PER, i = t / WBN, j = t % WBN;
-        if (ks < 3 && t < WBM + WBN) {   // fragments of slice ks + 1
-          if (t < WBM) fx[(ks + 1) & 1][t] = frag_tr(st, xc + t * 32, (ks + 1) * 16, lane);
-          else fy[(ks + 1) & 1][t - WBM] = frag_tr(st, yc + (t - WBM) * 32, (ks + 1) * 16, lane);
+        if (n == 3 * PER) __syncthreads();
+        if (t < WBM + WBN) {   // fragments of slice ks + 1, or of the next stage's slice 0
+          const bf16* src = ks < 3 ? st : sn;
+          const int kk = ks < 3 ? (ks + 1) * 16 : 0;
+          if (t < WBM) fx[(ks + 1) & 1][t] = frag_tr(src, xc + t * 32, kk, lane);
+          else fy[(ks + 1) & 1][t - WBM] = frag_tr(src, yc + (t - WBM) * 32, kk, lane);
         }
         acc[i][j] = LANE_IS_X
                         ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[ks & 1][j], fx[ks & 1][i], acc[i][j], 0, 0, 0)
@@ -191,17 +198,18 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
         }
         __builtin_amdgcn_sched_barrier(0);
       }
-      __syncthreads();
     };
 
     auto run = [&](auto csm) {   // one instance per column-sum mode: the step stays free of branches
       issue_x(std::integral_constant<int, 0>{}, 0);
       issue_y(0);
       issue_x(std::integral_constant<int, 1>{}, 1);
+      __syncthreads();   // the item before may still be fetching its last (unused) fragments from stage 0
       stash(std::integral_constant<int, 0>{}, csm);
       issue_x(std::integral_constant<int, 0>{}, 2);
       issue_y(1);
       __syncthreads();
+      first_frags();
       for (int kt = 0; kt < nk; kt += 2) {       // loads past the slab's end read the zero row
         step(std::integral_constant<int, 0>{}, kt, csm);
         step(std::integral_constant<int, 1>{}, kt + 1, csm);
@@ -212,7 +220,7 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
       else if (cs_y) run(std::integral_constant<int, 2>{});
       else run(std::integral_constant<int, 0>{});
     }
-    // (the last step stashed zero rows into stage 0 and passed the barrier: both stages are free again)
+    // (after the last step's barrier nothing reads stage 1 any more; stage 0 is still being read)
 
     // column sums: the 8 threads lr = 0..7 that share a 16-byte chunk -> one value per column
     if (cs_x || cs_y) {

@@ -53,6 +53,27 @@ __global__ void __launch_bounds__(256) patchify_k(const T* __restrict__ pix, T* 
   pat[i] = pix[((n * 3 + c) * S + gy * P + py) * S + gx * P + px];
 }
 
+// bf16, P % 8 == 0, S % 8 == 0: one workgroup per band of patches (tile n, patch row gy).  The band's 3 x P image
+// rows are read with 16-byte accesses along the rows into LDS and written as whole patch rows, again 16 bytes
+// per lane and contiguous (the element-wise kernel above moves 2 bytes per lane).
+__global__ void __launch_bounds__(256) patchify_band_k(const bf16* __restrict__ pix, bf16* __restrict__ pat, int S, int P) {
+  extern __shared__ uint4 band[];   // [3 * P][S / 8] chunks of 8 pixels
+  const int g = S / P, SC = S / 8, PC = P / 8, rows = 3 * P;
+  const long long n = blockIdx.x / g;
+  const int gy = blockIdx.x % g;
+  for (int i = threadIdx.x; i < rows * SC; i += 256) {
+    int r = i / SC, xc = i % SC, c = r / P, py = r % P;
+    band[i] = *reinterpret_cast<const uint4*>(pix + ((n * 3 + c) * S + gy * P + py) * (long long)S + xc * 8);
+  }
+  __syncthreads();
+  const int KC = rows * PC;          // chunks per patch row of the output
+  bf16* out = pat + (n * g + gy) * (long long)g * (3 * P * P);
+  for (int i = threadIdx.x; i < g * KC; i += 256) {
+    int gx = i / KC, k = i % KC, r = k / PC, pc = k % PC;   // r = c * P + py
+    *reinterpret_cast<uint4*>(out + (long long)i * 8) = band[r * SC + gx * PC + pc];
+  }
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256) unpatchify_k(const T* __restrict__ dpat, T* __restrict__ dpix, long long total,
                                                     int S, int P) {
@@ -71,6 +92,9 @@ hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long 
   unsigned grid = (unsigned)((total + 255) / 256);
   if (dt == DT_F32)
     hipLaunchKernelGGL(patchify_k<float>, dim3(grid), dim3(256), 0, s, (const float*)pixels, (float*)patches, total, S, P);
+  else if (P % 8 == 0 && S % P == 0 && n * (S / P) < (1LL << 31) && (size_t)3 * P * S * 2 <= 65536)
+    hipLaunchKernelGGL(patchify_band_k, dim3((unsigned)(n * (S / P))), dim3(256), (size_t)3 * P * S * 2, s,
+                       (const bf16*)pixels, (bf16*)patches, S, P);
   else
     hipLaunchKernelGGL(patchify_k<bf16>, dim3(grid), dim3(256), 0, s, (const bf16*)pixels, (bf16*)patches, total, S, P);
   return hipGetLastError();
