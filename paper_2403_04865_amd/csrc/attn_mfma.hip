@@ -72,6 +72,21 @@ __device__ __forceinline__ bf16x8 frag_tr(const bf16* X, int ld, int c0, int j0,
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// The same with the lane-dependent part of the address taken out: lp = X + tr_lane_off(ld, lane) is formed once,
+// off = j0 * ld + c0 is a compile-time or wave-uniform element offset (LDS instructions carry it as an immediate).
+__device__ __forceinline__ int tr_lane_off(int ld, int lane) {
+  int g = lane >> 4, s = lane & 15;
+  return (4 * (g >> 1) + (s >> 2)) * ld + 16 * (g & 1) + (s & 3) * 4;
+}
+__device__ __forceinline__ bf16x8 frag_tr_at(const bf16* lp, int ld, int off) {
+  const bf16* p = lp + off;
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 8 * ld));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
 // copy rows [0,T) x DH of a row-major global matrix (row stride gs) into LDS row-major [TP][DH+8]
 template <int DH>
 __device__ __forceinline__ void load_rm(const bf16* __restrict__ g, long long gs, int T, int TP, bf16* dst) {
@@ -134,6 +149,9 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
   float sl2 = LOG2E / sqrtf((float)DH);
+  // lane-dependent parts of the LDS addresses, formed once; the key-block loop only advances them
+  const bf16* const krow0 = Ks + li * LDR + h2 * 8;
+  const bf16* const vtr0 = Vs + tr_lane_off(LDR, lane);
   for (int qb = wave; qb < NB; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
     int qc = q < T ? q : T - 1;
@@ -148,14 +166,16 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
     float mx = -INFINITY, l = 0.f;
+    const bf16* krow = krow0;
+    const bf16* vtr = vtr0;
 #pragma unroll 1
-    for (int kb = 0; kb < NB; ++kb) {
+    for (int kb = 0; kb < NB; ++kb, krow += 32 * LDR, vtr += 32 * LDR) {
       f32x16 sc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fq[ks], sc, 0, 0, 0);
       }
       float bm = -INFINITY;
@@ -180,10 +200,12 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
       }
       l = l * resc + ls;
       mx = mn;
+      if (__builtin_amdgcn_ballot_w64(resc != 1.0f) != 0) {   // uniform: after the first blocks the maximum rarely moves
 #pragma unroll
-      for (int d = 0; d < DB; ++d)
+        for (int d = 0; d < DB; ++d)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[d][r] *= resc;
+          for (int r = 0; r < 16; ++r) o[d][r] *= resc;
+      }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         float pv[8];
@@ -192,7 +214,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
         bf16x8 pb = pack8(pv);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          bf16x8 a = frag_tr(Vs, LDR, d * 32, kb * 32 + 16 * t, lane);
+          bf16x8 a = frag_tr_at(vtr, LDR, 16 * t * LDR + d * 32);
           o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[d], 0, 0, 0);
         }
       }
@@ -241,6 +263,9 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
   int li = lane & 31, h2 = lane >> 5;
   float scale = 1.0f / sqrtf((float)DH);
   float sl2 = LOG2E * scale;
+  const bf16* const krow0 = Ks + li * LDR + h2 * 8;
+  const bf16* const vrow0 = Vs + li * LDR + h2 * 8;
+  const bf16* const ktr0 = Ks + tr_lane_off(LDR, lane);
   for (int qb = wave; qb < NB; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
     int qc = q < T ? q : T - 1;
@@ -263,23 +288,29 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
     for (int d = 0; d < DB; ++d)
 #pragma unroll
       for (int r = 0; r < 16; ++r) dq[d][r] = 0.f;
+    const bf16* krow = krow0;
+    const bf16* vrow = vrow0;
+    const bf16* ktr = ktr0;
 #pragma unroll 1
-    for (int kb = 0; kb < NB; ++kb) {
+    for (int kb = 0; kb < NB; ++kb, krow += 32 * LDR, vrow += 32 * LDR, ktr += 32 * LDR) {
       f32x16 s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + (kb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fq[ks], s, 0, 0, 0);
-        bf16x8 v = *reinterpret_cast<const bf16x8*>(Vs + (kb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        bf16x8 v = *reinterpret_cast<const bf16x8*>(vrow + ks * 16);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v, fdo[ks], dp, 0, 0, 0);
       }
       float ds[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        int key = kb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
-        float p = key < T ? __builtin_amdgcn_exp2f(s[r] * sl2 - lq) : 0.f;
+        float p = __builtin_amdgcn_exp2f(s[r] * sl2 - lq);
+        if (kb == NB - 1) {   // only the last block holds padded keys
+          int key = kb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
+          if (key >= T) p = 0.f;
+        }
         ds[r] = p * (dp[r] - delta);
       }
 #pragma unroll
@@ -287,7 +318,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
         bf16x8 db = pack8(ds + 8 * t);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          bf16x8 a = frag_tr(Ks, LDR, d * 32, kb * 32 + 16 * t, lane);
+          bf16x8 a = frag_tr_at(ktr, LDR, 16 * t * LDR + d * 32);
           dq[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, db, dq[d], 0, 0, 0);
         }
       }
@@ -354,6 +385,10 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
   int li = lane & 31, h2 = lane >> 5;
   float scale = 1.0f / sqrtf((float)DH);
   float sl2 = LOG2E * scale;
+  const bf16* const qrow0 = Qs + li * LDR + h2 * 8;
+  const bf16* const grow0 = Gs + li * LDR + h2 * 8;
+  const bf16* const qtr0 = Qs + tr_lane_off(LDR, lane);
+  const bf16* const gtr0 = Gs + tr_lane_off(LDR, lane);
   for (int kb = wave; kb < NB; kb += 4) {
     int key = kb * 32 + li;
     int kc = key < T ? key : T - 1;
@@ -368,24 +403,35 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
     for (int d = 0; d < DB; ++d)
 #pragma unroll
       for (int r = 0; r < 16; ++r) { dk[d][r] = 0.f; dv[d][r] = 0.f; }
+    const bf16* qrow = qrow0;
+    const bf16* grow = grow0;
+    const bf16* qtr = qtr0;
+    const bf16* gtr = gtr0;
+    const float* lsq = ls + h2 * 4;
+    const float* dlq = dl + h2 * 4;
 #pragma unroll 1
-    for (int qb = 0; qb < NB; ++qb) {
+    for (int qb = 0; qb < NB; ++qb, qrow += 32 * LDR, grow += 32 * LDR, qtr += 32 * LDR, gtr += 32 * LDR, lsq += 32, dlq += 32) {
       f32x16 s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 a = *reinterpret_cast<const bf16x8*>(Qs + (qb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fk[ks], s, 0, 0, 0);
-        bf16x8 g = *reinterpret_cast<const bf16x8*>(Gs + (qb * 32 + li) * LDR + ks * 16 + h2 * 8);
+        bf16x8 g = *reinterpret_cast<const bf16x8*>(grow + ks * 16);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(g, fv[ks], dp, 0, 0, 0);
       }
       float p[16], ds[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        int qi = qb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
-        p[r] = __builtin_amdgcn_exp2f(s[r] * sl2 - ls[qi]);  // padding rows: lse = +inf -> 0
-        ds[r] = p[r] * (dp[r] - dl[qi]);
+      for (int g4 = 0; g4 < 4; ++g4) {   // accumulator registers 4 g4 .. 4 g4 + 3 are four consecutive queries
+        float4 lv = *reinterpret_cast<const float4*>(lsq + g4 * 8), dv4 = *reinterpret_cast<const float4*>(dlq + g4 * 8);
+        float lr[4] = {lv.x, lv.y, lv.z, lv.w}, dr[4] = {dv4.x, dv4.y, dv4.z, dv4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          int r = g4 * 4 + e;
+          p[r] = __builtin_amdgcn_exp2f(s[r] * sl2 - lr[e]);  // padding rows: lse = +inf -> 0
+          ds[r] = p[r] * (dp[r] - dr[e]);
+        }
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -393,9 +439,9 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
         bf16x8 db = pack8(ds + 8 * t);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
-          bf16x8 ag = frag_tr(Gs, LDR, d * 32, qb * 32 + 16 * t, lane);
+          bf16x8 ag = frag_tr_at(gtr, LDR, 16 * t * LDR + d * 32);
           dv[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ag, pb, dv[d], 0, 0, 0);
-          bf16x8 aq = frag_tr(Qs, LDR, d * 32, qb * 32 + 16 * t, lane);
+          bf16x8 aq = frag_tr_at(qtr, LDR, 16 * t * LDR + d * 32);
           dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, db, dk[d], 0, 0, 0);
         }
       }
