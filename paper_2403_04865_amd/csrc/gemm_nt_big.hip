@@ -126,16 +126,18 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     }
   }
 
+  // (every lambda below is forced inline: left to its size heuristics the compiler keeps some of them as calls,
+  // and the register arrays they touch would then live in memory)
   // tile id -> (row tile, column tile): ids are dealt round-robin to the XCDs and the column tiles of one
   // row panel get consecutive slots of one XCD (the grid size is a multiple of 8)
-  auto tile_of = [&](int id, long long& m0, int& n0) {
+  auto tile_of = [&](int id, long long& m0, int& n0) __attribute__((always_inline)) {
     int xcd = id % NXCD, slot = id / NXCD;
     int mt = (slot / NTL) * NXCD + xcd;
     m0 = (long long)mt * BM;
     n0 = (slot % NTL) * BN;
     return mt < MT;
   };
-  auto next_valid = [&](int id, long long& m0, int& n0) {
+  auto next_valid = [&](int id, long long& m0, int& n0) __attribute__((always_inline)) {
     while (id < total && !tile_of(id, m0, n0)) id += gridDim.x;
     return id;
   };
@@ -143,42 +145,39 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   // ---- operand loads: uniform base + 32-bit per-thread byte offsets --------------------------------------
   const bf16* Ab;
   const bf16* Bb;
-  unsigned aoff[CA], boff[CB];
+  // chunk i of a thread is row0 + 32 i: one per-thread offset plus a uniform row stride serves all chunks.
+  // Rows past the end of A (last row tile only) are redirected to row M - 1 by clamping the offset: they are
+  // loaded (valid memory) but never stored.
+  const unsigned aoff0 = 2u * (unsigned)(row0 * (int)g.lda + kc * 8), boff0 = 2u * (unsigned)(row0 * (int)g.ldb + kc * 8);
+  const unsigned astride = 2u * RSTEP * (unsigned)g.lda, bstride = 2u * RSTEP * (unsigned)g.ldb;  // bytes
+  unsigned amax = 0xffffffffu;   // largest valid offset of this thread: (M - 1 - m0) rows + its chunk column
   u32x4 ra[2][CA], rb[CB];   // A: two register slots (loads up to three steps ahead, it may miss to HBM); B: one (L2 hits)
   float rbias = 0.f;
-  bool off_special = true;   // aoff must be (re)built
-#pragma unroll
-  for (int i = 0; i < CB; ++i) boff[i] = 2u * (unsigned)((row0 + i * RSTEP) * (int)g.ldb + kc * 8);  // N % 192 == 0: no clamp
-  auto set_offsets_a = [&](long long m0) {
-    long long base_row = g.amap.map32((unsigned)m0);
-    Ab = (const bf16*)g.A + base_row * g.lda;
-    // per-thread offsets depend on the tile only through the row map and the clamp at the last row:
-    // they are rebuilt for such tiles (and for the tile after one), otherwise kept
-    bool special = g.amap.g2 != 0 || m0 + BM > g.M;
-    if (special || off_special) {
-#pragma unroll
-      for (int i = 0; i < CA; ++i) {
-        unsigned am = (unsigned)m0 + (unsigned)(row0 + i * RSTEP);  // M < 2^31
-        if (am > (unsigned)g.M - 1u) am = (unsigned)g.M - 1u;  // rows past the end are loaded (valid memory) but never stored
-        aoff[i] = 2u * (unsigned)((g.amap.map32(am) - base_row) * g.lda + kc * 8);
-      }
-    }
-    off_special = special;
+  auto set_offsets_a = [&](long long m0) __attribute__((always_inline)) {
+    Ab = (const bf16*)g.A + m0 * g.lda;
+    amax = m0 + BM > g.M ? 2u * (unsigned)((g.M - 1 - m0) * g.lda + kc * 8) : 0xffffffffu;
   };
-  auto set_offsets_b = [&](int n0) {
+  auto set_offsets_b = [&](int n0) __attribute__((always_inline)) {
     Bb = (const bf16*)g.B + (long long)n0 * g.ldb;
     if (HAS_BIAS && tid < BN) rbias = g.bias[n0 + tid];  // else stays 0
   };
-  auto issue_a = [&](auto slot, int k0) {
+  auto load_a = [&](int i, int k0) __attribute__((always_inline)) {
+    unsigned off = aoff0 + (unsigned)i * astride;
+    return ldg16((const char*)(Ab + k0), off < amax ? off : amax);
+  };
+  auto load_b = [&](int i, int k0) __attribute__((always_inline)) {
+    return ldg16((const char*)(Bb + k0) + (unsigned)i * bstride, boff0);   // N % 192 == 0: no clamp
+  };
+  auto issue_a = [&](auto slot, int k0) __attribute__((always_inline)) {
     constexpr int S = decltype(slot)::value;
 #pragma unroll
-    for (int i = 0; i < CA; ++i) ra[S][i] = ldg16((const char*)(Ab + k0), aoff[i]);
+    for (int i = 0; i < CA; ++i) ra[S][i] = load_a(i, k0);
   };
-  auto issue_b = [&](int k0) {
+  auto issue_b = [&](int k0) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < CB; ++i) rb[i] = ldg16((const char*)(Bb + k0), boff[i]);
+    for (int i = 0; i < CB; ++i) rb[i] = load_b(i, k0);
   };
-  auto stash = [&](auto slot) {
+  auto stash = [&](auto slot) __attribute__((always_inline)) {
     constexpr int S = decltype(slot)::value;
     bf16* st = S ? ring1 : ring0;
 #pragma unroll
@@ -191,7 +190,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   f32x16 acc[WBM][WBN];
   bf16x8 fa[2][WBM], fb[2][WBN];   // two buffers of one 16-wide slice each
   // fragment t (0..3: A row blocks, 4..6: B column blocks) of slice KS of stage S -> buffer BF
-  auto rd_one = [&](auto slot, auto slice, auto buf, auto frag) {
+  auto rd_one = [&](auto slot, auto slice, auto buf, auto frag) __attribute__((always_inline)) {
     constexpr int S = decltype(slot)::value, KS = decltype(slice)::value, BF = decltype(buf)::value;
     constexpr int T = decltype(frag)::value;
     const bf16* st = S ? ring1 : ring0;
@@ -204,7 +203,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     }
   };
   // LDS write w of the next stage: 0..7 the A chunks of register slot S, 8..13 the B chunks
-  auto wr_one = [&](auto slot, auto idx) {
+  auto wr_one = [&](auto slot, auto idx) __attribute__((always_inline)) {
     constexpr int S = decltype(slot)::value, W = decltype(idx)::value;
     bf16* st = S ? ring1 : ring0;
     if constexpr (W < CA) *reinterpret_cast<u32x4*>(st + soff + W * RSTEP * LDT) = ra[S][W];
@@ -213,12 +212,12 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   // global load l of a step: 0..5 the B chunks (they are needed first and hit L2), 6..13 the A chunks.
   // Loads return in order: the B chunks, issued one step before their LDS writes, do not wait for younger A
   // loads that may miss to HBM.
-  auto ld_one = [&](auto slot, auto idx, int ka, int kb) {
+  auto ld_one = [&](auto slot, auto idx, int ka, int kb) __attribute__((always_inline)) {
     constexpr int S = decltype(slot)::value, Lx = decltype(idx)::value;
-    if constexpr (Lx < CB) rb[Lx] = ldg16((const char*)(Bb + kb), boff[Lx]);
-    else ra[S][Lx - CB] = ldg16((const char*)(Ab + ka), aoff[Lx - CB]);
+    if constexpr (Lx < CB) rb[Lx] = load_b(Lx, kb);
+    else ra[S][Lx - CB] = load_a(Lx - CB, ka);
   };
-  auto mfma_one = [&](auto buf, auto tt) {
+  auto mfma_one = [&](auto buf, auto tt) __attribute__((always_inline)) {
     constexpr int BF = decltype(buf)::value, T = decltype(tt)::value, i = T / WBN, j = T % WBN;
     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[BF][j], fa[BF][i], acc[i][j], 0, 0, 0);
   };
@@ -233,7 +232,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   u32x2 park[WBM - 1][WBN][4];
   long long pmw = 0;   // first row / column of the parked block (uniform)
   int pnw = 0;
-  u32x4 rowdat[NPASS], auxv[NPASS];
+  u32x4 rowdat[NPASS], auxv[2][NPASS];   // auxiliary row segments of two strips: one in use, one in flight
   const int er = lane < 60 ? lane / 12 : 0;    // row inside a pass (idle lanes: a valid address)
   const int erc = lane < 60 ? lane / 12 : 64;  // the same for comparisons: idle lanes never pass
   const int esg = lane % 12;
@@ -246,37 +245,37 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   const char* const aux_ptr = (const char*)(MODE == EPI_BIAS_RESID ? g.resid : g.pre);
 
   // rows of strip I of the parked block that exist (uniform, may be <= 0)
-  auto strip_lim = [&](int I) {
+  auto strip_lim = [&](int I) __attribute__((always_inline)) {
     long long r = g.M - (pmw + I * 32);
     return r > 32 ? 32 : (int)r;
   };
-  auto bg_w = [&](auto ic, auto wc) {
+  auto bg_w = [&](auto ic, auto wc) __attribute__((always_inline)) {
     constexpr int I = decltype(ic)::value, W = decltype(wc)::value, j = W / 4, q = W % 4;
     *reinterpret_cast<u32x2*>(pw + j * 64 + q * 16) = park[I - 1][j][q];
   };
-  auto bg_r = [&](auto pc) {
+  auto bg_r = [&](auto pc) __attribute__((always_inline)) {
     constexpr int p = decltype(pc)::value;
     rowdat[p] = *reinterpret_cast<const u32x4*>(pr + p * 5 * PSB);
   };
-  auto bg_aux = [&](auto ic, auto pc, int lim) {
+  auto bg_aux = [&](auto ic, auto pc, int lim) __attribute__((always_inline)) {
     constexpr int I = decltype(ic)::value, p = decltype(pc)::value;
     if constexpr (HAS_AUX) {
       if (p * 5 < lim) {  // uniform; lanes past the end read the pass's first row (never stored)
         const char* base = aux_ptr + ((pmw + I * 32 + p * 5) * (long long)lda_b + 2 * pnw);
-        auxv[p] = ldg16(base, p * 5 + erc < lim ? eo_a : (unsigned)(esg * 16));
+        auxv[I & 1][p] = ldg16(base, p * 5 + erc < lim ? eo_a : (unsigned)(esg * 16));
       }
     }
   };
   // pass p of strip I: combine the row segment with the auxiliary operand (results stay in registers) ...
   u32x4 res[NPASS], res2[MODE == EPI_BIAS_GELU ? NPASS : 1];
-  auto bg_cmp = [&](auto pc) {
-    constexpr int p = decltype(pc)::value;
+  auto bg_cmp = [&](auto ic, auto pc) __attribute__((always_inline)) {
+    constexpr int I = decltype(ic)::value, p = decltype(pc)::value;
     if constexpr (MODE == EPI_PLAIN || MODE == EPI_BIAS) {
       res[p] = rowdat[p];
     } else if constexpr (MODE == EPI_BIAS_RESID || MODE == EPI_DGELU) {
       float v[8], t[8];
       unpack8(rowdat[p], v);
-      unpack8(auxv[p], t);
+      unpack8(auxv[I & 1][p], t);
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = MODE == EPI_DGELU ? v[e] * t[e] : v[e] + t[e];
       res[p] = pack8(v);
@@ -297,7 +296,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   // ... and its stores.  They are issued after the step's operand loads: memory operations complete in
   // order, so loads queued behind stores wait for the stores to drain, and the loads of one step are
   // needed one step later; stores at the end of a step have two steps to complete before anything waits.
-  auto bg_put = [&](auto ic, auto pc, int lim) {
+  auto bg_put = [&](auto ic, auto pc, int lim) __attribute__((always_inline)) {
     constexpr int I = decltype(ic)::value, p = decltype(pc)::value;
     if (p * 5 < lim) {  // uniform
       bool ok = p * 5 + erc < lim;
@@ -317,33 +316,36 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   // (A: register slot S^1, loaded two steps ago; B: loaded one step ago) is completely written, so the
   // fragments of the next step's slice 0 are fetched under the MFMAs of slice 3 and no wavefront starts a
   // step with an empty MFMA pipe.  The registers are re-used for A three steps and B two steps ahead
-  // (element offsets ka, kb).  BG = 0: nothing else; BG = 1 + I: strip I of the previous tile's block is
+  // (element offsets ka, kb).  BG = 0: nothing else; BG < 0: only the auxiliary loads of strip 0; BG = 1 + I: strip I of the previous tile's block is
   // moved through the patch and stored.
-  auto step = [&](auto slot, auto bgc, int ka, int kb) {
+  auto step = [&](auto slot, auto bgc, int ka, int kb) __attribute__((always_inline)) {
     constexpr int S = decltype(slot)::value, BG = decltype(bgc)::value, I = BG - 1;
     using SN = IC<S ^ 1>;
     int lim = 0;
     if constexpr (BG > 0) lim = strip_lim(I);
-    static_for<36>([&](auto pc) {
+    static_for<36>([&](auto pc) __attribute__((always_inline)) {
       constexpr int P = decltype(pc)::value, KS = P / 12, T = P % 12;
       mfma_one(IC<KS & 1>{}, IC<T>{});
       if constexpr (T < WBM + WBN) rd_one(slot, IC<KS + 1>{}, IC<(KS + 1) & 1>{}, IC<T>{});
       if constexpr (KS < 2 && T >= 7) wr_one(SN{}, IC<KS * 5 + T - 7>{});
       if constexpr (KS == 2 && T < 4) wr_one(SN{}, IC<10 + T>{});
       if constexpr (KS == 2 && T >= 7) ld_one(SN{}, IC<T - 7>{}, ka, kb);
+      if constexpr (BG < 0) {
+        if constexpr (P < NPASS) bg_aux(IC<0>{}, IC<P>{}, strip_lim(0));   // strip 0 is processed in the next step
+      }
       if constexpr (BG > 0) {
-        if constexpr (P < NPASS) bg_aux(IC<I>{}, IC<P>{}, lim);
+        if constexpr (P < NPASS && I + 1 < WBM) bg_aux(IC<I + 1>{}, IC<P>{}, strip_lim(I + 1));   // needed one step later
         if constexpr (I > 0 && P < 12) bg_w(IC<I>{}, IC<P>{});
         if constexpr (P >= 17 && (P - 17) % 4 == 0 && (P - 17) / 4 < NPASS) bg_r(IC<(P - 17) / 4>{});
         if constexpr (P >= 20 && (P - 20) % 4 == 0 && (P - 20) / 4 < NPASS) {
-          bg_cmp(IC<(P - 20) / 4>{});
+          bg_cmp(IC<I>{}, IC<(P - 20) / 4>{});
           if constexpr (!LATE_STORES) bg_put(IC<I>{}, IC<(P - 20) / 4>{}, lim);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
     });
     __syncthreads();
-    static_for<12>([&](auto tc) {
+    static_for<12>([&](auto tc) __attribute__((always_inline)) {
       constexpr int T = decltype(tc)::value, P = 36 + T;
       mfma_one(IC<1>{}, tc);
       if constexpr (T < WBM + WBN) rd_one(SN{}, IC<0>{}, IC<0>{}, tc);
@@ -351,7 +353,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
       if constexpr (BG > 0) {
         if constexpr (P >= 17 && (P - 17) % 4 == 0 && (P - 17) / 4 < NPASS) bg_r(IC<(P - 17) / 4>{});
         if constexpr (P >= 20 && (P - 20) % 4 == 0 && (P - 20) / 4 < NPASS) {
-          bg_cmp(IC<(P - 20) / 4>{});
+          bg_cmp(IC<I>{}, IC<(P - 20) / 4>{});
           if constexpr (!LATE_STORES) bg_put(IC<I>{}, IC<(P - 20) / 4>{}, lim);
         }
         if constexpr (LATE_STORES && T == 9) { bg_put(IC<I>{}, IC<0>{}, lim); bg_put(IC<I>{}, IC<1>{}, lim); }
@@ -363,14 +365,14 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   };
 
   // the same strip work on its own (after the last tile)
-  auto strip_alone = [&](auto ic) {
+  auto strip_alone = [&](auto ic) __attribute__((always_inline)) {
     constexpr int I = decltype(ic)::value;
     int lim = strip_lim(I);
-    static_for<NPASS>([&](auto pc) { bg_aux(ic, pc, lim); });
-    if constexpr (I > 0) static_for<12>([&](auto wc) { bg_w(ic, wc); });
-    static_for<NPASS>([&](auto pc) { bg_r(pc); });
-    static_for<NPASS>([&](auto pc) { bg_cmp(pc); });
-    static_for<NPASS>([&](auto pc) { bg_put(ic, pc, lim); });
+    static_for<NPASS>([&](auto pc) __attribute__((always_inline)) { bg_aux(ic, pc, lim); });
+    if constexpr (I > 0) static_for<12>([&](auto wc) __attribute__((always_inline)) { bg_w(ic, wc); });
+    static_for<NPASS>([&](auto pc) __attribute__((always_inline)) { bg_r(pc); });
+    static_for<NPASS>([&](auto pc) __attribute__((always_inline)) { bg_cmp(ic, pc); });
+    static_for<NPASS>([&](auto pc) __attribute__((always_inline)) { bg_put(ic, pc, lim); });
   };
 
   long long m0, m1;
@@ -395,14 +397,14 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   __builtin_amdgcn_sched_barrier(0);
   if (tid < BN) lbias_all[tid] = rbias;
   __syncthreads();
-  static_for<WBM + WBN>([&](auto tc) { rd_one(IC<0>{}, IC<0>{}, IC<0>{}, tc); });
+  static_for<WBM + WBN>([&](auto tc) __attribute__((always_inline)) { rd_one(IC<0>{}, IC<0>{}, IC<0>{}, tc); });
 
   // One tile: K steps 0 .. nk - 1 (nk even, >= 6); steps 1..4 carry the strips of the block parked by the
   // tile before (BGON).  Loads run ahead into the next tile: its A offsets are in place before step nk - 3,
   // its B offsets before step nk - 2.  The last step stores the next tile's first stage and fetches its
   // first fragments like any other step, so the MFMA pipe only waits while the accumulators are parked.
-  auto koff = [&](int x) { return (x >= nk ? x - nk : x) * BK; };
-  auto run_tile = [&](auto bgon) {
+  auto koff = [&](int x) __attribute__((always_inline)) { return (x >= nk ? x - nk : x) * BK; };
+  auto run_tile = [&](auto bgon) __attribute__((always_inline)) {
     constexpr bool BGON = decltype(bgon)::value;
     const long long mw = m0 + wm * (WBM * 32);
     const int nw = n0 + wn * (WBN * 32);
@@ -418,11 +420,11 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
           acc[i][j][4 * q] = b.x; acc[i][j][4 * q + 1] = b.y; acc[i][j][4 * q + 2] = b.z; acc[i][j][4 * q + 3] = b.w;
         }
       }
-    auto pre = [&](int s) {
+    auto pre = [&](int s) __attribute__((always_inline)) {
       if (s == nk - 3) set_offsets_a(m1);
       if (s == nk - 2) set_offsets_b(n1);
     };
-    pre(0); step(IC<0>{}, IC<0>{}, koff(3), koff(2));
+    pre(0); step(IC<0>{}, IC<(BGON && HAS_AUX) ? -1 : 0>{}, koff(3), koff(2));
     pre(1); step(IC<1>{}, IC<BGON ? 1 : 0>{}, koff(4), koff(3));
     pre(2); step(IC<0>{}, IC<BGON ? 2 : 0>{}, koff(5), koff(4));
     pre(3); step(IC<1>{}, IC<BGON ? 3 : 0>{}, koff(6), koff(5));
@@ -477,7 +479,7 @@ bool gemm_nt_big_ok(const GemmNT& g) {
                g.K >= MIN_STEPS * BK && g.M >= 4096;
   bool mode = g.epi == EPI_PLAIN || g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_DGELU ||
               (g.epi == EPI_BIAS_RESID && sizeof(rs_bf16path_t) == 2);
-  return shape && mode;
+  return shape && mode && g.amap.g2 == 0;
 }
 
 template <int MODE>
