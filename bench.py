@@ -31,6 +31,15 @@ def model_flops_per_tile(cfg):
     return fwd + bwd
 
 
+# what the exact pruning of the last block leaves out (its output is read at the CLS row only: projection and MLP on
+# one row instead of T, attention for one query instead of T), forward + backward
+def pruned_flops_per_tile(cfg):
+    T, D, F, H = cfg.tokens, cfg.dim, cfg.ffn, cfg.heads
+    dh = D // H
+    rows = (T - 1) * (2 * D * D + 2 * 2 * D * F) + 2 * 2 * H * (T - 1) * T * dh
+    return 3 * rows
+
+
 PEAK = {"mfma_bf16": 2.5e15, "hbm": 8e12}
 
 
@@ -214,7 +223,7 @@ def main():
 
     ms_per_step = dt / a.steps * 1e3
     tiles_per_s = N * a.steps / dt
-    mflops = model_flops_per_tile(cfg)
+    mflops = model_flops_per_tile(cfg) - pruned_flops_per_tile(cfg)   # the bf16 path prunes the last block
     mfu = tiles_per_s * mflops / PEAK["mfma_bf16"]
     tr = load_traffic(a.workload, a.prof_kernel) if not a.tiles else None
     hbm_bound = a.prof_kernel in ("ln_fwd", "ln_bwd", "pool_fwd", "pool_bwd", "colsum", "elementwise")
@@ -254,6 +263,7 @@ def main():
                                f"x {cfg.heads} heads, gated-attention MIL hidden {cfg.mil_hidden}, {cfg.n_classes} classes",
                    "tiles": N, "slide_steps_per_s": round(a.steps / dt, 4),
                    "model_gflop_per_tile": round(mflops / 1e9, 3), "mfu_bf16_peak": round(mfu, 4),
+                   "last_block": "CLS row only after attention (exact; its FLOPs are not counted)",
                    "activation_policy": "block inputs + re-run blocks in backward" if recompute else "all block activations kept",
                    "arena_gb": round(nbytes / 1e9, 2), "peak_alloc_gb_of_288": round(peak_alloc, 2),
                    "loss": float(loss.item()), "input_gen_s": round(gen_s, 1)},

@@ -7,9 +7,10 @@
 
 namespace sl {
 
-hipError_t launch_attn_fwd_mfma(const void* qkv, void* O, float* lse, long long n, int T, int H, int dh, hipStream_t s);
+hipError_t launch_attn_fwd_mfma(const void* qkv, void* O, float* lse, long long n, int T, int H, int dh, int cls_only,
+                                hipStream_t s);
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
-                                long long n, int T, int H, int dh, hipStream_t s);
+                                long long n, int T, int H, int dh, int cls_only, hipStream_t s);
 bool attn_mfma_ok(int T, int dh);
 
 template <typename T, int DH>
@@ -162,10 +163,13 @@ static hipError_t set_lds(K kernel, size_t bytes) {
   return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
+bool attn_cls_only_ok(int dt, int T, int dh, bool use_mfma) { return dt == DT_BF16 && use_mfma && attn_mfma_ok(T, dh); }
+
 hipError_t launch_attn_fwd(int dt, const void* qkv, void* O, float* lse, long long n, int T, int H, int dh,
-                           bool use_mfma, hipStream_t s) {
+                           bool use_mfma, hipStream_t s, bool cls_only) {
   if (n <= 0) return hipSuccess;
-  if (dt == DT_BF16 && use_mfma && attn_mfma_ok(T, dh)) return launch_attn_fwd_mfma(qkv, O, lse, n, T, H, dh, s);
+  if (dt == DT_BF16 && use_mfma && attn_mfma_ok(T, dh)) return launch_attn_fwd_mfma(qkv, O, lse, n, T, H, dh, cls_only, s);
+  if (cls_only) return hipErrorInvalidValue;
   size_t lds = attn_lds_bytes(T, dh);
   dim3 grid((unsigned)(n * H));
   hipError_t e = hipSuccess;
@@ -182,9 +186,11 @@ hipError_t launch_attn_fwd(int dt, const void* qkv, void* O, float* lse, long lo
 }
 
 hipError_t launch_attn_bwd(int dt, const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
-                           long long n, int T, int H, int dh, bool use_mfma, hipStream_t s) {
+                           long long n, int T, int H, int dh, bool use_mfma, hipStream_t s, bool cls_only) {
   if (n <= 0) return hipSuccess;
-  if (dt == DT_BF16 && use_mfma && attn_mfma_ok(T, dh)) return launch_attn_bwd_mfma(qkv, O, lse, dO, dqkv, n, T, H, dh, s);
+  if (dt == DT_BF16 && use_mfma && attn_mfma_ok(T, dh))
+    return launch_attn_bwd_mfma(qkv, O, lse, dO, dqkv, n, T, H, dh, cls_only, s);
+  if (cls_only) return hipErrorInvalidValue;
   size_t lds = attn_lds_bytes(T, dh);
   dim3 grid((unsigned)(n * H));
   hipError_t e = hipSuccess;

@@ -130,7 +130,7 @@ template <int NB> constexpr int attn_threads() { return NB >= 7 ? NB * 64 : 256;
 // --------------------------------------------------------------------------------------------
 template <int DH, int NB>
 __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const bf16* __restrict__ qkv, bf16* __restrict__ O,
-                                                       float* __restrict__ lse, int T, int H, long long ntiles) {
+                                                       float* __restrict__ lse, int T, int H, long long ntiles, int cls_only) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
@@ -152,7 +152,8 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
   // lane-dependent parts of the LDS addresses, formed once; the key-block loop only advances them
   const bf16* const krow0 = Ks + li * LDR + h2 * 8;
   const bf16* const vtr0 = Vs + tr_lane_off(LDR, lane);
-  for (int qb = wave; qb < NB; qb += attn_threads<NB>() / 64) {
+  const int nqb = cls_only ? 1 : NB;   // cls_only: only query 0 is needed (its block of 32 is computed)
+  for (int qb = wave; qb < nqb; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
     int qc = q < T ? q : T - 1;
     bf16x8 fq[KS];
@@ -243,7 +244,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
 template <int DH, int NB>
 __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
-                                                         bf16* __restrict__ dqkv, int T, int H, long long ntiles) {
+                                                         bf16* __restrict__ dqkv, int T, int H, long long ntiles, int cls_only) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
@@ -269,6 +270,15 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
   for (int qb = wave; qb < NB; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
     int qc = q < T ? q : T - 1;
+    if (cls_only && qb > 0) {   // uniform: the output gradient is zero for these queries, and so is dQ
+      if (q < T) {
+        bf16* out = dqkv + (tile * T + q) * gs + h * DH;
+#pragma unroll
+        for (int c = 0; c < DH / 8; ++c)
+          if ((c & 1) == h2) *reinterpret_cast<u32x4*>(out + c * 8) = u32x4{0, 0, 0, 0};   // the row's two lanes share it
+      }
+      continue;
+    }
     bf16x8 fq[KS], fdo[KS];
     float delta = 0.f;
     const bf16* orow = O + (tile * T + qc) * D + h * DH;
@@ -277,6 +287,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
     for (int ks = 0; ks < KS; ++ks) {
       fq[ks] = as_bf16x8(ldg16(base + qc * gs + ks * 16 + h2 * 8));
       fdo[ks] = as_bf16x8(ldg16(gor + ks * 16 + h2 * 8));
+      if (cls_only && q != 0) fdo[ks] = as_bf16x8(u32x4{0, 0, 0, 0});   // only query 0 carries a gradient; the rest of dO is not defined
       bf16x8 fo = as_bf16x8(ldg16(orow + ks * 16 + h2 * 8));
 #pragma unroll
       for (int i = 0; i < 8; ++i) delta += (float)fdo[ks][i] * (float)fo[i];
@@ -346,7 +357,7 @@ template <int DH, int NB>
 // compute unit, would leave it, and measured slower with seven and one workgroup)
 __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
-                                                         bf16* __restrict__ dqkv, int T, int H, long long ntiles) {
+                                                         bf16* __restrict__ dqkv, int T, int H, long long ntiles, int cls_only) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Qs = reinterpret_cast<bf16*>(smem);   // [TP][LDR]
@@ -363,11 +374,12 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
   const bf16* base = qkv + tile * T * gs + h * DH;
   const bf16* gbase = dO + tile * T * (long long)D + h * DH;
   const bf16* obase = O + tile * T * (long long)D + h * DH;
+  const int TG = cls_only ? 1 : T;   // rows of dO that are defined (cls_only: query 0 alone carries a gradient)
   load_rm<DH>(base, gs, T, TP, Qs);
-  load_rm<DH>(gbase, D, T, TP, Gs);
+  load_rm<DH>(gbase, D, TG, TP, Gs);
   for (int i = threadIdx.x; i < TP; i += blockDim.x) {
     float d = 0.f, lv = INFINITY;
-    if (i < T) {
+    if (i < TG) {
 #pragma unroll
       for (int c = 0; c < DH / 8; ++c) {
         bf16x8 a = as_bf16x8(ldg16(gbase + (long long)i * D + c * 8));
@@ -409,8 +421,9 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
     const bf16* gtr = gtr0;
     const float* lsq = ls + h2 * 4;
     const float* dlq = dl + h2 * 4;
+    const int nqb = cls_only ? 1 : NB;
 #pragma unroll 1
-    for (int qb = 0; qb < NB; ++qb, qrow += 32 * LDR, grow += 32 * LDR, qtr += 32 * LDR, gtr += 32 * LDR, lsq += 32, dlq += 32) {
+    for (int qb = 0; qb < nqb; ++qb, qrow += 32 * LDR, grow += 32 * LDR, qtr += 32 * LDR, gtr += 32 * LDR, lsq += 32, dlq += 32) {
       f32x16 s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
@@ -479,28 +492,28 @@ hipError_t set_lds(K kernel, size_t bytes) {
 }
 
 template <int DH, int NB>
-hipError_t fwd_go(const void* qkv, void* O, float* lse, long long n, int T, int H, hipStream_t s) {
+hipError_t fwd_go(const void* qkv, void* O, float* lse, long long n, int T, int H, int cls_only, hipStream_t s) {
   size_t lds = fwd_lds<DH, NB>();
   hipError_t e = set_lds(attn_fwd_mfma_k<DH, NB>, lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_fwd_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(attn_threads<NB>()), lds, s,
-                     (const bf16*)qkv, (bf16*)O, lse, T, H, n);
+                     (const bf16*)qkv, (bf16*)O, lse, T, H, n, cls_only);
   return hipGetLastError();
 }
 
 template <int DH, int NB>
 hipError_t bwd_go(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv, long long n, int T,
-                  int H, hipStream_t s) {
+                  int H, int cls_only, hipStream_t s) {
   size_t lq = bq_lds<DH, NB>(), lk = bk_lds<DH, NB>();
   hipError_t e = set_lds(attn_bwd_q_mfma_k<DH, NB>, lq);
   if (e != hipSuccess) return e;
   e = set_lds(attn_bwd_k_mfma_k<DH, NB>, lk);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_bwd_q_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(attn_threads<NB>()), lq, s,
-                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n);
+                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n, cls_only);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((attn_bwd_k_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(256), lk, s,
-                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n);
+                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n, cls_only);
   return hipGetLastError();
 }
 
@@ -512,15 +525,16 @@ bool attn_mfma_ok(int T, int dh) {
   return (dh == 64 && nb == 7) || (dh == 32 && nb == 1);
 }
 
-hipError_t launch_attn_fwd_mfma(const void* qkv, void* O, float* lse, long long n, int T, int H, int dh, hipStream_t s) {
-  if (dh == 64) return fwd_go<64, 7>(qkv, O, lse, n, T, H, s);
-  return fwd_go<32, 1>(qkv, O, lse, n, T, H, s);
+hipError_t launch_attn_fwd_mfma(const void* qkv, void* O, float* lse, long long n, int T, int H, int dh, int cls_only,
+                                hipStream_t s) {
+  if (dh == 64) return fwd_go<64, 7>(qkv, O, lse, n, T, H, cls_only, s);
+  return fwd_go<32, 1>(qkv, O, lse, n, T, H, cls_only, s);
 }
 
 hipError_t launch_attn_bwd_mfma(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
-                                long long n, int T, int H, int dh, hipStream_t s) {
-  if (dh == 64) return bwd_go<64, 7>(qkv, O, lse, dO, dqkv, n, T, H, s);
-  return bwd_go<32, 1>(qkv, O, lse, dO, dqkv, n, T, H, s);
+                                long long n, int T, int H, int dh, int cls_only, hipStream_t s) {
+  if (dh == 64) return bwd_go<64, 7>(qkv, O, lse, dO, dqkv, n, T, H, cls_only, s);
+  return bwd_go<32, 1>(qkv, O, lse, dO, dqkv, n, T, H, cls_only, s);
 }
 
 }  // namespace sl

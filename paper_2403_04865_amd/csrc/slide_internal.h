@@ -162,10 +162,14 @@ hipError_t launch_ln_bwd(int dt, const void* x, long long x_stride, const void* 
                          long long rows, int D, float eps, float* part, bool dy_f32, hipStream_t s);
 
 // Attention over qkv [n*T, 3D] (T): O [n*T, D] (T), lse [n,H,T] fp32.
+// cls_only (bf16 MFMA kernels only, see attn_cls_only_ok): only query 0 of every tile is wanted (forward: the rest
+// of O and lse beyond the first block of 32 queries is not written) / only query 0 carries an output gradient
+// (backward: other rows of dO are not read; dqkv is complete: dQ is zero for every other query).
+bool attn_cls_only_ok(int dt, int T, int dh, bool use_mfma);
 hipError_t launch_attn_fwd(int dt, const void* qkv, void* O, float* lse, long long n, int T, int H, int dh,
-                           bool use_mfma, hipStream_t s);
+                           bool use_mfma, hipStream_t s, bool cls_only = false);
 hipError_t launch_attn_bwd(int dt, const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
-                           long long n, int T, int H, int dh, bool use_mfma, hipStream_t s);
+                           long long n, int T, int H, int dh, bool use_mfma, hipStream_t s, bool cls_only = false);
 size_t attn_lds_bytes(int T, int dh);
 
 // Gated-attention MIL pool.

@@ -303,6 +303,14 @@ int check_bound(const slide_ctx* c) {
 // One transformer block forward: x_in(l) -> x_in(l+1), leaving qkv, O, lse, x_mid, the MLP activation
 // a = gelu(m) and gelu'(m) of block l in their (per-block or shared) arena slots.  `replay` (backward of the
 // block-inputs-only policy): x_in(l+1) is already stored, so the fc2 GEMM is skipped.
+// The last block's output is only read at the CLS rows (final LayerNorm of token 0), so everything of it that
+// works row by row - projection, LN2, MLP - runs on those n rows alone (they are rows 0, T, 2T, ... of the token
+// matrices: leading dimension T * D), and its attention needs query 0 only.  K and V still need every token, so LN1
+// and the QKV GEMM stay dense.  Exact, not an approximation; taken where the attention kernels support it.
+bool prune_last_block(const slide_ctx* c) {
+  return attn_cls_only_ok(c->dt, c->T, c->dh, c->use_mfma) && rs_size(c->dt) == elem_size(c->dt) && !getenv("SLIDE_NO_PRUNE");
+}
+
 void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
   slide_ctx* c = r.c;
   hipStream_t s = r.s;
@@ -326,6 +334,31 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
     g.A = u; g.lda = D; g.B = weight(c, wi + 0); g.ldb = D; g.M = M; g.N = 3 * D; g.K = D;
     g.epi = EPI_BIAS; g.bias = c->params + o.qkvb; g.out = qkv; g.ldc = 3 * D;
     gemm_nt(r, g);
+  }
+  if (l == c->L - 1 && !replay && prune_last_block(c)) {
+    long long TD = (long long)T * D;
+    launch(r, K_ATTN_FWD, 4.0 * n * c->H * (double)T * c->dh, (double)M * 2 * D * elem_size(dt),
+           [&] { return launch_attn_fwd(dt, qkv, O, lse, n, T, c->H, c->dh, c->use_mfma, s, true); });
+    {
+      GemmNT g{};
+      g.A = O; g.lda = TD; g.B = weight(c, wi + 1); g.ldb = D; g.M = n; g.N = D; g.K = D;
+      g.epi = EPI_BIAS_RESID; g.bias = c->params + o.projb; g.resid = xin; g.ldr = TD; g.out = xmid; g.ldc = TD;
+      gemm_nt(r, g);
+    }
+    ln_fwd(r, xmid, TD, c->params + o.ln2g, c->params + o.ln2b, u, D, n);
+    {
+      GemmNT g{};
+      g.A = u; g.lda = D; g.B = weight(c, wi + 2); g.ldb = D; g.M = n; g.N = F; g.K = D;
+      g.epi = EPI_BIAS_GELU; g.bias = c->params + o.fc1b; g.out = a; g.ldc = F; g.out2 = m; g.ldc2 = F;
+      gemm_nt(r, g);
+    }
+    {
+      GemmNT g{};
+      g.A = a; g.lda = F; g.B = weight(c, wi + 3); g.ldb = F; g.M = n; g.N = D; g.K = F;
+      g.epi = EPI_BIAS_RESID; g.bias = c->params + o.fc2b; g.resid = xmid; g.ldr = TD; g.out = xout; g.ldc = TD;
+      gemm_nt(r, g);
+    }
+    return;
   }
   launch(r, K_ATTN_FWD, 4.0 * n * c->H * (double)T * T * c->dh, (double)M * 4 * D * elem_size(dt),
          [&] { return launch_attn_fwd(dt, qkv, O, lse, n, T, c->H, c->dh, c->use_mfma, s); });
@@ -422,8 +455,49 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
     // block inputs only were kept: re-create this block's activations in the shared slots (the
     // last block's are still there from the forward)
     if (c->cfg.recompute && l != c->L - 1) block_fwd(r, y, l, n, true);
-    // ---- MLP half: x_out = x_mid + gelu(LN2(x_mid) W1^T + b1) W2^T + b2
     char* a = ar + y.e_a + (size_t)l * y.s_a;
+    if (l == c->L - 1 && prune_last_block(c)) {
+      // the gradient of the last block's output is zero away from the CLS rows: its MLP, LN2 and projection
+      // work on those n rows (leading dimension T * D); dxB is zero elsewhere
+      long long TD = (long long)T * D;
+      launch(r, K_ELEMWISE, 0, (double)M * D * rs, [&] { return launch_fill_zero(dxB, (size_t)M * D * rs, s); });
+      {
+        GemmNT g{};
+        g.A = dxAt; g.lda = TD; g.B = weight_t(c, wi + 3); g.ldb = D; g.M = n; g.N = F; g.K = D;
+        g.epi = EPI_DGELU; g.pre = m; g.ldpre = F; g.out = dm; g.ldc = F;
+        gemm_nt(r, g);
+      }
+      gemm_tn(r, dxAt, TD, id, a, F, id, n, D, F, wpart, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
+      ln_fwd(r, xmid, TD, c->params + o.ln2g, c->params + o.ln2b, u, D, n);
+      gemm_tn(r, dm, F, id, u, D, id, n, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
+      {
+        GemmNT g{};
+        g.A = dm; g.lda = F; g.B = weight_t(c, wi + 2); g.ldb = F; g.M = n; g.N = D; g.K = F;
+        g.epi = EPI_PLAIN; g.out = du; g.ldc = D;   // compact [n, D]
+        gemm_nt(r, g);
+      }
+      ln_bwd(r, xmid, TD, du, D, o.ln2g, o.ln2b, dxA, dxB, dxBt, TD, n, lnpart, accumulate);
+      gemm_tn(r, dxBt, TD, id, O, TD, id, n, D, D, wpart, G + o.projW, accumulate, -1, G + o.projb, cpart);
+      {
+        GemmNT g{};
+        g.A = dxBt; g.lda = TD; g.B = weight_t(c, wi + 1); g.ldb = D; g.M = n; g.N = D; g.K = D;
+        g.epi = EPI_PLAIN; g.out = du; g.ldc = TD;   // the CLS rows of dO; the attention backward reads no other
+        gemm_nt(r, g);
+      }
+      launch(r, K_ATTN_BWD, 10.0 * n * c->H * (double)T * c->dh, (double)M * 7 * D * e,
+             [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s, true); });
+      ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
+      gemm_tn(r, dqkv, 3 * D, id, u, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
+      {
+        GemmNT g{};
+        g.A = dqkv; g.lda = 3 * D; g.B = weight_t(c, wi + 0); g.ldb = 3 * D; g.M = M; g.N = D; g.K = 3 * D;
+        g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
+        gemm_nt(r, g);
+      }
+      ln_bwd(r, xin, D, du, D, o.ln1g, o.ln1b, dxB, dxA, dxAt, D, M, lnpart, accumulate);
+      continue;
+    }
+    // ---- MLP half: x_out = x_mid + gelu(LN2(x_mid) W1^T + b1) W2^T + b2
     {  // dm = (dx W2) * gelu'(m), gelu'(m) as stored by the forward
       GemmNT g{};
       g.A = dxAt; g.lda = D; g.B = weight_t(c, wi + 3); g.ldb = D; g.M = M; g.N = F; g.K = D;
