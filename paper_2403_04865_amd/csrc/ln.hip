@@ -277,7 +277,10 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
                                                       const bf16* __restrict__ dy, long long dys,
                                                       const float* __restrict__ gam, const bf16* __restrict__ dres,
                                                       bf16* __restrict__ dxo, long long os, long long rows, float eps,
-                                                      float* __restrict__ part) {
+                                                      float* __restrict__ part, const float* __restrict__ bet,
+                                                      bf16* __restrict__ uo, long long us) {
+  // uo != nullptr: the normalised rows xh * gamma + beta (the forward output, which the weight gradient of the
+  // following linear map needs and the forward did not keep) are written on the way, [rows][us]
   constexpr int D = 128 * NP;
   __shared__ float red[4 * 2 * D];
   int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l16 = lane & 15, grp = lane >> 4;
@@ -333,6 +336,17 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
       }
     s1 = sum16(s1) * (1.0f / D);
     s2 = sum16(s2) * (1.0f / D);
+    if (uo && ok) {
+#pragma unroll
+      for (int k = 0; k < NP; ++k) {
+        int c = (l16 + 16 * k) * 8;
+        float4 b0 = *reinterpret_cast<const float4*>(bet + c), b1 = *reinterpret_cast<const float4*>(bet + c + 4);
+        float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w}, o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = v[k][e] * g[k][e] + bb[e];
+        ln_st8(uo + r * us + c, o);
+      }
+    }
     if (ok) {
 #pragma unroll
       for (int k = 0; k < NP; ++k) {
@@ -494,16 +508,28 @@ int ln_bwd_slabs(long long rows) {
   return (int)s;
 }
 
+// the backward kernel that can also write the normalised rows is the 16-lanes-per-row one
+bool ln_bwd_emits_u(int dt, const void* x, long long x_stride, const void* dy, long long dy_stride, const float* gam,
+                    const void* dres, const void* dx_out, long long o_stride, int D, bool dy_f32, const float* bet,
+                    const void* u_out, long long u_stride) {
+  return dt == DT_BF16 && !dy_f32 && ln_row16_ok(x, dy, dx_out, x_stride, dy_stride, o_stride, D) &&
+         ((uintptr_t)gam & 15) == 0 && ((uintptr_t)dres & 15) == 0 && ((uintptr_t)bet & 15) == 0 &&
+         ((uintptr_t)u_out & 15) == 0 && u_stride % 8 == 0;
+}
+
 hipError_t launch_ln_bwd(int dt, const void* x, long long x_stride, const void* dy, long long dy_stride,
                          const float* gam, const void* dres, void* dx_out, void* dx_out_t, long long o_stride,
-                         long long rows, int D, float eps, float* part, bool dy_f32, hipStream_t s) {
+                         long long rows, int D, float eps, float* part, bool dy_f32, hipStream_t s, const float* bet,
+                         void* u_out, long long u_stride) {
   if (rows <= 0) return hipSuccess;
+  if (u_out && !ln_bwd_emits_u(dt, x, x_stride, dy, dy_stride, gam, dres, dx_out, o_stride, D, dy_f32, bet, u_out, u_stride))
+    return hipErrorInvalidValue;
   dim3 grid(ln_bwd_slabs(rows));
   size_t lds = (size_t)4 * 2 * D * sizeof(float);
   if (dt == DT_BF16 && !dy_f32 && ln_row16_ok(x, dy, dx_out, x_stride, dy_stride, o_stride, D) &&
       ((uintptr_t)gam & 15) == 0 && ((uintptr_t)dres & 15) == 0) {
-    if (D == 384) hipLaunchKernelGGL(ln_bwd_row16_k<3>, grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part);
-    else hipLaunchKernelGGL(ln_bwd_row16_k<6>, grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part);
+    if (D == 384) hipLaunchKernelGGL(ln_bwd_row16_k<3>, grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride);
+    else hipLaunchKernelGGL(ln_bwd_row16_k<6>, grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride);
     return hipGetLastError();
   }
   {

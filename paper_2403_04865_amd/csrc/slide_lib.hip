@@ -275,15 +275,20 @@ void ln_fwd(Run& r, const void* x, long long xs, const float* g, const float* b,
          [&] { return launch_ln_fwd(c->dt, x, xs, g, b, out, os, rows, c->D, c->cfg.ln_eps, out_f32, r.s); });
 }
 
+// u_out: the forward output of this LayerNorm (needed by the weight gradient of the linear map behind it, not kept by
+// the forward) is produced as well: by the backward kernel itself where it can, else by a forward launch
 void ln_bwd(Run& r, const void* x, long long xs, const void* dy, long long dys, size_t o_gam, size_t o_bet,
             const void* dres, void* dxo, void* dxo_t, long long os, long long rows, float* part, int accumulate,
-            bool dy_f32 = false) {
+            bool dy_f32 = false, void* u_out = nullptr) {
   slide_ctx* c = r.c;
   size_t rs = rs_size(c->dt), e = elem_size(c->dt);
-  double bytes = (double)rows * c->D * (rs + e + (dres ? rs : 0) + rs + (rs != e ? e : 0));
+  bool emit = u_out && ln_bwd_emits_u(c->dt, x, xs, dy, dys, c->params + o_gam, dres, dxo, os, c->D, dy_f32,
+                                      c->params + o_bet, u_out, c->D);
+  if (u_out && !emit) ln_fwd(r, x, xs, c->params + o_gam, c->params + o_bet, u_out, c->D, rows);
+  double bytes = (double)rows * c->D * (rs + e + (dres ? rs : 0) + rs + (rs != e ? e : 0) + (emit ? e : 0));
   launch(r, K_LN_BWD, 0, bytes, [&] {
     return launch_ln_bwd(c->dt, x, xs, dy, dys, c->params + o_gam, dres, dxo, dxo_t, os, rows, c->D, c->cfg.ln_eps, part,
-                         dy_f32, r.s);
+                         dy_f32, r.s, c->params + o_bet, emit ? u_out : nullptr, c->D);
   });
   int slabs = ln_bwd_slabs(rows);
   launch(r, K_ELEMWISE, 0, 0, [&] {
@@ -505,15 +510,15 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       gemm_nt(r, g);
     }
     gemm_tn(r, dxAt, D, id, a, F, id, M, D, F, wpart, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
-    ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u, D, M);
-    gemm_tn(r, dm, F, id, u, D, id, M, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
     {
       GemmNT g{};
       g.A = dm; g.lda = F; g.B = weight_t(c, wi + 2); g.ldb = F; g.M = M; g.N = D; g.K = F;
       g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
       gemm_nt(r, g);
     }
-    ln_bwd(r, xmid, D, du, D, o.ln2g, o.ln2b, dxA, dxB, dxBt, D, M, lnpart, accumulate);
+    // LN2 backward also re-creates u = LN2(x_mid), which the fc1 weight gradient needs
+    ln_bwd(r, xmid, D, du, D, o.ln2g, o.ln2b, dxA, dxB, dxBt, D, M, lnpart, accumulate, false, u);
+    gemm_tn(r, dm, F, id, u, D, id, M, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
     // ---- attention half: x_mid = x_in + attn(LN1(x_in)) Wo^T + bo
     gemm_tn(r, dxBt, D, id, O, D, id, M, D, D, wpart, G + o.projW, accumulate, -1, G + o.projb, cpart);
     {
@@ -524,15 +529,14 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
     }
     launch(r, K_ATTN_BWD, 10.0 * n * c->H * (double)T * T * c->dh, (double)M * 9 * D * e,
            [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s); });
-    ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
-    gemm_tn(r, dqkv, 3 * D, id, u, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
     {
       GemmNT g{};
       g.A = dqkv; g.lda = 3 * D; g.B = weight_t(c, wi + 0); g.ldb = 3 * D; g.M = M; g.N = D; g.K = 3 * D;
       g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
       gemm_nt(r, g);
     }
-    ln_bwd(r, xin, D, du, D, o.ln1g, o.ln1b, dxB, dxA, dxAt, D, M, lnpart, accumulate);
+    ln_bwd(r, xin, D, du, D, o.ln1g, o.ln1b, dxB, dxA, dxAt, D, M, lnpart, accumulate, false, u);
+    gemm_tn(r, dqkv, 3 * D, id, u, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
   }
   // ---- token assembly: x0[n,0] = cls + pos[0]; x0[n,1+j] = patch_j W_pe^T + b_pe + pos[1+j]
   {
