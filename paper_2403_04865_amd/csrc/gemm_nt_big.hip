@@ -151,7 +151,12 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   const unsigned aoff0 = 2u * (unsigned)(row0 * (int)g.lda + kc * 8), boff0 = 2u * (unsigned)(row0 * (int)g.ldb + kc * 8);
   const unsigned astride = 2u * RSTEP * (unsigned)g.lda, bstride = 2u * RSTEP * (unsigned)g.ldb;  // bytes
   unsigned amax = 0xffffffffu;   // largest valid offset of this thread: (M - 1 - m0) rows + its chunk column
-  u32x4 ra[2][CA], rb[CB];   // A: two register slots (loads up to three steps ahead, it may miss to HBM); B: one (L2 hits)
+  // A: two register slots (loads three steps ahead of their MFMAs; it may miss to HBM).  B: two slots and the same
+  // lead where the registers allow it (with every load an L1 hit the K loop runs a third faster: it is the time
+  // the L2 takes to answer that the loop waits for), one slot and one step less in the modes that keep two
+  // strips of auxiliary rows in registers.
+  constexpr bool B2 = !HAS_AUX;
+  u32x4 ra[2][CA], rb[2][CB];
   float rbias = 0.f;
   auto set_offsets_a = [&](long long m0) __attribute__((always_inline)) {
     Ab = (const bf16*)g.A + m0 * g.lda;
@@ -173,9 +178,10 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
 #pragma unroll
     for (int i = 0; i < CA; ++i) ra[S][i] = load_a(i, k0);
   };
-  auto issue_b = [&](int k0) __attribute__((always_inline)) {
+  auto issue_b = [&](auto slot, int k0) __attribute__((always_inline)) {
+    constexpr int S = B2 ? decltype(slot)::value : 0;
 #pragma unroll
-    for (int i = 0; i < CB; ++i) rb[i] = load_b(i, k0);
+    for (int i = 0; i < CB; ++i) rb[S][i] = load_b(i, k0);
   };
   auto stash = [&](auto slot) __attribute__((always_inline)) {
     constexpr int S = decltype(slot)::value;
@@ -183,7 +189,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
 #pragma unroll
     for (int i = 0; i < CA; ++i) *reinterpret_cast<u32x4*>(st + soff + i * RSTEP * LDT) = ra[S][i];
 #pragma unroll
-    for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(st + BM * LDT + soff + i * RSTEP * LDT) = rb[i];
+    for (int i = 0; i < CB; ++i) *reinterpret_cast<u32x4*>(st + BM * LDT + soff + i * RSTEP * LDT) = rb[B2 ? S : 0][i];
   };
 
   // ---- MFMA side ----------------------------------------------------------------------------------------------
@@ -207,14 +213,14 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     constexpr int S = decltype(slot)::value, W = decltype(idx)::value;
     bf16* st = S ? ring1 : ring0;
     if constexpr (W < CA) *reinterpret_cast<u32x4*>(st + soff + W * RSTEP * LDT) = ra[S][W];
-    else *reinterpret_cast<u32x4*>(st + BM * LDT + soff + (W - CA) * RSTEP * LDT) = rb[W - CA];
+    else *reinterpret_cast<u32x4*>(st + BM * LDT + soff + (W - CA) * RSTEP * LDT) = rb[B2 ? S : 0][W - CA];
   };
   // global load l of a step: 0..5 the B chunks (they are needed first and hit L2), 6..13 the A chunks.
   // Loads return in order: the B chunks, issued one step before their LDS writes, do not wait for younger A
   // loads that may miss to HBM.
   auto ld_one = [&](auto slot, auto idx, int ka, int kb) __attribute__((always_inline)) {
     constexpr int S = decltype(slot)::value, Lx = decltype(idx)::value;
-    if constexpr (Lx < CB) rb[Lx] = load_b(Lx, kb);
+    if constexpr (Lx < CB) rb[B2 ? S : 0][Lx] = load_b(Lx, kb);
     else ra[S][Lx - CB] = load_a(Lx - CB, ka);
   };
   auto mfma_one = [&](auto buf, auto tt) __attribute__((always_inline)) {
@@ -385,13 +391,14 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   set_offsets_a(m0);
   set_offsets_b(n0);
   issue_a(IC<0>{}, 0);
-  issue_b(0);
+  issue_b(IC<0>{}, 0);
   __builtin_amdgcn_sched_barrier(0);
+  if constexpr (B2) issue_b(IC<1>{}, BK);
   issue_a(IC<1>{}, BK);
   __builtin_amdgcn_sched_barrier(0);
   stash(IC<0>{});
   __builtin_amdgcn_sched_barrier(0);
-  issue_b(BK);
+  issue_b(IC<0>{}, B2 ? 2 * BK : BK);
   __builtin_amdgcn_sched_barrier(0);
   issue_a(IC<0>{}, 2 * BK);
   __builtin_amdgcn_sched_barrier(0);
@@ -422,19 +429,19 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
       }
     auto pre = [&](int s) __attribute__((always_inline)) {
       if (s == nk - 3) set_offsets_a(m1);
-      if (s == nk - 2) set_offsets_b(n1);
+      if (s == nk - (B2 ? 3 : 2)) set_offsets_b(n1);
     };
-    pre(0); step(IC<0>{}, IC<(BGON && HAS_AUX) ? -1 : 0>{}, koff(3), koff(2));
-    pre(1); step(IC<1>{}, IC<BGON ? 1 : 0>{}, koff(4), koff(3));
-    pre(2); step(IC<0>{}, IC<BGON ? 2 : 0>{}, koff(5), koff(4));
-    pre(3); step(IC<1>{}, IC<BGON ? 3 : 0>{}, koff(6), koff(5));
-    pre(4); step(IC<0>{}, IC<BGON ? 4 : 0>{}, koff(7), koff(6));
+    pre(0); step(IC<0>{}, IC<(BGON && HAS_AUX) ? -1 : 0>{}, koff(3), B2 ? koff(3) : koff(2));
+    pre(1); step(IC<1>{}, IC<BGON ? 1 : 0>{}, koff(4), B2 ? koff(4) : koff(3));
+    pre(2); step(IC<0>{}, IC<BGON ? 2 : 0>{}, koff(5), B2 ? koff(5) : koff(4));
+    pre(3); step(IC<1>{}, IC<BGON ? 3 : 0>{}, koff(6), B2 ? koff(6) : koff(5));
+    pre(4); step(IC<0>{}, IC<BGON ? 4 : 0>{}, koff(7), B2 ? koff(7) : koff(6));
     for (int s = 5; s < nk - 1; s += 2) {
-      pre(s); step(IC<1>{}, IC<0>{}, koff(s + 3), koff(s + 2));
-      pre(s + 1); step(IC<0>{}, IC<0>{}, koff(s + 4), koff(s + 3));
+      pre(s); step(IC<1>{}, IC<0>{}, koff(s + 3), B2 ? koff(s + 3) : koff(s + 2));
+      pre(s + 1); step(IC<0>{}, IC<0>{}, koff(s + 4), B2 ? koff(s + 4) : koff(s + 3));
     }
     if (tid < BN) lbias_all[tid] = rbias;  // next tile's bias; this tile's was consumed at its start
-    step(IC<1>{}, IC<0>{}, 2 * BK, BK);
+    step(IC<1>{}, IC<0>{}, 2 * BK, B2 ? 2 * BK : BK);
     // park the block: strip 0 in the patch, strips 1..3 in registers
 #pragma unroll
     for (int i = 0; i < WBM; ++i)
