@@ -66,7 +66,7 @@ def pool_sweep(a):
     grads = torch.zeros_like(params)
     names = lib.kernel_names()
     rows = []
-    for lg in range(13, a.pool_max_log2 + 1):
+    for lg in range(a.pool_min_log2, a.pool_max_log2 + 1):
         N = 1 << lg
         nbytes = lib.slide_pool_arena_bytes(N)
         arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
@@ -149,6 +149,7 @@ def main():
     ap.add_argument("--calib-copy", type=int, default=0, help="run the plain copy kernel over this many bytes and exit")
     ap.add_argument("--pool-sweep", action="store_true", help="bandwidth sweep of the pool kernels instead of the step")
     ap.add_argument("--pool-hidden", type=int, default=128)
+    ap.add_argument("--pool-min-log2", type=int, default=13)
     ap.add_argument("--pool-max-log2", type=int, default=22)
     a = ap.parse_args()
     if a.gpus != 1:

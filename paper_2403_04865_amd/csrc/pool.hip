@@ -109,19 +109,10 @@ __global__ void __launch_bounds__(256) pool_gate_part_k(PoolArgs p) {
   for (int d = threadIdx.x; d < D; d += 256) out[2 + d] = zb[d];
 }
 
-// forward, stage 2 (one workgroup): combine partials -> m, Z, z, logits, loss, dy, dz, z.dz
-__global__ void __launch_bounds__(256) pool_combine_k(PoolArgs p) {
-  __shared__ float sm[256];
-  __shared__ double smd[256];
-  __shared__ float gm;
-  __shared__ double gZ;
-  int D = p.D, C = p.C, B = p.blocks;
-  float* scal = p.scal;
-  float* y = scal + 4;
-  float* dy = y + C;
-  float* z = dy + C;
-  float* dz = z + D;
-  float* zlo = dz + D;  // z = z[d] + zlo[d] to fp64 accuracy
+// Softmax statistics over the partials of stage 1: running max m and normaliser Z of the whole slide; wts[b] (if
+// given) is the weight exp(m_b - m) of partial b.  Called by all 256 threads of a workgroup.
+__device__ void pool_partial_stats(const PoolArgs& p, float* sm, double* smd, float* wts, float& m_out, double& Z_out) {
+  const int D = p.D, B = p.blocks;
   float m = -INFINITY;
   for (int b = threadIdx.x; b < B; b += 256) m = fmaxf(m, (float)p.part[(size_t)b * (2 + D)]);
   sm[threadIdx.x] = m;
@@ -130,13 +121,13 @@ __global__ void __launch_bounds__(256) pool_combine_k(PoolArgs p) {
     if (threadIdx.x < o) sm[threadIdx.x] = fmaxf(sm[threadIdx.x], sm[threadIdx.x + o]);
     __syncthreads();
   }
-  if (threadIdx.x == 0) gm = sm[0];
-  __syncthreads();
-  m = gm;
+  m = sm[0];
   double l = 0.0;
   for (int b = threadIdx.x; b < B; b += 256) {
     const double* q = p.part + (size_t)b * (2 + D);
-    l += q[1] * (double)__expf((float)q[0] - m);
+    float wt = __expf((float)q[0] - m);
+    if (wts) wts[b] = wt;
+    l += q[1] * (double)wt;
   }
   smd[threadIdx.x] = l;
   __syncthreads();
@@ -144,20 +135,55 @@ __global__ void __launch_bounds__(256) pool_combine_k(PoolArgs p) {
     if (threadIdx.x < o) smd[threadIdx.x] += smd[threadIdx.x + o];
     __syncthreads();
   }
-  if (threadIdx.x == 0) gZ = smd[0];
+  m_out = m;
+  Z_out = smd[0];
+}
+
+// forward, stage 2a: z = sum_b wts[b] z_b / Z.  One workgroup per 16 columns, 16 slices of the partials per column:
+// a single compute unit fetching all partials (written by every other unit a moment ago) is bound by its own
+// handful of outstanding misses, so the sum is spread over D / 16 units with every load of a thread in flight at once.
+__global__ void __launch_bounds__(256) pool_combine_z_k(PoolArgs p) {
+  __shared__ float sm[256];
+  __shared__ double smd[256];
+  __shared__ float wts[1024];   // at most 1024 workgroups in stage 1
+  __shared__ double red[16][17];
+  const int D = p.D, B = p.blocks;
+  float* z = p.scal + 4 + 2 * p.C;
+  float* zlo = z + 2 * D;
+  float m;
+  double Z;
+  pool_partial_stats(p, sm, smd, wts, m, Z);
+  const int c = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int d = blockIdx.x * 16 + c, dc = d < D ? d : D - 1;
+  double acc = 0.0;
+#pragma unroll 8
+  for (int b = sl; b < B; b += 16) acc += p.part[(size_t)b * (2 + D) + 2 + dc] * (double)wts[b];
+  red[sl][c] = acc;
   __syncthreads();
-  double Z = gZ;
-  for (int d = threadIdx.x; d < D; d += 256) {
-    double acc = 0.0;
-    for (int b = 0; b < B; ++b) {
-      const double* q = p.part + (size_t)b * (2 + D);
-      acc += q[2 + d] * (double)__expf((float)q[0] - m);
-    }
-    acc /= Z;
-    float hi = (float)acc;
+  if (threadIdx.x < 16 && d < D) {
+    double t = 0.0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += red[i][c];
+    t /= Z;
+    float hi = (float)t;
     z[d] = hi;
-    zlo[d] = (float)(acc - (double)hi);
+    zlo[d] = (float)(t - (double)hi);   // z = z[d] + zlo[d] to fp64 accuracy
   }
+}
+
+// forward, stage 2b (one workgroup): m, Z, logits, loss, dy, dz, z.dz
+__global__ void __launch_bounds__(256) pool_combine_k(PoolArgs p) {
+  __shared__ float sm[256];
+  __shared__ double smd[256];
+  int D = p.D, C = p.C;
+  float* scal = p.scal;
+  float* y = scal + 4;
+  float* dy = y + C;
+  float* z = dy + C;
+  float* dz = z + D;
+  float m;
+  double Z;
+  pool_partial_stats(p, sm, smd, nullptr, m, Z);
   __syncthreads();
   // logits: one wave per class round-robin
   int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -338,6 +364,9 @@ hipError_t launch_pool_fwd(const PoolArgs& p0, hipStream_t s) {
     hipLaunchKernelGGL(pool_gate_part_k, dim3(p.blocks), dim3(256), lds, s, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
+  if (p.blocks > 1024) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(pool_combine_z_k, dim3((unsigned)((p.D + 15) / 16)), dim3(256), 0, s, p);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(pool_combine_k, dim3(1), dim3(256), 0, s, p);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   if (p.alpha) {

@@ -212,6 +212,217 @@ __global__ void __launch_bounds__(256) pool_gate_part_mfma_k(PoolArgs p, const b
   for (int d = tid; d < D; d += 256) out[2 + d] = zb[d];
 }
 
+// Variant for the shape whose [V;U] fits the register file (D = 384, M_h = 128: 2 M_h * D bf16 = 192 KB, 192
+// registers per lane): each wavefront holds the MFMA fragments of its 32 gate units for the whole kernel, so the only
+// traffic per block of 32 feature rows is the block itself (the kernel above re-reads the weights from L2 for every
+// block, twice the bytes of the features).
+//   * A thread owns 4 rows x 12 columns of every block (fixed columns), in fp32 registers: two register sets, the
+//     block being processed and the one in flight from HBM.  LDS holds only the bf16 image of a block (double
+//     buffered) for the MFMA fragments; the weighted feature sum is taken from the fp32 registers, per block in fp32
+//     (4 terms), across blocks in fp64 (z feeds a cancelling difference in the backward).
+//   * Every wavefront computes the block's softmax terms itself from the four partial logits (no serial section).
+//   * Two barriers per block: partial logits visible; next bf16 image visible.
+template <int D, int MH>
+__global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf16* __restrict__ VU) {
+  constexpr int RB = 32, LDB = D + 8, KS = D / 16, CJ = D / 128, NR = 4 * CJ;
+  static_assert(MH == 128 && D % 128 == 0, "shape");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* Hb = reinterpret_cast<bf16*>(smem);                            // [2][RB][LDB]
+  float* gb = reinterpret_cast<float*>(Hb + 2 * RB * LDB);             // scaled bV[MH], scaled bU[MH], w[MH]
+  float* apart = gb + 3 * MH;                                          // [4][RB]
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 31, h2 = lane >> 5;
+  const int rgrp = tid >> 5, cl = tid & 31;   // loads: rows 4 rgrp .. + 3 of a block, column groups cl + 32 j
+  const float* H = p.H;
+  const long long groups = (p.N + RB - 1) / RB;
+  constexpr float C1 = -2.0f * 1.44269504088896f, C2 = -1.44269504088896f;   // exp(-2x) and exp(-x) as exp2
+
+  for (int j = tid; j < MH; j += 256) { gb[j] = C1 * p.Vb[j]; gb[MH + j] = C2 * p.Ub[j]; gb[2 * MH + j] = p.w[j]; }
+  // this wavefront's gate units: 32 * wave .. + 31 of V and of U
+  bf16x8 wv[KS], wu[KS];
+  {
+    const bf16* wr = VU + (size_t)(32 * wave + li) * D + h2 * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 a = *reinterpret_cast<const u32x4*>(wr + ks * 16);
+      u32x4 b = *reinterpret_cast<const u32x4*>(wr + (size_t)MH * D + ks * 16);
+      // the weights live in the accumulation half of the register file (MFMA reads its operands from either half;
+      // left to itself the allocator keeps them there as spills and copies them back before every MFMA)
+      asm volatile("" : "+a"(a), "+a"(b));
+      wv[ks] = __builtin_bit_cast(bf16x8, a);
+      wu[ks] = __builtin_bit_cast(bf16x8, b);
+    }
+  }
+  float4 ra[NR], rb[NR];
+  auto issue_h = [&](float4 (&r)[NR], long long g) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      // rows past the end (ragged last block, prefetch beyond the last block) re-read the last row: their softmax
+      // term is set to zero below, so whatever finite values they hold never reach a result
+      long long row = g * RB + 4 * rgrp + k;
+      row = row < p.N ? row : p.N - 1;
+      const float* hr = H + row * D + cl * 4;
+#pragma unroll
+      for (int j = 0; j < CJ; ++j) r[k * CJ + j] = *reinterpret_cast<const float4*>(hr + j * 128);
+    }
+  };
+  auto stash_h = [&](const float4 (&r)[NR], int buf) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+#pragma unroll
+      for (int j = 0; j < CJ; ++j) {
+        float4 v = r[k * CJ + j];
+        f32x2 p0 = {v.x, v.y}, p1 = {v.z, v.w};
+        bf16x2 h0 = __builtin_convertvector(p0, bf16x2), h1 = __builtin_convertvector(p1, bf16x2);
+        uint2 w2;
+        w2.x = __builtin_bit_cast(unsigned, h0);
+        w2.y = __builtin_bit_cast(unsigned, h1);
+        *reinterpret_cast<uint2*>(Hb + (buf * RB + 4 * rgrp + k) * LDB + (cl + 32 * j) * 4) = w2;
+      }
+  };
+  double z[4 * CJ];
+#pragma unroll
+  for (int i = 0; i < 4 * CJ; ++i) z[i] = 0.0;
+  double run_l = 0.0;
+  float run_m = -INFINITY;
+
+  auto block = [&](float4 (&cur)[NR], float4 (&nxt)[NR], int buf, long long gi) __attribute__((always_inline)) {
+    f32x16 av, au;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { av[r] = 0.f; au[r] = 0.f; }
+    const bf16* hrow = Hb + (buf * RB + li) * LDB + h2 * 8;
+    // one wavefront per SIMD: nothing else covers the LDS latency, so the fragments are read PF slices ahead and the
+    // order is fenced slice by slice
+    constexpr int PF = 4;
+    u32x4 hf[PF];
+#pragma unroll
+    for (int ks = 0; ks < PF; ++ks) hf[ks] = *reinterpret_cast<const u32x4*>(hrow + ks * 16);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      bf16x8 f = __builtin_bit_cast(bf16x8, hf[ks % PF]);
+      if (ks + PF < KS) hf[ks % PF] = *reinterpret_cast<const u32x4*>(hrow + (ks + PF) * 16);
+#ifndef PX_NOMFMA
+      av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[ks], f, av, 0, 0, 0);
+      au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu[ks], f, au, 0, 0, 0);
+#else
+      av[ks % 16] += (float)f[0] * (float)wv[ks][0]; au[ks % 16] += (float)f[1] * (float)wu[ks][0];
+#endif
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // gate: lane = feature row li; accumulator register r = gate unit (r / 4) * 8 + h2 * 4 + r % 4 of the wave's 32
+    float part = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int j = 32 * wave + q * 8 + h2 * 4;
+      float4 bv = *reinterpret_cast<const float4*>(gb + j);
+      float4 bu = *reinterpret_cast<const float4*>(gb + MH + j);
+      float4 wj = *reinterpret_cast<const float4*>(gb + 2 * MH + j);
+      float bvv[4] = {bv.x, bv.y, bv.z, bv.w}, buu[4] = {bu.x, bu.y, bu.z, bu.w}, ww[4] = {wj.x, wj.y, wj.z, wj.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        // tanh(xv) * sigmoid(xu) = (1 - e1) / ((1 + e1) (1 + e2)), e1 = exp(-2 xv), e2 = exp(-xu)
+        float e1 = __builtin_amdgcn_exp2f(fminf(fmaf(av[4 * q + e], C1, bvv[e]), 57.f));
+        float e2 = __builtin_amdgcn_exp2f(fminf(fmaf(au[4 * q + e], C2, buu[e]), 57.f));
+#ifndef PX_NOGATE
+        float s1 = 1.0f + e1;
+        part = fmaf(ww[e] * (1.0f - e1), __builtin_amdgcn_rcpf(fmaf(s1, e2, s1)), part);
+#else
+        part += ww[e] * av[4 * q + e] * au[4 * q + e] + bvv[e] * buu[e];
+#endif
+      }
+    }
+    part += __shfl_xor(part, 32, 64);
+    if (h2 == 0) apart[wave * RB + li] = part;
+    __syncthreads();   // (A) the four partial logits of every row are there
+    {
+      const long long n0 = gi * RB;
+      float a = apart[li] + apart[RB + li] + apart[2 * RB + li] + apart[3 * RB + li];
+      bool ok = n0 + li < p.N;
+      if (wave == 0 && h2 == 0 && ok) p.a[n0 + li] = a;
+      a = ok ? a : -INFINITY;
+      float m = fmaxf(run_m, wave_max(a));   // finite: the block has at least one row
+      float e = __expf(a - m);               // lanes li and li + 32: row li
+      float sc = __expf(run_m - m);          // exp(-inf) = 0 on the first block
+      run_m = m;
+      run_l = run_l * (double)sc + (double)(0.5f * wave_sum(e));
+      float ek[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) ek[k] = __shfl(e, 4 * (rgrp & 7) + k, 64);
+      const double scd = (double)sc;
+#ifdef PX_NOZ
+      for (int j = 0; j < 1; ++j) {
+#else
+#pragma unroll
+      for (int j = 0; j < CJ; ++j) {
+#endif
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          float4 v = cur[k * CJ + j];
+          s.x = fmaf(ek[k], v.x, s.x); s.y = fmaf(ek[k], v.y, s.y);
+          s.z = fmaf(ek[k], v.z, s.z); s.w = fmaf(ek[k], v.w, s.w);
+        }
+        z[4 * j + 0] = fma(z[4 * j + 0], scd, (double)s.x);
+        z[4 * j + 1] = fma(z[4 * j + 1], scd, (double)s.y);
+        z[4 * j + 2] = fma(z[4 * j + 2], scd, (double)s.z);
+        z[4 * j + 3] = fma(z[4 * j + 3], scd, (double)s.w);
+      }
+    }
+#ifndef PX_NOLOAD
+    issue_h(cur, gi + 2 * (long long)gridDim.x);   // in flight
+#endif
+#ifdef PX_NOSTASH
+    if (gi < 0)
+#endif
+    stash_h(nxt, buf ^ 1);                          // the next block (loaded during the previous one)
+    __syncthreads();   // (B) the next bf16 image is visible; apart is free again
+  };
+
+  long long gi = blockIdx.x;
+  const long long st = gridDim.x;
+  issue_h(ra, gi);
+  issue_h(rb, gi + st);
+  stash_h(ra, 0);
+  __syncthreads();
+  while (true) {
+    if (gi >= groups) break;
+    block(ra, rb, 0, gi);
+    gi += st;
+    if (gi >= groups) break;
+    block(rb, ra, 1, gi);
+    gi += st;
+  }
+  // column sums over the 8 row groups (the bf16 images are dead: every wavefront is past the last barrier (B))
+  double* zred = reinterpret_cast<double*>(smem);   // [8][D]
+  static_assert(8 * D * 8 <= 2 * RB * LDB * 2, "reduction buffer");
+#pragma unroll
+  for (int j = 0; j < CJ; ++j)
+#pragma unroll
+    for (int c = 0; c < 4; ++c) zred[rgrp * D + (cl + 32 * j) * 4 + c] = z[4 * j + c];
+  __syncthreads();
+  double* out = p.part + (size_t)blockIdx.x * (2 + D);
+  if (tid == 0) { out[0] = (double)run_m; out[1] = run_l; }
+  for (int d = tid; d < D; d += 256) {
+    double t = 0.0;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) t += zred[g * D + d];
+    out[2 + d] = t;
+  }
+}
+
+template <int D, int MH>
+hipError_t go_reg(const PoolArgs& p, hipStream_t s) {
+  auto kern = pool_gate_part_reg_k<D, MH>;
+  size_t lds = (size_t)2 * 32 * (D + 8) * 2 + (size_t)3 * MH * 4 + 4 * 32 * 4;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  long long n = (long long)p.Mh * p.D;
+  hipLaunchKernelGGL(pool_cast_vu_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.VW, p.UW, (bf16*)p.vub, n);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(256), lds, s, p, (const bf16*)p.vub);
+  return hipGetLastError();
+}
+
 template <int RB, int MH, int BK, int HCH>
 hipError_t go(const PoolArgs& p, hipStream_t s) {
   using C = PoolCfg<RB, MH, BK>;
@@ -234,10 +445,10 @@ bool pool_mfma_ok(const PoolArgs& p) {
          ((uintptr_t)p.H & 15) == 0 && ((uintptr_t)p.vub & 15) == 0;
 }
 
-int pool_mfma_rows(const PoolArgs& p) { return p.D == 384 ? 64 : 32; }
+int pool_mfma_rows(const PoolArgs& p) { return (p.D == 384 && p.Mh == 256) ? 64 : 32; }
 
 hipError_t launch_pool_gate_part_mfma(const PoolArgs& p, hipStream_t s) {
-  if (p.D == 384 && p.Mh == 128) return go<64, 128, 32, 24>(p, s);
+  if (p.D == 384 && p.Mh == 128) return go_reg<384, 128>(p, s);
   if (p.D == 384 && p.Mh == 256) return go<64, 256, 16, 24>(p, s);
   if (p.D == 768 && p.Mh == 128) return go<32, 128, 32, 24>(p, s);
   if (p.D == 768 && p.Mh == 256) return go<32, 256, 16, 24>(p, s);
