@@ -382,6 +382,10 @@ hipError_t launch_pool_bwd_rows(const PoolArgs& p, float* Dp, hipStream_t s) {
   if ((e = set_lds(pool_bwd_rows_k, lds)) != hipSuccess) return e;
   hipLaunchKernelGGL(pool_bwd_rows_k, dim3(p.blocks), dim3(256), lds, s, p, Dp);
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  return launch_pool_head_grads(p, s);
+}
+
+hipError_t launch_pool_head_grads(const PoolArgs& p, hipStream_t s) {
   hipLaunchKernelGGL(pool_head_grads_k, dim3(4), dim3(256), 0, s, p);
   return hipGetLastError();
 }

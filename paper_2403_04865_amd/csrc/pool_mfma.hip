@@ -301,12 +301,8 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
     for (int ks = 0; ks < KS; ++ks) {
       bf16x8 f = __builtin_bit_cast(bf16x8, hf[ks % PF]);
       if (ks + PF < KS) hf[ks % PF] = *reinterpret_cast<const u32x4*>(hrow + (ks + PF) * 16);
-#ifndef PX_NOMFMA
       av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[ks], f, av, 0, 0, 0);
       au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu[ks], f, au, 0, 0, 0);
-#else
-      av[ks % 16] += (float)f[0] * (float)wv[ks][0]; au[ks % 16] += (float)f[1] * (float)wu[ks][0];
-#endif
       __builtin_amdgcn_sched_barrier(0);
     }
     // gate: lane = feature row li; accumulator register r = gate unit (r / 4) * 8 + h2 * 4 + r % 4 of the wave's 32
@@ -323,22 +319,19 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
         // tanh(xv) * sigmoid(xu) = (1 - e1) / ((1 + e1) (1 + e2)), e1 = exp(-2 xv), e2 = exp(-xu)
         float e1 = __builtin_amdgcn_exp2f(fminf(fmaf(av[4 * q + e], C1, bvv[e]), 57.f));
         float e2 = __builtin_amdgcn_exp2f(fminf(fmaf(au[4 * q + e], C2, buu[e]), 57.f));
-#ifndef PX_NOGATE
         float s1 = 1.0f + e1;
         part = fmaf(ww[e] * (1.0f - e1), __builtin_amdgcn_rcpf(fmaf(s1, e2, s1)), part);
-#else
-        part += ww[e] * av[4 * q + e] * au[4 * q + e] + bvv[e] * buu[e];
-#endif
       }
     }
     part += __shfl_xor(part, 32, 64);
     if (h2 == 0) apart[wave * RB + li] = part;
     __syncthreads();   // (A) the four partial logits of every row are there
+    float a_out;
     {
       const long long n0 = gi * RB;
       float a = apart[li] + apart[RB + li] + apart[2 * RB + li] + apart[3 * RB + li];
       bool ok = n0 + li < p.N;
-      if (wave == 0 && h2 == 0 && ok) p.a[n0 + li] = a;
+      a_out = a;
       a = ok ? a : -INFINITY;
       float m = fmaxf(run_m, wave_max(a));   // finite: the block has at least one row
       float e = __expf(a - m);               // lanes li and li + 32: row li
@@ -349,12 +342,8 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
 #pragma unroll
       for (int k = 0; k < 4; ++k) ek[k] = __shfl(e, 4 * (rgrp & 7) + k, 64);
       const double scd = (double)sc;
-#ifdef PX_NOZ
-      for (int j = 0; j < 1; ++j) {
-#else
 #pragma unroll
       for (int j = 0; j < CJ; ++j) {
-#endif
         float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -368,13 +357,10 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
         z[4 * j + 3] = fma(z[4 * j + 3], scd, (double)s.w);
       }
     }
-#ifndef PX_NOLOAD
-    issue_h(cur, gi + 2 * (long long)gridDim.x);   // in flight
-#endif
-#ifdef PX_NOSTASH
-    if (gi < 0)
-#endif
+    issue_h(cur, gi + 2 * (long long)gridDim.x);   // in flight during the whole next block
     stash_h(nxt, buf ^ 1);                          // the next block (loaded during the previous one)
+    // the logits are kept for the backward; stored last so that no wait on the loads above also waits for this store
+    if (wave == 0 && h2 == 0 && gi * RB + li < p.N) p.a[gi * RB + li] = a_out;
     __syncthreads();   // (B) the next bf16 image is visible; apart is free again
   };
 

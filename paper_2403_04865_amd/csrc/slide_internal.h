@@ -190,7 +190,7 @@ struct PoolArgs {
   float* grads;                  // flat gradient vector
   size_t ocW, ocb;               // offsets of head.W / head.b in it
   int accumulate;
-  void* vub;     // [2 Mh][D] bf16 copy of [V;U] (scratch; only the matrix-core forward uses it), may be null
+  void* vub;     // 2 x [2 Mh][D] bf16: copy of [V;U] and room for its transpose (scratch of the matrix-core kernels), may be null
   int use_mfma;  // bf16 path: gate projections on the matrix cores where the shape is built
 };
 int pool_blocks(long long N);
@@ -199,5 +199,12 @@ int pool_mfma_rows(const PoolArgs& p);
 hipError_t launch_pool_gate_part_mfma(const PoolArgs& p, hipStream_t s);
 hipError_t launch_pool_fwd(const PoolArgs& p, hipStream_t s);
 hipError_t launch_pool_bwd_rows(const PoolArgs& p, float* Dp, hipStream_t s);
+hipError_t launch_pool_head_grads(const PoolArgs& p, hipStream_t s);
+// matrix-core backward over the rows (bf16 path, D = 384, M_h = 128): Dp [N][3 Mh] bf16 (dpV | dpU | da t s),
+// Hb16 [N][D] bf16 feature copy; writes p.G.  p.vub must have room for two bf16 copies of [V;U] (the second is the
+// transposed one).
+bool pool_bwd_mfma_ok(const PoolArgs& p);
+int pool_bwd_mfma_blocks(const PoolArgs& p);
+hipError_t launch_pool_bwd_mfma(const PoolArgs& p, void* Dp, void* Hb16, hipStream_t s);
 
 }  // namespace sl

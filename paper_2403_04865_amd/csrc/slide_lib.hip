@@ -117,9 +117,9 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   y.p_part = take((size_t)1024 * (2 + D) * 8);
   y.p_scal = take((size_t)(4 + 2 * C + 3 * D) * 4);
   y.p_Dp = take((size_t)PN * 3 * Mh * 4);
-  y.p_tn = take((size_t)32 * Mh * D * 4);
-  y.p_cs = take((size_t)128 * 3 * Mh * 4);
-  y.p_vub = take((size_t)2 * Mh * D * 2);
+  y.p_tn = take((size_t)64 * 2 * Mh * D * 4);
+  y.p_cs = take((size_t)1024 * 3 * Mh * 4);
+  y.p_vub = take((size_t)2 * 2 * Mh * D * 2);
   y.p_H = take((size_t)PN * D * 4);
   y.p_G = take((size_t)PN * D * 4);
   y.pool_end = cur;
@@ -235,7 +235,8 @@ void colsum(Run& r, int elem, const void* A, long long lda, RowMap map, long lon
 // dW (+)= A^T B through split partials; optionally also db (+)= column sums of A
 void gemm_tn(Run& r, const void* A, long long lda, RowMap amap, const void* B, long long ldb, RowMap bmap, long long M,
              int N1, int N2, float* part, float* out, int accumulate, int dt_override = -1, float* bias_out = nullptr,
-             float* cpart = nullptr) {
+             float* cpart = nullptr, float* out2 = nullptr, float* bias_out2 = nullptr) {
+  // out2 / bias_out2: the result rows N1/2 .. N1-1 (and their column sums) belong to a second tensor
   GemmTN g;
   int dt = dt_override >= 0 ? dt_override : r.c->dt;
   g.A = A; g.lda = lda; g.amap = amap; g.B = B; g.ldb = ldb; g.bmap = bmap; g.M = M; g.N1 = N1; g.N2 = N2;
@@ -247,16 +248,31 @@ void gemm_tn(Run& r, const void* A, long long lda, RowMap amap, const void* B, l
   else g.slabs = gemm_tn_pick_slabs(M, N1, N2, 32);
   bool fused = bias_out && gemm_tn_fuses_colsum(dt, g, r.c->use_mfma);
   if (fused) g.cs_part = cpart;
-  if (bias_out && !fused) colsum(r, dt, A, lda, amap, M, N1, cpart, bias_out, accumulate);
+  if (bias_out && !fused) {
+    if (bias_out2) {
+      colsum(r, dt, A, lda, amap, M, N1 / 2, cpart, bias_out, accumulate);
+      colsum(r, dt, (const char*)A + (size_t)(N1 / 2) * elem_size(dt), lda, amap, M, N1 / 2, cpart, bias_out2, accumulate);
+    } else {
+      colsum(r, dt, A, lda, amap, M, N1, cpart, bias_out, accumulate);
+    }
+  }
   size_t e = elem_size(dt);
   launch(r, K_GEMM_TN, 2.0 * M * N1 * N2, (double)M * (N1 + N2) * e + (double)g.slabs * N1 * N2 * 4,
          [&] { return launch_gemm_tn(dt, g, r.c->use_mfma, r.s); });
-  launch(r, K_ELEMWISE, 0, (double)(g.slabs + 1) * N1 * N2 * 4, [&] {
-    return launch_reduce_partials(part, g.slabs, (long long)N1 * N2, (long long)N1 * N2, out, accumulate, r.s);
-  });
-  if (fused)
+  const long long len = (long long)N1 * N2, len1 = out2 ? len / 2 : len;
+  launch(r, K_ELEMWISE, 0, (double)(g.slabs + 1) * len1 * 4,
+         [&] { return launch_reduce_partials(part, g.slabs, len, len1, out, accumulate, r.s); });
+  if (out2)
+    launch(r, K_ELEMWISE, 0, (double)(g.slabs + 1) * len1 * 4,
+           [&] { return launch_reduce_partials(part + len1, g.slabs, len, len1, out2, accumulate, r.s); });
+  if (fused) {
+    const int n1 = bias_out2 ? N1 / 2 : N1;
     launch(r, K_ELEMWISE, 0, 0,
-           [&] { return launch_reduce_partials(cpart, g.slabs, N1, N1, bias_out, accumulate, r.s); });
+           [&] { return launch_reduce_partials(cpart, g.slabs, N1, n1, bias_out, accumulate, r.s); });
+    if (bias_out2)
+      launch(r, K_ELEMWISE, 0, 0,
+             [&] { return launch_reduce_partials(cpart + n1, g.slabs, N1, n1, bias_out2, accumulate, r.s); });
+  }
 }
 
 void colsum(Run& r, int elem, const void* A, long long lda, RowMap map, long long M, int N, float* part, float* out,
@@ -598,10 +614,21 @@ int pool_bwd(slide_ctx* c, const Layout& y, const void* feats, long long N, int 
   int D = c->D, Mh = c->Mh;
   launch(r, K_POOL_FWD, 4.0 * N * D * Mh, (double)N * D * 4, [&] { return launch_pool_fwd(p, s); });
   char* Dp = ar + y.p_Dp;
-  launch(r, K_POOL_BWD, 8.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_rows(p, (float*)Dp, s); });
   RowMap id{0, 0};
   float* tn = (float*)(ar + y.p_tn);
   float* cs = (float*)(ar + y.p_cs);
+  // the matrix-core path keeps [dpV dpU da.t.s] and a feature copy as bf16 in the room of the fp32 [N, 3 Mh] array;
+  // db_V and db_U come out of the weight-gradient GEMMs as column sums of their first operand
+  if (pool_bwd_mfma_ok(p) && (size_t)D * 2 <= (size_t)3 * Mh * 2 && !getenv("SLIDE_POOL_BWD_ALU")) {
+    char* Hb16 = Dp + (size_t)N * 3 * Mh * 2;
+    launch(r, K_POOL_BWD, 12.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_mfma(p, Dp, Hb16, s); });
+    launch(r, K_ELEMWISE, 0, 0, [&] { return launch_pool_head_grads(p, s); });
+    gemm_tn(r, Dp, 3 * Mh, id, Hb16, D, id, N, 2 * Mh, D, tn, c->grads + c->o_VW, accumulate, DT_BF16,
+            c->grads + c->o_Vb, cs, c->grads + c->o_UW, c->grads + c->o_Ub);
+    colsum(r, DT_BF16, Dp + (size_t)2 * Mh * 2, 3 * Mh, id, N, Mh, cs, c->grads + c->o_w, accumulate);
+    return finish(r);
+  }
+  launch(r, K_POOL_BWD, 8.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_rows(p, (float*)Dp, s); });
   gemm_tn(r, Dp, 3 * Mh, id, feats, D, id, N, Mh, D, tn, c->grads + c->o_VW, accumulate, DT_F32);
   gemm_tn(r, Dp + (size_t)Mh * 4, 3 * Mh, id, feats, D, id, N, Mh, D, tn, c->grads + c->o_UW, accumulate, DT_F32);
   int slabs = colsum_slabs(N);

@@ -84,6 +84,10 @@ def test_pool_bf16_ragged_rows():          # row count that is no multiple of th
     _pool_case("medium", 1000 + 37, 1, label=1)
 
 
+def test_pool_bf16_many_rows():            # enough rows for the persistent kernels to walk several blocks per workgroup
+    _pool_case("medium", 65536 + 4096 + 19, 1, label=1)   # and for the large-M weight-gradient GEMM; ragged tail
+
+
 def test_pool_bf16_vit_b_shape():          # 768-wide features (32-row blocks), M_h 256
     _pool_case("full", 4096 + 5, 1)
 
