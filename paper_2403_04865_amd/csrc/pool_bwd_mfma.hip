@@ -9,8 +9,8 @@
 // Three contractions with three different contracted indices, and [V;U] (192 KB as bf16) fills the register file in
 // one orientation only, so the work is two passes over the rows plus the ordinary weight-gradient GEMM:
 //   pass 1: gate GEMM (weights as MFMA operands in registers, as in the forward), the row dot products from the fp32
-//           registers, the elementwise gradients; writes [dpV dpU da.t.s] and the features as bf16 (db_V, db_U and
-//           dw are column sums of that array).
+//           registers, the elementwise gradients; writes [dpV dpU] and the features as bf16 and sums dw (db_V and
+//           db_U are column sums of the written array, taken by the weight-gradient GEMM).
 //   pass 2: G = alpha dz + [dpV dpU] [V;U] with the transposed weights in registers; rows are the M index so that a
 //           lane owns a column of G and every store instruction writes whole 128-byte lines.
 //   dV, dU: large-M TN GEMM of the two bf16 arrays written by pass 1.
@@ -23,6 +23,16 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+template <int V>
+struct IC { static constexpr int value = V; };
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(IC<I>{});
+    static_for<I + 1, N>(f);
+  }
+}
 
 __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
   f32x2 v = {a, b};
@@ -41,12 +51,12 @@ __global__ void __launch_bounds__(256) pool_cast_vut_k(const float* __restrict__
 // Pass 1.  Same skeleton as the forward kernel with register-resident weights: persistent workgroups of 4
 // wavefronts over blocks of 32 rows, a wavefront owns 32 gate units, a thread owns 4 rows x 12 columns of every block
 // in fp32 registers (two sets), LDS holds the bf16 image of the block for the MFMA fragments.
-//   Dp  [N][3 Mh] bf16: dpV | dpU | da t s     Hb16 [N][D] bf16: the features
-// (db_V, db_U, dw are column sums of Dp, taken by the kernels that read it afterwards)
+//   Dp  [N][2 Mh] bf16: dpV | dpU     Hb16 [N][D] bf16: the features
+//   csp [gridDim.x][Mh] fp32: this workgroup's sum of da t s (dw)
 template <int D, int MH>
 __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* __restrict__ VU, bf16* __restrict__ Dp,
-                                                       bf16* __restrict__ Hb16) {
-  constexpr int RB = 32, LDB = D + 8, KS = D / 16, CJ = D / 128, NR = 4 * CJ, KU = 3 * MH, LDP = KU + 8;
+                                                       bf16* __restrict__ Hb16, float* __restrict__ csp) {
+  constexpr int RB = 32, LDB = D + 8, KS = D / 16, CJ = D / 128, NR = 4 * CJ, KU = 2 * MH, LDP = KU + 8;
   static_assert(MH == 128 && D % 128 == 0, "shape");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* Hb = reinterpret_cast<bf16*>(smem);                            // [2][RB][LDB]
@@ -101,6 +111,14 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
       for (int j = 0; j < CJ; ++j) r[k * CJ + j] = *reinterpret_cast<const float4*>(hr + j * 128);
     }
   };
+  // one of the NR loads of block g (i = k * CJ + j); spread over the MFMA loop: a wavefront that issues all of
+  // them at once stalls in the issue until the compute unit's outstanding-miss queue has room for the last one
+  auto issue_one = [&](float4 (&r)[NR], long long g, auto ic) __attribute__((always_inline)) {
+    constexpr int i = decltype(ic)::value, k = i / CJ, j = i % CJ;
+    long long row = g * RB + 4 * rgrp + k;
+    row = row < p.N ? row : p.N - 1;
+    r[i] = *reinterpret_cast<const float4*>(H + row * D + cl * 4 + j * 128);
+  };
   // bf16 image of block g: to LDS for the MFMA, and to the bf16 feature copy the weight-gradient GEMM reads
   auto stash_h = [&](const float4 (&r)[NR], int buf, long long g) __attribute__((always_inline)) {
 #pragma unroll
@@ -117,6 +135,9 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
       }
     }
   };
+  float sW[16];   // sum over this lane's rows of da t s, per gate unit of the accumulator layout
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sW[i] = 0.f;
   auto block = [&](float4 (&cur)[NR], float4 (&nxt)[NR], int buf, long long gi) __attribute__((always_inline)) {
     const long long n0 = gi * RB;
     const bool ok = n0 + li < p.N;
@@ -153,14 +174,15 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
     u32x4 hf[PF];
 #pragma unroll
     for (int ks = 0; ks < PF; ++ks) hf[ks] = *reinterpret_cast<const u32x4*>(hrow + ks * 16);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    static_for<0, KS>([&](auto kc) __attribute__((always_inline)) {
+      constexpr int ks = decltype(kc)::value;
       bf16x8 f = __builtin_bit_cast(bf16x8, hf[ks % PF]);
-      if (ks + PF < KS) hf[ks % PF] = *reinterpret_cast<const u32x4*>(hrow + (ks + PF) * 16);
+      if constexpr (ks + PF < KS) hf[ks % PF] = *reinterpret_cast<const u32x4*>(hrow + (ks + PF) * 16);
+      if constexpr (ks % 2 == 0 && ks / 2 < NR) issue_one(nxt, gi + (long long)gridDim.x, IC<ks / 2>{});
       av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[ks], f, av, 0, 0, 0);
       au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu[ks], f, au, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-    }
+    });
     __syncthreads();   // (A) the row dot products are there; the previous block's gradient image has been copied out
     {
       // lane = feature row li; accumulator register r = gate unit (r / 4) * 8 + h2 * 4 + r % 4 of the wave's 32
@@ -174,7 +196,7 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
         float4 bu = *reinterpret_cast<const float4*>(gb + MH + j);
         float4 wj = *reinterpret_cast<const float4*>(gb + 2 * MH + j);
         float bvv[4] = {bv.x, bv.y, bv.z, bv.w}, buu[4] = {bu.x, bu.y, bu.z, bu.w}, ww[4] = {wj.x, wj.y, wj.z, wj.w};
-        float dv[4], du[4], dw[4];
+        float dv[4], du[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           // t = tanh(xv) = (1 - e1) / (1 + e1), s = sigmoid(xu) = 1 / (1 + e2), e1 = exp(-2 xv), e2 = exp(-xu)
@@ -185,21 +207,18 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
           float ts = t * s, gw = da * ww[e];
           dv[e] = gw * s * fmaf(-t, t, 1.0f);
           du[e] = gw * ts * (1.0f - s);
-          dw[e] = da * ts;
+          sW[4 * q + e] = fmaf(da, ts, sW[4 * q + e]);
         }
-        uint2 pv, pu, pw;
+        uint2 pv, pu;
         pv.x = pack_bf16(dv[0], dv[1]); pv.y = pack_bf16(dv[2], dv[3]);
         pu.x = pack_bf16(du[0], du[1]); pu.y = pack_bf16(du[2], du[3]);
-        pw.x = pack_bf16(dw[0], dw[1]); pw.y = pack_bf16(dw[2], dw[3]);
         *reinterpret_cast<uint2*>(prow + q * 8) = pv;
         *reinterpret_cast<uint2*>(prow + MH + q * 8) = pu;
-        *reinterpret_cast<uint2*>(prow + 2 * MH + q * 8) = pw;
       }
     }
-    issue_h(cur, gi + 2 * (long long)gridDim.x);      // in flight during the whole next block
     stash_h(nxt, buf ^ 1, gi + (long long)gridDim.x);  // the next block (loaded during the previous one)
     __syncthreads();   // (B) the gradient image and the next bf16 image are visible; dotr is free again
-    // gradient image -> Dp: 48 threads write one row of 768 bytes
+    // gradient image -> Dp: 32 threads write one row of 512 bytes
 #pragma unroll
     for (int i = 0; i < RB * KU / 8 / 256; ++i) {
       int ch = tid + 256 * i, row = ch / (KU / 8), c16 = ch % (KU / 8);
@@ -212,7 +231,6 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
   long long gi = blockIdx.x;
   const long long st = gridDim.x;
   issue_h(ra, gi);
-  issue_h(rb, gi + st);
   stash_h(ra, 0, gi);
   __syncthreads();
   while (true) {
@@ -223,6 +241,18 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
     block(rb, ra, 1, gi);
     gi += st;
   }
+  // dw: sum over the rows (the 32 lanes of a half hold the same gate units)
+#pragma unroll
+  for (int o = 1; o < 32; o <<= 1)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sW[i] += __shfl_xor(sW[i], o, 64);
+  if (li == 0) {
+    float* out = csp + (size_t)blockIdx.x * MH + 32 * wave + h2 * 4;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) out[q * 8 + e] = sW[4 * q + e];
+  }
 }
 
 // Pass 2.  G[n][d] = alpha_n dz[d] + sum_u Dp[n][u] VUT[d][u].  A wavefront holds the transposed weights of its
@@ -232,7 +262,7 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
 template <int D, int MH>
 __global__ void __launch_bounds__(256) pool_bwd_g_k(PoolArgs p, const bf16* __restrict__ VUT,
                                                     const bf16* __restrict__ Dp) {
-  constexpr int RB = 32, KU = 2 * MH, KS = KU / 16, LDP = KU + 8, NT = D / 128, CH = RB * KU / 8 / 256, LDG = 3 * MH;
+  constexpr int RB = 32, KU = 2 * MH, KS = KU / 16, LDP = KU + 8, NT = D / 128, CH = RB * KU / 8 / 256, LDG = 2 * MH;
   static_assert(MH == 128 && D % 128 == 0, "shape");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* Dps = reinterpret_cast<bf16*>(smem);                           // [2][RB][LDP]
@@ -260,18 +290,20 @@ __global__ void __launch_bounds__(256) pool_bwd_g_k(PoolArgs p, const bf16* __re
   }
   u32x4 rp[CH];
   float ra = 0.f;
-  auto issue = [&](long long g) __attribute__((always_inline)) {
-#pragma unroll
-    for (int i = 0; i < CH; ++i) {
+  auto issue_one = [&](long long g, auto ic) __attribute__((always_inline)) {
+    constexpr int i = decltype(ic)::value;
+    if constexpr (i < CH) {
       int ch = tid + 256 * i, row = ch / (KU / 8), c16 = ch % (KU / 8);
       long long gr = g * RB + row;   // past the end: the last row again (never stored)
       gr = gr < p.N ? gr : p.N - 1;
       rp[i] = *reinterpret_cast<const u32x4*>(Dp + gr * LDG + c16 * 8);
-    }
-    if (tid < RB) {
+    } else if (tid < RB) {
       long long gr = g * RB + tid;
       ra = p.a[gr < p.N ? gr : p.N - 1];
     }
+  };
+  auto issue = [&](long long g) __attribute__((always_inline)) {
+    static_for<0, CH + 1>([&](auto ic) __attribute__((always_inline)) { issue_one(g, ic); });
   };
   auto stash = [&](int buf, long long g) __attribute__((always_inline)) {
 #pragma unroll
@@ -286,7 +318,6 @@ __global__ void __launch_bounds__(256) pool_bwd_g_k(PoolArgs p, const bf16* __re
   const long long st = gridDim.x;
   issue(gi);
   stash(0, gi);
-  issue(gi + st);
   __syncthreads();
   for (int buf = 0; gi < groups; gi += st, buf ^= 1) {
     const long long n0 = gi * RB;
@@ -300,14 +331,16 @@ __global__ void __launch_bounds__(256) pool_bwd_g_k(PoolArgs p, const bf16* __re
     u32x4 pf[PF];
 #pragma unroll
     for (int ks = 0; ks < PF; ++ks) pf[ks] = *reinterpret_cast<const u32x4*>(prow + ks * 16);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    static_for<0, KS>([&](auto kc) __attribute__((always_inline)) {
+      constexpr int ks = decltype(kc)::value;
       bf16x8 f = __builtin_bit_cast(bf16x8, pf[ks % PF]);
-      if (ks + PF < KS) pf[ks % PF] = *reinterpret_cast<const u32x4*>(prow + (ks + PF) * 16);
+      if constexpr (ks + PF < KS) pf[ks % PF] = *reinterpret_cast<const u32x4*>(prow + (ks + PF) * 16);
+      // the next block's loads, spread over the loop (issued at once they would stall the wavefront in the issue)
+      if constexpr (ks % 2 == 0 && ks / 2 < CH + 1) issue_one(gi + st, IC<ks / 2>{});
 #pragma unroll
       for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, wt[t][ks], acc[t], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-    }
+    });
     float al[16];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -331,7 +364,6 @@ __global__ void __launch_bounds__(256) pool_bwd_g_k(PoolArgs p, const bf16* __re
         }
     }
     stash(buf ^ 1, gi + st);     // the next block (loaded during this one)
-    issue(gi + 2 * st);          // in flight during the whole next block
     __syncthreads();             // the next gradient image and its alpha are visible
   }
 }
@@ -355,9 +387,9 @@ int pool_bwd_mfma_blocks(const PoolArgs& p) {
   return (int)(b > 1024 ? 1024 : b);
 }
 
-// Dp: [N][3 Mh] bf16, Hb16: [N][D] bf16.  p.vub holds [V;U] as bf16 (written
+// Dp: [N][2 Mh] bf16, Hb16: [N][D] bf16, csp: [pool_bwd_mfma_blocks][Mh] fp32 partial sums of dw.  p.vub holds [V;U] as bf16 (written
 // by the forward of the same call) followed by room for the transposed copy.
-hipError_t launch_pool_bwd_mfma(const PoolArgs& p, void* Dp, void* Hb16, hipStream_t s) {
+hipError_t launch_pool_bwd_mfma(const PoolArgs& p, void* Dp, void* Hb16, float* csp, hipStream_t s) {
   constexpr int D = 384, MH = 128;
   if (!pool_bwd_mfma_ok(p)) return hipErrorInvalidValue;
   const int blocks = pool_bwd_mfma_blocks(p);
@@ -368,10 +400,10 @@ hipError_t launch_pool_bwd_mfma(const PoolArgs& p, void* Dp, void* Hb16, hipStre
   if ((e = hipGetLastError()) != hipSuccess) return e;
   {
     auto kern = pool_bwd_gate_k<D, MH>;
-    size_t lds = (size_t)2 * 32 * (D + 8) * 2 + (size_t)32 * (3 * MH + 8) * 2 + (size_t)3 * MH * 4 + 32 * 4 + 2 * D * 4;
+    size_t lds = (size_t)2 * 32 * (D + 8) * 2 + (size_t)32 * (2 * MH + 8) * 2 + (size_t)3 * MH * 4 + 32 * 4 + 2 * D * 4;
     if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
       return e;
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, s, p, (const bf16*)vu, (bf16*)Dp, (bf16*)Hb16);
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, s, p, (const bf16*)vu, (bf16*)Dp, (bf16*)Hb16, csp);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {

@@ -22,6 +22,16 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
+template <int V>
+struct IC { static constexpr int value = V; };
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(IC<I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
 __device__ __forceinline__ bf16x8 cvt8(float4 a, float4 b) {
   f32x2 p0 = {a.x, a.y}, p1 = {a.z, a.w}, p2 = {b.x, b.y}, p3 = {b.z, b.w};
   bf16x2 h0 = __builtin_convertvector(p0, bf16x2), h1 = __builtin_convertvector(p1, bf16x2);
@@ -266,6 +276,14 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
       for (int j = 0; j < CJ; ++j) r[k * CJ + j] = *reinterpret_cast<const float4*>(hr + j * 128);
     }
   };
+  // one of the NR loads of block g (i = k * CJ + j); spread over the MFMA loop: a wavefront that issues all of
+  // them at once stalls in the issue until the compute unit's outstanding-miss queue has room for the last one
+  auto issue_one = [&](float4 (&r)[NR], long long g, auto ic) __attribute__((always_inline)) {
+    constexpr int i = decltype(ic)::value, k = i / CJ, j = i % CJ;
+    long long row = g * RB + 4 * rgrp + k;
+    row = row < p.N ? row : p.N - 1;
+    r[i] = *reinterpret_cast<const float4*>(H + row * D + cl * 4 + j * 128);
+  };
   auto stash_h = [&](const float4 (&r)[NR], int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int k = 0; k < 4; ++k)
@@ -297,14 +315,15 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
     u32x4 hf[PF];
 #pragma unroll
     for (int ks = 0; ks < PF; ++ks) hf[ks] = *reinterpret_cast<const u32x4*>(hrow + ks * 16);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+    static_for<0, KS>([&](auto kc) __attribute__((always_inline)) {
+      constexpr int ks = decltype(kc)::value;
       bf16x8 f = __builtin_bit_cast(bf16x8, hf[ks % PF]);
-      if (ks + PF < KS) hf[ks % PF] = *reinterpret_cast<const u32x4*>(hrow + (ks + PF) * 16);
+      if constexpr (ks + PF < KS) hf[ks % PF] = *reinterpret_cast<const u32x4*>(hrow + (ks + PF) * 16);
+      if constexpr (ks % 2 == 0 && ks / 2 < NR) issue_one(nxt, gi + (long long)gridDim.x, IC<ks / 2>{});
       av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[ks], f, av, 0, 0, 0);
       au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu[ks], f, au, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-    }
+    });
     // gate: lane = feature row li; accumulator register r = gate unit (r / 4) * 8 + h2 * 4 + r % 4 of the wave's 32
     float part = 0.f;
 #pragma unroll
@@ -357,7 +376,6 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
         z[4 * j + 3] = fma(z[4 * j + 3], scd, (double)s.w);
       }
     }
-    issue_h(cur, gi + 2 * (long long)gridDim.x);   // in flight during the whole next block
     stash_h(nxt, buf ^ 1);                          // the next block (loaded during the previous one)
     // the logits are kept for the backward; stored last so that no wait on the loads above also waits for this store
     if (wave == 0 && h2 == 0 && gi * RB + li < p.N) p.a[gi * RB + li] = a_out;
@@ -367,7 +385,6 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
   long long gi = blockIdx.x;
   const long long st = gridDim.x;
   issue_h(ra, gi);
-  issue_h(rb, gi + st);
   stash_h(ra, 0);
   __syncthreads();
   while (true) {

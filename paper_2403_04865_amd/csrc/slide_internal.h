@@ -200,11 +200,11 @@ hipError_t launch_pool_gate_part_mfma(const PoolArgs& p, hipStream_t s);
 hipError_t launch_pool_fwd(const PoolArgs& p, hipStream_t s);
 hipError_t launch_pool_bwd_rows(const PoolArgs& p, float* Dp, hipStream_t s);
 hipError_t launch_pool_head_grads(const PoolArgs& p, hipStream_t s);
-// matrix-core backward over the rows (bf16 path, D = 384, M_h = 128): Dp [N][3 Mh] bf16 (dpV | dpU | da t s),
-// Hb16 [N][D] bf16 feature copy; writes p.G.  p.vub must have room for two bf16 copies of [V;U] (the second is the
-// transposed one).
+// matrix-core backward over the rows (bf16 path, D = 384, M_h = 128): Dp [N][2 Mh] bf16 (dpV | dpU), Hb16 [N][D] bf16
+// feature copy, csp [pool_bwd_mfma_blocks][Mh] partial sums of da t s (dw); writes p.G.  p.vub must have room for two
+// bf16 copies of [V;U] (the second is the transposed one).
 bool pool_bwd_mfma_ok(const PoolArgs& p);
 int pool_bwd_mfma_blocks(const PoolArgs& p);
-hipError_t launch_pool_bwd_mfma(const PoolArgs& p, void* Dp, void* Hb16, hipStream_t s);
+hipError_t launch_pool_bwd_mfma(const PoolArgs& p, void* Dp, void* Hb16, float* csp, hipStream_t s);
 
 }  // namespace sl

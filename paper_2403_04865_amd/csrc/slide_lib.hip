@@ -617,15 +617,18 @@ int pool_bwd(slide_ctx* c, const Layout& y, const void* feats, long long N, int 
   RowMap id{0, 0};
   float* tn = (float*)(ar + y.p_tn);
   float* cs = (float*)(ar + y.p_cs);
-  // the matrix-core path keeps [dpV dpU da.t.s] and a feature copy as bf16 in the room of the fp32 [N, 3 Mh] array;
-  // db_V and db_U come out of the weight-gradient GEMMs as column sums of their first operand
-  if (pool_bwd_mfma_ok(p) && (size_t)D * 2 <= (size_t)3 * Mh * 2 && !getenv("SLIDE_POOL_BWD_ALU")) {
-    char* Hb16 = Dp + (size_t)N * 3 * Mh * 2;
-    launch(r, K_POOL_BWD, 12.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_mfma(p, Dp, Hb16, s); });
+  // the matrix-core path keeps [dpV dpU] and a feature copy as bf16 in the room of the fp32 [N, 3 Mh] array; db_V and
+  // db_U come out of the weight-gradient GEMM as column sums of its first operand
+  if (pool_bwd_mfma_ok(p) && (size_t)(2 * Mh + D) * 2 <= (size_t)3 * Mh * 4 && !getenv("SLIDE_POOL_BWD_ALU")) {
+    char* Hb16 = Dp + (size_t)N * 2 * Mh * 2;
+    float* csw = cs + (size_t)64 * 2 * Mh;   // behind the column-sum partials of the GEMM (at most 64 slabs)
+    int blocks = pool_bwd_mfma_blocks(p);
+    launch(r, K_POOL_BWD, 12.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_mfma(p, Dp, Hb16, csw, s); });
     launch(r, K_ELEMWISE, 0, 0, [&] { return launch_pool_head_grads(p, s); });
-    gemm_tn(r, Dp, 3 * Mh, id, Hb16, D, id, N, 2 * Mh, D, tn, c->grads + c->o_VW, accumulate, DT_BF16,
+    launch(r, K_ELEMWISE, 0, 0,
+           [&] { return launch_reduce_partials(csw, blocks, Mh, Mh, c->grads + c->o_w, accumulate, s); });
+    gemm_tn(r, Dp, 2 * Mh, id, Hb16, D, id, N, 2 * Mh, D, tn, c->grads + c->o_VW, accumulate, DT_BF16,
             c->grads + c->o_Vb, cs, c->grads + c->o_UW, c->grads + c->o_Ub);
-    colsum(r, DT_BF16, Dp + (size_t)2 * Mh * 2, 3 * Mh, id, N, Mh, cs, c->grads + c->o_w, accumulate);
     return finish(r);
   }
   launch(r, K_POOL_BWD, 8.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_rows(p, (float*)Dp, s); });
