@@ -111,13 +111,17 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
       for (int j = 0; j < CJ; ++j) r[k * CJ + j] = *reinterpret_cast<const float4*>(hr + j * 128);
     }
   };
-  // one of the NR loads of block g (i = k * CJ + j); spread over the MFMA loop: a wavefront that issues all of
-  // them at once stalls in the issue until the compute unit's outstanding-miss queue has room for the last one
+  // one of the NR loads of block g (i = k * CJ + j); spread over the MFMA loop: issued as one burst they hold the
+  // wavefronts in the issue for the ~770 clocks the address unit needs for a block's 48 KB
+  const float* hrp = H;   // row base of the loads in progress
   auto issue_one = [&](float4 (&r)[NR], long long g, auto ic) __attribute__((always_inline)) {
     constexpr int i = decltype(ic)::value, k = i / CJ, j = i % CJ;
-    long long row = g * RB + 4 * rgrp + k;
-    row = row < p.N ? row : p.N - 1;
-    r[i] = *reinterpret_cast<const float4*>(H + row * D + cl * 4 + j * 128);
+    if constexpr (j == 0) {
+      long long row = g * RB + 4 * rgrp + k;
+      row = row < p.N ? row : p.N - 1;
+      hrp = H + row * D + cl * 4;
+    }
+    r[i] = *reinterpret_cast<const float4*>(hrp + j * 128);
   };
   // bf16 image of block g: to LDS for the MFMA, and to the bf16 feature copy the weight-gradient GEMM reads
   auto stash_h = [&](const float4 (&r)[NR], int buf, long long g) __attribute__((always_inline)) {
@@ -335,7 +339,7 @@ __global__ void __launch_bounds__(256) pool_bwd_g_k(PoolArgs p, const bf16* __re
       constexpr int ks = decltype(kc)::value;
       bf16x8 f = __builtin_bit_cast(bf16x8, pf[ks % PF]);
       if constexpr (ks + PF < KS) pf[ks % PF] = *reinterpret_cast<const u32x4*>(prow + (ks + PF) * 16);
-      // the next block's loads, spread over the loop (issued at once they would stall the wavefront in the issue)
+      // the next block's loads, spread over the loop
       if constexpr (ks % 2 == 0 && ks / 2 < CH + 1) issue_one(gi + st, IC<ks / 2>{});
 #pragma unroll
       for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, wt[t][ks], acc[t], 0, 0, 0);

@@ -276,13 +276,17 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
       for (int j = 0; j < CJ; ++j) r[k * CJ + j] = *reinterpret_cast<const float4*>(hr + j * 128);
     }
   };
-  // one of the NR loads of block g (i = k * CJ + j); spread over the MFMA loop: a wavefront that issues all of
-  // them at once stalls in the issue until the compute unit's outstanding-miss queue has room for the last one
+  // one of the NR loads of block g (i = k * CJ + j); spread over the MFMA loop: issued as one burst they hold the
+  // wavefronts in the issue for the ~770 clocks the address unit needs for a block's 48 KB
+  const float* hrp = H;   // row base of the loads in progress
   auto issue_one = [&](float4 (&r)[NR], long long g, auto ic) __attribute__((always_inline)) {
     constexpr int i = decltype(ic)::value, k = i / CJ, j = i % CJ;
-    long long row = g * RB + 4 * rgrp + k;
-    row = row < p.N ? row : p.N - 1;
-    r[i] = *reinterpret_cast<const float4*>(H + row * D + cl * 4 + j * 128);
+    if constexpr (j == 0) {
+      long long row = g * RB + 4 * rgrp + k;
+      row = row < p.N ? row : p.N - 1;
+      hrp = H + row * D + cl * 4;
+    }
+    r[i] = *reinterpret_cast<const float4*>(hrp + j * 128);
   };
   auto stash_h = [&](const float4 (&r)[NR], int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -337,9 +341,9 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
       for (int e = 0; e < 4; ++e) {
         // tanh(xv) * sigmoid(xu) = (1 - e1) / ((1 + e1) (1 + e2)), e1 = exp(-2 xv), e2 = exp(-xu)
         float e1 = __builtin_amdgcn_exp2f(fminf(fmaf(av[4 * q + e], C1, bvv[e]), 57.f));
-        float e2 = __builtin_amdgcn_exp2f(fminf(fmaf(au[4 * q + e], C2, buu[e]), 57.f));
+        float e2 = __builtin_amdgcn_exp2f(fmaf(au[4 * q + e], C2, buu[e]));   // inf is fine: 1 / inf = 0, e1 is finite
         float s1 = 1.0f + e1;
-        part = fmaf(ww[e] * (1.0f - e1), __builtin_amdgcn_rcpf(fmaf(s1, e2, s1)), part);
+        part = fmaf(fmaf(-ww[e], e1, ww[e]), __builtin_amdgcn_rcpf(fmaf(s1, e2, s1)), part);
       }
     }
     part += __shfl_xor(part, 32, 64);
