@@ -272,11 +272,15 @@ int gemm_tn_big_slabs(const GemmTN& g, int max_slabs) {
   bool a_is_x = padded(g.N1, g.N2) <= padded(g.N2, g.N1);
   int nx = a_is_x ? g.N1 : g.N2, ny = a_is_x ? g.N2 : g.N1;
   int tiles = ((nx + BX - 1) / BX) * ((ny + BY - 1) / BY);
-  // per XCD: spx slabs x tiles items over 32 workgroups; prefer a whole number of rounds
-  int spx = 8;
-  for (int c = 4; c <= 8; ++c)
-    if ((c * tiles) % 32 == 0) { spx = c; break; }
-  while (spx > 1 && 8 * spx > max_slabs) --spx;
+  // per XCD: spx slabs x tiles items over 32 workgroups; take the count whose last round is fullest (ties: more
+  // slabs, i.e. shorter items)
+  int spx = 1;
+  double best = 0.0;
+  for (int c = 1; c <= 8 && 8 * c <= max_slabs; ++c) {
+    int items = c * tiles, rounds = (items + 31) / 32;
+    double fill = (double)items / (rounds * 32.0);
+    if (c >= 3 ? fill >= best : fill > best + 0.2) { best = fill; spx = c; }   // fewer than 3 only if much fuller
+  }
   return 8 * spx;
 }
 

@@ -888,6 +888,18 @@ int slide_debug_gemm_nt(long long M, int N, int K, const void* A, const void* B,
   hipError_t e = launch_gemm_nt(DT_BF16, g, true, (hipStream_t)stream);
   return e == hipSuccess ? 0 : SLIDE_EHIP;
 }
+// one large-M TN GEMM (partials only) on caller-provided buffers; part must hold 64 * N1 * N2 floats
+int slide_debug_gemm_tn(long long M, int N1, int N2, const void* A, const void* B, float* part, void* stream) {
+  GemmTN g{};
+  RowMap id{0, 0};
+  g.A = A; g.lda = N1; g.amap = id; g.B = B; g.ldb = N2; g.bmap = id; g.M = M; g.N1 = N1; g.N2 = N2; g.part = part;
+  g.cs_part = nullptr;
+  g.slabs = gemm_tn_big_slabs(g, 64);
+  if (!g.slabs) return SLIDE_EUNSUPPORTED;
+  g.big = 1;
+  hipError_t e = launch_gemm_tn(DT_BF16, g, true, (hipStream_t)stream);
+  return e == hipSuccess ? g.slabs : SLIDE_EHIP;
+}
 #endif
 
 int slide_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
