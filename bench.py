@@ -107,6 +107,40 @@ def pool_sweep(a):
     print(json.dumps({"pool_sweep": rows, "D": cfg.dim, "mil_hidden": cfg.mil_hidden, "peak_GBps": PEAK["hbm"] / 1e9}))
 
 
+def adamw_bench(a):
+    """AdamW update of every parameter of the workload's model: achieved HBM bandwidth against the 28 bytes per
+    parameter the update has to move (read theta, g, m, v; write theta, m, v), HIP events on the launch stream."""
+    import numpy as np
+    import torch
+    import gen
+    sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), "tests"))
+    from slide_harness import lib_config
+    from paper_2403_04865_amd import SlideLib
+    cfg, _ = gen.CONFIGS[a.workload]
+    lib = SlideLib(lib_config(cfg, 1))
+    n = lib.slide_param_count()
+    dev = torch.device("cuda:0")
+    rng = np.random.Generator(np.random.PCG64(7))
+    P = torch.from_numpy((rng.standard_normal(n) * 0.02).astype(np.float32)).to(dev)
+    G = torch.from_numpy((rng.standard_normal(n) * 1e-3).astype(np.float32)).to(dev)
+    M = torch.zeros_like(P)
+    V = torch.zeros_like(P)
+    for t in range(1, a.warmup + 1):
+        lib.slide_adamw_step(P, G, M, V, n, t, 5e-5)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for t in range(a.warmup + 1, a.warmup + a.steps + 1):
+        lib.slide_adamw_step(P, G, M, V, n, t, 5e-5)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / a.steps
+    gbps = n * 28 / (ms * 1e-3) / 1e9
+    print(json.dumps({"adamw": {"workload": a.workload, "parameters": n, "us_per_update": round(ms * 1e3, 1),
+                                "bytes_per_parameter": 28, "achieved_GBps": round(gbps, 1), "peak_GBps": PEAK["hbm"] / 1e9,
+                                "frac": round(gbps * 1e9 / PEAK["hbm"], 4), "steps": a.steps, "warmup": a.warmup}}))
+
+
 def calib_copy(a):
     """One warm-up and three launches of the library's plain copy kernel over --calib-copy bytes: the known-size
     kernel whose FETCH_SIZE / WRITE_SIZE readings give the scale of those counters."""
@@ -147,6 +181,7 @@ def main():
     ap.add_argument("--recompute", type=int, default=-1,
                     help="1 = keep block inputs only and re-run blocks in the backward (default: only for 'full')")
     ap.add_argument("--calib-copy", type=int, default=0, help="run the plain copy kernel over this many bytes and exit")
+    ap.add_argument("--adamw", action="store_true", help="time the AdamW update of the workload's parameters instead")
     ap.add_argument("--pool-sweep", action="store_true", help="bandwidth sweep of the pool kernels instead of the step")
     ap.add_argument("--pool-hidden", type=int, default=128)
     ap.add_argument("--pool-min-log2", type=int, default=13)
@@ -158,6 +193,8 @@ def main():
 
     if a.pool_sweep:
         return pool_sweep(a)
+    if a.adamw:
+        return adamw_bench(a)
     if a.calib_copy:
         return calib_copy(a)
 

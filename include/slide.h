@@ -141,6 +141,18 @@ int  slide_step_bwd(slide_ctx* ctx, int accumulate, void* pixel_grad_or_null, vo
 const void* slide_features(const slide_ctx* ctx);
 const void* slide_feature_grads(const slide_ctx* ctx);
 
+/* One AdamW update of `count` fp32 parameters in place (paper, Experiments: the optimiser both training set-ups
+ * use; Adam with decoupled weight decay as in the work cited there):
+ *   m = beta1 m + (1 - beta1) g;  v = beta2 v + (1 - beta2) g^2;
+ *   params -= lr * ((m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps) + weight_decay * params)
+ * params, exp_avg (m) and exp_avg_sq (v) are device pointers to `count` floats each, read and written; grads is read.
+ * The caller owns all four and zero-fills m and v before step 1.  step counts from 1.  After slide_step_bwd the
+ * arguments are the buffers given to slide_bind (the next forward reads the updated parameters).
+ * SLIDE_EINVAL: null pointer, count == 0, step < 1, beta outside [0,1), lr or eps or weight_decay negative. */
+int  slide_adamw_step(float* params, const float* grads, float* exp_avg, float* exp_avg_sq, size_t count,
+                      int64_t step, float lr, float beta1, float beta2, float eps, float weight_decay,
+                      void* hip_stream);
+
 /* hipError_t of the most recent failing HIP call on this thread (0 if none). */
 int  slide_last_hip_error(void);
 

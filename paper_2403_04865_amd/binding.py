@@ -69,6 +69,8 @@ _SYMS = {
     "slide_prof_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "slide_kernel_name": (C.c_char_p, [C.c_int]),
     "slide_calib_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "slide_adamw_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int64, C.c_float,
+                                   C.c_float, C.c_float, C.c_float, C.c_float, C.c_void_p]),
 }
 
 
@@ -76,6 +78,10 @@ def load_cdll():
     p = lib_path()
     if not os.path.exists(p):
         raise OSError(f"{p} is not built: run `python -m paper_2403_04865_amd.build` (there is no fallback path)")
+    # Device memory and streams come from torch, so the process must run on torch's HIP runtime: with the library
+    # loaded first, its own dependency brings up a second runtime and every launch on torch's pointers fails
+    # (hipErrorNoDevice).
+    import torch  # noqa: F401
     lib = C.CDLL(p)
     for name, (res, args) in _SYMS.items():
         f = getattr(lib, name)
@@ -193,6 +199,12 @@ class SlideLib:
         ms, n, fl, by = C.c_double(), C.c_int(), C.c_double(), C.c_double()
         self._check(self.lib.slide_prof_end(self.ctx, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)), "slide_prof_end")
         return ms.value, n.value, fl.value, by.value
+
+    def slide_adamw_step(self, params, grads, exp_avg, exp_avg_sq, count, step, lr, beta1=0.9, beta2=0.999, eps=1e-8,
+                         weight_decay=0.01, stream=None):
+        self._check(self.lib.slide_adamw_step(_ptr(params), _ptr(grads), _ptr(exp_avg), _ptr(exp_avg_sq),
+                                              C.c_size_t(count), int(step), lr, beta1, beta2, eps, weight_decay,
+                                              _stream(stream)), "slide_adamw_step")
 
     def slide_calib_copy(self, dst, src, nbytes, stream=None):
         self._check(self.lib.slide_calib_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream(stream)), "slide_calib_copy")

@@ -902,6 +902,17 @@ int slide_debug_gemm_tn(long long M, int N1, int N2, const void* A, const void* 
 }
 #endif
 
+int slide_adamw_step(float* params, const float* grads, float* m, float* v, size_t count, int64_t step, float lr,
+                     float beta1, float beta2, float eps, float weight_decay, void* stream) {
+  if (!params || !grads || !m || !v || count == 0 || step < 1) return SLIDE_EINVAL;
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return SLIDE_EINVAL;
+  if (!(lr >= 0.f) || !(eps >= 0.f) || !(weight_decay >= 0.f)) return SLIDE_EINVAL;
+  (void)hipGetLastError();   // the launch status below must be this call's, not an older error left on the thread
+  hipError_t e = launch_adamw(params, grads, m, v, count, step, lr, beta1, beta2, eps, weight_decay, (hipStream_t)stream);
+  if (e != hipSuccess) { g_last_hip = (int)e; return SLIDE_EHIP; }
+  return SLIDE_OK;
+}
+
 int slide_calib_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return SLIDE_EINVAL;
   hipError_t e = launch_calib_copy(dst, src, bytes, (hipStream_t)stream);
