@@ -174,7 +174,9 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="large")
-    ap.add_argument("--tiles", type=int, default=0, help="override the tile count (debugging)")
+    ap.add_argument("--tiles", type=int, default=0, help="override the tile count")
+    ap.add_argument("--chunk-tiles", type=int, default=0,
+                    help="run the chunked step (slide_step_chunked) with this many tiles per encoder chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tiles", type=int, default=16)
     ap.add_argument("--prof-kernel", default="gemm_nt")
@@ -219,7 +221,7 @@ def main():
         flat[off:off + ln] = prm[name].reshape(-1)
     params = torch.from_numpy(flat).to(dev)
     grads = torch.zeros_like(params)
-    nbytes = lib.slide_arena_bytes(N)
+    nbytes = lib.slide_chunked_arena_bytes(N, a.chunk_tiles) if a.chunk_tiles else lib.slide_arena_bytes(N)
     arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
     o = (-arena.data_ptr()) % 256
     arena = arena[o:o + nbytes]
@@ -242,6 +244,9 @@ def main():
     stream = torch.cuda.current_stream()
 
     def one_step():
+        if a.chunk_tiles:   # features of all chunks, pool, then forward again + backward chunk by chunk
+            lib.slide_step_chunked(px, N, a.chunk_tiles, label, 0, loss, logits, None, None, stream)
+            return
         lib.slide_step_fwd(px, N, label, loss, logits, None, stream)
         lib.slide_step_bwd(0, None, stream)
 
@@ -263,7 +268,7 @@ def main():
     tiles_per_s = N * a.steps / dt
     mflops = model_flops_per_tile(cfg) - pruned_flops_per_tile(cfg)   # the bf16 path prunes the last block
     mfu = tiles_per_s * mflops / PEAK["mfma_bf16"]
-    tr = load_traffic(a.workload, a.prof_kernel) if not a.tiles else None
+    tr = load_traffic(a.workload, a.prof_kernel) if not (a.tiles or a.chunk_tiles) else None
     hbm_bound = a.prof_kernel in ("ln_fwd", "ln_bwd", "pool_fwd", "pool_bwd", "colsum", "elementwise")
     if hbm_bound:   # streaming kernels: algorithmic bytes over time against the HBM peak
         achieved = (k_bytes / (k_ms * 1e-3)) / 1e9 if k_ms > 0 else 0.0
@@ -302,7 +307,8 @@ def main():
                    "tiles": N, "slide_steps_per_s": round(a.steps / dt, 4),
                    "model_gflop_per_tile": round(mflops / 1e9, 3), "mfu_bf16_peak": round(mfu, 4),
                    "last_block": "CLS row only after attention (exact; its FLOPs are not counted)",
-                   "activation_policy": "block inputs + re-run blocks in backward" if recompute else "all block activations kept",
+                   "activation_policy": ("block inputs + re-run blocks in backward" if recompute else "all block activations kept") +
+                                        (f"; encoder in chunks of {a.chunk_tiles} tiles (one extra forward)" if a.chunk_tiles else ""),
                    "arena_gb": round(nbytes / 1e9, 2), "peak_alloc_gb_of_288": round(peak_alloc, 2),
                    "loss": float(loss.item()), "input_gen_s": round(gen_s, 1)},
         "roofline": roof,

@@ -136,6 +136,19 @@ int  slide_step_fwd(slide_ctx* ctx, const void* pixels, int64_t N, int32_t label
  * parameter (overwrite or add).  SLIDE_ESTATE without a preceding slide_step_fwd. */
 int  slide_step_bwd(slide_ctx* ctx, int accumulate, void* pixel_grad_or_null, void* hip_stream);
 
+/* The same step for a slide whose activations do not fit the arena (the paper's resource-constrained setting;
+ * Results, gradient equivalence: the gradients of a slide are the sum over any partition of its tiles once the
+ * feature gradients are known).  The tiles go through the encoder in chunks of at most chunk_tiles: first every
+ * chunk forward without keeping anything (features only), then aggregator, loss and feature gradients on all N
+ * rows, then chunk by chunk a second forward with the activations kept and the backward seeded with that chunk's
+ * feature gradients, accumulating the parameter gradients.  One call does forward and backward; it costs one extra
+ * encoder forward.  Arguments as slide_step_fwd / slide_step_bwd; pixel_grad_or_null: [N,3,S,S] of T.
+ * The arena must hold slide_chunked_arena_bytes(N, chunk_tiles).  Errors as slide_step_fwd. */
+size_t slide_chunked_arena_bytes(const slide_ctx* ctx, int64_t N, int64_t chunk_tiles);
+int  slide_step_chunked(slide_ctx* ctx, const void* pixels, int64_t N, int64_t chunk_tiles, int32_t label,
+                        int accumulate, float* loss_out, float* logits_out_or_null, float* alpha_out_or_null,
+                        void* pixel_grad_or_null, void* hip_stream);
+
 /* Device pointers into the arena, valid after slide_step_fwd / slide_step_bwd until
  * the next forward: features H [N,D] and feature gradients G [N,D], float32. */
 const void* slide_features(const slide_ctx* ctx);

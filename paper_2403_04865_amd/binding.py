@@ -62,6 +62,9 @@ _SYMS = {
     "mil_pool_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int, C.c_void_p]),
     "slide_step_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "slide_step_bwd": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
+    "slide_chunked_arena_bytes": (C.c_size_t, [C.c_void_p, C.c_int64, C.c_int64]),
+    "slide_step_chunked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "slide_features": (C.c_void_p, [C.c_void_p]),
     "slide_feature_grads": (C.c_void_p, [C.c_void_p]),
     "slide_last_hip_error": (C.c_int, []),
@@ -185,6 +188,15 @@ class SlideLib:
 
     def slide_step_bwd(self, accumulate, pixel_grad=None, stream=None):
         self._check(self.lib.slide_step_bwd(self.ctx, int(accumulate), _ptr(pixel_grad), _stream(stream)), "slide_step_bwd")
+
+    def slide_chunked_arena_bytes(self, N, chunk_tiles):
+        return int(self.lib.slide_chunked_arena_bytes(self.ctx, N, chunk_tiles))
+
+    def slide_step_chunked(self, pixels, N, chunk_tiles, label, accumulate, loss=None, logits=None, alpha=None,
+                           pixel_grad=None, stream=None):
+        self._check(self.lib.slide_step_chunked(self.ctx, _ptr(pixels), N, chunk_tiles, label, int(accumulate),
+                                                _ptr(loss), _ptr(logits), _ptr(alpha), _ptr(pixel_grad),
+                                                _stream(stream)), "slide_step_chunked")
 
     def slide_features(self):
         return self.lib.slide_features(self.ctx)

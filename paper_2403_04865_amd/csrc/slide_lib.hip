@@ -841,6 +841,53 @@ int slide_step_bwd(slide_ctx* c, int accumulate, void* pixel_grad, void* stream)
   return rc;
 }
 
+size_t slide_chunked_arena_bytes(const slide_ctx* c, int64_t N, int64_t chunk_tiles) {
+  if (!c || N <= 0 || chunk_tiles <= 0) return 0;
+  if (chunk_tiles > N) chunk_tiles = N;
+  return make_layout(c, chunk_tiles, N, c->cfg.recompute ? KEEP_INPUTS : KEEP_ALL).total;
+}
+
+int slide_step_chunked(slide_ctx* c, const void* pixels, int64_t N, int64_t chunk_tiles, int32_t label, int accumulate,
+                       float* loss, float* logits, float* alpha, void* pixel_grad, void* stream) {
+  int rc = check_bound(c);
+  if (rc) return rc;
+  if (!pixels || N <= 0 || chunk_tiles <= 0) return SLIDE_EINVAL;
+  if (label < 0 || label >= (c->C == 1 ? 2 : c->C)) return SLIDE_EINVAL;
+  if (chunk_tiles > N) chunk_tiles = N;
+  hipStream_t s = (hipStream_t)stream;
+  // the pool part of the layout (features H, feature gradients G, pool work space) depends on N only and lies in
+  // front of the encoder part, so every chunk call below sees H and G at the same place
+  Layout y = make_layout(c, chunk_tiles, N, c->cfg.recompute ? KEEP_INPUTS : KEEP_ALL);
+  if (y.total > c->arena_bytes) return SLIDE_EARENA;
+  const size_t tile_bytes = (size_t)3 * c->cfg.tile * c->cfg.tile * elem_size(c->dt);
+  const size_t row_bytes = (size_t)c->D * 4;
+  char* H = c->arena + y.p_H;
+  char* G = c->arena + y.p_G;
+  // pass 1: features of every tile, nothing kept
+  for (int64_t t0 = 0; t0 < N; t0 += chunk_tiles) {
+    int64_t n = N - t0 < chunk_tiles ? N - t0 : chunk_tiles;
+    rc = enc_fwd(c, (const char*)pixels + t0 * tile_bytes, n, H + t0 * row_bytes, false, N, s);
+    if (rc) return rc;
+  }
+  // aggregator and loss on the whole slide, then the gradient of every feature row
+  rc = pool_fwd(c, y, H, N, label, loss, logits, alpha, s);
+  if (rc) return rc;
+  rc = pool_bwd(c, y, H, N, label, G, accumulate, s);
+  if (rc) return rc;
+  // pass 2: chunk by chunk, forward again with the activations kept, backward seeded with the chunk's rows of G
+  for (int64_t t0 = 0; t0 < N; t0 += chunk_tiles) {
+    int64_t n = N - t0 < chunk_tiles ? N - t0 : chunk_tiles;
+    rc = enc_fwd(c, (const char*)pixels + t0 * tile_bytes, n, H + t0 * row_bytes, true, N, s);
+    if (rc) return rc;
+    rc = enc_bwd(c, G + t0 * row_bytes, n, (accumulate || t0 > 0) ? 1 : 0,
+                 pixel_grad ? (char*)pixel_grad + t0 * tile_bytes : nullptr, s);
+    if (rc) return rc;
+  }
+  c->enc_saved = false;
+  c->step_saved = false;
+  return SLIDE_OK;
+}
+
 const void* slide_features(const slide_ctx* c) {
   if (!c || !c->arena) return nullptr;
   return c->arena + c->enc_layout.p_H;

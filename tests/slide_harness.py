@@ -15,7 +15,8 @@ def lib_config(cfg: gen.SlideConfig, dtype: int, recompute: int = 0):
 class GpuSlide:
     """A bound library context on cuda:0 with flat parameter / gradient vectors."""
 
-    def __init__(self, cfg: gen.SlideConfig, prm: dict, dtype: int, n_tiles: int, recompute: int = 0):
+    def __init__(self, cfg: gen.SlideConfig, prm: dict, dtype: int, n_tiles: int, recompute: int = 0,
+                 arena_bytes: int | None = None):
         import torch
         from paper_2403_04865_amd import SlideLib
         self.torch = torch
@@ -34,9 +35,10 @@ class GpuSlide:
         self.shapes = shapes
         self.params = torch.from_numpy(flat).to(self.dev)
         self.grads = torch.zeros_like(self.params)
-        self.arena = torch.empty(self.lib.slide_arena_bytes(n_tiles) + 256, dtype=torch.uint8, device=self.dev)
+        nbytes = self.lib.slide_arena_bytes(n_tiles) if arena_bytes is None else arena_bytes(self.lib)
+        self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.dev)
         off = (-self.arena.data_ptr()) % 256
-        self.arena = self.arena[off:off + self.lib.slide_arena_bytes(n_tiles)]
+        self.arena = self.arena[off:off + nbytes]
         self.lib.slide_bind(self.params, self.grads, self.arena)
 
     def to_dev(self, x):
@@ -52,6 +54,23 @@ class GpuSlide:
         off = ptr - self.arena.data_ptr()
         n = int(np.prod(shape)) * 4
         return self.arena[off:off + n].view(torch.float32).reshape(shape).cpu().numpy().astype(np.float64)
+
+    def step_chunked(self, X, label, chunk_tiles, want_pixel_grad=True, accumulate=False):
+        """The same outputs as step() through slide_step_chunked (the arena may be smaller than step() needs)."""
+        torch = self.torch
+        N = X.shape[0]
+        px = self.to_dev(X)
+        loss = torch.zeros(1, device=self.dev)
+        logits = torch.zeros(self.cfg.n_classes, device=self.dev)
+        alpha = torch.zeros(N, device=self.dev)
+        dX = torch.zeros_like(px) if want_pixel_grad else None
+        self.lib.slide_step_chunked(px, N, chunk_tiles, label, accumulate, loss, logits, alpha, dX)
+        torch.cuda.synchronize()
+        H = self.view(self.lib.slide_features(), (N, self.cfg.dim))
+        G = self.view(self.lib.slide_feature_grads(), (N, self.cfg.dim))
+        return {"loss": float(loss.item()), "logits": logits.cpu().numpy().astype(np.float64),
+                "alpha": alpha.cpu().numpy().astype(np.float64), "H": H, "G": G, "grads": self.grads_dict(),
+                "dX": None if dX is None else dX.float().cpu().numpy().astype(np.float64)}
 
     def step(self, X, label, want_pixel_grad=True, accumulate=False):
         torch = self.torch
