@@ -222,6 +222,12 @@ __device__ __forceinline__ void ln_st8(bf16* p, const float (&v)[8]) {
   }
   *reinterpret_cast<lnu4*>(p) = r;
 }
+template <int LPR>
+__device__ __forceinline__ float sum_row(float v) {   // over the LPR lanes of a row group
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
 __device__ __forceinline__ float sum16(float v) {   // over the 16 lanes of a row group
 #pragma unroll
   for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -272,7 +278,9 @@ __global__ void __launch_bounds__(256) ln_fwd_row16_k(const bf16* __restrict__ x
 
 // dx = (dres ? dres : 0) + rstd * (dxh - mean(dxh) - xh * mean(dxh * xh)), dxh = dy * gamma;
 // dgamma / dbeta partials of the workgroup -> part[block][0][D], part[block][1][D]
-template <int NP>
+// LPR lanes per row (16 or 32), NP chunks of 8 columns per lane: D = 8 * LPR * NP.  (768 columns on 16 lanes would
+// need 240 registers for the per-lane arrays and leave one wavefront per SIMD: 35 % of the HBM rate instead of 70 %.)
+template <int NP, int LPR>
 __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x, long long xs,
                                                       const bf16* __restrict__ dy, long long dys,
                                                       const float* __restrict__ gam, const bf16* __restrict__ dres,
@@ -281,21 +289,21 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
                                                       bf16* __restrict__ uo, long long us) {
   // uo != nullptr: the normalised rows xh * gamma + beta (the forward output, which the weight gradient of the
   // following linear map needs and the forward did not keep) are written on the way, [rows][us]
-  constexpr int D = 128 * NP;
+  constexpr int D = 8 * LPR * NP, RPW = 64 / LPR;   // rows per wavefront
   __shared__ float red[4 * 2 * D];
-  int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l16 = lane & 15, grp = lane >> 4;
+  int lane = threadIdx.x & 63, w = threadIdx.x >> 6, l16 = lane & (LPR - 1), grp = lane / LPR;
   float dg[NP][8], db[NP][8], g[NP][8];
 #pragma unroll
   for (int k = 0; k < NP; ++k) {
-    int c = (l16 + 16 * k) * 8;
+    int c = (l16 + LPR * k) * 8;
     float4 g0 = *reinterpret_cast<const float4*>(gam + c), g1 = *reinterpret_cast<const float4*>(gam + c + 4);
     g[k][0] = g0.x; g[k][1] = g0.y; g[k][2] = g0.z; g[k][3] = g0.w; g[k][4] = g1.x; g[k][5] = g1.y; g[k][6] = g1.z; g[k][7] = g1.w;
 #pragma unroll
     for (int e = 0; e < 8; ++e) { dg[k][e] = 0.f; db[k][e] = 0.f; }
   }
-  long long nsets = (rows + 3) / 4;   // sets of four rows; a wavefront takes every (gridDim * 4)-th set
+  long long nsets = (rows + RPW - 1) / RPW;   // sets of RPW rows; a wavefront takes every (gridDim * 4)-th set
   for (long long set = (long long)blockIdx.x * 4 + w; set < nsets; set += (long long)gridDim.x * 4) {
-    long long r = set * 4 + grp;
+    long long r = set * RPW + grp;
     bool ok = r < rows;
     float okf = ok ? 1.f : 0.f;
     long long rc = ok ? r : rows - 1;
@@ -305,13 +313,13 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
     float sum = 0.f;
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
-      int c = (l16 + 16 * k) * 8;
+      int c = (l16 + LPR * k) * 8;
       ln_ld8(xr + c, v[k]);
       ln_ld8(dyr + c, d[k]);
 #pragma unroll
       for (int e = 0; e < 8; ++e) sum += v[k][e];
     }
-    float mean = sum16(sum) * (1.0f / D);
+    float mean = sum_row<LPR>(sum) * (1.0f / D);
     float sq = 0.f;
 #pragma unroll
     for (int k = 0; k < NP; ++k)
@@ -320,7 +328,7 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
         v[k][e] -= mean;
         sq += v[k][e] * v[k][e];
       }
-    float rstd = 1.0f / sqrtf(sum16(sq) * (1.0f / D) + eps);
+    float rstd = 1.0f / sqrtf(sum_row<LPR>(sq) * (1.0f / D) + eps);
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int k = 0; k < NP; ++k)
@@ -334,12 +342,12 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
         s1 += d[k][e];
         s2 += d[k][e] * v[k][e];
       }
-    s1 = sum16(s1) * (1.0f / D);
-    s2 = sum16(s2) * (1.0f / D);
+    s1 = sum_row<LPR>(s1) * (1.0f / D);
+    s2 = sum_row<LPR>(s2) * (1.0f / D);
     if (uo && ok) {
 #pragma unroll
       for (int k = 0; k < NP; ++k) {
-        int c = (l16 + 16 * k) * 8;
+        int c = (l16 + LPR * k) * 8;
         float4 b0 = *reinterpret_cast<const float4*>(bet + c), b1 = *reinterpret_cast<const float4*>(bet + c + 4);
         float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w}, o[8];
 #pragma unroll
@@ -350,7 +358,7 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
     if (ok) {
 #pragma unroll
       for (int k = 0; k < NP; ++k) {
-        int c = (l16 + 16 * k) * 8;
+        int c = (l16 + LPR * k) * 8;
         float o[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = rstd * (d[k][e] - s1 - v[k][e] * s2);
@@ -364,22 +372,23 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
       }
     }
   }
-  // the four row groups of a wavefront, then the four wavefronts
+  // the row groups of a wavefront, then the four wavefronts
 #pragma unroll
   for (int k = 0; k < NP; ++k)
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      dg[k][e] += __shfl_xor(dg[k][e], 16, 64);
-      dg[k][e] += __shfl_xor(dg[k][e], 32, 64);
-      db[k][e] += __shfl_xor(db[k][e], 16, 64);
-      db[k][e] += __shfl_xor(db[k][e], 32, 64);
+#pragma unroll
+      for (int o = LPR; o < 64; o <<= 1) {
+        dg[k][e] += __shfl_xor(dg[k][e], o, 64);
+        db[k][e] += __shfl_xor(db[k][e], o, 64);
+      }
     }
   if (grp == 0) {
 #pragma unroll
     for (int k = 0; k < NP; ++k)
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        int c = (l16 + 16 * k) * 8 + e;
+        int c = (l16 + LPR * k) * 8 + e;
         red[(w * 2 + 0) * D + c] = dg[k][e];
         red[(w * 2 + 1) * D + c] = db[k][e];
       }
@@ -528,8 +537,8 @@ hipError_t launch_ln_bwd(int dt, const void* x, long long x_stride, const void* 
   size_t lds = (size_t)4 * 2 * D * sizeof(float);
   if (dt == DT_BF16 && !dy_f32 && ln_row16_ok(x, dy, dx_out, x_stride, dy_stride, o_stride, D) &&
       ((uintptr_t)gam & 15) == 0 && ((uintptr_t)dres & 15) == 0) {
-    if (D == 384) hipLaunchKernelGGL(ln_bwd_row16_k<3>, grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride);
-    else hipLaunchKernelGGL(ln_bwd_row16_k<6>, grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride);
+    if (D == 384) hipLaunchKernelGGL((ln_bwd_row16_k<3, 16>), grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride);
+    else hipLaunchKernelGGL((ln_bwd_row16_k<3, 32>), grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride);
     return hipGetLastError();
   }
   {
