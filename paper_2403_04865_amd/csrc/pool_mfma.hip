@@ -305,8 +305,15 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
   double z[4 * CJ];
 #pragma unroll
   for (int i = 0; i < 4 * CJ; ++i) z[i] = 0.0;
-  double run_l = 0.0;
-  float run_m = -INFINITY;
+  // |a_n| <= sum_j |w_j| (tanh * sigmoid lies in (-1, 1)): where that bound is small enough for exp not to underflow
+  // it serves as the softmax shift of every block, which takes the running maximum and the rescaling (two wave-wide
+  // reductions and a chain of dependent exponentials per block) out of the loop
+  float wabs = 0.f;
+  for (int j = lane; j < MH; j += 64) wabs += fabsf(p.w[j]);
+  wabs = wave_sum(wabs);
+  const bool fixed = wabs <= 40.f;
+  float run_m = fixed ? wabs : -INFINITY;
+  double lsum = 0.0;   // per lane: the softmax terms of its row of every block
 
   auto block = [&](float4 (&cur)[NR], float4 (&nxt)[NR], int buf, long long gi) __attribute__((always_inline)) {
     f32x16 av, au;
@@ -355,12 +362,19 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
       float a = apart[li] + apart[RB + li] + apart[2 * RB + li] + apart[3 * RB + li];
       bool ok = n0 + li < p.N;
       a_out = a;
-      a = ok ? a : -INFINITY;
-      float m = fmaxf(run_m, wave_max(a));   // finite: the block has at least one row
-      float e = __expf(a - m);               // lanes li and li + 32: row li
-      float sc = __expf(run_m - m);          // exp(-inf) = 0 on the first block
-      run_m = m;
-      run_l = run_l * (double)sc + (double)(0.5f * wave_sum(e));
+      float e, sc;
+      if (fixed) {   // uniform: the shift is a bound of every logit, no running maximum, nothing to rescale
+        e = ok ? __expf(a - run_m) : 0.f;
+        sc = 1.0f;
+      } else {
+        a = ok ? a : -INFINITY;
+        float m = fmaxf(run_m, wave_max(a));   // finite: the block has at least one row
+        e = __expf(a - m);                     // lanes li and li + 32: row li
+        sc = __expf(run_m - m);                // exp(-inf) = 0 on the first block
+        run_m = m;
+        lsum *= (double)sc;
+      }
+      lsum += (double)e;   // summed over the rows once, at the end
       float ek[4];
 #pragma unroll
       for (int k = 0; k < 4; ++k) ek[k] = __shfl(e, 4 * (rgrp & 7) + k, 64);
@@ -408,7 +422,9 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
     for (int c = 0; c < 4; ++c) zred[rgrp * D + (cl + 32 * j) * 4 + c] = z[4 * j + c];
   __syncthreads();
   double* out = p.part + (size_t)blockIdx.x * (2 + D);
-  if (tid == 0) { out[0] = (double)run_m; out[1] = run_l; }
+  // lanes li and li + 32 hold the same rows: sum over one half
+  for (int o = 1; o < 32; o <<= 1) lsum += __shfl_xor(lsum, o, 64);
+  if (tid == 0) { out[0] = (double)run_m; out[1] = lsum; }
   for (int d = tid; d < D; d += 256) {
     double t = 0.0;
 #pragma unroll
