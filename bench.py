@@ -79,7 +79,7 @@ def pool_sweep(a):
         loss = torch.zeros(1, device=dev)
         res = {"N": N, "feature_MB": round(N * cfg.dim * 4 / 1e6, 1)}
         for which, kid in (("fwd", names.index("pool_fwd")), ("bwd", names.index("pool_bwd"))):
-            reps = 5
+            reps = 20
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             for it in range(reps + 1):
                 if it == 1:
