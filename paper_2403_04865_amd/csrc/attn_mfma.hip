@@ -99,6 +99,35 @@ __device__ __forceinline__ void load_rm(const bf16* __restrict__ g, long long gs
   }
 }
 
+// Two such copies at once by a workgroup of NTHR threads, all global loads issued before the first LDS store: the
+// loop above waits for every load before it stores (its trip count and the row test are run-time), which puts one
+// memory latency per iteration and matrix in front of the kernel's work, as long as the work itself.
+// Rows past T0 / T1 are filled with zeros.
+template <int DH, int TP, int NTHR>
+__device__ __forceinline__ void load_rm2(const bf16* __restrict__ g0, long long gs0, int T0, bf16* dst0,
+                                         const bf16* __restrict__ g1, long long gs1, int T1, bf16* dst1) {
+  constexpr int CH = DH / 8, TOTAL = TP * CH, ITER = (TOTAL + NTHR - 1) / NTHR;
+  u32x4 va[ITER], vb[ITER];
+#pragma unroll
+  for (int i = 0; i < ITER; ++i) {
+    int c = threadIdx.x + i * NTHR;
+    int row = c / CH, kc = c % CH;
+    int r0 = row < T0 ? row : T0 - 1, r1 = row < T1 ? row : T1 - 1;
+    va[i] = ldg16(g0 + r0 * gs0 + kc * 8);
+    vb[i] = ldg16(g1 + r1 * gs1 + kc * 8);
+  }
+#pragma unroll
+  for (int i = 0; i < ITER; ++i) {
+    int c = threadIdx.x + i * NTHR;
+    int row = c / CH, kc = c % CH;
+    if (TOTAL % NTHR == 0 || c < TOTAL) {
+      u32x4 z = {0, 0, 0, 0};
+      *reinterpret_cast<u32x4*>(dst0 + row * (DH + 8) + kc * 8) = row < T0 ? va[i] : z;
+      *reinterpret_cast<u32x4*>(dst1 + row * (DH + 8) + kc * 8) = row < T1 ? vb[i] : z;
+    }
+  }
+}
+
 // same source, transposed into LDS [DH][TP+8]
 template <int DH>
 __device__ __forceinline__ void load_tr(const bf16* __restrict__ g, long long gs, int T, int TP, bf16* dst) {
@@ -143,8 +172,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
   int D = H * DH;
   long long gs = 3LL * D;
   const bf16* base = qkv + tile * T * gs + h * DH;
-  load_rm<DH>(base + D, gs, T, TP, Ks);
-  load_rm<DH>(base + 2 * D, gs, T, TP, Vs);
+  load_rm2<DH, TP, attn_threads<NB>()>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs);
   __syncthreads();
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
@@ -257,8 +285,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
   int D = H * DH;
   long long gs = 3LL * D;
   const bf16* base = qkv + tile * T * gs + h * DH;
-  load_rm<DH>(base + D, gs, T, TP, Ks);
-  load_rm<DH>(base + 2 * D, gs, T, TP, Vs);
+  load_rm2<DH, TP, attn_threads<NB>()>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs);
   __syncthreads();
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
@@ -375,8 +402,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
   const bf16* gbase = dO + tile * T * (long long)D + h * DH;
   const bf16* obase = O + tile * T * (long long)D + h * DH;
   const int TG = cls_only ? 1 : T;   // rows of dO that are defined (cls_only: query 0 alone carries a gradient)
-  load_rm<DH>(base, gs, T, TP, Qs);
-  load_rm<DH>(gbase, D, TG, TP, Gs);
+  load_rm2<DH, TP, 256>(base, gs, T, Qs, gbase, D, TG, Gs);
   for (int i = threadIdx.x; i < TP; i += blockDim.x) {
     float d = 0.f, lv = INFINITY;
     if (i < TG) {
