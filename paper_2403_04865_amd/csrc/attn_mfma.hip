@@ -172,10 +172,19 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
   int D = H * DH;
   long long gs = 3LL * D;
   const bf16* base = qkv + tile * T * gs + h * DH;
-  load_rm2<DH, TP, attn_threads<NB>()>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs);
-  __syncthreads();
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
+  // the wavefront's query fragments are requested before the K/V copy so that they arrive with it (asked for after
+  // the barrier they would cost a memory latency of their own)
+  bf16x8 fq[KS];
+  {
+    int q0 = wave * 32 + li;
+    q0 = q0 < T ? q0 : T - 1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fq[ks] = as_bf16x8(ldg16(base + q0 * gs + ks * 16 + h2 * 8));
+  }
+  load_rm2<DH, TP, attn_threads<NB>()>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs);
+  __syncthreads();
   float sl2 = LOG2E / sqrtf((float)DH);
   // lane-dependent parts of the LDS addresses, formed once; the key-block loop only advances them
   const bf16* const krow0 = Ks + li * LDR + h2 * 8;
@@ -184,9 +193,10 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
   for (int qb = wave; qb < nqb; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
     int qc = q < T ? q : T - 1;
-    bf16x8 fq[KS];
+    if (qb != wave) {   // uniform; later query blocks of a wavefront (workgroups with fewer wavefronts than blocks)
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) fq[ks] = as_bf16x8(ldg16(base + qc * gs + ks * 16 + h2 * 8));
+      for (int ks = 0; ks < KS; ++ks) fq[ks] = as_bf16x8(ldg16(base + qc * gs + ks * 16 + h2 * 8));
+    }
     // keys are taken one block of 32 at a time with a running maximum and sum (the whole row of
     // scores never sits in registers); o is rescaled when the maximum moves
     f32x16 o[DB];
@@ -285,10 +295,34 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
   int D = H * DH;
   long long gs = 3LL * D;
   const bf16* base = qkv + tile * T * gs + h * DH;
-  load_rm2<DH, TP, attn_threads<NB>()>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs);
-  __syncthreads();
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
+  // per query block: fragments of Q and dO, delta = dO . O, the row's log-sum-exp
+  bf16x8 fq[KS], fdo[KS];
+  float delta, lq;
+  auto load_qblock = [&](int qb) __attribute__((always_inline)) {
+    int q = qb * 32 + li;
+    int qc = q < T ? q : T - 1;
+    int qg = cls_only ? 0 : qc;   // cls_only: only row 0 of dO (and of O) is defined
+    const bf16* orow = O + (tile * T + qg) * D + h * DH;
+    const bf16* gor = dO + (tile * T + qg) * D + h * DH;
+    delta = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      fq[ks] = as_bf16x8(ldg16(base + qc * gs + ks * 16 + h2 * 8));
+      fdo[ks] = as_bf16x8(ldg16(gor + ks * 16 + h2 * 8));
+      if (cls_only && q != 0) fdo[ks] = as_bf16x8(u32x4{0, 0, 0, 0});   // only query 0 carries a gradient
+      bf16x8 fo = as_bf16x8(ldg16(orow + ks * 16 + h2 * 8));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) delta += (float)fdo[ks][i] * (float)fo[i];
+    }
+    delta += __shfl_xor(delta, 32, 64);
+    lq = lse[(tile * H + h) * T + qc] * LOG2E;
+  };
+  // the first block's loads are requested before the K/V copy so that they arrive with it
+  load_qblock(wave < NB ? wave : 0);
+  load_rm2<DH, TP, attn_threads<NB>()>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs);
+  __syncthreads();
   float scale = 1.0f / sqrtf((float)DH);
   float sl2 = LOG2E * scale;
   const bf16* const krow0 = Ks + li * LDR + h2 * 8;
@@ -306,21 +340,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
       }
       continue;
     }
-    bf16x8 fq[KS], fdo[KS];
-    float delta = 0.f;
-    const bf16* orow = O + (tile * T + qc) * D + h * DH;
-    const bf16* gor = dO + (tile * T + qc) * D + h * DH;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      fq[ks] = as_bf16x8(ldg16(base + qc * gs + ks * 16 + h2 * 8));
-      fdo[ks] = as_bf16x8(ldg16(gor + ks * 16 + h2 * 8));
-      if (cls_only && q != 0) fdo[ks] = as_bf16x8(u32x4{0, 0, 0, 0});   // only query 0 carries a gradient; the rest of dO is not defined
-      bf16x8 fo = as_bf16x8(ldg16(orow + ks * 16 + h2 * 8));
-#pragma unroll
-      for (int i = 0; i < 8; ++i) delta += (float)fdo[ks][i] * (float)fo[i];
-    }
-    delta += __shfl_xor(delta, 32, 64);
-    float lq = lse[(tile * H + h) * T + qc] * LOG2E;
+    if (qb != wave) load_qblock(qb);   // uniform; later blocks of a wavefront (fewer wavefronts than blocks)
     f32x16 dq[DB];
 #pragma unroll
     for (int d = 0; d < DB; ++d)
@@ -402,25 +422,43 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
   const bf16* gbase = dO + tile * T * (long long)D + h * DH;
   const bf16* obase = O + tile * T * (long long)D + h * DH;
   const int TG = cls_only ? 1 : T;   // rows of dO that are defined (cls_only: query 0 alone carries a gradient)
-  load_rm2<DH, TP, 256>(base, gs, T, Qs, gbase, D, TG, Gs);
-  for (int i = threadIdx.x; i < TP; i += blockDim.x) {
-    float d = 0.f, lv = INFINITY;
-    if (i < TG) {
-#pragma unroll
-      for (int c = 0; c < DH / 8; ++c) {
-        bf16x8 a = as_bf16x8(ldg16(gbase + (long long)i * D + c * 8));
-        bf16x8 b = as_bf16x8(ldg16(obase + (long long)i * D + c * 8));
-#pragma unroll
-        for (int e = 0; e < 8; ++e) d += (float)a[e] * (float)b[e];
-      }
-      lv = lse[(tile * H + h) * T + i] * LOG2E;
-    }
-    dl[i] = d;
-    ls[i] = lv;
-  }
-  __syncthreads();
+  static_assert(TP <= 256, "one row of delta / lse per thread");
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
+  // Everything that comes from global memory before the main loop is requested up front, in one go, so that the
+  // workgroup waits for one memory latency and not for one per step: delta_i = dO_i . O_i and the log-sum-exp of row
+  // i = thread id (no branches around the loads: rows past the end read the last defined row and are overwritten
+  // below), the K/V fragments of the wavefront's first key block, then the Q / dO copy.
+  float d_row = 0.f, l_row;
+  {
+    int i = threadIdx.x < TG ? threadIdx.x : TG - 1;
+#pragma unroll
+    for (int c = 0; c < DH / 8; ++c) {
+      bf16x8 x = as_bf16x8(ldg16(gbase + (long long)i * D + c * 8));
+      bf16x8 y = as_bf16x8(ldg16(obase + (long long)i * D + c * 8));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d_row += (float)x[e] * (float)y[e];
+    }
+    l_row = lse[(tile * H + h) * T + i] * LOG2E;
+  }
+  bf16x8 fk[KS], fv[KS];
+  auto load_kv = [&](int kb, bf16x8 (&k8)[KS], bf16x8 (&v8)[KS]) __attribute__((always_inline)) {
+    int key = kb * 32 + li;
+    int kc = key < T ? key : T - 1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      k8[ks] = as_bf16x8(ldg16(base + D + kc * gs + ks * 16 + h2 * 8));
+      v8[ks] = as_bf16x8(ldg16(base + 2 * D + kc * gs + ks * 16 + h2 * 8));
+    }
+  };
+  load_kv(wave, fk, fv);
+  load_rm2<DH, TP, 256>(base, gs, T, Qs, gbase, D, TG, Gs);
+  if (threadIdx.x < TP) {
+    bool def = threadIdx.x < TG;
+    dl[threadIdx.x] = def ? d_row : 0.f;
+    ls[threadIdx.x] = def ? l_row : INFINITY;   // +inf on padding rows: their probabilities come out as zero
+  }
+  __syncthreads();
   float scale = 1.0f / sqrtf((float)DH);
   float sl2 = LOG2E * scale;
   const bf16* const qrow0 = Qs + li * LDR + h2 * 8;
@@ -429,13 +467,10 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
   const bf16* const gtr0 = Gs + tr_lane_off(LDR, lane);
   for (int kb = wave; kb < NB; kb += 4) {
     int key = kb * 32 + li;
-    int kc = key < T ? key : T - 1;
-    bf16x8 fk[KS], fv[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      fk[ks] = as_bf16x8(ldg16(base + D + kc * gs + ks * 16 + h2 * 8));
-      fv[ks] = as_bf16x8(ldg16(base + 2 * D + kc * gs + ks * 16 + h2 * 8));
-    }
+    // the fragments of the wavefront's next key block travel while this one is worked on
+    const bool more = kb + 4 < NB;   // uniform
+    bf16x8 nk[KS], nv[KS];
+    if (more) load_kv(kb + 4, nk, nv);
     f32x16 dk[DB], dv[DB];
 #pragma unroll
     for (int d = 0; d < DB; ++d)
@@ -501,6 +536,10 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
           *reinterpret_cast<bf16x4*>(outk + d * 32 + g4 * 8 + h2 * 4) = vk;
           *reinterpret_cast<bf16x4*>(outv + d * 32 + g4 * 8 + h2 * 4) = vv;
         }
+    }
+    if (more) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) { fk[ks] = nk[ks]; fv[ks] = nv[ks]; }
     }
   }
 }
