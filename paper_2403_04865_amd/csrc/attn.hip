@@ -9,7 +9,7 @@ namespace sl {
 
 hipError_t launch_attn_fwd_mfma(const void* qkv, void* O, float* lse, long long n, int T, int H, int dh, int cls_only,
                                 hipStream_t s);
-hipError_t launch_attn_bwd_mfma(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
+hipError_t launch_attn_bwd_mfma(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv, float* delta_ws,
                                 long long n, int T, int H, int dh, int cls_only, hipStream_t s);
 bool attn_mfma_ok(int T, int dh);
 
@@ -186,10 +186,12 @@ hipError_t launch_attn_fwd(int dt, const void* qkv, void* O, float* lse, long lo
 }
 
 hipError_t launch_attn_bwd(int dt, const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
-                           long long n, int T, int H, int dh, bool use_mfma, hipStream_t s, bool cls_only) {
+                           long long n, int T, int H, int dh, bool use_mfma, hipStream_t s, bool cls_only, float* delta_ws) {
   if (n <= 0) return hipSuccess;
-  if (dt == DT_BF16 && use_mfma && attn_mfma_ok(T, dh))
-    return launch_attn_bwd_mfma(qkv, O, lse, dO, dqkv, n, T, H, dh, cls_only, s);
+  if (dt == DT_BF16 && use_mfma && attn_mfma_ok(T, dh)) {
+    if (!delta_ws) return hipErrorInvalidValue;
+    return launch_attn_bwd_mfma(qkv, O, lse, dO, dqkv, delta_ws, n, T, H, dh, cls_only, s);
+  }
   if (cls_only) return hipErrorInvalidValue;
   size_t lds = attn_lds_bytes(T, dh);
   dim3 grid((unsigned)(n * H));

@@ -103,9 +103,9 @@ __device__ __forceinline__ void load_rm(const bf16* __restrict__ g, long long gs
 // loop above waits for every load before it stores (its trip count and the row test are run-time), which puts one
 // memory latency per iteration and matrix in front of the kernel's work, as long as the work itself.
 // Rows past T0 / T1 are filled with zeros.
-template <int DH, int TP, int NTHR>
+template <int DH, int TP, int NTHR, bool FENCE, typename MID>
 __device__ __forceinline__ void load_rm2(const bf16* __restrict__ g0, long long gs0, int T0, bf16* dst0,
-                                         const bf16* __restrict__ g1, long long gs1, int T1, bf16* dst1) {
+                                         const bf16* __restrict__ g1, long long gs1, int T1, bf16* dst1, MID mid) {
   constexpr int CH = DH / 8, TOTAL = TP * CH, ITER = (TOTAL + NTHR - 1) / NTHR;
   u32x4 va[ITER], vb[ITER];
 #pragma unroll
@@ -116,6 +116,10 @@ __device__ __forceinline__ void load_rm2(const bf16* __restrict__ g0, long long 
     va[i] = ldg16(g0 + r0 * gs0 + kc * 8);
     vb[i] = ldg16(g1 + r1 * gs1 + kc * 8);
   }
+  // everything requested so far (also by the caller, before this call) is in flight before anything is waited for:
+  // `mid` is the caller's arithmetic on its own, older loads
+  if (FENCE) __builtin_amdgcn_sched_barrier(0);
+  mid();
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
     int c = threadIdx.x + i * NTHR;
@@ -183,7 +187,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) fq[ks] = as_bf16x8(ldg16(base + q0 * gs + ks * 16 + h2 * 8));
   }
-  load_rm2<DH, TP, attn_threads<NB>()>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs);
+  load_rm2<DH, TP, attn_threads<NB>(), false>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs, [] {});
   __syncthreads();
   float sl2 = LOG2E / sqrtf((float)DH);
   // lane-dependent parts of the LDS addresses, formed once; the key-block loop only advances them
@@ -282,7 +286,8 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
 template <int DH, int NB>
 __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
-                                                         bf16* __restrict__ dqkv, int T, int H, long long ntiles, int cls_only) {
+                                                         bf16* __restrict__ dqkv, float* __restrict__ delta_ws, int T, int H,
+                                                         long long ntiles, int cls_only) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
   bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
@@ -297,31 +302,41 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
   const bf16* base = qkv + tile * T * gs + h * DH;
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
-  // per query block: fragments of Q and dO, delta = dO . O, the row's log-sum-exp
-  bf16x8 fq[KS], fdo[KS];
+  // per query block: fragments of Q and dO, delta = dO . O, the row's log-sum-exp.  Requesting and consuming are
+  // separate so that the first block's loads and the K/V copy's are all in flight before anything is waited for.
+  bf16x8 fq[KS], fdo[KS], fo[KS];
   float delta, lq;
-  auto load_qblock = [&](int qb) __attribute__((always_inline)) {
+  auto issue_qblock = [&](int qb) __attribute__((always_inline)) {
     int q = qb * 32 + li;
     int qc = q < T ? q : T - 1;
     int qg = cls_only ? 0 : qc;   // cls_only: only row 0 of dO (and of O) is defined
     const bf16* orow = O + (tile * T + qg) * D + h * DH;
     const bf16* gor = dO + (tile * T + qg) * D + h * DH;
-    delta = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       fq[ks] = as_bf16x8(ldg16(base + qc * gs + ks * 16 + h2 * 8));
       fdo[ks] = as_bf16x8(ldg16(gor + ks * 16 + h2 * 8));
-      if (cls_only && q != 0) fdo[ks] = as_bf16x8(u32x4{0, 0, 0, 0});   // only query 0 carries a gradient
-      bf16x8 fo = as_bf16x8(ldg16(orow + ks * 16 + h2 * 8));
+      fo[ks] = as_bf16x8(ldg16(orow + ks * 16 + h2 * 8));
+    }
+    lq = lse[(tile * H + h) * T + qc];
+  };
+  auto finish_qblock = [&](int qb) __attribute__((always_inline)) {
+    int q = qb * 32 + li;
+    delta = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) delta += (float)fdo[ks][i] * (float)fo[i];
+    for (int ks = 0; ks < KS; ++ks) {
+      if (cls_only && q != 0) fdo[ks] = as_bf16x8(u32x4{0, 0, 0, 0});   // only query 0 carries a gradient
+#pragma unroll
+      for (int i = 0; i < 8; ++i) delta += (float)fdo[ks][i] * (float)fo[ks][i];
     }
     delta += __shfl_xor(delta, 32, 64);
-    lq = lse[(tile * H + h) * T + qc] * LOG2E;
+    lq *= LOG2E;
+    // kept for the key-owned pass (which would otherwise read dO and O once more to form it)
+    if (h2 == 0 && q < T) delta_ws[(tile * H + h) * T + q] = delta;
   };
-  // the first block's loads are requested before the K/V copy so that they arrive with it
-  load_qblock(wave < NB ? wave : 0);
-  load_rm2<DH, TP, attn_threads<NB>()>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs);
+  const int qb0 = wave < NB ? wave : 0;
+  issue_qblock(qb0);
+  load_rm2<DH, TP, attn_threads<NB>(), true>(base + D, gs, T, Ks, base + 2 * D, gs, T, Vs, [&] { finish_qblock(qb0); });
   __syncthreads();
   float scale = 1.0f / sqrtf((float)DH);
   float sl2 = LOG2E * scale;
@@ -340,7 +355,10 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
       }
       continue;
     }
-    if (qb != wave) load_qblock(qb);   // uniform; later blocks of a wavefront (fewer wavefronts than blocks)
+    if (qb != wave) {   // uniform; later blocks of a wavefront (fewer wavefronts than blocks)
+      issue_qblock(qb);
+      finish_qblock(qb);
+    }
     f32x16 dq[DB];
 #pragma unroll
     for (int d = 0; d < DB; ++d)
@@ -402,7 +420,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
 template <int DH, int NB>
 // (four wavefronts: this kernel needs more registers than seven wavefronts per workgroup, two workgroups per
 // compute unit, would leave it, and measured slower with seven and one workgroup)
-__global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restrict__ qkv, const bf16* __restrict__ O,
+__global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restrict__ qkv, const float* __restrict__ delta_ws,
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
                                                          bf16* __restrict__ dqkv, int T, int H, long long ntiles, int cls_only) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -420,26 +438,19 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
   long long gs = 3LL * D;
   const bf16* base = qkv + tile * T * gs + h * DH;
   const bf16* gbase = dO + tile * T * (long long)D + h * DH;
-  const bf16* obase = O + tile * T * (long long)D + h * DH;
   const int TG = cls_only ? 1 : T;   // rows of dO that are defined (cls_only: query 0 alone carries a gradient)
   static_assert(TP <= 256, "one row of delta / lse per thread");
   int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   int li = lane & 31, h2 = lane >> 5;
   // Everything that comes from global memory before the main loop is requested up front, in one go, so that the
-  // workgroup waits for one memory latency and not for one per step: delta_i = dO_i . O_i and the log-sum-exp of row
-  // i = thread id (no branches around the loads: rows past the end read the last defined row and are overwritten
-  // below), the K/V fragments of the wavefront's first key block, then the Q / dO copy.
-  float d_row = 0.f, l_row;
+  // workgroup waits for one memory latency and not for one per step: delta and log-sum-exp of row i = thread id (no
+  // branches around the loads: rows past the end read the last defined row and are overwritten below), the K/V
+  // fragments of the wavefront's first key block, then the Q / dO copy.
+  float d_row, l_row;   // delta_i = dO_i . O_i (left by the query-owned pass) and the log-sum-exp of row i = thread id
   {
     int i = threadIdx.x < TG ? threadIdx.x : TG - 1;
-#pragma unroll
-    for (int c = 0; c < DH / 8; ++c) {
-      bf16x8 x = as_bf16x8(ldg16(gbase + (long long)i * D + c * 8));
-      bf16x8 y = as_bf16x8(ldg16(obase + (long long)i * D + c * 8));
-#pragma unroll
-      for (int e = 0; e < 8; ++e) d_row += (float)x[e] * (float)y[e];
-    }
-    l_row = lse[(tile * H + h) * T + i] * LOG2E;
+    d_row = delta_ws[(tile * H + h) * T + i];
+    l_row = lse[(tile * H + h) * T + i];
   }
   bf16x8 fk[KS], fv[KS];
   auto load_kv = [&](int kb, bf16x8 (&k8)[KS], bf16x8 (&v8)[KS]) __attribute__((always_inline)) {
@@ -452,7 +463,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
     }
   };
   load_kv(wave, fk, fv);
-  load_rm2<DH, TP, 256>(base, gs, T, Qs, gbase, D, TG, Gs);
+  load_rm2<DH, TP, 256, true>(base, gs, T, Qs, gbase, D, TG, Gs, [&] { l_row *= LOG2E; });
   if (threadIdx.x < TP) {
     bool def = threadIdx.x < TG;
     dl[threadIdx.x] = def ? d_row : 0.f;
@@ -567,18 +578,18 @@ hipError_t fwd_go(const void* qkv, void* O, float* lse, long long n, int T, int 
 }
 
 template <int DH, int NB>
-hipError_t bwd_go(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv, long long n, int T,
-                  int H, int cls_only, hipStream_t s) {
+hipError_t bwd_go(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv, float* delta_ws,
+                  long long n, int T, int H, int cls_only, hipStream_t s) {
   size_t lq = bq_lds<DH, NB>(), lk = bk_lds<DH, NB>();
   hipError_t e = set_lds(attn_bwd_q_mfma_k<DH, NB>, lq);
   if (e != hipSuccess) return e;
   e = set_lds(attn_bwd_k_mfma_k<DH, NB>, lk);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((attn_bwd_q_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(attn_threads<NB>()), lq, s,
-                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n, cls_only);
+                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, delta_ws, T, H, n, cls_only);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL((attn_bwd_k_mfma_k<DH, NB>), dim3((unsigned)((n + 7) / 8 * 8 * H)), dim3(256), lk, s,
-                     (const bf16*)qkv, (const bf16*)O, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n, cls_only);
+                     (const bf16*)qkv, (const float*)delta_ws, lse, (const bf16*)dO, (bf16*)dqkv, T, H, n, cls_only);
   return hipGetLastError();
 }
 
@@ -596,10 +607,10 @@ hipError_t launch_attn_fwd_mfma(const void* qkv, void* O, float* lse, long long 
   return fwd_go<32, 1>(qkv, O, lse, n, T, H, cls_only, s);
 }
 
-hipError_t launch_attn_bwd_mfma(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
+hipError_t launch_attn_bwd_mfma(const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv, float* delta_ws,
                                 long long n, int T, int H, int dh, int cls_only, hipStream_t s) {
-  if (dh == 64) return bwd_go<64, 7>(qkv, O, lse, dO, dqkv, n, T, H, cls_only, s);
-  return bwd_go<32, 1>(qkv, O, lse, dO, dqkv, n, T, H, cls_only, s);
+  if (dh == 64) return bwd_go<64, 7>(qkv, O, lse, dO, dqkv, delta_ws, n, T, H, cls_only, s);
+  return bwd_go<32, 1>(qkv, O, lse, dO, dqkv, delta_ws, n, T, H, cls_only, s);
 }
 
 }  // namespace sl

@@ -174,7 +174,8 @@ bool attn_cls_only_ok(int dt, int T, int dh, bool use_mfma);
 hipError_t launch_attn_fwd(int dt, const void* qkv, void* O, float* lse, long long n, int T, int H, int dh,
                            bool use_mfma, hipStream_t s, bool cls_only = false);
 hipError_t launch_attn_bwd(int dt, const void* qkv, const void* O, const float* lse, const void* dO, void* dqkv,
-                           long long n, int T, int H, int dh, bool use_mfma, hipStream_t s, bool cls_only = false);
+                           long long n, int T, int H, int dh, bool use_mfma, hipStream_t s, bool cls_only = false,
+                           float* delta_ws = nullptr);   // [n][H][T] floats, needed by the matrix-core kernels
 size_t attn_lds_bytes(int T, int dh);
 
 // Gated-attention MIL pool.

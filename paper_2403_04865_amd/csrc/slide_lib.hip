@@ -44,6 +44,7 @@ struct Layout {
   // encoder
   size_t enc_begin;
   size_t e_patches, e_x, e_qkv, e_O, e_lse, e_xmid, e_m;              // first instance
+  size_t e_dl;                                                        // [n][H][T] fp32 work space of the attention backward
   size_t s_x, s_qkv, s_O, s_lse, s_xmid, s_m, s_a;                    // per-layer strides (0 when not saved)
   size_t e_u, e_a, e_dm, e_dxA, e_dxB, e_dxAt, e_dxBt, e_du, e_dqkv;
 };
@@ -142,6 +143,7 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   y.e_O = take(0); cur += (size_t)inst * align256(M * D * e);
   y.s_lse = save ? align256((size_t)nn * c->H * c->T * 4) : 0;
   y.e_lse = take(0); cur += (size_t)inst * align256((size_t)nn * c->H * c->T * 4);
+  y.e_dl = take(bwd ? (size_t)nn * c->H * c->T * 4 : 0);
   if (bwd) {
     y.s_xmid = save ? align256(M * D * rs) : 0;
     y.e_xmid = take(0); cur += (size_t)inst * align256(M * D * rs);
@@ -506,7 +508,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
         gemm_nt(r, g);
       }
       launch(r, K_ATTN_BWD, 10.0 * n * c->H * (double)T * c->dh, (double)M * 7 * D * e,
-             [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s, true); });
+             [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s, true, (float*)(ar + y.e_dl)); });
       ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
       gemm_tn(r, dqkv, 3 * D, id, u, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
       {
@@ -544,7 +546,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       gemm_nt(r, g);
     }
     launch(r, K_ATTN_BWD, 10.0 * n * c->H * (double)T * T * c->dh, (double)M * 9 * D * e,
-           [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s); });
+           [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s, false, (float*)(ar + y.e_dl)); });
     {
       GemmNT g{};
       g.A = dqkv; g.lda = 3 * D; g.B = weight_t(c, wi + 0); g.ldb = 3 * D; g.M = M; g.N = D; g.K = 3 * D;
