@@ -38,6 +38,8 @@ __device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[
   }
 }
 
+__device__ __attribute__((aligned(16))) unsigned int g_zero16[4];
+
 __global__ void __launch_bounds__(256, 2) gemm_tn_mfma_k(GemmTN g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* At = reinterpret_cast<bf16*>(smem);   // [2][128][LDK]
@@ -64,12 +66,30 @@ __global__ void __launch_bounds__(256, 2) gemm_tn_mfma_k(GemmTN g) {
   bool col_ok = cbase < ncols;  // N1, N2 are multiples of 8 (checked on the host)
   bf16* dst = (isB ? Bt : At) + (cb * 8) * LDK + mb * 8;
 
+  // The 8 consecutive rows of a thread: no branch around the loads (they would be issued and waited for one by one)
+  // and one 32-bit division per step instead of a 64-bit one per row: rows past the slab's end re-read its last
+  // row and are zeroed afterwards; threads whose columns lie outside the matrix read a row of zeros with stride 0.
+  const bf16* lbase = col_ok ? src + cbase : reinterpret_cast<const bf16*>(g_zero16);
+  const long long lld = col_ok ? ld : 0;
   auto load = [&](long long mstep, u32x4 (&v)[8]) {
+    long long m0 = mstep + mb * 8;
+    long long mc = m0 < hi ? m0 : hi - 1;   // lo < hi here
+    unsigned q = 0, rem = 0;
+    if (map.g2) { q = (unsigned)mc / (unsigned)map.g2; rem = (unsigned)mc - q * (unsigned)map.g2; }
+    long long row = map.g2 ? (long long)q * map.T + 1 + rem : mc;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-      long long m = mstep + mb * 8 + r;
-      if (col_ok && m < hi) v[r] = ldg16(src + map(m) * ld + cbase);
-      else v[r] = u32x4{0, 0, 0, 0};
+      v[r] = ldg16(lbase + row * lld);
+      if (m0 + r >= hi) v[r] = u32x4{0, 0, 0, 0};
+      if (m0 + r + 1 < hi) {   // the next row exists: step the mapped index
+        if (map.g2) {
+          ++rem;
+          if (rem == (unsigned)map.g2) { rem = 0; ++q; }
+          row = (long long)q * map.T + 1 + rem;
+        } else {
+          ++row;
+        }
+      }
     }
   };
   auto store = [&](int buf, const u32x4 (&v)[8]) {
@@ -171,7 +191,8 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 }  // namespace
 
 bool gemm_tn_mfma_ok(const GemmTN& g) {
-  return g.N1 % 8 == 0 && g.N2 % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && aligned16(g.A) && aligned16(g.B);
+  return g.N1 % 8 == 0 && g.N2 % 8 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && aligned16(g.A) && aligned16(g.B) &&
+         g.M < (1LL << 31);   // row indices are mapped with 32-bit arithmetic
 }
 
 hipError_t launch_gemm_tn_mfma(const GemmTN& g, hipStream_t s) {
