@@ -25,7 +25,11 @@ namespace {
 constexpr int NXCD = 8;
 constexpr int BX = 256, BY = 192, BK = 64, NTH = 256;
 constexpr int BYP = 256;                            // Y columns in LDS (lanes past the tile park duplicates behind it)
-constexpr int LDW = BX + BYP + 8;                   // LDS row: 256 X columns, 256 Y columns, pad
+// LDS row: 256 X columns, 256 Y columns, pad.  The pad makes the row stride 64 bytes modulo 256 (16 banks): a
+// transpose read's group of 16 lanes touches 4 rows x 32 bytes, and the two groups that are served together sit 32
+// bytes apart, so with this stride their eight 32-byte pieces fall on eight different bank ranges (with a 16-byte
+// stride modulo 256 they overlapped: 58 % of the LDS cycles were bank-conflict cycles).
+constexpr int LDW = BX + BYP + 32;
 constexpr int STAGE = BK * LDW;                     // bf16 elements per LDS stage
 constexpr int WBM = 4, WBN = 3;
 
