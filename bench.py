@@ -79,10 +79,10 @@ def pool_sweep(a):
         loss = torch.zeros(1, device=dev)
         res = {"N": N, "feature_MB": round(N * cfg.dim * 4 / 1e6, 1)}
         for which, kid in (("fwd", names.index("pool_fwd")), ("bwd", names.index("pool_bwd"))):
-            reps = 20
+            reps, warm = a.pool_reps, a.pool_warmup
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            for it in range(reps + 1):
-                if it == 1:
+            for it in range(warm + reps):
+                if it == warm:
                     torch.cuda.synchronize()
                     lib.slide_prof_begin(kid)
                     e0.record()
@@ -188,6 +188,9 @@ def main():
     ap.add_argument("--pool-hidden", type=int, default=128)
     ap.add_argument("--pool-min-log2", type=int, default=13)
     ap.add_argument("--pool-max-log2", type=int, default=22)
+    ap.add_argument("--pool-reps", type=int, default=20, help="timed calls per size and direction")
+    ap.add_argument("--pool-warmup", type=int, default=40,
+                    help="untimed calls before them (the first ~40 ms of a run of these kernels are up to 40 % slower)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)

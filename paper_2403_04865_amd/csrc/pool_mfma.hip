@@ -226,19 +226,28 @@ __global__ void __launch_bounds__(256) pool_gate_part_mfma_k(PoolArgs p, const b
 // registers per lane): each wavefront holds the MFMA fragments of its 32 gate units for the whole kernel, so the only
 // traffic per block of 32 feature rows is the block itself (the kernel above re-reads the weights from L2 for every
 // block, twice the bytes of the features).
-//   * A thread owns 4 rows x 12 columns of every block (fixed columns), in fp32 registers: two register sets, the
-//     block being processed and the one in flight from HBM.  LDS holds only the bf16 image of a block (double
-//     buffered) for the MFMA fragments; the weighted feature sum is taken from the fp32 registers, per block in fp32
-//     (4 terms), across blocks in fp64 (z feeds a cancelling difference in the backward).
+//   * A thread owns 4 rows x 12 columns of every block (fixed columns), in fp32 registers.  LDS holds only the bf16
+//     image of a block (double buffered) for the MFMA fragments; the weighted feature sum is taken from the fp32
+//     registers: per lane in fp32 (4 rows per block, a few thousand terms at most), over row groups and workgroups
+//     in fp64 (z feeds a cancelling difference in the backward).
+//   * The gate of block i - 1 runs under the MFMAs of block i inside each wavefront (the matrix pipe and the vector
+//     ALU are separate, and with one wavefront per SIMD nothing else overlaps them).  The pre-activations of two
+//     blocks are alive (two accumulator sets), and the softmax terms, hence the weighted sum, of a block come one
+//     iteration after its MFMAs: three fp32 row sets rotate (block i - 1 waiting for its weights, block i whose bf16
+//     image is being multiplied, block i + 1 in flight).  The set that the weighted sum frees takes the first loads
+//     of block i + 2 at once.  The roles repeat every 6 iterations (2 images x 3 row sets), which are written out.
 //   * Every wavefront computes the block's softmax terms itself from the four partial logits (no serial section).
 //   * Two barriers per block: partial logits visible; next bf16 image visible.
+constexpr int POOL_REG_NL = 4;   // weight slices read from LDS (the rest stay in registers)
 template <int D, int MH>
 __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf16* __restrict__ VU) {
-  constexpr int RB = 32, LDB = D + 8, KS = D / 16, CJ = D / 128, NR = 4 * CJ;
-  static_assert(MH == 128 && D % 128 == 0, "shape");
+  constexpr int RB = 32, LDB = D + 8, KS = D / 16, CJ = D / 128, NR = 4 * CJ, EARLY = CJ;
+  constexpr int NL = POOL_REG_NL, KR = KS - NL;   // the last NL slices of the weights are read from LDS
+  static_assert(MH == 128 && D % 128 == 0 && KS % 3 == 0 && KS / 3 * 2 == 16 && NR - EARLY <= KS && EARLY % CJ == 0, "shape");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* Hb = reinterpret_cast<bf16*>(smem);                            // [2][RB][LDB]
-  float* gb = reinterpret_cast<float*>(Hb + 2 * RB * LDB);             // scaled bV[MH], scaled bU[MH], w[MH]
+  u32x4* Wl = reinterpret_cast<u32x4*>(Hb + 2 * RB * LDB);             // [4 waves][NL][2][64 lanes] weight fragments
+  float* gb = reinterpret_cast<float*>(Wl + 4 * NL * 2 * 64);          // scaled bV[MH], scaled bU[MH], w[MH]
   float* apart = gb + 3 * MH;                                          // [4][RB]
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int li = lane & 31, h2 = lane >> 5;
@@ -248,45 +257,45 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
   constexpr float C1 = -2.0f * 1.44269504088896f, C2 = -1.44269504088896f;   // exp(-2x) and exp(-x) as exp2
 
   for (int j = tid; j < MH; j += 256) { gb[j] = C1 * p.Vb[j]; gb[MH + j] = C2 * p.Ub[j]; gb[2 * MH + j] = p.w[j]; }
-  // this wavefront's gate units: 32 * wave .. + 31 of V and of U
-  bf16x8 wv[KS], wu[KS];
+  // this wavefront's gate units 32 wave .. + 31 of V and of U: slices 0 .. KR - 1 of their weights stay in the
+  // accumulation half of the register file (the MFMA reads them there), the last NL go to LDS in fragment order
+  // (each lane reads back what it wrote): with all of them in registers the two accumulator sets fill that half
+  // to the last register and the allocator spills
+  bf16x8 wv[KR], wu[KR];
+  u32x4* wl = Wl + (size_t)wave * NL * 2 * 64 + lane;
   {
     const bf16* wr = VU + (size_t)(32 * wave + li) * D + h2 * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       u32x4 a = *reinterpret_cast<const u32x4*>(wr + ks * 16);
       u32x4 b = *reinterpret_cast<const u32x4*>(wr + (size_t)MH * D + ks * 16);
-      // the weights live in the accumulation half of the register file (MFMA reads its operands from either half;
-      // left to itself the allocator keeps them there as spills and copies them back before every MFMA)
-      asm volatile("" : "+a"(a), "+a"(b));
-      wv[ks] = __builtin_bit_cast(bf16x8, a);
-      wu[ks] = __builtin_bit_cast(bf16x8, b);
+      if (ks < KR) {
+        asm volatile("" : "+a"(a), "+a"(b));
+        wv[ks] = __builtin_bit_cast(bf16x8, a);
+        wu[ks] = __builtin_bit_cast(bf16x8, b);
+      } else {
+        wl[((ks - KR) * 2 + 0) * 64] = a;
+        wl[((ks - KR) * 2 + 1) * 64] = b;
+      }
     }
   }
-  float4 ra[NR], rb[NR];
-  auto issue_h = [&](float4 (&r)[NR], long long g) __attribute__((always_inline)) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      // rows past the end (ragged last block, prefetch beyond the last block) re-read the last row: their softmax
-      // term is set to zero below, so whatever finite values they hold never reach a result
-      long long row = g * RB + 4 * rgrp + k;
-      row = row < p.N ? row : p.N - 1;
-      const float* hr = H + row * D + cl * 4;
-#pragma unroll
-      for (int j = 0; j < CJ; ++j) r[k * CJ + j] = *reinterpret_cast<const float4*>(hr + j * 128);
-    }
-  };
-  // one of the NR loads of block g (i = k * CJ + j); spread over the MFMA loop: issued as one burst they hold the
-  // wavefronts in the issue for the ~770 clocks the address unit needs for a block's 48 KB
-  const float* hrp = H;   // row base of the loads in progress
-  auto issue_one = [&](float4 (&r)[NR], long long g, auto ic) __attribute__((always_inline)) {
+  float4 rs[3][NR];
+  f32x16 acc[2][2];
+  // The blocks of a workgroup are loaded strictly one after the other (load 0 .. NR - 1 of a block, then the next
+  // block), so one running row index serves every load site; 32-bit (N < 2^31 - 2^24 is checked on the host).
+  const unsigned lastrow = (unsigned)(p.N - 1), lstep = gridDim.x * RB;
+  unsigned lrow = blockIdx.x * RB + 4 * rgrp;   // first of this thread's 4 rows of the block being loaded
+  const float* hrp = H;                         // row base of the loads in progress
+  // load i = k * CJ + j; rows past the end re-read the last row (their softmax term is set to zero)
+  auto issue_one = [&](float4 (&r)[NR], auto ic) __attribute__((always_inline)) {
     constexpr int i = decltype(ic)::value, k = i / CJ, j = i % CJ;
     if constexpr (j == 0) {
-      long long row = g * RB + 4 * rgrp + k;
-      row = row < p.N ? row : p.N - 1;
-      hrp = H + row * D + cl * 4;
+      unsigned row = lrow + k;
+      row = row < lastrow ? row : lastrow;
+      hrp = H + (size_t)row * D + cl * 4;
     }
     r[i] = *reinterpret_cast<const float4*>(hrp + j * 128);
+    if constexpr (i == NR - 1) lrow += lstep;
   };
   auto stash_h = [&](const float4 (&r)[NR], int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -302,68 +311,111 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
         *reinterpret_cast<uint2*>(Hb + (buf * RB + 4 * rgrp + k) * LDB + (cl + 32 * j) * 4) = w2;
       }
   };
-  double z[4 * CJ];
+  // fp32 partial sums: a lane adds 4 rows per block, a few thousand terms at most (N < 2^31, 256 workgroups x 8 row
+  // groups), before the fp64 reduction over row groups and workgroups
+  float z[4 * CJ];
 #pragma unroll
-  for (int i = 0; i < 4 * CJ; ++i) z[i] = 0.0;
-  // |a_n| <= sum_j |w_j| (tanh * sigmoid lies in (-1, 1)): where that bound is small enough for exp not to underflow
-  // it serves as the softmax shift of every block, which takes the running maximum and the rescaling (two wave-wide
-  // reductions and a chain of dependent exponentials per block) out of the loop
+  for (int i = 0; i < 4 * CJ; ++i) z[i] = 0.f;
   float wabs = 0.f;
   for (int j = lane; j < MH; j += 64) wabs += fabsf(p.w[j]);
   wabs = wave_sum(wabs);
-  const bool fixed = wabs <= 40.f;
+  const bool fixed = wabs <= 40.f;   // a bound of every logit serves as the softmax shift
   float run_m = fixed ? wabs : -INFINITY;
-  double lsum = 0.0;   // per lane: the softmax terms of its row of every block
+  double lsum = 0.0;
+  const int st = gridDim.x;
+  const int nblk = (int)((groups - blockIdx.x + st - 1) / st);   // blocks of this workgroup (>= 1)
 
-  auto block = [&](float4 (&cur)[NR], float4 (&nxt)[NR], int buf, long long gi) __attribute__((always_inline)) {
-    f32x16 av, au;
+  // iteration `it` (role phase ph = it mod 6): MFMAs of block it (on the last image again when it == nblk: unused),
+  // gate, softmax terms and weighted sum of block it - 1, loads of block it + 1 (and the first of block it + 2)
+  auto iter = [&](auto phc, int it) __attribute__((always_inline)) {
+    constexpr int ph = decltype(phc)::value, buf = ph & 1, ls = (ph + 1) % 3, zs = (ph + 2) % 3;
+    f32x16 (&ac)[2] = acc[ph & 1];
+    const f32x16 (&ap)[2] = acc[(ph & 1) ^ 1];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { av[r] = 0.f; au[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) { ac[0][r] = 0.f; ac[1][r] = 0.f; }
     const bf16* hrow = Hb + (buf * RB + li) * LDB + h2 * 8;
-    // one wavefront per SIMD: nothing else covers the LDS latency, so the fragments are read PF slices ahead and the
-    // order is fenced slice by slice
-    constexpr int PF = 4;
+    constexpr int PF = 3;
     u32x4 hf[PF];
 #pragma unroll
     for (int ks = 0; ks < PF; ++ks) hf[ks] = *reinterpret_cast<const u32x4*>(hrow + ks * 16);
+    float part = 0.f;
+    u32x4 lw[2][2];
+    const float* gbl = gb + 32 * wave + h2 * 4;   // scaled biases and w of this lane's gate units
+    float2 bv2 = *reinterpret_cast<const float2*>(gbl), bu2, w2;
+    float ge1[2], ge2[2], gnum[2], part2 = 0.f;
     static_for<0, KS>([&](auto kc) __attribute__((always_inline)) {
       constexpr int ks = decltype(kc)::value;
       bf16x8 f = __builtin_bit_cast(bf16x8, hf[ks % PF]);
       if constexpr (ks + PF < KS) hf[ks % PF] = *reinterpret_cast<const u32x4*>(hrow + (ks + PF) * 16);
-      if constexpr (ks % 2 == 0 && ks / 2 < NR) issue_one(nxt, gi + (long long)gridDim.x, IC<ks / 2>{});
-      av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[ks], f, av, 0, 0, 0);
-      au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu[ks], f, au, 0, 0, 0);
+      // one load per slice: issued as one burst they hold the wavefronts in the issue for the ~770 clocks the address
+      // unit needs for a block's 48 KB
+      if constexpr (ks + EARLY < NR) issue_one(rs[ls], IC<ks + EARLY>{});
+      if constexpr (ks < KR) {
+        ac[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv[ks], f, ac[0], 0, 0, 0);
+        ac[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wu[ks], f, ac[1], 0, 0, 0);
+      } else {
+        ac[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, lw[(ks - KR) % 2][0]), f, ac[0], 0, 0, 0);
+        ac[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, lw[(ks - KR) % 2][1]), f, ac[1], 0, 0, 0);
+      }
+      if constexpr (ks + 2 >= KR && ks + 2 < KS) {   // weight fragments from LDS, two slices ahead
+        lw[(ks + 2 - KR) % 2][0] = wl[((ks + 2 - KR) * 2 + 0) * 64];
+        lw[(ks + 2 - KR) % 2][1] = wl[((ks + 2 - KR) * 2 + 1) * 64];
+      }
+      // gate of the previous block: two elements (accumulator registers 2t, 2t + 1) per three slices, each a third
+      // of its chain per slice, so that the vector ALU always has two independent chains and a slice's share stays
+      // under the 64 clocks of its two MFMAs.  Accumulator register r of a lane = gate unit
+      // (r / 4) * 8 + h2 * 4 + r % 4 of the wavefront's 32, row li.  The finished accumulators are read where they
+      // are, in the accumulation half of the register file (left to itself the allocator moves them to 32 ordinary
+      // registers first, which the three row sets need).
+      // tanh(xv) * sigmoid(xu) = (1 - e1) / ((1 + e1) (1 + e2)), e1 = exp(-2 xv), e2 = exp(-xu)
+      {
+        constexpr int t = ks / 3, stage = ks % 3, r0 = 2 * t, off = (r0 / 4) * 8 + r0 % 4;
+        if constexpr (stage == 0) {
+          bu2 = *reinterpret_cast<const float2*>(gbl + MH + off);
+          w2 = *reinterpret_cast<const float2*>(gbl + 2 * MH + off);
+          float xa, xb;
+          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xa) : "a"(ap[0][r0]));
+          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xb) : "a"(ap[0][r0 + 1]));
+          ge1[0] = __builtin_amdgcn_exp2f(fminf(fmaf(xa, C1, bv2.x), 57.f));
+          ge1[1] = __builtin_amdgcn_exp2f(fminf(fmaf(xb, C1, bv2.y), 57.f));
+        } else if constexpr (stage == 1) {
+          float xa, xb;
+          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xa) : "a"(ap[1][r0]));
+          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xb) : "a"(ap[1][r0 + 1]));
+          ge2[0] = __builtin_amdgcn_exp2f(fmaf(xa, C2, bu2.x));   // inf is fine: 1 / inf = 0, e1 is finite
+          ge2[1] = __builtin_amdgcn_exp2f(fmaf(xb, C2, bu2.y));
+          gnum[0] = fmaf(-w2.x, ge1[0], w2.x);
+          gnum[1] = fmaf(-w2.y, ge1[1], w2.y);
+          ge1[0] += 1.0f;
+          ge1[1] += 1.0f;
+        } else {
+          if constexpr (t + 1 < 8) {
+            constexpr int r1 = r0 + 2, off1 = (r1 / 4) * 8 + r1 % 4;
+            bv2 = *reinterpret_cast<const float2*>(gbl + off1);
+          }
+          float ra = __builtin_amdgcn_rcpf(fmaf(ge1[0], ge2[0], ge1[0]));
+          float rb = __builtin_amdgcn_rcpf(fmaf(ge1[1], ge2[1], ge1[1]));
+          part = fmaf(gnum[0], ra, part);
+          part2 = fmaf(gnum[1], rb, part2);
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
     });
-    // gate: lane = feature row li; accumulator register r = gate unit (r / 4) * 8 + h2 * 4 + r % 4 of the wave's 32
-    float part = 0.f;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      int j = 32 * wave + q * 8 + h2 * 4;
-      float4 bv = *reinterpret_cast<const float4*>(gb + j);
-      float4 bu = *reinterpret_cast<const float4*>(gb + MH + j);
-      float4 wj = *reinterpret_cast<const float4*>(gb + 2 * MH + j);
-      float bvv[4] = {bv.x, bv.y, bv.z, bv.w}, buu[4] = {bu.x, bu.y, bu.z, bu.w}, ww[4] = {wj.x, wj.y, wj.z, wj.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        // tanh(xv) * sigmoid(xu) = (1 - e1) / ((1 + e1) (1 + e2)), e1 = exp(-2 xv), e2 = exp(-xu)
-        float e1 = __builtin_amdgcn_exp2f(fminf(fmaf(av[4 * q + e], C1, bvv[e]), 57.f));
-        float e2 = __builtin_amdgcn_exp2f(fmaf(au[4 * q + e], C2, buu[e]));   // inf is fine: 1 / inf = 0, e1 is finite
-        float s1 = 1.0f + e1;
-        part = fmaf(fmaf(-ww[e], e1, ww[e]), __builtin_amdgcn_rcpf(fmaf(s1, e2, s1)), part);
-      }
-    }
+    // both accumulator sets stay in the accumulation half of the register file (left to itself the allocator moves
+    // the finished one to 32 ordinary registers, which the three row sets need)
+    asm volatile("" : "+a"(ac[0]), "+a"(ac[1]));
+    part += part2;
     part += __shfl_xor(part, 32, 64);
     if (h2 == 0) apart[wave * RB + li] = part;
-    __syncthreads();   // (A) the four partial logits of every row are there
-    float a_out;
-    {
-      const long long n0 = gi * RB;
+    __syncthreads();   // (A) the four partial logits of every row of block it - 1 are there
+    float a_out = 0.f;
+    const long long n0 = ((long long)blockIdx.x + (long long)(it - 1) * st) * RB;   // first row of block it - 1
+    if (it >= 1) {     // uniform
       float a = apart[li] + apart[RB + li] + apart[2 * RB + li] + apart[3 * RB + li];
-      bool ok = n0 + li < p.N;
+      const bool ok = n0 + li < p.N;
       a_out = a;
       float e, sc;
-      if (fixed) {   // uniform: the shift is a bound of every logit, no running maximum, nothing to rescale
+      if (fixed) {   // uniform
         e = ok ? __expf(a - run_m) : 0.f;
         sc = 1.0f;
       } else {
@@ -378,40 +430,41 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
       float ek[4];
 #pragma unroll
       for (int k = 0; k < 4; ++k) ek[k] = __shfl(e, 4 * (rgrp & 7) + k, 64);
-      const double scd = (double)sc;
 #pragma unroll
       for (int j = 0; j < CJ; ++j) {
-        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 s = make_float4(z[4 * j] * sc, z[4 * j + 1] * sc, z[4 * j + 2] * sc, z[4 * j + 3] * sc);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          float4 v = cur[k * CJ + j];
+          float4 v = rs[zs][k * CJ + j];
           s.x = fmaf(ek[k], v.x, s.x); s.y = fmaf(ek[k], v.y, s.y);
           s.z = fmaf(ek[k], v.z, s.z); s.w = fmaf(ek[k], v.w, s.w);
         }
-        z[4 * j + 0] = fma(z[4 * j + 0], scd, (double)s.x);
-        z[4 * j + 1] = fma(z[4 * j + 1], scd, (double)s.y);
-        z[4 * j + 2] = fma(z[4 * j + 2], scd, (double)s.z);
-        z[4 * j + 3] = fma(z[4 * j + 3], scd, (double)s.w);
+        z[4 * j] = s.x; z[4 * j + 1] = s.y; z[4 * j + 2] = s.z; z[4 * j + 3] = s.w;
       }
     }
-    stash_h(nxt, buf ^ 1);                          // the next block (loaded during the previous one)
-    // the logits are kept for the backward; stored last so that no wait on the loads above also waits for this store
-    if (wave == 0 && h2 == 0 && gi * RB + li < p.N) p.a[gi * RB + li] = a_out;
+    // the freed set takes the first loads of block it + 2 (the next iteration continues with load EARLY); they must
+    // not move above the weighted sum, which still reads the registers they land in
+    asm volatile("" ::: "memory");
+    static_for<0, EARLY>([&](auto ic) __attribute__((always_inline)) { issue_one(rs[zs], ic); });
+    stash_h(rs[ls], buf ^ 1);   // block it + 1: its image replaces that of block it - 1
+    if (it >= 1 && wave == 0 && h2 == 0 && n0 + li < p.N) p.a[n0 + li] = a_out;   // kept for the backward
     __syncthreads();   // (B) the next bf16 image is visible; apart is free again
   };
 
-  long long gi = blockIdx.x;
-  const long long st = gridDim.x;
-  issue_h(ra, gi);
-  stash_h(ra, 0);
+  // prologue: block 0 of this workgroup, and the first loads of block 1
+  static_for<0, NR>([&](auto ic) __attribute__((always_inline)) { issue_one(rs[0], ic); });
+  static_for<0, EARLY>([&](auto ic) __attribute__((always_inline)) { issue_one(rs[1], ic); });
+  stash_h(rs[0], 0);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) { acc[1][0][r] = 0.f; acc[1][1][r] = 0.f; }
   __syncthreads();
-  while (true) {
-    if (gi >= groups) break;
-    block(ra, rb, 0, gi);
-    gi += st;
-    if (gi >= groups) break;
-    block(rb, ra, 1, gi);
-    gi += st;
+  for (int it = 0;;) {
+    iter(IC<0>{}, it); if (++it > nblk) break;
+    iter(IC<1>{}, it); if (++it > nblk) break;
+    iter(IC<2>{}, it); if (++it > nblk) break;
+    iter(IC<3>{}, it); if (++it > nblk) break;
+    iter(IC<4>{}, it); if (++it > nblk) break;
+    iter(IC<5>{}, it); if (++it > nblk) break;
   }
   // column sums over the 8 row groups (the bf16 images are dead: every wavefront is past the last barrier (B))
   double* zred = reinterpret_cast<double*>(smem);   // [8][D]
@@ -419,7 +472,7 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
 #pragma unroll
   for (int j = 0; j < CJ; ++j)
 #pragma unroll
-    for (int c = 0; c < 4; ++c) zred[rgrp * D + (cl + 32 * j) * 4 + c] = z[4 * j + c];
+    for (int c = 0; c < 4; ++c) zred[rgrp * D + (cl + 32 * j) * 4 + c] = (double)z[4 * j + c];
   __syncthreads();
   double* out = p.part + (size_t)blockIdx.x * (2 + D);
   // lanes li and li + 32 hold the same rows: sum over one half
@@ -436,7 +489,7 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
 template <int D, int MH>
 hipError_t go_reg(const PoolArgs& p, hipStream_t s) {
   auto kern = pool_gate_part_reg_k<D, MH>;
-  size_t lds = (size_t)2 * 32 * (D + 8) * 2 + (size_t)3 * MH * 4 + 4 * 32 * 4;
+  size_t lds = (size_t)2 * 32 * (D + 8) * 2 + (size_t)4 * POOL_REG_NL * 2 * 64 * 16 + (size_t)3 * MH * 4 + 4 * 32 * 4;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
   long long n = (long long)p.Mh * p.D;
@@ -464,7 +517,7 @@ hipError_t go(const PoolArgs& p, hipStream_t s) {
 
 // shapes built: (D, M_h) in {384, 768} x {128, 256}
 bool pool_mfma_ok(const PoolArgs& p) {
-  return p.vub && p.N >= 512 && (p.D == 384 || p.D == 768) && (p.Mh == 128 || p.Mh == 256) &&
+  return p.vub && p.N >= 512 && p.N < (1LL << 31) - (1 << 24) && (p.D == 384 || p.D == 768) && (p.Mh == 128 || p.Mh == 256) &&
          ((uintptr_t)p.H & 15) == 0 && ((uintptr_t)p.vub & 15) == 0;
 }
 
