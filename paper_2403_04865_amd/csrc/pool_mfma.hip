@@ -297,6 +297,16 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
     r[i] = *reinterpret_cast<const float4*>(hrp + j * 128);
     if constexpr (i == NR - 1) lrow += lstep;
   };
+  auto stash_one = [&](const float4 (&r)[NR], int buf, auto ic) __attribute__((always_inline)) {
+    constexpr int i = decltype(ic)::value, k = i / CJ, j = i % CJ;
+    float4 v = r[i];
+    f32x2 p0 = {v.x, v.y}, p1 = {v.z, v.w};
+    bf16x2 h0 = __builtin_convertvector(p0, bf16x2), h1 = __builtin_convertvector(p1, bf16x2);
+    uint2 w2;
+    w2.x = __builtin_bit_cast(unsigned, h0);
+    w2.y = __builtin_bit_cast(unsigned, h1);
+    *reinterpret_cast<uint2*>(Hb + (buf * RB + 4 * rgrp + k) * LDB + (cl + 32 * j) * 4) = w2;
+  };
   auto stash_h = [&](const float4 (&r)[NR], int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int k = 0; k < 4; ++k)
@@ -338,11 +348,56 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
     u32x4 hf[PF];
 #pragma unroll
     for (int ks = 0; ks < PF; ++ks) hf[ks] = *reinterpret_cast<const u32x4*>(hrow + ks * 16);
-    float part = 0.f;
+    float part = 0.f, part2 = 0.f;
     u32x4 lw[2][2];
     const float* gbl = gb + 32 * wave + h2 * 4;   // scaled biases and w of this lane's gate units
     float2 bv2 = *reinterpret_cast<const float2*>(gbl), bu2, w2;
-    float ge1[2], ge2[2], gnum[2], part2 = 0.f;
+    float ge1[2], ge2[2], gnum[2];
+    // Gate of the previous block, two elements (accumulator registers 2t, 2t + 1) at a time in three stages, one per
+    // slice, a new pair every second slice (slices 2t, 2t + 1, 2t + 2): the vector ALU always has independent chains
+    // and a slice's share stays under the 64 clocks of its two MFMAs.  Accumulator register r of a lane = gate unit
+    // (r / 4) * 8 + h2 * 4 + r % 4 of the wavefront's 32, row li.  The finished accumulators are read where they are,
+    // in the accumulation half of the register file (left to itself the allocator moves them to 32 ordinary registers
+    // first, which the three row sets need).
+    // tanh(xv) * sigmoid(xu) = (1 - e1) / ((1 + e1) (1 + e2)), e1 = exp(-2 xv), e2 = exp(-xu)
+    auto gate0 = [&](auto tc) __attribute__((always_inline)) {
+      constexpr int t = decltype(tc)::value, r0 = 2 * t, off = (r0 / 4) * 8 + r0 % 4;
+      bu2 = *reinterpret_cast<const float2*>(gbl + MH + off);
+      w2 = *reinterpret_cast<const float2*>(gbl + 2 * MH + off);
+      float xa, xb;
+      asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xa) : "a"(ap[0][r0]));
+      asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xb) : "a"(ap[0][r0 + 1]));
+      ge1[0] = __builtin_amdgcn_exp2f(fminf(fmaf(xa, C1, bv2.x), 57.f));
+      ge1[1] = __builtin_amdgcn_exp2f(fminf(fmaf(xb, C1, bv2.y), 57.f));
+    };
+    auto gate1 = [&](auto tc) __attribute__((always_inline)) {
+      constexpr int t = decltype(tc)::value, r0 = 2 * t;
+      float xa, xb;
+      asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xa) : "a"(ap[1][r0]));
+      asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xb) : "a"(ap[1][r0 + 1]));
+      ge2[0] = __builtin_amdgcn_exp2f(fmaf(xa, C2, bu2.x));   // inf is fine: 1 / inf = 0, e1 is finite
+      ge2[1] = __builtin_amdgcn_exp2f(fmaf(xb, C2, bu2.y));
+      gnum[0] = fmaf(-w2.x, ge1[0], w2.x);
+      gnum[1] = fmaf(-w2.y, ge1[1], w2.y);
+      ge1[0] = fmaf(ge1[0] + 1.0f, ge2[0], ge1[0] + 1.0f);   // (1 + e1) (1 + e2)
+      ge1[1] = fmaf(ge1[1] + 1.0f, ge2[1], ge1[1] + 1.0f);
+      if constexpr (t + 1 < 8) {   // the next pair's first constants
+        constexpr int r1 = r0 + 2, off1 = (r1 / 4) * 8 + r1 % 4;
+        bv2 = *reinterpret_cast<const float2*>(gbl + off1);
+      }
+    };
+    float gden[2];
+    auto gate2 = [&]() __attribute__((always_inline)) {
+      part = fmaf(gnum[0], __builtin_amdgcn_rcpf(gden[0]), part);
+      part2 = fmaf(gnum[1], __builtin_amdgcn_rcpf(gden[1]), part2);
+    };
+    // After the last gate stage (slice GA): the partial logits are exchanged, and the softmax terms, the weighted sum
+    // of block it - 1, the first loads of block it + 2 and the bf16 image of block it + 1 run under the remaining
+    // slices' MFMAs.
+    constexpr int GA = 16, SP = (KS - 1 - GA - CJ);   // SP slices share the NR registers of the image
+    static_assert(GA + CJ + 1 < KS && NR % SP == 0, "tail schedule");
+    const long long n0 = ((long long)blockIdx.x + (long long)(it - 1) * st) * RB;   // first row of block it - 1
+    float a_out = 0.f, sc = 1.0f, ek[4] = {0.f, 0.f, 0.f, 0.f};
     static_for<0, KS>([&](auto kc) __attribute__((always_inline)) {
       constexpr int ks = decltype(kc)::value;
       bf16x8 f = __builtin_bit_cast(bf16x8, hf[ks % PF]);
@@ -361,77 +416,36 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
         lw[(ks + 2 - KR) % 2][0] = wl[((ks + 2 - KR) * 2 + 0) * 64];
         lw[(ks + 2 - KR) % 2][1] = wl[((ks + 2 - KR) * 2 + 1) * 64];
       }
-      // gate of the previous block: two elements (accumulator registers 2t, 2t + 1) per three slices, each a third
-      // of its chain per slice, so that the vector ALU always has two independent chains and a slice's share stays
-      // under the 64 clocks of its two MFMAs.  Accumulator register r of a lane = gate unit
-      // (r / 4) * 8 + h2 * 4 + r % 4 of the wavefront's 32, row li.  The finished accumulators are read where they
-      // are, in the accumulation half of the register file (left to itself the allocator moves them to 32 ordinary
-      // registers first, which the three row sets need).
-      // tanh(xv) * sigmoid(xu) = (1 - e1) / ((1 + e1) (1 + e2)), e1 = exp(-2 xv), e2 = exp(-xu)
-      {
-        constexpr int t = ks / 3, stage = ks % 3, r0 = 2 * t, off = (r0 / 4) * 8 + r0 % 4;
-        if constexpr (stage == 0) {
-          bu2 = *reinterpret_cast<const float2*>(gbl + MH + off);
-          w2 = *reinterpret_cast<const float2*>(gbl + 2 * MH + off);
-          float xa, xb;
-          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xa) : "a"(ap[0][r0]));
-          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xb) : "a"(ap[0][r0 + 1]));
-          ge1[0] = __builtin_amdgcn_exp2f(fminf(fmaf(xa, C1, bv2.x), 57.f));
-          ge1[1] = __builtin_amdgcn_exp2f(fminf(fmaf(xb, C1, bv2.y), 57.f));
-        } else if constexpr (stage == 1) {
-          float xa, xb;
-          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xa) : "a"(ap[1][r0]));
-          asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(xb) : "a"(ap[1][r0 + 1]));
-          ge2[0] = __builtin_amdgcn_exp2f(fmaf(xa, C2, bu2.x));   // inf is fine: 1 / inf = 0, e1 is finite
-          ge2[1] = __builtin_amdgcn_exp2f(fmaf(xb, C2, bu2.y));
-          gnum[0] = fmaf(-w2.x, ge1[0], w2.x);
-          gnum[1] = fmaf(-w2.y, ge1[1], w2.y);
-          ge1[0] += 1.0f;
-          ge1[1] += 1.0f;
-        } else {
-          if constexpr (t + 1 < 8) {
-            constexpr int r1 = r0 + 2, off1 = (r1 / 4) * 8 + r1 % 4;
-            bv2 = *reinterpret_cast<const float2*>(gbl + off1);
+      if constexpr (ks % 2 == 0 && ks >= 2 && ks <= GA) gate2();                      // pair (ks - 2) / 2
+      if constexpr (ks % 2 == 0 && ks / 2 < 8) gate0(IC<ks / 2>{});
+      if constexpr (ks % 2 == 1 && ks / 2 < 8) { gate1(IC<ks / 2>{}); gden[0] = ge1[0]; gden[1] = ge1[1]; }
+      if constexpr (ks == GA) {
+        part += part2;
+        part += __shfl_xor(part, 32, 64);
+        if (h2 == 0) apart[wave * RB + li] = part;
+        __syncthreads();   // (A) the four partial logits of every row of block it - 1 are there
+        if (it >= 1) {     // uniform
+          float a = apart[li] + apart[RB + li] + apart[2 * RB + li] + apart[3 * RB + li];
+          const bool ok = n0 + li < p.N;
+          a_out = a;
+          float e;
+          if (fixed) {   // uniform
+            e = ok ? __expf(a - run_m) : 0.f;
+          } else {
+            a = ok ? a : -INFINITY;
+            float m = fmaxf(run_m, wave_max(a));   // finite: the block has at least one row
+            e = __expf(a - m);                     // lanes li and li + 32: row li
+            sc = __expf(run_m - m);                // exp(-inf) = 0 on the first block
+            run_m = m;
+            lsum *= (double)sc;
           }
-          float ra = __builtin_amdgcn_rcpf(fmaf(ge1[0], ge2[0], ge1[0]));
-          float rb = __builtin_amdgcn_rcpf(fmaf(ge1[1], ge2[1], ge1[1]));
-          part = fmaf(gnum[0], ra, part);
-          part2 = fmaf(gnum[1], rb, part2);
+          lsum += (double)e;   // summed over the rows once, at the end
+#pragma unroll
+          for (int k = 0; k < 4; ++k) ek[k] = __shfl(e, 4 * (rgrp & 7) + k, 64);
         }
       }
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    // both accumulator sets stay in the accumulation half of the register file (left to itself the allocator moves
-    // the finished one to 32 ordinary registers, which the three row sets need)
-    asm volatile("" : "+a"(ac[0]), "+a"(ac[1]));
-    part += part2;
-    part += __shfl_xor(part, 32, 64);
-    if (h2 == 0) apart[wave * RB + li] = part;
-    __syncthreads();   // (A) the four partial logits of every row of block it - 1 are there
-    float a_out = 0.f;
-    const long long n0 = ((long long)blockIdx.x + (long long)(it - 1) * st) * RB;   // first row of block it - 1
-    if (it >= 1) {     // uniform
-      float a = apart[li] + apart[RB + li] + apart[2 * RB + li] + apart[3 * RB + li];
-      const bool ok = n0 + li < p.N;
-      a_out = a;
-      float e, sc;
-      if (fixed) {   // uniform
-        e = ok ? __expf(a - run_m) : 0.f;
-        sc = 1.0f;
-      } else {
-        a = ok ? a : -INFINITY;
-        float m = fmaxf(run_m, wave_max(a));   // finite: the block has at least one row
-        e = __expf(a - m);                     // lanes li and li + 32: row li
-        sc = __expf(run_m - m);                // exp(-inf) = 0 on the first block
-        run_m = m;
-        lsum *= (double)sc;
-      }
-      lsum += (double)e;   // summed over the rows once, at the end
-      float ek[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) ek[k] = __shfl(e, 4 * (rgrp & 7) + k, 64);
-#pragma unroll
-      for (int j = 0; j < CJ; ++j) {
+      if constexpr (ks > GA && ks <= GA + CJ) {   // weighted sum, one group of 4 columns per slice (all zero when it = 0)
+        constexpr int j = ks - GA - 1;
         float4 s = make_float4(z[4 * j] * sc, z[4 * j + 1] * sc, z[4 * j + 2] * sc, z[4 * j + 3] * sc);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -441,12 +455,21 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
         }
         z[4 * j] = s.x; z[4 * j + 1] = s.y; z[4 * j + 2] = s.z; z[4 * j + 3] = s.w;
       }
-    }
-    // the freed set takes the first loads of block it + 2 (the next iteration continues with load EARLY); they must
-    // not move above the weighted sum, which still reads the registers they land in
-    asm volatile("" ::: "memory");
-    static_for<0, EARLY>([&](auto ic) __attribute__((always_inline)) { issue_one(rs[zs], ic); });
-    stash_h(rs[ls], buf ^ 1);   // block it + 1: its image replaces that of block it - 1
+      if constexpr (ks == GA + CJ) {
+        // the freed set takes the first loads of block it + 2 (the next iteration continues with load EARLY); they
+        // must not move above the weighted sum, which still reads the registers they land in
+        asm volatile("" ::: "memory");
+        static_for<0, EARLY>([&](auto ic) __attribute__((always_inline)) { issue_one(rs[zs], ic); });
+      }
+      if constexpr (ks > GA + CJ) {   // bf16 image of block it + 1 (replaces that of block it - 1), NR / SP registers per slice
+        constexpr int q = ks - GA - CJ - 1;
+        static_for<q * (NR / SP), (q + 1) * (NR / SP)>([&](auto ic) __attribute__((always_inline)) { stash_one(rs[ls], buf ^ 1, ic); });
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // both accumulator sets stay in the accumulation half of the register file (left to itself the allocator moves
+    // the finished one to 32 ordinary registers, which the three row sets need)
+    asm volatile("" : "+a"(ac[0]), "+a"(ac[1]));
     if (it >= 1 && wave == 0 && h2 == 0 && n0 + li < p.N) p.a[n0 + li] = a_out;   // kept for the backward
     __syncthreads();   // (B) the next bf16 image is visible; apart is free again
   };
@@ -455,6 +478,9 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
   static_for<0, NR>([&](auto ic) __attribute__((always_inline)) { issue_one(rs[0], ic); });
   static_for<0, EARLY>([&](auto ic) __attribute__((always_inline)) { issue_one(rs[1], ic); });
   stash_h(rs[0], 0);
+  // iteration 0 has no previous block: its gate reads zeros and its weighted sum adds zero times zero
+#pragma unroll
+  for (int i = 0; i < NR; ++i) rs[2][i] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
   for (int r = 0; r < 16; ++r) { acc[1][0][r] = 0.f; acc[1][1][r] = 0.f; }
   __syncthreads();
