@@ -86,8 +86,8 @@ def test_pool_bf16_ragged_rows():          # row count that is no multiple of th
     _pool_case("medium", 1000 + 37, 1, label=1)
 
 
-def test_pool_bf16_many_rows():            # enough rows for the persistent kernels to walk several blocks per workgroup
-    _pool_case("medium", 65536 + 4096 + 19, 1, label=1)   # and for the large-M weight-gradient GEMM; ragged tail
+def test_pool_bf16_many_rows():            # 16-17 blocks per workgroup of the persistent forward (its register roles
+    _pool_case("medium", 131072 + 4096 + 19, 1, label=1)   # repeat every 6), unevenly; large-M weight-gradient GEMM; ragged tail
 
 
 def test_pool_bf16_large_logit_weights():  # sum |w| > 40: the logit bound is no usable softmax shift, running maximum instead
