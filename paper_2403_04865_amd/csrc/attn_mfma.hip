@@ -165,7 +165,7 @@ template <int DH, int NB>
 __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const bf16* __restrict__ qkv, bf16* __restrict__ O,
                                                        float* __restrict__ lse, int T, int H, long long ntiles, int cls_only) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
+  constexpr int TP = NB * 32, LDR = DH + 8, KS = DH / 16, DB = DH / 32;
   bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
   bf16* Vs = Ks + TP * LDR;                  // [TP][LDR]
   // workgroup ids are dealt round-robin to the 8 XCDs: the heads of one tile go to one XCD, next to each other
@@ -289,7 +289,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
                                                          bf16* __restrict__ dqkv, float* __restrict__ delta_ws, int T, int H,
                                                          long long ntiles, int cls_only) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
+  constexpr int TP = NB * 32, LDR = DH + 8, KS = DH / 16, DB = DH / 32;
   bf16* Ks = reinterpret_cast<bf16*>(smem);  // [TP][LDR]
   bf16* Vs = Ks + TP * LDR;                  // [TP][LDR]
   // workgroup ids are dealt round-robin to the 8 XCDs: the heads of one tile go to one XCD, next to each other
@@ -345,7 +345,6 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
   const bf16* const ktr0 = Ks + tr_lane_off(LDR, lane);
   for (int qb = wave; qb < NB; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
-    int qc = q < T ? q : T - 1;
     if (cls_only && qb > 0) {   // uniform: the output gradient is zero for these queries, and so is dQ
       if (q < T) {
         bf16* out = dqkv + (tile * T + q) * gs + h * DH;
@@ -424,7 +423,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
                                                          const float* __restrict__ lse, const bf16* __restrict__ dO,
                                                          bf16* __restrict__ dqkv, int T, int H, long long ntiles, int cls_only) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int TP = NB * 32, LDR = DH + 8, LDT = TP + 8, KS = DH / 16, DB = DH / 32;
+  constexpr int TP = NB * 32, LDR = DH + 8, KS = DH / 16, DB = DH / 32;
   bf16* Qs = reinterpret_cast<bf16*>(smem);   // [TP][LDR]
   bf16* Gs = Qs + TP * LDR;                   // [TP][LDR]  dO
   float* ls = reinterpret_cast<float*>(Gs + TP * LDR);  // [TP] lse * log2(e), +inf on padding rows

@@ -48,6 +48,13 @@ __global__ void __launch_bounds__(256) pool_cast_vut_k(const float* __restrict__
   out[i] = (bf16)(u < Mh ? V[(size_t)u * D + d] : U[(size_t)(u - Mh) * D + d]);
 }
 
+// out (bf16, [2 Mh][D]) = [V; U]
+__global__ void __launch_bounds__(256) pool_cast_vu2_k(const float* __restrict__ V, const float* __restrict__ U,
+                                                       bf16* __restrict__ out, long long n) {
+  long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) { out[i] = (bf16)V[i]; out[n + i] = (bf16)U[i]; }
+}
+
 // Pass 1.  Same skeleton as the forward kernel with register-resident weights: persistent workgroups of 4
 // wavefronts over blocks of 32 rows, a wavefront owns 32 gate units, a thread owns 4 rows x 12 columns of every block
 // in fp32 registers (two sets), LDS holds the bf16 image of the block for the MFMA fragments.
@@ -259,11 +266,12 @@ __global__ void __launch_bounds__(256) pool_bwd_gate_k(PoolArgs p, const bf16* _
   }
 }
 
-// Pass 2.  G[n][d] = alpha_n dz[d] + sum_u Dp[n][u] VUT[d][u].  A wavefront holds the transposed weights of its
+// Pass 2.  G[n][d] = alpha_n dz[d] + sum_u Dp[n][u] VUT[d][u]; with ADD the first term is what G already holds (the
+// second half of the gate units when M_h = 256 is taken as two halves).  A wavefront holds the transposed weights of its
 // D / 4 columns (3 tiles of 32 x 256: 192 registers); the block's gradient rows go through LDS (double buffered, the
 // next block in flight in registers).  Rows are the M index: accumulator register r of a lane is row
 // (r / 4) * 8 + h2 * 4 + r % 4, the lane is the column, so a store instruction writes two 128-byte lines.
-template <int D, int MH>
+template <int D, int MH, bool ADD>
 __global__ void __launch_bounds__(256) pool_bwd_g_k(PoolArgs p, const bf16* __restrict__ VUT,
                                                     const bf16* __restrict__ Dp) {
   constexpr int RB = 32, KU = 2 * MH, KS = KU / 16, LDP = KU + 8, NT = D / 128, CH = RB * KU / 8 / 256, LDG = 2 * MH;
@@ -356,15 +364,18 @@ __global__ void __launch_bounds__(256) pool_bwd_g_k(PoolArgs p, const bf16* __re
 #pragma unroll
       for (int t = 0; t < NT; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r)
-          gout[(size_t)((r / 4) * 8 + h2 * 4 + r % 4) * D + 32 * t] = fmaf(al[r], dzr[t], acc[t][r]);
+        for (int r = 0; r < 16; ++r) {
+          float* o = gout + (size_t)((r / 4) * 8 + h2 * 4 + r % 4) * D + 32 * t;
+          *o = ADD ? *o + acc[t][r] : fmaf(al[r], dzr[t], acc[t][r]);
+        }
     } else {
 #pragma unroll
       for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           int row = (r / 4) * 8 + h2 * 4 + r % 4;
-          if (n0 + row < p.N) gout[(size_t)row * D + 32 * t] = fmaf(al[r], dzr[t], acc[t][r]);
+          float* o = gout + (size_t)row * D + 32 * t;
+          if (n0 + row < p.N) *o = ADD ? *o + acc[t][r] : fmaf(al[r], dzr[t], acc[t][r]);
         }
     }
     stash(buf ^ 1, gi + st);     // the next block (loaded during this one)
@@ -375,7 +386,7 @@ __global__ void __launch_bounds__(256) pool_bwd_g_k(PoolArgs p, const bf16* __re
 }  // namespace
 
 bool pool_bwd_mfma_ok(const PoolArgs& p) {
-  return p.use_mfma && pool_mfma_ok(p) && p.D == 384 && p.Mh == 128;
+  return p.use_mfma && pool_mfma_ok(p) && p.D == 384 && (p.Mh == 128 || p.Mh == 256);
 }
 
 int pool_bwd_mfma_blocks(const PoolArgs& p) {
@@ -391,32 +402,50 @@ int pool_bwd_mfma_blocks(const PoolArgs& p) {
   return (int)(b > 1024 ? 1024 : b);
 }
 
-// Dp: [N][2 Mh] bf16, Hb16: [N][D] bf16, csp: [pool_bwd_mfma_blocks][Mh] fp32 partial sums of dw.  p.vub holds [V;U] as bf16 (written
-// by the forward of the same call) followed by room for the transposed copy.
-hipError_t launch_pool_bwd_mfma(const PoolArgs& p, void* Dp, void* Hb16, float* csp, hipStream_t s) {
+// Dp: [N][2 Mh] bf16, Hb16: [N][D] bf16, csp: [pool_bwd_mfma_blocks][Mh] fp32 partial sums of dw.  p.vub has room for two
+// bf16 copies of [V;U] (plain and transposed).
+// M_h = 256 does not fit the register file (2 M_h D bf16 = 384 KB) and is taken as two halves of 128 gate units, which
+// are independent given the softmax gradient of the row: each half is the M_h = 128 problem on its rows of V, U, b_V, b_U
+// and w; the second half adds its part of G to the first's.  Then Dp is [2][N][256] (half h: dpV | dpU of its units),
+// csp [2][blocks][128], and the feature copy is written twice.
+hipError_t launch_pool_bwd_mfma(const PoolArgs& p0, void* Dp, void* Hb16, float* csp, hipStream_t s) {
   constexpr int D = 384, MH = 128;
-  if (!pool_bwd_mfma_ok(p)) return hipErrorInvalidValue;
-  const int blocks = pool_bwd_mfma_blocks(p);
-  bf16* vu = (bf16*)p.vub;
-  bf16* vut = vu + (size_t)2 * MH * D;
+  if (!pool_bwd_mfma_ok(p0)) return hipErrorInvalidValue;
+  const int blocks = pool_bwd_mfma_blocks(p0);
+  const int halves = p0.Mh / MH;
   hipError_t e;
-  hipLaunchKernelGGL(pool_cast_vut_k, dim3((unsigned)((2 * MH * D + 255) / 256)), dim3(256), 0, s, p.VW, p.UW, vut, MH, D);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  {
-    auto kern = pool_bwd_gate_k<D, MH>;
-    size_t lds = (size_t)2 * 32 * (D + 8) * 2 + (size_t)32 * (2 * MH + 8) * 2 + (size_t)3 * MH * 4 + 32 * 4 + 2 * D * 4;
-    if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
-      return e;
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, s, p, (const bf16*)vu, (bf16*)Dp, (bf16*)Hb16, csp);
+  for (int h = 0; h < halves; ++h) {
+    PoolArgs p = p0;
+    p.Mh = MH;
+    p.VW = p0.VW + (size_t)h * MH * D; p.UW = p0.UW + (size_t)h * MH * D;
+    p.Vb = p0.Vb + h * MH; p.Ub = p0.Ub + h * MH; p.w = p0.w + h * MH;
+    bf16* vu = (bf16*)p0.vub + (size_t)h * 2 * (2 * MH * D);
+    bf16* vut = vu + (size_t)2 * MH * D;
+    bf16* dp = (bf16*)Dp + (size_t)h * p0.N * 2 * MH;
+    const long long n = (long long)MH * D;
+    hipLaunchKernelGGL(pool_cast_vu2_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.VW, p.UW, vu, n);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-  }
-  {
-    auto kern = pool_bwd_g_k<D, MH>;
-    size_t lds = (size_t)2 * 32 * (2 * MH + 8) * 2 + (size_t)2 * 32 * 4;
-    if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
-      return e;
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, s, p, (const bf16*)vut, (const bf16*)Dp);
+    hipLaunchKernelGGL(pool_cast_vut_k, dim3((unsigned)((2 * MH * D + 255) / 256)), dim3(256), 0, s, p.VW, p.UW, vut, MH, D);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    {
+      auto kern = pool_bwd_gate_k<D, MH>;
+      size_t lds = (size_t)2 * 32 * (D + 8) * 2 + (size_t)32 * (2 * MH + 8) * 2 + (size_t)3 * MH * 4 + 32 * 4 + 2 * D * 4;
+      if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+        return e;
+      hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, s, p, (const bf16*)vu, dp, (bf16*)Hb16,
+                         csp + (size_t)h * blocks * MH);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    {
+      size_t lds = (size_t)2 * 32 * (2 * MH + 8) * 2 + (size_t)2 * 32 * 4;
+      auto k0 = pool_bwd_g_k<D, MH, false>;
+      auto k1 = pool_bwd_g_k<D, MH, true>;
+      auto kern = h == 0 ? k0 : k1;
+      if ((e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) != hipSuccess)
+        return e;
+      hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), lds, s, p, (const bf16*)vut, (const bf16*)dp);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
   }
   return hipSuccess;
 }

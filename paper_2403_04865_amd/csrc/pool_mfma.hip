@@ -327,7 +327,7 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
 #pragma unroll
   for (int i = 0; i < 4 * CJ; ++i) z[i] = 0.f;
   float wabs = 0.f;
-  for (int j = lane; j < MH; j += 64) wabs += fabsf(p.w[j]);
+  for (int j = lane; j < MH; j += 64) wabs += fabsf(p.w[j]) + (p.w_other ? fabsf(p.w_other[j]) : 0.f);
   wabs = wave_sum(wabs);
   const bool fixed = wabs <= 40.f;   // a bound of every logit serves as the softmax shift
   float run_m = fixed ? wabs : -INFINITY;
@@ -398,6 +398,8 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
     static_assert(GA + CJ + 1 < KS && NR % SP == 0, "tail schedule");
     const long long n0 = ((long long)blockIdx.x + (long long)(it - 1) * st) * RB;   // first row of block it - 1
     float a_out = 0.f, sc = 1.0f, ek[4] = {0.f, 0.f, 0.f, 0.f};
+    float a_prev = 0.f;   // the other half's partial logit of this lane's row (two-pass use)
+    if (p.a_in != nullptr && it >= 1) a_prev = p.a_in[n0 + li < p.N ? n0 + li : p.N - 1];   // uniform
     static_for<0, KS>([&](auto kc) __attribute__((always_inline)) {
       constexpr int ks = decltype(kc)::value;
       bf16x8 f = __builtin_bit_cast(bf16x8, hf[ks % PF]);
@@ -425,11 +427,13 @@ __global__ void __launch_bounds__(256) pool_gate_part_reg_k(PoolArgs p, const bf
         if (h2 == 0) apart[wave * RB + li] = part;
         __syncthreads();   // (A) the four partial logits of every row of block it - 1 are there
         if (it >= 1) {     // uniform
-          float a = apart[li] + apart[RB + li] + apart[2 * RB + li] + apart[3 * RB + li];
+          float a = apart[li] + apart[RB + li] + apart[2 * RB + li] + apart[3 * RB + li] + a_prev;
           const bool ok = n0 + li < p.N;
           a_out = a;
           float e;
-          if (fixed) {   // uniform
+          if (p.partial) {   // uniform: only the partial logits are wanted
+            e = 0.f;
+          } else if (fixed) {   // uniform
             e = ok ? __expf(a - run_m) : 0.f;
           } else {
             a = ok ? a : -INFINITY;
@@ -518,11 +522,28 @@ hipError_t go_reg(const PoolArgs& p, hipStream_t s) {
   size_t lds = (size_t)2 * 32 * (D + 8) * 2 + (size_t)4 * POOL_REG_NL * 2 * 64 * 16 + (size_t)3 * MH * 4 + 4 * 32 * 4;
   hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   if (e != hipSuccess) return e;
-  long long n = (long long)p.Mh * p.D;
+  long long n = (long long)MH * p.D;
   hipLaunchKernelGGL(pool_cast_vu_k, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p.VW, p.UW, (bf16*)p.vub, n);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(256), lds, s, p, (const bf16*)p.vub);
   return hipGetLastError();
+}
+
+// M_h = 256 as two passes of the M_h = 128 kernel over the rows (the features are read twice, against the weights
+// streaming from L2 for every block of rows in the one-pass kernel): pass 1 leaves the partial logits of gate units
+// 0..127 in a_tmp, pass 2 adds those of units 128..255 and does the softmax partials.
+hipError_t go_reg_halves(const PoolArgs& p0, hipStream_t s) {
+  constexpr int MH = 128;
+  if (!p0.a_tmp) return hipErrorInvalidValue;
+  PoolArgs p = p0;
+  p.Mh = MH; p.partial = 1; p.a_in = nullptr; p.w_other = nullptr; p.a = p0.a_tmp;
+  hipError_t e = go_reg<384, MH>(p, s);
+  if (e != hipSuccess) return e;
+  p = p0;
+  p.Mh = MH; p.partial = 0; p.a_in = p0.a_tmp; p.w_other = p0.w;
+  p.VW = p0.VW + (size_t)MH * p0.D; p.UW = p0.UW + (size_t)MH * p0.D;
+  p.Vb = p0.Vb + MH; p.Ub = p0.Ub + MH; p.w = p0.w + MH;
+  return go_reg<384, MH>(p, s);
 }
 
 template <int RB, int MH, int BK, int HCH>
@@ -547,10 +568,15 @@ bool pool_mfma_ok(const PoolArgs& p) {
          ((uintptr_t)p.H & 15) == 0 && ((uintptr_t)p.vub & 15) == 0;
 }
 
-int pool_mfma_rows(const PoolArgs& p) { return (p.D == 384 && p.Mh == 256) ? 64 : 32; }
+// above this many rows M_h = 256 goes through the register-resident kernel in two passes (below it the launches cost
+// more than the weights streaming from L2)
+static bool pool_two_pass(const PoolArgs& p) { return p.D == 384 && p.Mh == 256 && p.N >= 32768 && p.a_tmp != nullptr; }
+
+int pool_mfma_rows(const PoolArgs& p) { return (p.D == 384 && p.Mh == 256 && !pool_two_pass(p)) ? 64 : 32; }
 
 hipError_t launch_pool_gate_part_mfma(const PoolArgs& p, hipStream_t s) {
   if (p.D == 384 && p.Mh == 128) return go_reg<384, 128>(p, s);
+  if (pool_two_pass(p)) return go_reg_halves(p, s);
   if (p.D == 384 && p.Mh == 256) return go<64, 256, 16, 24>(p, s);
   if (p.D == 768 && p.Mh == 128) return go<32, 128, 32, 24>(p, s);
   if (p.D == 768 && p.Mh == 256) return go<32, 256, 16, 24>(p, s);

@@ -193,6 +193,10 @@ struct PoolArgs {
   int accumulate;
   void* vub;     // 2 x [2 Mh][D] bf16: copy of [V;U] and room for its transpose (scratch of the matrix-core kernels), may be null
   int use_mfma;  // bf16 path: gate projections on the matrix cores where the shape is built
+  // M_h = 256 taken as two halves of 128 gate units by the register-resident forward kernel: the first half only writes
+  // its partial logits (partial = 1), the second adds them (a_in) and does everything else; w_other = the other half's w
+  // (the softmax shift is a bound over all gate units).  a_tmp: [N] floats of scratch for the partial logits.
+  const float* a_in; int partial; const float* w_other; float* a_tmp;
 };
 int pool_blocks(long long N);
 bool pool_mfma_ok(const PoolArgs& p);

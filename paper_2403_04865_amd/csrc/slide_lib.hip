@@ -595,6 +595,7 @@ PoolArgs pool_args(slide_ctx* c, const Layout& y, const void* feats, long long N
   p.blocks = pool_blocks(N);
   p.grads = c->grads; p.ocW = c->o_cW; p.ocb = c->o_cb;
   p.vub = ar + y.p_vub; p.use_mfma = c->use_mfma && c->dt == DT_BF16;
+  p.a_tmp = (float*)(ar + y.p_Dp);   // the backward's work space is idle during the forward
   return p;
 }
 
@@ -622,15 +623,22 @@ int pool_bwd(slide_ctx* c, const Layout& y, const void* feats, long long N, int 
   // the matrix-core path keeps [dpV dpU] and a feature copy as bf16 in the room of the fp32 [N, 3 Mh] array; db_V and
   // db_U come out of the weight-gradient GEMM as column sums of its first operand
   if (pool_bwd_mfma_ok(p) && (size_t)(2 * Mh + D) * 2 <= (size_t)3 * Mh * 4 && !getenv("SLIDE_POOL_BWD_ALU")) {
+    // M_h = 256 runs as two halves of 128 gate units: Dp is then [2][N][256], the dw partials [2][blocks][128]
+    const int MHK = 128, halves = Mh / MHK;
     char* Hb16 = Dp + (size_t)N * 2 * Mh * 2;
-    float* csw = cs + (size_t)64 * 2 * Mh;   // behind the column-sum partials of the GEMM (at most 64 slabs)
+    float* csw = cs + (size_t)64 * 2 * MHK;   // behind the column-sum partials of the GEMM (at most 64 slabs)
     int blocks = pool_bwd_mfma_blocks(p);
     launch(r, K_POOL_BWD, 12.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_mfma(p, Dp, Hb16, csw, s); });
     launch(r, K_ELEMWISE, 0, 0, [&] { return launch_pool_head_grads(p, s); });
-    launch(r, K_ELEMWISE, 0, 0,
-           [&] { return launch_reduce_partials(csw, blocks, Mh, Mh, c->grads + c->o_w, accumulate, s); });
-    gemm_tn(r, Dp, 2 * Mh, id, Hb16, D, id, N, 2 * Mh, D, tn, c->grads + c->o_VW, accumulate, DT_BF16,
-            c->grads + c->o_Vb, cs, c->grads + c->o_UW, c->grads + c->o_Ub);
+    for (int h = 0; h < halves; ++h) {
+      launch(r, K_ELEMWISE, 0, 0, [&] {
+        return launch_reduce_partials(csw + (size_t)h * blocks * MHK, blocks, MHK, MHK, c->grads + c->o_w + h * MHK,
+                                      accumulate, s);
+      });
+      const size_t ow = (size_t)h * MHK * D;
+      gemm_tn(r, Dp + (size_t)h * N * 2 * MHK * 2, 2 * MHK, id, Hb16, D, id, N, 2 * MHK, D, tn, c->grads + c->o_VW + ow,
+              accumulate, DT_BF16, c->grads + c->o_Vb + h * MHK, cs, c->grads + c->o_UW + ow, c->grads + c->o_Ub + h * MHK);
+    }
     return finish(r);
   }
   launch(r, K_POOL_BWD, 8.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_rows(p, (float*)Dp, s); });

@@ -90,6 +90,10 @@ def test_pool_bf16_many_rows():            # 16-17 blocks per workgroup of the p
     _pool_case("medium", 131072 + 4096 + 19, 1, label=1)   # repeat every 6), unevenly; large-M weight-gradient GEMM; ragged tail
 
 
+def test_pool_bf16_mh256_many_rows():       # M_h = 256 above 32768 rows: forward in two passes of 128 gate units each
+    _pool_case("large", 32768 + 4096 + 7, 1)   # (the backward takes M_h = 256 as two halves at every size)
+
+
 def test_pool_bf16_large_logit_weights():  # sum |w| > 40: the logit bound is no usable softmax shift, running maximum instead
     _pool_case("medium", 4096 + 77, 1, w_scale=30.0)
 
