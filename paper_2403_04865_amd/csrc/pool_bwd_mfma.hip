@@ -1,5 +1,5 @@
 // Gated-attention MIL pooling, backward over the feature rows on the matrix cores (gfx950, bf16 path, the shape
-// whose gate weights fit the register file: D = 384, M_h = 128).
+// whose gate weights fit the register file: D = 384, M_h = 128; M_h = 256 runs as two such halves of the gate units).
 //
 // Per feature row h_n (attention logit a_n saved by the forward; m, Z, z, dz from the combine kernel):
 //   alpha_n = exp(a_n - m) / Z,   da_n = alpha_n * dz . (h_n - z)

@@ -209,9 +209,10 @@ hipError_t launch_pool_head_grads(const PoolArgs& p, hipStream_t s);
 // theta, m, v updated in place (fp32, n elements); step counts from 1
 hipError_t launch_adamw(float* theta, const float* g, float* m, float* v, size_t n, long long step, float lr, float b1,
                         float b2, float eps, float wd, hipStream_t s);
-// matrix-core backward over the rows (bf16 path, D = 384, M_h = 128): Dp [N][2 Mh] bf16 (dpV | dpU), Hb16 [N][D] bf16
-// feature copy, csp [pool_bwd_mfma_blocks][Mh] partial sums of da t s (dw); writes p.G.  p.vub must have room for two
-// bf16 copies of [V;U] (the second is the transposed one).
+// matrix-core backward over the rows (bf16 path, D = 384, M_h = 128 or 256 = two halves of 128 gate units): per half
+// Dp [N][256] bf16 (dpV | dpU of its units) and csp [pool_bwd_mfma_blocks][128] partial sums of da t s (dw), half after
+// half; Hb16 [N][D] bf16 feature copy; writes p.G.  p.vub must have room for two bf16 copies of [V;U] (plain and
+// transposed).
 bool pool_bwd_mfma_ok(const PoolArgs& p);
 int pool_bwd_mfma_blocks(const PoolArgs& p);
 hipError_t launch_pool_bwd_mfma(const PoolArgs& p, void* Dp, void* Hb16, float* csp, hipStream_t s);
