@@ -46,7 +46,8 @@ struct Layout {
   size_t e_patches, e_x, e_qkv, e_O, e_lse, e_xmid, e_m;              // first instance
   size_t e_dl;                                                        // [n][H][T] fp32 work space of the attention backward
   size_t s_x, s_qkv, s_O, s_lse, s_xmid, s_m, s_a;                    // per-layer strides (0 when not saved)
-  size_t e_u, e_a, e_dm, e_dxA, e_dxB, e_dxAt, e_dxBt, e_du, e_dqkv;
+  size_t e_u1, e_u2, s_u1, s_u2;                                          // LayerNorm outputs of a block (inputs of its QKV / fc1 GEMMs)
+  size_t e_a, e_dm, e_dxA, e_dxB, e_dxAt, e_dxBt, e_du, e_dqkv;
 };
 
 }  // namespace
@@ -152,7 +153,13 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   }
   y.s_m = save ? align256(M * c->F * e) : 0;
   y.e_m = take(0); cur += (size_t)inst * align256(M * c->F * e);
-  y.e_u = take(M * D * e);
+  // the two LayerNorm outputs of a block are kept like its other activations: the weight gradients of the GEMMs
+  // behind them need them again, and a LayerNorm backward that re-creates them writes a fifth more than one that
+  // does not (+2 D e bytes per token and block)
+  y.s_u1 = save ? align256(M * D * e) : 0;
+  y.e_u1 = take(0); cur += (size_t)inst * align256(M * D * e);
+  y.s_u2 = save ? align256(M * D * e) : 0;
+  y.e_u2 = take(0); cur += (size_t)inst * align256(M * D * e);
   size_t abytes = M * c->F * e, pbytes = (size_t)nn * c->g2 * c->Kp * e;
   y.s_a = save ? align256(abytes) : 0;
   y.e_a = take(0); cur += (size_t)inst * align256(abytes);
@@ -348,13 +355,14 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
   char* O = ar + y.e_O + (size_t)l * y.s_O;
   float* lse = (float*)(ar + y.e_lse + (size_t)l * y.s_lse);
   char* m = ar + y.e_m + (size_t)l * y.s_m;
-  char* u = ar + y.e_u;
+  char* u1 = ar + y.e_u1 + (size_t)l * y.s_u1;
+  char* u2 = ar + y.e_u2 + (size_t)l * y.s_u2;
   char* a = ar + y.e_a + (size_t)l * y.s_a;
   int wi = 1 + 4 * l;
-  ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
+  ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u1, D, M);
   {
     GemmNT g{};
-    g.A = u; g.lda = D; g.B = weight(c, wi + 0); g.ldb = D; g.M = M; g.N = 3 * D; g.K = D;
+    g.A = u1; g.lda = D; g.B = weight(c, wi + 0); g.ldb = D; g.M = M; g.N = 3 * D; g.K = D;
     g.epi = EPI_BIAS; g.bias = c->params + o.qkvb; g.out = qkv; g.ldc = 3 * D;
     gemm_nt(r, g);
   }
@@ -368,10 +376,10 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
       g.epi = EPI_BIAS_RESID; g.bias = c->params + o.projb; g.resid = xin; g.ldr = TD; g.out = xmid; g.ldc = TD;
       gemm_nt(r, g);
     }
-    ln_fwd(r, xmid, TD, c->params + o.ln2g, c->params + o.ln2b, u, D, n);
+    ln_fwd(r, xmid, TD, c->params + o.ln2g, c->params + o.ln2b, u2, D, n);   // compact [n, D]
     {
       GemmNT g{};
-      g.A = u; g.lda = D; g.B = weight(c, wi + 2); g.ldb = D; g.M = n; g.N = F; g.K = D;
+      g.A = u2; g.lda = D; g.B = weight(c, wi + 2); g.ldb = D; g.M = n; g.N = F; g.K = D;
       g.epi = EPI_BIAS_GELU; g.bias = c->params + o.fc1b; g.out = a; g.ldc = F; g.out2 = m; g.ldc2 = F;
       gemm_nt(r, g);
     }
@@ -391,10 +399,10 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
     g.epi = EPI_BIAS_RESID; g.bias = c->params + o.projb; g.resid = xin; g.ldr = D; g.out = xmid; g.ldc = D;
     gemm_nt(r, g);
   }
-  ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u, D, M);
+  ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u2, D, M);
   {
     GemmNT g{};
-    g.A = u; g.lda = D; g.B = weight(c, wi + 2); g.ldb = D; g.M = M; g.N = F; g.K = D;
+    g.A = u2; g.lda = D; g.B = weight(c, wi + 2); g.ldb = D; g.M = M; g.N = F; g.K = D;
     g.epi = EPI_BIAS_GELU; g.bias = c->params + o.fc1b; g.out = a; g.ldc = F;
     g.out2 = m; g.ldc2 = F;   // m slot: gelu'(pre-activation), all the backward needs of it
     gemm_nt(r, g);
@@ -458,7 +466,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
   float* cpart = (float*)(ar + y.w_cpart);
   float* lnpart = (float*)(ar + y.w_lnpart);
   char *dxA = ar + y.e_dxA, *dxB = ar + y.e_dxB, *dxAt = ar + y.e_dxAt, *dxBt = ar + y.e_dxBt;
-  char *du = ar + y.e_du, *dqkv = ar + y.e_dqkv, *u = ar + y.e_u, *dm = ar + y.e_dm;
+  char *du = ar + y.e_du, *dqkv = ar + y.e_dqkv, *dm = ar + y.e_dm;
   RowMap id{0, 0};
   float* G = c->grads;
   launch(r, K_ELEMWISE, 0, (double)M * D * rs, [&] { return launch_fill_zero(dxA, (size_t)M * D * rs, s); });
@@ -474,6 +482,8 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
     char* O = ar + y.e_O + (size_t)l * y.s_O;
     float* lse = (float*)(ar + y.e_lse + (size_t)l * y.s_lse);
     char* m = ar + y.e_m + (size_t)l * y.s_m;
+    char* u1 = ar + y.e_u1 + (size_t)l * y.s_u1;   // LN1(x_in), LN2(x_mid) as the forward (or its re-run) left them
+    char* u2 = ar + y.e_u2 + (size_t)l * y.s_u2;
     int wi = 1 + 4 * l;
     // block inputs only were kept: re-create this block's activations in the shared slots (the
     // last block's are still there from the forward)
@@ -491,8 +501,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
         gemm_nt(r, g);
       }
       gemm_tn(r, dxAt, TD, id, a, F, id, n, D, F, wpart, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
-      ln_fwd(r, xmid, TD, c->params + o.ln2g, c->params + o.ln2b, u, D, n);
-      gemm_tn(r, dm, F, id, u, D, id, n, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
+      gemm_tn(r, dm, F, id, u2, D, id, n, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
       {
         GemmNT g{};
         g.A = dm; g.lda = F; g.B = weight_t(c, wi + 2); g.ldb = F; g.M = n; g.N = D; g.K = F;
@@ -509,8 +518,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       }
       launch(r, K_ATTN_BWD, 10.0 * n * c->H * (double)T * c->dh, (double)M * 7 * D * e,
              [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s, true, (float*)(ar + y.e_dl)); });
-      ln_fwd(r, xin, D, c->params + o.ln1g, c->params + o.ln1b, u, D, M);
-      gemm_tn(r, dqkv, 3 * D, id, u, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
+      gemm_tn(r, dqkv, 3 * D, id, u1, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
       {
         GemmNT g{};
         g.A = dqkv; g.lda = 3 * D; g.B = weight_t(c, wi + 0); g.ldb = 3 * D; g.M = M; g.N = D; g.K = 3 * D;
@@ -534,9 +542,8 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
       gemm_nt(r, g);
     }
-    // LN2 backward also re-creates u = LN2(x_mid), which the fc1 weight gradient needs
-    ln_bwd(r, xmid, D, du, D, o.ln2g, o.ln2b, dxA, dxB, dxBt, D, M, lnpart, accumulate, false, u);
-    gemm_tn(r, dm, F, id, u, D, id, M, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
+    ln_bwd(r, xmid, D, du, D, o.ln2g, o.ln2b, dxA, dxB, dxBt, D, M, lnpart, accumulate);
+    gemm_tn(r, dm, F, id, u2, D, id, M, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
     // ---- attention half: x_mid = x_in + attn(LN1(x_in)) Wo^T + bo
     gemm_tn(r, dxBt, D, id, O, D, id, M, D, D, wpart, G + o.projW, accumulate, -1, G + o.projb, cpart);
     {
@@ -553,8 +560,8 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
       gemm_nt(r, g);
     }
-    ln_bwd(r, xin, D, du, D, o.ln1g, o.ln1b, dxB, dxA, dxAt, D, M, lnpart, accumulate, false, u);
-    gemm_tn(r, dqkv, 3 * D, id, u, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
+    ln_bwd(r, xin, D, du, D, o.ln1g, o.ln1b, dxB, dxA, dxAt, D, M, lnpart, accumulate);
+    gemm_tn(r, dqkv, 3 * D, id, u1, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
   }
   // ---- token assembly: x0[n,0] = cls + pos[0]; x0[n,1+j] = patch_j W_pe^T + b_pe + pos[1+j]
   {
