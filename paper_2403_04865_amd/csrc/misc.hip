@@ -39,9 +39,11 @@ hipError_t launch_cast_transpose(int dt, const float* src, int R, int C, void* d
 // ---------------------------------------------------------------------------------------
 // pixels [n,3,S,S] <-> patches [n*g*g, 3*P*P]   (patch order (gy,gx), flatten order (c,py,px))
 // ---------------------------------------------------------------------------------------
+// Patch matrix: tile n owns rows n * (g * g + lead) .. of 3 P P columns: `lead` rows of zeros (the slots of the tokens
+// that are no patches, so that the matrix lines up row by row with the token matrix), then its g * g patches.
 template <typename T>
 __global__ void __launch_bounds__(256) patchify_k(const T* __restrict__ pix, T* __restrict__ pat, long long total,
-                                                  int S, int P) {
+                                                  int S, int P, int lead) {
   long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i >= total) return;
   int g = S / P, Kp = 3 * P * P;
@@ -50,13 +52,17 @@ __global__ void __launch_bounds__(256) patchify_k(const T* __restrict__ pix, T* 
   int px = col % P, py = (col / P) % P, c = col / (P * P);
   int gx = (int)(row % g), gy = (int)((row / g) % g);
   long long n = row / (g * g);
-  pat[i] = pix[((n * 3 + c) * S + gy * P + py) * S + gx * P + px];
+  long long base = n * (g * g + lead);
+  pat[(base + lead + row % (g * g)) * Kp + col] = pix[((n * 3 + c) * S + gy * P + py) * S + gx * P + px];
+  if (row % (g * g) == 0)
+    for (int l = 0; l < lead; ++l) pat[(base + l) * Kp + col] = from_f<T>(0.f);
 }
 
 // bf16, P % 8 == 0, S % 8 == 0: one workgroup per band of patches (tile n, patch row gy).  The band's 3 x P image
 // rows are read with 16-byte accesses along the rows into LDS and written as whole patch rows, again 16 bytes
 // per lane and contiguous (the element-wise kernel above moves 2 bytes per lane).
-__global__ void __launch_bounds__(256) patchify_band_k(const bf16* __restrict__ pix, bf16* __restrict__ pat, int S, int P) {
+__global__ void __launch_bounds__(256) patchify_band_k(const bf16* __restrict__ pix, bf16* __restrict__ pat, int S, int P,
+                                                       int lead) {
   extern __shared__ uint4 band[];   // [3 * P][S / 8] chunks of 8 pixels
   const int g = S / P, SC = S / 8, PC = P / 8, rows = 3 * P;
   const long long n = blockIdx.x / g;
@@ -67,7 +73,10 @@ __global__ void __launch_bounds__(256) patchify_band_k(const bf16* __restrict__ 
   }
   __syncthreads();
   const int KC = rows * PC;          // chunks per patch row of the output
-  bf16* out = pat + (n * g + gy) * (long long)g * (3 * P * P);
+  bf16* out = pat + ((n * (g * g + lead) + lead) + gy * g) * (long long)(3 * P * P);
+  if (gy == 0)   // the tile's leading rows of zeros
+    for (int i = threadIdx.x; i < lead * KC; i += 256)
+      *reinterpret_cast<uint4*>(pat + n * (g * g + lead) * (long long)(3 * P * P) + (long long)i * 8) = make_uint4(0, 0, 0, 0);
   for (int i = threadIdx.x; i < g * KC; i += 256) {
     int gx = i / KC, k = i % KC, r = k / PC, pc = k % PC;   // r = c * P + py
     *reinterpret_cast<uint4*>(out + (long long)i * 8) = band[r * SC + gx * PC + pc];
@@ -87,16 +96,16 @@ __global__ void __launch_bounds__(256) unpatchify_k(const T* __restrict__ dpat, 
   dpix[i] = dpat[row * Kp + col];
 }
 
-hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long n, int S, int P, hipStream_t s) {
+hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long n, int S, int P, hipStream_t s, int lead) {
   long long total = n * 3LL * S * S;
   unsigned grid = (unsigned)((total + 255) / 256);
   if (dt == DT_F32)
-    hipLaunchKernelGGL(patchify_k<float>, dim3(grid), dim3(256), 0, s, (const float*)pixels, (float*)patches, total, S, P);
+    hipLaunchKernelGGL(patchify_k<float>, dim3(grid), dim3(256), 0, s, (const float*)pixels, (float*)patches, total, S, P, lead);
   else if (P % 8 == 0 && S % P == 0 && n * (S / P) < (1LL << 31) && (size_t)3 * P * S * 2 <= 65536)
     hipLaunchKernelGGL(patchify_band_k, dim3((unsigned)(n * (S / P))), dim3(256), (size_t)3 * P * S * 2, s,
-                       (const bf16*)pixels, (bf16*)patches, S, P);
+                       (const bf16*)pixels, (bf16*)patches, S, P, lead);
   else
-    hipLaunchKernelGGL(patchify_k<bf16>, dim3(grid), dim3(256), 0, s, (const bf16*)pixels, (bf16*)patches, total, S, P);
+    hipLaunchKernelGGL(patchify_k<bf16>, dim3(grid), dim3(256), 0, s, (const bf16*)pixels, (bf16*)patches, total, S, P, lead);
   return hipGetLastError();
 }
 

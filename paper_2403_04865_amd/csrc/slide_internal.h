@@ -137,7 +137,8 @@ int gemm_tn_pick_slabs(long long M, int N1, int N2, int max_slabs);
 bool gemm_tn_fuses_colsum(int dt, const GemmTN& g, bool use_mfma);  // will launch_gemm_tn fill cs_part?
 
 hipError_t launch_cast_transpose(int dt, const float* src, int R, int C, void* dstW, void* dstWT, hipStream_t s);
-hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long n, int S, int P, hipStream_t s);
+// patches: [n * (g*g + lead)][3 P P], every tile's g*g patch rows behind `lead` rows of zeros
+hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long n, int S, int P, hipStream_t s, int lead);
 hipError_t launch_unpatchify(int dt, const void* dpatches, void* dpix, long long n, int S, int P, hipStream_t s);
 hipError_t launch_cls_rows(int dt, void* x, const float* cls, const float* pos, long long n, int T, int D, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);

@@ -134,7 +134,7 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   y.w_lnpart = take((size_t)1024 * 2 * D * 4);
   y.enc_begin = cur;
   int inst = save ? c->L : (c->L > 0 ? 1 : 0);
-  y.e_patches = take((size_t)nn * c->g2 * c->Kp * e);
+  y.e_patches = take((size_t)nn * c->T * c->Kp * e);   // one row per token: the CLS slot is a row of zeros
   y.s_x = bwd ? align256(M * D * rs) : 0;
   y.e_x = take(0);
   cur += (bwd ? (size_t)(c->L + 1) : 1) * align256(M * D * rs);
@@ -430,10 +430,12 @@ int enc_fwd(slide_ctx* c, const void* pixels, long long n, void* feats_out, bool
   int D = c->D, T = c->T, dt = c->dt;
   cast_weights(r);
   launch(r, K_ELEMWISE, 0, 2.0 * n * 3 * c->cfg.tile * c->cfg.tile * elem_size(dt),
-         [&] { return launch_patchify(dt, pixels, ar + y.e_patches, n, c->cfg.tile, c->cfg.patch, s); });
+         [&] { return launch_patchify(dt, pixels, ar + y.e_patches, n, c->cfg.tile, c->cfg.patch, s, T - c->g2); });
   {
+    // the patch matrix has the token matrix's rows (a row of zeros in each tile's CLS slot): its weight gradient is
+    // then a plain product of two row-aligned matrices and runs on the large-M kernel
     GemmNT g{};
-    g.A = ar + y.e_patches; g.lda = c->Kp; g.amap = RowMap{0, 0};
+    g.A = ar + y.e_patches; g.lda = c->Kp; g.amap = RowMap{c->g2, T};
     g.B = weight(c, 0); g.ldb = c->Kp;
     g.M = n * c->g2; g.N = D; g.K = c->Kp;
     g.epi = EPI_PATCH; g.bias = c->params + c->o_peb; g.pos = c->params + c->o_pos;
@@ -573,11 +575,16 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
            [&] { return launch_reduce_partials(cpart, slabs, cols, cols, G + c->o_pos, accumulate, s); });
     launch(r, K_ELEMWISE, 0, 0,
            [&] { return launch_reduce_partials(cpart, slabs, cols, D, G + c->o_cls, accumulate, s); });
+    // the patch-embedding bias sees every patch token: its gradient is this step's position gradient summed over the
+    // patch positions (rows 1 .. T - 1), taken from the same partial sums
+    launch(r, K_ELEMWISE, 0, 0, [&] { return launch_reduce_partials(cpart, slabs, cols, cols, wpart, 0, s); });
+    launch(r, K_ELEMWISE, 0, 0,
+           [&] { return launch_reduce_partials(wpart + D, T - 1, D, D, G + c->o_peb, accumulate, s); });
   }
   RowMap pm{c->g2, T};
   long long Mp = n * c->g2;
-  gemm_tn(r, dxAt, D, pm, ar + y.e_patches, c->Kp, id, Mp, D, c->Kp, wpart, G + c->o_peW, accumulate, -1,
-          G + c->o_peb, cpart);
+  // all token rows: the CLS rows meet rows of zeros in the patch matrix
+  gemm_tn(r, dxAt, D, id, ar + y.e_patches, c->Kp, id, M, D, c->Kp, wpart, G + c->o_peW, accumulate);
   if (pixel_grad) {
     GemmNT g{};
     g.A = dxAt; g.lda = D; g.amap = pm; g.B = weight_t(c, 0); g.ldb = D; g.M = Mp; g.N = c->Kp; g.K = D;
