@@ -17,7 +17,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 # model FLOPs per tile, forward + backward (2mnk per GEMM, both attention GEMMs, dgrad + wgrad,
 # no pixel gradient)
@@ -55,7 +54,7 @@ def pool_sweep(a):
     import torch
     import gen
     from dataclasses import replace
-    from slide_harness import lib_config
+    from paper_2403_04865_amd import config_from as lib_config
     from paper_2403_04865_amd import SlideLib
     cfg, _ = gen.CONFIGS["medium"]
     cfg = replace(cfg, mil_hidden=a.pool_hidden)
@@ -120,8 +119,7 @@ def adamw_bench(a):
     import numpy as np
     import torch
     import gen
-    sys.path.insert(0, os.path.join(os.path.dirname(os.path.abspath(__file__)), "tests"))
-    from slide_harness import lib_config
+    from paper_2403_04865_amd import config_from as lib_config
     from paper_2403_04865_amd import SlideLib
     cfg, _ = gen.CONFIGS[a.workload]
     lib = SlideLib(lib_config(cfg, 1))
@@ -213,7 +211,7 @@ def main():
     import numpy as np
     import torch
     import gen
-    from slide_harness import lib_config
+    from paper_2403_04865_amd import config_from as lib_config
     from paper_2403_04865_amd import SlideLib
 
     cfg, N = gen.CONFIGS[a.workload]

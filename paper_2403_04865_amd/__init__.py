@@ -2,4 +2,4 @@
 behind the C ABI of libslide.so (see include/slide.h).  This package is only the ctypes binding:
 argument marshalling, nothing else.  There is no CPU fallback: importing `binding` without a
 built libslide.so raises."""
-from .binding import SlideLib, SlideConfig, SlideError, lib_path  # noqa: F401
+from .binding import SlideLib, SlideConfig, SlideError, config_from, lib_path  # noqa: F401

@@ -46,6 +46,13 @@ class SlideConfig:
     want_pixel_grad: int = 0
 
 
+def config_from(shape, dtype: int, recompute: int = 0) -> SlideConfig:
+    """SlideConfig from any object with the fields tile, patch, dim, layers, heads, mlp_ratio, mil_hidden, n_classes
+    and ln_eps (such as a workload description of the input generators)."""
+    return SlideConfig(shape.tile, shape.patch, shape.dim, shape.layers, shape.heads, shape.mlp_ratio, shape.mil_hidden,
+                       shape.n_classes, dtype=dtype, recompute=recompute, ln_eps=shape.ln_eps)
+
+
 _SYMS = {
     "slide_ctx_create": (C.c_int, [C.POINTER(_CConfig), C.POINTER(C.c_void_p)]),
     "slide_ctx_destroy": (None, [C.c_void_p]),

@@ -14,14 +14,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Residual-stream element type of the bf16 path (activations that are summed layer after
-// layer, forward x and backward dx).  bf16 halves the traffic of every kernel that touches the
-// stream and stays inside the 2e-2 parity budget; -DSLIDE_BF16_STREAM_IS_F32 keeps the running
-// sums in fp32 instead (about half the error, 4*D more bytes per token and layer).
-#ifdef SLIDE_BF16_STREAM_IS_F32
-typedef float rs_bf16path_t;
-#else
+// layer, forward x and backward dx): bf16, which halves the traffic of every kernel that touches the
+// stream.  The one row per tile whose rounding decides the accuracy of the slide gradient (the CLS
+// row) is carried in fp32 beside it (cls_lane.hip).
 typedef bf16 rs_bf16path_t;
-#endif
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
 
@@ -206,6 +202,17 @@ hipError_t launch_pool_gate_part_mfma(const PoolArgs& p, hipStream_t s);
 hipError_t launch_pool_fwd(const PoolArgs& p, hipStream_t s);
 hipError_t launch_pool_bwd_rows(const PoolArgs& p, float* Dp, hipStream_t s);
 hipError_t launch_pool_head_grads(const PoolArgs& p, hipStream_t s);
+
+// fp32 lane of the CLS rows (bf16 path, cls_lane.hip)
+bool cls_lane_ok(int D, int F);
+hipError_t launch_lane_init(const float* cls, const float* pos, float* xc, long long n, int D, hipStream_t s);
+hipError_t launch_lane_ln(const float* x, long long xs, const float* gam, const float* bet, float* out, long long os,
+                          long long rows, int D, float eps, hipStream_t s);
+// out[n,N] (fp32) = A[n,K] W[N,K]^T + bias, then + resid (fp32) or, with gelu, gelu(.).  A: fp32, or bf16 with a_bf16;
+// W: bf16.  copy (may be null): bf16 copy of the result rows (row stride ldcopy), residual mode only.
+hipError_t launch_lane_gemm(bool gelu, bool a_bf16, const void* A, long long lda, const void* W, long long ldw, long long n,
+                            int N, int K, const float* bias, const float* resid, long long ldr, float* out, long long ldc,
+                            void* copy, long long ldcopy, hipStream_t s);
 
 // theta, m, v updated in place (fp32, n elements); step counts from 1
 hipError_t launch_adamw(float* theta, const float* g, float* m, float* v, size_t n, long long step, float lr, float b1,

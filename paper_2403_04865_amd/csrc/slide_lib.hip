@@ -15,10 +15,11 @@ thread_local int g_last_hip = 0;
 
 enum KernelId {
   K_GEMM_NT = 0, K_GEMM_TN, K_ATTN_FWD, K_ATTN_BWD, K_LN_FWD, K_LN_BWD, K_COLSUM, K_POOL_FWD, K_POOL_BWD,
-  K_ELEMWISE, K_COUNT
+  K_ELEMWISE, K_CLS_LANE, K_COUNT
 };
 const char* const kKernelNames[K_COUNT] = {
-  "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "pool_fwd", "pool_bwd", "elementwise"};
+  "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "pool_fwd", "pool_bwd", "elementwise",
+  "cls_lane"};
 
 struct Prof {
   bool active = false;
@@ -48,6 +49,9 @@ struct Layout {
   size_t s_x, s_qkv, s_O, s_lse, s_xmid, s_m, s_a;                    // per-layer strides (0 when not saved)
   size_t e_u1, e_u2, s_u1, s_u2;                                          // LayerNorm outputs of a block (inputs of its QKV / fc1 GEMMs)
   size_t e_a, e_dm, e_dxA, e_dxB, e_dxAt, e_dxBt, e_du, e_dqkv;
+  // fp32 lane of the CLS rows: stream at the input of every block and behind the last [L + 1][n][D] (stride s_xc),
+  // and one instance each of the stream behind the attention half, its LayerNorm and the MLP activation
+  size_t l_xc, s_xc, l_xcm, l_u2c, l_ac;
 };
 
 }  // namespace
@@ -73,6 +77,7 @@ struct slide_ctx {
   bool step_saved = false;    // slide_step_fwd state (features in arena, label)
   int step_label = 0;
   bool use_mfma = true;
+  bool use_lane = false;      // bf16 path: the CLS rows' stream and row-wise work are repeated in fp32 (cls_lane.hip)
   Prof prof;
 };
 
@@ -133,6 +138,11 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   y.w_cpart = take((size_t)128 * (maxcols > tokcols ? maxcols : tokcols) * 4);
   y.w_lnpart = take((size_t)1024 * 2 * D * 4);
   y.enc_begin = cur;
+  y.s_xc = align256((size_t)nn * D * 4);
+  y.l_xc = take(0); cur += (size_t)(c->L + 1) * y.s_xc;
+  y.l_xcm = take((size_t)nn * D * 4);
+  y.l_u2c = take((size_t)nn * D * 4);
+  y.l_ac = take((size_t)nn * c->F * 4);
   int inst = save ? c->L : (c->L > 0 ? 1 : 0);
   y.e_patches = take((size_t)nn * c->T * c->Kp * e);   // one row per token: the CLS slot is a row of zeros
   y.s_x = bwd ? align256(M * D * rs) : 0;
@@ -252,7 +262,7 @@ void gemm_tn(Run& r, const void* A, long long lda, RowMap amap, const void* B, l
   g.part = part;
   g.cs_part = nullptr;
   g.big = 0;
-  int bs = (dt == DT_BF16 && r.c->use_mfma && !getenv("SLIDE_TN_SMALL")) ? gemm_tn_big_slabs(g, 64) : 0;
+  int bs = (dt == DT_BF16 && r.c->use_mfma) ? gemm_tn_big_slabs(g, 64) : 0;
   if (bs) { g.slabs = bs; g.big = 1; }
   else g.slabs = gemm_tn_pick_slabs(M, N1, N2, 32);
   bool fused = bias_out && gemm_tn_fuses_colsum(dt, g, r.c->use_mfma);
@@ -338,7 +348,47 @@ int check_bound(const slide_ctx* c) {
 // matrices: leading dimension T * D), and its attention needs query 0 only.  K and V still need every token, so LN1
 // and the QKV GEMM stay dense.  Exact, not an approximation; taken where the attention kernels support it.
 bool prune_last_block(const slide_ctx* c) {
-  return attn_cls_only_ok(c->dt, c->T, c->dh, c->use_mfma) && rs_size(c->dt) == elem_size(c->dt) && !getenv("SLIDE_NO_PRUNE");
+  return attn_cls_only_ok(c->dt, c->T, c->dh, c->use_mfma) && rs_size(c->dt) == elem_size(c->dt);
+}
+
+// ---- fp32 lane of the CLS rows (bf16 path).  xc(l) is the lane's stream at the input of block l.
+float* lane_xc(const slide_ctx* c, const Layout& y, int l) { return (float*)(c->arena + y.l_xc + (size_t)l * y.s_xc); }
+
+// attention half: xcm = xc(l) + O[cls rows] Wo^T + bo, and its rounded copy over the CLS rows of x_mid
+void lane_attn_half(Run& r, const Layout& y, int l, long long n, const void* O, void* xmid) {
+  slide_ctx* c = r.c;
+  if (!c->use_lane) return;
+  const int D = c->D;
+  const long long TD = (long long)c->T * D;
+  const LayerOff& o = c->lo[l];
+  float* xcm = (float*)(c->arena + y.l_xcm);
+  launch(r, K_CLS_LANE, 2.0 * n * D * D, (double)n * D * 14, [&] {
+    return launch_lane_gemm(false, true, O, TD, weight(c, 2 + 4 * l), D, n, D, D, c->params + o.projb, lane_xc(c, y, l), D,
+                            xcm, D, xmid, TD, r.s);
+  });
+}
+
+// MLP half: xc(l+1) = xcm + gelu(LN2(xcm) W1^T + b1) W2^T + b2, and its rounded copy over the CLS rows of x_out
+void lane_mlp_half(Run& r, const Layout& y, int l, long long n, void* xout) {
+  slide_ctx* c = r.c;
+  if (!c->use_lane) return;
+  const int D = c->D, F = c->F;
+  const long long TD = (long long)c->T * D;
+  const LayerOff& o = c->lo[l];
+  float* xcm = (float*)(c->arena + y.l_xcm);
+  float* u2c = (float*)(c->arena + y.l_u2c);
+  float* ac = (float*)(c->arena + y.l_ac);
+  launch(r, K_CLS_LANE, 0, (double)n * D * 8, [&] {
+    return launch_lane_ln(xcm, D, c->params + o.ln2g, c->params + o.ln2b, u2c, D, n, D, c->cfg.ln_eps, r.s);
+  });
+  launch(r, K_CLS_LANE, 4.0 * n * D * F, (double)n * (D + F) * 4, [&] {
+    return launch_lane_gemm(true, false, u2c, D, weight(c, 3 + 4 * l), D, n, F, D, c->params + o.fc1b, nullptr, 0, ac, F,
+                            nullptr, 0, r.s);
+  });
+  launch(r, K_CLS_LANE, 4.0 * n * D * F, (double)n * (F * 4 + D * 10), [&] {
+    return launch_lane_gemm(false, false, ac, F, weight(c, 4 + 4 * l), F, n, D, F, c->params + o.fc2b, xcm, D,
+                            lane_xc(c, y, l + 1), D, xout, TD, r.s);
+  });
 }
 
 void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
@@ -376,6 +426,7 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
       g.epi = EPI_BIAS_RESID; g.bias = c->params + o.projb; g.resid = xin; g.ldr = TD; g.out = xmid; g.ldc = TD;
       gemm_nt(r, g);
     }
+    lane_attn_half(r, y, l, n, O, xmid);
     ln_fwd(r, xmid, TD, c->params + o.ln2g, c->params + o.ln2b, u2, D, n);   // compact [n, D]
     {
       GemmNT g{};
@@ -389,6 +440,7 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
       g.epi = EPI_BIAS_RESID; g.bias = c->params + o.fc2b; g.resid = xmid; g.ldr = TD; g.out = xout; g.ldc = TD;
       gemm_nt(r, g);
     }
+    lane_mlp_half(r, y, l, n, xout);
     return;
   }
   launch(r, K_ATTN_FWD, 4.0 * n * c->H * (double)T * T * c->dh, (double)M * 4 * D * elem_size(dt),
@@ -399,6 +451,7 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
     g.epi = EPI_BIAS_RESID; g.bias = c->params + o.projb; g.resid = xin; g.ldr = D; g.out = xmid; g.ldc = D;
     gemm_nt(r, g);
   }
+  lane_attn_half(r, y, l, n, O, xmid);
   ln_fwd(r, xmid, D, c->params + o.ln2g, c->params + o.ln2b, u2, D, M);
   {
     GemmNT g{};
@@ -412,6 +465,7 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
     g.A = a; g.lda = F; g.B = weight(c, wi + 3); g.ldb = F; g.M = M; g.N = D; g.K = F;
     g.epi = EPI_BIAS_RESID; g.bias = c->params + o.fc2b; g.resid = xmid; g.ldr = D; g.out = xout; g.ldc = D;
     gemm_nt(r, g);
+    lane_mlp_half(r, y, l, n, xout);   // a replay only re-creates x_mid: x_in(l + 1) is stored with the lane's row in it
   }
 }
 
@@ -444,9 +498,18 @@ int enc_fwd(slide_ctx* c, const void* pixels, long long n, void* feats_out, bool
   }
   launch(r, K_ELEMWISE, 0, 0,
          [&] { return launch_cls_rows(dt, ar + y.e_x, c->params + c->o_cls, c->params + c->o_pos, n, T, D, s); });
+  if (c->use_lane)
+    launch(r, K_CLS_LANE, 0, (double)n * D * 4,
+           [&] { return launch_lane_init(c->params + c->o_cls, c->params + c->o_pos, lane_xc(c, y, 0), n, D, s); });
   for (int l = 0; l < c->L; ++l) block_fwd(r, y, l, n, false);
   char* xL = ar + y.e_x + (size_t)c->L * y.s_x;
-  ln_fwd(r, xL, (long long)T * D, c->params + c->o_lnfg, c->params + c->o_lnfb, feats_out, D, n, true);
+  if (c->use_lane)   // the features are the final LayerNorm of the lane's stream (its rounded copy is the CLS row of xL)
+    launch(r, K_CLS_LANE, 0, (double)n * D * 8, [&] {
+      return launch_lane_ln(lane_xc(c, y, c->L), D, c->params + c->o_lnfg, c->params + c->o_lnfb, (float*)feats_out, D, n, D,
+                            c->cfg.ln_eps, s);
+    });
+  else
+    ln_fwd(r, xL, (long long)T * D, c->params + c->o_lnfg, c->params + c->o_lnfb, feats_out, D, n, true);
   if (r.ok() && save) { c->enc_saved = true; c->enc_n = n; c->enc_layout = y; }
   return finish(r);
 }
@@ -636,7 +699,7 @@ int pool_bwd(slide_ctx* c, const Layout& y, const void* feats, long long N, int 
   float* cs = (float*)(ar + y.p_cs);
   // the matrix-core path keeps [dpV dpU] and a feature copy as bf16 in the room of the fp32 [N, 3 Mh] array; db_V and
   // db_U come out of the weight-gradient GEMM as column sums of its first operand
-  if (pool_bwd_mfma_ok(p) && (size_t)(2 * Mh + D) * 2 <= (size_t)3 * Mh * 4 && !getenv("SLIDE_POOL_BWD_ALU")) {
+  if (pool_bwd_mfma_ok(p) && (size_t)(2 * Mh + D) * 2 <= (size_t)3 * Mh * 4) {
     // M_h = 256 runs as two halves of 128 gate units: Dp is then [2][N][256], the dw partials [2][blocks][128]
     const int MHK = 128, halves = Mh / MHK;
     char* Hb16 = Dp + (size_t)N * 2 * Mh * 2;
@@ -735,8 +798,8 @@ int slide_ctx_create(const slide_config* cfg, slide_ctx** out) {
   c->o_cW = add_tensor(c, "head.W", (size_t)c->C * D);
   c->o_cb = add_tensor(c, "head.b", c->C);
   if ((size_t)c->Mh * D > c->max_w) c->max_w = (size_t)c->Mh * D;
-  const char* env = getenv("SLIDE_NO_MFMA");
-  c->use_mfma = !(env && env[0] == '1');
+  c->use_mfma = true;
+  c->use_lane = c->dt == DT_BF16 && cls_lane_ok(c->D, c->F);
   *out = c;
   return SLIDE_OK;
 }
@@ -812,8 +875,11 @@ static int pool_check(slide_ctx* c, const void* feats, int64_t N, int32_t label,
   if (label < 0 || label >= (c->C == 1 ? 2 : c->C)) return SLIDE_EINVAL;
   *y = make_layout(c, 0, N, KEEP_NONE);
   if (y->pool_end > c->arena_bytes) return SLIDE_EARENA;
-  // a pool over more rows than the saved encoder state was laid out for would overwrite it
+  // a pool over more rows than the saved encoder state was laid out for would overwrite it: its work space then
+  // reaches into the encoder part, and already for any N beyond the saved step's it lies over that step's features
+  // (the pool part is laid out front to back with sizes that grow with N)
   if (c->enc_saved && y->pool_end > c->enc_layout.enc_begin) { c->enc_saved = false; c->step_saved = false; }
+  if (c->step_saved && N > c->enc_n) c->step_saved = false;
   return SLIDE_OK;
 }
 

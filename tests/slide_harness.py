@@ -7,9 +7,8 @@ import gen
 
 
 def lib_config(cfg: gen.SlideConfig, dtype: int, recompute: int = 0):
-    from paper_2403_04865_amd import SlideConfig
-    return SlideConfig(cfg.tile, cfg.patch, cfg.dim, cfg.layers, cfg.heads, cfg.mlp_ratio, cfg.mil_hidden,
-                       cfg.n_classes, dtype=dtype, recompute=recompute, ln_eps=cfg.ln_eps)
+    from paper_2403_04865_amd import config_from
+    return config_from(cfg, dtype, recompute)
 
 
 class GpuSlide:
@@ -114,10 +113,10 @@ def compare_step(gpu, ref, tol, cfg, grad_tol=None, pool_same_input=None):
       softmax-invariant): checked absolutely against the norm of the whole tensor.
     * The gate tensors of the pool (mil.V.*, mil.U.*, mil.w) depend on the features only
       through differences between rows (sum_n da_n = 0), so a relative error eps in the
-      features appears amplified by kappa = |H| / |H - mean row|.  They are therefore held
-      to `grad_tol` against the oracle's pool evaluated on the SAME feature matrix the GPU
-      produced (`pool_same_input`: dict of oracle pool gradients on gpu["H"]), and end to
-      end to kappa * tol.
+      features appears amplified by kappa = |H| / |H - mean row| (returned for the log).
+      They are held to `grad_tol` end to end like every other tensor, and in addition
+      against the oracle's pool evaluated on the SAME feature matrix the GPU produced
+      (`pool_same_input`: dict of oracle pool gradients on gpu["H"]).
     """
     grad_tol = tol if grad_tol is None else grad_tol
     errs, lim = {}, {}
@@ -142,7 +141,7 @@ def compare_step(gpu, ref, tol, cfg, grad_tol=None, pool_same_input=None):
             errs[name + "@sameH"] = rel_l2(a, pool_same_input[name])
             lim[name + "@sameH"] = grad_tol
             errs[name + "@e2e"] = rel_l2(a, g)
-            lim[name + "@e2e"] = max(grad_tol, kappa * tol)
+            lim[name + "@e2e"] = grad_tol
         else:
             errs[name] = rel_l2(a, g)
             lim[name] = grad_tol

@@ -32,7 +32,8 @@ def _upload_pixels(torch, cfg, N, seed, dev):
     return px
 
 
-@pytest.mark.parametrize("name,n_sample,n_chunks", [("medium", 6, 8), ("large", 6, 4), ("full", 3, 2)])
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name,n_sample,n_chunks", [("small", 6, 4), ("medium", 6, 8), ("large", 6, 4), ("full", 3, 2)])
 def test_fullsize_links(name, n_sample, n_chunks):
     import torch
     from oracle import slide_oracle as so

@@ -105,3 +105,94 @@ def test_recompute_is_bit_identical_to_keeping_everything(dtype):
         assert np.array_equal(a[k], b[k]), k
     for k in a["grads"]:
         assert np.array_equal(a["grads"][k], b["grads"][k]), k
+
+
+# ---- the Small workload at its own size (256 ViT-S tiles) and a 336-tile slide -------------------------------
+def _oracle_chunked(prm, X, label, cfg, chunk=16):
+    """The oracle's whole-slide step with bounded memory: tile chunks, features first, each chunk's forward run
+    again just before its backward (the result is the one-piece gradient: sums over chunks)."""
+    import time
+    from oracle import slide_oracle as so
+    N = X.shape[0]
+    t0 = time.time()
+    ref = so.slide_step(prm, X.astype(np.float64), label, cfg,
+                        chunks=[(lo, min(N, lo + chunk)) for lo in range(0, N, chunk)], keep_caches=False)
+    print(f"oracle step over {N} tiles: {time.time() - t0:.0f} s", flush=True)
+    return ref
+
+
+@pytest.mark.timeout(900)
+def test_small_256_tiles_fp32_and_bf16():
+    """cfg 2: 256 tiles of 224 px through ViT-S/16, M_h 128, one logit; both precisions against one oracle run on
+    inputs that lie on the bf16 grid (valid fp32 numbers as well)."""
+    from oracle import slide_oracle as so
+    from slide_harness import GpuSlide, compare_step
+    cfg, prm, X, lab = _inputs("small", bf16=True)
+    assert X.shape[0] == 256
+    outs = {}
+    for dtype in (0, 1):
+        print(f"case small n=256 dtype={dtype} label={lab}", flush=True)
+        g = GpuSlide(cfg, prm, dtype, X.shape[0])
+        outs[dtype] = g.step(X, lab)
+        del g
+    ref = _oracle_chunked(prm, X, lab, cfg)
+    for dtype, tol in ((0, FP32_TOL), (1, BF16_TOL)):
+        _, pool_same = so.pool_bwd(so.pool_fwd(prm, outs[dtype]["H"], lab, cfg)[4])
+        errs, bad, kappa = compare_step(outs[dtype], ref, tol, cfg, None, pool_same)
+        print(f"dtype={dtype} kappa={kappa:.1f} worst:", sorted(errs.items(), key=lambda kv: -kv[1])[:8], flush=True)
+        assert not bad, (dtype, bad)
+
+
+@pytest.mark.timeout(900)
+def test_vit_s_bf16_336_tiles_large_m_kernels_and_determinism():
+    """336 consecutive tiles of the medium workload as a slide of their own: 66,192 token rows, so every
+    activation-side GEMM runs several output tiles per workgroup of the large-M kernel (its background epilogue, in
+    the forward and in both input-gradient epilogues) and every weight gradient runs the large-M kernel with the
+    fused bias sums.  (a) whole step against the oracle; (b) encoder backward seeded with the ORACLE's feature
+    gradients against the oracle's encoder gradients; (c) the same step twice gives the same bits."""
+    import torch
+    from slide_harness import GpuSlide, compare_step, rel_l2
+    from oracle import slide_oracle as so
+    cfg, _ = gen.CONFIGS["medium"]
+    ds, ws, ls = gen.SEEDS["medium"]
+    n = 336
+    prm = {k: gen.to_bf16_grid(v) for k, v in gen.make_params(cfg, ws, perturbed=True).items()}
+    X = gen.to_bf16_grid(gen.make_pixels(cfg, n, ds, first_tile=512))
+    lab = gen.make_label(cfg, ls)
+    print(f"case medium tiles 512..847 n={n} dtype=1 label={lab}", flush=True)
+    g = GpuSlide(cfg, prm, 1, n)
+    out = g.step(X, lab)
+    again = g.step(X, lab)
+    assert out["loss"] == again["loss"]
+    for k in ("H", "G", "alpha", "dX", "logits"):
+        assert np.array_equal(out[k], again[k]), k
+    for k in out["grads"]:
+        assert np.array_equal(out["grads"][k], again["grads"][k]), k
+    print("two runs bit-identical", flush=True)
+    ref = _oracle_chunked(prm, X, lab, cfg)
+    _, pool_same = so.pool_bwd(so.pool_fwd(prm, out["H"], lab, cfg)[4])
+    errs, bad, kappa = compare_step(out, ref, BF16_TOL, cfg, None, pool_same)
+    print(f"kappa={kappa:.1f} worst:", sorted(errs.items(), key=lambda kv: -kv[1])[:8], flush=True)
+    assert not bad, bad
+    # (b) encoder backward alone, seeded with the oracle's G
+    px = g.to_dev(X)
+    feats = torch.zeros((n, cfg.dim), device=g.dev)
+    dpx = torch.zeros_like(px)
+    g.lib.encoder_fwd_tiles(px, n, feats, 1)
+    Gs = torch.from_numpy(ref["G"].astype(np.float32)).to(g.dev)
+    g.lib.encoder_bwd_tiles(Gs, n, 0, dpx)
+    torch.cuda.synchronize()
+    gc = g.grads_dict()
+    D = cfg.dim
+    e3 = {"dX": rel_l2(dpx.float().cpu().numpy(), ref["dX"])}
+    for k, v in ref["grads"].items():
+        if k.startswith(("mil.", "head.")):
+            continue
+        a = gc[k]
+        if k.endswith("qkv.b"):
+            e3[k + "[q,v]"] = rel_l2(np.concatenate([a[:D], a[2 * D:]]), np.concatenate([v[:D], v[2 * D:]]))
+            e3[k + "[k]abs"] = float(np.linalg.norm(a[D:2 * D]) / np.linalg.norm(v))
+        else:
+            e3[k] = rel_l2(a, v)
+    print("encoder backward seeded with the oracle's G:", sorted(e3.items(), key=lambda kv: -kv[1])[:6], flush=True)
+    assert all(v <= BF16_TOL for v in e3.values()), {k: v for k, v in e3.items() if v > BF16_TOL}

@@ -121,3 +121,38 @@ def test_pool_bf16_small_bag():            # fewer rows than the matrix-core ker
 
 def test_pool_single_row():                # N = 1: alpha = 1, z = h_1
     _pool_case("medium", 1, 0)
+
+
+def test_pool_over_more_rows_invalidates_a_saved_step():
+    """A pool call over more rows than the saved slide step has tiles lays its work space over that step's features:
+    the step must be dropped (slide_step_bwd reports SLIDE_ESTATE) instead of running on overwritten rows.  A pool
+    call over no more rows than the step leaves it intact."""
+    import torch
+    from paper_2403_04865_amd import SlideError
+    from slide_harness import GpuSlide
+    cfg, n = gen.CONFIGS["tiny"]
+    ds, ws, ls = gen.SEEDS["tiny"]
+    prm = gen.make_params(cfg, ws, perturbed=True)
+    X = gen.make_pixels(cfg, n, ds, kind="uniform")
+    print("case pool call between slide_step_fwd and slide_step_bwd (tiny, fp32)", flush=True)
+    g = GpuSlide(cfg, prm, 0, 64)      # arena sized for 64 tiles: a 48-row pool fits beside a 16-tile step
+    dev = g.dev
+    ref = g.step(X, 1)
+    px = g.to_dev(X)
+    loss = torch.zeros(1, device=dev)
+    feats = torch.from_numpy(gen.make_features(cfg, 48, 3)).to(dev)
+    # same number of rows: the step survives and gives the same gradients
+    g.lib.slide_step_fwd(px, n, 1, loss, None, None)
+    g.lib.mil_pool_fwd(feats[:n].contiguous(), n, 1, loss, None, None)
+    g.lib.slide_step_bwd(0, None)
+    torch.cuda.synchronize()
+    same = g.grads_dict()
+    for k in ref["grads"]:
+        assert np.array_equal(ref["grads"][k], same[k]), k
+    # more rows: the step is gone
+    g.lib.slide_step_fwd(px, n, 1, loss, None, None)
+    g.lib.mil_pool_fwd(feats, 48, 1, loss, None, None)
+    with pytest.raises(SlideError) as e:
+        g.lib.slide_step_bwd(0, None)
+    assert e.value.code == -4
+    torch.cuda.synchronize()
