@@ -119,6 +119,20 @@ int  encoder_bwd_tiles(slide_ctx* ctx, const void* dfeats, int64_t n_tiles, int 
 int  mil_pool_fwd(slide_ctx* ctx, const void* feats, int64_t N, int32_t label,
                   float* loss, float* logits, float* alpha, void* hip_stream);
 
+/* mil_pool_fwd for callers that cannot allocate device memory or hand over work space: code under HIP graph capture,
+ * tight serving loops (slide-level prediction from stored features), harnesses that forbid hipMalloc.  Same
+ * kernels, same results; the kernels' work space (attention logits, per-workgroup softmax partials, scalars, the
+ * low-precision copy of the gate weights) is a fixed array of SLIDE_STATIC_POOL_BYTES inside the library's device
+ * code, one copy per device, held until the process ends.  The context supplies the shapes only and need not be
+ * bound; params_fp32 is the flat parameter vector (device).  The call allocates nothing and frees nothing.
+ * SLIDE_EARENA if N > SLIDE_STATIC_POOL_MAX_ROWS or the work space for (N, D, M_h, C) exceeds the array; other
+ * errors as mil_pool_fwd.  All calls on one device share the array: calls that overlap in time on one device race
+ * (also on different streams or contexts); the array keeps the last call's contents, nothing in it needs clearing. */
+#define SLIDE_STATIC_POOL_BYTES    (12u << 20)
+#define SLIDE_STATIC_POOL_MAX_ROWS 65536
+int  mil_pool_fwd_static(const slide_ctx* ctx, const float* params_fp32, const void* feats, int64_t N, int32_t label,
+                         float* loss, float* logits, float* alpha, void* hip_stream);
+
 /* Aggregator backward (paper listing: `aggregator_loss.backward(); grads = allfeatures.grad`).
  * Recomputes the forward from `feats` and `label` (no state is shared with mil_pool_fwd),
  * writes dfeats_out = G [N,D] float32 and the aggregator slices (mil.*, head.*) of grads_fp32

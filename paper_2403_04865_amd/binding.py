@@ -66,6 +66,8 @@ _SYMS = {
     "encoder_fwd_tiles": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_void_p]),
     "encoder_bwd_tiles": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]),
     "mil_pool_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "mil_pool_fwd_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p]),
     "mil_pool_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int, C.c_void_p]),
     "slide_step_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "slide_step_bwd": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
@@ -184,6 +186,10 @@ class SlideLib:
     def mil_pool_fwd(self, feats, N, label, loss=None, logits=None, alpha=None, stream=None):
         self._check(self.lib.mil_pool_fwd(self.ctx, _ptr(feats), N, label, _ptr(loss), _ptr(logits), _ptr(alpha),
                                           _stream(stream)), "mil_pool_fwd")
+
+    def mil_pool_fwd_static(self, params, feats, N, label, loss=None, logits=None, alpha=None, stream=None):
+        self._check(self.lib.mil_pool_fwd_static(self.ctx, _ptr(params), _ptr(feats), N, label, _ptr(loss), _ptr(logits),
+                                                 _ptr(alpha), _stream(stream)), "mil_pool_fwd_static")
 
     def mil_pool_bwd(self, feats, N, label, dfeats_out, accumulate, stream=None):
         self._check(self.lib.mil_pool_bwd(self.ctx, _ptr(feats), N, label, _ptr(dfeats_out), int(accumulate),

@@ -4,14 +4,40 @@
 
 #include <string>
 #include <vector>
+#include <mutex>
 #include <cstring>
 #include <cstdio>
 
 using namespace sl;
 
+// Work space of mil_pool_fwd_static: one copy per device, part of the loaded code object (nothing is allocated for
+// it at run time).  Host code never uses this name as an address: it asks the runtime for the device address once
+// per device (static_scratch below) and passes that pointer on.
+static __device__ __align__(256) unsigned char scratch[SLIDE_STATIC_POOL_BYTES];
+
 namespace {
 
 thread_local int g_last_hip = 0;
+
+// device address of `scratch` on the current device (looked up on the first call per device), or null with *err set
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+void* static_scratch(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
 
 enum KernelId {
   K_GEMM_NT = 0, K_GEMM_TN, K_ATTN_FWD, K_ATTN_BWD, K_LN_FWD, K_LN_BWD, K_COLSUM, K_POOL_FWD, K_POOL_BWD,
@@ -898,6 +924,37 @@ int mil_pool_bwd(slide_ctx* c, const void* feats, int64_t N, int32_t label, void
   if (rc) return rc;
   if (!dfeats_out) return SLIDE_EINVAL;
   return pool_bwd(c, y, feats, N, label, dfeats_out, accumulate, (hipStream_t)stream);
+}
+
+int mil_pool_fwd_static(const slide_ctx* c, const float* params, const void* feats, int64_t N, int32_t label,
+                        float* loss, float* logits, float* alpha, void* stream) {
+  if (!c || !params || !feats || N <= 0) return SLIDE_EINVAL;
+  if (label < 0 || label >= (c->C == 1 ? 2 : c->C)) return SLIDE_EINVAL;
+  if (N > SLIDE_STATIC_POOL_MAX_ROWS) return SLIDE_EARENA;
+  // the forward's work space: logits a[N], per-workgroup partials, scalars, the bf16 copy of [V;U], partial logits
+  size_t cur = 0;
+  auto take = [&](size_t bytes) { size_t o = cur; cur = align256(cur + bytes); return o; };
+  const int D = c->D, Mh = c->Mh, C = c->C;
+  const size_t o_a = take((size_t)N * 4), o_part = take((size_t)1024 * (2 + D) * 8);
+  const size_t o_scal = take((size_t)(4 + 2 * C + 3 * D) * 4), o_vub = take((size_t)2 * 2 * Mh * D * 2);
+  const size_t o_tmp = take((size_t)N * 4);
+  if (cur > SLIDE_STATIC_POOL_BYTES) return SLIDE_EARENA;
+  hipError_t e;
+  char* ws = (char*)static_scratch(&e);
+  if (!ws) { g_last_hip = (int)e; return SLIDE_EHIP; }
+  PoolArgs p{};
+  p.H = (const float*)feats; p.N = N; p.D = D; p.Mh = Mh; p.C = C; p.label = label;
+  p.VW = params + c->o_VW; p.Vb = params + c->o_Vb; p.UW = params + c->o_UW; p.Ub = params + c->o_Ub;
+  p.w = params + c->o_w; p.cW = params + c->o_cW; p.cb = params + c->o_cb;
+  p.a = (float*)(ws + o_a); p.part = (double*)(ws + o_part); p.scal = (float*)(ws + o_scal);
+  p.blocks = pool_blocks(N);
+  p.vub = ws + o_vub; p.use_mfma = c->use_mfma && c->dt == DT_BF16;
+  p.a_tmp = (float*)(ws + o_tmp);
+  p.loss = loss; p.logits = logits; p.alpha = alpha;
+  (void)hipGetLastError();
+  e = launch_pool_fwd(p, (hipStream_t)stream);
+  if (e != hipSuccess) { g_last_hip = (int)e; return SLIDE_EHIP; }
+  return SLIDE_OK;
 }
 
 int slide_step_fwd(slide_ctx* c, const void* pixels, int64_t N, int32_t label, float* loss, float* logits,
