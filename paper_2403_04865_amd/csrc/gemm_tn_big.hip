@@ -1,9 +1,9 @@
 // bf16 MFMA weight-gradient GEMM for gfx950, large-M variant: C[N1,N2] = sum_m A[m,N1]^T B[m,N2] (fp32 partials).
 //
 // Same machine balance as the activation GEMMs (what a compute unit can pull out of its L2 bounds the tile from
-// below), so the same shape: one persistent workgroup of 4 wavefronts per compute unit, a 256 x 192 output tile
-// (wavefront: 128 x 96), 64 rows of m per step, operands global -> registers -> LDS with the loads of A two steps
-// and of B one step ahead, MFMA / LDS / global instructions dealt out by hand.  What differs:
+// below), so the same tile area: one persistent workgroup of 4 wavefronts per compute unit, a 128 x 384 output tile
+// (wavefront: 64 x 192), 64 rows of m per step, operands global -> registers -> LDS with the loads of X two steps
+// and of Y one step ahead, MFMA / LDS / global instructions dealt out by hand.  What differs:
 //   * The contraction runs over the ROW index of both operands.  The 64-row slices go to LDS as they are
 //     (row-major, 16-byte stores) and the MFMA fragments, which need 8 consecutive contraction indices per
 //     lane, are read with LDS transpose reads (ds_read_b64_tr_b16: a group of 16 lanes addresses a 4-row x
@@ -12,7 +12,14 @@
 //     tile once, a second kernel adds the slabs in a fixed order (no atomics: results are run-to-run identical).
 //     All tiles of a slab run on ONE XCD at about the same time, so the slab's rows come from HBM once and the
 //     other tiles find them in that XCD's L2 (with tiles spread over XCDs the rows were fetched several times).
-//   * Either operand can play the 256-wide side ("X"), whichever leaves fewer empty tile columns; the output
+//   * The tile is as wide as the narrow operand of the encoder's weight gradients (384 columns, "Y"), so the wide
+//     operand ("X": 1152 or 1536 columns, four fifths of the bytes) is read by exactly one workgroup and streams
+//     from HBM once whatever the workgroups' relative progress; only the narrow operand is shared through L2, and
+//     its window (a few steps x 48 kB per slab) is a small part of the 4 MB.  With 256 x 192 tiles every row was
+//     shared by up to twelve workgroups that each run three steps of loads ahead: the windows of the slabs in
+//     flight on an XCD filled its L2, any drift between the sharers missed, and the kernel moved 1.7 x its operand
+//     bytes and ran at HBM speed.
+//   * Either operand can play the 128-tiled side, whichever leaves fewer empty tile columns; the output
 //     strides follow.  Column sums of A (the bias gradient) are taken from the registers of the loads.
 #include "slide_internal.h"
 
@@ -23,15 +30,16 @@ namespace sl {
 namespace {
 
 constexpr int NXCD = 8;
-constexpr int BX = 256, BY = 192, BK = 64, NTH = 256;
-constexpr int BYP = 256;                            // Y columns in LDS (lanes past the tile park duplicates behind it)
-// LDS row: 256 X columns, 256 Y columns, pad.  The pad makes the row stride 64 bytes modulo 256 (16 banks): a
+constexpr int BX = 128, BY = 384, BK = 64, NTH = 256;
+constexpr int XL = BX / 8 * BK / NTH, YG = BY / 128, YL = 4;   // 16-byte loads per thread and step: X 4, Y 3 x 4
+// LDS row: 128 X columns, 384 Y columns, pad.  The pad makes the row stride 64 bytes modulo 256 (16 banks): a
 // transpose read's group of 16 lanes touches 4 rows x 32 bytes, and the two groups that are served together sit 32
 // bytes apart, so with this stride their eight 32-byte pieces fall on eight different bank ranges (with a 16-byte
 // stride modulo 256 they overlapped: 58 % of the LDS cycles were bank-conflict cycles).
-constexpr int LDW = BX + BYP + 32;
+constexpr int LDW = BX + BY + 32;
 constexpr int STAGE = BK * LDW;                     // bf16 elements per LDS stage
-constexpr int WBM = 4, WBN = 3;
+constexpr int WBM = 2, WBN = 6;
+static_assert(XL == 4 && YG * 128 == BY && WBM == 2, "loader split, fragment schedule");
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
@@ -56,8 +64,8 @@ __device__ __forceinline__ bf16x8 frag_tr(const bf16* S, int c0, int k0, int lan
 __device__ __attribute__((aligned(16))) unsigned int g_zero_row[64];
 
 struct TnBig {
-  const bf16* X; long long ldx; int NX;   // 256-wide side
-  const bf16* Y; long long ldy; int NY;   // 192-wide side
+  const bf16* X; long long ldx; int NX;   // side tiled by 128
+  const bf16* Y; long long ldy; int NY;   // side tiled by 384
   long long M;
   float* part; long long sx, sy;          // partial of slab s: part[s * NX * NY + x * sx + y * sy]
   float* cs_part; int cs_on_x;            // column sums of X (1) or Y (0) per slab, [slabs][N of that side]; may be null
@@ -71,17 +79,16 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
   __shared__ __attribute__((aligned(16))) bf16 ring1[STAGE];
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
-  // loader: 32 lanes cover 512 contiguous bytes of one row; thread t takes 16-byte chunk t % 32 of rows t / 32 + 8 i.
-  // Y has 24 chunks per row: lanes 24..31 re-load chunk 23 and park it behind the tile (no divergent code).
-  const int lr = tid >> 5, lc = tid & 31;
-  const int lcy = lc < BY / 8 ? lc : BY / 8 - 1;
+  // loader: 16 lanes cover 256 contiguous bytes of one row; thread t takes 16-byte chunk t % 16 of rows t / 16 + 16 i
+  // of X, and the chunks t % 16 + 16 g (g < 3) of the same rows of Y
+  const int lr = tid >> 4, lc = tid & 15;
   const int xcd = blockIdx.x % NXCD, wg = blockIdx.x / NXCD, wgs = gridDim.x / NXCD;
   const int tiles = g.TX * g.TY;
   const int items = g.spx * tiles;
   long long per = (g.M + g.slabs - 1) / g.slabs;
   per = (per + 2 * BK - 1) / (2 * BK) * (2 * BK);          // whole double steps
 
-  u32x4 rx[2][8], ry[8];
+  u32x4 rx[2][XL], ry[YG * YL];
   for (int idx = wg; idx < items; idx += wgs) {            // uniform for the workgroup
     const int s = xcd * g.spx + idx / tiles;
     const int tile = idx % tiles;
@@ -89,36 +96,39 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
     const long long lo = (long long)s * per;
     const long long hi = lo + per < g.M ? lo + per : g.M;
     const int nk = lo < hi ? (int)((hi - lo + 2 * BK - 1) / (2 * BK)) * 2 : 0;
-    // this thread's columns exist?  (N % 8 == 0: a chunk is inside or outside as a whole)
-    const bool xok = x0 + lc * 8 < g.NX, yok = y0 + lcy * 8 < g.NY;
+    // (NX % 128 == 0 and NY % 384 == 0: every column of a tile exists)
     const bf16* zero = reinterpret_cast<const bf16*>(g_zero_row);
-    const bf16* xp = xok ? g.X + (x0 + lc * 8) : zero;
-    const bf16* yp = yok ? g.Y + (y0 + lcy * 8) : zero;
-    const long long ldx = xok ? g.ldx : 0, ldy = yok ? g.ldy : 0;
-    // rows of step kt this thread loads: lo + kt * 64 + lr + 8 i; rows past the slab's end read the zero row
+    const bf16* xp = g.X + (x0 + lc * 8);
+    const bf16* yp = g.Y + (y0 + lc * 8);
+    const long long ldx = g.ldx, ldy = g.ldy;
+    // rows of step kt this thread loads: lo + kt * 64 + lr + 16 i; rows past the slab's end read the zero row
     auto issue_x = [&](auto slot, int kt) {
       constexpr int S = decltype(slot)::value;
       long long m = lo + (long long)kt * BK + lr;
       const bf16* p = xp + m * ldx;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) rx[S][i] = ldg16(m + 8 * i < hi ? p + 8 * i * ldx : zero);
+      for (int i = 0; i < XL; ++i) rx[S][i] = ldg16(m + 16 * i < hi ? p + 16 * i * ldx : zero);
     };
     auto issue_y = [&](int kt) {
       long long m = lo + (long long)kt * BK + lr;
       const bf16* p = yp + m * ldy;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) ry[i] = ldg16(m + 8 * i < hi ? p + 8 * i * ldy : zero);
+      for (int q = 0; q < YG; ++q)
+#pragma unroll
+        for (int i = 0; i < YL; ++i) ry[q * YL + i] = ldg16(m + 16 * i < hi ? p + 16 * i * ldy + q * 128 : zero);
     };
     const bool cs_x = g.cs_part != nullptr && g.cs_on_x && y0 == 0;
     const bool cs_y = g.cs_part != nullptr && !g.cs_on_x && x0 == 0;
-    float cs[8];
+    float cs[YG][8];   // column sums of this thread's chunk(s): X uses cs[0]
 #pragma unroll
-    for (int c = 0; c < 8; ++c) cs[c] = 0.f;
-    auto add_cs_row = [&](const u32x4& v) {
+    for (int q = 0; q < YG; ++q)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) cs[q][c] = 0.f;
+    auto add_cs_row = [&](const u32x4& v, float (&a)[8]) {
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        cs[2 * w] += __uint_as_float(v[w] << 16);
-        cs[2 * w + 1] += __uint_as_float(v[w] & 0xffff0000u);
+        a[2 * w] += __uint_as_float(v[w] << 16);
+        a[2 * w + 1] += __uint_as_float(v[w] & 0xffff0000u);
       }
     };
     const int sx_off = lr * LDW + lc * 8, sy_off = lr * LDW + BX + lc * 8;
@@ -127,12 +137,17 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
       constexpr int CSM = decltype(csm)::value;
       bf16* st = S ? ring1 : ring0;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (CSM == 1) add_cs_row(rx[S][i]);
-        if (CSM == 2) add_cs_row(ry[i]);
-        *reinterpret_cast<u32x4*>(st + sx_off + 8 * i * LDW) = rx[S][i];
-        *reinterpret_cast<u32x4*>(st + sy_off + 8 * i * LDW) = ry[i];
+      for (int i = 0; i < XL; ++i) {
+        if (CSM == 1) add_cs_row(rx[S][i], cs[0]);
+        *reinterpret_cast<u32x4*>(st + sx_off + 16 * i * LDW) = rx[S][i];
       }
+#pragma unroll
+      for (int q = 0; q < YG; ++q)
+#pragma unroll
+        for (int i = 0; i < YL; ++i) {
+          if (CSM == 2) add_cs_row(ry[q * YL + i], cs[q]);
+          *reinterpret_cast<u32x4*>(st + sy_off + q * 128 + 16 * i * LDW) = ry[q * YL + i];
+        }
     };
 
     f32x16 acc[WBM][WBN];
@@ -152,12 +167,15 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
     // 3: by then this stage has been read and the next one is written, so the fragments of the next step's
     // slice 0 are fetched under the MFMAs of slice 3 and no wavefront starts a step with an empty MFMA pipe.
     const int xc = wm * (WBM * 32), yc = BX + wn * (WBN * 32);
-    bf16x8 fx[2][WBM], fy[2][WBN];
+    // One set of fragments: within a slice the MFMAs run over (i, j) with i outermost, so fx[0] is free after the first
+    // six MFMAs, fy[j] after MFMA (1, j) and fx[1] after the last; each is re-read for the next slice right behind its
+    // last use, six or more MFMAs before its next one.
+    bf16x8 fx[WBM], fy[WBN];
     auto first_frags = [&]() {   // slice 0 of stage 0
 #pragma unroll
-      for (int i = 0; i < WBM; ++i) fx[0][i] = frag_tr(ring0, xc + i * 32, 0, lane);
+      for (int i = 0; i < WBM; ++i) fx[i] = frag_tr(ring0, xc + i * 32, 0, lane);
 #pragma unroll
-      for (int j = 0; j < WBN; ++j) fy[0][j] = frag_tr(ring0, yc + j * 32, 0, lane);
+      for (int j = 0; j < WBN; ++j) fy[j] = frag_tr(ring0, yc + j * 32, 0, lane);
     };
     auto step = [&](auto slot, int kt, auto csm) {
       constexpr int S = decltype(slot)::value;
@@ -173,32 +191,32 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
         constexpr int PER = WBM * WBN;
         const int ks = n / PER, t = n % PER, i = t / WBN, j = t % WBN;
         if (n == 3 * PER) __syncthreads();
-        if (t < WBM + WBN) {   // fragments of slice ks + 1, or of the next stage's slice 0
+        acc[i][j] = LANE_IS_X ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[j], fx[i], acc[i][j], 0, 0, 0)
+                              : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[i], fy[j], acc[i][j], 0, 0, 0);
+        {   // fragments of slice ks + 1, or of the next stage's slice 0
           const bf16* src = ks < 3 ? st : sn;
           const int kk = ks < 3 ? (ks + 1) * 16 : 0;
-          if (t < WBM) fx[(ks + 1) & 1][t] = frag_tr(src, xc + t * 32, kk, lane);
-          else fy[(ks + 1) & 1][t - WBM] = frag_tr(src, yc + (t - WBM) * 32, kk, lane);
+          if (t == WBN - 1) fx[0] = frag_tr(src, xc, kk, lane);
+          if (t >= WBN) fy[t - WBN] = frag_tr(src, yc + (t - WBN) * 32, kk, lane);
+          if (t == PER - 1) fx[1] = frag_tr(src, xc + 32, kk, lane);
         }
-        acc[i][j] = LANE_IS_X
-                        ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fy[ks & 1][j], fx[ks & 1][i], acc[i][j], 0, 0, 0)
-                        : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[ks & 1][i], fy[ks & 1][j], acc[i][j], 0, 0, 0);
-        // pieces: 0..7 store X rows; 8..15 column sums; 16..23 store Y rows; 24..31 load Y (needed again 40
-        // pieces later); 32..39 load X (needed two steps later)
-        if (n < 8) {
-          *reinterpret_cast<u32x4*>(sn + sx_off + 8 * n * LDW) = rx[N][n];
-        } else if (n < 16) {
-          if (CSM == 1) add_cs_row(rx[N][n - 8]);
-          if (CSM == 2) add_cs_row(ry[n - 8]);
-          if (n == 14) { my = lo + (long long)(kt + 2) * BK + lr; py = yp + my * ldy; }
-          if (n == 15) { mx = lo + (long long)(kt + 3) * BK + lr; px = xp + mx * ldx; }
-        } else if (n < 24) {
-          *reinterpret_cast<u32x4*>(sn + sy_off + 8 * (n - 16) * LDW) = ry[n - 16];
-        } else if (n < 32) {
-          int r = n - 24;
-          ry[r] = ldg16(my + 8 * r < hi ? py + 8 * r * ldy : zero);
-        } else if (n < 40) {
-          int r = n - 32;
-          rx[N][r] = ldg16(mx + 8 * r < hi ? px + 8 * r * ldx : zero);
+        // pieces: 0..3 store X rows (and their column sums); 4..15 store Y rows (and theirs); 16..27 load Y
+        // (needed again 36 pieces later); 28..31 load X (needed two steps later)
+        if (n < XL) {
+          if (CSM == 1) add_cs_row(rx[N][n], cs[0]);
+          *reinterpret_cast<u32x4*>(sn + sx_off + 16 * n * LDW) = rx[N][n];
+        } else if (n < XL + YG * YL) {
+          const int r = n - XL, q = r / YL, ri = r % YL;
+          if (CSM == 2) add_cs_row(ry[r], cs[q]);
+          *reinterpret_cast<u32x4*>(sn + sy_off + q * 128 + 16 * ri * LDW) = ry[r];
+          if (n == XL + YG * YL - 2) { my = lo + (long long)(kt + 2) * BK + lr; py = yp + my * ldy; }
+          if (n == XL + YG * YL - 1) { mx = lo + (long long)(kt + 3) * BK + lr; px = xp + mx * ldx; }
+        } else if (n < XL + 2 * YG * YL) {
+          const int r = n - XL - YG * YL, q = r / YL, ri = r % YL;
+          ry[r] = ldg16(my + 16 * ri < hi ? py + 16 * ri * ldy + q * 128 : zero);
+        } else if (n < 2 * XL + 2 * YG * YL) {
+          const int r = n - XL - 2 * YG * YL;
+          rx[N][r] = ldg16(mx + 16 * r < hi ? px + 16 * r * ldx : zero);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -226,22 +244,28 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
     }
     // (after the last step's barrier nothing reads stage 1 any more; stage 0 is still being read)
 
-    // column sums: the 8 threads lr = 0..7 that share a 16-byte chunk -> one value per column
+    // column sums: the 16 threads lr = 0..15 that share a 16-byte chunk -> one value per column
     if (cs_x || cs_y) {
-      float* red = reinterpret_cast<float*>(ring1);   // [8][256]
-      bool mine = cs_x || lc < BY / 8;                // lanes 24..31 hold duplicates of Y chunks
-      if (mine) {
+      float* red = reinterpret_cast<float*>(ring1);   // [16][BX] or [16][BY]
+      const int ncol = cs_x ? BX : BY;
+      if (cs_x) {
 #pragma unroll
-        for (int c = 0; c < 8; ++c) red[lr * 256 + lc * 8 + c] = cs[c];
+        for (int c = 0; c < 8; ++c) red[lr * BX + lc * 8 + c] = cs[0][c];
+      } else {
+#pragma unroll
+        for (int q = 0; q < YG; ++q)
+#pragma unroll
+          for (int c = 0; c < 8; ++c) red[lr * BY + (lc + 16 * q) * 8 + c] = cs[q][c];
       }
       __syncthreads();
-      int ncol = cs_x ? BX : BY, c0 = cs_x ? x0 : y0, nn = cs_x ? g.NX : g.NY;
-      if (tid < ncol && c0 + tid < nn) {
-        float a = 0.f;
+      const int c0 = cs_x ? x0 : y0, nn = cs_x ? g.NX : g.NY;
+      for (int col = tid; col < ncol; col += NTH)
+        if (c0 + col < nn) {
+          float a = 0.f;
 #pragma unroll
-        for (int m = 0; m < 8; ++m) a += red[m * 256 + tid];
-        g.cs_part[(size_t)s * nn + c0 + tid] = a;
-      }
+          for (int m = 0; m < 16; ++m) a += red[m * ncol + col];
+          g.cs_part[(size_t)s * nn + c0 + col] = a;
+        }
       __syncthreads();
     }
 
@@ -262,8 +286,14 @@ __global__ void __launch_bounds__(NTH) gemm_tn_big_k(TnBig g) {
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-long long padded(int n1, int n2) {   // cells of the tile grid with n1 on the 256 side
-  return (long long)((n1 + BX - 1) / BX * BX) * ((n2 + BY - 1) / BY * BY);
+// A on the side tiled by 128 and B on the side tiled by 384, or the other way round: whichever way the tiles cover
+// the output exactly, and of two such ways the one with fewer tiles along the 384 side (the operand on the 128 side
+// is then shared by fewer workgroups; with one tile along the 384 side it is read by exactly one)
+bool tn_fits(int nx, int ny) { return nx % BX == 0 && ny % BY == 0; }
+bool tn_a_is_x(const GemmTN& g) {
+  bool ax = tn_fits(g.N1, g.N2), bx = tn_fits(g.N2, g.N1);
+  if (ax && bx) return g.N2 <= g.N1;
+  return ax;
 }
 
 }  // namespace
@@ -271,19 +301,21 @@ long long padded(int n1, int n2) {   // cells of the tile grid with n1 on the 25
 // Shapes this kernel takes: identity row maps, enough rows.  Returns the number of slabs it will use (0: not taken).
 int gemm_tn_big_slabs(const GemmTN& g, int max_slabs) {
   if (g.amap.g2 != 0 || g.bmap.g2 != 0 || g.M < 65536) return 0;
-  if (g.N1 % 8 || g.N2 % 8 || g.lda % 8 || g.ldb % 8 || !aligned16(g.A) || !aligned16(g.B)) return 0;
+  if (g.lda % 8 || g.ldb % 8 || !aligned16(g.A) || !aligned16(g.B)) return 0;
   if ((long long)g.N1 * g.N2 >= (1LL << 31)) return 0;
-  bool a_is_x = padded(g.N1, g.N2) <= padded(g.N2, g.N1);
+  // the tiles must cover the output exactly, one way round or the other (no column is masked in the kernel)
+  if (!tn_fits(g.N1, g.N2) && !tn_fits(g.N2, g.N1)) return 0;
+  bool a_is_x = tn_a_is_x(g);
   int nx = a_is_x ? g.N1 : g.N2, ny = a_is_x ? g.N2 : g.N1;
   int tiles = ((nx + BX - 1) / BX) * ((ny + BY - 1) / BY);
-  // per XCD: spx slabs x tiles items over 32 workgroups; take the count whose last round is fullest (ties: more
-  // slabs, i.e. shorter items)
+  // per XCD: spx slabs x tiles items over 32 workgroups; more slabs while that fills the last round of workgroups
+  // noticeably better (every slab costs one partial result to write and to add)
   int spx = 1;
   double best = 0.0;
-  for (int c = 1; c <= 8 && 8 * c <= max_slabs; ++c) {
+  for (int c = 1; c <= 32 && 8 * c <= max_slabs; ++c) {
     int items = c * tiles, rounds = (items + 31) / 32;
     double fill = (double)items / (rounds * 32.0);
-    if (c >= 3 ? fill >= best : fill > best + 0.2) { best = fill; spx = c; }   // fewer than 3 only if much fuller
+    if (fill > best + 0.04 || (c <= 3 && fill >= best)) { best = fill; spx = c; }
   }
   return 8 * spx;
 }
@@ -299,7 +331,7 @@ hipError_t launch_gemm_tn_big(const GemmTN& g, hipStream_t s) {
     cus = prop.multiProcessorCount / NXCD * NXCD;
     if (cus < NXCD) cus = NXCD;
   }
-  bool a_is_x = padded(g.N1, g.N2) <= padded(g.N2, g.N1);
+  bool a_is_x = tn_a_is_x(g);
   TnBig t{};
   t.M = g.M; t.part = g.part; t.cs_part = g.cs_part; t.slabs = g.slabs; t.spx = g.slabs / NXCD;
   if (a_is_x) {

@@ -279,8 +279,9 @@ void colsum(Run& r, int elem, const void* A, long long lda, RowMap map, long lon
 
 // dW (+)= A^T B through split partials; optionally also db (+)= column sums of A
 void gemm_tn(Run& r, const void* A, long long lda, RowMap amap, const void* B, long long ldb, RowMap bmap, long long M,
-             int N1, int N2, float* part, float* out, int accumulate, int dt_override = -1, float* bias_out = nullptr,
-             float* cpart = nullptr, float* out2 = nullptr, float* bias_out2 = nullptr) {
+             int N1, int N2, float* part, size_t part_floats, float* out, int accumulate, int dt_override = -1,
+             float* bias_out = nullptr, float* cpart = nullptr, float* out2 = nullptr, float* bias_out2 = nullptr) {
+  // part: room for part_floats floats of slab partials (at least 64 results).
   // out2 / bias_out2: the result rows N1/2 .. N1-1 (and their column sums) belong to a second tensor
   GemmTN g;
   int dt = dt_override >= 0 ? dt_override : r.c->dt;
@@ -288,7 +289,8 @@ void gemm_tn(Run& r, const void* A, long long lda, RowMap amap, const void* B, l
   g.part = part;
   g.cs_part = nullptr;
   g.big = 0;
-  int bs = (dt == DT_BF16 && r.c->use_mfma) ? gemm_tn_big_slabs(g, 64) : 0;
+  size_t fit = part_floats / ((size_t)N1 * N2);
+  int bs = (dt == DT_BF16 && r.c->use_mfma) ? gemm_tn_big_slabs(g, fit > 256 ? 256 : (int)fit) : 0;
   if (bs) { g.slabs = bs; g.big = 1; }
   else g.slabs = gemm_tn_pick_slabs(M, N1, N2, 32);
   bool fused = bias_out && gemm_tn_fuses_colsum(dt, g, r.c->use_mfma);
@@ -554,6 +556,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
   bool dual = rs != e;
   int rs_elem = rs == 4 ? DT_F32 : DT_BF16;
   float* wpart = (float*)(ar + y.w_wpart);
+  const size_t wcap = (size_t)64 * c->max_w;   // floats of room behind wpart (make_layout)
   float* cpart = (float*)(ar + y.w_cpart);
   float* lnpart = (float*)(ar + y.w_lnpart);
   char *dxA = ar + y.e_dxA, *dxB = ar + y.e_dxB, *dxAt = ar + y.e_dxAt, *dxBt = ar + y.e_dxBt;
@@ -591,8 +594,8 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
         g.epi = EPI_DGELU; g.pre = m; g.ldpre = F; g.out = dm; g.ldc = F;
         gemm_nt(r, g);
       }
-      gemm_tn(r, dxAt, TD, id, a, F, id, n, D, F, wpart, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
-      gemm_tn(r, dm, F, id, u2, D, id, n, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
+      gemm_tn(r, dxAt, TD, id, a, F, id, n, D, F, wpart, wcap, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
+      gemm_tn(r, dm, F, id, u2, D, id, n, F, D, wpart, wcap, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
       {
         GemmNT g{};
         g.A = dm; g.lda = F; g.B = weight_t(c, wi + 2); g.ldb = F; g.M = n; g.N = D; g.K = F;
@@ -600,7 +603,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
         gemm_nt(r, g);
       }
       ln_bwd(r, xmid, TD, du, D, o.ln2g, o.ln2b, dxA, dxB, dxBt, TD, n, lnpart, accumulate);
-      gemm_tn(r, dxBt, TD, id, O, TD, id, n, D, D, wpart, G + o.projW, accumulate, -1, G + o.projb, cpart);
+      gemm_tn(r, dxBt, TD, id, O, TD, id, n, D, D, wpart, wcap, G + o.projW, accumulate, -1, G + o.projb, cpart);
       {
         GemmNT g{};
         g.A = dxBt; g.lda = TD; g.B = weight_t(c, wi + 1); g.ldb = D; g.M = n; g.N = D; g.K = D;
@@ -609,7 +612,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       }
       launch(r, K_ATTN_BWD, 10.0 * n * c->H * (double)T * c->dh, (double)M * 7 * D * e,
              [&] { return launch_attn_bwd(dt, qkv, O, lse, du, dqkv, n, T, c->H, c->dh, c->use_mfma, s, true, (float*)(ar + y.e_dl)); });
-      gemm_tn(r, dqkv, 3 * D, id, u1, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
+      gemm_tn(r, dqkv, 3 * D, id, u1, D, id, M, 3 * D, D, wpart, wcap, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
       {
         GemmNT g{};
         g.A = dqkv; g.lda = 3 * D; g.B = weight_t(c, wi + 0); g.ldb = 3 * D; g.M = M; g.N = D; g.K = 3 * D;
@@ -626,7 +629,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       g.epi = EPI_DGELU; g.pre = m; g.ldpre = F; g.out = dm; g.ldc = F;
       gemm_nt(r, g);
     }
-    gemm_tn(r, dxAt, D, id, a, F, id, M, D, F, wpart, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
+    gemm_tn(r, dxAt, D, id, a, F, id, M, D, F, wpart, wcap, G + o.fc2W, accumulate, -1, G + o.fc2b, cpart);
     {
       GemmNT g{};
       g.A = dm; g.lda = F; g.B = weight_t(c, wi + 2); g.ldb = F; g.M = M; g.N = D; g.K = F;
@@ -634,9 +637,9 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       gemm_nt(r, g);
     }
     ln_bwd(r, xmid, D, du, D, o.ln2g, o.ln2b, dxA, dxB, dxBt, D, M, lnpart, accumulate);
-    gemm_tn(r, dm, F, id, u2, D, id, M, F, D, wpart, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
+    gemm_tn(r, dm, F, id, u2, D, id, M, F, D, wpart, wcap, G + o.fc1W, accumulate, -1, G + o.fc1b, cpart);
     // ---- attention half: x_mid = x_in + attn(LN1(x_in)) Wo^T + bo
-    gemm_tn(r, dxBt, D, id, O, D, id, M, D, D, wpart, G + o.projW, accumulate, -1, G + o.projb, cpart);
+    gemm_tn(r, dxBt, D, id, O, D, id, M, D, D, wpart, wcap, G + o.projW, accumulate, -1, G + o.projb, cpart);
     {
       GemmNT g{};
       g.A = dxBt; g.lda = D; g.B = weight_t(c, wi + 1); g.ldb = D; g.M = M; g.N = D; g.K = D;
@@ -652,7 +655,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       gemm_nt(r, g);
     }
     ln_bwd(r, xin, D, du, D, o.ln1g, o.ln1b, dxB, dxA, dxAt, D, M, lnpart, accumulate);
-    gemm_tn(r, dqkv, 3 * D, id, u1, D, id, M, 3 * D, D, wpart, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
+    gemm_tn(r, dqkv, 3 * D, id, u1, D, id, M, 3 * D, D, wpart, wcap, G + o.qkvW, accumulate, -1, G + o.qkvb, cpart);
   }
   // ---- token assembly: x0[n,0] = cls + pos[0]; x0[n,1+j] = patch_j W_pe^T + b_pe + pos[1+j]
   {
@@ -673,7 +676,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
   RowMap pm{c->g2, T};
   long long Mp = n * c->g2;
   // all token rows: the CLS rows meet rows of zeros in the patch matrix
-  gemm_tn(r, dxAt, D, id, ar + y.e_patches, c->Kp, id, M, D, c->Kp, wpart, G + c->o_peW, accumulate);
+  gemm_tn(r, dxAt, D, id, ar + y.e_patches, c->Kp, id, M, D, c->Kp, wpart, wcap, G + c->o_peW, accumulate);
   if (pixel_grad) {
     GemmNT g{};
     g.A = dxAt; g.lda = D; g.amap = pm; g.B = weight_t(c, 0); g.ldb = D; g.M = Mp; g.N = c->Kp; g.K = D;
@@ -722,6 +725,9 @@ int pool_bwd(slide_ctx* c, const Layout& y, const void* feats, long long N, int 
   char* Dp = ar + y.p_Dp;
   RowMap id{0, 0};
   float* tn = (float*)(ar + y.p_tn);
+  // room for 64 results of [2 M_h, D]; the column-sum partials behind it are laid out for 64 slabs, so a
+  // weight gradient of half the gate units must not take more either
+  const size_t tncap = (size_t)64 * (2 * Mh >= 256 ? 256 : 2 * Mh) * D;
   float* cs = (float*)(ar + y.p_cs);
   // the matrix-core path keeps [dpV dpU] and a feature copy as bf16 in the room of the fp32 [N, 3 Mh] array; db_V and
   // db_U come out of the weight-gradient GEMM as column sums of its first operand
@@ -739,14 +745,14 @@ int pool_bwd(slide_ctx* c, const Layout& y, const void* feats, long long N, int 
                                       accumulate, s);
       });
       const size_t ow = (size_t)h * MHK * D;
-      gemm_tn(r, Dp + (size_t)h * N * 2 * MHK * 2, 2 * MHK, id, Hb16, D, id, N, 2 * MHK, D, tn, c->grads + c->o_VW + ow,
+      gemm_tn(r, Dp + (size_t)h * N * 2 * MHK * 2, 2 * MHK, id, Hb16, D, id, N, 2 * MHK, D, tn, tncap, c->grads + c->o_VW + ow,
               accumulate, DT_BF16, c->grads + c->o_Vb + h * MHK, cs, c->grads + c->o_UW + ow, c->grads + c->o_Ub + h * MHK);
     }
     return finish(r);
   }
   launch(r, K_POOL_BWD, 8.0 * N * D * Mh, 2.0 * N * D * 4, [&] { return launch_pool_bwd_rows(p, (float*)Dp, s); });
-  gemm_tn(r, Dp, 3 * Mh, id, feats, D, id, N, Mh, D, tn, c->grads + c->o_VW, accumulate, DT_F32);
-  gemm_tn(r, Dp + (size_t)Mh * 4, 3 * Mh, id, feats, D, id, N, Mh, D, tn, c->grads + c->o_UW, accumulate, DT_F32);
+  gemm_tn(r, Dp, 3 * Mh, id, feats, D, id, N, Mh, D, tn, tncap, c->grads + c->o_VW, accumulate, DT_F32);
+  gemm_tn(r, Dp + (size_t)Mh * 4, 3 * Mh, id, feats, D, id, N, Mh, D, tn, tncap, c->grads + c->o_UW, accumulate, DT_F32);
   int slabs = colsum_slabs(N);
   launch(r, K_COLSUM, 0, (double)N * 3 * Mh * 4,
          [&] { return launch_colsum_part(DT_F32, Dp, 3 * Mh, id, N, 3 * Mh, cs, slabs, s); });
