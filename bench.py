@@ -106,11 +106,14 @@ def pool_sweep(a):
             res[which + "_us"] = round(ms * 1e3, 1)
             res[which + "_GBps"] = round(alg / (ms * 1e-3) / 1e9, 1)
             res[which + "_frac_hbm"] = round(alg / (ms * 1e-3) / PEAK["hbm"], 4)
+            # the same time against half the bytes: what the fraction would be if the features were counted as bf16
+            res[which + "_frac_hbm_if_bf16_features"] = round(0.5 * alg / (ms * 1e-3) / PEAK["hbm"], 4)
         rows.append(res)
         print(json.dumps(res), flush=True)
         del arena, H, G
         torch.cuda.empty_cache()
-    print(json.dumps({"pool_sweep": rows, "D": cfg.dim, "mil_hidden": cfg.mil_hidden, "peak_GBps": PEAK["hbm"] / 1e9}))
+    print(json.dumps({"pool_sweep": rows, "D": cfg.dim, "mil_hidden": cfg.mil_hidden, "peak_GBps": PEAK["hbm"] / 1e9,
+                      "bytes_basis": "features and feature gradients are float32: forward N*D*4, backward 2*N*D*4 bytes"}))
 
 
 def adamw_bench(a):
@@ -162,15 +165,36 @@ def calib_copy(a):
     print(json.dumps({"calib_copy_bytes": n, "launches": 4}))
 
 
-def load_traffic(workload, kernel):
+def load_traffic(workload, kernel=None):
     """HBM bytes per launch of `kernel` measured with rocprofv3 --pmc (profiles/traffic_<workload>.json, written by
-    `python -m paper_2403_04865_amd.pmc_traffic`); None when no measurement of this workload is stored."""
+    `python -m paper_2403_04865_amd.pmc_traffic`; a STORED figure of an earlier run, not measured by this one: the
+    file names the commit it was measured at); None when no measurement of this workload is stored.  Without
+    `kernel`: the whole file."""
     path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
     if not os.path.exists(path):
         return None
     with open(path) as f:
         d = json.load(f)
-    return d.get(kernel)
+    return d if kernel is None else d.get(kernel)
+
+
+HBM_BOUND = ("ln_fwd", "ln_bwd", "pool_fwd", "pool_bwd", "colsum", "elementwise")
+
+
+def roofline_of(name, ms, n, flops, nbytes, step_ms, traffic):
+    """One family's figures from its HIP-event times: contractions against the dense bf16 MFMA peak, streaming kernels
+    (algorithmic bytes) against the HBM peak."""
+    hbm = name in HBM_BOUND
+    if hbm:
+        achieved = (nbytes / (ms * 1e-3)) / 1e9 if ms > 0 else 0.0
+        peak, unit = PEAK["hbm"] / 1e9, "GB/s"
+    else:
+        achieved = (flops / (ms * 1e-3)) / 1e12 if ms > 0 else 0.0
+        peak, unit = PEAK["mfma_bf16"] / 1e12, "TFLOP/s"
+    return {"bound": "hbm" if hbm else "mfma", "kernel": name, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+            "frac": round(achieved / peak, 4), "traffic": None if traffic is None else traffic["hbm_bytes_per_launch"],
+            "algorithmic_bytes_per_launch": round(nbytes / max(n, 1)), "launches": n,
+            "avg_launch_ms": round(ms / max(n, 1), 4), "share_of_step": round(ms / step_ms, 4) if step_ms > 0 else None}
 
 
 def main():
@@ -276,20 +300,25 @@ def main():
     tiles_per_s = N * a.steps / dt
     mflops = model_flops_per_tile(cfg) - pruned_flops_per_tile(cfg)   # the bf16 path prunes the last block
     mfu = tiles_per_s * mflops / PEAK["mfma_bf16"]
-    tr = load_traffic(a.workload, a.prof_kernel) if not (a.tiles or a.chunk_tiles) else None
-    hbm_bound = a.prof_kernel in ("ln_fwd", "ln_bwd", "pool_fwd", "pool_bwd", "colsum", "elementwise")
-    if hbm_bound:   # streaming kernels: algorithmic bytes over time against the HBM peak
-        achieved = (k_bytes / (k_ms * 1e-3)) / 1e9 if k_ms > 0 else 0.0
-        peak, unit = PEAK["hbm"] / 1e9, "GB/s"
-    else:           # contractions: FLOP/s of the kernel family against the dense bf16 MFMA peak
-        achieved = (k_flops / (k_ms * 1e-3)) / 1e12 if k_ms > 0 else 0.0
-        peak, unit = PEAK["mfma_bf16"] / 1e12, "TFLOP/s"
-    roof = {"bound": "hbm" if hbm_bound else "mfma", "kernel": a.prof_kernel, "achieved": round(achieved, 2), "peak": peak,
-            "unit": unit, "frac": round(achieved / peak, 4),
-            "traffic": None if tr is None else tr["hbm_bytes_per_launch"],
-            "algorithmic_bytes_per_launch": round(k_bytes / max(k_n, 1)),
-            "launches": k_n, "avg_launch_ms": round(k_ms / max(k_n, 1), 4),
-            "share_of_step": round(k_ms / (dt * 1e3), 4)}
+    stored = load_traffic(a.workload) if not (a.tiles or a.chunk_tiles) else None
+    roof = roofline_of(a.prof_kernel, k_ms, k_n, k_flops, k_bytes, dt * 1e3, (stored or {}).get(a.prof_kernel))
+    # every family from one more (untimed) step with all launches bracketed by events
+    names = lib.kernel_names()
+    lib.slide_prof_begin(-1)
+    t1 = time.perf_counter()
+    one_step()
+    torch.cuda.synchronize()
+    all_ms = (time.perf_counter() - t1) * 1e3
+    lib.slide_prof_end()
+    roof_all = []
+    for i, nm in enumerate(names):
+        f_ms, f_n, f_fl, f_by = lib.slide_prof_family(i)
+        if f_n:
+            roof_all.append(roofline_of(nm, f_ms, f_n, f_fl, f_by, all_ms, (stored or {}).get(nm)))
+    roof_all.sort(key=lambda r: -(r["share_of_step"] or 0))
+    traffic_src = None if stored is None else {
+        "kind": "stored", "file": f"profiles/traffic_{a.workload}.json", "measured_at_commit": stored.get("_commit"),
+        "note": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command, scaled by a copy kernel"}
 
     cpu = None
     if not a.no_cpu_baseline:
@@ -320,6 +349,8 @@ def main():
                    "arena_gb": round(nbytes / 1e9, 2), "peak_alloc_gb_of_288": round(peak_alloc, 2),
                    "loss": float(loss.item()), "input_gen_s": round(gen_s, 1)},
         "roofline": roof,
+        "roofline_all": roof_all,
+        "traffic_source": traffic_src,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

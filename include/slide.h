@@ -3,12 +3,11 @@
  * pathology slide on one MI355X (gfx950).
  *
  * The step is the one-device counterpart of the scheme in the paper's Method
- * section and appendix listing: every tile goes through a tile encoder
- * (`features = encoder(batch)`), the feature matrix goes through a gated-attention
- * MIL aggregator and a slide-level criterion (`aggregator(allfeatures)`,
- * `criterion(output, label)`), the loss is back-propagated to the feature matrix
- * (`allfeatures.grad`) and from there through the encoder (the pseudo-loss
- * sum f*g, whose gradient is J^T g; no rank factor on one device).
+ * section and appendix listing: every tile goes through a tile encoder, the
+ * feature matrix goes through a gated-attention MIL aggregator and a slide-level
+ * criterion, the loss is back-propagated to the feature matrix and from there
+ * through the encoder (the pseudo-loss of the Method section, whose gradient is
+ * J^T g; no rank factor on one device).
  *
  * Conventions common to every call
  *  - All data pointers are DEVICE pointers unless a comment says "host".
@@ -57,7 +56,7 @@ typedef struct slide_config {
   int32_t dtype;       /* 0 = float32 path, 1 = bfloat16 storage / float32 accumulate */
   int32_t recompute;   /* 0 = keep every block's activations; 1 = keep block inputs, re-run blocks in backward */
   float   ln_eps;      /* LayerNorm epsilon (1e-6) */
-  int32_t want_pixel_grad; /* reserved; pixel gradients are requested per call by a non-null pointer */
+  int32_t reserved;    /* must be 0 (pixel gradients are requested per call by a non-null pointer) */
 } slide_config;
 
 typedef struct slide_ctx slide_ctx;
@@ -96,15 +95,15 @@ size_t slide_pool_arena_bytes(const slide_ctx* ctx, int64_t N);
 int  slide_bind(slide_ctx* ctx, const float* params_fp32, float* grads_fp32,
                 void* arena, size_t arena_bytes);
 
-/* Tile encoder forward (paper listing: `features = encoder(batch)`).
+/* Tile encoder forward (paper, appendix listing: the encoder ranks' forward step; Method, first paragraph).
  * pixels: [n_tiles,3,S,S] of T, planar, already normalised.  feats_out: [n_tiles,D] float32.
  * save_for_bwd != 0 keeps this call's activations in the arena for one
  * encoder_bwd_tiles on the same tiles; 0 keeps nothing (feature extraction). */
 int  encoder_fwd_tiles(slide_ctx* ctx, const void* pixels, int64_t n_tiles,
                        void* feats_out, int save_for_bwd, void* hip_stream);
 
-/* Encoder backward seeded with the feature-gradient rows of these tiles (paper
- * Method: pseudo-loss l_e = sum f*g; listing: `encoder_loss.backward()`), without the
+/* Encoder backward seeded with the feature-gradient rows of these tiles (paper, Method:
+ * pseudo-loss equation; appendix listing: the encoder ranks' backward step), without the
  * rank factor.  dfeats: [n_tiles,D] float32.  Encoder slices of grads_fp32 are overwritten
  * (accumulate == 0) or added to (accumulate != 0; chunk gradients SUM to the slide
  * gradient).  pixel_grad_or_null: [n_tiles,3,S,S] of T or NULL.
@@ -112,8 +111,8 @@ int  encoder_fwd_tiles(slide_ctx* ctx, const void* pixels, int64_t n_tiles,
 int  encoder_bwd_tiles(slide_ctx* ctx, const void* dfeats, int64_t n_tiles, int accumulate,
                        void* pixel_grad_or_null, void* hip_stream);
 
-/* Gated-attention MIL pooling, class logits and slide loss (paper listing:
- * `output = aggregator(allfeatures); aggregator_loss = criterion(output, label)`).
+/* Gated-attention MIL pooling, class logits and slide loss (paper, appendix listing: the
+ * aggregator rank's forward and criterion; Method, paragraph on the aggregator).
  * feats: [N,D] float32.  label: 0/1 for C == 1, class index for C > 1.
  * Outputs (device, float32; any may be NULL): loss[1], logits[C], alpha[N] (attention weights). */
 int  mil_pool_fwd(slide_ctx* ctx, const void* feats, int64_t N, int32_t label,
@@ -133,7 +132,8 @@ int  mil_pool_fwd(slide_ctx* ctx, const void* feats, int64_t N, int32_t label,
 int  mil_pool_fwd_static(const slide_ctx* ctx, const float* params_fp32, const void* feats, int64_t N, int32_t label,
                          float* loss, float* logits, float* alpha, void* hip_stream);
 
-/* Aggregator backward (paper listing: `aggregator_loss.backward(); grads = allfeatures.grad`).
+/* Aggregator backward (paper, appendix listing: the aggregator rank's backward step, which yields
+ * the gradient of the loss with respect to the gathered feature matrix).
  * Recomputes the forward from `feats` and `label` (no state is shared with mil_pool_fwd),
  * writes dfeats_out = G [N,D] float32 and the aggregator slices (mil.*, head.*) of grads_fp32
  * (overwrite, or add when accumulate != 0). */
@@ -182,24 +182,6 @@ int  slide_adamw_step(float* params, const float* grads, float* exp_avg, float* 
 
 /* hipError_t of the most recent failing HIP call on this thread (0 if none). */
 int  slide_last_hip_error(void);
-
-/* Timing hooks for benchmarks.  Between slide_prof_begin and slide_prof_end every launch
- * of the kernel family `kernel_id` is bracketed by a pair of HIP events recorded on the
- * launch's own stream (events are created by the library on first use; at most
- * SLIDE_PROF_MAX launches are recorded, later ones run unrecorded).  slide_prof_end
- * synchronises on the recorded events and returns the summed duration (milliseconds),
- * the number of launches recorded and the FLOPs / algorithmic bytes those launches
- * were asked to do (host pointers; any may be NULL). */
-#define SLIDE_PROF_MAX 4096
-int         slide_prof_begin(slide_ctx* ctx, int kernel_id);
-int         slide_prof_end(slide_ctx* ctx, double* total_ms, int* launches,
-                           double* flops, double* bytes);
-const char* slide_kernel_name(int kernel_id);  /* NULL past the last id */
-
-/* Measurement aid: a plain device-to-device copy kernel (calib_copy_k) of `bytes` bytes (a multiple
- * of 16; dst and src 16-byte aligned device pointers, not overlapping).  It moves a known number of
- * bytes, which is what the hardware traffic counters of the other kernels are scaled with. */
-int  slide_calib_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -100,7 +100,7 @@ def unpatchify(dp, cfg):
 
 
 # ----------------------------------------------------------------------------
-# tile encoder (paper: `features = encoder(batch)`)
+# tile encoder (paper, appendix listing: the encoder ranks' forward step)
 # ----------------------------------------------------------------------------
 
 def encoder_fwd(prm, X, cfg, dtype=np.float64):
@@ -194,8 +194,8 @@ def encoder_bwd(cache, G, cfg, want_pixel_grad=True):
 
 
 # ----------------------------------------------------------------------------
-# aggregator + criterion (paper: `output = aggregator(allfeatures)`,
-# `criterion(output, label)`, `allfeatures.grad`)
+# aggregator + criterion (paper, appendix listing: the aggregator rank's forward, criterion and
+# backward to the gathered features; Method, paragraph on the aggregator)
 # ----------------------------------------------------------------------------
 
 def pool_fwd(prm, Hf, label, cfg, dtype=np.float64):

@@ -27,7 +27,7 @@ class SlideError(RuntimeError):
 class _CConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("tile", "patch", "dim", "layers", "heads", "mlp_ratio", "mil_hidden",
                                          "n_classes", "dtype", "recompute")] + \
-               [("ln_eps", C.c_float), ("want_pixel_grad", C.c_int32)]
+               [("ln_eps", C.c_float), ("reserved", C.c_int32)]
 
 
 @dataclass
@@ -43,7 +43,6 @@ class SlideConfig:
     dtype: int = 0          # 0 float32, 1 bfloat16
     recompute: int = 0
     ln_eps: float = 1e-6
-    want_pixel_grad: int = 0
 
 
 def config_from(shape, dtype: int, recompute: int = 0) -> SlideConfig:
@@ -79,6 +78,8 @@ _SYMS = {
     "slide_last_hip_error": (C.c_int, []),
     "slide_prof_begin": (C.c_int, [C.c_void_p, C.c_int]),
     "slide_prof_end": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int), C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+    "slide_prof_family": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int), C.POINTER(C.c_double),
+                                   C.POINTER(C.c_double)]),
     "slide_kernel_name": (C.c_char_p, [C.c_int]),
     "slide_calib_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "slide_adamw_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_int64, C.c_float,
@@ -126,7 +127,7 @@ class SlideLib:
         self.lib = load_cdll()
         self.cfg = cfg
         cc = _CConfig(cfg.tile, cfg.patch, cfg.dim, cfg.layers, cfg.heads, cfg.mlp_ratio, cfg.mil_hidden,
-                      cfg.n_classes, cfg.dtype, cfg.recompute, cfg.ln_eps, cfg.want_pixel_grad)
+                      cfg.n_classes, cfg.dtype, cfg.recompute, cfg.ln_eps, 0)
         h = C.c_void_p()
         self._check(self.lib.slide_ctx_create(C.byref(cc), C.byref(h)), "slide_ctx_create")
         self.ctx = h
@@ -223,6 +224,12 @@ class SlideLib:
     def slide_prof_end(self):
         ms, n, fl, by = C.c_double(), C.c_int(), C.c_double(), C.c_double()
         self._check(self.lib.slide_prof_end(self.ctx, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)), "slide_prof_end")
+        return ms.value, n.value, fl.value, by.value
+
+    def slide_prof_family(self, kernel_id):
+        ms, n, fl, by = C.c_double(), C.c_int(), C.c_double(), C.c_double()
+        self._check(self.lib.slide_prof_family(self.ctx, kernel_id, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)),
+                    "slide_prof_family")
         return ms.value, n.value, fl.value, by.value
 
     def slide_adamw_step(self, params, grads, exp_avg, exp_avg_sq, count, step, lr, beta1=0.9, beta2=0.999, eps=1e-8,

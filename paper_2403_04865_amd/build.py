@@ -36,7 +36,7 @@ def _newer(src_files, target):
 def build(force: bool = False, verbose: bool = True, extra_flags=()):
     os.makedirs(OBJ, exist_ok=True)
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    headers.append(os.path.join(HERE, "..", "include", "slide.h"))
+    headers += [os.path.join(HERE, "..", "include", h) for h in ("slide.h", "slide_prof.h")]
     hipcc = _hipcc()
     jobs = []
     for src in SOURCES:

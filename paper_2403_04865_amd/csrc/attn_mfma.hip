@@ -6,8 +6,8 @@
 // reduction inside each lane plus one exchange between the two lane halves, and the
 // probabilities are already in the lane layout the next MFMA wants as its B operand.
 // Operands whose contraction index is the row index of a row-major matrix (V in P.V, K in
-// dS.K, Q and dO in the key-owned backward) are transposed 8x8 in registers while being
-// copied into LDS.
+// dS.K, Q and dO in the key-owned backward) stay row-major in LDS and are fetched with LDS
+// transpose reads (ds_read_b64_tr_b16); no transposed copy is kept.
 //
 // Backward is two deterministic passes, both recomputing P from the saved row log-sum-exp:
 //   pass Q (query blocks owned by a wave): dQ = scale * dS K
@@ -24,18 +24,6 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ u32x4 ldg16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
 
-__device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
-#pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    int w = c >> 1;
-    unsigned sel = (c & 1) ? 0x07060302u : 0x05040100u;
-    u32x4 o;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) o[p] = __builtin_amdgcn_perm(in[2 * p + 1][w], in[2 * p][w], sel);
-    out[c] = o;
-  }
-}
-
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // pack 8 floats into the bf16x8 B operand
@@ -46,33 +34,13 @@ __device__ __forceinline__ bf16x8 pack8(const float* p) {
   return o;
 }
 
-// A operand from a transposed LDS image Xt[d][j] (row stride ldt): 8 contraction indices
-// j0 + 4*h2 + {0..3} and j0 + 8 + 4*h2 + {0..3}, matching accumulator registers 8t..8t+7.
-__device__ __forceinline__ bf16x8 frag_t(const bf16* Xt, int ldt, int d, int j0, int h2) {
-  const bf16* p = Xt + d * ldt + j0 + 4 * h2;
-  u32x2 a = *reinterpret_cast<const u32x2*>(p);
-  u32x2 b = *reinterpret_cast<const u32x2*>(p + 8);
-  u32x4 v = {a[0], a[1], b[0], b[1]};
-  return as_bf16x8(v);
-}
-
 // A operand whose contraction index runs along the ROWS of a row-major LDS matrix X[row][col] (row stride ld):
 // lane l gets column c0 + l % 32 and the rows j0 + 4*h2 + {0..3}, j0 + 8 + 4*h2 + {0..3} (h2 = l / 32), the order
 // of accumulator registers 8t..8t+7.  Two LDS transpose reads (ds_read_b64_tr_b16): within a group of 16
 // lanes, lane s addresses 4 consecutive columns of row s / 4 and receives, for column s of the group's 16, the
 // four rows.  No transposed copy of X is kept.
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ bf16x8 frag_tr(const bf16* X, int ld, int c0, int j0, int lane) {
-  int g = lane >> 4, s = lane & 15;
-  const bf16* p = X + (j0 + 4 * (g >> 1) + (s >> 2)) * ld + c0 + 16 * (g & 1) + (s & 3) * 4;
-  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
-  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 8 * ld));
-  typedef short s16x8 __attribute__((ext_vector_type(8)));
-  s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-  return __builtin_bit_cast(bf16x8, r);
-}
-
-// The same with the lane-dependent part of the address taken out: lp = X + tr_lane_off(ld, lane) is formed once,
+// The lane-dependent part of the address is taken out: lp = X + tr_lane_off(ld, lane) is formed once,
 // off = j0 * ld + c0 is a compile-time or wave-uniform element offset (LDS instructions carry it as an immediate).
 __device__ __forceinline__ int tr_lane_off(int ld, int lane) {
   int g = lane >> 4, s = lane & 15;
@@ -87,21 +55,10 @@ __device__ __forceinline__ bf16x8 frag_tr_at(const bf16* lp, int ld, int off) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
-// copy rows [0,T) x DH of a row-major global matrix (row stride gs) into LDS row-major [TP][DH+8]
-template <int DH>
-__device__ __forceinline__ void load_rm(const bf16* __restrict__ g, long long gs, int T, int TP, bf16* dst) {
-  constexpr int CH = DH / 8;
-  for (int c = threadIdx.x; c < TP * CH; c += blockDim.x) {
-    int row = c / CH, kc = c % CH;
-    u32x4 v = {0, 0, 0, 0};
-    if (row < T) v = ldg16(g + row * gs + kc * 8);
-    *reinterpret_cast<u32x4*>(dst + row * (DH + 8) + kc * 8) = v;
-  }
-}
-
-// Two such copies at once by a workgroup of NTHR threads, all global loads issued before the first LDS store: the
-// loop above waits for every load before it stores (its trip count and the row test are run-time), which puts one
-// memory latency per iteration and matrix in front of the kernel's work, as long as the work itself.
+// Copies rows [0,T) x DH of two row-major global matrices (row strides gs0, gs1) into LDS row-major [TP][DH+8], by a
+// workgroup of NTHR threads, all global loads issued before the first LDS store (a copy loop with a run-time trip
+// count waits for every load before it stores, which puts one memory latency per iteration in front of the
+// kernel's work, as long as the work itself).
 // Rows past T0 / T1 are filled with zeros.
 template <int DH, int TP, int NTHR, bool FENCE, typename MID>
 __device__ __forceinline__ void load_rm2(const bf16* __restrict__ g0, long long gs0, int T0, bf16* dst0,
@@ -129,26 +86,6 @@ __device__ __forceinline__ void load_rm2(const bf16* __restrict__ g0, long long 
       *reinterpret_cast<u32x4*>(dst0 + row * (DH + 8) + kc * 8) = row < T0 ? va[i] : z;
       *reinterpret_cast<u32x4*>(dst1 + row * (DH + 8) + kc * 8) = row < T1 ? vb[i] : z;
     }
-  }
-}
-
-// same source, transposed into LDS [DH][TP+8]
-template <int DH>
-__device__ __forceinline__ void load_tr(const bf16* __restrict__ g, long long gs, int T, int TP, bf16* dst) {
-  constexpr int NDB = DH / 8;
-  int nblk = (TP / 8) * NDB;
-  for (int b = threadIdx.x; b < nblk; b += blockDim.x) {
-    int jb = b / NDB, db = b % NDB;
-    u32x4 v[8], o[8];
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      int j = jb * 8 + r;
-      v[r] = u32x4{0, 0, 0, 0};
-      if (j < T) v[r] = ldg16(g + j * gs + db * 8);
-    }
-    transpose8x8(v, o);
-#pragma unroll
-    for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4*>(dst + (db * 8 + c) * (TP + 8) + jb * 8) = o[c];
   }
 }
 

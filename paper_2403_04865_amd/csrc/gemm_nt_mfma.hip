@@ -228,11 +228,7 @@ __global__ void __launch_bounds__(64 * WVM * WVN) gemm_nt_tile_k(GemmNT g, int M
     for (int kt = 0; kt < nk; ++kt) {
       int cur = kt & 1;
       bool more = kt + 1 < nk;
-#ifdef SLIDE_DEBUG_HOOKS
-      if (more && !(g.dbg & 4)) {
-#else
       if (more) {
-#endif
 #pragma unroll
         for (int i = 0; i < CA; ++i) ra[i] = ldg16(A + aoff[i] + (kt + 1) * BK);
 #pragma unroll
@@ -256,9 +252,6 @@ __global__ void __launch_bounds__(64 * WVM * WVN) gemm_nt_tile_k(GemmNT g, int M
           for (int j = 0; j < WBN; ++j)
             fb[(ks + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * LDT + (ks + 1) * 16);
         }
-#ifdef SLIDE_DEBUG_HOOKS
-        if (!(g.dbg & 1))
-#endif
 #pragma unroll
         for (int i = 0; i < WBM; ++i)
 #pragma unroll
@@ -291,11 +284,6 @@ __global__ void __launch_bounds__(64 * WVM * WVN) gemm_nt_tile_k(GemmNT g, int M
     float* patch = reinterpret_cast<float*>(smem) + wave * 32 * (WBN * 32 + 4);
     long long mw = m0 + wm * WBM * 32;
     int nw = n0 + wn * WBN * 32;
-#ifdef SLIDE_DEBUG_HOOKS
-    if (g.dbg & 2) {
-      if (acc[0][0][0] == 12345.678f) ((float*)g.out)[0] = 1.f;  // keeps the accumulators alive
-    } else
-#endif
     switch (g.epi) {
       case EPI_PLAIN: nt_epilogue<EPI_PLAIN, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
       case EPI_BIAS: nt_epilogue<EPI_BIAS, RS, WBM, WBN>(g, acc, mw, nw, lane, patch); break;
@@ -334,8 +322,6 @@ hipError_t go(const GemmNT& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-int g_variant = -1;
-
 }  // namespace
 
 bool gemm_nt_mfma_ok(const GemmNT& g) {
@@ -352,28 +338,10 @@ bool gemm_nt_mfma_ok(const GemmNT& g) {
 bool gemm_nt_big_ok(const GemmNT& g);
 hipError_t launch_gemm_nt_big(const GemmNT& g, hipStream_t s);
 
-// Large problems go to the 256 x 192 persistent kernel; the rest to the small-tile kernel below, whose
-// tile shape SLIDE_NT_VARIANT (tuning aid; 0 = never use the large kernel) overrides.
+// Large problems go to the 256 x 192 persistent kernel, the rest to the 128 x 128 tiles of the kernel above.
 hipError_t launch_gemm_nt_mfma(const GemmNT& g, hipStream_t s) {
-  if (g_variant < 0) {
-    const char* e = getenv("SLIDE_NT_VARIANT");
-    g_variant = e ? atoi(e) : 100;
-  }
-  if (g_variant >= 100 && gemm_nt_big_ok(g)) return launch_gemm_nt_big(g, s);
-  int v = g_variant >= 100 ? 1 : g_variant;
-  if (g.M < 1024) v = 1;  // small problems: small tiles
-  switch (v) {
-    case 1: return go<2, 2, 2, 2, 64>(g, s);   // 128 x 128
-    case 2: return go<4, 2, 2, 2, 64>(g, s);   // 256 x 128
-    case 3: return go<4, 4, 2, 2, 64>(g, s);   // 256 x 256
-    case 6: return go<2, 2, 4, 2, 64>(g, s);   // 256 x 128, 8 waves
-    case 7: return go<2, 4, 4, 1, 64>(g, s);   // 256 x 128, 4x1 waves of 64 x 128
-    case 8: return go<2, 4, 2, 1, 64>(g, s);   // 128 x 128, 2 waves of 64 x 128
-    case 9: return go<2, 2, 2, 2, 32>(g, s);   // 128 x 128, K step 32
-    case 10: return go<4, 2, 2, 2, 32>(g, s);  // 256 x 128, K step 32
-    case 11: return go<4, 4, 2, 2, 32>(g, s);  // 256 x 256, K step 32
-    default: return go<4, 2, 2, 2, 64>(g, s);
-  }
+  if (gemm_nt_big_ok(g)) return launch_gemm_nt_big(g, s);
+  return go<2, 2, 2, 2, 64>(g, s);
 }
 
 }  // namespace sl

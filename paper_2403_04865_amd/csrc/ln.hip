@@ -1,6 +1,10 @@
-// LayerNorm forward / backward: one 64-lane wavefront per token row, statistics in fp32.
-// Rows are re-normalised from the saved layer input wherever the normalised value is needed
-// again (weight-gradient operand, backward), so no per-row statistics are stored.
+// LayerNorm forward / backward, statistics in fp32.  No per-row statistics are stored: the backward takes the two
+// row reductions again from the saved layer input.  Three generations of kernels, picked by the launchers at the
+// end of the file: ln_*_row16_k (bf16 path, D = 384 / 768: 16 or 32 lanes per row, 16-byte accesses, several rows
+// per wavefront; the ones the large workloads run), ln_*_fast_k (paired elements, any D up to 1024) and ln_*_k (one
+// wavefront per row, any element types; the fp32 path).  The backward can also write the normalised rows
+// x_hat * gamma + beta next to dx (the operand of the weight gradient behind the LayerNorm) where the forward's own
+// copy was not kept.
 #include "slide_internal.h"
 
 namespace sl {

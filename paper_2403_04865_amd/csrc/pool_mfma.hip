@@ -5,13 +5,18 @@
 // bf16 MFMA GEMM [rows] x [V;U]^T with fp32 accumulation.  Everything else stays fp32 / fp64 on the
 // unrounded features: the softmax over tiles is a two-level online reduction (every workgroup keeps a running
 // max, sum and weighted feature sum over its row blocks; one workgroup combines them afterwards).
-//   * One persistent workgroup (4 wavefronts) per compute unit walks over blocks of RB feature rows.
-//   * The block's rows sit in LDS as fp32 (they are needed again, exactly, for the weighted sum); MFMA operands
-//     are converted to bf16 on the way from LDS to the registers.  The next block is in flight from HBM, in
-//     registers, while the current one is processed: each feature row is read from HBM exactly once.
-//   * [V;U] (bf16 copy, 2 M_h x D) streams from L2 through a double-buffered LDS ring, BK columns per step.
-//   * Operands are passed swapped (weights first): a lane then owns one feature row and 16 gate units per
-//     accumulator, so the sum over gate units is in-lane plus one exchange between the lane halves.
+// Two kernels:
+//   * pool_gate_part_reg_k (D = 384, M_h = 128; M_h = 256 as two passes over halves of the gate units above
+//     32768 rows): the main one.  One persistent workgroup (4 wavefronts) per compute unit; the bf16 copy of
+//     [V;U] is 192 kB, which is what the accumulation half of a compute unit's register file holds, so every
+//     wavefront keeps the fragments of its 32 gate units in registers for the whole kernel and the only traffic is
+//     the feature rows, each read from HBM exactly once into fp32 registers (a bf16 image in LDS feeds the MFMAs;
+//     the weighted feature sum is taken from the unrounded registers).  The gate arithmetic of block i - 1 is
+//     issued between the MFMAs of block i.
+//   * pool_gate_part_mfma_k (the other built shapes: M_h = 256 below 32768 rows, D = 768): rows in LDS as fp32,
+//     [V;U] streams from L2 through a double-buffered LDS ring, BK columns per step.
+//   Operands are passed swapped (weights first): a lane then owns one feature row and 16 gate units per
+//   accumulator, so the sum over gate units is in-lane plus one exchange between the lane halves.
 #include "slide_internal.h"
 
 namespace sl {

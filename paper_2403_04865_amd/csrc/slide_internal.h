@@ -110,7 +110,6 @@ struct GemmNT {
   const void* pre; long long ldpre;
   const float* pos;  // [T, N] position table (EPI_PATCH)
   RowMap cmap;       // EPI_PATCH output rows
-  int dbg;           // tuning builds only: 1 = no MFMAs, 2 = no epilogue, 4 = no operand loads in the K loop
 };
 
 // C[N1,N2] (fp32) = sum_m A[m,N1]^T B[m,N2]; split over `slabs` ranges of m, partial s is

@@ -1,5 +1,6 @@
 // libslide: C ABI, parameter layout, arena carving and the launch sequence of one slide step.
 #include "../../include/slide.h"
+#include "../../include/slide_prof.h"
 #include "slide_internal.h"
 
 #include <string>
@@ -49,10 +50,13 @@ const char* const kKernelNames[K_COUNT] = {
 
 struct Prof {
   bool active = false;
-  int id = -1;
+  int id = -1;                 // family being recorded, SLIDE_PROF_ALL = every family
   int count = 0;
-  double flops = 0, bytes = 0;
   std::vector<hipEvent_t> ev;  // 2 per launch
+  std::vector<int> fam;        // family of recorded launch i
+  // per family, filled by launch() (flops, bytes, n) and slide_prof_end (ms)
+  double flops[K_COUNT] = {}, bytes[K_COUNT] = {}, ms[K_COUNT] = {};
+  int n[K_COUNT] = {};
 };
 
 struct Tensor { std::string name; size_t off, len; };
@@ -226,7 +230,7 @@ template <typename F>
 void launch(Run& r, int id, double flops, double bytes, F f) {
   if (!r.ok()) return;
   Prof& p = r.c->prof;
-  bool rec = p.active && p.id == id && p.count < SLIDE_PROF_MAX;
+  bool rec = p.active && (p.id == id || p.id == SLIDE_PROF_ALL) && p.count < SLIDE_PROF_MAX;
   if (rec) {
     while ((int)p.ev.size() < 2 * (p.count + 1)) {
       hipEvent_t e;
@@ -238,9 +242,12 @@ void launch(Run& r, int id, double flops, double bytes, F f) {
   hipError_t e = f();
   if (rec) {
     (void)hipEventRecord(p.ev[2 * p.count + 1], r.s);
+    if ((int)p.fam.size() <= p.count) p.fam.resize(p.count + 1);
+    p.fam[p.count] = id;
     p.count++;
-    p.flops += flops;
-    p.bytes += bytes;
+    p.flops[id] += flops;
+    p.bytes[id] += bytes;
+    p.n[id]++;
   }
   if (e != hipSuccess) { r.err = e; g_last_hip = (int)e; }
 }
@@ -787,6 +794,7 @@ int slide_ctx_create(const slide_config* cfg, slide_ctx** out) {
   if (cfg->dim > 1024 || cfg->n_classes > 64 || cfg->mil_hidden > 1024) return SLIDE_EUNSUPPORTED;
   if (attn_lds_bytes(T, dh) > 160 * 1024) return SLIDE_EUNSUPPORTED;
   if (cfg->recompute != 0 && cfg->recompute != 1) return SLIDE_EINVAL;
+  if (cfg->reserved != 0) return SLIDE_EINVAL;
   slide_ctx* c = new (std::nothrow) slide_ctx();
   if (!c) return SLIDE_EINVAL;
   c->cfg = *cfg;
@@ -1053,54 +1061,43 @@ const void* slide_feature_grads(const slide_ctx* c) {
 int slide_last_hip_error(void) { return g_last_hip; }
 
 int slide_prof_begin(slide_ctx* c, int kernel_id) {
-  if (!c || kernel_id < 0 || kernel_id >= K_COUNT) return SLIDE_EINVAL;
-  c->prof.active = true; c->prof.id = kernel_id; c->prof.count = 0; c->prof.flops = 0; c->prof.bytes = 0;
+  if (!c || kernel_id < SLIDE_PROF_ALL || kernel_id >= K_COUNT) return SLIDE_EINVAL;
+  Prof& p = c->prof;
+  p.active = true; p.id = kernel_id; p.count = 0;
+  for (int k = 0; k < K_COUNT; ++k) { p.flops[k] = p.bytes[k] = p.ms[k] = 0; p.n[k] = 0; }
   return SLIDE_OK;
 }
 
 int slide_prof_end(slide_ctx* c, double* total_ms, int* launches, double* flops, double* bytes) {
   if (!c) return SLIDE_EINVAL;
   Prof& p = c->prof;
-  double tot = 0;
   int rc = SLIDE_OK;
   for (int i = 0; i < p.count; ++i) {
     float ms = 0.f;
     hipError_t e = hipEventSynchronize(p.ev[2 * i + 1]);
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]);
     if (e != hipSuccess) { g_last_hip = (int)e; rc = SLIDE_EHIP; break; }
-    tot += ms;
+    p.ms[p.fam[i]] += ms;
   }
+  double tot = 0, fl = 0, by = 0;
+  for (int k = 0; k < K_COUNT; ++k) { tot += p.ms[k]; fl += p.flops[k]; by += p.bytes[k]; }
   if (total_ms) *total_ms = tot;
   if (launches) *launches = p.count;
-  if (flops) *flops = p.flops;
-  if (bytes) *bytes = p.bytes;
+  if (flops) *flops = fl;
+  if (bytes) *bytes = by;
   p.active = false;
   return rc;
 }
 
-#ifdef SLIDE_DEBUG_HOOKS
-// Tuning aid (not part of the ABI, not built by default): one NT GEMM on caller-provided buffers.
-int slide_debug_gemm_nt(long long M, int N, int K, const void* A, const void* B, const float* bias, const void* aux,
-                        void* out, void* out2, int epi, int dbg, void* stream) {
-  GemmNT g{};
-  g.A = A; g.lda = K; g.B = B; g.ldb = K; g.M = M; g.N = N; g.K = K; g.epi = epi; g.bias = bias;
-  g.resid = aux; g.ldr = N; g.pre = aux; g.ldpre = N; g.out = out; g.ldc = N; g.out2 = out2; g.ldc2 = N; g.dbg = dbg;
-  hipError_t e = launch_gemm_nt(DT_BF16, g, true, (hipStream_t)stream);
-  return e == hipSuccess ? 0 : SLIDE_EHIP;
+int slide_prof_family(const slide_ctx* c, int kernel_id, double* total_ms, int* launches, double* flops, double* bytes) {
+  if (!c || kernel_id < 0 || kernel_id >= K_COUNT) return SLIDE_EINVAL;
+  const Prof& p = c->prof;
+  if (total_ms) *total_ms = p.ms[kernel_id];
+  if (launches) *launches = p.n[kernel_id];
+  if (flops) *flops = p.flops[kernel_id];
+  if (bytes) *bytes = p.bytes[kernel_id];
+  return SLIDE_OK;
 }
-// one large-M TN GEMM (partials only) on caller-provided buffers; part must hold 64 * N1 * N2 floats
-int slide_debug_gemm_tn(long long M, int N1, int N2, const void* A, const void* B, float* part, void* stream) {
-  GemmTN g{};
-  RowMap id{0, 0};
-  g.A = A; g.lda = N1; g.amap = id; g.B = B; g.ldb = N2; g.bmap = id; g.M = M; g.N1 = N1; g.N2 = N2; g.part = part;
-  g.cs_part = nullptr;
-  g.slabs = gemm_tn_big_slabs(g, 64);
-  if (!g.slabs) return SLIDE_EUNSUPPORTED;
-  g.big = 1;
-  hipError_t e = launch_gemm_tn(DT_BF16, g, true, (hipStream_t)stream);
-  return e == hipSuccess ? g.slabs : SLIDE_EHIP;
-}
-#endif
 
 int slide_adamw_step(float* params, const float* grads, float* m, float* v, size_t count, int64_t step, float lr,
                      float beta1, float beta2, float eps, float weight_decay, void* stream) {

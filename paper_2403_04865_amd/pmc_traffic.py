@@ -1,6 +1,6 @@
 """Turn four rocprofv3 --pmc counter dumps into HBM bytes per launch of each kernel family.
 
-    python -m paper_2403_04865_amd.pmc_traffic WORKLOAD FETCH.csv WRITE.csv COPY_FETCH.csv COPY_WRITE.csv COPY_BYTES
+    python -m paper_2403_04865_amd.pmc_traffic WORKLOAD FETCH.csv WRITE.csv COPY_FETCH.csv COPY_WRITE.csv COPY_BYTES [COMMIT]
 
 FETCH.csv / WRITE.csv: `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs of `bench.py --workload WORKLOAD`
 (counter_collection csv, one row per dispatch and counter).  COPY_*.csv: the same two counters over
@@ -9,6 +9,8 @@ counter (bytes per count).  Writes profiles/traffic_WORKLOAD.json:
     {family: {"hbm_bytes_per_launch", "fetch_bytes_per_launch", "write_bytes_per_launch", "launches"}, ...,
      "_scale": {...}}
 Kernel families are the names the library's timing hooks use (gemm_nt, gemm_tn, attn_fwd, ...).
+COMMIT (optional) is recorded as "_commit": the source revision the counters were collected on; bench.py prints it
+beside the traffic figures it reads from this file.
 """
 from __future__ import annotations
 
@@ -20,7 +22,8 @@ import sys
 
 FAMILIES = [("gemm_nt", ("gemm_nt_",)), ("gemm_tn", ("gemm_tn_",)), ("attn_fwd", ("attn_fwd",)),
             ("attn_bwd", ("attn_bwd",)), ("ln_fwd", ("ln_fwd",)), ("ln_bwd", ("ln_bwd",)),
-            ("pool_fwd", ("pool_gate", "pool_combine", "pool_alpha", "pool_cast")), ("pool_bwd", ("pool_bwd",))]
+            ("pool_fwd", ("pool_gate", "pool_combine", "pool_alpha", "pool_cast")), ("pool_bwd", ("pool_bwd",)),
+            ("cls_lane", ("lane_",))]
 
 
 def per_dispatch(path, counter):
@@ -57,7 +60,8 @@ def main(argv):
             agg[fam][counter] += v * scale[counter]
             if counter == "FETCH_SIZE":
                 agg[fam]["n"] += 1
-    out = {"_scale": {"bytes_per_count": scale, "copy_bytes": copy_bytes,
+    out = {"_commit": argv[6] if len(argv) > 6 else None,
+           "_scale": {"bytes_per_count": scale, "copy_bytes": copy_bytes,
                       "note": "counter readings of a plain copy of copy_bytes bytes define the scale"}}
     for fam, d in agg.items():
         n = max(d["n"], 1)

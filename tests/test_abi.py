@@ -21,7 +21,7 @@ def lib():
 
 
 def test_header_symbols_exported(lib):
-    hdr = open(os.path.join(ROOT, "include", "slide.h")).read()
+    hdr = open(os.path.join(ROOT, "include", "slide.h")).read() + open(os.path.join(ROOT, "include", "slide_prof.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b([a-z_0-9]+)\s*\(", hdr)) - {"defined"}
     names = {n for n in names if n.startswith(("slide_", "encoder_", "mil_"))}
