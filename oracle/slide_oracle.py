@@ -143,7 +143,7 @@ def encoder_bwd(cache, G, cfg, want_pixel_grad=True):
     """Backward of the encoder with upstream feature gradient G [n,D].
 
     This is the gradient of the paper's pseudo-loss sum_{tiles,features} f*g
-    (Method, inline equation; listing `pseudo_loss(features, grads_recv)`) with
+    (Method, inline equation; appendix listing, the encoder ranks' backward step) with
     no rank factor: on one device the encoder gradient is J^T g as is.
     Returns (dict of parameter gradients, pixel gradient or None).
     """
