@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libslide.so")
-SOURCES = ["slide_lib.hip", "misc.hip", "ln.hip", "gemm.hip", "gemm_mfma.hip", "gemm_nt_mfma.hip", "gemm_nt_big.hip", "gemm_tn_big.hip", "attn.hip", "attn_mfma.hip", "cls_lane.hip", "pool.hip", "pool_mfma.hip", "pool_bwd_mfma.hip", "optim.hip"]
+SOURCES = ["slide_lib.hip", "misc.hip", "ln.hip", "gemm.hip", "gemm_mfma.hip", "gemm_nt_mfma.hip", "gemm_nt_big.hip", "gemm_nt_gelu.hip", "gemm_tn_big.hip", "attn.hip", "attn_mfma.hip", "cls_lane.hip", "pool.hip", "pool_mfma.hip", "pool_bwd_mfma.hip", "optim.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -337,9 +337,13 @@ bool gemm_nt_mfma_ok(const GemmNT& g) {
 
 bool gemm_nt_big_ok(const GemmNT& g);
 hipError_t launch_gemm_nt_big(const GemmNT& g, hipStream_t s);
+bool gemm_nt_gelu_ok(const GemmNT& g);
+hipError_t launch_gemm_nt_gelu(const GemmNT& g, hipStream_t s);
 
-// Large problems go to the 256 x 192 persistent kernel, the rest to the 128 x 128 tiles of the kernel above.
+// Large problems go to the 256 x 192 persistent kernels (the bias + GELU epilogue has one of its own), the rest to the
+// 128 x 128 tiles of the kernel above.
 hipError_t launch_gemm_nt_mfma(const GemmNT& g, hipStream_t s) {
+  if (gemm_nt_gelu_ok(g)) return launch_gemm_nt_gelu(g, s);
   if (gemm_nt_big_ok(g)) return launch_gemm_nt_big(g, s);
   return go<2, 2, 2, 2, 64>(g, s);
 }
