@@ -15,6 +15,8 @@ TCP_PENDING_STALL_CYCLES_sum, GRBM_GUI_ACTIVE.  Prints one block per family (ave
   wait_any, wait_lds, valu_active = the wave-cycle counters over SQ_WAVE_CYCLES
   lds_conflict   = SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE
   tcp_pending    = TCP_PENDING_STALL_CYCLES_sum / (compute units * kernel clocks), kernel clocks = GRBM_GUI_ACTIVE / 8 XCDs
+  clock_ghz      = kernel clocks / launch time: the clock the chip held during the kernel (frac_of_peak is against the
+                   peak at 2.4 GHz, mfma_busy against the cycles that actually passed)
 """
 from __future__ import annotations
 
@@ -53,7 +55,7 @@ def main(dirs):
             continue
         c = {k: v / max(n[fam][k], 1) for k, v in cnt[fam].items()}   # per launch
         ms = sum(dur[fam]) / len(dur[fam]) / 1e6 if dur.get(fam) else None
-        out = [f"{fam}: launches {max(n[fam].values())}" + (f", avg {ms:.4f} ms" if ms else "")]
+        out = [f"{fam}: launches {len(dur[fam]) if dur.get(fam) else min(n[fam].values())}" + (f", avg {ms:.4f} ms" if ms else "")]
 
         def ratio(a, b, scale=1.0):
             return c[a] / (c[b] * scale) if a in c and b in c and c[b] > 0 else None
@@ -66,6 +68,8 @@ def main(dirs):
         if "SQ_INSTS_VALU_MFMA_MOPS_BF16" in c and ms:
             tf = c["SQ_INSTS_VALU_MFMA_MOPS_BF16"] * 512 / (ms * 1e-3) / 1e12
             fields += [("tflops_counter", tf), ("frac_of_peak", tf / PEAK_TFLOPS)]
+        if "GRBM_GUI_ACTIVE" in c and ms:
+            fields += [("clock_ghz", c["GRBM_GUI_ACTIVE"] / XCDS / (ms * 1e-3) / 1e9)]
         out.append("   " + "  ".join(f"{k} {v:.3f}" for k, v in fields if v is not None))
         print("\n".join(out))
 
