@@ -7,3 +7,6 @@ from .slide_inputs import (  # noqa: F401
     SlideConfig, CONFIGS, SEEDS, param_shapes, make_params, make_pixels,
     make_label, make_features, to_bf16_grid,
 )
+from .resnet_inputs import (  # noqa: F401
+    ResNetConfig, RESNET_CONFIGS, RESNET_SEEDS, resnet_blocks, resnet_param_shapes, make_resnet_params,
+)
