@@ -25,6 +25,16 @@ the call and all positions (Results, gradient equivalence: the normalisation lay
 synchronised across devices so that the statistics are those of the whole slide; on one device
 that is the plain batch statistic over every tile of the slide).
 
+Storage precision.  The paper trains these encoders with 16-bit mixed precision (Method, the
+tiles-per-device figures with automatic mixed precision), and a ReLU or a max pooling turns a
+floating-point value into a decision (which inputs pass a gradient).  For a comparison with a path
+that stores its activations in 16 bits both sides must take those decisions on the same numbers, so
+every function here takes `store`: a function applied to each activation tensor at the point where a
+16-bit path writes it to memory (convolution outputs; outputs of normalisation + ReLU; block outputs
+behind the residual sum and ReLU).  The default is the identity (plain float64: the definition);
+the parity tests of the bfloat16 path pass round-to-nearest-even to bfloat16.  Arithmetic between
+two such points stays float64, and nothing is rounded in the backward.
+
 Parity pins: tests/test_oracle_resnet.py (finite differences of the scalar loss, an independent
 autograd graph of library routines, brute-force loops, 1x1 convolution = matrix product,
 normalisation invariants, pooling routing).  Nothing is "parity unpinned".
@@ -134,8 +144,12 @@ def _blocks(cfg):
     return out
 
 
-def _conv_bn(P, x, conv, bn, stride, pad, eps):
-    c = conv2d_fwd(x, P[conv + ".W"], stride, pad)
+def _identity(a):
+    return a
+
+
+def _conv_bn(P, x, conv, bn, stride, pad, eps, store):
+    c = store(conv2d_fwd(x, P[conv + ".W"], stride, pad))
     y, bc = bn_fwd(c, P[bn + ".g"], P[bn + ".b"], eps)
     return y, (x, conv, bn, stride, pad, bc)
 
@@ -147,35 +161,35 @@ def _conv_bn_bwd(P, g, dy, cache):
     return dx
 
 
-def encoder_fwd(prm, X, cfg, dtype=np.float64):
+def encoder_fwd(prm, X, cfg, dtype=np.float64, store=_identity):
     """Tile features H [n, dim] and the cache for encoder_bwd.  X: [n,3,S,S] normalised pixels."""
     P = {k: np.asarray(v, dtype=dtype) for k, v in prm.items() if not k.startswith(("mil.", "head."))}
     eps = cfg.bn_eps
     x = np.asarray(X, dtype=dtype)
-    y, c0 = _conv_bn(P, x, "stem.conv", "stem.bn", 2, 3, eps)
-    r0 = np.maximum(y, 0.0)
+    y, c0 = _conv_bn(P, x, "stem.conv", "stem.bn", 2, 3, eps, store)
+    r0 = store(np.maximum(y, 0.0))
     x, mp = maxpool_fwd(r0)
     caches = []
     for name, stride, down in _blocks(cfg):
         p = name + "."
         x0 = x
         if cfg.block == "basic":
-            y1, k1 = _conv_bn(P, x0, p + "conv1", p + "bn1", stride, 1, eps)
-            r1 = np.maximum(y1, 0.0)
-            y2, k2 = _conv_bn(P, r1, p + "conv2", p + "bn2", 1, 1, eps)
+            y1, k1 = _conv_bn(P, x0, p + "conv1", p + "bn1", stride, 1, eps, store)
+            r1 = store(np.maximum(y1, 0.0))
+            y2, k2 = _conv_bn(P, r1, p + "conv2", p + "bn2", 1, 1, eps, store)
             body, ks, rs = y2, [k1, k2], [r1]
         else:
-            y1, k1 = _conv_bn(P, x0, p + "conv1", p + "bn1", 1, 0, eps)
-            r1 = np.maximum(y1, 0.0)
-            y2, k2 = _conv_bn(P, r1, p + "conv2", p + "bn2", stride, 1, eps)
-            r2 = np.maximum(y2, 0.0)
-            y3, k3 = _conv_bn(P, r2, p + "conv3", p + "bn3", 1, 0, eps)
+            y1, k1 = _conv_bn(P, x0, p + "conv1", p + "bn1", 1, 0, eps, store)
+            r1 = store(np.maximum(y1, 0.0))
+            y2, k2 = _conv_bn(P, r1, p + "conv2", p + "bn2", stride, 1, eps, store)
+            r2 = store(np.maximum(y2, 0.0))
+            y3, k3 = _conv_bn(P, r2, p + "conv3", p + "bn3", 1, 0, eps, store)
             body, ks, rs = y3, [k1, k2, k3], [r1, r2]
         if down:
-            sc, kd = _conv_bn(P, x0, p + "down.conv", p + "down.bn", stride, 0, eps)
+            sc, kd = _conv_bn(P, x0, p + "down.conv", p + "down.bn", stride, 0, eps, store)
         else:
             sc, kd = x0, None
-        x = np.maximum(body + sc, 0.0)
+        x = store(np.maximum(body + sc, 0.0))
         caches.append((ks, rs, kd, x))
     H = x.mean(axis=(2, 3))
     return H, {"P": P, "stem": (c0, r0, mp), "blocks": caches, "last_shape": x.shape}
@@ -200,14 +214,14 @@ def encoder_bwd(cache, G):
     return g
 
 
-def slide_loss(prm, X, label, cfg, dtype=np.float64):
-    Hf, _ = encoder_fwd(prm, X, cfg, dtype)
+def slide_loss(prm, X, label, cfg, dtype=np.float64, store=_identity):
+    Hf, _ = encoder_fwd(prm, X, cfg, dtype, store)
     return pool_fwd(prm, Hf, label, cfg, dtype)[0]
 
 
-def slide_step(prm, X, label, cfg, dtype=np.float64):
+def slide_step(prm, X, label, cfg, dtype=np.float64, store=_identity):
     """One forward + backward step over all tiles of a slide: dict(loss, logits, alpha, H, G, grads)."""
-    Hf, cache = encoder_fwd(prm, X, cfg, dtype)
+    Hf, cache = encoder_fwd(prm, X, cfg, dtype, store)
     loss, y, alpha, z, pc = pool_fwd(prm, Hf, label, cfg, dtype)
     G, grads = pool_bwd(pc)
     grads.update(encoder_bwd(cache, G))

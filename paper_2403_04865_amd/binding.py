@@ -87,6 +87,54 @@ _SYMS = {
 }
 
 
+class _CResNetConfig(C.Structure):
+    _fields_ = [("tile", C.c_int32), ("block", C.c_int32), ("depths", C.c_int32 * 4), ("width", C.c_int32),
+                ("mil_hidden", C.c_int32), ("n_classes", C.c_int32), ("bn_eps", C.c_float), ("reserved", C.c_int32)]
+
+
+@dataclass
+class ResNetConfig:
+    tile: int
+    block: int              # 0 basic, 1 bottleneck
+    depths: tuple
+    width: int
+    mil_hidden: int
+    n_classes: int
+    bn_eps: float = 1e-5
+
+
+def resnet_config_from(shape) -> ResNetConfig:
+    """ResNetConfig from any object with the fields tile, block ("basic" / "bottleneck"), depths, width, mil_hidden,
+    n_classes and bn_eps (such as a workload description of the input generators)."""
+    return ResNetConfig(shape.tile, 0 if shape.block == "basic" else 1, tuple(shape.depths), shape.width,
+                        shape.mil_hidden, shape.n_classes, shape.bn_eps)
+
+
+_P4 = [C.POINTER(C.c_double), C.POINTER(C.c_int), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+_SYMS.update({
+    "resnet_ctx_create": (C.c_int, [C.POINTER(_CResNetConfig), C.POINTER(C.c_void_p)]),
+    "resnet_ctx_destroy": (None, [C.c_void_p]),
+    "resnet_param_count": (C.c_size_t, [C.c_void_p]),
+    "resnet_param_tensors": (C.c_int, [C.c_void_p]),
+    "resnet_param_name": (C.c_int, [C.c_void_p, C.c_int, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]),
+    "resnet_feature_dim": (C.c_int, [C.c_void_p]),
+    "resnet_arena_bytes": (C.c_size_t, [C.c_void_p, C.c_int64]),
+    "resnet_bind": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
+    "resnet_encoder_fwd_tiles": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]),
+    "resnet_encoder_bwd_tiles": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p]),
+    "resnet_slide_step_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "resnet_slide_step_bwd": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
+    "resnet_features": (C.c_void_p, [C.c_void_p]),
+    "resnet_feature_grads": (C.c_void_p, [C.c_void_p]),
+    "resnet_saved_activations": (C.c_int, [C.c_void_p]),
+    "resnet_saved_activation": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
+    "resnet_prof_begin": (C.c_int, [C.c_void_p, C.c_int]),
+    "resnet_prof_end": (C.c_int, [C.c_void_p] + _P4),
+    "resnet_prof_family": (C.c_int, [C.c_void_p, C.c_int] + _P4),
+    "resnet_kernel_name": (C.c_char_p, [C.c_int]),
+})
+
+
 def load_cdll():
     p = lib_path()
     if not os.path.exists(p):
@@ -245,6 +293,110 @@ class SlideLib:
         out, i = [], 0
         while True:
             s = self.lib.slide_kernel_name(i)
+            if s is None:
+                return out
+            out.append(s.decode())
+            i += 1
+
+
+class ResNetLib:
+    """One resnet_ctx (include/resnet.h).  Methods carry the C ABI's names and pass torch tensors' device pointers."""
+
+    def __init__(self, cfg: ResNetConfig):
+        self.lib = load_cdll()
+        self.cfg = cfg
+        cc = _CResNetConfig(cfg.tile, cfg.block, (C.c_int32 * 4)(*cfg.depths), cfg.width, cfg.mil_hidden, cfg.n_classes,
+                            cfg.bn_eps, 0)
+        h = C.c_void_p()
+        self._check(self.lib.resnet_ctx_create(C.byref(cc), C.byref(h)), "resnet_ctx_create")
+        self.ctx = h
+        self._keep = []
+
+    def __del__(self):
+        try:
+            if getattr(self, "ctx", None):
+                self.lib.resnet_ctx_destroy(self.ctx)
+                self.ctx = None
+        except Exception:
+            pass
+
+    def _check(self, rc, what):
+        if rc != 0:
+            raise SlideError(rc, what, self.lib.slide_last_hip_error())
+
+    def resnet_param_count(self):
+        return int(self.lib.resnet_param_count(self.ctx))
+
+    def resnet_feature_dim(self):
+        return int(self.lib.resnet_feature_dim(self.ctx))
+
+    def param_layout(self):
+        """[(name, offset, length)] in layout order."""
+        out = []
+        buf = C.create_string_buffer(64)
+        off, ln = C.c_size_t(), C.c_size_t()
+        for i in range(self.lib.resnet_param_tensors(self.ctx)):
+            self._check(self.lib.resnet_param_name(self.ctx, i, buf, 64, C.byref(off), C.byref(ln)), "resnet_param_name")
+            out.append((buf.value.decode(), off.value, ln.value))
+        return out
+
+    def resnet_arena_bytes(self, n_tiles):
+        return int(self.lib.resnet_arena_bytes(self.ctx, n_tiles))
+
+    def resnet_bind(self, params, grads, arena):
+        self._keep = [params, grads, arena]
+        self._check(self.lib.resnet_bind(self.ctx, _ptr(params), _ptr(grads), _ptr(arena),
+                                         arena.numel() * arena.element_size()), "resnet_bind")
+
+    def resnet_encoder_fwd_tiles(self, pixels, n_tiles, feats_out, stream=None):
+        self._check(self.lib.resnet_encoder_fwd_tiles(self.ctx, _ptr(pixels), n_tiles, _ptr(feats_out), _stream(stream)),
+                    "resnet_encoder_fwd_tiles")
+
+    def resnet_encoder_bwd_tiles(self, dfeats, n_tiles, accumulate, stream=None):
+        self._check(self.lib.resnet_encoder_bwd_tiles(self.ctx, _ptr(dfeats), n_tiles, int(accumulate), _stream(stream)),
+                    "resnet_encoder_bwd_tiles")
+
+    def resnet_slide_step_fwd(self, pixels, N, label, loss=None, logits=None, alpha=None, stream=None):
+        self._check(self.lib.resnet_slide_step_fwd(self.ctx, _ptr(pixels), N, label, _ptr(loss), _ptr(logits), _ptr(alpha),
+                                                   _stream(stream)), "resnet_slide_step_fwd")
+
+    def resnet_slide_step_bwd(self, accumulate, stream=None):
+        self._check(self.lib.resnet_slide_step_bwd(self.ctx, int(accumulate), _stream(stream)), "resnet_slide_step_bwd")
+
+    def resnet_features(self):
+        return self.lib.resnet_features(self.ctx)
+
+    def resnet_feature_grads(self):
+        return self.lib.resnet_feature_grads(self.ctx)
+
+    def resnet_saved_activations(self):
+        return int(self.lib.resnet_saved_activations(self.ctx))
+
+    def resnet_saved_activation(self, index):
+        """(device pointer, side, channels) of saved activation `index`."""
+        p, side, ch = C.c_void_p(), C.c_int32(), C.c_int32()
+        self._check(self.lib.resnet_saved_activation(self.ctx, index, C.byref(p), C.byref(side), C.byref(ch)),
+                    "resnet_saved_activation")
+        return p.value, side.value, ch.value
+
+    def resnet_prof_begin(self, kernel_id):
+        self._check(self.lib.resnet_prof_begin(self.ctx, kernel_id), "resnet_prof_begin")
+
+    def resnet_prof_end(self):
+        ms, n, fl, by = C.c_double(), C.c_int(), C.c_double(), C.c_double()
+        self._check(self.lib.resnet_prof_end(self.ctx, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)), "resnet_prof_end")
+        return ms.value, n.value, fl.value, by.value
+
+    def resnet_prof_family(self, kernel_id):
+        ms, n, fl, by = C.c_double(), C.c_int(), C.c_double(), C.c_double()
+        self._check(self.lib.resnet_prof_family(self.ctx, kernel_id, C.byref(ms), C.byref(n), C.byref(fl), C.byref(by)),
+                    "resnet_prof_family")
+        return ms.value, n.value, fl.value, by.value
+
+    def kernel_names(self):
+        out, i = [], 0
+        while True:
+            s = self.lib.resnet_kernel_name(i)
             if s is None:
                 return out
             out.append(s.decode())

@@ -14,7 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libslide.so")
-SOURCES = ["slide_lib.hip", "misc.hip", "ln.hip", "gemm.hip", "gemm_mfma.hip", "gemm_nt_mfma.hip", "gemm_nt_big.hip", "gemm_nt_gelu.hip", "gemm_tn_big.hip", "attn.hip", "attn_mfma.hip", "cls_lane.hip", "pool.hip", "pool_mfma.hip", "pool_bwd_mfma.hip", "optim.hip"]
+SOURCES = ["slide_lib.hip", "misc.hip", "ln.hip", "gemm.hip", "gemm_mfma.hip", "gemm_nt_mfma.hip", "gemm_nt_big.hip", "gemm_nt_gelu.hip", "gemm_tn_big.hip", "attn.hip", "attn_mfma.hip", "cls_lane.hip", "pool.hip", "pool_mfma.hip", "pool_bwd_mfma.hip", "optim.hip",
+           "conv.hip", "bn_pool.hip", "resnet_lib.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -36,7 +37,7 @@ def _newer(src_files, target):
 def build(force: bool = False, verbose: bool = True, extra_flags=()):
     os.makedirs(OBJ, exist_ok=True)
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    headers += [os.path.join(HERE, "..", "include", h) for h in ("slide.h", "slide_prof.h")]
+    headers += [os.path.join(HERE, "..", "include", h) for h in ("slide.h", "slide_prof.h", "resnet.h")]
     hipcc = _hipcc()
     jobs = []
     for src in SOURCES:

@@ -1,0 +1,369 @@
+// Row-wise kernels of the ResNet tile encoder (gfx950): batch normalisation with the statistics of all rows of the
+// call, its backward, max and average pooling.  Tensors are bf16 [rows][C], C a power of two between 64 and 2048;
+// every thread moves 16-byte pieces (8 channels).  All of them are bound by memory traffic.
+//
+// Reductions over the rows (statistics, gain / shift gradients) are two-stage and deterministic: a fixed number of
+// workgroups each sums a contiguous range of rows in fp32 (8 channels per thread, rows strided over the threads, then
+// one pass through LDS), and one thread per channel adds the workgroups' partial sums in double, in order.
+#include "resnet_internal.h"
+
+namespace sl {
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void unpack8(const u32x4& t, float (&v)[8]) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    v[2 * w] = __uint_as_float(t[w] << 16);
+    v[2 * w + 1] = __uint_as_float(t[w] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ u32x4 ld16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
+__device__ __forceinline__ void st8(bf16* p, const float (&v)[8]) {
+  bf16x8 t;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) t[e] = (bf16)v[e];
+  *reinterpret_cast<bf16x8*>(p) = t;
+}
+
+constexpr int BN_MAX_BLOCKS = 1024;
+
+// Two per-channel sums over the rows of one workgroup's range.  F(row pointer offset, channel base, out a[8], out b[8])
+// yields the two summands of 8 channels of one row.
+template <typename F>
+__device__ __forceinline__ void two_sums(long long M, int C, float* part, F f) {
+  __shared__ float red[2][256 * 8];
+  const int tcols = C >> 3, rpp = 256 / tcols;          // threads per row, rows per pass
+  const int tc = threadIdx.x % tcols, tr = threadIdx.x / tcols;
+  const long long per = (M + gridDim.x - 1) / gridDim.x;
+  const long long lo = (long long)blockIdx.x * per, hi = lo + per < M ? lo + per : M;
+  float s[8], q[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s[e] = q[e] = 0.f;
+  for (long long m = lo + tr; m < hi; m += rpp) {
+    float a[8], b[8];
+    f(m * C + tc * 8, tc * 8, a, b);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { s[e] += a[e]; q[e] += b[e]; }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { red[0][threadIdx.x * 8 + e] = s[e]; red[1][threadIdx.x * 8 + e] = q[e]; }
+  __syncthreads();
+  // thread (tr, tc) -> flat index (tr * tcols + tc) * 8 + e = tr * C + channel
+  for (int ch = threadIdx.x; ch < C; ch += 256) {
+    float a = 0.f, b = 0.f;
+    for (int r = 0; r < rpp; ++r) { a += red[0][r * C + ch]; b += red[1][r * C + ch]; }
+    part[((long long)blockIdx.x * 2 + 0) * C + ch] = a;
+    part[((long long)blockIdx.x * 2 + 1) * C + ch] = b;
+  }
+}
+
+__global__ void __launch_bounds__(256) bn_stats_part_k(const bf16* __restrict__ x, long long M, int C, float* __restrict__ part) {
+  two_sums(M, C, part, [&](long long off, int, float (&a)[8], float (&b)[8]) {
+    unpack8(ld16(x + off), a);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[e] = a[e] * a[e];
+  });
+}
+
+__global__ void __launch_bounds__(256) bn_stats_final_k(const float* __restrict__ part, int blocks, long long M, int C,
+                                                         const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                         float eps, float* __restrict__ stats) {
+  const int ch = blockIdx.x * 256 + threadIdx.x;
+  if (ch >= C) return;
+  double s = 0.0, q = 0.0;
+  for (int b = 0; b < blocks; ++b) { s += (double)part[((long long)b * 2) * C + ch]; q += (double)part[((long long)b * 2 + 1) * C + ch]; }
+  const double mean = s / (double)M;
+  double var = q / (double)M - mean * mean;
+  if (var < 0.0) var = 0.0;
+  const double rstd = 1.0 / sqrt(var + (double)eps);
+  const double a = (double)gamma[ch] * rstd;
+  stats[ch] = (float)mean;
+  stats[C + ch] = (float)rstd;
+  stats[2 * C + ch] = (float)a;
+  stats[3 * C + ch] = (float)((double)beta[ch] - mean * a);
+}
+
+__global__ void __launch_bounds__(256) bn_apply_k(const bf16* __restrict__ x, long long chunks, int C,
+                                                   const float* __restrict__ stats, const bf16* __restrict__ resid,
+                                                   const float* __restrict__ rstats, int relu, bf16* __restrict__ y) {
+  const int tcols = C >> 3;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (long long)gridDim.x * 256) {
+    const int c0 = (int)(i % tcols) * 8;
+    float v[8];
+    unpack8(ld16(x + i * 8), v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = stats[2 * C + c0 + e] * v[e] + stats[3 * C + c0 + e];
+    if (resid) {
+      float r[8];
+      unpack8(ld16(resid + i * 8), r);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += rstats ? rstats[2 * C + c0 + e] * r[e] + rstats[3 * C + c0 + e] : r[e];
+    }
+    if (relu) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
+    }
+    st8(y + i * 8, v);
+  }
+}
+
+__global__ void __launch_bounds__(256) bn_bwd_part_k(const bf16* __restrict__ dy, const bf16* __restrict__ mask,
+                                                      const bf16* __restrict__ x, long long M, int C,
+                                                      const float* __restrict__ stats, float* __restrict__ part) {
+  two_sums(M, C, part, [&](long long off, int c0, float (&a)[8], float (&b)[8]) {
+    float xv[8];
+    unpack8(ld16(dy + off), a);
+    unpack8(ld16(x + off), xv);
+    if (mask) {
+      float mv[8];
+      unpack8(ld16(mask + off), mv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = mv[e] > 0.f ? a[e] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) b[e] = a[e] * ((xv[e] - stats[c0 + e]) * stats[C + c0 + e]);
+  });
+}
+
+// coef[0][c] = dbeta / M, coef[1][c] = dgamma / M; parameter gradients written or added to
+__global__ void __launch_bounds__(256) bn_bwd_final_k(const float* __restrict__ part, int blocks, long long M, int C,
+                                                       float* __restrict__ coef, float* __restrict__ dgamma,
+                                                       float* __restrict__ dbeta, int accumulate) {
+  const int ch = blockIdx.x * 256 + threadIdx.x;
+  if (ch >= C) return;
+  double s = 0.0, q = 0.0;
+  for (int b = 0; b < blocks; ++b) { s += (double)part[((long long)b * 2) * C + ch]; q += (double)part[((long long)b * 2 + 1) * C + ch]; }
+  coef[ch] = (float)(s / (double)M);
+  coef[C + ch] = (float)(q / (double)M);
+  dbeta[ch] = accumulate ? dbeta[ch] + (float)s : (float)s;
+  dgamma[ch] = accumulate ? dgamma[ch] + (float)q : (float)q;
+}
+
+__global__ void __launch_bounds__(256) bn_bwd_apply_k(const bf16* __restrict__ dy, const bf16* __restrict__ mask,
+                                                       const bf16* __restrict__ x, long long chunks, int C,
+                                                       const float* __restrict__ stats, const float* __restrict__ coef,
+                                                       bf16* __restrict__ dx) {
+  const int tcols = C >> 3;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (long long)gridDim.x * 256) {
+    const int c0 = (int)(i % tcols) * 8;
+    float d[8], xv[8];
+    unpack8(ld16(dy + i * 8), d);
+    unpack8(ld16(x + i * 8), xv);
+    if (mask) {
+      float mv[8];
+      unpack8(ld16(mask + i * 8), mv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] = mv[e] > 0.f ? d[e] : 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float xh = (xv[e] - stats[c0 + e]) * stats[C + c0 + e];
+      d[e] = stats[2 * C + c0 + e] * (d[e] - coef[c0 + e] - xh * coef[C + c0 + e]);
+    }
+    st8(dx + i * 8, d);
+  }
+}
+
+// ---- pooling ---------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) maxpool_fwd_k(const bf16* __restrict__ x, bf16* __restrict__ y, long long chunks,
+                                                      int H, int W, int C) {
+  const int tcols = C >> 3, OH = H / 2, OW = W / 2;
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= chunks) return;
+  const int tc = (int)(i % tcols);
+  long long pos = i / tcols;
+  const int ox = (int)(pos % OW); pos /= OW;
+  const int oy = (int)(pos % OH);
+  const long long n = pos / OH;
+  float best[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+  for (int kh = 0; kh < 3; ++kh)
+    for (int kw = 0; kw < 3; ++kw) {
+      const int iy = 2 * oy + kh - 1, ix = 2 * ox + kw - 1;
+      if ((unsigned)iy < (unsigned)H && (unsigned)ix < (unsigned)W) {
+        float v[8];
+        unpack8(ld16(x + (((n * H + iy) * W + ix) * C + tc * 8)), v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], v[e]);
+      }
+    }
+  st8(y + i * 8, best);
+}
+
+// one thread per input position and 8 channels: for each of the (at most four) windows that contain the position,
+// find the window's first maximum in (kh, kw) order again and take the window's gradient if it is this position
+__global__ void __launch_bounds__(256) maxpool_bwd_k(const bf16* __restrict__ x, const bf16* __restrict__ dy,
+                                                      bf16* __restrict__ dx, long long chunks, int H, int W, int C) {
+  const int tcols = C >> 3, OH = H / 2, OW = W / 2;
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= chunks) return;
+  const int tc = (int)(i % tcols);
+  long long pos = i / tcols;
+  const int ix = (int)(pos % W); pos /= W;
+  const int iy = (int)(pos % H);
+  const long long n = pos / H;
+  float g[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) g[e] = 0.f;
+  // windows (oy, ox) with 2 oy - 1 <= iy <= 2 oy + 1: oy = iy / 2 for even iy, (iy - 1) / 2 and (iy + 1) / 2 for odd iy
+  const int oy0 = iy >> 1, ny = (iy & 1) ? 2 : 1;
+  const int ox0 = ix >> 1, nx = (ix & 1) ? 2 : 1;
+  for (int a = 0; a < ny; ++a)
+    for (int b = 0; b < nx; ++b) {
+      const int oy = oy0 + a, ox = ox0 + b;
+      if (oy >= OH || ox >= OW) continue;
+      const int mine = (iy - 2 * oy + 1) * 3 + (ix - 2 * ox + 1);
+      float best[8];
+      int at[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { best[e] = -INFINITY; at[e] = -1; }
+      for (int kh = 0; kh < 3; ++kh)
+        for (int kw = 0; kw < 3; ++kw) {
+          const int sy = 2 * oy + kh - 1, sx = 2 * ox + kw - 1;
+          if ((unsigned)sy < (unsigned)H && (unsigned)sx < (unsigned)W) {
+            float v[8];
+            unpack8(ld16(x + (((n * H + sy) * W + sx) * C + tc * 8)), v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (v[e] > best[e]) { best[e] = v[e]; at[e] = kh * 3 + kw; }
+          }
+        }
+      float d[8];
+      unpack8(ld16(dy + (((n * OH + oy) * OW + ox) * C + tc * 8)), d);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) g[e] += at[e] == mine ? d[e] : 0.f;
+    }
+  st8(dx + i * 8, g);
+}
+
+// one workgroup per tile; thread t sums channels t, t + 256, ... over the positions (neighbouring threads read
+// neighbouring channels)
+__global__ void __launch_bounds__(256) avgpool_fwd_k(const bf16* __restrict__ x, float* __restrict__ feats, int HW, int C) {
+  const long long n = blockIdx.x;
+  for (int ch = threadIdx.x; ch < C; ch += 256) {
+    float a = 0.f;
+    for (int p = 0; p < HW; ++p) a += (float)x[(n * HW + p) * C + ch];
+    feats[n * C + ch] = a / (float)HW;
+  }
+}
+
+__global__ void __launch_bounds__(256) avgpool_bwd_k(const float* __restrict__ df, bf16* __restrict__ dx, long long chunks,
+                                                      int HW, int C) {
+  const int tcols = C >> 3;
+  const float inv = 1.0f / (float)HW;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (long long)gridDim.x * 256) {
+    const int c0 = (int)(i % tcols) * 8;
+    const long long n = i / tcols / HW;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = df[n * C + c0 + e] * inv;
+    st8(dx + i * 8, v);
+  }
+}
+
+__global__ void __launch_bounds__(256) add_masked_k(bf16* __restrict__ dst, const bf16* __restrict__ src,
+                                                     const bf16* __restrict__ mask, long long chunks) {
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (long long)gridDim.x * 256) {
+    float a[8], b[8], m[8];
+    unpack8(ld16(dst + i * 8), a);
+    unpack8(ld16(src + i * 8), b);
+    unpack8(ld16(mask + i * 8), m);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] += m[e] > 0.f ? b[e] : 0.f;
+    st8(dst + i * 8, a);
+  }
+}
+
+bool chan_ok(int C) { return C >= 64 && C <= 2048 && (C & (C - 1)) == 0; }
+bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+unsigned stream_grid(long long chunks) {
+  long long b = (chunks + 255) / 256;
+  return (unsigned)(b < 1 ? 1 : (b > 16384 ? 16384 : b));
+}
+
+}  // namespace
+
+int bn_blocks(long long M, int C) {
+  (void)C;
+  long long b = M / 256;
+  return (int)(b < 1 ? 1 : (b > BN_MAX_BLOCKS ? BN_MAX_BLOCKS : b));
+}
+
+hipError_t launch_bn_stats(const bf16* x, long long M, int C, const float* gamma, const float* beta, float eps,
+                           float* part, float* stats, hipStream_t s) {
+  if (!x || !gamma || !beta || !part || !stats || M <= 0 || !chan_ok(C) || !al16(x)) return hipErrorInvalidValue;
+  const int blocks = bn_blocks(M, C);
+  hipLaunchKernelGGL(bn_stats_part_k, dim3(blocks), dim3(256), 0, s, x, M, C, part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(bn_stats_final_k, dim3((C + 255) / 256), dim3(256), 0, s, part, blocks, M, C, gamma, beta, eps, stats);
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_apply(const bf16* x, long long M, int C, const float* stats, const bf16* resid, const float* rstats,
+                           int relu, bf16* y, hipStream_t s) {
+  if (!x || !stats || !y || M <= 0 || !chan_ok(C) || !al16(x) || !al16(y) || !al16(resid)) return hipErrorInvalidValue;
+  const long long chunks = M * (C >> 3);
+  hipLaunchKernelGGL(bn_apply_k, dim3(stream_grid(chunks)), dim3(256), 0, s, x, chunks, C, stats, resid, rstats, relu, y);
+  return hipGetLastError();
+}
+
+hipError_t launch_bn_bwd(const bf16* dy, const bf16* mask, const bf16* x, long long M, int C, const float* stats,
+                         float* part, float* coef, float* dgamma, float* dbeta, int accumulate, bf16* dx, hipStream_t s) {
+  if (!dy || !x || !stats || !part || !coef || !dgamma || !dbeta || !dx || M <= 0 || !chan_ok(C) || !al16(dy) ||
+      !al16(mask) || !al16(x) || !al16(dx))
+    return hipErrorInvalidValue;
+  const int blocks = bn_blocks(M, C);
+  hipLaunchKernelGGL(bn_bwd_part_k, dim3(blocks), dim3(256), 0, s, dy, mask, x, M, C, stats, part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(bn_bwd_final_k, dim3((C + 255) / 256), dim3(256), 0, s, part, blocks, M, C, coef, dgamma, dbeta, accumulate);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const long long chunks = M * (C >> 3);
+  hipLaunchKernelGGL(bn_bwd_apply_k, dim3(stream_grid(chunks)), dim3(256), 0, s, dy, mask, x, chunks, C, stats, coef, dx);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool_fwd(const bf16* x, bf16* y, long long n, int H, int W, int C, hipStream_t s) {
+  if (!x || !y || n <= 0 || H <= 0 || W <= 0 || H % 2 || W % 2 || !chan_ok(C) || !al16(x) || !al16(y)) return hipErrorInvalidValue;
+  const long long chunks = n * (H / 2) * (W / 2) * (C >> 3);
+  if ((chunks + 255) / 256 >= (1LL << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(maxpool_fwd_k, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, x, y, chunks, H, W, C);
+  return hipGetLastError();
+}
+
+hipError_t launch_maxpool_bwd(const bf16* x, const bf16* dy, bf16* dx, long long n, int H, int W, int C, hipStream_t s) {
+  if (!x || !dy || !dx || n <= 0 || H <= 0 || W <= 0 || H % 2 || W % 2 || !chan_ok(C) || !al16(x) || !al16(dy) || !al16(dx))
+    return hipErrorInvalidValue;
+  const long long chunks = n * H * W * (C >> 3);
+  if ((chunks + 255) / 256 >= (1LL << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(maxpool_bwd_k, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, x, dy, dx, chunks, H, W, C);
+  return hipGetLastError();
+}
+
+hipError_t launch_avgpool_fwd(const bf16* x, float* feats, long long n, int HW, int C, hipStream_t s) {
+  if (!x || !feats || n <= 0 || n >= (1LL << 31) || HW <= 0 || !chan_ok(C)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(avgpool_fwd_k, dim3((unsigned)n), dim3(256), 0, s, x, feats, HW, C);
+  return hipGetLastError();
+}
+
+hipError_t launch_avgpool_bwd(const float* dfeats, bf16* dx, long long n, int HW, int C, hipStream_t s) {
+  if (!dfeats || !dx || n <= 0 || HW <= 0 || !chan_ok(C) || !al16(dx)) return hipErrorInvalidValue;
+  const long long chunks = n * HW * (C >> 3);
+  hipLaunchKernelGGL(avgpool_bwd_k, dim3(stream_grid(chunks)), dim3(256), 0, s, dfeats, dx, chunks, HW, C);
+  return hipGetLastError();
+}
+
+hipError_t launch_add_masked(bf16* dst, const bf16* src, const bf16* mask, long long count, hipStream_t s) {
+  if (!dst || !src || !mask || count <= 0 || count % 8 || !al16(dst) || !al16(src) || !al16(mask)) return hipErrorInvalidValue;
+  const long long chunks = count / 8;
+  hipLaunchKernelGGL(add_masked_k, dim3(stream_grid(chunks)), dim3(256), 0, s, dst, src, mask, chunks);
+  return hipGetLastError();
+}
+
+}  // namespace sl

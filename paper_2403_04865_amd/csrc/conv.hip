@@ -1,0 +1,414 @@
+// Convolutions of the ResNet tile encoder on the bf16 matrix cores of gfx950 (v_mfma_f32_32x32x16_bf16, fp32
+// accumulation), as implicit GEMMs over channels-last activations: a tensor is a matrix [n * H * W][C], one row per
+// position, so a tap of a convolution is a row gather and a channel slice of a tap is 128 contiguous bytes.
+//
+//   conv_nt_k    : forward and input gradient.  out[M][N] = sum_taps gather_tap(src)[M][Cs] * W_tap[N][Cs]^T.  The
+//                  contraction index is (tap, channel); a K step is 64 channels of one tap, so the tap of a step is the
+//                  same for the whole workgroup and only the row addresses change from step to step.  Rows that fall
+//                  into the zero padding (or, for the input gradient of a strided convolution, between the taps) load
+//                  zeros.  128 x 128 (or 128 x 64) output tile, 4 wavefronts, operands one step ahead in registers,
+//                  two LDS stages, one barrier per step.  The MFMA takes the weights as its first operand, so a lane
+//                  ends up with four consecutive output channels of one row; the tile goes through LDS once and leaves
+//                  as whole 256-byte row segments.
+//   conv_wgrad_k : weight gradient.  dW[co][tap][ci] = sum_rows dout[row][co] * gather_tap(src)[row][ci]: the
+//                  contraction runs over the rows, so the 32-row slices go to LDS as they are and the MFMA operands
+//                  come from LDS transpose reads.  One workgroup owns a 64 x 64 block of (co, ci) for ALL taps (the
+//                  output-gradient slice is loaded once for the nine taps) over one slab of rows; slabs are added in
+//                  a fixed order by wgrad_reduce_k (no atomics: run-to-run identical), which also turns the
+//                  [co][tap][ci] order of the kernels into the parameter's [co][ci][kh][kw].
+#include "resnet_internal.h"
+
+namespace sl {
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ u32x4 ldg16(const bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+constexpr int ROW_ABSENT = -(1 << 20);   // y of a row past the end: no tap of it is ever inside a grid
+
+// source row of produced row (n, y, x) for tap (kh, kw), or -1
+__device__ __forceinline__ long long src_row(const ConvGeom& g, int n, int y, int x, int kh, int kw) {
+  int ys, xs;
+  bool ok;
+  if (!g.transposed) {
+    ys = y * g.stride + kh - g.pad;
+    xs = x * g.stride + kw - g.pad;
+    ok = (unsigned)ys < (unsigned)g.YS && (unsigned)xs < (unsigned)g.XS;
+  } else {
+    const int ty = y + g.pad - kh, tx = x + g.pad - kw;
+    const int sm = g.stride - 1, sh = g.stride >> 1;   // stride is 1 or 2
+    ok = ty >= 0 && tx >= 0 && !(ty & sm) && !(tx & sm);
+    ys = ty >> sh;
+    xs = tx >> sh;
+    ok = ok && ys < g.YS && xs < g.XS;
+  }
+  return ok ? ((long long)n * g.YS + ys) * g.XS + xs : -1;
+}
+
+__device__ __forceinline__ void row_pos(long long m, long long M, const ConvGeom& g, int& n, int& y, int& x) {
+  if (m < M) {
+    const unsigned plane = (unsigned)(g.YO * g.XO);
+    const unsigned mm = (unsigned)m;
+    const unsigned q = mm / plane, rem = mm - q * plane;
+    const unsigned yy = rem / (unsigned)g.XO;
+    n = (int)q; y = (int)yy; x = (int)(rem - yy * (unsigned)g.XO);
+  } else {
+    n = 0; y = ROW_ABSENT; x = 0;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// forward / input gradient
+// ---------------------------------------------------------------------------------------------------------------
+constexpr int CBM = 128, CBK = 64, CLD = CBK + 8;   // 144-byte LDS rows: conflict-free 16-byte reads
+
+template <int BN>
+__global__ void __launch_bounds__(256) conv_nt_k(ConvNT p, int row_tiles, int col_tiles) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* As = reinterpret_cast<bf16*>(smem);   // [2][CBM][CLD]
+  bf16* Bs = As + 2 * CBM * CLD;              // [2][BN][CLD]
+  // workgroup ids are dealt round-robin to the 8 XCDs: the column tiles of one row tile (which gather the same source
+  // rows) get ids of one XCD, one after the other
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int rt = (slot / col_tiles) * 8 + xcd, ct = slot % col_tiles;
+  if (rt >= row_tiles) return;
+  const long long m0 = (long long)rt * CBM;
+  const int n0 = ct * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  constexpr int WJ = BN / 64;   // 32-column blocks per wavefront
+  const int c = tid & 7, r0 = tid >> 3;
+  int pn[4], py[4], px[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) row_pos(m0 + r0 + 32 * i, p.M, p.g, pn[i], py[i], px[i]);
+  const int cpt = p.Cs / CBK;                 // K steps per tap
+  const int nk = p.g.KH * p.g.KW * cpt;
+  const long long ldw = (long long)nk * CBK;
+  const bf16* wp = p.W + (long long)(n0 + r0) * ldw + c * 8;
+  const bf16* sp = p.src + c * 8;
+
+  u32x4 ra[4], rb[BN / 32];
+  auto fetch = [&](int kt) {
+    const int tap = kt / cpt, c0 = (kt - tap * cpt) * CBK;
+    const int kh = tap / p.g.KW, kw = tap - kh * p.g.KW;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const long long sr = src_row(p.g, pn[i], py[i], px[i], kh, kw);
+      u32x4 v = ldg16(sp + (sr < 0 ? 0 : sr) * p.Cs + c0);   // no branch around the load
+      if (sr < 0) v = u32x4{0, 0, 0, 0};
+      ra[i] = v;
+    }
+#pragma unroll
+    for (int i = 0; i < BN / 32; ++i) rb[i] = ldg16(wp + (long long)(32 * i) * ldw + (long long)kt * CBK);
+  };
+  auto stash = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&As[st * CBM * CLD + (r0 + 32 * i) * CLD + c * 8]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < BN / 32; ++i) *reinterpret_cast<u32x4*>(&Bs[st * BN * CLD + (r0 + 32 * i) * CLD + c * 8]) = rb[i];
+  };
+
+  f32x16 acc[2][WJ];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < WJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int frow = lane & 31, fk = (lane >> 5) * 8;
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) fetch(kt + 1);
+    const bf16* as = As + cur * CBM * CLD + (wm * 64 + frow) * CLD + fk;
+    const bf16* bs = Bs + cur * BN * CLD + (wn * (BN / 2) + frow) * CLD + fk;
+#pragma unroll
+    for (int ks = 0; ks < CBK / 16; ++ks) {
+      bf16x8 fa[2], fb[WJ];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * CLD + ks * 16);
+#pragma unroll
+      for (int j = 0; j < WJ; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * CLD + ks * 16);
+      // weights first: the result block is [output channel][row], so lane l holds row l % 32 and the channels
+      // (r / 4) * 8 + (l / 32) * 4 + r % 4: four neighbours per register group
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < WJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) stash(cur ^ 1);   // the other stage: its readers finished before the last barrier
+    __syncthreads();
+  }
+
+  // the tile as bf16 through LDS (every operand read is behind the last barrier), then whole row segments
+  constexpr int CLDC = BN + 8;
+  bf16* Cs = reinterpret_cast<bf16*>(smem);
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < WJ; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = wm * 64 + i * 32 + (lane & 31);
+        const int col = wn * (BN / 2) + j * 32 + q * 8 + (lane >> 5) * 4;
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)acc[i][j][q * 4 + e];
+        *reinterpret_cast<bf16x4*>(&Cs[row * CLDC + col]) = v;
+      }
+  __syncthreads();
+  constexpr int CH = BN / 8;
+#pragma unroll
+  for (int it = 0; it < CBM * CH / 256; ++it) {
+    const int idx = tid + 256 * it;
+    const int row = idx / CH, ch = idx - row * CH;
+    const long long m = m0 + row;
+    if (m < p.M) {
+      u32x4 v = *reinterpret_cast<const u32x4*>(&Cs[row * CLDC + ch * 8]);
+      bf16* dst = p.out + m * p.N + n0 + ch * 8;
+      if (p.add) {
+        const u32x4 o = *reinterpret_cast<const u32x4*>(dst);
+        bf16x8 t;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          t[2 * w] = (bf16)(__uint_as_float(v[w] << 16) + __uint_as_float(o[w] << 16));
+          t[2 * w + 1] = (bf16)(__uint_as_float(v[w] & 0xffff0000u) + __uint_as_float(o[w] & 0xffff0000u));
+        }
+        *reinterpret_cast<bf16x8*>(dst) = t;
+      } else {
+        *reinterpret_cast<u32x4*>(dst) = v;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// weight gradient
+// ---------------------------------------------------------------------------------------------------------------
+constexpr int WBK = 32;   // rows per step
+
+// MFMA operand from a row-major LDS slice S[k][col] (row stride LDW elements): lane l gets column c0 + l % 32 and
+// the contraction indices k0 + 8 * (l / 32) + {0..7}.  A transpose read's group of 16 lanes addresses a 4-row x
+// 16-column patch and every lane receives one column of it.
+template <int LDW>
+__device__ __forceinline__ bf16x8 frag_tr(const bf16* S, int c0, int k0, int lane) {
+  const int g = lane >> 4, q = lane & 15;
+  const bf16* p = S + (k0 + 8 * (g >> 1) + (q >> 2)) * LDW + c0 + 16 * (g & 1) + (q & 3) * 4;
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * LDW));
+  s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+template <int TAPS>
+__global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
+  // LDS row of one contraction index: 64 output channels, then TAPS x 64 input channels; the pad makes the row stride
+  // 64 bytes modulo 256, which keeps the transpose reads free of bank conflicts
+  constexpr int LDW = 64 * (1 + TAPS) + 32;
+  __shared__ __attribute__((aligned(16))) bf16 S[WBK * LDW];
+  const int co0 = blockIdx.x * 64, ci0 = blockIdx.y * 64, slab = blockIdx.z;
+  const long long lo = (long long)slab * p.per;
+  const long long hi = lo + p.per < p.M ? lo + p.per : p.M;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int qa = wave >> 1, qb = wave & 1;
+  const int c = tid & 7, r = tid >> 3;
+  const bf16* dp = p.dout + co0 + c * 8;
+  const bf16* sp = p.src + ci0 + c * 8;
+
+  u32x4 rd, rs[TAPS];
+  auto fetch = [&](long long mstep) {   // only called with mstep < hi
+    const long long m = mstep + r;
+    const bool ok = m < hi;
+    const long long mc = ok ? m : hi - 1;
+    int n, y, x;
+    row_pos(mc, p.M, p.g, n, y, x);
+    u32x4 v = ldg16(dp + mc * p.Co);
+    if (!ok) v = u32x4{0, 0, 0, 0};
+    rd = v;
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) {
+      const int kh = TAPS == 1 ? 0 : t / 3, kw = TAPS == 1 ? 0 : t % 3;
+      const long long sr = src_row(p.g, n, y, x, kh, kw);
+      u32x4 w = ldg16(sp + (sr < 0 ? 0 : sr) * p.Cs);
+      if (sr < 0 || !ok) w = u32x4{0, 0, 0, 0};
+      rs[t] = w;
+    }
+  };
+  auto stash = [&]() {
+    *reinterpret_cast<u32x4*>(&S[r * LDW + c * 8]) = rd;
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) *reinterpret_cast<u32x4*>(&S[r * LDW + 64 + t * 64 + c * 8]) = rs[t];
+  };
+
+  f32x16 acc[TAPS];
+#pragma unroll
+  for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+
+  if (lo < hi) fetch(lo);
+  for (long long mstep = lo; mstep < hi; mstep += WBK) {
+    __syncthreads();   // the previous step's operand reads are done
+    stash();
+    __syncthreads();
+    if (mstep + WBK < hi) fetch(mstep + WBK);
+#pragma unroll
+    for (int kk = 0; kk < WBK; kk += 16) {
+      const bf16x8 fa = frag_tr<LDW>(S, qa * 32, kk, lane);
+#pragma unroll
+      for (int t = 0; t < TAPS; ++t) {
+        const bf16x8 fb = frag_tr<LDW>(S, 64 + t * 64 + qb * 32, kk, lane);
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[t], 0, 0, 0);
+      }
+    }
+  }
+  // block rows = output channels (r / 4) * 8 + (l / 32) * 4 + r % 4, block columns = input channels l % 32.  A slab
+  // without rows still writes its zeros: the reduction adds every slab.
+  const long long ldk = (long long)TAPS * p.Cs;
+  float* P = p.part + (long long)slab * p.Co * ldk;
+#pragma unroll
+  for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int co = co0 + qa * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+      P[(long long)co * ldk + (long long)t * p.Cs + ci0 + qb * 32 + (lane & 31)] = acc[t][e];
+    }
+}
+
+__global__ void __launch_bounds__(256) wgrad_reduce_k(const float* __restrict__ part, int slabs, int Co, int Cin, int taps,
+                                                       int ldk, float* __restrict__ dW, int accumulate) {
+  const int K = taps * Cin;
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long long)Co * K) return;
+  const int co = (int)(i / K), col = (int)(i - (long long)co * K);
+  const int tap = col / Cin, ci = col - tap * Cin;
+  float a = 0.f;
+  for (int s = 0; s < slabs; ++s) a += part[((long long)s * Co + co) * ldk + col];
+  const long long o = ((long long)co * Cin + ci) * taps + tap;
+  dW[o] = accumulate ? dW[o] + a : a;
+}
+
+__global__ void __launch_bounds__(256) conv_cast_w_k(const float* __restrict__ W, int Co, int Cin, int taps, int ldk,
+                                                      bf16* __restrict__ Wk, bf16* __restrict__ Wt) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long long)Co * ldk) return;
+  const int co = (int)(i / ldk), col = (int)(i - (long long)co * ldk);
+  float v = 0.f;
+  if (col < taps * Cin) {
+    const int tap = col / Cin, ci = col - tap * Cin;
+    v = W[((long long)co * Cin + ci) * taps + tap];
+    if (Wt) Wt[(long long)ci * taps * Co + (long long)tap * Co + co] = (bf16)v;
+  }
+  Wk[i] = (bf16)v;
+}
+
+// one thread per (row, chunk of 8 columns) of the spelled-out stem rows
+__global__ void __launch_bounds__(256) stem_im2col_k(const bf16* __restrict__ px, bf16* __restrict__ out, long long rows,
+                                                      int S, int OS) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= rows * 24) return;
+  const long long m = i / 24;
+  const int j = (int)(i - m * 24);
+  const unsigned plane = (unsigned)(OS * OS);
+  const unsigned mm = (unsigned)m;
+  const unsigned n = mm / plane, rem = mm - n * plane;
+  const int oy = (int)(rem / (unsigned)OS), ox = (int)(rem - (rem / (unsigned)OS) * (unsigned)OS);
+  bf16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int col = j * 8 + e;
+    const int tap = col / 3, ch = col - tap * 3;
+    const int kh = tap / 7, kw = tap - kh * 7;
+    const int iy = oy * 2 + kh - 3, ix = ox * 2 + kw - 3;
+    const bool ok = col < 147 && (unsigned)iy < (unsigned)S && (unsigned)ix < (unsigned)S;
+    const long long a = (((long long)n * 3 + ch) * S + (ok ? iy : 0)) * S + (ok ? ix : 0);
+    const bf16 t = px[col < 147 ? a : 0];
+    v[e] = ok ? t : (bf16)0.f;
+  }
+  *reinterpret_cast<bf16x8*>(out + m * 192 + j * 8) = v;
+}
+
+bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+bool geom_ok(const ConvGeom& g) {
+  return g.YO > 0 && g.XO > 0 && g.YS > 0 && g.XS > 0 && g.KH > 0 && g.KW > 0 && (g.stride == 1 || g.stride == 2) &&
+         g.pad >= 0 && g.pad < (1 << 10) && g.KH < (1 << 10) && g.KW < (1 << 10);
+}
+
+}  // namespace
+
+hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
+  if (!geom_ok(p.g) || p.M <= 0 || p.M >= (1LL << 31) - CBM || p.Cs <= 0 || p.Cs % CBK || p.N <= 0 || p.N % 64 ||
+      !al16(p.src) || !al16(p.W) || !al16(p.out) || p.M % ((long long)p.g.YO * p.g.XO))
+    return hipErrorInvalidValue;
+  // every source row index must fit the tensor the caller holds: n * YS * XS rows, n = M / (YO * XO)
+  const long long n = p.M / ((long long)p.g.YO * p.g.XO);
+  if (n * p.g.YS * p.g.XS >= (1LL << 31)) return hipErrorInvalidValue;
+  const int row_tiles = (int)((p.M + CBM - 1) / CBM);
+  const bool wide = p.N % 128 == 0;
+  const int col_tiles = p.N / (wide ? 128 : 64);
+  const unsigned grid = (unsigned)((row_tiles + 7) / 8 * 8) * (unsigned)col_tiles;
+  static bool attr_done = false;
+  const size_t lds_w = (size_t)2 * (CBM + 128) * CLD * sizeof(bf16), lds_n = (size_t)2 * (CBM + 64) * CLD * sizeof(bf16);
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)conv_nt_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)conv_nt_k<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_n);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if (wide) hipLaunchKernelGGL(conv_nt_k<128>, dim3(grid), dim3(256), lds_w, s, p, row_tiles, col_tiles);
+  else hipLaunchKernelGGL(conv_nt_k<64>, dim3(grid), dim3(256), lds_n, s, p, row_tiles, col_tiles);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s) {
+  const int taps = p.g.KH * p.g.KW;
+  if (!geom_ok(p.g) || p.g.transposed || (taps != 1 && !(p.g.KH == 3 && p.g.KW == 3)) || p.M <= 0 ||
+      p.M >= (1LL << 31) - WBK || p.Co <= 0 || p.Co % 64 || p.Cs <= 0 || p.Cs % 64 || p.slabs <= 0 || p.slabs > 65535 ||
+      p.per <= 0 || p.per % WBK || p.per * p.slabs < p.M || !al16(p.dout) || !al16(p.src) || !p.part ||
+      p.M % ((long long)p.g.YO * p.g.XO))
+    return hipErrorInvalidValue;
+  const long long n = p.M / ((long long)p.g.YO * p.g.XO);
+  if (n * p.g.YS * p.g.XS >= (1LL << 31)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)(p.Co / 64), (unsigned)(p.Cs / 64), (unsigned)p.slabs);
+  if (taps == 1) hipLaunchKernelGGL(conv_wgrad_k<1>, grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(conv_wgrad_k<9>, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_wgrad_reduce(const float* part, int slabs, int Co, int Cin, int taps, int ldk, float* dW, int accumulate,
+                               hipStream_t s) {
+  if (!part || !dW || slabs <= 0 || Co <= 0 || Cin <= 0 || taps <= 0 || ldk < taps * Cin) return hipErrorInvalidValue;
+  const long long total = (long long)Co * taps * Cin;
+  hipLaunchKernelGGL(wgrad_reduce_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, part, slabs, Co, Cin, taps, ldk,
+                     dW, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_cast_w(const float* W, int Co, int Cin, int taps, int ldk, bf16* Wk, bf16* Wt, hipStream_t s) {
+  if (!W || !Wk || Co <= 0 || Cin <= 0 || taps <= 0 || ldk < taps * Cin) return hipErrorInvalidValue;
+  const long long total = (long long)Co * ldk;
+  hipLaunchKernelGGL(conv_cast_w_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, W, Co, Cin, taps, ldk, Wk, Wt);
+  return hipGetLastError();
+}
+
+hipError_t launch_stem_im2col(const bf16* pixels, bf16* out, long long n, int S, hipStream_t s) {
+  if (!pixels || !out || n <= 0 || S <= 0 || S % 2 || !al16(out)) return hipErrorInvalidValue;
+  const int OS = S / 2;
+  const long long rows = n * OS * OS;
+  if (rows >= (1LL << 31) / 24) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stem_im2col_k, dim3((unsigned)((rows * 24 + 255) / 256)), dim3(256), 0, s, pixels, out, rows, S, OS);
+  return hipGetLastError();
+}
+
+}  // namespace sl

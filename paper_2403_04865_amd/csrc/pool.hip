@@ -7,10 +7,12 @@
 
 namespace sl {
 
-constexpr int PR = 16;  // rows per group
+constexpr int PR_WIDE = 16;   // rows per group
+constexpr int PR_NARROW = 8;  // ... where 16 rows of features do not fit the LDS (feature width 2048)
 
 // Gate activations of PR feature rows held in LDS (hs [PR][D] fp32):
 // tl[r][j] = tanh(V_j.h_r + bV_j), sg[r][j] = sigmoid(U_j.h_r + bU_j).  One wave per gate unit j.
+template <int PR>
 __device__ __forceinline__ void gate_rows(const float* hs, int D, int Mh, const float* __restrict__ VW,
                                           const float* __restrict__ Vb, const float* __restrict__ UW,
                                           const float* __restrict__ Ub, float* tl, float* sg) {
@@ -44,6 +46,7 @@ __device__ __forceinline__ void gate_rows(const float* hs, int D, int Mh, const 
   }
 }
 
+template <int PR>
 __device__ __forceinline__ void load_rows(const float* __restrict__ H, long long n0, long long N, int D, float* hs) {
   for (int i = threadIdx.x; i < PR * D; i += 256) {
     long long n = n0 + i / D;
@@ -52,6 +55,7 @@ __device__ __forceinline__ void load_rows(const float* __restrict__ H, long long
 }
 
 // forward, stage 1: attention logits a[n] and per-workgroup partials part[b] = {max, sum, zsum[D]}
+template <int PR>
 __global__ void __launch_bounds__(256) pool_gate_part_k(PoolArgs p) {
   extern __shared__ float lds[];
   int D = p.D, Mh = p.Mh;
@@ -70,9 +74,9 @@ __global__ void __launch_bounds__(256) pool_gate_part_k(PoolArgs p) {
   for (long long gi = blockIdx.x; gi < groups; gi += gridDim.x) {
     long long n0 = gi * PR;
     __syncthreads();
-    load_rows(H, n0, p.N, D, hs);
+    load_rows<PR>(H, n0, p.N, D, hs);
     __syncthreads();
-    gate_rows(hs, D, Mh, p.VW, p.Vb, p.UW, p.Ub, tl, sg);
+    gate_rows<PR>(hs, D, Mh, p.VW, p.Vb, p.UW, p.Ub, tl, sg);
     __syncthreads();
     if (threadIdx.x < PR) {
       int r = threadIdx.x;
@@ -241,6 +245,7 @@ __global__ void __launch_bounds__(256) pool_alpha_k(const float* __restrict__ a,
 //   [0,Mh)   dpV = da * w * s * (1 - t^2)     (gradient at V's pre-activation)
 //   [Mh,2Mh) dpU = da * w * t * s * (1 - s)   (gradient at U's pre-activation)
 //   [2Mh,3Mh) da * t * s                      (summed over rows this is dw)
+template <int PR>
 __global__ void __launch_bounds__(256) pool_bwd_rows_k(PoolArgs p, float* __restrict__ Dp) {
   extern __shared__ float lds[];
   int D = p.D, Mh = p.Mh, C = p.C;
@@ -261,9 +266,9 @@ __global__ void __launch_bounds__(256) pool_bwd_rows_k(PoolArgs p, float* __rest
   for (long long gi = blockIdx.x; gi < groups; gi += gridDim.x) {
     long long n0 = gi * PR;
     __syncthreads();
-    load_rows(H, n0, p.N, D, hs);
+    load_rows<PR>(H, n0, p.N, D, hs);
     __syncthreads();
-    gate_rows(hs, D, Mh, p.VW, p.Vb, p.UW, p.Ub, tl, sg);
+    gate_rows<PR>(hs, D, Mh, p.VW, p.Vb, p.UW, p.Ub, tl, sg);
     for (int r = w; r < PR; r += 4) {  // softmax backward: da_n = alpha_n (h_n - z) . dz
       float acc = 0.f;
       for (int d = lane; d < D; d += 64) acc += ((hs[r * D + d] - zv[d]) - zlo[d]) * dz[d];
@@ -326,13 +331,15 @@ __global__ void __launch_bounds__(256) pool_head_grads_k(PoolArgs p) {
 }
 
 int pool_blocks(long long N) {
-  long long g = (N + PR - 1) / PR;
+  long long g = (N + PR_WIDE - 1) / PR_WIDE;
   if (g > 1024) g = 1024;
   if (g < 1) g = 1;
   return (int)g;
 }
 
-static size_t pool_lds(int D, int Mh) { return ((size_t)PR * D + 2 * PR * Mh + 2 * PR + 2 * D) * sizeof(float); }
+static size_t pool_lds(int PR, int D, int Mh) { return ((size_t)PR * D + 2 * PR * Mh + 2 * PR + 2 * D) * sizeof(float); }
+// rows per group: 16 where that fits the 160 KB of LDS, else 8
+static int pool_pr(int D, int Mh) { return pool_lds(PR_WIDE, D, Mh) <= 160 * 1024 ? PR_WIDE : PR_NARROW; }
 
 template <typename K>
 static hipError_t set_lds(K kernel, size_t bytes) {
@@ -342,7 +349,8 @@ static hipError_t set_lds(K kernel, size_t bytes) {
 
 hipError_t launch_pool_fwd(const PoolArgs& p0, hipStream_t s) {
   PoolArgs p = p0;
-  size_t lds = pool_lds(p.D, p.Mh);
+  const int pr = pool_pr(p.D, p.Mh);
+  size_t lds = pool_lds(pr, p.D, p.Mh);
   hipError_t e;
   if (p.use_mfma && pool_mfma_ok(p)) {
     // persistent grid: one workgroup per compute unit (it owns almost all of the unit's LDS)
@@ -360,8 +368,13 @@ hipError_t launch_pool_fwd(const PoolArgs& p0, hipStream_t s) {
     if (p.blocks > 1024) p.blocks = 1024;
     if ((e = launch_pool_gate_part_mfma(p, s)) != hipSuccess) return e;
   } else {
-    if ((e = set_lds(pool_gate_part_k, lds)) != hipSuccess) return e;
-    hipLaunchKernelGGL(pool_gate_part_k, dim3(p.blocks), dim3(256), lds, s, p);
+    if (pr == PR_WIDE) {
+      if ((e = set_lds(pool_gate_part_k<PR_WIDE>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL(pool_gate_part_k<PR_WIDE>, dim3(p.blocks), dim3(256), lds, s, p);
+    } else {
+      if ((e = set_lds(pool_gate_part_k<PR_NARROW>, lds)) != hipSuccess) return e;
+      hipLaunchKernelGGL(pool_gate_part_k<PR_NARROW>, dim3(p.blocks), dim3(256), lds, s, p);
+    }
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   if (p.blocks > 1024) return hipErrorInvalidValue;
@@ -377,10 +390,16 @@ hipError_t launch_pool_fwd(const PoolArgs& p0, hipStream_t s) {
 }
 
 hipError_t launch_pool_bwd_rows(const PoolArgs& p, float* Dp, hipStream_t s) {
-  size_t lds = pool_lds(p.D, p.Mh);
+  const int pr = pool_pr(p.D, p.Mh);
+  size_t lds = pool_lds(pr, p.D, p.Mh);
   hipError_t e;
-  if ((e = set_lds(pool_bwd_rows_k, lds)) != hipSuccess) return e;
-  hipLaunchKernelGGL(pool_bwd_rows_k, dim3(p.blocks), dim3(256), lds, s, p, Dp);
+  if (pr == PR_WIDE) {
+    if ((e = set_lds(pool_bwd_rows_k<PR_WIDE>, lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL(pool_bwd_rows_k<PR_WIDE>, dim3(p.blocks), dim3(256), lds, s, p, Dp);
+  } else {
+    if ((e = set_lds(pool_bwd_rows_k<PR_NARROW>, lds)) != hipSuccess) return e;
+    hipLaunchKernelGGL(pool_bwd_rows_k<PR_NARROW>, dim3(p.blocks), dim3(256), lds, s, p, Dp);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   return launch_pool_head_grads(p, s);
 }

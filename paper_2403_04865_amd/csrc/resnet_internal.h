@@ -1,0 +1,79 @@
+// Internal declarations of the convolutional (ResNet) tile encoder of libslide (gfx950 only).
+// Activations are bf16, channels-last: a tensor is a matrix [n * H * W][C] whose row is one position of one tile.
+#pragma once
+#include "slide_internal.h"
+
+namespace sl {
+
+// How the rows of a convolution's source tensor are found from the rows being produced.
+//   transposed == 0 (forward, weight gradient): produced row (n, y, x), tap (kh, kw) -> source position
+//       (y * stride + kh - pad, x * stride + kw - pad), absent outside the source grid (zero padding).
+//   transposed == 1 (input gradient): produced row (n, y, x) is an INPUT position, the source is the output
+//       gradient: tap (kh, kw) -> ((y + pad - kh) / stride, (x + pad - kw) / stride), absent unless both
+//       divisions are exact and the result lies in the source grid.
+struct ConvGeom {
+  int YO, XO;   // grid of the produced rows
+  int YS, XS;   // grid of the source rows
+  int KH, KW, stride, pad;
+  int transposed;
+};
+
+// out[M][N] (bf16) = sum over taps of src_tap[M][Cs] * W[N][tap * Cs .. + Cs]^T   (+ out when add != 0).
+// M = n * YO * XO < 2^31, Cs % 64 == 0, N % 64 == 0; W row stride = KH * KW * Cs.
+struct ConvNT {
+  const bf16* src; int Cs;
+  const bf16* W;
+  bf16* out; int N;
+  long long M;
+  ConvGeom g;
+  int add;
+};
+hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s);
+
+// part[slab][Co][KH * KW * Cs] (fp32) = sum over the slab's rows m of dout[m][co] * src_tap(m)[ci]; the rows
+// (n, y, x) run over the OUTPUT grid of the convolution (geometry not transposed).  Co % 64 == 0, Cs % 64 == 0,
+// KH * KW is 1 or 9.  Slab s covers rows [s * per, (s + 1) * per), per % 32 == 0.
+struct ConvWG {
+  const bf16* dout; int Co;
+  const bf16* src; int Cs;
+  float* part;
+  long long M;
+  ConvGeom g;
+  int slabs; long long per;
+};
+hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s);
+
+// dW[co][ci][kh][kw] (fp32, the parameter's own layout) = (accumulate ? dW : 0) + sum_s part[s][co][tap * Cin + ci],
+// part row stride ldk (>= taps * Cin)
+hipError_t launch_wgrad_reduce(const float* part, int slabs, int Co, int Cin, int taps, int ldk, float* dW, int accumulate,
+                               hipStream_t s);
+// fp32 W[co][ci][kh][kw] -> bf16 Wk[co][ldk] (column tap * Cin + ci, zero beyond taps * Cin) and, if Wt is not null,
+// Wt[ci][tap * Co + co]
+hipError_t launch_conv_cast_w(const float* W, int Co, int Cin, int taps, int ldk, bf16* Wk, bf16* Wt, hipStream_t s);
+// rows of the 7x7 stride-2 pad-3 stem convolution spelled out: out[(n, oy, ox)][tap * 3 + c], 192 columns (147 used,
+// the rest zero) from planar pixels [n][3][S][S] (bf16)
+hipError_t launch_stem_im2col(const bf16* pixels, bf16* out, long long n, int S, hipStream_t s);
+
+// ---- batch normalisation over all rows of [M][C] (C % 8 == 0, C <= 2048) --------------------------------------------
+// stats: [4][C] floats: mean, 1 / sqrt(var + eps), a = gamma * rstd, b = beta - mean * a
+int bn_blocks(long long M, int C);
+hipError_t launch_bn_stats(const bf16* x, long long M, int C, const float* gamma, const float* beta, float eps,
+                           float* part, float* stats, hipStream_t s);
+// y = a x + b  (+ resid, or + ra resid + rb when rstats is not null), then max(., 0) when relu
+hipError_t launch_bn_apply(const bf16* x, long long M, int C, const float* stats, const bf16* resid, const float* rstats,
+                           int relu, bf16* y, hipStream_t s);
+// dz = (mask == null || mask > 0) ? dy : 0;  dgamma = sum dz x_hat, dbeta = sum dz (written or added to the
+// parameter gradients); dx = a (dz - dbeta / M - x_hat dgamma / M)
+hipError_t launch_bn_bwd(const bf16* dy, const bf16* mask, const bf16* x, long long M, int C, const float* stats,
+                         float* part, float* coef, float* dgamma, float* dbeta, int accumulate, bf16* dx, hipStream_t s);
+
+// 3x3 stride-2 pad-1 max pooling on [n][H][W][C]; of equal maxima the first in (kh, kw) order takes the gradient
+hipError_t launch_maxpool_fwd(const bf16* x, bf16* y, long long n, int H, int W, int C, hipStream_t s);
+hipError_t launch_maxpool_bwd(const bf16* x, const bf16* dy, bf16* dx, long long n, int H, int W, int C, hipStream_t s);
+// global average over the HW positions of each tile: feats [n][C] fp32; and its gradient
+hipError_t launch_avgpool_fwd(const bf16* x, float* feats, long long n, int HW, int C, hipStream_t s);
+hipError_t launch_avgpool_bwd(const float* dfeats, bf16* dx, long long n, int HW, int C, hipStream_t s);
+// dst += (mask > 0 ? src : 0), count elements (a multiple of 8)
+hipError_t launch_add_masked(bf16* dst, const bf16* src, const bf16* mask, long long count, hipStream_t s);
+
+}  // namespace sl

@@ -2,6 +2,7 @@
 #include "../../include/slide.h"
 #include "../../include/slide_prof.h"
 #include "slide_internal.h"
+#include "run_internal.h"
 
 #include <string>
 #include <vector>
@@ -16,9 +17,9 @@ using namespace sl;
 // per device (static_scratch below) and passes that pointer on.
 static __device__ __align__(256) unsigned char scratch[SLIDE_STATIC_POOL_BYTES];
 
-namespace {
+thread_local int sl::g_last_hip = 0;
 
-thread_local int g_last_hip = 0;
+namespace {
 
 // device address of `scratch` on the current device (looked up on the first call per device), or null with *err set
 constexpr int kMaxDevices = 64;
@@ -47,17 +48,6 @@ enum KernelId {
 const char* const kKernelNames[K_COUNT] = {
   "gemm_nt", "gemm_tn", "attn_fwd", "attn_bwd", "ln_fwd", "ln_bwd", "colsum", "pool_fwd", "pool_bwd", "elementwise",
   "cls_lane"};
-
-struct Prof {
-  bool active = false;
-  int id = -1;                 // family being recorded, SLIDE_PROF_ALL = every family
-  int count = 0;
-  std::vector<hipEvent_t> ev;  // 2 per launch
-  std::vector<int> fam;        // family of recorded launch i
-  // per family, filled by launch() (flops, bytes, n) and slide_prof_end (ms)
-  double flops[K_COUNT] = {}, bytes[K_COUNT] = {}, ms[K_COUNT] = {};
-  int n[K_COUNT] = {};
-};
 
 struct Tensor { std::string name; size_t off, len; };
 
@@ -108,6 +98,7 @@ struct slide_ctx {
   int step_label = 0;
   bool use_mfma = true;
   bool use_lane = false;      // bf16 path: the CLS rows' stream and row-wise work are repeated in fp32 (cls_lane.hip)
+  bool pool_only = false;     // aggregator of another encoder family: only mil.* / head.* exist, encoder calls are refused
   Prof prof;
 };
 
@@ -218,41 +209,7 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   return y;
 }
 
-struct Run {
-  slide_ctx* c;
-  hipStream_t s;
-  hipError_t err = hipSuccess;
-  bool ok() const { return err == hipSuccess; }
-};
-
-// Launch wrapper: skips work after the first failure and records profiling events.
-template <typename F>
-void launch(Run& r, int id, double flops, double bytes, F f) {
-  if (!r.ok()) return;
-  Prof& p = r.c->prof;
-  bool rec = p.active && (p.id == id || p.id == SLIDE_PROF_ALL) && p.count < SLIDE_PROF_MAX;
-  if (rec) {
-    while ((int)p.ev.size() < 2 * (p.count + 1)) {
-      hipEvent_t e;
-      if (hipEventCreate(&e) != hipSuccess) { rec = false; break; }
-      p.ev.push_back(e);
-    }
-  }
-  if (rec) (void)hipEventRecord(p.ev[2 * p.count], r.s);
-  hipError_t e = f();
-  if (rec) {
-    (void)hipEventRecord(p.ev[2 * p.count + 1], r.s);
-    if ((int)p.fam.size() <= p.count) p.fam.resize(p.count + 1);
-    p.fam[p.count] = id;
-    p.count++;
-    p.flops[id] += flops;
-    p.bytes[id] += bytes;
-    p.n[id]++;
-  }
-  if (e != hipSuccess) { r.err = e; g_last_hip = (int)e; }
-}
-
-int finish(Run& r) { return r.ok() ? SLIDE_OK : SLIDE_EHIP; }
+typedef RunT<slide_ctx> Run;
 
 const void* weight(const slide_ctx* c, int idx) {  // [out][in] in T
   const ShadowMat& m = c->sh[idx];
@@ -509,6 +466,7 @@ void block_fwd(Run& r, const Layout& y, int l, long long n, bool replay) {
 // ------------------------------------------------------------------------------------------
 int enc_fwd(slide_ctx* c, const void* pixels, long long n, void* feats_out, bool save, long long pool_N,
             hipStream_t s) {
+  if (c->pool_only) return SLIDE_EUNSUPPORTED;
   int keep = !save ? KEEP_NONE : (c->cfg.recompute ? KEEP_INPUTS : KEEP_ALL);
   Layout y = make_layout(c, n, pool_N, keep);
   if (y.total > c->arena_bytes) return SLIDE_EARENA;
@@ -553,6 +511,7 @@ int enc_fwd(slide_ctx* c, const void* pixels, long long n, void* feats_out, bool
 // encoder backward
 // ------------------------------------------------------------------------------------------
 int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void* pixel_grad, hipStream_t s) {
+  if (c->pool_only) return SLIDE_EUNSUPPORTED;
   if (!c->enc_saved || c->enc_n != n) return SLIDE_ESTATE;
   const Layout& y = c->enc_layout;
   Run r{c, s};
@@ -774,6 +733,34 @@ int pool_bwd(slide_ctx* c, const Layout& y, const void* feats, long long N, int 
 
 }  // namespace
 
+// A context that holds the aggregator alone (tensors mil.V.W, mil.V.b, mil.U.W, mil.U.b, mil.w, head.W, head.b in
+// this order from offset 0): the other encoder families run mil_pool_fwd / mil_pool_bwd on it over their own features.
+int sl::pool_ctx_create(int D, int Mh, int C, int dt, slide_ctx** out) {
+  if (!out) return SLIDE_EINVAL;
+  *out = nullptr;
+  if (D <= 0 || Mh <= 0 || C <= 0 || (dt != DT_F32 && dt != DT_BF16)) return SLIDE_EINVAL;
+  if (D > 2048 || C > 64 || Mh > 1024) return SLIDE_EUNSUPPORTED;   // 8 feature rows + gate rows must fit the LDS
+  slide_ctx* c = new (std::nothrow) slide_ctx();
+  if (!c) return SLIDE_EINVAL;
+  c->cfg = slide_config{};
+  c->cfg.dim = D; c->cfg.mil_hidden = Mh; c->cfg.n_classes = C; c->cfg.dtype = dt;
+  c->g = 0; c->g2 = 0; c->T = 1; c->D = D; c->F = D; c->Kp = 0; c->dh = D; c->L = 0; c->H = 1;
+  c->Mh = Mh; c->C = C; c->dt = dt;
+  c->pool_only = true;
+  c->o_VW = add_tensor(c, "mil.V.W", (size_t)Mh * D);
+  c->o_Vb = add_tensor(c, "mil.V.b", Mh);
+  c->o_UW = add_tensor(c, "mil.U.W", (size_t)Mh * D);
+  c->o_Ub = add_tensor(c, "mil.U.b", Mh);
+  c->o_w = add_tensor(c, "mil.w", Mh);
+  c->o_cW = add_tensor(c, "head.W", (size_t)C * D);
+  c->o_cb = add_tensor(c, "head.b", C);
+  c->max_w = (size_t)Mh * D;
+  c->use_mfma = true;
+  c->use_lane = false;
+  *out = c;
+  return SLIDE_OK;
+}
+
 // ============================================================================================
 // C ABI
 // ============================================================================================
@@ -846,7 +833,7 @@ int slide_ctx_create(const slide_config* cfg, slide_ctx** out) {
 
 void slide_ctx_destroy(slide_ctx* c) {
   if (!c) return;
-  for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
+  prof_destroy(c->prof);
   delete c;
 }
 
@@ -1061,42 +1048,18 @@ const void* slide_feature_grads(const slide_ctx* c) {
 int slide_last_hip_error(void) { return g_last_hip; }
 
 int slide_prof_begin(slide_ctx* c, int kernel_id) {
-  if (!c || kernel_id < SLIDE_PROF_ALL || kernel_id >= K_COUNT) return SLIDE_EINVAL;
-  Prof& p = c->prof;
-  p.active = true; p.id = kernel_id; p.count = 0;
-  for (int k = 0; k < K_COUNT; ++k) { p.flops[k] = p.bytes[k] = p.ms[k] = 0; p.n[k] = 0; }
-  return SLIDE_OK;
+  if (!c) return SLIDE_EINVAL;
+  return prof_begin(c->prof, kernel_id, K_COUNT);
 }
 
 int slide_prof_end(slide_ctx* c, double* total_ms, int* launches, double* flops, double* bytes) {
   if (!c) return SLIDE_EINVAL;
-  Prof& p = c->prof;
-  int rc = SLIDE_OK;
-  for (int i = 0; i < p.count; ++i) {
-    float ms = 0.f;
-    hipError_t e = hipEventSynchronize(p.ev[2 * i + 1]);
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]);
-    if (e != hipSuccess) { g_last_hip = (int)e; rc = SLIDE_EHIP; break; }
-    p.ms[p.fam[i]] += ms;
-  }
-  double tot = 0, fl = 0, by = 0;
-  for (int k = 0; k < K_COUNT; ++k) { tot += p.ms[k]; fl += p.flops[k]; by += p.bytes[k]; }
-  if (total_ms) *total_ms = tot;
-  if (launches) *launches = p.count;
-  if (flops) *flops = fl;
-  if (bytes) *bytes = by;
-  p.active = false;
-  return rc;
+  return prof_end(c->prof, total_ms, launches, flops, bytes);
 }
 
 int slide_prof_family(const slide_ctx* c, int kernel_id, double* total_ms, int* launches, double* flops, double* bytes) {
-  if (!c || kernel_id < 0 || kernel_id >= K_COUNT) return SLIDE_EINVAL;
-  const Prof& p = c->prof;
-  if (total_ms) *total_ms = p.ms[kernel_id];
-  if (launches) *launches = p.n[kernel_id];
-  if (flops) *flops = p.flops[kernel_id];
-  if (bytes) *bytes = p.bytes[kernel_id];
-  return SLIDE_OK;
+  if (!c) return SLIDE_EINVAL;
+  return prof_family(c->prof, kernel_id, K_COUNT, total_ms, launches, flops, bytes);
 }
 
 int slide_adamw_step(float* params, const float* grads, float* m, float* v, size_t count, int64_t step, float lr,

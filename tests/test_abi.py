@@ -21,11 +21,12 @@ def lib():
 
 
 def test_header_symbols_exported(lib):
-    hdr = open(os.path.join(ROOT, "include", "slide.h")).read() + open(os.path.join(ROOT, "include", "slide_prof.h")).read()
+    hdr = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b([a-z_0-9]+)\s*\(", hdr)) - {"defined"}
-    names = {n for n in names if n.startswith(("slide_", "encoder_", "mil_"))}
-    assert {"slide_step_fwd", "slide_step_bwd", "encoder_fwd_tiles", "mil_pool_fwd", "mil_pool_bwd"} <= names
+    names = {n for n in names if n.startswith(("slide_", "encoder_", "mil_", "resnet_"))}
+    assert {"slide_step_fwd", "slide_step_bwd", "encoder_fwd_tiles", "mil_pool_fwd", "mil_pool_bwd",
+            "resnet_slide_step_fwd", "resnet_slide_step_bwd", "resnet_encoder_fwd_tiles"} <= names
     for n in sorted(names):
         assert hasattr(lib, n), n
 
@@ -121,3 +122,46 @@ def test_paper_capacity_arithmetic_and_arena_accounting():
     # the same accounting puts the paper's largest slide, with per-block recompute, inside one 288 GB device
     lib_r = SlideLib(lib_config(cfg, 1, 1))
     assert lib_r.slide_arena_bytes(16384) < 288e9 < lib.slide_arena_bytes(16384)
+
+
+def test_resnet_layout_validation_and_arena(lib):
+    """Host side of include/resnet.h: tensor order and sizes are those of the generator (and so of the oracle), bad
+    shapes are refused, the arena grows with the tile count and the paper's per-device shares fit one device."""
+    from paper_2403_04865_amd import ResNetLib, ResNetConfig, SlideError, resnet_config_from
+    for name in ("rn_tiny", "rn_tiny_bneck", "rn18", "rn50"):
+        cfg, n = gen.RESNET_CONFIGS[name]
+        L = ResNetLib(resnet_config_from(cfg))
+        assert L.resnet_feature_dim() == cfg.dim
+        lay = L.param_layout()
+        shapes = gen.resnet_param_shapes(cfg)
+        assert [a for a, _, _ in lay] == [a for a, _ in shapes]
+        off = 0
+        for (nm, o, ln), (_, shp) in zip(lay, shapes):
+            size = 1
+            for d in shp:
+                size *= d
+            assert o == off and ln == size, nm
+            off += ln
+        assert off == L.resnet_param_count()
+        assert L.resnet_arena_bytes(0) == 0
+        sizes = [L.resnet_arena_bytes(k) for k in (1, max(2, n // 2), n)]
+        assert sizes == sorted(sizes) and all(b % 256 == 0 for b in sizes)
+        if name in ("rn18", "rn50"):
+            # 4,096 ResNet18 tiles (one device's share of the whole-slide breast experiment) and 1,848 ResNet50 tiles
+            # (the most the paper fits on 80 GB with 16-bit activations) each fit the 288 GB device with their pixels
+            assert sizes[-1] + n * 3 * 224 * 224 * 2 < 270e9, (name, sizes[-1])
+    ok = dict(tile=64, block=0, depths=(1, 1, 1, 1), width=64, mil_hidden=32, n_classes=1)
+    ResNetLib(ResNetConfig(**ok))
+    for bad in (dict(tile=48), dict(block=2), dict(depths=(1, 0, 1, 1)), dict(n_classes=0), dict(bn_eps=0.0)):
+        with pytest.raises(SlideError) as e:
+            ResNetLib(ResNetConfig(**{**ok, **bad}))
+        assert e.value.code == -1
+    for bad in (dict(width=8), dict(width=96), dict(width=128, block=1)):
+        with pytest.raises(SlideError) as e:
+            ResNetLib(ResNetConfig(**{**ok, **bad}))
+        assert e.value.code == -3
+    L = ResNetLib(ResNetConfig(**ok))
+    with pytest.raises(SlideError) as e:
+        L._check(L.lib.resnet_slide_step_bwd(L.ctx, 0, None), "resnet_slide_step_bwd")
+    assert e.value.code == -4
+    assert L.kernel_names()[0] == "conv_fwd"

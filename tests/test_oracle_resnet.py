@@ -276,3 +276,35 @@ def test_batch_statistics_couple_the_tiles():
     H_all = ro.encoder_fwd(prm, X, cfg)[0]
     H_two = ro.encoder_fwd(prm, X[:2], cfg)[0]
     assert np.abs(H_all[:2] - H_two).max() > 1e-3
+
+
+def test_storage_hook_points_and_default():
+    """`store` is applied exactly where a 16-bit path writes an activation (every convolution output, every ReLU
+    output), the default is the plain float64 definition, and with rounding to bfloat16 the masks of the backward are
+    taken on the rounded values."""
+    cfg, prm, X, label = _case("rn_probe")
+    seen = []
+
+    def spy(a):
+        seen.append(a.shape)
+        return a
+
+    plain = ro.slide_step(prm, X, label, cfg)
+    spied = ro.slide_step(prm, X, label, cfg, store=spy)
+    assert plain["loss"] == spied["loss"]
+    for k, v in plain["grads"].items():
+        assert np.array_equal(v, spied["grads"][k]), k
+    blocks = rgen.resnet_blocks(cfg)
+    convs = 1 + sum(2 + int(b["down"]) for b in blocks)      # basic blocks
+    relus = 1 + 2 * len(blocks)
+    assert len(seen) == convs + relus
+
+    def bf16(a):
+        return gen.to_bf16_grid(a.astype(np.float32)).astype(np.float64)
+
+    H, cache = ro.encoder_fwd(prm, X, cfg, store=bf16)
+    for ks, rs, kd, out in cache["blocks"]:
+        for t in rs + [out]:
+            assert np.array_equal(t, bf16(t))
+    rel = np.linalg.norm(H - plain["H"]) / np.linalg.norm(plain["H"])
+    assert 1e-4 < rel < 5e-2      # 16-bit storage moves the features by a fraction of a percent, not more
