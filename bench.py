@@ -6,6 +6,7 @@ over every tile, gated-attention pool forward and backward, all parameter gradie
 synthetic slide that is already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large|medium|small|full]
+    python bench.py --workload rn18|rn50      the same step with a ResNet tile encoder (include/resnet.h)
 """
 from __future__ import annotations
 
@@ -165,6 +166,134 @@ def calib_copy(a):
     print(json.dumps({"calib_copy_bytes": n, "launches": 4}))
 
 
+def resnet_model_flops_per_tile(cfg):
+    """Model FLOPs of one tile through the ResNet encoder, forward + backward: 2 * positions * Cout * Cin * k * k per
+    convolution; backward = input gradient + weight gradient of every convolution except the stem's input gradient."""
+    import gen
+    S = cfg.tile
+    fwd = 2.0 * (S // 2) ** 2 * cfg.width * 3 * 49
+    bwd = fwd
+    H = S // 4
+    for b in gen.resnet_blocks(cfg):
+        Ho = H // b["stride"]
+        if cfg.block == "basic":
+            convs = [(Ho, b["mid"], b["cin"], 3), (Ho, b["cout"], b["mid"], 3)]
+        else:
+            convs = [(H, b["mid"], b["cin"], 1), (Ho, b["mid"], b["mid"], 3), (Ho, b["cout"], b["mid"], 1)]
+        if b["down"]:
+            convs.append((Ho, b["cout"], b["cin"], 1))
+        f = sum(2.0 * h * h * co * ci * k * k for h, co, ci, k in convs)
+        fwd += f
+        bwd += 2 * f
+        H = Ho
+    return fwd + bwd
+
+
+def resnet_bench(a):
+    """The slide step with a ResNet tile encoder (resnet_slide_step_fwd + resnet_slide_step_bwd) on one synthetic slide
+    resident in HBM; same output contract as the default run."""
+    import numpy as np
+    import torch
+    import gen
+    from paper_2403_04865_amd import ResNetLib, resnet_config_from
+    cfg, N = gen.RESNET_CONFIGS[a.workload]
+    if a.tiles:
+        N = a.tiles
+    ds, ws, ls = gen.RESNET_SEEDS[a.workload]
+    dev = torch.device("cuda:0")
+    lib = ResNetLib(resnet_config_from(cfg))
+    prm = gen.make_resnet_params(cfg, ws)
+    flat = np.zeros(lib.resnet_param_count(), dtype=np.float32)
+    for name, off, ln in lib.param_layout():
+        flat[off:off + ln] = prm[name].reshape(-1)
+    params = torch.from_numpy(flat).to(dev)
+    grads = torch.zeros_like(params)
+    nbytes = lib.resnet_arena_bytes(N)
+    arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    o = (-arena.data_ptr()) % 256
+    arena = arena[o:o + nbytes]
+    lib.resnet_bind(params, grads, arena)
+    t0 = time.time()
+    px = torch.empty((N, 3, cfg.tile, cfg.tile), dtype=torch.bfloat16, device=dev)
+    workers = min(16, os.cpu_count() or 1)
+    for lo in range(0, N, 512):
+        hi = min(N, lo + 512)
+        px[lo:hi] = torch.from_numpy(gen.make_pixels(cfg, hi - lo, ds, first_tile=lo, workers=workers)).to(dev).to(torch.bfloat16)
+    rng = np.random.Generator(np.random.PCG64(ls))
+    label = int(rng.random() < 0.5) if cfg.n_classes == 1 else int(rng.integers(0, cfg.n_classes))
+    gen_s = time.time() - t0
+    loss = torch.zeros(1, device=dev)
+    logits = torch.zeros(cfg.n_classes, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def one_step():
+        lib.resnet_slide_step_fwd(px, N, label, loss, logits, None, stream)
+        lib.resnet_slide_step_bwd(0, stream)
+
+    for _ in range(a.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    names = lib.kernel_names()
+    prof = a.prof_kernel if a.prof_kernel in names else "conv_fwd"
+    lib.resnet_prof_begin(names.index(prof))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    k_ms, k_n, k_flops, k_bytes = lib.resnet_prof_end()
+    peak_alloc = torch.cuda.max_memory_allocated() / 1e9
+    stored = load_traffic(a.workload) if not a.tiles else None
+    roof = roofline_of(prof, k_ms, k_n, k_flops, k_bytes, dt * 1e3, (stored or {}).get(prof))
+    lib.resnet_prof_begin(-1)
+    t1 = time.perf_counter()
+    one_step()
+    torch.cuda.synchronize()
+    all_ms = (time.perf_counter() - t1) * 1e3
+    lib.resnet_prof_end()
+    roof_all = []
+    for i, nm in enumerate(names):
+        f_ms, f_n, f_fl, f_by = lib.resnet_prof_family(i)
+        if f_n:
+            roof_all.append(roofline_of(nm, f_ms, f_n, f_fl, f_by, all_ms, (stored or {}).get(nm)))
+    roof_all.sort(key=lambda r: -(r["share_of_step"] or 0))
+    tiles_per_s = N * a.steps / dt
+    mflops = resnet_model_flops_per_tile(cfg)
+    cpu = None
+    if not a.no_cpu_baseline:
+        from oracle import resnet_oracle as ro
+        from threadpoolctl import threadpool_info
+        nt = min(a.cpu_tiles, N)
+        Xc = px[:nt].float().cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        ro.slide_step({k: v.astype(np.float64) for k, v in prm.items()}, Xc, label, cfg)
+        cs = time.perf_counter() - t0
+        cores = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+        cpu = {"value": round(nt / cs, 3), "unit": "tiles/s", "cores": cores, "kind": "oracle",
+               "sample": f"{nt} tiles of the same slide, fp64 numpy oracle, full fwd+bwd step"}
+    out = {
+        "metric": "tiles/sec fwd+bwd per slide step (1 MI355X); MFMA util % of bf16 peak",
+        "value": round(tiles_per_s, 2), "unit": "tiles/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(dt / a.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: {N} tiles {cfg.tile}x{cfg.tile}x3, ResNet {cfg.block} blocks {list(cfg.depths)} "
+                               f"width {cfg.width}, batch statistics over all tiles, gated-attention MIL hidden "
+                               f"{cfg.mil_hidden}, {cfg.n_classes} classes",
+                   "tiles": N, "slide_steps_per_s": round(a.steps / dt, 4),
+                   "model_gflop_per_tile": round(mflops / 1e9, 3),
+                   "mfu_bf16_peak": round(tiles_per_s * mflops / PEAK["mfma_bf16"], 4),
+                   "activation_policy": "all activations kept",
+                   "arena_gb": round(nbytes / 1e9, 2), "peak_alloc_gb_of_288": round(peak_alloc, 2),
+                   "loss": float(loss.item()), "input_gen_s": round(gen_s, 1)},
+        "roofline": roof, "roofline_all": roof_all,
+        "traffic_source": None if stored is None else {"kind": "stored", "file": f"profiles/traffic_{a.workload}.json",
+                                                       "measured_at_commit": stored.get("_commit")},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
 def load_traffic(workload, kernel=None):
     """HBM bytes per launch of `kernel` measured with rocprofv3 --pmc (profiles/traffic_<workload>.json, written by
     `python -m paper_2403_04865_amd.pmc_traffic`; a STORED figure of an earlier run, not measured by this one: the
@@ -178,7 +307,8 @@ def load_traffic(workload, kernel=None):
     return d if kernel is None else d.get(kernel)
 
 
-HBM_BOUND = ("ln_fwd", "ln_bwd", "pool_fwd", "pool_bwd", "colsum", "elementwise")
+HBM_BOUND = ("ln_fwd", "ln_bwd", "pool_fwd", "pool_bwd", "colsum", "elementwise",
+             "bn_stats", "bn_apply", "bn_bwd", "pooling", "mil_pool")
 
 
 def roofline_of(name, ms, n, flops, nbytes, step_ms, traffic):
@@ -232,9 +362,12 @@ def main():
     if a.calib_copy:
         return calib_copy(a)
 
+    import gen
+    if a.workload in gen.RESNET_CONFIGS:
+        return resnet_bench(a)
+
     import numpy as np
     import torch
-    import gen
     from paper_2403_04865_amd import config_from as lib_config
     from paper_2403_04865_amd import SlideLib
 

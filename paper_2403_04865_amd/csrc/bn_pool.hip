@@ -4,7 +4,7 @@
 //
 // Reductions over the rows (statistics, gain / shift gradients) are two-stage and deterministic: a fixed number of
 // workgroups each sums a contiguous range of rows in fp32 (8 channels per thread, rows strided over the threads, then
-// one pass through LDS), and one thread per channel adds the workgroups' partial sums in double, in order.
+// one pass through LDS), and one wavefront per channel adds the workgroups' partial sums in double, in a fixed order.
 #include "resnet_internal.h"
 
 namespace sl {
@@ -68,13 +68,27 @@ __global__ void __launch_bounds__(256) bn_stats_part_k(const bf16* __restrict__ 
   });
 }
 
+// The workgroups' partial sums of one channel, added in double by one wavefront: lane l takes partials l, l + 64, ...
+// in order, then the lanes are combined in a fixed butterfly (the same bits on every run).
+__device__ __forceinline__ void channel_sums(const float* __restrict__ part, int blocks, int C, int ch, double& s, double& q) {
+  const int lane = threadIdx.x & 63;
+  s = 0.0; q = 0.0;
+  for (int b = lane; b < blocks; b += 64) {
+    s += (double)part[((long long)b * 2) * C + ch];
+    q += (double)part[((long long)b * 2 + 1) * C + ch];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { s += __shfl_xor(s, o, 64); q += __shfl_xor(q, o, 64); }
+}
+
 __global__ void __launch_bounds__(256) bn_stats_final_k(const float* __restrict__ part, int blocks, long long M, int C,
                                                          const float* __restrict__ gamma, const float* __restrict__ beta,
                                                          float eps, float* __restrict__ stats) {
-  const int ch = blockIdx.x * 256 + threadIdx.x;
+  const int ch = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (ch >= C) return;
-  double s = 0.0, q = 0.0;
-  for (int b = 0; b < blocks; ++b) { s += (double)part[((long long)b * 2) * C + ch]; q += (double)part[((long long)b * 2 + 1) * C + ch]; }
+  double s, q;
+  channel_sums(part, blocks, C, ch, s, q);
+  if (threadIdx.x & 63) return;
   const double mean = s / (double)M;
   double var = q / (double)M - mean * mean;
   if (var < 0.0) var = 0.0;
@@ -132,10 +146,11 @@ __global__ void __launch_bounds__(256) bn_bwd_part_k(const bf16* __restrict__ dy
 __global__ void __launch_bounds__(256) bn_bwd_final_k(const float* __restrict__ part, int blocks, long long M, int C,
                                                        float* __restrict__ coef, float* __restrict__ dgamma,
                                                        float* __restrict__ dbeta, int accumulate) {
-  const int ch = blockIdx.x * 256 + threadIdx.x;
+  const int ch = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (ch >= C) return;
-  double s = 0.0, q = 0.0;
-  for (int b = 0; b < blocks; ++b) { s += (double)part[((long long)b * 2) * C + ch]; q += (double)part[((long long)b * 2 + 1) * C + ch]; }
+  double s, q;
+  channel_sums(part, blocks, C, ch, s, q);
+  if (threadIdx.x & 63) return;
   coef[ch] = (float)(s / (double)M);
   coef[C + ch] = (float)(q / (double)M);
   dbeta[ch] = accumulate ? dbeta[ch] + (float)s : (float)s;
@@ -168,8 +183,10 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_k(const bf16* __restrict__ d
 }
 
 // ---- pooling ---------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) maxpool_fwd_k(const bf16* __restrict__ x, bf16* __restrict__ y, long long chunks,
-                                                      int H, int W, int C) {
+// forward: the maximum and, per output element, which of the nine taps it came from (the first in (kh, kw) order of
+// equal maxima), one byte each
+__global__ void __launch_bounds__(256) maxpool_fwd_k(const bf16* __restrict__ x, bf16* __restrict__ y,
+                                                      unsigned char* __restrict__ arg, long long chunks, int H, int W, int C) {
   const int tcols = C >> 3, OH = H / 2, OW = W / 2;
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i >= chunks) return;
@@ -179,8 +196,9 @@ __global__ void __launch_bounds__(256) maxpool_fwd_k(const bf16* __restrict__ x,
   const int oy = (int)(pos % OH);
   const long long n = pos / OH;
   float best[8];
+  unsigned at[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+  for (int e = 0; e < 8; ++e) { best[e] = -INFINITY; at[e] = 0; }
   for (int kh = 0; kh < 3; ++kh)
     for (int kw = 0; kw < 3; ++kw) {
       const int iy = 2 * oy + kh - 1, ix = 2 * ox + kw - 1;
@@ -188,15 +206,20 @@ __global__ void __launch_bounds__(256) maxpool_fwd_k(const bf16* __restrict__ x,
         float v[8];
         unpack8(ld16(x + (((n * H + iy) * W + ix) * C + tc * 8)), v);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], v[e]);
+        for (int e = 0; e < 8; ++e)
+          if (v[e] > best[e]) { best[e] = v[e]; at[e] = (unsigned)(kh * 3 + kw); }
       }
     }
   st8(y + i * 8, best);
+  uint2 packed;
+  packed.x = at[0] | (at[1] << 8) | (at[2] << 16) | (at[3] << 24);
+  packed.y = at[4] | (at[5] << 8) | (at[6] << 16) | (at[7] << 24);
+  *reinterpret_cast<uint2*>(arg + i * 8) = packed;
 }
 
-// one thread per input position and 8 channels: for each of the (at most four) windows that contain the position,
-// find the window's first maximum in (kh, kw) order again and take the window's gradient if it is this position
-__global__ void __launch_bounds__(256) maxpool_bwd_k(const bf16* __restrict__ x, const bf16* __restrict__ dy,
+// one thread per input position and 8 channels: each of the (at most four) windows that contain the position hands
+// over its gradient if its stored tap is this position
+__global__ void __launch_bounds__(256) maxpool_bwd_k(const unsigned char* __restrict__ arg, const bf16* __restrict__ dy,
                                                       bf16* __restrict__ dx, long long chunks, int H, int W, int C) {
   const int tcols = C >> 3, OH = H / 2, OW = W / 2;
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -216,26 +239,16 @@ __global__ void __launch_bounds__(256) maxpool_bwd_k(const bf16* __restrict__ x,
     for (int b = 0; b < nx; ++b) {
       const int oy = oy0 + a, ox = ox0 + b;
       if (oy >= OH || ox >= OW) continue;
-      const int mine = (iy - 2 * oy + 1) * 3 + (ix - 2 * ox + 1);
-      float best[8];
-      int at[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { best[e] = -INFINITY; at[e] = -1; }
-      for (int kh = 0; kh < 3; ++kh)
-        for (int kw = 0; kw < 3; ++kw) {
-          const int sy = 2 * oy + kh - 1, sx = 2 * ox + kw - 1;
-          if ((unsigned)sy < (unsigned)H && (unsigned)sx < (unsigned)W) {
-            float v[8];
-            unpack8(ld16(x + (((n * H + sy) * W + sx) * C + tc * 8)), v);
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (v[e] > best[e]) { best[e] = v[e]; at[e] = kh * 3 + kw; }
-          }
-        }
+      const unsigned mine = (unsigned)((iy - 2 * oy + 1) * 3 + (ix - 2 * ox + 1));
+      const long long o = (((n * OH + oy) * OW + ox) * C + tc * 8);
+      const uint2 t = *reinterpret_cast<const uint2*>(arg + o);
       float d[8];
-      unpack8(ld16(dy + (((n * OH + oy) * OW + ox) * C + tc * 8)), d);
+      unpack8(ld16(dy + o), d);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) g[e] += at[e] == mine ? d[e] : 0.f;
+      for (int e = 0; e < 8; ++e) {
+        const unsigned at = ((e < 4 ? t.x : t.y) >> (8 * (e & 3))) & 0xffu;
+        g[e] += at == mine ? d[e] : 0.f;
+      }
     }
   st8(dx + i * 8, g);
 }
@@ -300,7 +313,7 @@ hipError_t launch_bn_stats(const bf16* x, long long M, int C, const float* gamma
   hipLaunchKernelGGL(bn_stats_part_k, dim3(blocks), dim3(256), 0, s, x, M, C, part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bn_stats_final_k, dim3((C + 255) / 256), dim3(256), 0, s, part, blocks, M, C, gamma, beta, eps, stats);
+  hipLaunchKernelGGL(bn_stats_final_k, dim3((C + 3) / 4), dim3(256), 0, s, part, blocks, M, C, gamma, beta, eps, stats);
   return hipGetLastError();
 }
 
@@ -321,7 +334,7 @@ hipError_t launch_bn_bwd(const bf16* dy, const bf16* mask, const bf16* x, long l
   hipLaunchKernelGGL(bn_bwd_part_k, dim3(blocks), dim3(256), 0, s, dy, mask, x, M, C, stats, part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bn_bwd_final_k, dim3((C + 255) / 256), dim3(256), 0, s, part, blocks, M, C, coef, dgamma, dbeta, accumulate);
+  hipLaunchKernelGGL(bn_bwd_final_k, dim3((C + 3) / 4), dim3(256), 0, s, part, blocks, M, C, coef, dgamma, dbeta, accumulate);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const long long chunks = M * (C >> 3);
@@ -329,20 +342,22 @@ hipError_t launch_bn_bwd(const bf16* dy, const bf16* mask, const bf16* x, long l
   return hipGetLastError();
 }
 
-hipError_t launch_maxpool_fwd(const bf16* x, bf16* y, long long n, int H, int W, int C, hipStream_t s) {
-  if (!x || !y || n <= 0 || H <= 0 || W <= 0 || H % 2 || W % 2 || !chan_ok(C) || !al16(x) || !al16(y)) return hipErrorInvalidValue;
+hipError_t launch_maxpool_fwd(const bf16* x, bf16* y, unsigned char* arg, long long n, int H, int W, int C, hipStream_t s) {
+  if (!x || !y || !arg || ((uintptr_t)arg & 7) || n <= 0 || H <= 0 || W <= 0 || H % 2 || W % 2 || !chan_ok(C) || !al16(x) || !al16(y)) return hipErrorInvalidValue;
   const long long chunks = n * (H / 2) * (W / 2) * (C >> 3);
   if ((chunks + 255) / 256 >= (1LL << 31)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(maxpool_fwd_k, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, x, y, chunks, H, W, C);
+  hipLaunchKernelGGL(maxpool_fwd_k, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, x, y, arg, chunks, H, W, C);
   return hipGetLastError();
 }
 
-hipError_t launch_maxpool_bwd(const bf16* x, const bf16* dy, bf16* dx, long long n, int H, int W, int C, hipStream_t s) {
-  if (!x || !dy || !dx || n <= 0 || H <= 0 || W <= 0 || H % 2 || W % 2 || !chan_ok(C) || !al16(x) || !al16(dy) || !al16(dx))
+hipError_t launch_maxpool_bwd(const unsigned char* arg, const bf16* dy, bf16* dx, long long n, int H, int W, int C,
+                              hipStream_t s) {
+  if (!arg || !dy || !dx || n <= 0 || H <= 0 || W <= 0 || H % 2 || W % 2 || !chan_ok(C) || ((uintptr_t)arg & 7) || !al16(dy) ||
+      !al16(dx))
     return hipErrorInvalidValue;
   const long long chunks = n * H * W * (C >> 3);
   if ((chunks + 255) / 256 >= (1LL << 31)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(maxpool_bwd_k, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, x, dy, dx, chunks, H, W, C);
+  hipLaunchKernelGGL(maxpool_bwd_k, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, arg, dy, dx, chunks, H, W, C);
   return hipGetLastError();
 }
 

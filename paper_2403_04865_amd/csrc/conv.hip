@@ -8,8 +8,8 @@
 //                  into the zero padding (or, for the input gradient of a strided convolution, between the taps) load
 //                  zeros.  128 x 128 (or 128 x 64) output tile, 4 wavefronts, operands one step ahead in registers,
 //                  two LDS stages, one barrier per step.  The MFMA takes the weights as its first operand, so a lane
-//                  ends up with four consecutive output channels of one row; the tile goes through LDS once and leaves
-//                  as whole 256-byte row segments.
+//                  ends up with four consecutive output channels of one row; the tile goes through LDS once (fp32)
+//                  and leaves as whole 256-byte row segments, rounded once.
 //   conv_wgrad_k : weight gradient.  dW[co][tap][ci] = sum_rows dout[row][co] * gather_tap(src)[row][ci]: the
 //                  contraction runs over the rows, so the 32-row slices go to LDS as they are and the MFMA operands
 //                  come from LDS transpose reads.  One workgroup owns a 64 x 64 block of (co, ci) for ALL taps (the
@@ -149,9 +149,11 @@ __global__ void __launch_bounds__(256) conv_nt_k(ConvNT p, int row_tiles, int co
     __syncthreads();
   }
 
-  // the tile as bf16 through LDS (every operand read is behind the last barrier), then whole row segments
-  constexpr int CLDC = BN + 8;
-  bf16* Cs = reinterpret_cast<bf16*>(smem);
+  // the tile through LDS in fp32 (every operand read is behind the last barrier), then whole row segments: what is
+  // added on the way (the output's old value, the shortcut's gradient) is added to the unrounded sums, so every
+  // stored element is rounded once
+  constexpr int CLDC = BN + 4;
+  float* Cs = reinterpret_cast<float*>(smem);
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -160,10 +162,8 @@ __global__ void __launch_bounds__(256) conv_nt_k(ConvNT p, int row_tiles, int co
       for (int q = 0; q < 4; ++q) {
         const int row = wm * 64 + i * 32 + (lane & 31);
         const int col = wn * (BN / 2) + j * 32 + q * 8 + (lane >> 5) * 4;
-        bf16x4 v;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (bf16)acc[i][j][q * 4 + e];
-        *reinterpret_cast<bf16x4*>(&Cs[row * CLDC + col]) = v;
+        *reinterpret_cast<float4*>(&Cs[row * CLDC + col]) =
+            make_float4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
       }
   __syncthreads();
   constexpr int CH = BN / 8;
@@ -173,20 +173,28 @@ __global__ void __launch_bounds__(256) conv_nt_k(ConvNT p, int row_tiles, int co
     const int row = idx / CH, ch = idx - row * CH;
     const long long m = m0 + row;
     if (m < p.M) {
-      u32x4 v = *reinterpret_cast<const u32x4*>(&Cs[row * CLDC + ch * 8]);
-      bf16* dst = p.out + m * p.N + n0 + ch * 8;
+      const float4 lo = *reinterpret_cast<const float4*>(&Cs[row * CLDC + ch * 8]);
+      const float4 hi = *reinterpret_cast<const float4*>(&Cs[row * CLDC + ch * 8 + 4]);
+      float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      const long long at = m * p.N + n0 + ch * 8;
       if (p.add) {
-        const u32x4 o = *reinterpret_cast<const u32x4*>(dst);
-        bf16x8 t;
+        const u32x4 o = *reinterpret_cast<const u32x4*>(p.out + at);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { f[2 * w] += __uint_as_float(o[w] << 16); f[2 * w + 1] += __uint_as_float(o[w] & 0xffff0000u); }
+      }
+      if (p.extra) {
+        const u32x4 x = *reinterpret_cast<const u32x4*>(p.extra + at);
+        const u32x4 k = *reinterpret_cast<const u32x4*>(p.mask + at);
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          t[2 * w] = (bf16)(__uint_as_float(v[w] << 16) + __uint_as_float(o[w] << 16));
-          t[2 * w + 1] = (bf16)(__uint_as_float(v[w] & 0xffff0000u) + __uint_as_float(o[w] & 0xffff0000u));
+          f[2 * w] += __uint_as_float(k[w] << 16) > 0.f ? __uint_as_float(x[w] << 16) : 0.f;
+          f[2 * w + 1] += __uint_as_float(k[w] & 0xffff0000u) > 0.f ? __uint_as_float(x[w] & 0xffff0000u) : 0.f;
         }
-        *reinterpret_cast<bf16x8*>(dst) = t;
-      } else {
-        *reinterpret_cast<u32x4*>(dst) = v;
       }
+      bf16x8 t;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t[e] = (bf16)f[e];
+      *reinterpret_cast<bf16x8*>(p.out + at) = t;
     }
   }
 }
@@ -348,7 +356,8 @@ bool geom_ok(const ConvGeom& g) {
 
 hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
   if (!geom_ok(p.g) || p.M <= 0 || p.M >= (1LL << 31) - CBM || p.Cs <= 0 || p.Cs % CBK || p.N <= 0 || p.N % 64 ||
-      !al16(p.src) || !al16(p.W) || !al16(p.out) || p.M % ((long long)p.g.YO * p.g.XO))
+      !al16(p.src) || !al16(p.W) || !al16(p.out) || !al16(p.extra) || !al16(p.mask) || (p.extra && !p.mask) ||
+      p.M % ((long long)p.g.YO * p.g.XO))
     return hipErrorInvalidValue;
   // every source row index must fit the tensor the caller holds: n * YS * XS rows, n = M / (YO * XO)
   const long long n = p.M / ((long long)p.g.YO * p.g.XO);

@@ -18,8 +18,10 @@ struct ConvGeom {
   int transposed;
 };
 
-// out[M][N] (bf16) = sum over taps of src_tap[M][Cs] * W[N][tap * Cs .. + Cs]^T   (+ out when add != 0).
-// M = n * YO * XO < 2^31, Cs % 64 == 0, N % 64 == 0; W row stride = KH * KW * Cs.
+// out[M][N] (bf16) = sum over taps of src_tap[M][Cs] * W[N][tap * Cs .. + Cs]^T
+//                    (+ out when add != 0)  (+ (mask > 0 ? extra : 0) when extra is not null; extra, mask: [M][N]).
+// The sums are formed in fp32 and rounded once.  M = n * YO * XO < 2^31, Cs % 64 == 0, N % 64 == 0; W row stride =
+// KH * KW * Cs.
 struct ConvNT {
   const bf16* src; int Cs;
   const bf16* W;
@@ -27,6 +29,7 @@ struct ConvNT {
   long long M;
   ConvGeom g;
   int add;
+  const bf16* extra; const bf16* mask;
 };
 hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s);
 
@@ -67,9 +70,11 @@ hipError_t launch_bn_apply(const bf16* x, long long M, int C, const float* stats
 hipError_t launch_bn_bwd(const bf16* dy, const bf16* mask, const bf16* x, long long M, int C, const float* stats,
                          float* part, float* coef, float* dgamma, float* dbeta, int accumulate, bf16* dx, hipStream_t s);
 
-// 3x3 stride-2 pad-1 max pooling on [n][H][W][C]; of equal maxima the first in (kh, kw) order takes the gradient
-hipError_t launch_maxpool_fwd(const bf16* x, bf16* y, long long n, int H, int W, int C, hipStream_t s);
-hipError_t launch_maxpool_bwd(const bf16* x, const bf16* dy, bf16* dx, long long n, int H, int W, int C, hipStream_t s);
+// 3x3 stride-2 pad-1 max pooling on [n][H][W][C]; of equal maxima the first in (kh, kw) order takes the gradient.
+// arg: one byte per output element (the winning tap), written by the forward, read by the backward
+hipError_t launch_maxpool_fwd(const bf16* x, bf16* y, unsigned char* arg, long long n, int H, int W, int C, hipStream_t s);
+hipError_t launch_maxpool_bwd(const unsigned char* arg, const bf16* dy, bf16* dx, long long n, int H, int W, int C,
+                              hipStream_t s);
 // global average over the HW positions of each tile: feats [n][C] fp32; and its gradient
 hipError_t launch_avgpool_fwd(const bf16* x, float* feats, long long n, int HW, int C, hipStream_t s);
 hipError_t launch_avgpool_bwd(const float* dfeats, bf16* dx, long long n, int HW, int C, hipStream_t s);

@@ -47,7 +47,7 @@ struct BlockL {
 
 struct RLayout {
   size_t total = 0;
-  size_t pool, pool_bytes, H, G, bnpart, coef, wpart, wpart_bytes, gA, gB, gC;
+  size_t pool, pool_bytes, H, G, bnpart, coef, wpart, wpart_bytes, parg, gA, gB, gC;
 };
 
 }  // namespace
@@ -141,6 +141,7 @@ RLayout make_layout(resnet_ctx* c, long long n, bool commit) {
     size_t o = take(nn * a.H * a.H * a.C * 2);
     if (commit) a.off = o;
   }
+  y.parg = take(nn * (c->S / 4) * (c->S / 4) * c->cfg.width);   // winning taps of the max pooling, one byte each
   y.gA = take(nn * c->max_act * 2);
   y.gB = take(nn * c->max_act * 2);
   y.gC = take(nn * c->max_act * 2);
@@ -232,8 +233,10 @@ void conv_wgrad(Run& r, int id, long long n, const bf16* dout, int accumulate) {
   });
 }
 
-// gradient with respect to the convolution's source rows; add != 0 adds to what dsrc holds
-void conv_dgrad(Run& r, int id, long long n, const bf16* dout, bf16* dsrc, int add) {
+// gradient with respect to the convolution's source rows; add != 0 adds to what dsrc holds; extra (with mask): also
+// adds extra where mask > 0 (the gradient that reaches the block input through an identity shortcut)
+void conv_dgrad(Run& r, int id, long long n, const bf16* dout, bf16* dsrc, int add, const bf16* extra = nullptr,
+                const bf16* mask = nullptr) {
   resnet_ctx* c = r.c;
   const ConvL& L = c->convs[id];
   ConvNT p{};
@@ -241,10 +244,10 @@ void conv_dgrad(Run& r, int id, long long n, const bf16* dout, bf16* dsrc, int a
   p.M = rows_of(c, L.t_src, n);
   p.g.YO = p.g.XO = L.kinH; p.g.YS = p.g.XS = L.outH; p.g.KH = p.g.KW = L.kK; p.g.stride = L.kstride; p.g.pad = L.kpad;
   p.g.transposed = 1;
-  p.add = add;
+  p.add = add; p.extra = extra; p.mask = mask;
   const double K = (double)L.Cin * L.K * L.K;
   launch(r, RK_CONV_DGRAD, 2.0 * rows_of(c, L.t_conv, n) * L.Cout * K,
-         ((double)p.M * L.kCs * (add ? 2 : 1) + (double)rows_of(c, L.t_conv, n) * L.Cout) * 2,
+         ((double)p.M * L.kCs * (add ? 2 : (extra ? 3 : 1)) + (double)rows_of(c, L.t_conv, n) * L.Cout) * 2,
          [&] { return launch_conv_nt(p, r.s); });
 }
 
@@ -268,8 +271,11 @@ int enc_fwd(resnet_ctx* c, const void* pixels, long long n, void* feats_out, hip
   bn_apply(r, 0, n, nullptr, nullptr, act(c, c->t_r0));
   {
     const Act& a = c->acts[c->t_r0];
-    launch(r, RK_POOLING, 0, (double)rows_of(c, c->t_r0, n) * a.C * 2 * 1.25,
-           [&] { return launch_maxpool_fwd(act(c, c->t_r0), act(c, c->t_p0), n, a.H, a.H, a.C, s); });
+    launch(r, RK_POOLING, 0, (double)rows_of(c, c->t_r0, n) * a.C * 2 * 1.375,
+           [&] {
+             return launch_maxpool_fwd(act(c, c->t_r0), act(c, c->t_p0), (unsigned char*)(c->arena + c->lay.parg), n, a.H,
+                                       a.H, a.C, s);
+           });
   }
   for (const BlockL& b : c->blocks) {
     for (int k = 0; k < b.nconv; ++k) {
@@ -308,7 +314,10 @@ int enc_bwd(resnet_ctx* c, const void* dfeats, long long n, int accumulate, hipS
     bn_bwd(r, b.conv[b.nconv - 1], n, gA, out, gB, accumulate);
     for (int k = b.nconv - 1; k >= 0; --k) {
       conv_wgrad(r, b.conv[k], n, gB, accumulate);
-      conv_dgrad(r, b.conv[k], n, gB, gC, 0);
+      // the last input gradient of a block with an identity shortcut takes the shortcut's gradient along (one rounding
+      // of the sum, no pass of its own)
+      if (k == 0 && b.down < 0) conv_dgrad(r, b.conv[k], n, gB, gC, 0, gA, out);
+      else conv_dgrad(r, b.conv[k], n, gB, gC, 0);
       if (k > 0) bn_bwd(r, b.conv[k - 1], n, gC, act(c, b.t_r[k - 1]), gB, accumulate);
     }
     // gC: gradient at the block's input through the residual branch; add the shortcut's
@@ -316,17 +325,15 @@ int enc_bwd(resnet_ctx* c, const void* dfeats, long long n, int accumulate, hipS
       bn_bwd(r, b.down, n, gA, out, gB, accumulate);
       conv_wgrad(r, b.down, n, gB, accumulate);
       conv_dgrad(r, b.down, n, gB, gC, 1);
-    } else {
-      const long long count = rows_of(c, b.t_in, n) * c->acts[b.t_in].C;
-      launch(r, RK_ELEMWISE, 0, (double)count * 2 * 4, [&] { return launch_add_masked(gC, gA, out, count, s); });
     }
     bf16* t = gA; gA = gC; gC = t;
   }
   // stem: max pooling, ReLU + batch normalisation, weight gradient (no pixel gradient)
   {
     const Act& a = c->acts[c->t_r0];
-    launch(r, RK_POOLING, 0, (double)rows_of(c, c->t_r0, n) * a.C * 2 * 2.25,
-           [&] { return launch_maxpool_bwd(act(c, c->t_r0), gA, gB, n, a.H, a.H, a.C, s); });
+    launch(r, RK_POOLING, 0, (double)rows_of(c, c->t_r0, n) * a.C * 2 * 1.375, [&] {
+      return launch_maxpool_bwd((const unsigned char*)(c->arena + c->lay.parg), gA, gB, n, a.H, a.H, a.C, s);
+    });
     bn_bwd(r, 0, n, gB, act(c, c->t_r0), gC, accumulate);
     conv_wgrad(r, 0, n, gC, accumulate);
   }
