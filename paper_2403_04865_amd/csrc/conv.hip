@@ -2,14 +2,13 @@
 // accumulation), as implicit GEMMs over channels-last activations: a tensor is a matrix [n * H * W][C], one row per
 // position, so a tap of a convolution is a row gather and a channel slice of a tap is 128 contiguous bytes.
 //
-//   conv_nt_k    : forward and input gradient.  out[M][N] = sum_taps gather_tap(src)[M][Cs] * W_tap[N][Cs]^T.  The
+//   conv_nt_dl_k : forward and input gradient.  out[M][N] = sum_taps gather_tap(src)[M][Cs] * W_tap[N][Cs]^T.  The
 //                  contraction index is (tap, channel); a K step is 64 channels of one tap, so the tap of a step is the
 //                  same for the whole workgroup and only the row addresses change from step to step.  Rows that fall
-//                  into the zero padding (or, for the input gradient of a strided convolution, between the taps) load
-//                  zeros.  128 x 128 (or 128 x 64) output tile, 4 wavefronts, operands one step ahead in registers,
-//                  two LDS stages, one barrier per step.  The MFMA takes the weights as its first operand, so a lane
-//                  ends up with four consecutive output channels of one row; the tile goes through LDS once (fp32)
-//                  and leaves as whole 256-byte row segments, rounded once.
+//                  into the zero padding (or, for the input gradient of a strided convolution, between the taps) read
+//                  zeros.  Operands go from global memory straight into LDS (see the kernel).  The MFMA takes the
+//                  weights as its first operand, so a lane ends up with four consecutive output channels of one row;
+//                  the tile goes through LDS once (fp32) and leaves as whole row segments, rounded once.
 //   conv_wgrad_k : weight gradient.  dW[co][tap][ci] = sum_rows dout[row][co] * gather_tap(src)[row][ci]: the
 //                  contraction runs over the rows, so the 32-row slices go to LDS as they are and the MFMA operands
 //                  come from LDS transpose reads.  One workgroup owns a 64 x 64 block of (co, ci) for ALL taps (the
@@ -34,20 +33,20 @@ constexpr int ROW_ABSENT = -(1 << 20);   // y of a row past the end: no tap of i
 // source row of produced row (n, y, x) for tap (kh, kw), or -1
 __device__ __forceinline__ long long src_row(const ConvGeom& g, int n, int y, int x, int kh, int kw) {
   int ys, xs;
-  bool ok;
+  bool ok;   // bitwise combinations: no branch per condition
   if (!g.transposed) {
     ys = y * g.stride + kh - g.pad;
     xs = x * g.stride + kw - g.pad;
-    ok = (unsigned)ys < (unsigned)g.YS && (unsigned)xs < (unsigned)g.XS;
+    ok = ((unsigned)ys < (unsigned)g.YS) & ((unsigned)xs < (unsigned)g.XS);
   } else {
     const int ty = y + g.pad - kh, tx = x + g.pad - kw;
     const int sm = g.stride - 1, sh = g.stride >> 1;   // stride is 1 or 2
-    ok = ty >= 0 && tx >= 0 && !(ty & sm) && !(tx & sm);
     ys = ty >> sh;
     xs = tx >> sh;
-    ok = ok && ys < g.YS && xs < g.XS;
+    ok = ((ty | tx) >= 0) & (((ty | tx) & sm) == 0) & (ys < g.YS) & (xs < g.XS);
   }
-  return ok ? ((long long)n * g.YS + ys) * g.XS + xs : -1;
+  const long long r = ((long long)n * g.YS + ys) * g.XS + xs;
+  return ok ? r : -1;
 }
 
 __device__ __forceinline__ void row_pos(long long m, long long M, const ConvGeom& g, int& n, int& y, int& x) {
@@ -62,113 +61,150 @@ __device__ __forceinline__ void row_pos(long long m, long long M, const ConvGeom
   }
 }
 
+constexpr int CBK = 64;   // channels of one tap per K step
+
 // ---------------------------------------------------------------------------------------------------------------
 // forward / input gradient
 // ---------------------------------------------------------------------------------------------------------------
-constexpr int CBM = 128, CBK = 64, CLD = CBK + 8;   // 144-byte LDS rows: conflict-free 16-byte reads
+// The same contraction with global_load_lds_dwordx4: a wavefront instruction moves 64 x 16 bytes from 64 independent
+// global addresses to 1 KB of consecutive LDS (lane l -> bytes 16 l ..), without passing through registers, so three
+// K steps of operands are in flight per workgroup at no register cost and the loop waits only for the oldest.
+//   * One instruction fills 8 rows x 128 bytes (8 lanes per row).  Rows are unpadded; the 16-byte pieces of a row are
+//     stored permuted (piece c of row R sits in slot c ^ ((R >> 1) & 7)), which the loading lane realises by choosing
+//     its global address, so that the 16-byte fragment reads of 16 consecutive rows fall on 64 different banks.
+//   * A row in the zero padding reads a row of zeros in global memory instead (no branch, every lane loads).
+//   * Every wavefront owns a 64 x 64 block of the tile: 256 x 64 tiles (4 x 1 wavefronts) where the output has 64
+//     channels, 128 x 128 (2 x 2) otherwise.
+__device__ __attribute__((aligned(128))) bf16 g_zero_row[64];
 
-template <int BN>
-__global__ void __launch_bounds__(256) conv_nt_k(ConvNT p, int row_tiles, int col_tiles) {
+// LDS stages.  Two (64 / 80 KB per workgroup, two workgroups per compute unit, loads one step ahead) measured 22 %
+// faster over the ResNet18 step than three (one workgroup per compute unit, loads two steps ahead): the second
+// workgroup hides more than the deeper queue.
+constexpr int CONV_STAGES = 2;
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {   // until at most N vector-memory operations of this wavefront are pending
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070 | 0x0f00);
+}
+
+template <int BM, int BN, int NST>
+__global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int col_tiles) {
+  constexpr int STAGE = (BM + BN) * CBK;   // bf16 elements per stage
+  constexpr int WN = BN / 64, WM = 4 / WN;
+  static_assert(WM * 64 == BM && (BN == 64 || BN == 128), "one 64 x 64 block per wavefront");
+  constexpr int AG = BM / 32, BG = BN / 32;          // 8-row groups per wavefront and step
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16* As = reinterpret_cast<bf16*>(smem);   // [2][CBM][CLD]
-  bf16* Bs = As + 2 * CBM * CLD;              // [2][BN][CLD]
-  // workgroup ids are dealt round-robin to the 8 XCDs: the column tiles of one row tile (which gather the same source
-  // rows) get ids of one XCD, one after the other
+  bf16* S = reinterpret_cast<bf16*>(smem);
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int rt = (slot / col_tiles) * 8 + xcd, ct = slot % col_tiles;
   if (rt >= row_tiles) return;
-  const long long m0 = (long long)rt * CBM;
+  const long long m0 = (long long)rt * BM;
   const int n0 = ct * BN;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  constexpr int WJ = BN / 64;   // 32-column blocks per wavefront
-  const int c = tid & 7, r0 = tid >> 3;
-  int pn[4], py[4], px[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) row_pos(m0 + r0 + 32 * i, p.M, p.g, pn[i], py[i], px[i]);
-  const int cpt = p.Cs / CBK;                 // K steps per tap
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int lr = lane >> 3, ls = lane & 7;
+  const int cpt = p.Cs / CBK;
   const int nk = p.g.KH * p.g.KW * cpt;
   const long long ldw = (long long)nk * CBK;
-  const bf16* wp = p.W + (long long)(n0 + r0) * ldw + c * 8;
-  const bf16* sp = p.src + c * 8;
 
-  u32x4 ra[4], rb[BN / 32];
-  auto fetch = [&](int kt) {
+  int pn[AG], py[AG], px[AG], pc[AG];
+#pragma unroll
+  for (int j = 0; j < AG; ++j) {
+    const int R = (j * 4 + wave) * 8 + lr;
+    row_pos(m0 + R, p.M, p.g, pn[j], py[j], px[j]);
+    pc[j] = (ls ^ ((R >> 1) & 7)) * 8;
+  }
+  const bf16* wb[BG];
+#pragma unroll
+  for (int j = 0; j < BG; ++j) {
+    const int R = (j * 4 + wave) * 8 + lr;
+    wb[j] = p.W + (long long)(n0 + R) * ldw + (ls ^ ((R >> 1) & 7)) * 8;
+  }
+  typedef const void __attribute__((address_space(1)))* gptr_t;
+  typedef void __attribute__((address_space(3)))* lptr_t;
+  auto issue = [&](int kt, int st) {
     const int tap = kt / cpt, c0 = (kt - tap * cpt) * CBK;
     const int kh = tap / p.g.KW, kw = tap - kh * p.g.KW;
+    bf16* sa = S + st * STAGE;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const long long sr = src_row(p.g, pn[i], py[i], px[i], kh, kw);
-      u32x4 v = ldg16(sp + (sr < 0 ? 0 : sr) * p.Cs + c0);   // no branch around the load
-      if (sr < 0) v = u32x4{0, 0, 0, 0};
-      ra[i] = v;
+    for (int j = 0; j < AG; ++j) {
+      const long long sr = src_row(p.g, pn[j], py[j], px[j], kh, kw);
+      const bf16* gp = sr >= 0 ? p.src + sr * p.Cs + c0 + pc[j] : g_zero_row + pc[j];
+      __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(sa + (j * 4 + wave) * 8 * CBK), 16, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < BN / 32; ++i) rb[i] = ldg16(wp + (long long)(32 * i) * ldw + (long long)kt * CBK);
-  };
-  auto stash = [&](int st) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(&As[st * CBM * CLD + (r0 + 32 * i) * CLD + c * 8]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < BN / 32; ++i) *reinterpret_cast<u32x4*>(&Bs[st * BN * CLD + (r0 + 32 * i) * CLD + c * 8]) = rb[i];
+    for (int j = 0; j < BG; ++j)
+      __builtin_amdgcn_global_load_lds((gptr_t)(wb[j] + (long long)kt * CBK), (lptr_t)(sa + BM * CBK + (j * 4 + wave) * 8 * CBK),
+                                       16, 0, 0);
   };
 
-  f32x16 acc[2][WJ];
+  f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < WJ; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int frow = lane & 31, fk = (lane >> 5) * 8;
-  fetch(0);
-  stash(0);
-  __syncthreads();
+  const int frow = lane & 31, half = lane >> 5;
+  // element offsets of this lane's fragment rows inside a stage and their slot permutation
+  int offA[2], offB[2], swA[2], swB[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int Ra = wm * 64 + i * 32 + frow, Rb = wn * 64 + i * 32 + frow;
+    offA[i] = Ra * CBK; swA[i] = (Ra >> 1) & 7;
+    offB[i] = BM * CBK + Rb * CBK; swB[i] = (Rb >> 1) & 7;
+  }
+
+  issue(0, 0);
+  if (NST == 3 && nk > 1) issue(1, 1);
+  int st = 0;
   for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < nk) fetch(kt + 1);
-    const bf16* as = As + cur * CBM * CLD + (wm * 64 + frow) * CLD + fk;
-    const bf16* bs = Bs + cur * BN * CLD + (wn * (BN / 2) + frow) * CLD + fk;
+    // this step's operands have landed (with three stages the next step's may be pending)
+    if (NST == 3 && kt + 1 < nk) wait_vm<AG + BG>(); else wait_vm<0>();
+    // ... for every wavefront, and the stage of step kt - 1 is free (its fragment reads were waited for before the
+    // MFMAs that used them).  A bare barrier: the fence of __syncthreads would wait for every pending load.
+    __builtin_amdgcn_s_barrier();
+    if (NST == 3) { if (kt + 2 < nk) issue(kt + 2, st >= 1 ? st - 1 : 2); }   // (kt + 2) % 3
+    else if (kt + 1 < nk) issue(kt + 1, st ^ 1);
+    const bf16* sb = S + st * STAGE;
 #pragma unroll
     for (int ks = 0; ks < CBK / 16; ++ks) {
-      bf16x8 fa[2], fb[WJ];
+      const int c = ks * 2 + half;
+      bf16x8 fa[2], fb[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(as + i * 32 * CLD + ks * 16);
-#pragma unroll
-      for (int j = 0; j < WJ; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(bs + j * 32 * CLD + ks * 16);
-      // weights first: the result block is [output channel][row], so lane l holds row l % 32 and the channels
-      // (r / 4) * 8 + (l / 32) * 4 + r % 4: four neighbours per register group
+      for (int i = 0; i < 2; ++i) {
+        fa[i] = *reinterpret_cast<const bf16x8*>(sb + offA[i] + ((c ^ swA[i]) << 3));
+        fb[i] = *reinterpret_cast<const bf16x8*>(sb + offB[i] + ((c ^ swB[i]) << 3));
+      }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < WJ; ++j)
+        for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
-    if (kt + 1 < nk) stash(cur ^ 1);   // the other stage: its readers finished before the last barrier
-    __syncthreads();
+    st = st == NST - 1 ? 0 : st + 1;
   }
+  __syncthreads();   // every operand read is done: the stages become the fp32 copy of the tile
 
-  // the tile through LDS in fp32 (every operand read is behind the last barrier), then whole row segments: what is
-  // added on the way (the output's old value, the shortcut's gradient) is added to the unrounded sums, so every
-  // stored element is rounded once
   constexpr int CLDC = BN + 4;
   float* Cs = reinterpret_cast<float*>(smem);
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < WJ; ++j)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int row = wm * 64 + i * 32 + (lane & 31);
-        const int col = wn * (BN / 2) + j * 32 + q * 8 + (lane >> 5) * 4;
+        const int col = wn * 64 + j * 32 + q * 8 + (lane >> 5) * 4;
         *reinterpret_cast<float4*>(&Cs[row * CLDC + col]) =
             make_float4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
       }
   __syncthreads();
   constexpr int CH = BN / 8;
 #pragma unroll
-  for (int it = 0; it < CBM * CH / 256; ++it) {
+  for (int it = 0; it < BM * CH / 256; ++it) {
     const int idx = tid + 256 * it;
     const int row = idx / CH, ch = idx - row * CH;
     const long long m = m0 + row;
@@ -355,28 +391,35 @@ bool geom_ok(const ConvGeom& g) {
 }  // namespace
 
 hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
-  if (!geom_ok(p.g) || p.M <= 0 || p.M >= (1LL << 31) - CBM || p.Cs <= 0 || p.Cs % CBK || p.N <= 0 || p.N % 64 ||
+  if (!geom_ok(p.g) || p.M <= 0 || p.M >= (1LL << 31) - 256 || p.Cs <= 0 || p.Cs % CBK || p.N <= 0 || p.N % 64 ||
       !al16(p.src) || !al16(p.W) || !al16(p.out) || !al16(p.extra) || !al16(p.mask) || (p.extra && !p.mask) ||
       p.M % ((long long)p.g.YO * p.g.XO))
     return hipErrorInvalidValue;
   // every source row index must fit the tensor the caller holds: n * YS * XS rows, n = M / (YO * XO)
   const long long n = p.M / ((long long)p.g.YO * p.g.XO);
   if (n * p.g.YS * p.g.XS >= (1LL << 31)) return hipErrorInvalidValue;
-  const int row_tiles = (int)((p.M + CBM - 1) / CBM);
   const bool wide = p.N % 128 == 0;
-  const int col_tiles = p.N / (wide ? 128 : 64);
+  const int BMt = wide ? 128 : 256, BNt = wide ? 128 : 64;
+  const int row_tiles = (int)((p.M + BMt - 1) / BMt);
+  const int col_tiles = p.N / BNt;
   const unsigned grid = (unsigned)((row_tiles + 7) / 8 * 8) * (unsigned)col_tiles;
   static bool attr_done = false;
-  const size_t lds_w = (size_t)2 * (CBM + 128) * CLD * sizeof(bf16), lds_n = (size_t)2 * (CBM + 64) * CLD * sizeof(bf16);
+  constexpr int NST = CONV_STAGES;
+  // the operand stages, or the fp32 copy of the tile that takes their place at the end, whichever is larger
+  auto lds_of = [](size_t BM, size_t BN) {
+    const size_t st = (size_t)NST * (BM + BN) * CBK * sizeof(bf16), ep = BM * (BN + 4) * sizeof(float);
+    return st > ep ? st : ep;
+  };
+  const size_t lds_w = lds_of(128, 128), lds_n = lds_of(256, 64);
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)conv_nt_k<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
+    hipError_t e = hipFuncSetAttribute((const void*)conv_nt_dl_k<128, 128, NST>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)conv_nt_k<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_n);
+      e = hipFuncSetAttribute((const void*)conv_nt_dl_k<256, 64, NST>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_n);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  if (wide) hipLaunchKernelGGL(conv_nt_k<128>, dim3(grid), dim3(256), lds_w, s, p, row_tiles, col_tiles);
-  else hipLaunchKernelGGL(conv_nt_k<64>, dim3(grid), dim3(256), lds_n, s, p, row_tiles, col_tiles);
+  if (wide) hipLaunchKernelGGL((conv_nt_dl_k<128, 128, NST>), dim3(grid), dim3(256), lds_w, s, p, row_tiles, col_tiles);
+  else hipLaunchKernelGGL((conv_nt_dl_k<256, 64, NST>), dim3(grid), dim3(256), lds_n, s, p, row_tiles, col_tiles);
   return hipGetLastError();
 }
 
