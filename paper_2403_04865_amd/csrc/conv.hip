@@ -61,6 +61,13 @@ __device__ __forceinline__ void row_pos(long long m, long long M, const ConvGeom
   }
 }
 
+// stem geometry: element offset in the padded image of the 8 columns at contraction column k for produced row (n, y, x)
+__device__ __forceinline__ long long stem_off(const ConvGeom& g, int n, int y, int x, int k) {
+  int kh = k >> 5;
+  kh = kh > 6 ? 6 : kh;   // the eighth kernel row has zero weights: read the seventh again
+  return (((long long)n * g.YS + 2 * y + kh) * g.XS + 2 * x) * 4 + (k & 31);
+}
+
 constexpr int CBK = 64;   // channels of one tap per K step
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -87,7 +94,7 @@ __device__ __forceinline__ void wait_vm() {   // until at most N vector-memory o
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070 | 0x0f00);
 }
 
-template <int BM, int BN, int NST>
+template <int BM, int BN, int NST, bool STEM>
 __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int col_tiles) {
   constexpr int STAGE = (BM + BN) * CBK;   // bf16 elements per stage
   constexpr int WN = BN / 64, WM = 4 / WN;
@@ -129,8 +136,13 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
     bf16* sa = S + st * STAGE;
 #pragma unroll
     for (int j = 0; j < AG; ++j) {
-      const long long sr = src_row(p.g, pn[j], py[j], px[j], kh, kw);
-      const bf16* gp = sr >= 0 ? p.src + sr * p.Cs + c0 + pc[j] : g_zero_row + pc[j];
+      const bf16* gp;
+      if (STEM) {
+        gp = py[j] != ROW_ABSENT ? p.src + stem_off(p.g, pn[j], py[j], px[j], c0 + pc[j]) : g_zero_row + pc[j];
+      } else {
+        const long long sr = src_row(p.g, pn[j], py[j], px[j], kh, kw);
+        gp = sr >= 0 ? p.src + sr * p.Cs + c0 + pc[j] : g_zero_row + pc[j];
+      }
       __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(sa + (j * 4 + wave) * 8 * CBK), 16, 0, 0);
     }
 #pragma unroll
@@ -253,7 +265,7 @@ __device__ __forceinline__ bf16x8 frag_tr(const bf16* S, int c0, int k0, int lan
   return __builtin_bit_cast(bf16x8, r);
 }
 
-template <int TAPS>
+template <int TAPS, bool STEM>
 __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
   // LDS row of one contraction index: 64 output channels, then TAPS x 64 input channels; the pad makes the row stride
   // 64 bytes modulo 256, which keeps the transpose reads free of bank conflicts
@@ -281,9 +293,15 @@ __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
 #pragma unroll
     for (int t = 0; t < TAPS; ++t) {
       const int kh = TAPS == 1 ? 0 : t / 3, kw = TAPS == 1 ? 0 : t % 3;
-      const long long sr = src_row(p.g, n, y, x, kh, kw);
-      u32x4 w = ldg16(sp + (sr < 0 ? 0 : sr) * p.Cs);
-      if (sr < 0 || !ok) w = u32x4{0, 0, 0, 0};
+      u32x4 w;
+      if (STEM) {
+        w = ldg16(p.src + stem_off(p.g, n, y, x, ci0 + c * 8));
+        if (!ok) w = u32x4{0, 0, 0, 0};
+      } else {
+        const long long sr = src_row(p.g, n, y, x, kh, kw);
+        w = ldg16(sp + (sr < 0 ? 0 : sr) * p.Cs);
+        if (sr < 0 || !ok) w = u32x4{0, 0, 0, 0};
+      }
       rs[t] = w;
     }
   };
@@ -335,8 +353,18 @@ __global__ void __launch_bounds__(256) wgrad_reduce_k(const float* __restrict__ 
   if (i >= (long long)Co * K) return;
   const int co = (int)(i / K), col = (int)(i - (long long)co * K);
   const int tap = col / Cin, ci = col - tap * Cin;
-  float a = 0.f;
-  for (int s = 0; s < slabs; ++s) a += part[((long long)s * Co + co) * ldk + col];
+  // eight independent running sums (slab s goes to sum s % 8), combined in a fixed order: the loads of eight slabs are
+  // in flight together and the result is still the same bits on every run
+  float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const long long st = (long long)Co * ldk;
+  const float* pp = part + (long long)co * ldk + col;
+  int s = 0;
+  for (; s + 8 <= slabs; s += 8) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a8[u] += pp[(s + u) * st];
+  }
+  for (; s < slabs; ++s) a8[s & 7] += pp[s * st];
+  const float a = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
   const long long o = ((long long)co * Cin + ci) * taps + tap;
   dW[o] = accumulate ? dW[o] + a : a;
 }
@@ -355,35 +383,51 @@ __global__ void __launch_bounds__(256) conv_cast_w_k(const float* __restrict__ W
   Wk[i] = (bf16)v;
 }
 
-// one thread per (row, chunk of 8 columns) of the spelled-out stem rows
-__global__ void __launch_bounds__(256) stem_im2col_k(const bf16* __restrict__ px, bf16* __restrict__ out, long long rows,
-                                                      int S, int OS) {
+// one thread per pixel of the padded image
+__global__ void __launch_bounds__(256) stem_pad_pixels_k(const bf16* __restrict__ px, bf16* __restrict__ img, long long total,
+                                                          int S) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= rows * 24) return;
-  const long long m = i / 24;
-  const int j = (int)(i - m * 24);
-  const unsigned plane = (unsigned)(OS * OS);
-  const unsigned mm = (unsigned)m;
-  const unsigned n = mm / plane, rem = mm - n * plane;
-  const int oy = (int)(rem / (unsigned)OS), ox = (int)(rem - (rem / (unsigned)OS) * (unsigned)OS);
-  bf16x8 v;
+  if (i >= total) return;
+  const int XS = S + 8, YS = S + 6;
+  const int x = (int)(i % XS);
+  const long long t = i / XS;
+  const int y = (int)(t % YS);
+  const long long n = t / YS;
+  const int iy = y - 3, ix = x - 3;
+  bf16x4 v = {(bf16)0.f, (bf16)0.f, (bf16)0.f, (bf16)0.f};
+  if ((unsigned)iy < (unsigned)S && (unsigned)ix < (unsigned)S) {
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int col = j * 8 + e;
-    const int tap = col / 3, ch = col - tap * 3;
-    const int kh = tap / 7, kw = tap - kh * 7;
-    const int iy = oy * 2 + kh - 3, ix = ox * 2 + kw - 3;
-    const bool ok = col < 147 && (unsigned)iy < (unsigned)S && (unsigned)ix < (unsigned)S;
-    const long long a = (((long long)n * 3 + ch) * S + (ok ? iy : 0)) * S + (ok ? ix : 0);
-    const bf16 t = px[col < 147 ? a : 0];
-    v[e] = ok ? t : (bf16)0.f;
+    for (int ch = 0; ch < 3; ++ch) v[ch] = px[((n * 3 + ch) * S + iy) * S + ix];
   }
-  *reinterpret_cast<bf16x8*>(out + m * 192 + j * 8) = v;
+  *reinterpret_cast<bf16x4*>(img + i * 4) = v;
+}
+
+__global__ void __launch_bounds__(256) stem_cast_w_k(const float* __restrict__ W, int Co, bf16* __restrict__ Wk) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= Co * 256) return;
+  const int co = i >> 8, k = i & 255;
+  const int kh = k >> 5, kw = (k & 31) >> 2, ch = k & 3;
+  float v = 0.f;
+  if (kh < 7 && kw < 7 && ch < 3) v = W[((co * 3 + ch) * 7 + kh) * 7 + kw];
+  Wk[i] = (bf16)v;
+}
+
+__global__ void __launch_bounds__(256) stem_wgrad_reduce_k(const float* __restrict__ part, int slabs, int Co,
+                                                            float* __restrict__ dW, int accumulate) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= Co * 147) return;
+  const int co = i / 147, r = i - co * 147;
+  const int ch = r / 49, kh = (r - ch * 49) / 7, kw = r - ch * 49 - kh * 7;
+  const int col = kh * 32 + kw * 4 + ch;
+  float a = 0.f;
+  for (int s = 0; s < slabs; ++s) a += part[((long long)s * Co + co) * 256 + col];
+  dW[i] = accumulate ? dW[i] + a : a;
 }
 
 bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 bool geom_ok(const ConvGeom& g) {
+  if (g.stem && (g.KH != 1 || g.KW != 1 || g.transposed || g.YS != 2 * g.YO + 6 || g.XS != 2 * g.XO + 8)) return false;
   return g.YO > 0 && g.XO > 0 && g.YS > 0 && g.XS > 0 && g.KH > 0 && g.KW > 0 && (g.stride == 1 || g.stride == 2) &&
          g.pad >= 0 && g.pad < (1 << 10) && g.KH < (1 << 10) && g.KW < (1 << 10);
 }
@@ -395,6 +439,7 @@ hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
       !al16(p.src) || !al16(p.W) || !al16(p.out) || !al16(p.extra) || !al16(p.mask) || (p.extra && !p.mask) ||
       p.M % ((long long)p.g.YO * p.g.XO))
     return hipErrorInvalidValue;
+  if (p.g.stem && p.Cs != 256) return hipErrorInvalidValue;
   // every source row index must fit the tensor the caller holds: n * YS * XS rows, n = M / (YO * XO)
   const long long n = p.M / ((long long)p.g.YO * p.g.XO);
   if (n * p.g.YS * p.g.XS >= (1LL << 31)) return hipErrorInvalidValue;
@@ -412,14 +457,20 @@ hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
   };
   const size_t lds_w = lds_of(128, 128), lds_n = lds_of(256, 64);
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)conv_nt_dl_k<128, 128, NST>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
+    hipError_t e = hipFuncSetAttribute((const void*)conv_nt_dl_k<128, 128, NST, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)conv_nt_dl_k<256, 64, NST>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_n);
+      e = hipFuncSetAttribute((const void*)conv_nt_dl_k<256, 64, NST, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_n);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)conv_nt_dl_k<128, 128, NST, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)conv_nt_dl_k<256, 64, NST, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_n);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  if (wide) hipLaunchKernelGGL((conv_nt_dl_k<128, 128, NST>), dim3(grid), dim3(256), lds_w, s, p, row_tiles, col_tiles);
-  else hipLaunchKernelGGL((conv_nt_dl_k<256, 64, NST>), dim3(grid), dim3(256), lds_n, s, p, row_tiles, col_tiles);
+  if (wide && p.g.stem) hipLaunchKernelGGL((conv_nt_dl_k<128, 128, NST, true>), dim3(grid), dim3(256), lds_w, s, p, row_tiles, col_tiles);
+  else if (wide) hipLaunchKernelGGL((conv_nt_dl_k<128, 128, NST, false>), dim3(grid), dim3(256), lds_w, s, p, row_tiles, col_tiles);
+  else if (p.g.stem) hipLaunchKernelGGL((conv_nt_dl_k<256, 64, NST, true>), dim3(grid), dim3(256), lds_n, s, p, row_tiles, col_tiles);
+  else hipLaunchKernelGGL((conv_nt_dl_k<256, 64, NST, false>), dim3(grid), dim3(256), lds_n, s, p, row_tiles, col_tiles);
   return hipGetLastError();
 }
 
@@ -430,11 +481,13 @@ hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s) {
       p.per <= 0 || p.per % WBK || p.per * p.slabs < p.M || !al16(p.dout) || !al16(p.src) || !p.part ||
       p.M % ((long long)p.g.YO * p.g.XO))
     return hipErrorInvalidValue;
+  if (p.g.stem && (p.Cs != 256 || taps != 1)) return hipErrorInvalidValue;
   const long long n = p.M / ((long long)p.g.YO * p.g.XO);
   if (n * p.g.YS * p.g.XS >= (1LL << 31)) return hipErrorInvalidValue;
   dim3 grid((unsigned)(p.Co / 64), (unsigned)(p.Cs / 64), (unsigned)p.slabs);
-  if (taps == 1) hipLaunchKernelGGL(conv_wgrad_k<1>, grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL(conv_wgrad_k<9>, grid, dim3(256), 0, s, p);
+  if (p.g.stem) hipLaunchKernelGGL((conv_wgrad_k<1, true>), grid, dim3(256), 0, s, p);
+  else if (taps == 1) hipLaunchKernelGGL((conv_wgrad_k<1, false>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((conv_wgrad_k<9, false>), grid, dim3(256), 0, s, p);
   return hipGetLastError();
 }
 
@@ -454,12 +507,24 @@ hipError_t launch_conv_cast_w(const float* W, int Co, int Cin, int taps, int ldk
   return hipGetLastError();
 }
 
-hipError_t launch_stem_im2col(const bf16* pixels, bf16* out, long long n, int S, hipStream_t s) {
-  if (!pixels || !out || n <= 0 || S <= 0 || S % 2 || !al16(out)) return hipErrorInvalidValue;
-  const int OS = S / 2;
-  const long long rows = n * OS * OS;
-  if (rows >= (1LL << 31) / 24) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(stem_im2col_k, dim3((unsigned)((rows * 24 + 255) / 256)), dim3(256), 0, s, pixels, out, rows, S, OS);
+hipError_t launch_stem_pad_pixels(const bf16* pixels, bf16* img, long long n, int S, hipStream_t s) {
+  if (!pixels || !img || n <= 0 || S <= 0 || S % 2 || ((uintptr_t)img & 7)) return hipErrorInvalidValue;
+  const long long total = n * (S + 6) * (S + 8);
+  if ((total + 255) / 256 >= (1LL << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stem_pad_pixels_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, pixels, img, total, S);
+  return hipGetLastError();
+}
+
+hipError_t launch_stem_cast_w(const float* W, int Co, bf16* Wk, hipStream_t s) {
+  if (!W || !Wk || Co <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stem_cast_w_k, dim3((unsigned)(Co)), dim3(256), 0, s, W, Co, Wk);
+  return hipGetLastError();
+}
+
+hipError_t launch_stem_wgrad_reduce(const float* part, int slabs, int Co, float* dW, int accumulate, hipStream_t s) {
+  if (!part || !dW || slabs <= 0 || Co <= 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(stem_wgrad_reduce_k, dim3((unsigned)((Co * 147 + 255) / 256)), dim3(256), 0, s, part, slabs, Co, dW,
+                     accumulate);
   return hipGetLastError();
 }
 

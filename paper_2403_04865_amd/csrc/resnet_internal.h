@@ -11,11 +11,18 @@ namespace sl {
 //   transposed == 1 (input gradient): produced row (n, y, x) is an INPUT position, the source is the output
 //       gradient: tap (kh, kw) -> ((y + pad - kh) / stride, (x + pad - kw) / stride), absent unless both
 //       divisions are exact and the result lies in the source grid.
+//   stem != 0: the 7x7 stride-2 pad-3 convolution of the network's input read from the padded pixel image
+//       [n][YS = S + 6][XS = S + 8][4] (three channels and a zero, a zero border of three pixels): eight consecutive
+//       pixels of one image row are 64 contiguous bytes = one kernel row of taps (kw 0..7, the eighth with zero
+//       weights), so the contraction index is kh * 32 + kw * 4 + channel, 256 columns (kh = 7: zero weights), and no
+//       row is ever absent.  The kernels see KH = KW = 1 and Cs = 256; produced row (n, y, x), column chunk of 8 at
+//       column k reads image row 2 y + min(k / 32, 6), pixel 2 x + (k % 32) / 4.
 struct ConvGeom {
   int YO, XO;   // grid of the produced rows
   int YS, XS;   // grid of the source rows
   int KH, KW, stride, pad;
   int transposed;
+  int stem;
 };
 
 // out[M][N] (bf16) = sum over taps of src_tap[M][Cs] * W[N][tap * Cs .. + Cs]^T
@@ -53,9 +60,13 @@ hipError_t launch_wgrad_reduce(const float* part, int slabs, int Co, int Cin, in
 // fp32 W[co][ci][kh][kw] -> bf16 Wk[co][ldk] (column tap * Cin + ci, zero beyond taps * Cin) and, if Wt is not null,
 // Wt[ci][tap * Co + co]
 hipError_t launch_conv_cast_w(const float* W, int Co, int Cin, int taps, int ldk, bf16* Wk, bf16* Wt, hipStream_t s);
-// rows of the 7x7 stride-2 pad-3 stem convolution spelled out: out[(n, oy, ox)][tap * 3 + c], 192 columns (147 used,
-// the rest zero) from planar pixels [n][3][S][S] (bf16)
-hipError_t launch_stem_im2col(const bf16* pixels, bf16* out, long long n, int S, hipStream_t s);
+// planar pixels [n][3][S][S] (bf16) -> padded image [n][S + 6][S + 8][4] (see ConvGeom::stem), borders and the fourth
+// channel zero
+hipError_t launch_stem_pad_pixels(const bf16* pixels, bf16* img, long long n, int S, hipStream_t s);
+// fp32 W[co][3][7][7] -> bf16 Wk[co][256], column kh * 32 + kw * 4 + channel, zero elsewhere
+hipError_t launch_stem_cast_w(const float* W, int Co, bf16* Wk, hipStream_t s);
+// dW[co][3][7][7] = (accumulate ? dW : 0) + sum_s part[s][co][kh * 32 + kw * 4 + channel]
+hipError_t launch_stem_wgrad_reduce(const float* part, int slabs, int Co, float* dW, int accumulate, hipStream_t s);
 
 // ---- batch normalisation over all rows of [M][C] (C % 8 == 0, C <= 2048) --------------------------------------------
 // stats: [4][C] floats: mean, 1 / sqrt(var + eps), a = gamma * rstd, b = beta - mean * a

@@ -29,7 +29,7 @@ struct ConvL {
   int inH, outH;
   size_t oW, og, ob;               // parameter offsets
   int t_src, t_conv;               // activation ids: source rows, convolution output
-  // what the kernels see: the stem is a 1x1 convolution over its spelled-out rows (192 columns)
+  // what the kernels see: the stem is a 1x1 convolution with 256 columns read from the padded pixel image
   int kCs, kK, kstride, kpad, kinH;
   int ldk() const { return kK * kK * kCs; }
   bool need_wt;                    // an input gradient is taken through it
@@ -47,7 +47,7 @@ struct BlockL {
 
 struct RLayout {
   size_t total = 0;
-  size_t pool, pool_bytes, H, G, bnpart, coef, wpart, wpart_bytes, parg, gA, gB, gC;
+  size_t pool, pool_bytes, H, G, bnpart, coef, wpart, wpart_bytes, img, parg, gA, gB, gC;
 };
 
 }  // namespace
@@ -60,7 +60,7 @@ struct resnet_ctx {
   std::vector<Act> acts;
   std::vector<ConvL> convs;
   std::vector<BlockL> blocks;
-  int t_cols, t_r0, t_p0;      // spelled-out stem rows, stem ReLU output, max-pool output
+  int t_r0, t_p0;              // stem ReLU output, max-pool output
   int Cmax = 0;
   size_t max_act = 0;          // largest activation, elements per tile
   slide_ctx* agg = nullptr;
@@ -141,6 +141,7 @@ RLayout make_layout(resnet_ctx* c, long long n, bool commit) {
     size_t o = take(nn * a.H * a.H * a.C * 2);
     if (commit) a.off = o;
   }
+  y.img = take(nn * (c->S + 6) * (c->S + 8) * 4 * 2);   // padded pixel image of the stem
   y.parg = take(nn * (c->S / 4) * (c->S / 4) * c->cfg.width);   // winning taps of the max pooling, one byte each
   y.gA = take(nn * c->max_act * 2);
   y.gB = take(nn * c->max_act * 2);
@@ -153,20 +154,31 @@ bf16* act(const resnet_ctx* c, int id) { return (bf16*)(c->arena + c->acts[id].o
 long long rows_of(const resnet_ctx* c, int id, long long n) { return n * c->acts[id].H * c->acts[id].H; }
 const float* stats_of(const resnet_ctx* c, int conv) { return (const float*)(c->arena + c->convs[conv].stats); }
 
+bool is_stem(const ConvL& L) { return L.kK != L.K; }
+
 ConvGeom geom_fwd(const ConvL& L) {
   ConvGeom g{};
   g.YO = g.XO = L.outH; g.YS = g.XS = L.kinH; g.KH = g.KW = L.kK; g.stride = L.kstride; g.pad = L.kpad; g.transposed = 0;
+  if (is_stem(L)) { g.stem = 1; g.YS = L.inH + 6; g.XS = L.inH + 8; }
   return g;
+}
+
+const bf16* conv_src(const resnet_ctx* c, const ConvL& L) {
+  return is_stem(L) ? (const bf16*)(c->arena + c->lay.img) : act(c, L.t_src);
+}
+
+// algorithmic bytes of a convolution's forward or weight gradient: output (gradient) rows once, source tensor once
+double conv_bytes(const resnet_ctx* c, const ConvL& L, long long M, long long n) {
+  const double src = is_stem(L) ? (double)n * (c->S + 6) * (c->S + 8) * 4 : (double)n * L.inH * L.inH * L.Cin;
+  return ((double)M * L.Cout + src) * 2;
 }
 
 void cast_weights(Run& r) {
   resnet_ctx* c = r.c;
   for (const ConvL& L : c->convs) {
-    // the stem's copy keeps the network's 49 taps x 3 channels as one row of 192 columns
-    const bool stem = L.kK != L.K;
-    const int Cin = stem ? L.Cin : L.kCs, taps = stem ? L.K * L.K : L.kK * L.kK;
     launch(r, RK_ELEMWISE, 0, 0, [&] {
-      return launch_conv_cast_w(c->params + L.oW, L.Cout, Cin, taps, L.ldk(), (bf16*)(c->arena + L.w),
+      if (is_stem(L)) return launch_stem_cast_w(c->params + L.oW, L.Cout, (bf16*)(c->arena + L.w), r.s);
+      return launch_conv_cast_w(c->params + L.oW, L.Cout, L.kCs, L.kK * L.kK, L.ldk(), (bf16*)(c->arena + L.w),
                                 L.need_wt ? (bf16*)(c->arena + L.wt) : nullptr, r.s);
     });
   }
@@ -177,10 +189,10 @@ void conv_fwd(Run& r, int id, long long n) {
   resnet_ctx* c = r.c;
   const ConvL& L = c->convs[id];
   ConvNT p{};
-  p.src = act(c, L.t_src); p.Cs = L.kCs; p.W = (const bf16*)(c->arena + L.w);
+  p.src = conv_src(c, L); p.Cs = L.kCs; p.W = (const bf16*)(c->arena + L.w);
   p.out = act(c, L.t_conv); p.N = L.Cout; p.M = rows_of(c, L.t_conv, n); p.g = geom_fwd(L); p.add = 0;
   const double K = (double)L.Cin * L.K * L.K;
-  launch(r, RK_CONV_FWD, 2.0 * p.M * L.Cout * K, (double)p.M * (L.Cout + (double)L.kCs / (L.kstride * L.kstride)) * 2,
+  launch(r, RK_CONV_FWD, 2.0 * p.M * L.Cout * K, conv_bytes(c, L, p.M, n),
          [&] { return launch_conv_nt(p, r.s); });
   launch(r, RK_BN_STATS, 0, (double)p.M * L.Cout * 2, [&] {
     return launch_bn_stats(p.out, p.M, L.Cout, c->params + L.og, c->params + L.ob, c->cfg.bn_eps,
@@ -211,7 +223,7 @@ void conv_wgrad(Run& r, int id, long long n, const bf16* dout, int accumulate) {
   resnet_ctx* c = r.c;
   const ConvL& L = c->convs[id];
   ConvWG p{};
-  p.dout = dout; p.Co = L.Cout; p.src = act(c, L.t_src); p.Cs = L.kCs; p.part = (float*)(c->arena + c->lay.wpart);
+  p.dout = dout; p.Co = L.Cout; p.src = conv_src(c, L); p.Cs = L.kCs; p.part = (float*)(c->arena + c->lay.wpart);
   p.M = rows_of(c, L.t_conv, n); p.g = geom_fwd(L);
   const long long tiles = (long long)(L.Cout / 64) * (L.kCs / 64);
   long long slabs = (4096 + tiles - 1) / tiles;
@@ -224,12 +236,11 @@ void conv_wgrad(Run& r, int id, long long n, const bf16* dout, int accumulate) {
   p.slabs = (int)slabs;
   p.per = ((p.M + slabs - 1) / slabs + 31) / 32 * 32;
   const double K = (double)L.Cin * L.K * L.K;
-  launch(r, RK_CONV_WGRAD, 2.0 * p.M * L.Cout * K, (double)p.M * (L.Cout + (double)L.kCs / (L.kstride * L.kstride)) * 2,
+  launch(r, RK_CONV_WGRAD, 2.0 * p.M * L.Cout * K, conv_bytes(c, L, p.M, n),
          [&] { return launch_conv_wgrad(p, r.s); });
-  const bool stem = L.kK != L.K;
   launch(r, RK_ELEMWISE, 0, 0, [&] {
-    return launch_wgrad_reduce(p.part, p.slabs, L.Cout, stem ? L.Cin : L.kCs, stem ? L.K * L.K : L.kK * L.kK, L.ldk(),
-                               c->grads + L.oW, accumulate, r.s);
+    if (is_stem(L)) return launch_stem_wgrad_reduce(p.part, p.slabs, L.Cout, c->grads + L.oW, accumulate, r.s);
+    return launch_wgrad_reduce(p.part, p.slabs, L.Cout, L.kCs, L.kK * L.kK, L.ldk(), c->grads + L.oW, accumulate, r.s);
   });
 }
 
@@ -265,8 +276,8 @@ int enc_fwd(resnet_ctx* c, const void* pixels, long long n, void* feats_out, hip
   Run r{c, s};
   cast_weights(r);
   // stem
-  launch(r, RK_ELEMWISE, 0, (double)n * 3 * c->S * c->S * 2 + (double)rows_of(c, c->t_cols, n) * 192 * 2,
-         [&] { return launch_stem_im2col((const bf16*)pixels, act(c, c->t_cols), n, c->S, s); });
+  launch(r, RK_ELEMWISE, 0, (double)n * (3 * c->S * c->S + 4.0 * (c->S + 6) * (c->S + 8)) * 2,
+         [&] { return launch_stem_pad_pixels((const bf16*)pixels, (bf16*)(c->arena + c->lay.img), n, c->S, s); });
   conv_fwd(r, 0, n);
   bn_apply(r, 0, n, nullptr, nullptr, act(c, c->t_r0));
   {
@@ -363,12 +374,11 @@ int resnet_ctx_create(const resnet_config* cfg, resnet_ctx** out) {
   c->cfg = *cfg;
   c->S = cfg->tile; c->expansion = exp; c->D = cfg->width * 8 * exp; c->Mh = cfg->mil_hidden; c->C = cfg->n_classes;
   const int w = cfg->width;
-  // stem: the kernels see a 1x1 convolution over the spelled-out rows [n * (S/2)^2][192]
-  c->t_cols = add_act(c, c->S / 2, 192);
-  add_conv(c, "stem.conv", "stem.bn", 3, w, 7, 2, 3, c->S, c->t_cols, false);
+  // stem: the kernels see a 1x1 convolution with 256 columns whose rows are read from the padded pixel image
+  add_conv(c, "stem.conv", "stem.bn", 3, w, 7, 2, 3, c->S, -1, false);
   {
     ConvL& L = c->convs[0];
-    L.kCs = 192; L.kK = 1; L.kstride = 1; L.kpad = 0; L.kinH = L.outH;
+    L.kCs = 256; L.kK = 1; L.kstride = 1; L.kpad = 0; L.kinH = L.outH;
   }
   c->t_r0 = add_act(c, c->S / 2, w);
   c->t_p0 = add_act(c, c->S / 4, w);
@@ -532,12 +542,12 @@ int resnet_prof_family(const resnet_ctx* c, int kernel_id, double* total_ms, int
   if (!c) return SLIDE_EINVAL;
   return prof_family(c->prof, kernel_id, RK_COUNT, total_ms, launches, flops, bytes);
 }
-int resnet_saved_activations(const resnet_ctx* c) { return c ? (int)c->acts.size() - 1 : 0; }
+int resnet_saved_activations(const resnet_ctx* c) { return c ? (int)c->acts.size() : 0; }
 
 int resnet_saved_activation(const resnet_ctx* c, int index, const void** ptr, int32_t* side, int32_t* channels) {
-  if (!c || !ptr || !side || !channels || index < 0 || index + 1 >= (int)c->acts.size()) return SLIDE_EINVAL;
+  if (!c || !ptr || !side || !channels || index < 0 || index >= (int)c->acts.size()) return SLIDE_EINVAL;
   if (!c->arena || !c->enc_saved) return SLIDE_ESTATE;
-  const Act& a = c->acts[index + 1];   // activation 0 of the context is the spelled-out stem rows
+  const Act& a = c->acts[index];
   *ptr = c->arena + a.off; *side = a.H; *channels = a.C;
   return SLIDE_OK;
 }
