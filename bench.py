@@ -245,7 +245,8 @@ def resnet_bench(a):
     k_ms, k_n, k_flops, k_bytes = lib.resnet_prof_end()
     peak_alloc = torch.cuda.max_memory_allocated() / 1e9
     stored = load_traffic(a.workload) if not a.tiles else None
-    roof = roofline_of(prof, k_ms, k_n, k_flops, k_bytes, dt * 1e3, (stored or {}).get(prof))
+    roof = roofline_of(prof, k_ms, k_n, k_flops, k_bytes, dt * 1e3,
+                       (stored or {}).get("conv_nt" if prof in ("conv_fwd", "conv_dgrad") else prof))
     lib.resnet_prof_begin(-1)
     t1 = time.perf_counter()
     one_step()
@@ -256,7 +257,9 @@ def resnet_bench(a):
     for i, nm in enumerate(names):
         f_ms, f_n, f_fl, f_by = lib.resnet_prof_family(i)
         if f_n:
-            roof_all.append(roofline_of(nm, f_ms, f_n, f_fl, f_by, all_ms, (stored or {}).get(nm)))
+            # forward and input gradient are launches of one kernel: the counters know them as one family
+            key = "conv_nt" if nm in ("conv_fwd", "conv_dgrad") else nm
+            roof_all.append(roofline_of(nm, f_ms, f_n, f_fl, f_by, all_ms, (stored or {}).get(key)))
     roof_all.sort(key=lambda r: -(r["share_of_step"] or 0))
     tiles_per_s = N * a.steps / dt
     mflops = resnet_model_flops_per_tile(cfg)

@@ -8,7 +8,8 @@ FETCH.csv / WRITE.csv: `rocprofv3 --pmc FETCH_SIZE` and `--pmc WRITE_SIZE` runs 
 counter (bytes per count).  Writes profiles/traffic_WORKLOAD.json:
     {family: {"hbm_bytes_per_launch", "fetch_bytes_per_launch", "write_bytes_per_launch", "launches"}, ...,
      "_scale": {...}}
-Kernel families are the names the library's timing hooks use (gemm_nt, gemm_tn, attn_fwd, ...).
+Kernel families are the names the library's timing hooks use (gemm_nt, gemm_tn, attn_fwd, ...; for the ResNet step
+conv_nt = conv_fwd + conv_dgrad, conv_wgrad, bn_stats, bn_apply, bn_bwd, pooling).
 COMMIT (optional) is recorded as "_commit": the source revision the counters were collected on; bench.py prints it
 beside the traffic figures it reads from this file.
 """
@@ -23,7 +24,10 @@ import sys
 FAMILIES = [("gemm_nt", ("gemm_nt_",)), ("gemm_tn", ("gemm_tn_",)), ("attn_fwd", ("attn_fwd",)),
             ("attn_bwd", ("attn_bwd",)), ("ln_fwd", ("ln_fwd",)), ("ln_bwd", ("ln_bwd",)),
             ("pool_fwd", ("pool_gate", "pool_combine", "pool_alpha", "pool_cast")), ("pool_bwd", ("pool_bwd",)),
-            ("cls_lane", ("lane_",))]
+            ("cls_lane", ("lane_",)),
+            # convolutional encoders: forward and input gradient are launches of one kernel (family conv_nt)
+            ("conv_nt", ("conv_nt_",)), ("conv_wgrad", ("conv_wgrad_",)), ("bn_stats", ("bn_stats_",)),
+            ("bn_apply", ("bn_apply_",)), ("bn_bwd", ("bn_bwd_",)), ("pooling", ("maxpool_", "avgpool_"))]
 
 
 def per_dispatch(path, counter):
