@@ -61,6 +61,20 @@ __device__ __forceinline__ void row_pos(long long m, long long M, const ConvGeom
   }
 }
 
+// row m of a launch -> position (n, y, x) of the produced grid; with a parity class the rows enumerate that class only
+__device__ __forceinline__ void launch_pos(long long m, long long M, const ConvGeom& g, int& n, int& y, int& x) {
+  if (!g.cls) { row_pos(m, M, g, n, y, x); return; }
+  if (m < M) {
+    const unsigned hx = (unsigned)(g.XO >> 1), plane = (unsigned)(g.YO >> 1) * hx;
+    const unsigned mm = (unsigned)m;
+    const unsigned q = mm / plane, rem = mm - q * plane;
+    const unsigned yy = rem / hx;
+    n = (int)q; y = 2 * (int)yy + ((g.cls - 1) >> 1); x = 2 * (int)(rem - yy * hx) + ((g.cls - 1) & 1);
+  } else {
+    n = 0; y = ROW_ABSENT; x = 0;
+  }
+}
+
 // stem geometry: element offset in the padded image of the 8 columns at contraction column k for produced row (n, y, x)
 __device__ __forceinline__ long long stem_off(const ConvGeom& g, int n, int y, int x, int k) {
   int kh = k >> 5;
@@ -112,14 +126,18 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
   const int wm = wave / WN, wn = wave % WN;
   const int lr = lane >> 3, ls = lane & 7;
   const int cpt = p.Cs / CBK;
-  const int nk = p.g.KH * p.g.KW * cpt;
-  const long long ldw = (long long)nk * CBK;
+  const long long ldw = (long long)p.g.KH * p.g.KW * p.Cs;
+  // taps of this launch: all, or (parity class) kh = kh0 + 2 i, kw = kw0 + 2 i'
+  const int tstep = p.g.cls ? 2 : 1;
+  const int kh0 = p.g.cls ? ((((p.g.cls - 1) >> 1) + p.g.pad) & 1) : 0, kw0 = p.g.cls ? ((((p.g.cls - 1) & 1) + p.g.pad) & 1) : 0;
+  const int nky = p.g.KH > kh0 ? (p.g.KH - kh0 + tstep - 1) / tstep : 0, nkx = p.g.KW > kw0 ? (p.g.KW - kw0 + tstep - 1) / tstep : 0;
+  const int nk = nky * nkx * cpt;
 
   int pn[AG], py[AG], px[AG], pc[AG];
 #pragma unroll
   for (int j = 0; j < AG; ++j) {
     const int R = (j * 4 + wave) * 8 + lr;
-    row_pos(m0 + R, p.M, p.g, pn[j], py[j], px[j]);
+    launch_pos(m0 + R, p.M, p.g, pn[j], py[j], px[j]);
     pc[j] = (ls ^ ((R >> 1) & 7)) * 8;
   }
   const bf16* wb[BG];
@@ -132,7 +150,9 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
   typedef void __attribute__((address_space(3)))* lptr_t;
   auto issue = [&](int kt, int st) {
     const int tap = kt / cpt, c0 = (kt - tap * cpt) * CBK;
-    const int kh = tap / p.g.KW, kw = tap - kh * p.g.KW;
+    const int ty = tap / nkx;
+    const int kh = kh0 + tstep * ty, kw = kw0 + tstep * (tap - ty * nkx);
+    const long long wcol = (long long)(kh * p.g.KW + kw) * p.Cs + c0;   // column of this step in the weight rows
     bf16* sa = S + st * STAGE;
 #pragma unroll
     for (int j = 0; j < AG; ++j) {
@@ -147,8 +167,7 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
     }
 #pragma unroll
     for (int j = 0; j < BG; ++j)
-      __builtin_amdgcn_global_load_lds((gptr_t)(wb[j] + (long long)kt * CBK), (lptr_t)(sa + BM * CBK + (j * 4 + wave) * 8 * CBK),
-                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(wb[j] + wcol), (lptr_t)(sa + BM * CBK + (j * 4 + wave) * 8 * CBK), 16, 0, 0);
   };
 
   f32x16 acc[2][2];
@@ -169,7 +188,7 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
     offB[i] = BM * CBK + Rb * CBK; swB[i] = (Rb >> 1) & 7;
   }
 
-  issue(0, 0);
+  if (nk > 0) issue(0, 0);   // a parity class may have no tap at all (1x1 kernels): its positions get zeros
   if (NST == 3 && nk > 1) issue(1, 1);
   int st = 0;
   for (int kt = 0; kt < nk; ++kt) {
@@ -224,7 +243,13 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
       const float4 lo = *reinterpret_cast<const float4*>(&Cs[row * CLDC + ch * 8]);
       const float4 hi = *reinterpret_cast<const float4*>(&Cs[row * CLDC + ch * 8 + 4]);
       float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      const long long at = m * p.N + n0 + ch * 8;
+      long long orow = m;
+      if (p.g.cls) {   // the produced position's row in the full grid
+        int n, y, x;
+        launch_pos(m, p.M, p.g, n, y, x);
+        orow = ((long long)n * p.g.YO + y) * p.g.XO + x;
+      }
+      const long long at = orow * p.N + n0 + ch * 8;
       if (p.add) {
         const u32x4 o = *reinterpret_cast<const u32x4*>(p.out + at);
 #pragma unroll
@@ -269,7 +294,8 @@ template <int TAPS, bool STEM>
 __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
   // LDS row of one contraction index: 64 output channels, then TAPS x 64 input channels; the pad makes the row stride
   // 64 bytes modulo 256, which keeps the transpose reads free of bank conflicts
-  constexpr int LDW = 64 * (1 + TAPS) + 32;
+  constexpr int LDW = 64 * (1 + TAPS) + (TAPS == 4 ? 96 : 32);
+  static_assert((LDW * 2) % 256 == 64, "row stride 64 bytes modulo 256");
   __shared__ __attribute__((aligned(16))) bf16 S[WBK * LDW];
   const int co0 = blockIdx.x * 64, ci0 = blockIdx.y * 64, slab = blockIdx.z;
   const long long lo = (long long)slab * p.per;
@@ -294,8 +320,8 @@ __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
     for (int t = 0; t < TAPS; ++t) {
       const int kh = TAPS == 1 ? 0 : t / 3, kw = TAPS == 1 ? 0 : t % 3;
       u32x4 w;
-      if (STEM) {
-        w = ldg16(p.src + stem_off(p.g, n, y, x, ci0 + c * 8));
+      if (STEM) {   // the four 64-column groups of the stem's 256 contraction columns stand where the taps stand
+        w = ldg16(p.src + stem_off(p.g, n, y, x, t * 64 + c * 8));
         if (!ok) w = u32x4{0, 0, 0, 0};
       } else {
         const long long sr = src_row(p.g, n, y, x, kh, kw);
@@ -436,12 +462,16 @@ bool geom_ok(const ConvGeom& g) {
 
 hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
   if (!geom_ok(p.g) || p.M <= 0 || p.M >= (1LL << 31) - 256 || p.Cs <= 0 || p.Cs % CBK || p.N <= 0 || p.N % 64 ||
-      !al16(p.src) || !al16(p.W) || !al16(p.out) || !al16(p.extra) || !al16(p.mask) || (p.extra && !p.mask) ||
-      p.M % ((long long)p.g.YO * p.g.XO))
+      !al16(p.src) || !al16(p.W) || !al16(p.out) || !al16(p.extra) || !al16(p.mask) || (p.extra && !p.mask))
     return hipErrorInvalidValue;
   if (p.g.stem && p.Cs != 256) return hipErrorInvalidValue;
-  // every source row index must fit the tensor the caller holds: n * YS * XS rows, n = M / (YO * XO)
-  const long long n = p.M / ((long long)p.g.YO * p.g.XO);
+  if (p.g.cls && (p.g.cls < 1 || p.g.cls > 4 || !p.g.transposed || p.g.stride != 2 || p.g.YO % 2 || p.g.XO % 2))
+    return hipErrorInvalidValue;
+  // rows of one launch: whole tiles, or (parity class) a quarter of their positions
+  const long long per_tile = p.g.cls ? (long long)(p.g.YO / 2) * (p.g.XO / 2) : (long long)p.g.YO * p.g.XO;
+  if (p.M % per_tile) return hipErrorInvalidValue;
+  // every source row index must fit the tensor the caller holds: n * YS * XS rows
+  const long long n = p.M / per_tile;
   if (n * p.g.YS * p.g.XS >= (1LL << 31)) return hipErrorInvalidValue;
   const bool wide = p.N % 128 == 0;
   const int BMt = wide ? 128 : 256, BNt = wide ? 128 : 64;
@@ -481,11 +511,11 @@ hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s) {
       p.per <= 0 || p.per % WBK || p.per * p.slabs < p.M || !al16(p.dout) || !al16(p.src) || !p.part ||
       p.M % ((long long)p.g.YO * p.g.XO))
     return hipErrorInvalidValue;
-  if (p.g.stem && (p.Cs != 256 || taps != 1)) return hipErrorInvalidValue;
+  if (p.g.stem && (p.Cs != 64 || taps != 1)) return hipErrorInvalidValue;   // 4 column groups of 64
   const long long n = p.M / ((long long)p.g.YO * p.g.XO);
   if (n * p.g.YS * p.g.XS >= (1LL << 31)) return hipErrorInvalidValue;
   dim3 grid((unsigned)(p.Co / 64), (unsigned)(p.Cs / 64), (unsigned)p.slabs);
-  if (p.g.stem) hipLaunchKernelGGL((conv_wgrad_k<1, true>), grid, dim3(256), 0, s, p);
+  if (p.g.stem) hipLaunchKernelGGL((conv_wgrad_k<4, true>), grid, dim3(256), 0, s, p);
   else if (taps == 1) hipLaunchKernelGGL((conv_wgrad_k<1, false>), grid, dim3(256), 0, s, p);
   else hipLaunchKernelGGL((conv_wgrad_k<9, false>), grid, dim3(256), 0, s, p);
   return hipGetLastError();

@@ -23,6 +23,11 @@ struct ConvGeom {
   int KH, KW, stride, pad;
   int transposed;
   int stem;
+  // cls != 0 (input gradient of a stride-2 convolution only): the launch produces the positions of one parity class,
+  // (y % 2, x % 2) = ((cls - 1) / 2, (cls - 1) % 2), i.e. M = n * (YO / 2) * (XO / 2) rows.  Only the taps whose offset
+  // has the parity of the class reach a source position at all (kh = (y + pad) % 2 + 2 i): the contraction runs over
+  // those (a quarter of KH * KW on average) instead of multiplying zeros for the rest.
+  int cls;
 };
 
 // out[M][N] (bf16) = sum over taps of src_tap[M][Cs] * W[N][tap * Cs .. + Cs]^T

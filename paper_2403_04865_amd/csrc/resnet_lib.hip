@@ -223,9 +223,11 @@ void conv_wgrad(Run& r, int id, long long n, const bf16* dout, int accumulate) {
   resnet_ctx* c = r.c;
   const ConvL& L = c->convs[id];
   ConvWG p{};
-  p.dout = dout; p.Co = L.Cout; p.src = conv_src(c, L); p.Cs = L.kCs; p.part = (float*)(c->arena + c->lay.wpart);
+  p.dout = dout; p.Co = L.Cout; p.src = conv_src(c, L);
+  p.Cs = is_stem(L) ? 64 : L.kCs;   // the stem's 256 columns are four groups of 64 handled like taps
+  p.part = (float*)(c->arena + c->lay.wpart);
   p.M = rows_of(c, L.t_conv, n); p.g = geom_fwd(L);
-  const long long tiles = (long long)(L.Cout / 64) * (L.kCs / 64);
+  const long long tiles = (long long)(L.Cout / 64) * (p.Cs / 64);
   long long slabs = (4096 + tiles - 1) / tiles;
   const long long by_rows = (p.M + 255) / 256;
   const long long by_room = (long long)(c->lay.wpart_bytes / ((size_t)L.Cout * L.ldk() * 4));
@@ -257,9 +259,21 @@ void conv_dgrad(Run& r, int id, long long n, const bf16* dout, bf16* dsrc, int a
   p.g.transposed = 1;
   p.add = add; p.extra = extra; p.mask = mask;
   const double K = (double)L.Cin * L.K * L.K;
-  launch(r, RK_CONV_DGRAD, 2.0 * rows_of(c, L.t_conv, n) * L.Cout * K,
-         ((double)p.M * L.kCs * (add ? 2 : (extra ? 3 : 1)) + (double)rows_of(c, L.t_conv, n) * L.Cout) * 2,
-         [&] { return launch_conv_nt(p, r.s); });
+  const double flops = 2.0 * rows_of(c, L.t_conv, n) * L.Cout * K;
+  const double bytes = ((double)p.M * L.kCs * (add ? 2 : (extra ? 3 : 1)) + (double)rows_of(c, L.t_conv, n) * L.Cout) * 2;
+  if (L.kstride == 2) {
+    // one launch per parity class of the input positions: each only sees the taps that reach an output position
+    p.M /= 4;
+    for (int cls = 1; cls <= 4; ++cls) {
+      p.g.cls = cls;
+      const int kh0 = (((cls - 1) >> 1) + L.kpad) & 1, kw0 = (((cls - 1) & 1) + L.kpad) & 1;
+      const bool no_tap = kh0 >= L.kK || kw0 >= L.kK;
+      if (no_tap && add && !extra) continue;   // nothing to add to what is there
+      launch(r, RK_CONV_DGRAD, flops / 4, bytes / 4, [&] { return launch_conv_nt(p, r.s); });
+    }
+    return;
+  }
+  launch(r, RK_CONV_DGRAD, flops, bytes, [&] { return launch_conv_nt(p, r.s); });
 }
 
 int check_bound(const resnet_ctx* c) {
