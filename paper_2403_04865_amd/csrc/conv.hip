@@ -10,8 +10,8 @@
 //                  weights as its first operand, so a lane ends up with four consecutive output channels of one row;
 //                  the tile goes through LDS once (fp32) and leaves as whole row segments, rounded once.
 //   conv_wgrad_k : weight gradient.  dW[co][tap][ci] = sum_rows dout[row][co] * gather_tap(src)[row][ci]: the
-//                  contraction runs over the rows, so the 32-row slices go to LDS as they are and the MFMA operands
-//                  come from LDS transpose reads.  One workgroup owns a 64 x 64 block of (co, ci) for ALL taps (the
+//                  contraction runs over the rows, so the 32-row slices go to LDS as they are (straight from global
+//                  memory, like the other kernel's operands) and the MFMA operands come from LDS transpose reads.  One workgroup owns a 64 x 64 block of (co, ci) for ALL taps (the
 //                  output-gradient slice is loaded once for the nine taps) over one slab of rows; slabs are added in
 //                  a fixed order by wgrad_reduce_k (no atomics: run-to-run identical), which also turns the
 //                  [co][tap][ci] order of the kernels into the parameter's [co][ci][kh][kw].
@@ -277,64 +277,62 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
 // ---------------------------------------------------------------------------------------------------------------
 constexpr int WBK = 32;   // rows per step
 
-// MFMA operand from a row-major LDS slice S[k][col] (row stride LDW elements): lane l gets column c0 + l % 32 and
-// the contraction indices k0 + 8 * (l / 32) + {0..7}.  A transpose read's group of 16 lanes addresses a 4-row x
-// 16-column patch and every lane receives one column of it.
-template <int LDW>
-__device__ __forceinline__ bf16x8 frag_tr(const bf16* S, int c0, int k0, int lane) {
+// Operands go straight into LDS here too.  A stage holds 1 + TAPS slices of [32 rows][64 channels] (128-byte rows,
+// unpadded): slice 0 the output-gradient rows, slice 1 + t the source rows of tap t.  A wavefront instruction fills 8
+// rows of one slice; wavefront w always takes rows 8 w .. 8 w + 7, of every slice, so a lane resolves one row position
+// per step.  The 16-byte pieces of rows 2, 3, 6, 7, ... sit in the other 64-byte half of the row (slot = piece ^ 4):
+// a transpose read's two 16-lane groups that are served together touch 4 rows x 64 bytes, which then fall on four
+// different quarters of the banks.
+//
+// MFMA operand from slice B (row-major, 64 elements per row): lane l gets column c0 + l % 32 and the contraction
+// indices k0 + 8 * (l / 32) + {0..7}.  A transpose read's group of 16 lanes addresses a 4-row x 16-column patch and
+// every lane receives one column of it.
+__device__ __forceinline__ bf16x8 frag_tr_dl(const bf16* B, int c0, int k0, int lane) {
   const int g = lane >> 4, q = lane & 15;
-  const bf16* p = S + (k0 + 8 * (g >> 1) + (q >> 2)) * LDW + c0 + 16 * (g & 1) + (q & 3) * 4;
+  const int k = k0 + 8 * (g >> 1) + (q >> 2), col = c0 + 16 * (g & 1) + (q & 3) * 4;
+  const bf16* p = B + k * 64 + ((((col >> 3) ^ (((k >> 1) & 1) << 2)) << 3) | (col & 7));
   s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
-  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * LDW));
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p + 4 * 64));   // row k + 4: same half
   s16x8 r = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
   return __builtin_bit_cast(bf16x8, r);
 }
 
 template <int TAPS, bool STEM>
 __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
-  // LDS row of one contraction index: 64 output channels, then TAPS x 64 input channels; the pad makes the row stride
-  // 64 bytes modulo 256, which keeps the transpose reads free of bank conflicts
-  constexpr int LDW = 64 * (1 + TAPS) + (TAPS == 4 ? 96 : 32);
-  static_assert((LDW * 2) % 256 == 64, "row stride 64 bytes modulo 256");
-  __shared__ __attribute__((aligned(16))) bf16 S[WBK * LDW];
+  constexpr int SL = 1 + TAPS, SLICE = WBK * 64, STAGE = SL * SLICE;   // bf16 elements
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* S = reinterpret_cast<bf16*>(smem);   // [2][SL][32][64]
   const int co0 = blockIdx.x * 64, ci0 = blockIdx.y * 64, slab = blockIdx.z;
   const long long lo = (long long)slab * p.per;
   const long long hi = lo + p.per < p.M ? lo + p.per : p.M;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qa = wave >> 1, qb = wave & 1;
-  const int c = tid & 7, r = tid >> 3;
-  const bf16* dp = p.dout + co0 + c * 8;
-  const bf16* sp = p.src + ci0 + c * 8;
+  const int r = wave * 8 + (lane >> 3);                          // this lane's row of every slice
+  const int cl = ((lane & 7) ^ (((r >> 1) & 1) << 2)) * 8;       // the piece it fetches (its slot holds piece slot ^ ...)
+  typedef const void __attribute__((address_space(1)))* gptr_t;
+  typedef void __attribute__((address_space(3)))* lptr_t;
 
-  u32x4 rd, rs[TAPS];
-  auto fetch = [&](long long mstep) {   // only called with mstep < hi
+  auto issue = [&](long long mstep, int st) {   // only called with mstep < hi
     const long long m = mstep + r;
     const bool ok = m < hi;
-    const long long mc = ok ? m : hi - 1;
     int n, y, x;
-    row_pos(mc, p.M, p.g, n, y, x);
-    u32x4 v = ldg16(dp + mc * p.Co);
-    if (!ok) v = u32x4{0, 0, 0, 0};
-    rd = v;
+    row_pos(ok ? m : hi - 1, p.M, p.g, n, y, x);
+    bf16* sa = S + st * STAGE + wave * 8 * 64;
+    const bf16* gd = ok ? p.dout + m * p.Co + co0 + cl : g_zero_row + cl;
+    __builtin_amdgcn_global_load_lds((gptr_t)gd, (lptr_t)sa, 16, 0, 0);
 #pragma unroll
     for (int t = 0; t < TAPS; ++t) {
-      const int kh = TAPS == 1 ? 0 : t / 3, kw = TAPS == 1 ? 0 : t % 3;
-      u32x4 w;
+      const bf16* gp;
       if (STEM) {   // the four 64-column groups of the stem's 256 contraction columns stand where the taps stand
-        w = ldg16(p.src + stem_off(p.g, n, y, x, t * 64 + c * 8));
-        if (!ok) w = u32x4{0, 0, 0, 0};
+        gp = ok ? p.src + stem_off(p.g, n, y, x, t * 64 + cl) : g_zero_row + cl;
       } else {
+        const int kh = TAPS == 1 ? 0 : t / 3, kw = TAPS == 1 ? 0 : t % 3;
         const long long sr = src_row(p.g, n, y, x, kh, kw);
-        w = ldg16(sp + (sr < 0 ? 0 : sr) * p.Cs);
-        if (sr < 0 || !ok) w = u32x4{0, 0, 0, 0};
+        gp = (ok & (sr >= 0)) ? p.src + sr * p.Cs + ci0 + cl : g_zero_row + cl;
       }
-      rs[t] = w;
+      __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(sa + (1 + t) * SLICE), 16, 0, 0);
     }
-  };
-  auto stash = [&]() {
-    *reinterpret_cast<u32x4*>(&S[r * LDW + c * 8]) = rd;
-#pragma unroll
-    for (int t = 0; t < TAPS; ++t) *reinterpret_cast<u32x4*>(&S[r * LDW + 64 + t * 64 + c * 8]) = rs[t];
   };
 
   f32x16 acc[TAPS];
@@ -343,21 +341,23 @@ __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
 
-  if (lo < hi) fetch(lo);
+  if (lo < hi) issue(lo, 0);
+  int st = 0;
   for (long long mstep = lo; mstep < hi; mstep += WBK) {
-    __syncthreads();   // the previous step's operand reads are done
-    stash();
-    __syncthreads();
-    if (mstep + WBK < hi) fetch(mstep + WBK);
+    wait_vm<0>();                     // this step's rows have landed ...
+    __builtin_amdgcn_s_barrier();     // ... for every wavefront, and the other stage is no longer read
+    if (mstep + WBK < hi) issue(mstep + WBK, st ^ 1);
+    const bf16* sb = S + st * STAGE;
 #pragma unroll
     for (int kk = 0; kk < WBK; kk += 16) {
-      const bf16x8 fa = frag_tr<LDW>(S, qa * 32, kk, lane);
+      const bf16x8 fa = frag_tr_dl(sb, qa * 32, kk, lane);
 #pragma unroll
       for (int t = 0; t < TAPS; ++t) {
-        const bf16x8 fb = frag_tr<LDW>(S, 64 + t * 64 + qb * 32, kk, lane);
+        const bf16x8 fb = frag_tr_dl(sb + (1 + t) * SLICE, qb * 32, kk, lane);
         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[t], 0, 0, 0);
       }
     }
+    st ^= 1;
   }
   // block rows = output channels (r / 4) * 8 + (l / 32) * 4 + r % 4, block columns = input channels l % 32.  A slab
   // without rows still writes its zeros: the reduction adds every slab.
@@ -515,9 +515,17 @@ hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s) {
   const long long n = p.M / ((long long)p.g.YO * p.g.XO);
   if (n * p.g.YS * p.g.XS >= (1LL << 31)) return hipErrorInvalidValue;
   dim3 grid((unsigned)(p.Co / 64), (unsigned)(p.Cs / 64), (unsigned)p.slabs);
-  if (p.g.stem) hipLaunchKernelGGL((conv_wgrad_k<4, true>), grid, dim3(256), 0, s, p);
-  else if (taps == 1) hipLaunchKernelGGL((conv_wgrad_k<1, false>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((conv_wgrad_k<9, false>), grid, dim3(256), 0, s, p);
+  auto lds_of = [](int taps_) { return (size_t)2 * (1 + taps_) * WBK * 64 * sizeof(bf16); };
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)conv_wgrad_k<9, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds_of(9));
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  if (p.g.stem) hipLaunchKernelGGL((conv_wgrad_k<4, true>), grid, dim3(256), lds_of(4), s, p);
+  else if (taps == 1) hipLaunchKernelGGL((conv_wgrad_k<1, false>), grid, dim3(256), lds_of(1), s, p);
+  else hipLaunchKernelGGL((conv_wgrad_k<9, false>), grid, dim3(256), lds_of(9), s, p);
   return hipGetLastError();
 }
 
