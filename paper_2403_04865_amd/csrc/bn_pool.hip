@@ -102,7 +102,8 @@ __global__ void __launch_bounds__(256) bn_stats_final_k(const float* __restrict_
 
 __global__ void __launch_bounds__(256) bn_apply_k(const bf16* __restrict__ x, long long chunks, int C,
                                                    const float* __restrict__ stats, const bf16* __restrict__ resid,
-                                                   const float* __restrict__ rstats, int relu, bf16* __restrict__ y) {
+                                                   const float* __restrict__ rstats, int relu, bf16* __restrict__ y,
+                                                   unsigned char* __restrict__ bits) {
   const int tcols = C >> 3;
   for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (long long)gridDim.x * 256) {
     const int c0 = (int)(i % tcols) * 8;
@@ -120,11 +121,19 @@ __global__ void __launch_bounds__(256) bn_apply_k(const bf16* __restrict__ x, lo
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = fmaxf(v[e], 0.f);
     }
-    st8(y + i * 8, v);
+    bf16x8 t;
+    unsigned m = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      t[e] = (bf16)v[e];
+      m |= ((float)t[e] > 0.f ? 1u : 0u) << e;   // of the value as stored
+    }
+    *reinterpret_cast<bf16x8*>(y + i * 8) = t;
+    if (bits) bits[i] = (unsigned char)m;
   }
 }
 
-__global__ void __launch_bounds__(256) bn_bwd_part_k(const bf16* __restrict__ dy, const bf16* __restrict__ mask,
+__global__ void __launch_bounds__(256) bn_bwd_part_k(const bf16* __restrict__ dy, const unsigned char* __restrict__ mask,
                                                       const bf16* __restrict__ x, long long M, int C,
                                                       const float* __restrict__ stats, float* __restrict__ part) {
   two_sums(M, C, part, [&](long long off, int c0, float (&a)[8], float (&b)[8]) {
@@ -132,10 +141,9 @@ __global__ void __launch_bounds__(256) bn_bwd_part_k(const bf16* __restrict__ dy
     unpack8(ld16(dy + off), a);
     unpack8(ld16(x + off), xv);
     if (mask) {
-      float mv[8];
-      unpack8(ld16(mask + off), mv);
+      const unsigned m = mask[off >> 3];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) a[e] = mv[e] > 0.f ? a[e] : 0.f;
+      for (int e = 0; e < 8; ++e) a[e] = (m >> e) & 1u ? a[e] : 0.f;
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) b[e] = a[e] * ((xv[e] - stats[c0 + e]) * stats[C + c0 + e]);
@@ -157,7 +165,7 @@ __global__ void __launch_bounds__(256) bn_bwd_final_k(const float* __restrict__ 
   dgamma[ch] = accumulate ? dgamma[ch] + (float)q : (float)q;
 }
 
-__global__ void __launch_bounds__(256) bn_bwd_apply_k(const bf16* __restrict__ dy, const bf16* __restrict__ mask,
+__global__ void __launch_bounds__(256) bn_bwd_apply_k(const bf16* __restrict__ dy, const unsigned char* __restrict__ mask,
                                                        const bf16* __restrict__ x, long long chunks, int C,
                                                        const float* __restrict__ stats, const float* __restrict__ coef,
                                                        bf16* __restrict__ dx) {
@@ -168,10 +176,9 @@ __global__ void __launch_bounds__(256) bn_bwd_apply_k(const bf16* __restrict__ d
     unpack8(ld16(dy + i * 8), d);
     unpack8(ld16(x + i * 8), xv);
     if (mask) {
-      float mv[8];
-      unpack8(ld16(mask + i * 8), mv);
+      const unsigned m = mask[i];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) d[e] = mv[e] > 0.f ? d[e] : 0.f;
+      for (int e = 0; e < 8; ++e) d[e] = (m >> e) & 1u ? d[e] : 0.f;
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -278,19 +285,6 @@ __global__ void __launch_bounds__(256) avgpool_bwd_k(const float* __restrict__ d
   }
 }
 
-__global__ void __launch_bounds__(256) add_masked_k(bf16* __restrict__ dst, const bf16* __restrict__ src,
-                                                     const bf16* __restrict__ mask, long long chunks) {
-  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (long long)gridDim.x * 256) {
-    float a[8], b[8], m[8];
-    unpack8(ld16(dst + i * 8), a);
-    unpack8(ld16(src + i * 8), b);
-    unpack8(ld16(mask + i * 8), m);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) a[e] += m[e] > 0.f ? b[e] : 0.f;
-    st8(dst + i * 8, a);
-  }
-}
-
 bool chan_ok(int C) { return C >= 64 && C <= 2048 && (C & (C - 1)) == 0; }
 bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 unsigned stream_grid(long long chunks) {
@@ -318,17 +312,17 @@ hipError_t launch_bn_stats(const bf16* x, long long M, int C, const float* gamma
 }
 
 hipError_t launch_bn_apply(const bf16* x, long long M, int C, const float* stats, const bf16* resid, const float* rstats,
-                           int relu, bf16* y, hipStream_t s) {
+                           int relu, bf16* y, unsigned char* bits, hipStream_t s) {
   if (!x || !stats || !y || M <= 0 || !chan_ok(C) || !al16(x) || !al16(y) || !al16(resid)) return hipErrorInvalidValue;
   const long long chunks = M * (C >> 3);
-  hipLaunchKernelGGL(bn_apply_k, dim3(stream_grid(chunks)), dim3(256), 0, s, x, chunks, C, stats, resid, rstats, relu, y);
+  hipLaunchKernelGGL(bn_apply_k, dim3(stream_grid(chunks)), dim3(256), 0, s, x, chunks, C, stats, resid, rstats, relu, y, bits);
   return hipGetLastError();
 }
 
-hipError_t launch_bn_bwd(const bf16* dy, const bf16* mask, const bf16* x, long long M, int C, const float* stats,
+hipError_t launch_bn_bwd(const bf16* dy, const unsigned char* mask, const bf16* x, long long M, int C, const float* stats,
                          float* part, float* coef, float* dgamma, float* dbeta, int accumulate, bf16* dx, hipStream_t s) {
   if (!dy || !x || !stats || !part || !coef || !dgamma || !dbeta || !dx || M <= 0 || !chan_ok(C) || !al16(dy) ||
-      !al16(mask) || !al16(x) || !al16(dx))
+      !al16(x) || !al16(dx))
     return hipErrorInvalidValue;
   const int blocks = bn_blocks(M, C);
   hipLaunchKernelGGL(bn_bwd_part_k, dim3(blocks), dim3(256), 0, s, dy, mask, x, M, C, stats, part);
@@ -371,13 +365,6 @@ hipError_t launch_avgpool_bwd(const float* dfeats, bf16* dx, long long n, int HW
   if (!dfeats || !dx || n <= 0 || HW <= 0 || !chan_ok(C) || !al16(dx)) return hipErrorInvalidValue;
   const long long chunks = n * HW * (C >> 3);
   hipLaunchKernelGGL(avgpool_bwd_k, dim3(stream_grid(chunks)), dim3(256), 0, s, dfeats, dx, chunks, HW, C);
-  return hipGetLastError();
-}
-
-hipError_t launch_add_masked(bf16* dst, const bf16* src, const bf16* mask, long long count, hipStream_t s) {
-  if (!dst || !src || !mask || count <= 0 || count % 8 || !al16(dst) || !al16(src) || !al16(mask)) return hipErrorInvalidValue;
-  const long long chunks = count / 8;
-  hipLaunchKernelGGL(add_masked_k, dim3(stream_grid(chunks)), dim3(256), 0, s, dst, src, mask, chunks);
   return hipGetLastError();
 }
 

@@ -257,11 +257,11 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
       }
       if (p.extra) {
         const u32x4 x = *reinterpret_cast<const u32x4*>(p.extra + at);
-        const u32x4 k = *reinterpret_cast<const u32x4*>(p.mask + at);
+        const unsigned k = p.mask[at >> 3];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          f[2 * w] += __uint_as_float(k[w] << 16) > 0.f ? __uint_as_float(x[w] << 16) : 0.f;
-          f[2 * w + 1] += __uint_as_float(k[w] & 0xffff0000u) > 0.f ? __uint_as_float(x[w] & 0xffff0000u) : 0.f;
+          f[2 * w] += (k >> (2 * w)) & 1u ? __uint_as_float(x[w] << 16) : 0.f;
+          f[2 * w + 1] += (k >> (2 * w + 1)) & 1u ? __uint_as_float(x[w] & 0xffff0000u) : 0.f;
         }
       }
       bf16x8 t;
@@ -462,7 +462,7 @@ bool geom_ok(const ConvGeom& g) {
 
 hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
   if (!geom_ok(p.g) || p.M <= 0 || p.M >= (1LL << 31) - 256 || p.Cs <= 0 || p.Cs % CBK || p.N <= 0 || p.N % 64 ||
-      !al16(p.src) || !al16(p.W) || !al16(p.out) || !al16(p.extra) || !al16(p.mask) || (p.extra && !p.mask))
+      !al16(p.src) || !al16(p.W) || !al16(p.out) || !al16(p.extra) || (p.extra && !p.mask))
     return hipErrorInvalidValue;
   if (p.g.stem && p.Cs != 256) return hipErrorInvalidValue;
   if (p.g.cls && (p.g.cls < 1 || p.g.cls > 4 || !p.g.transposed || p.g.stride != 2 || p.g.YO % 2 || p.g.XO % 2))

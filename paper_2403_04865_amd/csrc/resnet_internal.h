@@ -31,7 +31,8 @@ struct ConvGeom {
 };
 
 // out[M][N] (bf16) = sum over taps of src_tap[M][Cs] * W[N][tap * Cs .. + Cs]^T
-//                    (+ out when add != 0)  (+ (mask > 0 ? extra : 0) when extra is not null; extra, mask: [M][N]).
+//                    (+ out when add != 0)  (+ (mask bit ? extra : 0) when extra is not null; extra: [M][N], mask: one
+//                    bit per element of [M][N], bit e of byte i = element 8 i + e, as launch_bn_apply writes them).
 // The sums are formed in fp32 and rounded once.  M = n * YO * XO < 2^31, Cs % 64 == 0, N % 64 == 0; W row stride =
 // KH * KW * Cs.
 struct ConvNT {
@@ -41,7 +42,7 @@ struct ConvNT {
   long long M;
   ConvGeom g;
   int add;
-  const bf16* extra; const bf16* mask;
+  const bf16* extra; const unsigned char* mask;
 };
 hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s);
 
@@ -78,12 +79,14 @@ hipError_t launch_stem_wgrad_reduce(const float* part, int slabs, int Co, float*
 int bn_blocks(long long M, int C);
 hipError_t launch_bn_stats(const bf16* x, long long M, int C, const float* gamma, const float* beta, float eps,
                            float* part, float* stats, hipStream_t s);
-// y = a x + b  (+ resid, or + ra resid + rb when rstats is not null), then max(., 0) when relu
+// y = a x + b  (+ resid, or + ra resid + rb when rstats is not null), then max(., 0) when relu.  bits (may be null):
+// one bit per element, set where the stored y is positive (bit e of byte i = element 8 i + e): the ReLU mask of the
+// backward, a sixteenth of the bytes of y
 hipError_t launch_bn_apply(const bf16* x, long long M, int C, const float* stats, const bf16* resid, const float* rstats,
-                           int relu, bf16* y, hipStream_t s);
-// dz = (mask == null || mask > 0) ? dy : 0;  dgamma = sum dz x_hat, dbeta = sum dz (written or added to the
+                           int relu, bf16* y, unsigned char* bits, hipStream_t s);
+// dz = (mask == null || mask bit) ? dy : 0;  dgamma = sum dz x_hat, dbeta = sum dz (written or added to the
 // parameter gradients); dx = a (dz - dbeta / M - x_hat dgamma / M)
-hipError_t launch_bn_bwd(const bf16* dy, const bf16* mask, const bf16* x, long long M, int C, const float* stats,
+hipError_t launch_bn_bwd(const bf16* dy, const unsigned char* mask, const bf16* x, long long M, int C, const float* stats,
                          float* part, float* coef, float* dgamma, float* dbeta, int accumulate, bf16* dx, hipStream_t s);
 
 // 3x3 stride-2 pad-1 max pooling on [n][H][W][C]; of equal maxima the first in (kh, kw) order takes the gradient.
@@ -94,7 +97,4 @@ hipError_t launch_maxpool_bwd(const unsigned char* arg, const bf16* dy, bf16* dx
 // global average over the HW positions of each tile: feats [n][C] fp32; and its gradient
 hipError_t launch_avgpool_fwd(const bf16* x, float* feats, long long n, int HW, int C, hipStream_t s);
 hipError_t launch_avgpool_bwd(const float* dfeats, bf16* dx, long long n, int HW, int C, hipStream_t s);
-// dst += (mask > 0 ? src : 0), count elements (a multiple of 8)
-hipError_t launch_add_masked(bf16* dst, const bf16* src, const bf16* mask, long long count, hipStream_t s);
-
 }  // namespace sl

@@ -21,7 +21,8 @@ static_assert(RK_COUNT <= PROF_FAMILIES, "family arrays");
 struct Tensor { std::string name; size_t off, len; };
 
 // an activation tensor [n * H * H][C] (bf16): per-tile element count and, once laid out, its arena offset
-struct Act { int H, C; size_t off = 0; };
+// bits: one bit per element, set where the stored value is positive (kept for ReLU outputs: the mask of the backward)
+struct Act { int H, C; bool relu; size_t off = 0, bits = 0; };
 
 // one convolution with its batch normalisation
 struct ConvL {
@@ -88,8 +89,8 @@ size_t add_tensor(resnet_ctx* c, const std::string& name, size_t len) {
   return off;
 }
 
-int add_act(resnet_ctx* c, int H, int C) {
-  c->acts.push_back(Act{H, C});
+int add_act(resnet_ctx* c, int H, int C, bool relu) {
+  c->acts.push_back(Act{H, C, relu});
   size_t e = (size_t)H * H * C;
   if (e > c->max_act) c->max_act = e;
   return (int)c->acts.size() - 1;
@@ -104,7 +105,7 @@ int add_conv(resnet_ctx* c, const std::string& conv, const std::string& bn, int 
   L.og = add_tensor(c, bn + ".g", Cout);
   L.ob = add_tensor(c, bn + ".b", Cout);
   L.t_src = t_src;
-  L.t_conv = add_act(c, L.outH, Cout);
+  L.t_conv = add_act(c, L.outH, Cout, false);
   L.kCs = Cin; L.kK = K; L.kstride = stride; L.kpad = pad; L.kinH = inH;
   L.need_wt = need_wt;
   if (Cout > c->Cmax) c->Cmax = Cout;
@@ -138,8 +139,8 @@ RLayout make_layout(resnet_ctx* c, long long n, bool commit) {
   if (y.wpart_bytes < 16 * wmax) y.wpart_bytes = 16 * wmax;
   y.wpart = take(y.wpart_bytes);
   for (Act& a : c->acts) {
-    size_t o = take(nn * a.H * a.H * a.C * 2);
-    if (commit) a.off = o;
+    size_t o = take(nn * a.H * a.H * a.C * 2), b = a.relu ? take(nn * a.H * a.H * a.C / 8) : 0;
+    if (commit) { a.off = o; a.bits = b; }
   }
   y.img = take(nn * (c->S + 6) * (c->S + 8) * 4 * 2);   // padded pixel image of the stem
   y.parg = take(nn * (c->S / 4) * (c->S / 4) * c->cfg.width);   // winning taps of the max pooling, one byte each
@@ -151,6 +152,7 @@ RLayout make_layout(resnet_ctx* c, long long n, bool commit) {
 }
 
 bf16* act(const resnet_ctx* c, int id) { return (bf16*)(c->arena + c->acts[id].off); }
+unsigned char* act_bits(const resnet_ctx* c, int id) { return (unsigned char*)(c->arena + c->acts[id].bits); }
 long long rows_of(const resnet_ctx* c, int id, long long n) { return n * c->acts[id].H * c->acts[id].H; }
 const float* stats_of(const resnet_ctx* c, int conv) { return (const float*)(c->arena + c->convs[conv].stats); }
 
@@ -200,20 +202,23 @@ void conv_fwd(Run& r, int id, long long n) {
   });
 }
 
-void bn_apply(Run& r, int id, long long n, const bf16* resid, const float* rstats, bf16* out) {
+void bn_apply(Run& r, int id, long long n, const bf16* resid, const float* rstats, int t_out) {
   resnet_ctx* c = r.c;
   const ConvL& L = c->convs[id];
   const long long M = rows_of(c, L.t_conv, n);
   launch(r, RK_BN_APPLY, 0, (double)M * L.Cout * 2 * (resid ? 3 : 2),
-         [&] { return launch_bn_apply(act(c, L.t_conv), M, L.Cout, stats_of(c, id), resid, rstats, 1, out, r.s); });
+         [&] {
+           return launch_bn_apply(act(c, L.t_conv), M, L.Cout, stats_of(c, id), resid, rstats, 1, act(c, t_out),
+                                  act_bits(c, t_out), r.s);
+         });
 }
 
 // dx (rows of the convolution's output) from dy through ReLU mask and batch normalisation; gain / shift gradients
-void bn_bwd(Run& r, int id, long long n, const bf16* dy, const bf16* mask, bf16* dx, int accumulate) {
+void bn_bwd(Run& r, int id, long long n, const bf16* dy, const unsigned char* mask, bf16* dx, int accumulate) {
   resnet_ctx* c = r.c;
   const ConvL& L = c->convs[id];
   const long long M = rows_of(c, L.t_conv, n);
-  launch(r, RK_BN_BWD, 0, (double)M * L.Cout * 2 * 7, [&] {
+  launch(r, RK_BN_BWD, 0, (double)M * L.Cout * (2 * 5 + 0.25), [&] {
     return launch_bn_bwd(dy, mask, act(c, L.t_conv), M, L.Cout, stats_of(c, id), (float*)(c->arena + c->lay.bnpart),
                          (float*)(c->arena + c->lay.coef), c->grads + L.og, c->grads + L.ob, accumulate, dx, r.s);
   });
@@ -249,7 +254,7 @@ void conv_wgrad(Run& r, int id, long long n, const bf16* dout, int accumulate) {
 // gradient with respect to the convolution's source rows; add != 0 adds to what dsrc holds; extra (with mask): also
 // adds extra where mask > 0 (the gradient that reaches the block input through an identity shortcut)
 void conv_dgrad(Run& r, int id, long long n, const bf16* dout, bf16* dsrc, int add, const bf16* extra = nullptr,
-                const bf16* mask = nullptr) {
+                const unsigned char* mask = nullptr) {
   resnet_ctx* c = r.c;
   const ConvL& L = c->convs[id];
   ConvNT p{};
@@ -293,7 +298,7 @@ int enc_fwd(resnet_ctx* c, const void* pixels, long long n, void* feats_out, hip
   launch(r, RK_ELEMWISE, 0, (double)n * (3 * c->S * c->S + 4.0 * (c->S + 6) * (c->S + 8)) * 2,
          [&] { return launch_stem_pad_pixels((const bf16*)pixels, (bf16*)(c->arena + c->lay.img), n, c->S, s); });
   conv_fwd(r, 0, n);
-  bn_apply(r, 0, n, nullptr, nullptr, act(c, c->t_r0));
+  bn_apply(r, 0, n, nullptr, nullptr, c->t_r0);
   {
     const Act& a = c->acts[c->t_r0];
     launch(r, RK_POOLING, 0, (double)rows_of(c, c->t_r0, n) * a.C * 2 * 1.375,
@@ -305,11 +310,11 @@ int enc_fwd(resnet_ctx* c, const void* pixels, long long n, void* feats_out, hip
   for (const BlockL& b : c->blocks) {
     for (int k = 0; k < b.nconv; ++k) {
       conv_fwd(r, b.conv[k], n);
-      if (k + 1 < b.nconv) bn_apply(r, b.conv[k], n, nullptr, nullptr, act(c, b.t_r[k]));
+      if (k + 1 < b.nconv) bn_apply(r, b.conv[k], n, nullptr, nullptr, b.t_r[k]);
     }
     if (b.down >= 0) conv_fwd(r, b.down, n);
     bn_apply(r, b.conv[b.nconv - 1], n, b.down >= 0 ? act(c, c->convs[b.down].t_conv) : act(c, b.t_in),
-             b.down >= 0 ? stats_of(c, b.down) : nullptr, act(c, b.t_out));
+             b.down >= 0 ? stats_of(c, b.down) : nullptr, b.t_out);
   }
   const int t_last = c->blocks.back().t_out;
   const Act& a = c->acts[t_last];
@@ -334,7 +339,7 @@ int enc_bwd(resnet_ctx* c, const void* dfeats, long long n, int accumulate, hipS
   }
   for (int bi = (int)c->blocks.size() - 1; bi >= 0; --bi) {
     const BlockL& b = c->blocks[bi];
-    const bf16* out = act(c, b.t_out);
+    const unsigned char* out = act_bits(c, b.t_out);   // where the block's output is positive
     // gA: gradient at the block's output (behind the ReLU)
     bn_bwd(r, b.conv[b.nconv - 1], n, gA, out, gB, accumulate);
     for (int k = b.nconv - 1; k >= 0; --k) {
@@ -343,7 +348,7 @@ int enc_bwd(resnet_ctx* c, const void* dfeats, long long n, int accumulate, hipS
       // of the sum, no pass of its own)
       if (k == 0 && b.down < 0) conv_dgrad(r, b.conv[k], n, gB, gC, 0, gA, out);
       else conv_dgrad(r, b.conv[k], n, gB, gC, 0);
-      if (k > 0) bn_bwd(r, b.conv[k - 1], n, gC, act(c, b.t_r[k - 1]), gB, accumulate);
+      if (k > 0) bn_bwd(r, b.conv[k - 1], n, gC, act_bits(c, b.t_r[k - 1]), gB, accumulate);
     }
     // gC: gradient at the block's input through the residual branch; add the shortcut's
     if (b.down >= 0) {
@@ -359,7 +364,7 @@ int enc_bwd(resnet_ctx* c, const void* dfeats, long long n, int accumulate, hipS
     launch(r, RK_POOLING, 0, (double)rows_of(c, c->t_r0, n) * a.C * 2 * 1.375, [&] {
       return launch_maxpool_bwd((const unsigned char*)(c->arena + c->lay.parg), gA, gB, n, a.H, a.H, a.C, s);
     });
-    bn_bwd(r, 0, n, gB, act(c, c->t_r0), gC, accumulate);
+    bn_bwd(r, 0, n, gB, act_bits(c, c->t_r0), gC, accumulate);
     conv_wgrad(r, 0, n, gC, accumulate);
   }
   return finish(r);
@@ -394,8 +399,8 @@ int resnet_ctx_create(const resnet_config* cfg, resnet_ctx** out) {
     ConvL& L = c->convs[0];
     L.kCs = 256; L.kK = 1; L.kstride = 1; L.kpad = 0; L.kinH = L.outH;
   }
-  c->t_r0 = add_act(c, c->S / 2, w);
-  c->t_p0 = add_act(c, c->S / 4, w);
+  c->t_r0 = add_act(c, c->S / 2, w, true);
+  c->t_p0 = add_act(c, c->S / 4, w, false);
   int t_in = c->t_p0, cin = w, H = c->S / 4;
   for (int s = 0; s < 4; ++s) {
     const int mid = w << s, cout = mid * exp;
@@ -408,19 +413,19 @@ int resnet_ctx_create(const resnet_config* cfg, resnet_ctx** out) {
       if (!cfg->block) {
         b.nconv = 2;
         b.conv[0] = add_conv(c, p + "conv1", p + "bn1", cin, mid, 3, stride, 1, H, t_in, true);
-        b.t_r[0] = add_act(c, c->convs[b.conv[0]].outH, mid);
+        b.t_r[0] = add_act(c, c->convs[b.conv[0]].outH, mid, true);
         b.conv[1] = add_conv(c, p + "conv2", p + "bn2", mid, cout, 3, 1, 1, c->convs[b.conv[0]].outH, b.t_r[0], true);
       } else {
         b.nconv = 3;
         b.conv[0] = add_conv(c, p + "conv1", p + "bn1", cin, mid, 1, 1, 0, H, t_in, true);
-        b.t_r[0] = add_act(c, H, mid);
+        b.t_r[0] = add_act(c, H, mid, true);
         b.conv[1] = add_conv(c, p + "conv2", p + "bn2", mid, mid, 3, stride, 1, H, b.t_r[0], true);
-        b.t_r[1] = add_act(c, c->convs[b.conv[1]].outH, mid);
+        b.t_r[1] = add_act(c, c->convs[b.conv[1]].outH, mid, true);
         b.conv[2] = add_conv(c, p + "conv3", p + "bn3", mid, cout, 1, 1, 0, c->convs[b.conv[1]].outH, b.t_r[1], true);
       }
       if (down) b.down = add_conv(c, p + "down.conv", p + "down.bn", cin, cout, 1, stride, 0, H, t_in, true);
       H = c->convs[b.conv[b.nconv - 1]].outH;
-      b.t_out = add_act(c, H, cout);
+      b.t_out = add_act(c, H, cout, true);
       c->blocks.push_back(b);
       t_in = b.t_out; cin = cout;
     }
