@@ -60,14 +60,6 @@ __device__ __forceinline__ void two_sums(long long M, int C, float* part, F f) {
   }
 }
 
-__global__ void __launch_bounds__(256) bn_stats_part_k(const bf16* __restrict__ x, long long M, int C, float* __restrict__ part) {
-  two_sums(M, C, part, [&](long long off, int, float (&a)[8], float (&b)[8]) {
-    unpack8(ld16(x + off), a);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) b[e] = a[e] * a[e];
-  });
-}
-
 // The workgroups' partial sums of one channel, added in double by one wavefront: lane l takes partials l, l + 64, ...
 // in order, then the lanes are combined in a fixed butterfly (the same bits on every run).
 __device__ __forceinline__ void channel_sums(const float* __restrict__ part, int blocks, int C, int ch, double& s, double& q) {
@@ -98,6 +90,17 @@ __global__ void __launch_bounds__(256) bn_stats_final_k(const float* __restrict_
   stats[C + ch] = (float)rstd;
   stats[2 * C + ch] = (float)a;
   stats[3 * C + ch] = (float)((double)beta[ch] - mean * a);
+}
+
+// tile_part[tiles][2 C] -> part[workgroups][2 C]: every workgroup adds a contiguous range of tiles, column by column
+__global__ void __launch_bounds__(256) bn_tiles_part_k(const float* __restrict__ tp, int tiles, int C2, float* __restrict__ part) {
+  const int per = (tiles + gridDim.x - 1) / gridDim.x;
+  const int lo = blockIdx.x * per, hi = lo + per < tiles ? lo + per : tiles;
+  for (int col = threadIdx.x; col < C2; col += 256) {
+    float a = 0.f;
+    for (int t = lo; t < hi; ++t) a += tp[(long long)t * C2 + col];
+    part[(long long)blockIdx.x * C2 + col] = a;
+  }
 }
 
 __global__ void __launch_bounds__(256) bn_apply_k(const bf16* __restrict__ x, long long chunks, int C,
@@ -300,11 +303,12 @@ int bn_blocks(long long M, int C) {
   return (int)(b < 1 ? 1 : (b > BN_MAX_BLOCKS ? BN_MAX_BLOCKS : b));
 }
 
-hipError_t launch_bn_stats(const bf16* x, long long M, int C, const float* gamma, const float* beta, float eps,
-                           float* part, float* stats, hipStream_t s) {
-  if (!x || !gamma || !beta || !part || !stats || M <= 0 || !chan_ok(C) || !al16(x)) return hipErrorInvalidValue;
-  const int blocks = bn_blocks(M, C);
-  hipLaunchKernelGGL(bn_stats_part_k, dim3(blocks), dim3(256), 0, s, x, M, C, part);
+hipError_t launch_bn_stats_tiles(const float* tile_part, int tiles, long long M, int C, const float* gamma, const float* beta,
+                                 float eps, float* part, float* stats, hipStream_t s) {
+  if (!tile_part || tiles <= 0 || !gamma || !beta || !part || !stats || M <= 0 || !chan_ok(C)) return hipErrorInvalidValue;
+  int blocks = (tiles + 15) / 16;
+  if (blocks > BN_MAX_BLOCKS) blocks = BN_MAX_BLOCKS;
+  hipLaunchKernelGGL(bn_tiles_part_k, dim3(blocks), dim3(256), 0, s, tile_part, tiles, 2 * C, part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(bn_stats_final_k, dim3((C + 3) / 4), dim3(256), 0, s, part, blocks, M, C, gamma, beta, eps, stats);

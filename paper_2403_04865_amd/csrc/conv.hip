@@ -234,6 +234,9 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
       }
   __syncthreads();
   constexpr int CH = BN / 8;
+  float ss[8], qq[8];   // this thread's 8 channels (the same in every iteration: 256 % CH == 0) summed over its rows
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ss[e] = qq[e] = 0.f;
 #pragma unroll
   for (int it = 0; it < BM * CH / 256; ++it) {
     const int idx = tid + 256 * it;
@@ -266,8 +269,27 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
       }
       bf16x8 t;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) t[e] = (bf16)f[e];
+      for (int e = 0; e < 8; ++e) {
+        t[e] = (bf16)f[e];
+        const float v = (float)t[e];   // the statistics are those of the stored values
+        ss[e] += v;
+        qq[e] += v * v;
+      }
       *reinterpret_cast<bf16x8*>(p.out + at) = t;
+    }
+  }
+  if (p.stat_part) {   // uniform
+    __syncthreads();   // the tile has been read out
+    float* red = reinterpret_cast<float*>(smem);   // [2][256][8]
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { red[tid * 8 + e] = ss[e]; red[2048 + tid * 8 + e] = qq[e]; }
+    __syncthreads();
+    if (tid < BN) {   // channel tid of the tile: threads ch + CH j hold its pieces, added in order
+      const int ch = tid >> 3, e = tid & 7;
+      float a = 0.f, b = 0.f;
+      for (int j = 0; j < 256 / CH; ++j) { a += red[(ch + CH * j) * 8 + e]; b += red[2048 + (ch + CH * j) * 8 + e]; }
+      p.stat_part[((long long)rt * 2) * p.N + n0 + tid] = a;
+      p.stat_part[((long long)rt * 2 + 1) * p.N + n0 + tid] = b;
     }
   }
 }
@@ -460,11 +482,17 @@ bool geom_ok(const ConvGeom& g) {
 
 }  // namespace
 
+int conv_nt_row_tiles(const ConvNT& p) {
+  const int BMt = p.N % 128 == 0 ? 128 : 256;
+  return (int)((p.M + BMt - 1) / BMt);
+}
+
 hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
   if (!geom_ok(p.g) || p.M <= 0 || p.M >= (1LL << 31) - 256 || p.Cs <= 0 || p.Cs % CBK || p.N <= 0 || p.N % 64 ||
       !al16(p.src) || !al16(p.W) || !al16(p.out) || !al16(p.extra) || (p.extra && !p.mask))
     return hipErrorInvalidValue;
   if (p.g.stem && p.Cs != 256) return hipErrorInvalidValue;
+  if (p.stat_part && (p.add || p.extra || p.g.cls)) return hipErrorInvalidValue;   // sums of a whole, fresh output only
   if (p.g.cls && (p.g.cls < 1 || p.g.cls > 4 || !p.g.transposed || p.g.stride != 2 || p.g.YO % 2 || p.g.XO % 2))
     return hipErrorInvalidValue;
   // rows of one launch: whole tiles, or (parity class) a quarter of their positions

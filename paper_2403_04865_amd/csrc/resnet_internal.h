@@ -43,8 +43,13 @@ struct ConvNT {
   ConvGeom g;
   int add;
   const bf16* extra; const unsigned char* mask;
+  // optional: per row tile of the launch, the sums over the tile's rows of every output channel's stored value and of
+  // its square: stat_part[tile][2][N] (conv_nt_row_tiles(p) tiles); the statistics of the batch normalisation behind
+  // the convolution are built from these instead of a pass over the output
+  float* stat_part;
 };
 hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s);
+int conv_nt_row_tiles(const ConvNT& p);
 
 // part[slab][Co][KH * KW * Cs] (fp32) = sum over the slab's rows m of dout[m][co] * src_tap(m)[ci]; the rows
 // (n, y, x) run over the OUTPUT grid of the convolution (geometry not transposed).  Co % 64 == 0, Cs % 64 == 0,
@@ -77,8 +82,9 @@ hipError_t launch_stem_wgrad_reduce(const float* part, int slabs, int Co, float*
 // ---- batch normalisation over all rows of [M][C] (C % 8 == 0, C <= 2048) --------------------------------------------
 // stats: [4][C] floats: mean, 1 / sqrt(var + eps), a = gamma * rstd, b = beta - mean * a
 int bn_blocks(long long M, int C);
-hipError_t launch_bn_stats(const bf16* x, long long M, int C, const float* gamma, const float* beta, float eps,
-                           float* part, float* stats, hipStream_t s);
+// from per-tile sums tile_part[tiles][2][C] (as ConvNT::stat_part) over M rows in all
+hipError_t launch_bn_stats_tiles(const float* tile_part, int tiles, long long M, int C, const float* gamma, const float* beta,
+                                 float eps, float* part, float* stats, hipStream_t s);
 // y = a x + b  (+ resid, or + ra resid + rb when rstats is not null), then max(., 0) when relu.  bits (may be null):
 // one bit per element, set where the stored y is positive (bit e of byte i = element 8 i + e): the ReLU mask of the
 // backward, a sixteenth of the bytes of y

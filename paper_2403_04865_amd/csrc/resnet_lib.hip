@@ -48,7 +48,7 @@ struct BlockL {
 
 struct RLayout {
   size_t total = 0;
-  size_t pool, pool_bytes, H, G, bnpart, coef, wpart, wpart_bytes, img, parg, gA, gB, gC;
+  size_t pool, pool_bytes, H, G, bnpart, tpart, coef, wpart, wpart_bytes, img, parg, gA, gB, gC;
 };
 
 }  // namespace
@@ -133,6 +133,13 @@ RLayout make_layout(resnet_ctx* c, long long n, bool commit) {
     if (wb * 2 > wmax) wmax = wb * 2;   // one slab in fp32
   }
   y.bnpart = take((size_t)1024 * 2 * c->Cmax * 4);
+  // per-tile channel sums of a convolution's output: 8 bytes per channel and row tile of at least 128 rows
+  size_t tp = 0;
+  for (const ConvL& L : c->convs) {
+    const size_t rows = nn * L.outH * L.outH, tiles = (rows + 127) / 128;
+    if (tiles * L.Cout * 8 > tp) tp = tiles * L.Cout * 8;
+  }
+  y.tpart = take(tp);
   y.coef = take((size_t)2 * c->Cmax * 4);
   // room for the slab partials of any weight gradient: 1024 slabs of the small ones, at least 16 of the largest
   y.wpart_bytes = (size_t)512 << 20;
@@ -193,12 +200,15 @@ void conv_fwd(Run& r, int id, long long n) {
   ConvNT p{};
   p.src = conv_src(c, L); p.Cs = L.kCs; p.W = (const bf16*)(c->arena + L.w);
   p.out = act(c, L.t_conv); p.N = L.Cout; p.M = rows_of(c, L.t_conv, n); p.g = geom_fwd(L); p.add = 0;
+  p.stat_part = (float*)(c->arena + c->lay.tpart);
   const double K = (double)L.Cin * L.K * L.K;
   launch(r, RK_CONV_FWD, 2.0 * p.M * L.Cout * K, conv_bytes(c, L, p.M, n),
          [&] { return launch_conv_nt(p, r.s); });
-  launch(r, RK_BN_STATS, 0, (double)p.M * L.Cout * 2, [&] {
-    return launch_bn_stats(p.out, p.M, L.Cout, c->params + L.og, c->params + L.ob, c->cfg.bn_eps,
-                           (float*)(c->arena + c->lay.bnpart), (float*)(c->arena + L.stats), r.s);
+  // the statistics come from the per-tile sums the convolution's epilogue left
+  const int tiles = conv_nt_row_tiles(p);
+  launch(r, RK_BN_STATS, 0, (double)tiles * L.Cout * 8, [&] {
+    return launch_bn_stats_tiles(p.stat_part, tiles, p.M, L.Cout, c->params + L.og, c->params + L.ob, c->cfg.bn_eps,
+                                 (float*)(c->arena + c->lay.bnpart), (float*)(c->arena + L.stats), r.s);
   });
 }
 
