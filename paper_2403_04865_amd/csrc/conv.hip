@@ -116,9 +116,14 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
   constexpr int AG = BM / 32, BG = BN / 32;          // 8-row groups per wavefront and step
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* S = reinterpret_cast<bf16*>(smem);
+  // Workgroup ids are dealt round-robin to the 8 XCDs (each with its own L2).  Every XCD gets a contiguous range of
+  // row tiles and walks it in order, the column tiles of a row tile one after the other: what runs on an XCD at one
+  // time are neighbouring row tiles, whose gathered source rows overlap (the taps reach a row of positions up and
+  // down), so those rows come from HBM once instead of once per XCD.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int rt = (slot / col_tiles) * 8 + xcd, ct = slot % col_tiles;
-  if (rt >= row_tiles) return;
+  const int per_xcd = (row_tiles + 7) >> 3;
+  const int rt = xcd * per_xcd + slot / col_tiles, ct = slot % col_tiles;
+  if (slot / col_tiles >= per_xcd || rt >= row_tiles) return;
   const long long m0 = (long long)rt * BM;
   const int n0 = ct * BN;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -324,7 +329,13 @@ __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
   constexpr int SL = 1 + TAPS, SLICE = WBK * 64, STAGE = SL * SLICE;   // bf16 elements
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* S = reinterpret_cast<bf16*>(smem);   // [2][SL][32][64]
-  const int co0 = blockIdx.x * 64, ci0 = blockIdx.y * 64, slab = blockIdx.z;
+  // Workgroup ids go round-robin to the 8 XCDs: all (c_out, c_in) blocks of one slab get ids of one XCD, one after the
+  // other, so the slab's rows are fetched into that XCD's L2 once and not once per XCD that holds one of the blocks.
+  const int nco = p.Co >> 6, nci = p.Cs >> 6, pairs = nco * nci;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int slab = (slot / pairs) * 8 + xcd, pair = slot % pairs;
+  if (slab >= p.slabs) return;
+  const int co0 = (pair % nco) * 64, ci0 = (pair / nco) * 64;
   const long long lo = (long long)slab * p.per;
   const long long hi = lo + p.per < p.M ? lo + p.per : p.M;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -505,7 +516,7 @@ hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
   const int BMt = wide ? 128 : 256, BNt = wide ? 128 : 64;
   const int row_tiles = (int)((p.M + BMt - 1) / BMt);
   const int col_tiles = p.N / BNt;
-  const unsigned grid = (unsigned)((row_tiles + 7) / 8 * 8) * (unsigned)col_tiles;
+  const unsigned grid = (unsigned)((row_tiles + 7) / 8 * 8) * (unsigned)col_tiles;   // 8 XCDs x tiles per XCD x column tiles
   static bool attr_done = false;
   constexpr int NST = CONV_STAGES;
   // the operand stages, or the fp32 copy of the tile that takes their place at the end, whichever is larger
@@ -542,7 +553,9 @@ hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s) {
   if (p.g.stem && (p.Cs != 64 || taps != 1)) return hipErrorInvalidValue;   // 4 column groups of 64
   const long long n = p.M / ((long long)p.g.YO * p.g.XO);
   if (n * p.g.YS * p.g.XS >= (1LL << 31)) return hipErrorInvalidValue;
-  dim3 grid((unsigned)(p.Co / 64), (unsigned)(p.Cs / 64), (unsigned)p.slabs);
+  const long long nwg = (long long)((p.slabs + 7) / 8 * 8) * (p.Co / 64) * (p.Cs / 64);
+  if (nwg >= (1LL << 31)) return hipErrorInvalidValue;
+  dim3 grid((unsigned)nwg);
   auto lds_of = [](int taps_) { return (size_t)2 * (1 + taps_) * WBK * 64 * sizeof(bf16); };
   static bool attr_done = false;
   if (!attr_done) {
