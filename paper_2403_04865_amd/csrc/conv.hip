@@ -108,6 +108,89 @@ __device__ __forceinline__ void wait_vm() {   // until at most N vector-memory o
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070 | 0x0f00);
 }
 
+// The accumulators of a tile (one 64 x 64 block per wavefront) to memory: through LDS in fp32, then whole row segments;
+// what is added on the way (the output's old value, the shortcut's gradient) is added to the unrounded sums, so every
+// stored element is rounded once; optionally the tile's channel sums for the batch statistics.
+template <int BM, int BN>
+__device__ __forceinline__ void conv_tile_out(const ConvNT& p, const f32x16 (&acc)[2][2], unsigned char* smem, long long m0,
+                                              int n0, int rt, int tid, int lane, int wm, int wn) {
+  __syncthreads();   // every operand read is done: the stages become the fp32 copy of the tile
+
+  constexpr int CLDC = BN + 4;
+  float* Cs = reinterpret_cast<float*>(smem);
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = wm * 64 + i * 32 + (lane & 31);
+        const int col = wn * 64 + j * 32 + q * 8 + (lane >> 5) * 4;
+        *reinterpret_cast<float4*>(&Cs[row * CLDC + col]) =
+            make_float4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
+      }
+  __syncthreads();
+  constexpr int CH = BN / 8;
+  float ss[8], qq[8];   // this thread's 8 channels (the same in every iteration: 256 % CH == 0) summed over its rows
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ss[e] = qq[e] = 0.f;
+#pragma unroll
+  for (int it = 0; it < BM * CH / 256; ++it) {
+    const int idx = tid + 256 * it;
+    const int row = idx / CH, ch = idx - row * CH;
+    const long long m = m0 + row;
+    if (m < p.M) {
+      const float4 lo = *reinterpret_cast<const float4*>(&Cs[row * CLDC + ch * 8]);
+      const float4 hi = *reinterpret_cast<const float4*>(&Cs[row * CLDC + ch * 8 + 4]);
+      float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      long long orow = m;
+      if (p.g.cls) {   // the produced position's row in the full grid
+        int n, y, x;
+        launch_pos(m, p.M, p.g, n, y, x);
+        orow = ((long long)n * p.g.YO + y) * p.g.XO + x;
+      }
+      const long long at = orow * p.N + n0 + ch * 8;
+      if (p.add) {
+        const u32x4 o = *reinterpret_cast<const u32x4*>(p.out + at);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { f[2 * w] += __uint_as_float(o[w] << 16); f[2 * w + 1] += __uint_as_float(o[w] & 0xffff0000u); }
+      }
+      if (p.extra) {
+        const u32x4 x = *reinterpret_cast<const u32x4*>(p.extra + at);
+        const unsigned k = p.mask[at >> 3];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          f[2 * w] += (k >> (2 * w)) & 1u ? __uint_as_float(x[w] << 16) : 0.f;
+          f[2 * w + 1] += (k >> (2 * w + 1)) & 1u ? __uint_as_float(x[w] & 0xffff0000u) : 0.f;
+        }
+      }
+      bf16x8 t;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        t[e] = (bf16)f[e];
+        const float v = (float)t[e];   // the statistics are those of the stored values
+        ss[e] += v;
+        qq[e] += v * v;
+      }
+      *reinterpret_cast<bf16x8*>(p.out + at) = t;
+    }
+  }
+  if (p.stat_part) {   // uniform
+    __syncthreads();   // the tile has been read out
+    float* red = reinterpret_cast<float*>(smem);   // [2][256][8]
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { red[tid * 8 + e] = ss[e]; red[2048 + tid * 8 + e] = qq[e]; }
+    __syncthreads();
+    if (tid < BN) {   // channel tid of the tile: threads ch + CH j hold its pieces, added in order
+      const int ch = tid >> 3, e = tid & 7;
+      float a = 0.f, b = 0.f;
+      for (int j = 0; j < 256 / CH; ++j) { a += red[(ch + CH * j) * 8 + e]; b += red[2048 + (ch + CH * j) * 8 + e]; }
+      p.stat_part[((long long)rt * 2) * p.N + n0 + tid] = a;
+      p.stat_part[((long long)rt * 2 + 1) * p.N + n0 + tid] = b;
+    }
+  }
+}
+
 template <int BM, int BN, int NST, bool STEM>
 __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int col_tiles) {
   constexpr int STAGE = (BM + BN) * CBK;   // bf16 elements per stage
@@ -222,81 +305,138 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
     }
     st = st == NST - 1 ? 0 : st + 1;
   }
-  __syncthreads();   // every operand read is done: the stages become the fp32 copy of the tile
+  conv_tile_out<BM, BN>(p, acc, smem, m0, n0, rt, tid, lane, wm, wn);
+}
 
-  constexpr int CLDC = BN + 4;
-  float* Cs = reinterpret_cast<float*>(smem);
+// ---------------------------------------------------------------------------------------------------------------
+// forward / input gradient of 3x3 stride-1 convolutions with the tile's source rows resident in LDS
+// ---------------------------------------------------------------------------------------------------------------
+// For a 3x3 stride-1 pad-1 convolution (forward, or its input gradient, which is the same correlation with the taps
+// mirrored) source and result live on the same grid, and in the flattened row order (n, y, x) the source row of tap
+// (dy, dx) for result row m is m + dy * XO + dx wherever it exists.  The nine gathers of the general kernel fetch
+// nearly the same rows nine times.  Here the workgroup loads the window of source rows [m0 - XO - 1, m0 + BM + XO]
+// once (straight into LDS, all channels, pieces slot-permuted as in the general kernel), and a tap is an offset into
+// the window when the MFMA fragments are read; rows whose tap falls outside the image (a neighbouring image row or tile
+// in the flattened order) are zeroed in the fragment by a per-row tap mask.  Per K step only the 64 weight columns
+// are loaded (two stages).  LDS fill per tile drops from 9 x (BM + BN) x 128 bytes x C/64 to the window + the weights.
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) conv_nt_halo_k(ConvNT p, int row_tiles, int col_tiles, int wrows) {
+  constexpr int WN = BN / 64, WM = 4 / WN;
+  static_assert(WM * 64 == BM && (BN == 64 || BN == 128), "one 64 x 64 block per wavefront");
+  constexpr int BG = BN / 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16* Wd = reinterpret_cast<bf16*>(smem);          // window [wrows][Cs]
+  bf16* Bs = Wd + (long long)wrows * p.Cs;            // weights [2][BN][64]
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int per_xcd = (row_tiles + 7) >> 3;
+  const int rt = xcd * per_xcd + slot / col_tiles, ct = slot % col_tiles;
+  if (slot / col_tiles >= per_xcd || rt >= row_tiles) return;
+  const long long m0 = (long long)rt * BM;
+  const int n0 = ct * BN;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int lr = lane >> 3, ls = lane & 7;
+  const int cpt = p.Cs / CBK, cpr = p.Cs >> 3;       // K steps per tap, 16-byte pieces per row
+  const int nk = 9 * cpt;
+  const long long ldw = 9LL * p.Cs;
+  const int halo = p.g.XO + 1;
+  const int sg = p.g.transposed ? -1 : 1;
+  typedef const void __attribute__((address_space(1)))* gptr_t;
+  typedef void __attribute__((address_space(3)))* lptr_t;
+
+  // the window: instruction q of this wavefront fills pieces [(q * 4 + wave) * 64, + 64) in row-major order
+  const int ninst = wrows * cpr / 256;
+  for (int q = 0; q < ninst; ++q) {
+    const int gidx = (q * 4 + wave) * 64 + lane;
+    const int j = gidx / cpr, sl = gidx - j * cpr;
+    const int piece = (sl & ~7) | ((sl ^ (j >> 1)) & 7);
+    const long long f = m0 - halo + j;
+    const bool ok = (f >= 0) & (f < p.M) & (j < BM + 2 * halo);
+    const bf16* gp = ok ? p.src + f * p.Cs + piece * 8 : g_zero_row + (piece & 7) * 8;
+    __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(Wd + (long long)(q * 4 + wave) * 64 * 8), 16, 0, 0);
+  }
+  const bf16* wb[BG];
+#pragma unroll
+  for (int j = 0; j < BG; ++j) {
+    const int R = (j * 4 + wave) * 8 + lr;
+    wb[j] = p.W + (long long)(n0 + R) * ldw + (ls ^ ((R >> 1) & 7)) * 8;
+  }
+  auto issue_w = [&](int kt, int st) {
+    const int tap = kt / cpt;
+    const long long wcol = (long long)tap * p.Cs + (kt - tap * cpt) * CBK;
+#pragma unroll
+    for (int j = 0; j < BG; ++j)
+      __builtin_amdgcn_global_load_lds((gptr_t)(wb[j] + wcol), (lptr_t)(Bs + st * BN * CBK + (j * 4 + wave) * 8 * CBK), 16, 0, 0);
+  };
+  issue_w(0, 0);
+
+  // this lane's two fragment rows: window row of the centre tap, and which taps exist for them
+  const int frow = lane & 31, half = lane >> 5;
+  int wr0[2], offB[2], swB[2];
+  unsigned vm[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int R = wm * 64 + i * 32 + frow;
+    wr0[i] = R + halo;
+    int n, y, x;
+    row_pos(m0 + R, p.M, p.g, n, y, x);
+    unsigned m = 0;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) m |= (src_row(p.g, n, y, x, t / 3, t % 3) >= 0 ? 1u : 0u) << t;
+    vm[i] = m;
+    const int Rb = wn * 64 + i * 32 + frow;
+    offB[i] = Rb * CBK; swB[i] = (Rb >> 1) & 7;
+  }
+
+  f32x16 acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int row = wm * 64 + i * 32 + (lane & 31);
-        const int col = wn * 64 + j * 32 + q * 8 + (lane >> 5) * 4;
-        *reinterpret_cast<float4*>(&Cs[row * CLDC + col]) =
-            make_float4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
-      }
-  __syncthreads();
-  constexpr int CH = BN / 8;
-  float ss[8], qq[8];   // this thread's 8 channels (the same in every iteration: 256 % CH == 0) summed over its rows
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  int st = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    wait_vm<0>();                   // the window (first step) and this step's weights have landed ...
+    __builtin_amdgcn_s_barrier();   // ... for every wavefront, and the other weight stage is no longer read
+    if (kt + 1 < nk) issue_w(kt + 1, st ^ 1);
+    const int tap = kt / cpt, cc = kt - tap * cpt;
+    const int th = tap / 3;
+    const int shift = sg * ((th - 1) * p.g.XO + (tap - th * 3 - 1));
+    const bf16* sb = Bs + st * BN * CBK;
+    const bf16* sa[2];
+    bool on[2];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) ss[e] = qq[e] = 0.f;
+    for (int i = 0; i < 2; ++i) {
+      sa[i] = Wd + (long long)(wr0[i] + shift) * p.Cs + cc * CBK;
+      on[i] = (vm[i] >> tap) & 1u;
+    }
+    const int sw0 = ((wr0[0] + shift) >> 1) & 7, sw1 = ((wr0[1] + shift) >> 1) & 7;
 #pragma unroll
-  for (int it = 0; it < BM * CH / 256; ++it) {
-    const int idx = tid + 256 * it;
-    const int row = idx / CH, ch = idx - row * CH;
-    const long long m = m0 + row;
-    if (m < p.M) {
-      const float4 lo = *reinterpret_cast<const float4*>(&Cs[row * CLDC + ch * 8]);
-      const float4 hi = *reinterpret_cast<const float4*>(&Cs[row * CLDC + ch * 8 + 4]);
-      float f[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-      long long orow = m;
-      if (p.g.cls) {   // the produced position's row in the full grid
-        int n, y, x;
-        launch_pos(m, p.M, p.g, n, y, x);
-        orow = ((long long)n * p.g.YO + y) * p.g.XO + x;
-      }
-      const long long at = orow * p.N + n0 + ch * 8;
-      if (p.add) {
-        const u32x4 o = *reinterpret_cast<const u32x4*>(p.out + at);
+    for (int ks = 0; ks < CBK / 16; ++ks) {
+      const int c = ks * 2 + half;
+      bf16x8 fa[2], fb[2];
+      fa[0] = *reinterpret_cast<const bf16x8*>(sa[0] + ((c ^ sw0) << 3));
+      fa[1] = *reinterpret_cast<const bf16x8*>(sa[1] + ((c ^ sw1) << 3));
 #pragma unroll
-        for (int w = 0; w < 4; ++w) { f[2 * w] += __uint_as_float(o[w] << 16); f[2 * w + 1] += __uint_as_float(o[w] & 0xffff0000u); }
-      }
-      if (p.extra) {
-        const u32x4 x = *reinterpret_cast<const u32x4*>(p.extra + at);
-        const unsigned k = p.mask[at >> 3];
+      for (int i = 0; i < 2; ++i) {
+        fb[i] = *reinterpret_cast<const bf16x8*>(sb + offB[i] + ((c ^ swB[i]) << 3));
+        if (!on[i]) {
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          f[2 * w] += (k >> (2 * w)) & 1u ? __uint_as_float(x[w] << 16) : 0.f;
-          f[2 * w + 1] += (k >> (2 * w + 1)) & 1u ? __uint_as_float(x[w] & 0xffff0000u) : 0.f;
+          for (int e = 0; e < 8; ++e) fa[i][e] = (bf16)0.f;
         }
       }
-      bf16x8 t;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        t[e] = (bf16)f[e];
-        const float v = (float)t[e];   // the statistics are those of the stored values
-        ss[e] += v;
-        qq[e] += v * v;
-      }
-      *reinterpret_cast<bf16x8*>(p.out + at) = t;
-    }
-  }
-  if (p.stat_part) {   // uniform
-    __syncthreads();   // the tile has been read out
-    float* red = reinterpret_cast<float*>(smem);   // [2][256][8]
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { red[tid * 8 + e] = ss[e]; red[2048 + tid * 8 + e] = qq[e]; }
-    __syncthreads();
-    if (tid < BN) {   // channel tid of the tile: threads ch + CH j hold its pieces, added in order
-      const int ch = tid >> 3, e = tid & 7;
-      float a = 0.f, b = 0.f;
-      for (int j = 0; j < 256 / CH; ++j) { a += red[(ch + CH * j) * 8 + e]; b += red[2048 + (ch + CH * j) * 8 + e]; }
-      p.stat_part[((long long)rt * 2) * p.N + n0 + tid] = a;
-      p.stat_part[((long long)rt * 2 + 1) * p.N + n0 + tid] = b;
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
     }
+    st ^= 1;
   }
+  conv_tile_out<BM, BN>(p, acc, smem, m0, n0, rt, tid, lane, wm, wn);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -517,6 +657,27 @@ hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
   const int row_tiles = (int)((p.M + BMt - 1) / BMt);
   const int col_tiles = p.N / BNt;
   const unsigned grid = (unsigned)((row_tiles + 7) / 8 * 8) * (unsigned)col_tiles;   // 8 XCDs x tiles per XCD x column tiles
+  // 3x3 stride-1 convolutions whose source window fits the LDS next to the weight stages: the resident-window kernel
+  if (!p.g.stem && !p.g.cls && p.g.KH == 3 && p.g.KW == 3 && p.g.stride == 1 && p.g.pad == 1 && p.g.YS == p.g.YO &&
+      p.g.XS == p.g.XO && p.Cs <= 256) {
+    const int cpr = p.Cs / 8, unit = 256 / cpr;   // window rows come in units of 256 pieces (one instruction per wavefront)
+    const int wrows = (BMt + 2 * (p.g.XO + 1) + unit - 1) / unit * unit;
+    const size_t st = (size_t)wrows * p.Cs * 2 + (size_t)2 * BNt * CBK * 2, ep = (size_t)BMt * (BNt + 4) * sizeof(float);
+    const size_t lds = st > ep ? st : ep;
+    if (lds <= 160 * 1024) {
+      static size_t attr_w = 0, attr_n = 0;   // largest size the attribute has been raised to
+      size_t& have = wide ? attr_w : attr_n;
+      if (lds > have) {
+        hipError_t e = wide ? hipFuncSetAttribute((const void*)conv_nt_halo_k<128, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)
+                            : hipFuncSetAttribute((const void*)conv_nt_halo_k<256, 64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        have = lds;
+      }
+      if (wide) hipLaunchKernelGGL((conv_nt_halo_k<128, 128>), dim3(grid), dim3(256), lds, s, p, row_tiles, col_tiles, wrows);
+      else hipLaunchKernelGGL((conv_nt_halo_k<256, 64>), dim3(grid), dim3(256), lds, s, p, row_tiles, col_tiles, wrows);
+      return hipGetLastError();
+    }
+  }
   static bool attr_done = false;
   constexpr int NST = CONV_STAGES;
   // the operand stages, or the fp32 copy of the tile that takes their place at the end, whichever is larger
