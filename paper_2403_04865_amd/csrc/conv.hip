@@ -16,6 +16,7 @@
 //                  a fixed order by wgrad_reduce_k (no atomics: run-to-run identical), which also turns the
 //                  [co][tap][ci] order of the kernels into the parameter's [co][ci][kh][kw].
 #include "resnet_internal.h"
+#include <type_traits>
 
 namespace sl {
 
@@ -314,19 +315,26 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
 // For a 3x3 stride-1 pad-1 convolution (forward, or its input gradient, which is the same correlation with the taps
 // mirrored) source and result live on the same grid, and in the flattened row order (n, y, x) the source row of tap
 // (dy, dx) for result row m is m + dy * XO + dx wherever it exists.  The nine gathers of the general kernel fetch
-// nearly the same rows nine times.  Here the workgroup loads the window of source rows [m0 - XO - 1, m0 + BM + XO]
-// once (straight into LDS, all channels, pieces slot-permuted as in the general kernel), and a tap is an offset into
-// the window when the MFMA fragments are read; rows whose tap falls outside the image (a neighbouring image row or tile
-// in the flattened order) are zeroed in the fragment by a per-row tap mask.  Per K step only the 64 weight columns
-// are loaded (two stages).  LDS fill per tile drops from 9 x (BM + BN) x 128 bytes x C/64 to the window + the weights.
+// nearly the same rows nine times, and its K loop stops at a barrier every step.  Here
+//   * the workgroup loads the window of source rows [m0 - XO - 1, m0 + BM + XO] once (straight into LDS, all
+//     channels, pieces slot-permuted as in the general kernel); a tap is an offset into the window when the MFMA
+//     fragments are read, and rows whose tap falls outside the image (a neighbouring image row or tile in the flattened
+//     order) are zeroed in the fragment by a per-row tap mask;
+//   * the weights do not pass through LDS at all: a second copy of the weight matrix is kept in FRAGMENT ORDER (for
+//     every block of 32 output channels and 16 contraction columns the 64 lanes' 16-byte operands back to back, see
+//     frag_index), so a wavefront's operand is one fully coalesced 1 KB load into registers, fetched two K steps ahead;
+//   * so after the window has landed nothing in the K loop is shared between wavefronts: no barrier, every wavefront
+//     runs at its own pace.
+__host__ __device__ __forceinline__ long long frag_index(int row, int col, int K) {
+  return ((((long long)(row >> 5) * (K >> 4) + (col >> 4)) * 64 + (row & 31) + 32 * ((col >> 3) & 1)) << 3) + (col & 7);
+}
+
 template <int BM, int BN>
 __global__ void __launch_bounds__(256) conv_nt_halo_k(ConvNT p, int row_tiles, int col_tiles, int wrows) {
   constexpr int WN = BN / 64, WM = 4 / WN;
   static_assert(WM * 64 == BM && (BN == 64 || BN == 128), "one 64 x 64 block per wavefront");
-  constexpr int BG = BN / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16* Wd = reinterpret_cast<bf16*>(smem);          // window [wrows][Cs]
-  bf16* Bs = Wd + (long long)wrows * p.Cs;            // weights [2][BN][64]
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
   const int per_xcd = (row_tiles + 7) >> 3;
   const int rt = xcd * per_xcd + slot / col_tiles, ct = slot % col_tiles;
@@ -336,10 +344,8 @@ __global__ void __launch_bounds__(256) conv_nt_halo_k(ConvNT p, int row_tiles, i
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
-  const int lr = lane >> 3, ls = lane & 7;
   const int cpt = p.Cs / CBK, cpr = p.Cs >> 3;       // K steps per tap, 16-byte pieces per row
-  const int nk = 9 * cpt;
-  const long long ldw = 9LL * p.Cs;
+  const int nk = 9 * cpt;                            // a multiple of 3
   const int halo = p.g.XO + 1;
   const int sg = p.g.transposed ? -1 : 1;
   typedef const void __attribute__((address_space(1)))* gptr_t;
@@ -356,24 +362,27 @@ __global__ void __launch_bounds__(256) conv_nt_halo_k(ConvNT p, int row_tiles, i
     const bf16* gp = ok ? p.src + f * p.Cs + piece * 8 : g_zero_row + (piece & 7) * 8;
     __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(Wd + (long long)(q * 4 + wave) * 64 * 8), 16, 0, 0);
   }
-  const bf16* wb[BG];
+
+  // weights: operand (j, ks) of K step kt is the 1 KB at slice (block of 32 channels, 16 columns) of the fragment-order copy
+  const long long kslices = 9LL * p.Cs / 16;
+  const bf16* wf[2];
 #pragma unroll
-  for (int j = 0; j < BG; ++j) {
-    const int R = (j * 4 + wave) * 8 + lr;
-    wb[j] = p.W + (long long)(n0 + R) * ldw + (ls ^ ((R >> 1) & 7)) * 8;
-  }
-  auto issue_w = [&](int kt, int st) {
-    const int tap = kt / cpt;
-    const long long wcol = (long long)tap * p.Cs + (kt - tap * cpt) * CBK;
+  for (int j = 0; j < 2; ++j) wf[j] = p.Wf + ((long long)((n0 + wn * 64 + j * 32) >> 5) * kslices * 64 + lane) * 8;
+  bf16x8 breg[3][2][4];
+  auto fetch_w = [&](auto sc, int kt) __attribute__((always_inline)) {
+    constexpr int S = decltype(sc)::value;
 #pragma unroll
-    for (int j = 0; j < BG; ++j)
-      __builtin_amdgcn_global_load_lds((gptr_t)(wb[j] + wcol), (lptr_t)(Bs + st * BN * CBK + (j * 4 + wave) * 8 * CBK), 16, 0, 0);
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        breg[S][j][ks] = *reinterpret_cast<const bf16x8*>(wf[j] + ((long long)kt * 4 + ks) * 512);
   };
-  issue_w(0, 0);
+  fetch_w(std::integral_constant<int, 0>{}, 0);
+  fetch_w(std::integral_constant<int, 1>{}, 1);
 
   // this lane's two fragment rows: window row of the centre tap, and which taps exist for them
   const int frow = lane & 31, half = lane >> 5;
-  int wr0[2], offB[2], swB[2];
+  int wr0[2];
   unsigned vm[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
@@ -385,8 +394,6 @@ __global__ void __launch_bounds__(256) conv_nt_halo_k(ConvNT p, int row_tiles, i
 #pragma unroll
     for (int t = 0; t < 9; ++t) m |= (src_row(p.g, n, y, x, t / 3, t % 3) >= 0 ? 1u : 0u) << t;
     vm[i] = m;
-    const int Rb = wn * 64 + i * 32 + frow;
-    offB[i] = Rb * CBK; swB[i] = (Rb >> 1) & 7;
   }
 
   f32x16 acc[2][2];
@@ -397,32 +404,31 @@ __global__ void __launch_bounds__(256) conv_nt_halo_k(ConvNT p, int row_tiles, i
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  int st = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    wait_vm<0>();                   // the window (first step) and this step's weights have landed ...
-    __builtin_amdgcn_s_barrier();   // ... for every wavefront, and the other weight stage is no longer read
-    if (kt + 1 < nk) issue_w(kt + 1, st ^ 1);
+  wait_vm<0>();        // the window has landed (and the first weight operands) ...
+  __syncthreads();     // ... for every wavefront.  From here on the window is only read.
+
+  auto step = [&](auto sc, int kt) __attribute__((always_inline)) {
+    constexpr int S = decltype(sc)::value;
+    if (kt + 2 < nk) fetch_w(std::integral_constant<int, (S + 2) % 3>{}, kt + 2);
     const int tap = kt / cpt, cc = kt - tap * cpt;
     const int th = tap / 3;
     const int shift = sg * ((th - 1) * p.g.XO + (tap - th * 3 - 1));
-    const bf16* sb = Bs + st * BN * CBK;
     const bf16* sa[2];
+    int sw[2];
     bool on[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       sa[i] = Wd + (long long)(wr0[i] + shift) * p.Cs + cc * CBK;
+      sw[i] = ((wr0[i] + shift) >> 1) & 7;
       on[i] = (vm[i] >> tap) & 1u;
     }
-    const int sw0 = ((wr0[0] + shift) >> 1) & 7, sw1 = ((wr0[1] + shift) >> 1) & 7;
 #pragma unroll
     for (int ks = 0; ks < CBK / 16; ++ks) {
       const int c = ks * 2 + half;
-      bf16x8 fa[2], fb[2];
-      fa[0] = *reinterpret_cast<const bf16x8*>(sa[0] + ((c ^ sw0) << 3));
-      fa[1] = *reinterpret_cast<const bf16x8*>(sa[1] + ((c ^ sw1) << 3));
+      bf16x8 fa[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        fb[i] = *reinterpret_cast<const bf16x8*>(sb + offB[i] + ((c ^ swB[i]) << 3));
+        fa[i] = *reinterpret_cast<const bf16x8*>(sa[i] + ((c ^ sw[i]) << 3));
         if (!on[i]) {
 #pragma unroll
           for (int e = 0; e < 8; ++e) fa[i][e] = (bf16)0.f;
@@ -432,9 +438,13 @@ __global__ void __launch_bounds__(256) conv_nt_halo_k(ConvNT p, int row_tiles, i
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(breg[S][j][ks], fa[i], acc[i][j], 0, 0, 0);
     }
-    st ^= 1;
+  };
+  for (int kt = 0; kt < nk; kt += 3) {
+    step(std::integral_constant<int, 0>{}, kt);
+    step(std::integral_constant<int, 1>{}, kt + 1);
+    step(std::integral_constant<int, 2>{}, kt + 2);
   }
   conv_tile_out<BM, BN>(p, acc, smem, m0, n0, rt, tid, lane, wm, wn);
 }
@@ -569,7 +579,8 @@ __global__ void __launch_bounds__(256) wgrad_reduce_k(const float* __restrict__ 
 }
 
 __global__ void __launch_bounds__(256) conv_cast_w_k(const float* __restrict__ W, int Co, int Cin, int taps, int ldk,
-                                                      bf16* __restrict__ Wk, bf16* __restrict__ Wt) {
+                                                      bf16* __restrict__ Wk, bf16* __restrict__ Wt, bf16* __restrict__ Wf,
+                                                      bf16* __restrict__ Wtf) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i >= (long long)Co * ldk) return;
   const int co = (int)(i / ldk), col = (int)(i - (long long)co * ldk);
@@ -578,6 +589,8 @@ __global__ void __launch_bounds__(256) conv_cast_w_k(const float* __restrict__ W
     const int tap = col / Cin, ci = col - tap * Cin;
     v = W[((long long)co * Cin + ci) * taps + tap];
     if (Wt) Wt[(long long)ci * taps * Co + (long long)tap * Co + co] = (bf16)v;
+    if (Wf) Wf[frag_index(co, col, taps * Cin)] = (bf16)v;
+    if (Wtf) Wtf[frag_index(ci, tap * Co + co, taps * Co)] = (bf16)v;
   }
   Wk[i] = (bf16)v;
 }
@@ -658,11 +671,11 @@ hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
   const int col_tiles = p.N / BNt;
   const unsigned grid = (unsigned)((row_tiles + 7) / 8 * 8) * (unsigned)col_tiles;   // 8 XCDs x tiles per XCD x column tiles
   // 3x3 stride-1 convolutions whose source window fits the LDS next to the weight stages: the resident-window kernel
-  if (!p.g.stem && !p.g.cls && p.g.KH == 3 && p.g.KW == 3 && p.g.stride == 1 && p.g.pad == 1 && p.g.YS == p.g.YO &&
-      p.g.XS == p.g.XO && p.Cs <= 256) {
+  if (p.Wf && !p.g.stem && !p.g.cls && p.g.KH == 3 && p.g.KW == 3 && p.g.stride == 1 && p.g.pad == 1 && p.g.YS == p.g.YO &&
+      p.g.XS == p.g.XO && p.Cs <= 256 && al16(p.Wf)) {
     const int cpr = p.Cs / 8, unit = 256 / cpr;   // window rows come in units of 256 pieces (one instruction per wavefront)
     const int wrows = (BMt + 2 * (p.g.XO + 1) + unit - 1) / unit * unit;
-    const size_t st = (size_t)wrows * p.Cs * 2 + (size_t)2 * BNt * CBK * 2, ep = (size_t)BMt * (BNt + 4) * sizeof(float);
+    const size_t st = (size_t)wrows * p.Cs * 2, ep = (size_t)BMt * (BNt + 4) * sizeof(float);
     const size_t lds = st > ep ? st : ep;
     if (lds <= 160 * 1024) {
       static size_t attr_w = 0, attr_n = 0;   // largest size the attribute has been raised to
@@ -740,10 +753,12 @@ hipError_t launch_wgrad_reduce(const float* part, int slabs, int Co, int Cin, in
   return hipGetLastError();
 }
 
-hipError_t launch_conv_cast_w(const float* W, int Co, int Cin, int taps, int ldk, bf16* Wk, bf16* Wt, hipStream_t s) {
+hipError_t launch_conv_cast_w(const float* W, int Co, int Cin, int taps, int ldk, bf16* Wk, bf16* Wt, bf16* Wf, bf16* Wtf,
+                              hipStream_t s) {
   if (!W || !Wk || Co <= 0 || Cin <= 0 || taps <= 0 || ldk < taps * Cin) return hipErrorInvalidValue;
+  if ((Wf || Wtf) && (Co % 32 || Cin % 32 || ldk != taps * Cin)) return hipErrorInvalidValue;   // whole fragments only
   const long long total = (long long)Co * ldk;
-  hipLaunchKernelGGL(conv_cast_w_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, W, Co, Cin, taps, ldk, Wk, Wt);
+  hipLaunchKernelGGL(conv_cast_w_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, W, Co, Cin, taps, ldk, Wk, Wt, Wf, Wtf);
   return hipGetLastError();
 }
 

@@ -38,6 +38,7 @@ struct ConvGeom {
 struct ConvNT {
   const bf16* src; int Cs;
   const bf16* W;
+  const bf16* Wf;           // optional: the same matrix in fragment order (launch_conv_cast_w), used by the 3x3 stride-1 kernel
   bf16* out; int N;
   long long M;
   ConvGeom g;
@@ -69,8 +70,10 @@ hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s);
 hipError_t launch_wgrad_reduce(const float* part, int slabs, int Co, int Cin, int taps, int ldk, float* dW, int accumulate,
                                hipStream_t s);
 // fp32 W[co][ci][kh][kw] -> bf16 Wk[co][ldk] (column tap * Cin + ci, zero beyond taps * Cin) and, if Wt is not null,
-// Wt[ci][tap * Co + co]
-hipError_t launch_conv_cast_w(const float* W, int Co, int Cin, int taps, int ldk, bf16* Wk, bf16* Wt, hipStream_t s);
+// Wt[ci][tap * Co + co]; Wf / Wtf (optional): the same two matrices in fragment order: for every block of 32 rows and
+// 16 columns, the 64 MFMA lanes' operands (row l % 32, columns 8 (l / 32) .. + 7) back to back
+hipError_t launch_conv_cast_w(const float* W, int Co, int Cin, int taps, int ldk, bf16* Wk, bf16* Wt, bf16* Wf, bf16* Wtf,
+                              hipStream_t s);
 // planar pixels [n][3][S][S] (bf16) -> padded image [n][S + 6][S + 8][4] (see ConvGeom::stem), borders and the fourth
 // channel zero
 hipError_t launch_stem_pad_pixels(const bf16* pixels, bf16* img, long long n, int S, hipStream_t s);

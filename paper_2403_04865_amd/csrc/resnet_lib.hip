@@ -35,6 +35,7 @@ struct ConvL {
   int ldk() const { return kK * kK * kCs; }
   bool need_wt;                    // an input gradient is taken through it
   size_t w = 0, wt = 0, stats = 0; // arena offsets
+  size_t wf = 0, wtf = 0;          // fragment-order copies (3x3 stride-1 convolutions), 0 = none
 };
 
 struct BlockL {
@@ -128,7 +129,9 @@ RLayout make_layout(resnet_ctx* c, long long n, bool commit) {
   for (ConvL& L : c->convs) {
     size_t wb = (size_t)L.Cout * L.ldk() * 2;
     size_t w = take(wb), wt = L.need_wt ? take(wb) : 0, st = take((size_t)4 * L.Cout * 4);
-    if (commit) { L.w = w; L.wt = wt; L.stats = st; }
+    const bool frag = L.kK == 3 && L.kstride == 1 && L.need_wt;
+    size_t wf = frag ? take(wb) : 0, wtf = frag ? take(wb) : 0;
+    if (commit) { L.w = w; L.wt = wt; L.stats = st; L.wf = wf; L.wtf = wtf; }
     // partial weight gradients: see wgrad_slabs
     if (wb * 2 > wmax) wmax = wb * 2;   // one slab in fp32
   }
@@ -188,7 +191,8 @@ void cast_weights(Run& r) {
     launch(r, RK_ELEMWISE, 0, 0, [&] {
       if (is_stem(L)) return launch_stem_cast_w(c->params + L.oW, L.Cout, (bf16*)(c->arena + L.w), r.s);
       return launch_conv_cast_w(c->params + L.oW, L.Cout, L.kCs, L.kK * L.kK, L.ldk(), (bf16*)(c->arena + L.w),
-                                L.need_wt ? (bf16*)(c->arena + L.wt) : nullptr, r.s);
+                                L.need_wt ? (bf16*)(c->arena + L.wt) : nullptr, L.wf ? (bf16*)(c->arena + L.wf) : nullptr,
+                                L.wtf ? (bf16*)(c->arena + L.wtf) : nullptr, r.s);
     });
   }
 }
@@ -199,6 +203,7 @@ void conv_fwd(Run& r, int id, long long n) {
   const ConvL& L = c->convs[id];
   ConvNT p{};
   p.src = conv_src(c, L); p.Cs = L.kCs; p.W = (const bf16*)(c->arena + L.w);
+  p.Wf = L.wf ? (const bf16*)(c->arena + L.wf) : nullptr;
   p.out = act(c, L.t_conv); p.N = L.Cout; p.M = rows_of(c, L.t_conv, n); p.g = geom_fwd(L); p.add = 0;
   p.stat_part = (float*)(c->arena + c->lay.tpart);
   const double K = (double)L.Cin * L.K * L.K;
@@ -269,6 +274,7 @@ void conv_dgrad(Run& r, int id, long long n, const bf16* dout, bf16* dsrc, int a
   const ConvL& L = c->convs[id];
   ConvNT p{};
   p.src = dout; p.Cs = L.Cout; p.W = (const bf16*)(c->arena + L.wt); p.out = dsrc; p.N = L.kCs;
+  p.Wf = L.wtf ? (const bf16*)(c->arena + L.wtf) : nullptr;
   p.M = rows_of(c, L.t_src, n);
   p.g.YO = p.g.XO = L.kinH; p.g.YS = p.g.XS = L.outH; p.g.KH = p.g.KW = L.kK; p.g.stride = L.kstride; p.g.pad = L.kpad;
   p.g.transposed = 1;
