@@ -28,7 +28,7 @@ __device__ __forceinline__ void st8(bf16* p, const float (&v)[8]) {
   *reinterpret_cast<bf16x8*>(p) = t;
 }
 
-constexpr int BN_MAX_BLOCKS = 1024;
+constexpr int BN_MAX_BLOCKS = 4096;
 
 // Two per-channel sums over the rows of one workgroup's range.  F(row pointer offset, channel base, out a[8], out b[8])
 // yields the two summands of 8 channels of one row.
@@ -290,16 +290,17 @@ __global__ void __launch_bounds__(256) avgpool_bwd_k(const float* __restrict__ d
 
 bool chan_ok(int C) { return C >= 64 && C <= 2048 && (C & (C - 1)) == 0; }
 bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+// one 16-byte piece per thread where the grid allows it (measured: 4.1 -> 4.5 TB/s against 16384 workgroups that loop)
 unsigned stream_grid(long long chunks) {
   long long b = (chunks + 255) / 256;
-  return (unsigned)(b < 1 ? 1 : (b > 16384 ? 16384 : b));
+  return (unsigned)(b < 1 ? 1 : (b > 4194304 ? 4194304 : b));
 }
 
 }  // namespace
 
 int bn_blocks(long long M, int C) {
   (void)C;
-  long long b = M / 256;
+  long long b = M / 128;
   return (int)(b < 1 ? 1 : (b > BN_MAX_BLOCKS ? BN_MAX_BLOCKS : b));
 }
 

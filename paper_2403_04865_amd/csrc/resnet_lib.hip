@@ -135,7 +135,7 @@ RLayout make_layout(resnet_ctx* c, long long n, bool commit) {
     // partial weight gradients: see wgrad_slabs
     if (wb * 2 > wmax) wmax = wb * 2;   // one slab in fp32
   }
-  y.bnpart = take((size_t)1024 * 2 * c->Cmax * 4);
+  y.bnpart = take((size_t)4096 * 2 * c->Cmax * 4);
   // per-tile channel sums of a convolution's output: 8 bytes per channel and row tile of at least 128 rows
   size_t tp = 0;
   for (const ConvL& L : c->convs) {
