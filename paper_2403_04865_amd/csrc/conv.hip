@@ -504,17 +504,29 @@ __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
     bf16* sa = S + st * STAGE + wave * 8 * 64;
     const bf16* gd = ok ? p.dout + m * p.Co + co0 + cl : g_zero_row + cl;
     __builtin_amdgcn_global_load_lds((gptr_t)gd, (lptr_t)sa, 16, 0, 0);
+    if (STEM) {   // the four 64-column groups of the stem's 256 contraction columns stand where the taps stand
 #pragma unroll
-    for (int t = 0; t < TAPS; ++t) {
-      const bf16* gp;
-      if (STEM) {   // the four 64-column groups of the stem's 256 contraction columns stand where the taps stand
-        gp = ok ? p.src + stem_off(p.g, n, y, x, t * 64 + cl) : g_zero_row + cl;
-      } else {
-        const int kh = TAPS == 1 ? 0 : t / 3, kw = TAPS == 1 ? 0 : t % 3;
-        const long long sr = src_row(p.g, n, y, x, kh, kw);
-        gp = (ok & (sr >= 0)) ? p.src + sr * p.Cs + ci0 + cl : g_zero_row + cl;
+      for (int t = 0; t < TAPS; ++t) {
+        const bf16* gp = ok ? p.src + stem_off(p.g, n, y, x, t * 64 + cl) : g_zero_row + cl;
+        __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(sa + (1 + t) * SLICE), 16, 0, 0);
       }
-      __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(sa + (1 + t) * SLICE), 16, 0, 0);
+    } else {
+      // the row's source position for tap (0, 0), once; a tap adds a uniform offset, and exists where both of its
+      // coordinates fall inside the source grid
+      const int ys0 = y * p.g.stride - p.g.pad, xs0 = x * p.g.stride - p.g.pad;
+      const bf16* base = p.src + (((long long)n * p.g.YS + ys0) * p.g.XS + xs0) * p.Cs + ci0 + cl;
+      bool oky[3], okx[3];
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        oky[k] = ok & ((unsigned)(ys0 + k) < (unsigned)p.g.YS);
+        okx[k] = (unsigned)(xs0 + k) < (unsigned)p.g.XS;
+      }
+#pragma unroll
+      for (int t = 0; t < TAPS; ++t) {
+        const int kh = TAPS == 1 ? 0 : t / 3, kw = TAPS == 1 ? 0 : t % 3;
+        const bf16* gp = (oky[kh] & okx[kw]) ? base + (long long)(kh * p.g.XS + kw) * p.Cs : g_zero_row + cl;
+        __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(sa + (1 + t) * SLICE), 16, 0, 0);
+      }
     }
   };
 
