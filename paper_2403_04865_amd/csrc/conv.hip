@@ -222,12 +222,28 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
   const int nky = p.g.KH > kh0 ? (p.g.KH - kh0 + tstep - 1) / tstep : 0, nkx = p.g.KW > kw0 ? (p.g.KW - kw0 + tstep - 1) / tstep : 0;
   const int nk = nky * nkx * cpt;
 
+  // Per row of the tile, once: the position, the address of its source row for tap offset zero and which of the
+  // launch's taps exist for it.  A K step then costs a mask test and the step's uniform offset per row.
   int pn[AG], py[AG], px[AG], pc[AG];
+  const bf16* rb[AG];
+  unsigned rm[AG];
+  const int sh = p.g.stride >> 1;
 #pragma unroll
   for (int j = 0; j < AG; ++j) {
     const int R = (j * 4 + wave) * 8 + lr;
     launch_pos(m0 + R, p.M, p.g, pn[j], py[j], px[j]);
     pc[j] = (ls ^ ((R >> 1) & 7)) * 8;
+    if (!STEM) {
+      const int yb = p.g.transposed ? (py[j] + p.g.pad) >> sh : py[j] * p.g.stride - p.g.pad;
+      const int xb = p.g.transposed ? (px[j] + p.g.pad) >> sh : px[j] * p.g.stride - p.g.pad;
+      rb[j] = p.src + (((long long)pn[j] * p.g.YS + yb) * p.g.XS + xb) * p.Cs + pc[j];
+      unsigned m = 0;
+      for (int t = 0; t < nky * nkx; ++t) {
+        const int ty = t / nkx;
+        m |= (src_row(p.g, pn[j], py[j], px[j], kh0 + tstep * ty, kw0 + tstep * (t - ty * nkx)) >= 0 ? 1u : 0u) << t;
+      }
+      rm[j] = m;
+    }
   }
   const bf16* wb[BG];
 #pragma unroll
@@ -242,16 +258,14 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
     const int ty = tap / nkx;
     const int kh = kh0 + tstep * ty, kw = kw0 + tstep * (tap - ty * nkx);
     const long long wcol = (long long)(kh * p.g.KW + kw) * p.Cs + c0;   // column of this step in the weight rows
+    // the tap's offset from a row's base address (input gradient: taps count backwards, in source steps)
+    const long long soff = (p.g.transposed ? -(long long)((kh >> sh) * p.g.XS + (kw >> sh)) : (long long)(kh * p.g.XS + kw)) * p.Cs + c0;
     bf16* sa = S + st * STAGE;
 #pragma unroll
     for (int j = 0; j < AG; ++j) {
       const bf16* gp;
-      if (STEM) {
-        gp = py[j] != ROW_ABSENT ? p.src + stem_off(p.g, pn[j], py[j], px[j], c0 + pc[j]) : g_zero_row + pc[j];
-      } else {
-        const long long sr = src_row(p.g, pn[j], py[j], px[j], kh, kw);
-        gp = sr >= 0 ? p.src + sr * p.Cs + c0 + pc[j] : g_zero_row + pc[j];
-      }
+      if (STEM) gp = py[j] != ROW_ABSENT ? p.src + stem_off(p.g, pn[j], py[j], px[j], c0 + pc[j]) : g_zero_row + pc[j];
+      else gp = (rm[j] >> tap) & 1u ? rb[j] + soff : g_zero_row + pc[j];
       __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(sa + (j * 4 + wave) * 8 * CBK), 16, 0, 0);
     }
 #pragma unroll
