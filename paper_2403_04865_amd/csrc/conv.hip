@@ -115,8 +115,52 @@ __device__ __forceinline__ void wait_vm() {   // until at most N vector-memory o
 template <int BM, int BN>
 __device__ __forceinline__ void conv_tile_out(const ConvNT& p, const f32x16 (&acc)[2][2], unsigned char* smem, long long m0,
                                               int n0, int rt, int tid, int lane, int wm, int wn) {
-  __syncthreads();   // every operand read is done: the stages become the fp32 copy of the tile
+  __syncthreads();   // every operand read is done: the stages become the copy of the tile
 
+  constexpr int CH = BN / 8;
+  float ss[8], qq[8];   // this thread's 8 channels (the same in every iteration: 256 % CH == 0) summed over its rows
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ss[e] = qq[e] = 0.f;
+  if (!p.add && !p.extra) {   // uniform: nothing is added on the way, the tile can cross LDS as bf16 (half the LDS traffic)
+    constexpr int CLDB = BN + 8;
+    bf16* Cb = reinterpret_cast<bf16*>(smem);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int row = wm * 64 + i * 32 + (lane & 31);
+          const int col = wn * 64 + j * 32 + q * 8 + (lane >> 5) * 4;
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = (bf16)acc[i][j][q * 4 + e];
+          *reinterpret_cast<bf16x4*>(&Cb[row * CLDB + col]) = v;
+        }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < BM * CH / 256; ++it) {
+      const int idx = tid + 256 * it;
+      const int row = idx / CH, ch = idx - row * CH;
+      const long long m = m0 + row;
+      if (m < p.M) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(&Cb[row * CLDB + ch * 8]);
+        long long orow = m;
+        if (p.g.cls) {   // the produced position's row in the full grid
+          int n, y, x;
+          launch_pos(m, p.M, p.g, n, y, x);
+          orow = ((long long)n * p.g.YO + y) * p.g.XO + x;
+        }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {   // the statistics are those of the stored values
+          const float lo = __uint_as_float(v[w] << 16), hi = __uint_as_float(v[w] & 0xffff0000u);
+          ss[2 * w] += lo; qq[2 * w] += lo * lo;
+          ss[2 * w + 1] += hi; qq[2 * w + 1] += hi * hi;
+        }
+        *reinterpret_cast<u32x4*>(p.out + orow * p.N + n0 + ch * 8) = v;
+      }
+    }
+  } else {
   constexpr int CLDC = BN + 4;
   float* Cs = reinterpret_cast<float*>(smem);
 #pragma unroll
@@ -131,10 +175,6 @@ __device__ __forceinline__ void conv_tile_out(const ConvNT& p, const f32x16 (&ac
             make_float4(acc[i][j][q * 4], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]);
       }
   __syncthreads();
-  constexpr int CH = BN / 8;
-  float ss[8], qq[8];   // this thread's 8 channels (the same in every iteration: 256 % CH == 0) summed over its rows
-#pragma unroll
-  for (int e = 0; e < 8; ++e) ss[e] = qq[e] = 0.f;
 #pragma unroll
   for (int it = 0; it < BM * CH / 256; ++it) {
     const int idx = tid + 256 * it;
@@ -175,6 +215,7 @@ __device__ __forceinline__ void conv_tile_out(const ConvNT& p, const f32x16 (&ac
       }
       *reinterpret_cast<bf16x8*>(p.out + at) = t;
     }
+  }
   }
   if (p.stat_part) {   // uniform
     __syncthreads();   // the tile has been read out
