@@ -15,6 +15,8 @@
 // with dS = P * (dP - delta), dP = dO V^T, delta_i = dO_i . O_i.  No atomics.
 #include "slide_internal.h"
 
+#include <type_traits>
+
 namespace sl {
 
 namespace {
@@ -148,8 +150,10 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
     float mx = -INFINITY, l = 0.f;
     const bf16* krow = krow0;
     const bf16* vtr = vtr0;
-#pragma unroll 1
-    for (int kb = 0; kb < NB; ++kb, krow += 32 * LDR, vtr += 32 * LDR) {
+    // one block of 32 keys; LASTB: the head's last block, the only one that holds padded keys (its own copy of the
+    // loop body, so that the other blocks carry no mask arithmetic)
+    auto key_block = [&](auto lastb) __attribute__((always_inline)) {
+      constexpr bool LASTB = decltype(lastb)::value;
       f32x16 sc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) sc[r] = 0.f;
@@ -161,8 +165,8 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
       float bm = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        if (kb == NB - 1) {   // only the last block holds padded keys
-          int key = kb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
+        if (LASTB) {
+          int key = (NB - 1) * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
           if (key >= T) sc[r] = -INFINITY;
         }
         bm = fmaxf(bm, sc[r]);
@@ -198,7 +202,10 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
           o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb, o[d], 0, 0, 0);
         }
       }
-    }
+    };
+#pragma unroll 1
+    for (int kb = 0; kb < NB - 1; ++kb, krow += 32 * LDR, vtr += 32 * LDR) key_block(std::false_type{});
+    key_block(std::true_type{});
     l += __shfl_xor(l, 32, 64);
     if (q < T) {
       float inv = 1.0f / l;
@@ -303,8 +310,10 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
     const bf16* krow = krow0;
     const bf16* vrow = vrow0;
     const bf16* ktr = ktr0;
-#pragma unroll 1
-    for (int kb = 0; kb < NB; ++kb, krow += 32 * LDR, vrow += 32 * LDR, ktr += 32 * LDR) {
+    // one block of 32 keys; LASTB: the head's last block, the only one that holds padded keys (its own copy of the
+    // loop body, so that the other blocks carry no mask arithmetic)
+    auto key_block = [&](auto lastb) __attribute__((always_inline)) {
+      constexpr bool LASTB = decltype(lastb)::value;
       f32x16 s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
@@ -319,8 +328,8 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         float p = __builtin_amdgcn_exp2f(s[r] * sl2 - lq);
-        if (kb == NB - 1) {   // only the last block holds padded keys
-          int key = kb * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
+        if (LASTB) {
+          int key = (NB - 1) * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
           if (key >= T) p = 0.f;
         }
         ds[r] = p * (dp[r] - delta);
@@ -334,7 +343,10 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
           dq[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, db, dq[d], 0, 0, 0);
         }
       }
-    }
+    };
+#pragma unroll 1
+    for (int kb = 0; kb < NB - 1; ++kb, krow += 32 * LDR, vrow += 32 * LDR, ktr += 32 * LDR) key_block(std::false_type{});
+    key_block(std::true_type{});
     if (q < T) {
       bf16* out = dqkv + (tile * T + q) * gs + h * DH;
 #pragma unroll

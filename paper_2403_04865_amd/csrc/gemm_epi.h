@@ -20,11 +20,12 @@ __device__ __forceinline__ void epi_store_mode(int mode, const GemmNT& g, long l
       float gl, dg;
       gelu_both(acc + g.bias[n], &gl, &dg);
       ((T*)g.out)[m * g.ldc + n] = from_f<T>(gl);
-      ((T*)g.out2)[m * g.ldc2 + n] = from_f<T>(dg);
+      ((typename dgelu_store<T>::type*)g.out2)[m * g.ldc2 + n] = dgelu_store<T>::put(dg);
       break;
     }
     case EPI_DGELU:
-      ((T*)g.out)[m * g.ldc + n] = from_f<T>(acc * to_f(((const T*)g.pre)[m * g.ldpre + n]));
+      ((T*)g.out)[m * g.ldc + n] =
+          from_f<T>(acc * dgelu_store<T>::get(((const typename dgelu_store<T>::type*)g.pre)[m * g.ldpre + n]));
       break;
     case EPI_PATCH: {
       long long mm = g.cmap(m);

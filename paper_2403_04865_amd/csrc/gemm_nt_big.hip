@@ -73,15 +73,16 @@ __device__ __forceinline__ void unpack8(u32x4 t, float (&v)[8]) {
   }
 }
 
-// table entry k: {cdf(x_k), cdf(x_k+1) - cdf(x_k), dg(x_k), dg(x_k+1) - dg(x_k)}, x_k = -7 + k/32,
-// cdf = standard normal distribution function, dg(x) = cdf(x) + x * pdf(x) = d/dx (x cdf(x))
-__device__ __forceinline__ void gelu_both_tab(const float4* tab, float x, float* gl, float* dg) {
+// table entry k: {cdf(x_k), cdf(x_k+1) - cdf(x_k), c(x_k), c(x_k+1) - c(x_k)}, x_k = -7 + k/32,
+// cdf = standard normal distribution function, dg(x) = cdf(x) + x * pdf(x) = d/dx (x cdf(x)) and c = dg8_code(dg),
+// the derivative in the code space of its one-byte storage
+__device__ __forceinline__ void gelu_both_tab(const float4* tab, float x, float* gl, float* dgc) {
   float t = __builtin_amdgcn_fmed3f(x * 32.0f + 224.0f, 0.0f, (float)TAB_N - 0.001f);
   int k = (int)t;                       // t >= 0: truncation is the floor
   float f = __builtin_amdgcn_fractf(t);
   float4 e = tab[k];
   *gl = x * (e.x + f * e.y);
-  *dg = e.z + f * e.w;
+  *dgc = e.z + f * e.w;
 }
 
 template <class F, int... Is>
@@ -122,7 +123,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
       float c0 = 0.5f * (1.0f + erff(x0 * 0.70710678118654752f)), c1 = 0.5f * (1.0f + erff(x1 * 0.70710678118654752f));
       float d0 = c0 + x0 * 0.39894228040143268f * expf(-0.5f * x0 * x0);
       float d1 = c1 + x1 * 0.39894228040143268f * expf(-0.5f * x1 * x1);
-      tab[k] = make_float4(c0, c1 - c0, d0, d1 - d0);
+      tab[k] = make_float4(c0, c1 - c0, dg8_code(d0), dg8_code(d1) - dg8_code(d0));
     }
   }
 
@@ -238,14 +239,17 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   u32x2 park[WBM - 1][WBN][4];
   long long pmw = 0;   // first row / column of the parked block (uniform)
   int pnw = 0;
-  u32x4 rowdat[NPASS], auxv[2][NPASS];   // auxiliary row segments of two strips: one in use, one in flight
+  typedef std::conditional_t<MODE == EPI_DGELU, u32x2, u32x4> aux_t;   // eight codes / eight bf16
+  u32x4 rowdat[NPASS];
+  aux_t auxv[2][NPASS];   // auxiliary row segments of two strips: one in use, one in flight
   const int er = lane < 60 ? lane / 12 : 0;    // row inside a pass (idle lanes: a valid address)
   const int erc = lane < 60 ? lane / 12 : 64;  // the same for comparisons: idle lanes never pass
   const int esg = lane % 12;
-  const unsigned ldc_b = 2u * (unsigned)g.ldc, ldc2_b = 2u * (unsigned)g.ldc2;
-  const unsigned lda_b = 2u * (unsigned)(MODE == EPI_BIAS_RESID ? g.ldr : g.ldpre);
-  const unsigned eo_c = (unsigned)er * ldc_b + esg * 16, eo_c2 = (unsigned)er * ldc2_b + esg * 16;
-  const unsigned eo_a = (unsigned)er * lda_b + esg * 16;
+  const unsigned ldc_b = 2u * (unsigned)g.ldc, ldc2_b = (unsigned)g.ldc2;   // bytes (the derivative: one per element)
+  const unsigned lda_b = MODE == EPI_BIAS_RESID ? 2u * (unsigned)g.ldr : (unsigned)g.ldpre;
+  constexpr int AUXW = MODE == EPI_DGELU ? 1 : 2;   // bytes per element of the auxiliary operand
+  const unsigned eo_c = (unsigned)er * ldc_b + esg * 16, eo_c2 = (unsigned)er * ldc2_b + esg * 8;
+  const unsigned eo_a = (unsigned)er * lda_b + esg * (8 * AUXW);
   unsigned char* const pw = patches + wave * PATCH_BYTES + (lane & 31) * PSB + (lane >> 5) * 8;
   const unsigned char* const pr = patches + wave * PATCH_BYTES + er * PSB + esg * 16;
   const char* const aux_ptr = (const char*)(MODE == EPI_BIAS_RESID ? g.resid : g.pre);
@@ -267,25 +271,34 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     constexpr int I = decltype(ic)::value, p = decltype(pc)::value;
     if constexpr (HAS_AUX) {
       if (p * 5 < lim) {  // uniform; lanes past the end read the pass's first row (never stored)
-        const char* base = aux_ptr + ((pmw + I * 32 + p * 5) * (long long)lda_b + 2 * pnw);
-        auxv[I & 1][p] = ldg16(base, p * 5 + erc < lim ? eo_a : (unsigned)(esg * 16));
+        const char* base = aux_ptr + ((pmw + I * 32 + p * 5) * (long long)lda_b + AUXW * pnw);
+        auxv[I & 1][p] = *reinterpret_cast<const aux_t*>(base + (p * 5 + erc < lim ? eo_a : (unsigned)(esg * (8 * AUXW))));
       }
     }
   };
   // pass p of strip I: combine the row segment with the auxiliary operand (results stay in registers) ...
-  u32x4 res[NPASS], res2[MODE == EPI_BIAS_GELU ? NPASS : 1];
+  u32x4 res[NPASS];
+  u32x2 res2[MODE == EPI_BIAS_GELU ? NPASS : 1];
   auto bg_cmp = [&](auto ic, auto pc) __attribute__((always_inline)) {
     constexpr int I = decltype(ic)::value, p = decltype(pc)::value;
     if constexpr (MODE == EPI_PLAIN || MODE == EPI_BIAS) {
       res[p] = rowdat[p];
-    } else if constexpr (MODE == EPI_BIAS_RESID || MODE == EPI_DGELU) {
+    } else if constexpr (MODE == EPI_BIAS_RESID) {
       float v[8], t[8];
       unpack8(rowdat[p], v);
       unpack8(auxv[I & 1][p], t);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = MODE == EPI_DGELU ? v[e] * t[e] : v[e] + t[e];
+      for (int e = 0; e < 8; ++e) v[e] += t[e];
       res[p] = pack8(v);
-    } else {  // EPI_BIAS_GELU: out = gelu(m), out2 = gelu'(m), m the bf16-rounded pre-activation
+    } else if constexpr (MODE == EPI_DGELU) {
+      float v[8], t0[4], t1[4];
+      unpack8(rowdat[p], v);
+      dg8_unpack4(auxv[I & 1][p][0], t0);
+      dg8_unpack4(auxv[I & 1][p][1], t1);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { v[e] *= t0[e]; v[4 + e] *= t1[e]; }
+      res[p] = pack8(v);
+    } else {  // EPI_BIAS_GELU: out = gelu(m), out2 = the code of gelu'(m), m the bf16-rounded pre-activation
       float v[8], t[8];
       unpack8(rowdat[p], v);
 #pragma unroll
@@ -296,7 +309,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
         t[e] = dg;
       }
       res[p] = pack8(v);
-      res2[p] = pack8(t);
+      res2[p] = u32x2{dg8_pack4_code(t[0], t[1], t[2], t[3]), dg8_pack4_code(t[4], t[5], t[6], t[7])};
     }
   };
   // ... and its stores.  They are issued after the step's operand loads: memory operations complete in
@@ -309,8 +322,8 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
       char* o = (char*)g.out + ((pmw + I * 32 + p * 5) * (long long)ldc_b + 2 * pnw);
       if (ok) *reinterpret_cast<u32x4*>(o + eo_c) = res[p];
       if constexpr (MODE == EPI_BIAS_GELU) {
-        char* o2 = (char*)g.out2 + ((pmw + I * 32 + p * 5) * (long long)ldc2_b + 2 * pnw);
-        if (ok) *reinterpret_cast<u32x4*>(o2 + eo_c2) = res2[p];
+        char* o2 = (char*)g.out2 + ((pmw + I * 32 + p * 5) * (long long)ldc2_b + pnw);
+        if (ok) *reinterpret_cast<u32x2*>(o2 + eo_c2) = res2[p];
       }
     }
   };

@@ -1,5 +1,5 @@
 // bf16 MFMA "NT" GEMM with fused bias + GELU for gfx950, large-M variant (the first MLP GEMM of a block):
-// m = A[M,K] * B[N,K]^T + bias;  out = gelu(m), out2 = gelu'(m), both bf16.
+// m = A[M,K] * B[N,K]^T + bias;  out = gelu(m) as bf16, out2 = gelu'(m) as the one-byte code of slide_internal.h.
 //
 // Same tile and operand pipeline as the large-M kernel of the other epilogues (gemm_nt_big.hip: 256 x 192 tiles,
 // one persistent workgroup per compute unit, operands global -> registers -> LDS three K steps ahead, explicit
@@ -11,7 +11,7 @@
 //   * The epilogue runs when the tile's last step is done, by all eight wavefronts at once: the accumulators
 //     (which started from the bias) go through wavefront-private fp32 patches in the (then idle) operand stages and
 //     come back as 8-column row segments, GELU and its derivative are evaluated on the UNROUNDED pre-activation and
-//     rounded once, and every global store is a 16-byte access along a row.  The first two K steps of the next tile
+//     rounded once, and every global store is a 16-byte (derivative codes: 8-byte) access along a row.  The first two K steps of the next tile
 //     are already in flight in the registers meanwhile.  (In the 4-wavefront kernel the same work rides between
 //     the MFMAs of the next tile on a bf16-rounded copy of the accumulators; measured 3.74 ms per launch on the
 //     8192-tile ViT-S workload against 3.2 ms here.  For the lighter epilogues the two organisations measure the
@@ -53,15 +53,16 @@ __device__ __forceinline__ u32x4 pack8(const float (&v)[8]) {
   return __builtin_bit_cast(u32x4, t);
 }
 
-// table entry k: {cdf(x_k), cdf(x_k+1) - cdf(x_k), dg(x_k), dg(x_k+1) - dg(x_k)}, x_k = -7 + k/32,
-// cdf = standard normal distribution function, dg(x) = cdf(x) + x * pdf(x) = d/dx (x cdf(x))
-__device__ __forceinline__ void gelu_both_tab(const float4* tab, float x, float* gl, float* dg) {
+// table entry k: {cdf(x_k), cdf(x_k+1) - cdf(x_k), c(x_k), c(x_k+1) - c(x_k)}, x_k = -7 + k/32,
+// cdf = standard normal distribution function, dg(x) = cdf(x) + x * pdf(x) = d/dx (x cdf(x)) and c = dg8_code(dg),
+// the derivative in the code space of its one-byte storage: *dgc comes out ready for the conversion
+__device__ __forceinline__ void gelu_both_tab(const float4* tab, float x, float* gl, float* dgc) {
   float t = __builtin_amdgcn_fmed3f(x * 32.0f + 224.0f, 0.0f, (float)TAB_N - 0.001f);
   int k = (int)t;                       // t >= 0: truncation is the floor
   float f = __builtin_amdgcn_fractf(t);
   float4 e = tab[k];
   *gl = x * (e.x + f * e.y);
-  *dg = e.z + f * e.w;
+  *dgc = e.z + f * e.w;
 }
 
 template <int V> using IC = std::integral_constant<int, V>;
@@ -87,7 +88,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_gelu_k(GemmNT g, int MT, int NTL)
       float c0 = 0.5f * (1.0f + erff(x0 * 0.70710678118654752f)), c1 = 0.5f * (1.0f + erff(x1 * 0.70710678118654752f));
       float d0 = c0 + x0 * 0.39894228040143268f * expf(-0.5f * x0 * x0);
       float d1 = c1 + x1 * 0.39894228040143268f * expf(-0.5f * x1 * x1);
-      tab[k] = make_float4(c0, c1 - c0, d0, d1 - d0);
+      tab[k] = make_float4(c0, c1 - c0, dg8_code(d0), dg8_code(d1) - dg8_code(d0));
     }
   }
 
@@ -205,7 +206,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_gelu_k(GemmNT g, int MT, int NTL)
   float* const patch = reinterpret_cast<float*>(ring) + wave * 32 * PS;
   float* const pw = patch + (lane & 31) * PS + (lane >> 5) * 4;
   const float* const pr = patch + er * PS + esg * 8;
-  const unsigned ldc_b = 2u * (unsigned)g.ldc, ldc2_b = 2u * (unsigned)g.ldc2;
+  const unsigned ldc_b = 2u * (unsigned)g.ldc, ldc2_b = (unsigned)g.ldc2;   // bytes: bf16 and one-byte codes
   auto epilogue = [&](long long m0, int n0) {
     const long long mw = m0 + wm * (WBM * 32);
     const int nw = n0 + wn * (WBN * 32);
@@ -236,9 +237,10 @@ __global__ void __launch_bounds__(NTH) gemm_nt_gelu_k(GemmNT g, int MT, int NTL)
           }
           const bool ok = p * 5 + erc < lim && p * 5 + er < 32;
           char* o = (char*)g.out + ((ms + p * 5) * (long long)ldc_b + 2 * nw);
-          char* o2 = (char*)g.out2 + ((ms + p * 5) * (long long)ldc2_b + 2 * nw);
+          char* o2 = (char*)g.out2 + ((ms + p * 5) * (long long)ldc2_b + nw);
           if (ok) *reinterpret_cast<u32x4*>(o + (unsigned)er * ldc_b + esg * 16) = pack8(v);
-          if (ok) *reinterpret_cast<u32x4*>(o2 + (unsigned)er * ldc2_b + esg * 16) = pack8(t);
+          if (ok) *reinterpret_cast<uint2*>(o2 + (unsigned)er * ldc2_b + esg * 8) =
+              make_uint2(dg8_pack4_code(t[0], t[1], t[2], t[3]), dg8_pack4_code(t[4], t[5], t[6], t[7]));
         }
       }
     }

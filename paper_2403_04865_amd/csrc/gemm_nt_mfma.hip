@@ -56,12 +56,25 @@ __device__ __forceinline__ void store8(bf16* p, const float (&v)[8]) {
   *reinterpret_cast<bf16x8*>(p) = t;
 }
 
+// eight one-byte codes of the stored GELU derivative
+__device__ __forceinline__ void load8_dg(const unsigned char* p, float (&v)[8]) {
+  uint2 t = *reinterpret_cast<const uint2*>(p);
+  float a[4], b[4];
+  dg8_unpack4(t.x, a);
+  dg8_unpack4(t.y, b);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+}
+__device__ __forceinline__ void store8_dg(unsigned char* p, const float (&v)[8]) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(dg8_pack4(v[0], v[1], v[2], v[3]), dg8_pack4(v[4], v[5], v[6], v[7]));
+}
+
 // Auxiliary operand of one 8-column row segment (residual / saved pre-activation / position
 // row), fetched ahead of the arithmetic so that its latency overlaps the LDS round trip.
 template <int MODE, typename RS>
 __device__ __forceinline__ void epi_aux8(const GemmNT& g, long long m, int n, float (&t)[8]) {
   if (MODE == EPI_BIAS_RESID) load8((const RS*)g.resid + m * g.ldr + n, t);
-  else if (MODE == EPI_DGELU) load8((const bf16*)g.pre + m * g.ldpre + n, t);
+  else if (MODE == EPI_DGELU) load8_dg((const unsigned char*)g.pre + m * g.ldpre + n, t);
   else if (MODE == EPI_PATCH) load8(g.pos + (size_t)(1 + (int)(m % g.cmap.g2)) * g.N + n, t);
 }
 
@@ -88,7 +101,7 @@ __device__ __forceinline__ void epi_seg8(const GemmNT& g, long long m, int n, fl
       t[i] = dg;
     }
     store8((bf16*)g.out + m * g.ldc + n, v);
-    store8((bf16*)g.out2 + m * g.ldc2 + n, t);
+    store8_dg((unsigned char*)g.out2 + m * g.ldc2 + n, t);
   } else if (MODE == EPI_DGELU) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) v[i] *= t[i];
@@ -328,8 +341,8 @@ bool gemm_nt_mfma_ok(const GemmNT& g) {
   bool ok = g.K % 64 == 0 && g.N % 16 == 0 && g.lda % 8 == 0 && g.ldb % 8 == 0 && aligned16(g.A) && aligned16(g.B) &&
             g.M > 0 && g.ldc % 8 == 0 && aligned16(g.out) && g.N % 8 == 0;
   if (g.epi == EPI_BIAS_RESID) ok = ok && g.ldr % 8 == 0 && aligned16(g.resid);
-  if (g.epi == EPI_BIAS_GELU) ok = ok && g.ldc2 % 8 == 0 && aligned16(g.out2);
-  if (g.epi == EPI_DGELU) ok = ok && g.ldpre % 8 == 0 && aligned16(g.pre);
+  if (g.epi == EPI_BIAS_GELU) ok = ok && g.ldc2 % 8 == 0 && ((size_t)g.out2 & 7) == 0;   // 8-byte code segments
+  if (g.epi == EPI_DGELU) ok = ok && g.ldpre % 8 == 0 && ((size_t)g.pre & 7) == 0;
   if (g.epi != EPI_PLAIN && g.epi != EPI_DGELU) ok = ok && aligned16(g.bias);
   if (g.epi == EPI_PATCH) ok = ok && aligned16(g.pos);
   return ok;

@@ -71,6 +71,44 @@ __device__ __forceinline__ float gelu_grad_f(float m) {
   return c + m * e * 0.39894228040143268f;
 }
 
+// The GELU derivative the bf16 path keeps for the backward is one byte per element: gelu'(m) lies in
+// [-0.1289, 1.1289] (extrema at m = -+sqrt(2)), and the code q = rne((gelu'(m) + DG8_OFF) * DG8_SCALE) in 0..254
+// gives it back as q / DG8_SCALE - DG8_OFF with an error of at most 2.5e-3 (rms 1.4e-3, the size of the bf16
+// rounding of a value near 1), in half the bytes of a bf16.  The fp32 path keeps the derivative as a float.
+constexpr float DG8_OFF = 0.12890625f, DG8_SCALE = 202.0f;
+// four values already in code space ((gelu' + DG8_OFF) * DG8_SCALE), a in byte 0
+__device__ __forceinline__ unsigned dg8_pack4_code(float a, float b, float c, float d) {
+  unsigned r = 0;
+  r = __builtin_amdgcn_cvt_pk_u8_f32(a, 0, r);   // rounds to nearest even, clamps to 0..255
+  r = __builtin_amdgcn_cvt_pk_u8_f32(b, 1, r);
+  r = __builtin_amdgcn_cvt_pk_u8_f32(c, 2, r);
+  r = __builtin_amdgcn_cvt_pk_u8_f32(d, 3, r);
+  return r;
+}
+__device__ __forceinline__ float dg8_code(float dg) { return __builtin_fmaf(dg, DG8_SCALE, DG8_OFF * DG8_SCALE); }
+__device__ __forceinline__ unsigned dg8_pack4(float a, float b, float c, float d) {
+  return dg8_pack4_code(dg8_code(a), dg8_code(b), dg8_code(c), dg8_code(d));
+}
+__device__ __forceinline__ void dg8_unpack4(unsigned q, float (&v)[4]) {
+  v[0] = (float)(q & 0xffu) * (1.0f / DG8_SCALE) - DG8_OFF;
+  v[1] = (float)((q >> 8) & 0xffu) * (1.0f / DG8_SCALE) - DG8_OFF;
+  v[2] = (float)((q >> 16) & 0xffu) * (1.0f / DG8_SCALE) - DG8_OFF;
+  v[3] = (float)(q >> 24) * (1.0f / DG8_SCALE) - DG8_OFF;
+}
+// what one element of the stored derivative is, by element type of the path
+template <typename T> struct dgelu_store;
+template <> struct dgelu_store<float> {
+  typedef float type;
+  static __device__ __forceinline__ float put(float dg) { return dg; }
+  static __device__ __forceinline__ float get(float q) { return q; }
+};
+template <> struct dgelu_store<bf16> {
+  typedef unsigned char type;
+  static __device__ __forceinline__ unsigned char put(float dg) { return (unsigned char)(dg8_pack4(dg, 0.f, 0.f, 0.f) & 0xffu); }
+  static __device__ __forceinline__ float get(unsigned char q) { return (float)q * (1.0f / DG8_SCALE) - DG8_OFF; }
+};
+__host__ __device__ inline size_t dgelu_elem_size(int dt) { return dt == DT_F32 ? 4 : 1; }   // bytes per element of it
+
 // Row map used where a GEMM operand lives in the token matrix but only patch-token rows
 // take part: logical row r (tile r / g2, patch r % g2) -> token row (r / g2) * T + 1 + r % g2.
 // g2 == 0 means identity.
@@ -92,8 +130,8 @@ enum {
   EPI_PLAIN = 0,       // out(T)  = acc
   EPI_BIAS = 1,        // out(T)  = acc + bias[n]
   EPI_BIAS_RESID = 2,  // out(RS) = acc + bias[n] + resid(RS)[m][n]
-  EPI_BIAS_GELU = 3,   // m = acc + bias[n];  out(T) = gelu(m);  out2(T) = gelu'(m)
-  EPI_DGELU = 4,       // out(T)  = acc * pre(T)[m][n]   (pre holds the gelu'(m) the forward stored)
+  EPI_BIAS_GELU = 3,   // m = acc + bias[n];  out(T) = gelu(m);  out2 = gelu'(m) (float / one-byte code, dgelu_store<T>)
+  EPI_DGELU = 4,       // out(T)  = acc * pre[m][n]   (pre holds the gelu'(m) the forward stored, same format)
   EPI_PATCH = 5,       // out(RS)[rowmap(m)] = acc + bias[n] + pos[1 + m % g2][n]
 };
 
@@ -106,7 +144,7 @@ struct GemmNT {
   const float* bias;
   const void* resid; long long ldr;
   void* out; long long ldc;
-  void* out2; long long ldc2;
+  void* out2; long long ldc2;          // leading dimensions in elements of the stored-derivative format
   const void* pre; long long ldpre;
   const float* pos;  // [T, N] position table (EPI_PATCH)
   RowMap cmap;       // EPI_PATCH output rows

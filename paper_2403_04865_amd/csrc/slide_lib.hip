@@ -182,8 +182,9 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   } else {
     y.s_xmid = 0; y.e_xmid = y.e_x;  // residual adds run in place
   }
-  y.s_m = save ? align256(M * c->F * e) : 0;
-  y.e_m = take(0); cur += (size_t)inst * align256(M * c->F * e);
+  const size_t dge = dgelu_elem_size(c->dt);   // gelu'(pre-activation): a float, or a one-byte code on the bf16 path
+  y.s_m = save ? align256(M * c->F * dge) : 0;
+  y.e_m = take(0); cur += (size_t)inst * align256(M * c->F * dge);
   // the two LayerNorm outputs of a block are kept like its other activations: the weight gradients of the GEMMs
   // behind them need them again, and a LayerNorm backward that re-creates them writes a fifth more than one that
   // does not (+2 D e bytes per token and block)
@@ -233,8 +234,7 @@ void gemm_nt(Run& r, const GemmNT& g) {
   // every operand once: A, B, the output(s), and the residual / saved pre-activation the epilogue reads
   double bytes = (double)g.M * g.K * e + (double)g.N * g.K * e + (double)g.M * g.N * e;
   if (g.epi == EPI_BIAS_RESID) bytes += (double)g.M * g.N * rs_size(r.c->dt);
-  if (g.epi == EPI_BIAS_GELU) bytes += (double)g.M * g.N * e;
-  if (g.epi == EPI_DGELU) bytes += (double)g.M * g.N * e;
+  if (g.epi == EPI_BIAS_GELU || g.epi == EPI_DGELU) bytes += (double)g.M * g.N * dgelu_elem_size(r.c->dt);
   launch(r, K_GEMM_NT, 2.0 * g.M * g.N * g.K, bytes, [&] { return launch_gemm_nt(r.c->dt, g, r.c->use_mfma, r.s); });
 }
 
