@@ -131,7 +131,7 @@ __global__ void __launch_bounds__(256) bn_apply_k(const bf16* __restrict__ x, lo
       t[e] = (bf16)v[e];
       m |= ((float)t[e] > 0.f ? 1u : 0u) << e;   // of the value as stored
     }
-    *reinterpret_cast<bf16x8*>(y + i * 8) = t;
+    __builtin_nontemporal_store(t, reinterpret_cast<bf16x8*>(y + i * 8));   // streamed: the reader is a later kernel
     if (bits) bits[i] = (unsigned char)m;
   }
 }

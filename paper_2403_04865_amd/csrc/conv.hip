@@ -157,7 +157,7 @@ __device__ __forceinline__ void conv_tile_out(const ConvNT& p, const f32x16 (&ac
           ss[2 * w] += lo; qq[2 * w] += lo * lo;
           ss[2 * w + 1] += hi; qq[2 * w + 1] += hi * hi;
         }
-        *reinterpret_cast<u32x4*>(p.out + orow * p.N + n0 + ch * 8) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p.out + orow * p.N + n0 + ch * 8));
       }
     }
   } else {
@@ -213,7 +213,7 @@ __device__ __forceinline__ void conv_tile_out(const ConvNT& p, const f32x16 (&ac
         ss[e] += v;
         qq[e] += v * v;
       }
-      *reinterpret_cast<bf16x8*>(p.out + at) = t;
+      __builtin_nontemporal_store(t, reinterpret_cast<bf16x8*>(p.out + at));
     }
   }
   }

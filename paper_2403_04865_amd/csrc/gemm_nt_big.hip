@@ -320,10 +320,10 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     if (p * 5 < lim) {  // uniform
       bool ok = p * 5 + erc < lim;
       char* o = (char*)g.out + ((pmw + I * 32 + p * 5) * (long long)ldc_b + 2 * pnw);
-      if (ok) *reinterpret_cast<u32x4*>(o + eo_c) = res[p];
+      if (ok) __builtin_nontemporal_store(res[p], reinterpret_cast<u32x4*>(o + eo_c));
       if constexpr (MODE == EPI_BIAS_GELU) {
         char* o2 = (char*)g.out2 + ((pmw + I * 32 + p * 5) * (long long)ldc2_b + pnw);
-        if (ok) *reinterpret_cast<u32x2*>(o2 + eo_c2) = res2[p];
+        if (ok) __builtin_nontemporal_store(res2[p], reinterpret_cast<u32x2*>(o2 + eo_c2));
       }
     }
   };

@@ -42,6 +42,7 @@ static_assert((size_t)NW * 32 * PS * 4 <= (size_t)2 * STAGE * 2, "epilogue patch
 static_assert(2 * (CA + CB) <= 3 * WBM * WBN, "piece schedule");
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 // uniform base (scalar registers) + 32-bit per-lane byte offset
 __device__ __forceinline__ u32x4 ldg16(const char* base, unsigned off) { return *reinterpret_cast<const u32x4*>(base + off); }
@@ -238,9 +239,9 @@ __global__ void __launch_bounds__(NTH) gemm_nt_gelu_k(GemmNT g, int MT, int NTL)
           const bool ok = p * 5 + erc < lim && p * 5 + er < 32;
           char* o = (char*)g.out + ((ms + p * 5) * (long long)ldc_b + 2 * nw);
           char* o2 = (char*)g.out2 + ((ms + p * 5) * (long long)ldc2_b + nw);
-          if (ok) *reinterpret_cast<u32x4*>(o + (unsigned)er * ldc_b + esg * 16) = pack8(v);
-          if (ok) *reinterpret_cast<uint2*>(o2 + (unsigned)er * ldc2_b + esg * 8) =
-              make_uint2(dg8_pack4_code(t[0], t[1], t[2], t[3]), dg8_pack4_code(t[4], t[5], t[6], t[7]));
+          if (ok) __builtin_nontemporal_store(pack8(v), reinterpret_cast<u32x4*>(o + (unsigned)er * ldc_b + esg * 16));
+          if (ok) __builtin_nontemporal_store(u32x2{dg8_pack4_code(t[0], t[1], t[2], t[3]), dg8_pack4_code(t[4], t[5], t[6], t[7])},
+                                              reinterpret_cast<u32x2*>(o2 + (unsigned)er * ldc2_b + esg * 8));
         }
       }
     }

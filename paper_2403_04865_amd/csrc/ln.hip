@@ -207,7 +207,7 @@ bool ln_bwd_fast(dim3 grid, const void* x, long long xs, const void* dy, long lo
 // wavefront keeps in flight, and one row of 2 * D bytes per wavefront (4-byte accesses) left HBM mostly idle.
 typedef unsigned int lnu4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void ln_ld8(const bf16* p, float (&v)[8]) {
-  lnu4 t = *reinterpret_cast<const lnu4*>(p);
+  lnu4 t = __builtin_nontemporal_load(reinterpret_cast<const lnu4*>(p));   // streamed: read once
 #pragma unroll
   for (int w = 0; w < 4; ++w) {
     v[2 * w] = __uint_as_float(t[w] << 16);
@@ -224,7 +224,7 @@ __device__ __forceinline__ void ln_st8(bf16* p, const float (&v)[8]) {
     lnb2 h = __builtin_convertvector(f, lnb2);
     r[w] = __builtin_bit_cast(unsigned, h);
   }
-  *reinterpret_cast<lnu4*>(p) = r;
+  __builtin_nontemporal_store(r, reinterpret_cast<lnu4*>(p));   // streamed: the reader is a later kernel
 }
 template <int LPR>
 __device__ __forceinline__ float sum_row(float v) {   // over the LPR lanes of a row group
