@@ -57,20 +57,23 @@ __device__ __forceinline__ u32x4 pack8(const float (&v)[8]) {
 // table entry k: {cdf(x_k), cdf(x_k+1) - cdf(x_k), c(x_k), c(x_k+1) - c(x_k)}, x_k = -7 + k/32,
 // cdf = standard normal distribution function, dg(x) = cdf(x) + x * pdf(x) = d/dx (x cdf(x)) and c = dg8_code(dg),
 // the derivative in the code space of its one-byte storage: *dgc comes out ready for the conversion
-__device__ __forceinline__ void gelu_both_tab(const float4* tab, float x, float* gl, float* dgc) {
+// (entries are four halves: 8 bytes per look-up instead of 16 keep the table's LDS traffic, which every wavefront's
+// epilogue shares, and its bank conflicts at half; a half has 11 significant bits against the 8 of the results)
+typedef _Float16 h16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void gelu_both_tab(const h16x4* tab, float x, float* gl, float* dgc) {
   float t = __builtin_amdgcn_fmed3f(x * 32.0f + 224.0f, 0.0f, (float)TAB_N - 0.001f);
   int k = (int)t;                       // t >= 0: truncation is the floor
   float f = __builtin_amdgcn_fractf(t);
-  float4 e = tab[k];
-  *gl = x * (e.x + f * e.y);
-  *dgc = e.z + f * e.w;
+  h16x4 e = tab[k];
+  *gl = x * ((float)e[0] + f * (float)e[1]);
+  *dgc = (float)e[2] + f * (float)e[3];
 }
 
 template <int V> using IC = std::integral_constant<int, V>;
 
 __global__ void __launch_bounds__(NTH) gemm_nt_gelu_k(GemmNT g, int MT, int NTL) {
   __shared__ __attribute__((aligned(16))) bf16 ring[2 * STAGE];
-  __shared__ float4 tab[TAB_N];
+  __shared__ h16x4 tab[TAB_N];
   __shared__ __attribute__((aligned(16))) float lbias[BN];   // the tile's bias columns (zeros without a bias)
   bf16* const ring0 = ring;
   bf16* const ring1 = ring + STAGE;
@@ -89,7 +92,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_gelu_k(GemmNT g, int MT, int NTL)
       float c0 = 0.5f * (1.0f + erff(x0 * 0.70710678118654752f)), c1 = 0.5f * (1.0f + erff(x1 * 0.70710678118654752f));
       float d0 = c0 + x0 * 0.39894228040143268f * expf(-0.5f * x0 * x0);
       float d1 = c1 + x1 * 0.39894228040143268f * expf(-0.5f * x1 * x1);
-      tab[k] = make_float4(c0, c1 - c0, dg8_code(d0), dg8_code(d1) - dg8_code(d0));
+      tab[k] = h16x4{(_Float16)c0, (_Float16)(c1 - c0), (_Float16)dg8_code(d0), (_Float16)(dg8_code(d1) - dg8_code(d0))};
     }
   }
 
