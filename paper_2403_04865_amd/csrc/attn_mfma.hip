@@ -133,6 +133,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
   const bf16* const krow0 = Ks + li * LDR + h2 * 8;
   const bf16* const vtr0 = Vs + tr_lane_off(LDR, lane);
   const int nqb = cls_only ? 1 : NB;   // cls_only: only query 0 is needed (its block of 32 is computed)
+  const int nlast = T - (NB - 1) * 32;   // real keys in the last block (1 .. 32)
   for (int qb = wave; qb < nqb; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
     int qc = q < T ? q : T - 1;
@@ -162,14 +163,21 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
         bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + ks * 16);
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fq[ks], sc, 0, 0, 0);
       }
+      // In the last block only the first nlast keys exist.  Accumulator registers 4g .. 4g + 3 hold keys 8g .. 8g + 7
+      // of the block: a group of registers past the last real key takes no part in the maximum, gets no exponential
+      // (its probabilities are zero) and, where the block's upper 16 keys are all padding, no second P V slice.
       float bm = -INFINITY;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         if (LASTB) {
-          int key = (NB - 1) * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
-          if (key >= T) sc[r] = -INFINITY;
+          if ((r >> 2) * 8 < nlast) {   // uniform
+            int key = (r >> 2) * 8 + h2 * 4 + (r & 3);
+            if (key >= nlast) sc[r] = -INFINITY;
+            bm = fmaxf(bm, sc[r]);
+          }
+        } else {
+          bm = fmaxf(bm, sc[r]);
         }
-        bm = fmaxf(bm, sc[r]);
       }
       bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
       float mn = fmaxf(mx, bm);                                  // finite: every block has a real key
@@ -178,9 +186,13 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
       float ls = 0.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float pe = __builtin_amdgcn_exp2f(sc[r] * sl2 - ms);
-        sc[r] = pe;
-        ls += pe;
+        if (!LASTB || (r >> 2) * 8 < nlast) {   // uniform
+          float pe = __builtin_amdgcn_exp2f(sc[r] * sl2 - ms);
+          sc[r] = pe;
+          ls += pe;
+        } else {
+          sc[r] = 0.f;
+        }
       }
       l = l * resc + ls;
       mx = mn;
@@ -192,6 +204,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_fwd_mfma_k(const b
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
+        if (LASTB && t == 1 && nlast <= 16) continue;   // uniform: all of these probabilities are zero
         float pv[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) pv[i] = sc[8 * t + i];
@@ -287,6 +300,7 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
   const bf16* const krow0 = Ks + li * LDR + h2 * 8;
   const bf16* const vrow0 = Vs + li * LDR + h2 * 8;
   const bf16* const ktr0 = Ks + tr_lane_off(LDR, lane);
+  const int nlast = T - (NB - 1) * 32;   // real keys in the last block (1 .. 32)
   for (int qb = wave; qb < NB; qb += attn_threads<NB>() / 64) {
     int q = qb * 32 + li;
     if (cls_only && qb > 0) {   // uniform: the output gradient is zero for these queries, and so is dQ
@@ -324,18 +338,25 @@ __global__ void __launch_bounds__(attn_threads<NB>(), 2) attn_bwd_q_mfma_k(const
         bf16x8 v = *reinterpret_cast<const bf16x8*>(vrow + ks * 16);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v, fdo[ks], dp, 0, 0, 0);
       }
+      // (last block: register groups past the last real key are zero without being computed, and the second dS K
+      // slice is skipped where the block's upper 16 keys are all padding; see the forward kernel)
       float ds[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(s[r] * sl2 - lq);
-        if (LASTB) {
-          int key = (NB - 1) * 32 + (r >> 2) * 8 + h2 * 4 + (r & 3);
-          if (key >= T) p = 0.f;
+        if (!LASTB || (r >> 2) * 8 < nlast) {   // uniform
+          float p = __builtin_amdgcn_exp2f(s[r] * sl2 - lq);
+          if (LASTB) {
+            int key = (r >> 2) * 8 + h2 * 4 + (r & 3);
+            if (key >= nlast) p = 0.f;
+          }
+          ds[r] = p * (dp[r] - delta);
+        } else {
+          ds[r] = 0.f;
         }
-        ds[r] = p * (dp[r] - delta);
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
+        if (LASTB && t == 1 && nlast <= 16) continue;   // uniform
         bf16x8 db = pack8(ds + 8 * t);
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
@@ -424,6 +445,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
   const bf16* const grow0 = Gs + li * LDR + h2 * 8;
   const bf16* const qtr0 = Qs + tr_lane_off(LDR, lane);
   const bf16* const gtr0 = Gs + tr_lane_off(LDR, lane);
+  const int nlast = T - (NB - 1) * 32;   // real queries in the last block (1 .. 32)
   for (int kb = wave; kb < NB; kb += 4) {
     int key = kb * 32 + li;
     // the fragments of the wavefront's next key block travel while this one is worked on
@@ -441,9 +463,11 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
     const bf16* gtr = gtr0;
     const float* lsq = ls + h2 * 4;
     const float* dlq = dl + h2 * 4;
-    const int nqb = cls_only ? 1 : NB;
-#pragma unroll 1
-    for (int qb = 0; qb < nqb; ++qb, qrow += 32 * LDR, grow += 32 * LDR, qtr += 32 * LDR, gtr += 32 * LDR, lsq += 32, dlq += 32) {
+    // one block of 32 queries; LASTQ: the head's last block, the only one with padding rows: accumulator registers
+    // 4g .. 4g + 3 hold queries 8g .. 8g + 7 of the block, and a group past the last real query is zero without being
+    // computed (no exponential); the second slice of both products is skipped where the upper 16 queries are padding
+    auto q_block = [&](auto lastq) __attribute__((always_inline)) {
+      constexpr bool LASTQ = decltype(lastq)::value;
       f32x16 s, dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
@@ -457,6 +481,11 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
       float p[16], ds[16];
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {   // accumulator registers 4 g4 .. 4 g4 + 3 are four consecutive queries
+        if (LASTQ && g4 * 8 >= nlast) {   // uniform
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { p[g4 * 4 + e] = 0.f; ds[g4 * 4 + e] = 0.f; }
+          continue;
+        }
         float4 lv = *reinterpret_cast<const float4*>(lsq + g4 * 8), dv4 = *reinterpret_cast<const float4*>(dlq + g4 * 8);
         float lr[4] = {lv.x, lv.y, lv.z, lv.w}, dr[4] = {dv4.x, dv4.y, dv4.z, dv4.w};
 #pragma unroll
@@ -468,6 +497,7 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
       }
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
+        if (LASTQ && t == 1 && nlast <= 16) continue;   // uniform
         bf16x8 pb = pack8(p + 8 * t);
         bf16x8 db = pack8(ds + 8 * t);
 #pragma unroll
@@ -478,7 +508,12 @@ __global__ void __launch_bounds__(256, 2) attn_bwd_k_mfma_k(const bf16* __restri
           dk[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, db, dk[d], 0, 0, 0);
         }
       }
-    }
+    };
+    const int nfull = cls_only ? 1 : NB - 1;
+#pragma unroll 1
+    for (int qb = 0; qb < nfull; ++qb, qrow += 32 * LDR, grow += 32 * LDR, qtr += 32 * LDR, gtr += 32 * LDR, lsq += 32, dlq += 32)
+      q_block(std::false_type{});
+    if (!cls_only) q_block(std::true_type{});
     if (key < T) {
       bf16* outk = dqkv + (tile * T + key) * gs + D + h * DH;
       bf16* outv = outk + D;
