@@ -1,6 +1,7 @@
 // bf16 MFMA softmax attention inside one tile for gfx950 (v_mfma_f32_32x32x16_bf16).
 //
-// One workgroup (4 wavefronts) per (tile, head); all keys/values of the head sit in LDS.
+// One workgroup per (tile, head), one wavefront per block of 32 queries (seven at 197 tokens; the key-owned
+// backward keeps four); all keys/values of the head (queries and output gradients in the key-owned pass) sit in LDS.
 // Scores are produced TRANSPOSED (keys x queries): a 32x32 accumulator block then holds one
 // query per lane column and the keys down the registers, so the softmax over keys is a
 // reduction inside each lane plus one exchange between the two lane halves, and the
