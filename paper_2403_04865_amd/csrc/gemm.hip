@@ -126,6 +126,8 @@ bool gemm_tn_fuses_colsum(int dt, const GemmTN& g, bool use_mfma) {
 
 hipError_t launch_gemm_nt(int dt, const GemmNT& g, bool use_mfma, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0) return hipSuccess;
+  // the periodic-table epilogue exists in the large-M kernel only (callers ask gemm_nt_big_ok first)
+  if (g.epi == EPI_ROWTAB && !(dt == DT_BF16 && use_mfma && gemm_nt_mfma_ok(g) && gemm_nt_big_ok(g))) return hipErrorInvalidValue;
   if (dt == DT_BF16 && use_mfma && gemm_nt_mfma_ok(g)) return launch_gemm_nt_mfma(g, s);
   dim3 grid((unsigned)((g.M + 63) / 64), (g.N + 63) / 64);
   if (dt == DT_F32)

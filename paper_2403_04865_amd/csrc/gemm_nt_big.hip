@@ -98,7 +98,7 @@ template <int V> using IC = std::integral_constant<int, V>;
 template <int MODE>
 __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) {
   constexpr bool HAS_BIAS = MODE == EPI_BIAS || MODE == EPI_BIAS_RESID || MODE == EPI_BIAS_GELU;
-  constexpr bool HAS_AUX = MODE == EPI_BIAS_RESID || MODE == EPI_DGELU;
+  constexpr bool HAS_AUX = MODE == EPI_BIAS_RESID || MODE == EPI_DGELU || MODE == EPI_ROWTAB;
   // stores issued in one burst at the end of a step measured slower than stores spread over the step
   constexpr bool LATE_STORES = false;
   // two separate arrays: the compiler then knows that the LDS writes of the next step's operands do not alias
@@ -246,13 +246,14 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
   const int erc = lane < 60 ? lane / 12 : 64;  // the same for comparisons: idle lanes never pass
   const int esg = lane % 12;
   const unsigned ldc_b = 2u * (unsigned)g.ldc, ldc2_b = (unsigned)g.ldc2;   // bytes (the derivative: one per element)
-  const unsigned lda_b = MODE == EPI_BIAS_RESID ? 2u * (unsigned)g.ldr : (unsigned)g.ldpre;
+  const unsigned lda_b = MODE == EPI_DGELU ? (unsigned)g.ldpre : 2u * (unsigned)g.ldr;
   constexpr int AUXW = MODE == EPI_DGELU ? 1 : 2;   // bytes per element of the auxiliary operand
   const unsigned eo_c = (unsigned)er * ldc_b + esg * 16, eo_c2 = (unsigned)er * ldc2_b + esg * 8;
   const unsigned eo_a = (unsigned)er * lda_b + esg * (8 * AUXW);
   unsigned char* const pw = patches + wave * PATCH_BYTES + (lane & 31) * PSB + (lane >> 5) * 8;
   const unsigned char* const pr = patches + wave * PATCH_BYTES + er * PSB + esg * 16;
-  const char* const aux_ptr = (const char*)(MODE == EPI_BIAS_RESID ? g.resid : g.pre);
+  const char* const aux_ptr = (const char*)(MODE == EPI_DGELU ? g.pre : g.resid);
+  unsigned pmod = 0;   // EPI_ROWTAB: first row of the parked block modulo the table's row count (uniform)
 
   // rows of strip I of the parked block that exist (uniform, may be <= 0)
   auto strip_lim = [&](int I) __attribute__((always_inline)) {
@@ -271,8 +272,21 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     constexpr int I = decltype(ic)::value, p = decltype(pc)::value;
     if constexpr (HAS_AUX) {
       if (p * 5 < lim) {  // uniform; lanes past the end read the pass's first row (never stored)
-        const char* base = aux_ptr + ((pmw + I * 32 + p * 5) * (long long)lda_b + AUXW * pnw);
-        auxv[I & 1][p] = *reinterpret_cast<const aux_t*>(base + (p * 5 + erc < lim ? eo_a : (unsigned)(esg * (8 * AUXW))));
+        if constexpr (MODE == EPI_ROWTAB) {
+          // the pass's rows modulo the table's row count: the block's first row is known modulo it, a pass is at
+          // most 131 rows further (fewer than a table has: one conditional subtraction each)
+          const unsigned per = (unsigned)g.rperiod;
+          unsigned pm = pmod;
+          asm volatile("" : "+s"(pm));   // formed where it is used: 28 addresses kept from the tile's start do not fit
+          unsigned r0 = pm + I * 32 + p * 5;
+          r0 = r0 >= per ? r0 - per : r0;
+          unsigned t = r0 + (unsigned)er;
+          t = t >= per ? t - per : t;
+          auxv[I & 1][p] = *reinterpret_cast<const aux_t*>(aux_ptr + 2 * pnw + (t * lda_b + esg * 16));
+        } else {
+          const char* base = aux_ptr + ((pmw + I * 32 + p * 5) * (long long)lda_b + AUXW * pnw);
+          auxv[I & 1][p] = *reinterpret_cast<const aux_t*>(base + (p * 5 + erc < lim ? eo_a : (unsigned)(esg * (8 * AUXW))));
+        }
       }
     }
   };
@@ -283,7 +297,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
     constexpr int I = decltype(ic)::value, p = decltype(pc)::value;
     if constexpr (MODE == EPI_PLAIN || MODE == EPI_BIAS) {
       res[p] = rowdat[p];
-    } else if constexpr (MODE == EPI_BIAS_RESID) {
+    } else if constexpr (MODE == EPI_BIAS_RESID || MODE == EPI_ROWTAB) {
       float v[8], t[8];
       unpack8(rowdat[p], v);
       unpack8(auxv[I & 1][p], t);
@@ -468,6 +482,7 @@ __global__ void __launch_bounds__(NTH) gemm_nt_big_k(GemmNT g, int MT, int NTL) 
         }
     pmw = mw;
     pnw = nw;
+    if constexpr (MODE == EPI_ROWTAB) pmod = (unsigned)mw % (unsigned)g.rperiod;   // (M < 2^31)
   };
 
   {
@@ -498,7 +513,8 @@ bool gemm_nt_big_ok(const GemmNT& g) {
                g.ldc2 < (1 << 20) && g.ldr < (1 << 20) && g.ldpre < (1 << 20) && g.K % (2 * BK) == 0 &&
                g.K >= MIN_STEPS * BK && g.M >= 4096;
   bool mode = g.epi == EPI_PLAIN || g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_DGELU ||
-              (g.epi == EPI_BIAS_RESID && sizeof(rs_bf16path_t) == 2);
+              (g.epi == EPI_BIAS_RESID && sizeof(rs_bf16path_t) == 2) ||
+              (g.epi == EPI_ROWTAB && sizeof(rs_bf16path_t) == 2 && g.rperiod >= 160);
   return shape && mode && g.amap.g2 == 0;
 }
 
@@ -529,6 +545,7 @@ hipError_t launch_gemm_nt_big(const GemmNT& g, hipStream_t s) {
     case EPI_BIAS_RESID: return launch_big<EPI_BIAS_RESID>(g, s);
     case EPI_BIAS_GELU: return launch_big<EPI_BIAS_GELU>(g, s);
     case EPI_DGELU: return launch_big<EPI_DGELU>(g, s);
+    case EPI_ROWTAB: return launch_big<EPI_ROWTAB>(g, s);
     default: return hipErrorInvalidValue;
   }
 }

@@ -139,6 +139,21 @@ hipError_t launch_cls_rows(int dt, void* x, const float* cls, const float* pos, 
   return hipGetLastError();
 }
 
+// The rows the patch embedding adds to its product, one per token position, as the residual-stream type:
+// tab[0] = cls + pos[0] (the patch matrix has a row of zeros there), tab[t] = bias + pos[t] for the patch tokens.
+__global__ void __launch_bounds__(256) pos_table_k(rs_bf16path_t* __restrict__ tab, const float* __restrict__ cls,
+                                                   const float* __restrict__ pos, const float* __restrict__ bias, int T, int D) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= T * D) return;
+  int d = i % D;
+  tab[i] = from_f<rs_bf16path_t>(pos[i] + (i < D ? cls[d] : bias[d]));
+}
+
+hipError_t launch_pos_table(void* tab, const float* cls, const float* pos, const float* bias, int T, int D, hipStream_t s) {
+  hipLaunchKernelGGL(pos_table_k, dim3((unsigned)((T * D + 255) / 256)), dim3(256), 0, s, (rs_bf16path_t*)tab, cls, pos, bias, T, D);
+  return hipGetLastError();
+}
+
 // zero fill in 16-byte words (bytes must be a multiple of 16; all arena regions are)
 __global__ void __launch_bounds__(256) fill_zero_k(uint4* __restrict__ p, size_t words) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;

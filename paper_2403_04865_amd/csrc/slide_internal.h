@@ -133,6 +133,7 @@ enum {
   EPI_BIAS_GELU = 3,   // m = acc + bias[n];  out(T) = gelu(m);  out2 = gelu'(m) (float / one-byte code, dgelu_store<T>)
   EPI_DGELU = 4,       // out(T)  = acc * pre[m][n]   (pre holds the gelu'(m) the forward stored, same format)
   EPI_PATCH = 5,       // out(RS)[rowmap(m)] = acc + bias[n] + pos[1 + m % g2][n]
+  EPI_ROWTAB = 6,      // out(RS) = acc + resid(RS)[m % rperiod][n]: a table of rperiod rows added periodically (large-M kernel only)
 };
 
 struct GemmNT {
@@ -143,6 +144,7 @@ struct GemmNT {
   int epi;
   const float* bias;
   const void* resid; long long ldr;
+  int rperiod;                   // EPI_ROWTAB: rows of the table
   void* out; long long ldc;
   void* out2; long long ldc2;          // leading dimensions in elements of the stored-derivative format
   const void* pre; long long ldpre;
@@ -174,6 +176,8 @@ hipError_t launch_cast_transpose(int dt, const float* src, int R, int C, void* d
 hipError_t launch_patchify(int dt, const void* pixels, void* patches, long long n, int S, int P, hipStream_t s, int lead);
 hipError_t launch_unpatchify(int dt, const void* dpatches, void* dpix, long long n, int S, int P, hipStream_t s);
 hipError_t launch_cls_rows(int dt, void* x, const float* cls, const float* pos, long long n, int T, int D, hipStream_t s);
+hipError_t launch_pos_table(void* tab, const float* cls, const float* pos, const float* bias, int T, int D, hipStream_t s);
+bool gemm_nt_big_ok(const GemmNT& g);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_calib_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_gelu(int dt, const void* m, void* a, long long count, hipStream_t s);

@@ -65,6 +65,7 @@ struct Layout {
   // encoder
   size_t enc_begin;
   size_t e_patches, e_x, e_qkv, e_O, e_lse, e_xmid, e_m;              // first instance
+  size_t e_postab;                                                    // [T, D] rows the patch embedding adds (bf16 path)
   size_t e_dl;                                                        // [n][H][T] fp32 work space of the attention backward
   size_t s_x, s_qkv, s_O, s_lse, s_xmid, s_m, s_a;                    // per-layer strides (0 when not saved)
   size_t e_u1, e_u2, s_u1, s_u2;                                          // LayerNorm outputs of a block (inputs of its QKV / fc1 GEMMs)
@@ -165,6 +166,7 @@ Layout make_layout(const slide_ctx* c, long long n, long long pool_N, int keep) 
   y.l_u2c = take((size_t)nn * D * 4);
   y.l_ac = take((size_t)nn * c->F * 4);
   int inst = save ? c->L : (c->L > 0 ? 1 : 0);
+  y.e_postab = take((size_t)c->T * D * rs);
   y.e_patches = take((size_t)nn * c->T * c->Kp * e);   // one row per token: the CLS slot is a row of zeros
   y.s_x = bwd ? align256(M * D * rs) : 0;
   y.e_x = take(0);
@@ -234,6 +236,7 @@ void gemm_nt(Run& r, const GemmNT& g) {
   // every operand once: A, B, the output(s), and the residual / saved pre-activation the epilogue reads
   double bytes = (double)g.M * g.K * e + (double)g.N * g.K * e + (double)g.M * g.N * e;
   if (g.epi == EPI_BIAS_RESID) bytes += (double)g.M * g.N * rs_size(r.c->dt);
+  if (g.epi == EPI_ROWTAB) bytes += (double)g.rperiod * g.N * rs_size(r.c->dt);
   if (g.epi == EPI_BIAS_GELU || g.epi == EPI_DGELU) bytes += (double)g.M * g.N * dgelu_elem_size(r.c->dt);
   launch(r, K_GEMM_NT, 2.0 * g.M * g.N * g.K, bytes, [&] { return launch_gemm_nt(r.c->dt, g, r.c->use_mfma, r.s); });
 }
@@ -478,9 +481,21 @@ int enc_fwd(slide_ctx* c, const void* pixels, long long n, void* feats_out, bool
   cast_weights(r);
   launch(r, K_ELEMWISE, 0, 2.0 * n * 3 * c->cfg.tile * c->cfg.tile * elem_size(dt),
          [&] { return launch_patchify(dt, pixels, ar + y.e_patches, n, c->cfg.tile, c->cfg.patch, s, T - c->g2); });
-  {
-    // the patch matrix has the token matrix's rows (a row of zeros in each tile's CLS slot): its weight gradient is
-    // then a plain product of two row-aligned matrices and runs on the large-M kernel
+  // the patch matrix has the token matrix's rows (a row of zeros in each tile's CLS slot): its weight gradient is
+  // then a plain product of two row-aligned matrices and runs on the large-M kernel, and so does the forward where
+  // that kernel takes the shape: every token row gets its row of a [T, D] table added (bias + position row; class
+  // token + position row in the CLS slot, where the product is zero)
+  GemmNT gt{};
+  gt.A = ar + y.e_patches; gt.lda = c->Kp; gt.B = weight(c, 0); gt.ldb = c->Kp;
+  gt.M = n * T; gt.N = D; gt.K = c->Kp;
+  gt.epi = EPI_ROWTAB; gt.resid = ar + y.e_postab; gt.ldr = D; gt.rperiod = T;
+  gt.out = ar + y.e_x; gt.ldc = D;
+  if (dt == DT_BF16 && c->use_mfma && gemm_nt_big_ok(gt)) {
+    launch(r, K_ELEMWISE, 0, 0, [&] {
+      return launch_pos_table(ar + y.e_postab, c->params + c->o_cls, c->params + c->o_pos, c->params + c->o_peb, T, D, s);
+    });
+    gemm_nt(r, gt);
+  } else {
     GemmNT g{};
     g.A = ar + y.e_patches; g.lda = c->Kp; g.amap = RowMap{c->g2, T};
     g.B = weight(c, 0); g.ldb = c->Kp;
@@ -488,9 +503,9 @@ int enc_fwd(slide_ctx* c, const void* pixels, long long n, void* feats_out, bool
     g.epi = EPI_PATCH; g.bias = c->params + c->o_peb; g.pos = c->params + c->o_pos;
     g.out = ar + y.e_x; g.ldc = D; g.cmap = RowMap{c->g2, T};
     gemm_nt(r, g);
+    launch(r, K_ELEMWISE, 0, 0,
+           [&] { return launch_cls_rows(dt, ar + y.e_x, c->params + c->o_cls, c->params + c->o_pos, n, T, D, s); });
   }
-  launch(r, K_ELEMWISE, 0, 0,
-         [&] { return launch_cls_rows(dt, ar + y.e_x, c->params + c->o_cls, c->params + c->o_pos, n, T, D, s); });
   if (c->use_lane)
     launch(r, K_CLS_LANE, 0, (double)n * D * 4,
            [&] { return launch_lane_init(c->params + c->o_cls, c->params + c->o_pos, lane_xc(c, y, 0), n, D, s); });
