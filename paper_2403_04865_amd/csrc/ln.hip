@@ -290,7 +290,8 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
                                                       const float* __restrict__ gam, const bf16* __restrict__ dres,
                                                       bf16* __restrict__ dxo, long long os, long long rows, float eps,
                                                       float* __restrict__ part, const float* __restrict__ bet,
-                                                      bf16* __restrict__ uo, long long us) {
+                                                      bf16* __restrict__ uo, long long us, int dres_period) {
+  // dres_period != 0: dres has a term only for rows r with r % dres_period == 0 (the other rows of it are not read)
   // uo != nullptr: the normalised rows xh * gamma + beta (the forward output, which the weight gradient of the
   // following linear map needs and the forward did not keep) are written on the way, [rows][us]
   constexpr int D = 8 * LPR * NP, RPW = 64 / LPR;   // rows per wavefront
@@ -366,7 +367,7 @@ __global__ void __launch_bounds__(256) ln_bwd_row16_k(const bf16* __restrict__ x
         float o[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = rstd * (d[k][e] - s1 - v[k][e] * s2);
-        if (dres) {
+        if (dres && (dres_period == 0 || (unsigned)r % (unsigned)dres_period == 0)) {
           float t[8];
           ln_ld8(dres + r * os + c, t);
 #pragma unroll
@@ -530,19 +531,28 @@ bool ln_bwd_emits_u(int dt, const void* x, long long x_stride, const void* dy, l
          ((uintptr_t)u_out & 15) == 0 && u_stride % 8 == 0;
 }
 
+// a residual-gradient term on every dres_period-th row only: the kernel with 16 (32) lanes per row takes it
+bool ln_bwd_periodic_ok(int dt, const void* x, long long x_stride, const void* dy, long long dy_stride, const float* gam,
+                        const void* dres, const void* dx_out, long long o_stride, int D, bool dy_f32) {
+  return dt == DT_BF16 && !dy_f32 && ln_row16_ok(x, dy, dx_out, x_stride, dy_stride, o_stride, D) &&
+         ((uintptr_t)gam & 15) == 0 && ((uintptr_t)dres & 15) == 0;
+}
+
 hipError_t launch_ln_bwd(int dt, const void* x, long long x_stride, const void* dy, long long dy_stride,
                          const float* gam, const void* dres, void* dx_out, void* dx_out_t, long long o_stride,
                          long long rows, int D, float eps, float* part, bool dy_f32, hipStream_t s, const float* bet,
-                         void* u_out, long long u_stride) {
+                         void* u_out, long long u_stride, int dres_period) {
   if (rows <= 0) return hipSuccess;
+  if (dres_period && !ln_bwd_periodic_ok(dt, x, x_stride, dy, dy_stride, gam, dres, dx_out, o_stride, D, dy_f32))
+    return hipErrorInvalidValue;
   if (u_out && !ln_bwd_emits_u(dt, x, x_stride, dy, dy_stride, gam, dres, dx_out, o_stride, D, dy_f32, bet, u_out, u_stride))
     return hipErrorInvalidValue;
   dim3 grid(ln_bwd_slabs(rows));
   size_t lds = (size_t)4 * 2 * D * sizeof(float);
   if (dt == DT_BF16 && !dy_f32 && ln_row16_ok(x, dy, dx_out, x_stride, dy_stride, o_stride, D) &&
       ((uintptr_t)gam & 15) == 0 && ((uintptr_t)dres & 15) == 0) {
-    if (D == 384) hipLaunchKernelGGL((ln_bwd_row16_k<3, 16>), grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride);
-    else hipLaunchKernelGGL((ln_bwd_row16_k<3, 32>), grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride);
+    if (D == 384) hipLaunchKernelGGL((ln_bwd_row16_k<3, 16>), grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride, dres_period);
+    else hipLaunchKernelGGL((ln_bwd_row16_k<3, 32>), grid, dim3(256), 0, s, (const bf16*)x, x_stride, (const bf16*)dy, dy_stride, gam, (const bf16*)dres, (bf16*)dx_out, o_stride, rows, eps, part, bet, (bf16*)u_out, u_stride, dres_period);
     return hipGetLastError();
   }
   {

@@ -198,7 +198,11 @@ int ln_bwd_slabs(long long rows);
 hipError_t launch_ln_bwd(int dt, const void* x, long long x_stride, const void* dy, long long dy_stride,
                          const float* gam, const void* dres, void* dx_out, void* dx_out_t, long long o_stride,
                          long long rows, int D, float eps, float* part, bool dy_f32, hipStream_t s,
-                         const float* bet = nullptr, void* u_out = nullptr, long long u_stride = 0);
+                         const float* bet = nullptr, void* u_out = nullptr, long long u_stride = 0, int dres_period = 0);
+// dres_period != 0: dres contributes on rows r % dres_period == 0 only (its other rows are not read); only where
+// ln_bwd_periodic_ok says so
+bool ln_bwd_periodic_ok(int dt, const void* x, long long x_stride, const void* dy, long long dy_stride, const float* gam,
+                        const void* dres, const void* dx_out, long long o_stride, int D, bool dy_f32);
 // u_out: also write the normalised rows x_hat * gamma + beta (bf16 [rows][u_stride]); only where ln_bwd_emits_u says so
 bool ln_bwd_emits_u(int dt, const void* x, long long x_stride, const void* dy, long long dy_stride, const float* gam,
                     const void* dres, const void* dx_out, long long o_stride, int D, bool dy_f32, const float* bet,

@@ -309,16 +309,16 @@ void ln_fwd(Run& r, const void* x, long long xs, const float* g, const float* b,
 // the forward) is produced as well: by the backward kernel itself where it can, else by a forward launch
 void ln_bwd(Run& r, const void* x, long long xs, const void* dy, long long dys, size_t o_gam, size_t o_bet,
             const void* dres, void* dxo, void* dxo_t, long long os, long long rows, float* part, int accumulate,
-            bool dy_f32 = false, void* u_out = nullptr) {
+            bool dy_f32 = false, void* u_out = nullptr, int dres_period = 0) {
   slide_ctx* c = r.c;
   size_t rs = rs_size(c->dt), e = elem_size(c->dt);
   bool emit = u_out && ln_bwd_emits_u(c->dt, x, xs, dy, dys, c->params + o_gam, dres, dxo, os, c->D, dy_f32,
                                       c->params + o_bet, u_out, c->D);
   if (u_out && !emit) ln_fwd(r, x, xs, c->params + o_gam, c->params + o_bet, u_out, c->D, rows);
-  double bytes = (double)rows * c->D * (rs + e + (dres ? rs : 0) + rs + (rs != e ? e : 0) + (emit ? e : 0));
+  double bytes = (double)rows * c->D * (rs + e + (dres && !dres_period ? rs : 0) + rs + (rs != e ? e : 0) + (emit ? e : 0));
   launch(r, K_LN_BWD, 0, bytes, [&] {
     return launch_ln_bwd(c->dt, x, xs, dy, dys, c->params + o_gam, dres, dxo, dxo_t, os, rows, c->D, c->cfg.ln_eps, part,
-                         dy_f32, r.s, c->params + o_bet, emit ? u_out : nullptr, c->D);
+                         dy_f32, r.s, c->params + o_bet, emit ? u_out : nullptr, c->D, dres_period);
   });
   int slabs = ln_bwd_slabs(rows);
   launch(r, K_ELEMWISE, 0, 0, [&] {
@@ -544,8 +544,13 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
   char *du = ar + y.e_du, *dqkv = ar + y.e_dqkv, *dm = ar + y.e_dm;
   RowMap id{0, 0};
   float* G = c->grads;
-  launch(r, K_ELEMWISE, 0, (double)M * D * rs, [&] { return launch_fill_zero(dxA, (size_t)M * D * rs, s); });
-  if (dual) launch(r, K_ELEMWISE, 0, (double)M * D * e, [&] { return launch_fill_zero(dxAt, (size_t)M * D * e, s); });
+  // all token rows of the output gradient start at zero, the CLS rows get the final LayerNorm's backward; where the
+  // last block is pruned to its CLS rows nothing reads the other rows before that block's LN1 backward writes them
+  const bool pruned = c->L > 0 && prune_last_block(c);
+  if (!pruned) {
+    launch(r, K_ELEMWISE, 0, (double)M * D * rs, [&] { return launch_fill_zero(dxA, (size_t)M * D * rs, s); });
+    if (dual) launch(r, K_ELEMWISE, 0, (double)M * D * e, [&] { return launch_fill_zero(dxAt, (size_t)M * D * e, s); });
+  }
   char* xL = ar + y.e_x + (size_t)c->L * y.s_x;
   ln_bwd(r, xL, (long long)T * D, dfeats, D, c->o_lnfg, c->o_lnfb, nullptr, dxA, dxAt, (long long)T * D, n, lnpart,
          accumulate, true);
@@ -568,7 +573,11 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
       // the gradient of the last block's output is zero away from the CLS rows: its MLP, LN2 and projection
       // work on those n rows (leading dimension T * D); dxB is zero elsewhere
       long long TD = (long long)T * D;
-      launch(r, K_ELEMWISE, 0, (double)M * D * rs, [&] { return launch_fill_zero(dxB, (size_t)M * D * rs, s); });
+      // the LN1 backward below adds dxB to every row: it is zero away from the CLS rows, which the kernel can be
+      // told (it then reads the CLS rows only); otherwise the buffer is cleared
+      const bool periodic = ln_bwd_periodic_ok(dt, xin, D, du, D, c->params + o.ln1g, dxB, dxA, D, D, false);
+      if (!periodic)
+        launch(r, K_ELEMWISE, 0, (double)M * D * rs, [&] { return launch_fill_zero(dxB, (size_t)M * D * rs, s); });
       {
         GemmNT g{};
         g.A = dxAt; g.lda = TD; g.B = weight_t(c, wi + 3); g.ldb = D; g.M = n; g.N = F; g.K = D;
@@ -600,7 +609,7 @@ int enc_bwd(slide_ctx* c, const void* dfeats, long long n, int accumulate, void*
         g.epi = EPI_PLAIN; g.out = du; g.ldc = D;
         gemm_nt(r, g);
       }
-      ln_bwd(r, xin, D, du, D, o.ln1g, o.ln1b, dxB, dxA, dxAt, D, M, lnpart, accumulate);
+      ln_bwd(r, xin, D, du, D, o.ln1g, o.ln1b, dxB, dxA, dxAt, D, M, lnpart, accumulate, false, nullptr, periodic ? T : 0);
       continue;
     }
     // ---- MLP half: x_out = x_mid + gelu(LN2(x_mid) W1^T + b1) W2^T + b2
