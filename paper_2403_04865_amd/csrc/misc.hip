@@ -322,9 +322,45 @@ __global__ void __launch_bounds__(256) reduce_partials4_k(const float* __restric
   }
 }
 
+// Short results (bias, gain and shift gradients: a few hundred outputs, up to a thousand slabs): 16 outputs per
+// workgroup and the slabs dealt to 16 groups of lanes, so that a launch has four times the workgroups and a quarter of
+// the loads per thread of the kernel above; the 16 group sums are added as a fixed binary tree.
+__global__ void __launch_bounds__(256) reduce_partials16_k(const float* __restrict__ part, int slabs, long long stride,
+                                                           long long len, float* __restrict__ out, int accumulate) {
+  __shared__ float red[16][17];
+  const int cl = threadIdx.x & 15, q = threadIdx.x >> 4;
+  const long long i = (long long)blockIdx.x * 16 + cl;
+  float a0 = 0.f, a1 = 0.f;
+  if (i < len) {
+    int s = q;
+    for (; s + 16 < slabs; s += 32) {
+      a0 += part[(size_t)s * stride + i];
+      a1 += part[(size_t)(s + 16) * stride + i];
+    }
+    if (s < slabs) a0 += part[(size_t)s * stride + i];
+  }
+  red[q][cl] = a0 + a1;
+  __syncthreads();
+  if (q == 0 && i < len) {
+    float t[16];
+#pragma unroll
+    for (int g = 0; g < 16; ++g) t[g] = red[g][cl];
+#pragma unroll
+    for (int w = 8; w > 0; w >>= 1)
+#pragma unroll
+      for (int g = 0; g < w; ++g) t[g] += t[g + w];
+    out[i] = accumulate ? out[i] + t[0] : t[0];
+  }
+}
+
 hipError_t launch_reduce_partials(const float* part, int slabs, long long stride, long long len, float* out,
                                   int accumulate, hipStream_t s) {
   if (len <= 0) return hipSuccess;
+  if (len < 4096 && slabs >= 64) {
+    hipLaunchKernelGGL(reduce_partials16_k, dim3((unsigned)((len + 15) / 16)), dim3(256), 0, s, part, slabs, stride, len, out,
+                       accumulate);
+    return hipGetLastError();
+  }
   if (len >= 4096 && len % 4 == 0 && stride % 4 == 0 && ((uintptr_t)part & 15) == 0 && ((uintptr_t)out & 15) == 0) {
     hipLaunchKernelGGL(reduce_partials4_k, dim3((unsigned)((len / 4 + 63) / 64)), dim3(256), 0, s, part, slabs, stride,
                        len, out, accumulate);

@@ -321,6 +321,12 @@ void ln_bwd(Run& r, const void* x, long long xs, const void* dy, long long dys, 
                          dy_f32, r.s, c->params + o_bet, emit ? u_out : nullptr, c->D, dres_period);
   });
   int slabs = ln_bwd_slabs(rows);
+  if (o_bet == o_gam + (size_t)c->D) {   // gain and shift are neighbours in the parameter vector, as in a slab's partials
+    launch(r, K_ELEMWISE, 0, 0, [&] {
+      return launch_reduce_partials(part, slabs, 2LL * c->D, 2LL * c->D, c->grads + o_gam, accumulate, r.s);
+    });
+    return;
+  }
   launch(r, K_ELEMWISE, 0, 0, [&] {
     return launch_reduce_partials(part, slabs, 2LL * c->D, c->D, c->grads + o_gam, accumulate, r.s);
   });
