@@ -143,6 +143,30 @@ def test_small_256_tiles_fp32_and_bf16():
         assert not bad, (dtype, bad)
 
 
+@pytest.mark.timeout(600)
+def test_vit_s_bf16_77_tiles_ragged_counts():
+    """77 tiles of the medium workload: 15,169 token rows (59 whole 256-row tiles and 65 rows: the large-M forward and
+    input-gradient kernels with a ragged last tile, the periodic position table of the patch embedding crossing tile
+    boundaries at every phase) and a tile count that is no multiple of the 16 rows a lane group of the position-gradient
+    sum takes at a time."""
+    from slide_harness import GpuSlide, compare_step
+    from oracle import slide_oracle as so
+    cfg, _ = gen.CONFIGS["medium"]
+    ds, ws, ls = gen.SEEDS["medium"]
+    n = 77
+    prm = {k: gen.to_bf16_grid(v) for k, v in gen.make_params(cfg, ws, perturbed=True).items()}
+    X = gen.to_bf16_grid(gen.make_pixels(cfg, n, ds, first_tile=1024))
+    lab = gen.make_label(cfg, ls)
+    print(f"case medium tiles 1024..1100 n={n} dtype=1 label={lab}", flush=True)
+    g = GpuSlide(cfg, prm, 1, n)
+    out = g.step(X, lab)
+    ref = _oracle_chunked(prm, X, lab, cfg)
+    _, pool_same = so.pool_bwd(so.pool_fwd(prm, out["H"], lab, cfg)[4])
+    errs, bad, kappa = compare_step(out, ref, BF16_TOL, cfg, None, pool_same)
+    print(f"kappa={kappa:.1f} worst:", sorted(errs.items(), key=lambda kv: -kv[1])[:8], flush=True)
+    assert not bad, bad
+
+
 @pytest.mark.timeout(900)
 def test_vit_s_bf16_336_tiles_large_m_kernels_and_determinism():
     """336 consecutive tiles of the medium workload as a slide of their own: 66,192 token rows, so every
