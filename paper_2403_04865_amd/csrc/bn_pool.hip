@@ -28,6 +28,13 @@ __device__ __forceinline__ void st8(bf16* p, const float (&v)[8]) {
   *reinterpret_cast<bf16x8*>(p) = t;
 }
 
+// 8 consecutive floats of a 16-byte aligned per-channel array
+__device__ __forceinline__ void ld8f(const float* p, float (&v)[8]) {
+  const float4 lo = *reinterpret_cast<const float4*>(p), hi = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
+  v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+}
+
 constexpr int BN_MAX_BLOCKS = 4096;
 
 // Two per-channel sums over the rows of one workgroup's range.  F(row pointer offset, channel base, out a[8], out b[8])
@@ -103,22 +110,50 @@ __global__ void __launch_bounds__(256) bn_tiles_part_k(const float* __restrict__
   }
 }
 
+// A thread of the two streaming kernels below takes SPT pieces 256 pieces apart: C / 8 divides 256, so they are the
+// same 8 channels of different rows and the per-channel coefficients are fetched once for all of them (fetched per
+// piece they are four to ten 16-byte loads against two or three of data); every load instruction of a wavefront still
+// covers 1 KB of consecutive addresses, and a thread has SPT rows in flight.
+// (measured on the ResNet18 step: forward 0.56 -> 0.45 ms per launch with 2, backward 0.64 -> 0.55 ms with 4)
+constexpr int SPT_APPLY = 2, SPT_BWD = 4;
+
+template <int SPT>
 __global__ void __launch_bounds__(256) bn_apply_k(const bf16* __restrict__ x, long long chunks, int C,
                                                    const float* __restrict__ stats, const bf16* __restrict__ resid,
                                                    const float* __restrict__ rstats, int relu, bf16* __restrict__ y,
                                                    unsigned char* __restrict__ bits) {
-  const int tcols = C >> 3;
-  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (long long)gridDim.x * 256) {
-    const int c0 = (int)(i % tcols) * 8;
-    float v[8];
-    unpack8(ld16(x + i * 8), v);
+  const long long i0 = (long long)blockIdx.x * (256 * SPT) + threadIdx.x;
+  const int c0 = (int)(threadIdx.x & ((C >> 3) - 1)) * 8;   // 256 * SPT * blockIdx.x is a multiple of C / 8
+  u32x4 xv[SPT], rv[SPT];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = stats[2 * C + c0 + e] * v[e] + stats[3 * C + c0 + e];
+  for (int j = 0; j < SPT; ++j) {
+    const long long i = i0 + j * 256;
+    if (i < chunks) {
+      xv[j] = ld16(x + i * 8);
+      if (resid) rv[j] = ld16(resid + i * 8);
+    }
+  }
+  float a[8], b[8], ra[8], rb[8];
+  ld8f(stats + 2 * C + c0, a);
+  ld8f(stats + 3 * C + c0, b);
+  if (resid) {   // (without a projection the values are not used; no branch per element around the loads)
+    const float* rs = rstats ? rstats : stats;
+    ld8f(rs + 2 * C + c0, ra);
+    ld8f(rs + 3 * C + c0, rb);
+  }
+#pragma unroll
+  for (int j = 0; j < SPT; ++j) {
+    const long long i = i0 + j * 256;
+    if (i >= chunks) break;
+    float v[8];
+    unpack8(xv[j], v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = a[e] * v[e] + b[e];
     if (resid) {
       float r[8];
-      unpack8(ld16(resid + i * 8), r);
+      unpack8(rv[j], r);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += rstats ? rstats[2 * C + c0 + e] * r[e] + rstats[3 * C + c0 + e] : r[e];
+      for (int e = 0; e < 8; ++e) v[e] += rstats ? ra[e] * r[e] + rb[e] : r[e];
     }
     if (relu) {
 #pragma unroll
@@ -168,25 +203,42 @@ __global__ void __launch_bounds__(256) bn_bwd_final_k(const float* __restrict__ 
   dgamma[ch] = accumulate ? dgamma[ch] + (float)q : (float)q;
 }
 
+template <int SPT>
 __global__ void __launch_bounds__(256) bn_bwd_apply_k(const bf16* __restrict__ dy, const unsigned char* __restrict__ mask,
                                                        const bf16* __restrict__ x, long long chunks, int C,
                                                        const float* __restrict__ stats, const float* __restrict__ coef,
                                                        bf16* __restrict__ dx) {
-  const int tcols = C >> 3;
-  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks; i += (long long)gridDim.x * 256) {
-    const int c0 = (int)(i % tcols) * 8;
-    float d[8], xv[8];
-    unpack8(ld16(dy + i * 8), d);
-    unpack8(ld16(x + i * 8), xv);
-    if (mask) {
-      const unsigned m = mask[i];
+  const long long i0 = (long long)blockIdx.x * (256 * SPT) + threadIdx.x;
+  const int c0 = (int)(threadIdx.x & ((C >> 3) - 1)) * 8;
+  u32x4 dv[SPT], xv[SPT];
+  unsigned mv[SPT];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) d[e] = (m >> e) & 1u ? d[e] : 0.f;
+  for (int j = 0; j < SPT; ++j) {
+    const long long i = i0 + j * 256;
+    if (i < chunks) {
+      dv[j] = ld16(dy + i * 8);
+      xv[j] = ld16(x + i * 8);
+      mv[j] = mask ? mask[i] : 0xffu;
     }
+  }
+  float mean[8], rstd[8], ga[8], k0[8], k1[8];
+  ld8f(stats + c0, mean);
+  ld8f(stats + C + c0, rstd);
+  ld8f(stats + 2 * C + c0, ga);
+  ld8f(coef + c0, k0);
+  ld8f(coef + C + c0, k1);
+#pragma unroll
+  for (int j = 0; j < SPT; ++j) {
+    const long long i = i0 + j * 256;
+    if (i >= chunks) break;
+    float d[8], xf[8];
+    unpack8(dv[j], d);
+    unpack8(xv[j], xf);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float xh = (xv[e] - stats[c0 + e]) * stats[C + c0 + e];
-      d[e] = stats[2 * C + c0 + e] * (d[e] - coef[c0 + e] - xh * coef[C + c0 + e]);
+      d[e] = (mv[j] >> e) & 1u ? d[e] : 0.f;
+      const float xh = (xf[e] - mean[e]) * rstd[e];
+      d[e] = ga[e] * (d[e] - k0[e] - xh * k1[e]);
     }
     st8(dx + i * 8, d);
   }
@@ -318,16 +370,20 @@ hipError_t launch_bn_stats_tiles(const float* tile_part, int tiles, long long M,
 
 hipError_t launch_bn_apply(const bf16* x, long long M, int C, const float* stats, const bf16* resid, const float* rstats,
                            int relu, bf16* y, unsigned char* bits, hipStream_t s) {
-  if (!x || !stats || !y || M <= 0 || !chan_ok(C) || !al16(x) || !al16(y) || !al16(resid)) return hipErrorInvalidValue;
+  if (!x || !stats || !y || M <= 0 || !chan_ok(C) || !al16(x) || !al16(y) || !al16(resid) || !al16(stats) || !al16(rstats))
+    return hipErrorInvalidValue;
   const long long chunks = M * (C >> 3);
-  hipLaunchKernelGGL(bn_apply_k, dim3(stream_grid(chunks)), dim3(256), 0, s, x, chunks, C, stats, resid, rstats, relu, y, bits);
+  constexpr int SPT = SPT_APPLY;
+  if ((chunks + 256 * SPT - 1) / (256 * SPT) >= (1LL << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bn_apply_k<SPT>, dim3((unsigned)((chunks + 256 * SPT - 1) / (256 * SPT))), dim3(256), 0, s, x, chunks, C, stats,
+                     resid, rstats, relu, y, bits);
   return hipGetLastError();
 }
 
 hipError_t launch_bn_bwd(const bf16* dy, const unsigned char* mask, const bf16* x, long long M, int C, const float* stats,
                          float* part, float* coef, float* dgamma, float* dbeta, int accumulate, bf16* dx, hipStream_t s) {
   if (!dy || !x || !stats || !part || !coef || !dgamma || !dbeta || !dx || M <= 0 || !chan_ok(C) || !al16(dy) ||
-      !al16(x) || !al16(dx))
+      !al16(x) || !al16(dx) || !al16(stats) || !al16(coef))
     return hipErrorInvalidValue;
   const int blocks = bn_blocks(M, C);
   hipLaunchKernelGGL(bn_bwd_part_k, dim3(blocks), dim3(256), 0, s, dy, mask, x, M, C, stats, part);
@@ -337,7 +393,10 @@ hipError_t launch_bn_bwd(const bf16* dy, const unsigned char* mask, const bf16* 
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   const long long chunks = M * (C >> 3);
-  hipLaunchKernelGGL(bn_bwd_apply_k, dim3(stream_grid(chunks)), dim3(256), 0, s, dy, mask, x, chunks, C, stats, coef, dx);
+  constexpr int SPT = SPT_BWD;
+  if ((chunks + 256 * SPT - 1) / (256 * SPT) >= (1LL << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(bn_bwd_apply_k<SPT>, dim3((unsigned)((chunks + 256 * SPT - 1) / (256 * SPT))), dim3(256), 0, s, dy, mask, x,
+                     chunks, C, stats, coef, dx);
   return hipGetLastError();
 }
 
