@@ -279,40 +279,55 @@ __global__ void __launch_bounds__(256) maxpool_fwd_k(const bf16* __restrict__ x,
   *reinterpret_cast<uint2*>(arg + i * 8) = packed;
 }
 
-// one thread per input position and 8 channels: each of the (at most four) windows that contain the position hands
-// over its gradient if its stored tap is this position
+// backward: a thread owns a 2 x 2 block of input positions (2 qy + {0, 1}, 2 qx + {0, 1}) of 8 channels.  The windows
+// that cover it are (qy, qx), (qy, qx + 1), (qy + 1, qx), (qy + 1, qx + 1): each is fetched once (gradient and
+// winning taps) and handed to the positions it covers; a position adds its windows in (oy, ox) order.  No lane
+// diverges on the parity of its position, and every store instruction of a wavefront writes whole rows of channels.
 __global__ void __launch_bounds__(256) maxpool_bwd_k(const unsigned char* __restrict__ arg, const bf16* __restrict__ dy,
-                                                      bf16* __restrict__ dx, long long chunks, int H, int W, int C) {
+                                                      bf16* __restrict__ dx, long long quads, int H, int W, int C) {
   const int tcols = C >> 3, OH = H / 2, OW = W / 2;
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= chunks) return;
+  if (i >= quads) return;
   const int tc = (int)(i % tcols);
   long long pos = i / tcols;
-  const int ix = (int)(pos % W); pos /= W;
-  const int iy = (int)(pos % H);
-  const long long n = pos / H;
-  float g[8];
+  const int qx = (int)(pos % OW); pos /= OW;
+  const int qy = (int)(pos % OH);
+  const long long n = pos / OH;
+  const bool hx = qx + 1 < OW, hy = qy + 1 < OH;
+  // window (qy + a, qx + b): gradient d[a][b], taps t[a][b]; absent windows contribute nothing (tap 255 matches none)
+  float d[2][2][8];
+  uint2 t[2][2];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) g[e] = 0.f;
-  // windows (oy, ox) with 2 oy - 1 <= iy <= 2 oy + 1: oy = iy / 2 for even iy, (iy - 1) / 2 and (iy + 1) / 2 for odd iy
-  const int oy0 = iy >> 1, ny = (iy & 1) ? 2 : 1;
-  const int ox0 = ix >> 1, nx = (ix & 1) ? 2 : 1;
-  for (int a = 0; a < ny; ++a)
-    for (int b = 0; b < nx; ++b) {
-      const int oy = oy0 + a, ox = ox0 + b;
-      if (oy >= OH || ox >= OW) continue;
-      const unsigned mine = (unsigned)((iy - 2 * oy + 1) * 3 + (ix - 2 * ox + 1));
-      const long long o = (((n * OH + oy) * OW + ox) * C + tc * 8);
-      const uint2 t = *reinterpret_cast<const uint2*>(arg + o);
-      float d[8];
-      unpack8(ld16(dy + o), d);
+  for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const unsigned at = ((e < 4 ? t.x : t.y) >> (8 * (e & 3))) & 0xffu;
-        g[e] += at == mine ? d[e] : 0.f;
-      }
+    for (int b = 0; b < 2; ++b) {
+      const bool have = (a == 0 || hy) && (b == 0 || hx);
+      const long long o = (((n * OH + qy + (have ? a : 0)) * OW + qx + (have ? b : 0)) * C + tc * 8);
+      const uint2 tt = *reinterpret_cast<const uint2*>(arg + o);
+      unpack8(ld16(dy + o), d[a][b]);
+      t[a][b] = have ? tt : uint2{0xffffffffu, 0xffffffffu};
     }
-  st8(dx + i * 8, g);
+  auto take = [&](float (&g)[8], int a, int b, unsigned tap) __attribute__((always_inline)) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const unsigned at = ((e < 4 ? t[a][b].x : t[a][b].y) >> (8 * (e & 3))) & 0xffu;
+      g[e] += at == tap ? d[a][b][e] : 0.f;
+    }
+  };
+  // tap of window (oy, ox) at input (iy, ix): (iy - 2 oy + 1) * 3 + (ix - 2 ox + 1)
+  float g00[8], g01[8], g10[8], g11[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) g00[e] = g01[e] = g10[e] = g11[e] = 0.f;
+  take(g00, 0, 0, 4);
+  take(g01, 0, 0, 5); take(g01, 0, 1, 3);
+  take(g10, 0, 0, 7); take(g10, 1, 0, 1);
+  take(g11, 0, 0, 8); take(g11, 0, 1, 6); take(g11, 1, 0, 2); take(g11, 1, 1, 0);
+  bf16* o0 = dx + (((n * H + 2 * qy) * W + 2 * qx) * C + tc * 8);
+  bf16* o1 = o0 + (long long)W * C;
+  st8(o0, g00);
+  st8(o0 + C, g01);
+  st8(o1, g10);
+  st8(o1 + C, g11);
 }
 
 // one workgroup per tile; thread t sums channels t, t + 256, ... over the positions (neighbouring threads read
@@ -413,9 +428,9 @@ hipError_t launch_maxpool_bwd(const unsigned char* arg, const bf16* dy, bf16* dx
   if (!arg || !dy || !dx || n <= 0 || H <= 0 || W <= 0 || H % 2 || W % 2 || !chan_ok(C) || ((uintptr_t)arg & 7) || !al16(dy) ||
       !al16(dx))
     return hipErrorInvalidValue;
-  const long long chunks = n * H * W * (C >> 3);
-  if ((chunks + 255) / 256 >= (1LL << 31)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(maxpool_bwd_k, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, arg, dy, dx, chunks, H, W, C);
+  const long long quads = n * (H / 2) * (W / 2) * (C >> 3);
+  if ((quads + 255) / 256 >= (1LL << 31)) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(maxpool_bwd_k, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, arg, dy, dx, quads, H, W, C);
   return hipGetLastError();
 }
 
