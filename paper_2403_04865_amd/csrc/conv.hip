@@ -505,6 +505,108 @@ __global__ void __launch_bounds__(256) conv_nt_halo_k(ConvNT p, int row_tiles, i
 }
 
 // ---------------------------------------------------------------------------------------------------------------
+// stem forward with the tile's window of the padded image resident in LDS
+// ---------------------------------------------------------------------------------------------------------------
+// The stem's contraction column k = kh * 32 + kw * 4 + c is 8 pixels of image row 2 y + kh from pixel 2 x on: the
+// kernel rows of neighbouring positions overlap almost entirely.  Gathered per position (the general kernel) a tile of
+// 256 positions pulls 128 KB of operand and 32 KB of weights through the compute unit's L1, which is what bounds it.
+// Here a persistent workgroup keeps the 64 x 224 weights in LDS for its whole life (the eighth kernel row, all zero,
+// is not multiplied at all), and a tile's operand is the contiguous block of image rows 2 y0 .. 2 y_last + 6 (24 KB
+// for 256 positions of a 112 x 112 grid): copied straight into LDS once, fragments read from it at
+// (2 (y - y0) + kh) rows + 2 x pixels.  No barrier in the K loop.  The window shares its LDS with the copy of the
+// finished tile, so two workgroups fit a compute unit (with the weights in registers, 112 of them, only one did, and
+// nothing covered its write-out: 3.3 ms per launch against 4.0 for the general kernel); one works while the other
+// waits for its next window.
+// Needs: positions per image a multiple of 256 (tiles never straddle images), 64 output channels.
+constexpr int STEM_KS = 14;                       // 16-wide slices of the contraction that carry weights
+constexpr int STEM_WPT = 6;                       // 16-byte pieces of the window per thread
+constexpr int STEM_WIN = STEM_WPT * 256 * 16;     // window buffer: 24 KB
+constexpr int STEM_OUTB = 256 * (64 + 8) * 2;     // conv_tile_out's copy of the tile (bf16 path) / its statistics
+constexpr int STEM_WROW = STEM_KS * 32 + 16;      // bytes per weight row in LDS: 464 (16 rows x 16 bytes cover all banks)
+constexpr int STEM_LDS = STEM_OUTB + 64 * STEM_WROW;
+static_assert(STEM_WIN <= STEM_OUTB, "the window lies inside the region of the tile's copy");
+
+__global__ void __launch_bounds__(256, 2) stem_fwd_k(ConvNT p, int tiles, int wbytes, long long img_bytes) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  unsigned char* const win = smem;                  // dead when the tile's copy takes its place
+  unsigned char* const wsm = smem + STEM_OUTB;      // weights [64][STEM_WROW]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int li = lane & 31, h2 = lane >> 5;
+  const int XO = p.g.XO, plane = p.g.YO * p.g.XO, XS = p.g.XS, YS = p.g.YS;
+  const int rowB = XS * 8;   // bytes of an image row (4 channels)
+  int t = blockIdx.x;
+  if (t >= tiles) return;
+
+  for (int idx = tid; idx < 64 * STEM_KS * 2; idx += 256) {   // 16-byte pieces of the 64 x 224 weights
+    const int row = idx / (STEM_KS * 2), pc = idx - row * (STEM_KS * 2);
+    *reinterpret_cast<u32x4*>(wsm + row * STEM_WROW + pc * 16) = ldg16(p.W + (long long)row * 256 + pc * 8);
+  }
+  const unsigned char* const wl = wsm + li * STEM_WROW + h2 * 16;   // this lane's row of column block 0
+
+  // the window of tile tt, straight into LDS (a wavefront instruction copies 1 KB): wbytes from image row 2 y0 of its
+  // image on; pieces past the end of the whole image buffer (only ever the unused tail of the last tiles' windows)
+  // read its last piece instead
+  typedef const void __attribute__((address_space(1)))* gptr_t;
+  typedef void __attribute__((address_space(3)))* lptr_t;
+  auto fetch = [&](int tt) __attribute__((always_inline)) {
+    const int m0 = tt * 256, n = m0 / plane, y0 = (m0 - n * plane) / XO;
+    const long long woff = ((long long)(n * YS + 2 * y0) * XS) * 8;
+    const char* src = reinterpret_cast<const char*>(p.src);
+#pragma unroll
+    for (int i = 0; i < STEM_WPT; ++i) {
+      const int c = i * 4 + wave;   // 1 KB chunk of the window
+      if (c * 1024 < wbytes) {      // uniform
+        long long o = woff + c * 1024 + lane * 16;
+        o = o > img_bytes - 16 ? img_bytes - 16 : o;
+        __builtin_amdgcn_global_load_lds((gptr_t)(src + o), (lptr_t)(win + c * 1024), 16, 0, 0);
+      }
+    }
+  };
+  fetch(t);
+  __syncthreads();   // (waits for the wavefront's own loads, then for the others)
+  while (true) {
+    const int nt = t + (int)gridDim.x;
+    const bool more = nt < tiles;   // uniform
+    const int m0 = t * 256, n = m0 / plane, p0 = m0 - n * plane, y0 = p0 / XO;
+    int ab[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int pp = p0 + wave * 64 + i * 32 + li;
+      const int y = pp / XO, x = pp - y * XO;
+      ab[i] = (2 * (y - y0) * XS + 2 * x) * 8 + 16 * h2;
+    }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < STEM_KS; ++s) {
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(win + ab[i] + (s >> 1) * rowB + (s & 1) * 32);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(wl + j * 32 * STEM_WROW + s * 32);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    // (starts with a barrier: every wavefront is done with the window before the tile's copy overwrites it)
+    conv_tile_out<256, 64>(p, acc, smem, (long long)m0, 0, t, tid, lane, wave, 0);
+    if (!more) break;
+    __syncthreads();   // the copy and the statistics have been read out
+    fetch(nt);
+    __syncthreads();   // (waits for the wavefront's own loads, then for the others)
+    t = nt;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
 // weight gradient
 // ---------------------------------------------------------------------------------------------------------------
 constexpr int WBK = 32;   // rows per step
@@ -755,6 +857,33 @@ hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
       }
       if (wide) hipLaunchKernelGGL((conv_nt_halo_k<128, 128>), dim3(grid), dim3(256), lds, s, p, row_tiles, col_tiles, wrows);
       else hipLaunchKernelGGL((conv_nt_halo_k<256, 64>), dim3(grid), dim3(256), lds, s, p, row_tiles, col_tiles, wrows);
+      return hipGetLastError();
+    }
+  }
+  // the stem where its tiles never straddle images and a tile's window of image rows fits the window buffer
+  if (p.g.stem && p.N == 64 && !p.add && !p.extra && !p.g.cls && per_tile % 256 == 0) {
+    const int rows_out = (p.g.XO - 1 + 255) / p.g.XO + 1;            // output rows a tile of 256 positions can touch
+    const long long wbytes = (long long)(2 * (rows_out - 1) + 7) * p.g.XS * 8;
+    const long long img_bytes = n * p.g.YS * p.g.XS * 8;
+    if (wbytes <= STEM_WIN && img_bytes >= 16) {
+      static int cus = 0;
+      if (!cus) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        hipError_t e;
+        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
+        if ((e = hipGetDeviceProperties(&prop, dev)) != hipSuccess) return e;
+        cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+      }
+      const int tiles = (int)(p.M / 256);
+      static bool stem_attr = false;
+      if (!stem_attr) {
+        hipError_t e = hipFuncSetAttribute((const void*)stem_fwd_k, hipFuncAttributeMaxDynamicSharedMemorySize, STEM_LDS);
+        if (e != hipSuccess) return e;
+        stem_attr = true;
+      }
+      const int g = tiles < 2 * cus ? tiles : 2 * cus;   // two workgroups per compute unit
+      hipLaunchKernelGGL(stem_fwd_k, dim3((unsigned)g), dim3(256), STEM_LDS, s, p, tiles, (int)wbytes, img_bytes);
       return hipGetLastError();
     }
   }
