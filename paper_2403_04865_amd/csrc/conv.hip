@@ -724,6 +724,172 @@ __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
     }
 }
 
+// Weight gradient of the 3x3 stride-1 pad-1 layers with the step's source rows fetched once.  In the flattened row
+// order (n, y, x) the source row of tap (kh, kw) for output row m is m + (kh - 1) XO + (kw - 1) wherever it exists,
+// so the nine slices the kernel above gathers for a step of 32 rows are three bands of consecutive rows, one per
+// kh: 19 KB per step and stage instead of 40 KB, which is what that kernel is bound by (the compute unit's L1 fills
+// at about 30 bytes per clock; a step is 580 clocks of MFMA).
+// Where a tap leaves the image the flattened neighbour is a wrong row, and the contraction index IS the row, so such
+// products must vanish element by element.  They do so by construction of the band in LDS:
+//   * a band is stored in padded coordinates: after the last position of every image row comes one row of zeros, so
+//     the left neighbour of x = 0 and the right neighbour of x = XO - 1 are that row.  Output row k of the step
+//     (x0 + k positions after the step's first row at column x0) reads band row k + wraps(k) + kw,
+//     wraps(k) = (x0 + k) / XO; the transpose read takes a row address per lane, so the uneven spacing costs nothing;
+//   * a source row whose output row would need an image row above the first or below the last (kh = 0 with y = 0,
+//     kh = 2 with y = YO - 1; also the neighbouring image in the flattened order) is fetched as zeros: within band
+//     kh every source row serves output rows of one image row only.
+// The loading lane decides per band row what to fetch (row, gap, or zeros); the K loop has no masks.  Needs XO >= 8.
+// The stages being half the size, four of them fit (two workgroups per compute unit): a step's rows are requested three
+// steps ahead.  With one step of lead a step cannot be shorter than a memory latency, which, not the bytes, is what
+// the two-stage kernels of this file wait for (measured: the halved traffic alone changed nothing).
+constexpr int WBAND = 40;   // band rows per step: 32 + 2 neighbours + at most 4 gap rows, rounded to the 8 of an instruction
+constexpr int WSTAGES = 4;
+
+__global__ void __launch_bounds__(256, 2) conv_wgrad_win_k(ConvWG p) {
+  constexpr int DOUT = WBK * 64, BAND = WBAND * 64, STAGE = DOUT + 3 * BAND;   // bf16 elements
+  constexpr int NINST = WBK / 8 + 3 * (WBAND / 8);                             // 1 KB load instructions per step: 19
+  // one array per stage: the compiler waits for every load in flight into an LDS array before it reads that array,
+  // so stages that share an array cannot have loads pending while another stage is read
+  __shared__ __attribute__((aligned(128))) bf16 sg0[STAGE];
+  __shared__ __attribute__((aligned(128))) bf16 sg1[STAGE];
+  __shared__ __attribute__((aligned(128))) bf16 sg2[STAGE];
+  __shared__ __attribute__((aligned(128))) bf16 sg3[STAGE];
+  static_assert(WSTAGES == 4, "four stage arrays");
+  const int nco = p.Co >> 6, nci = p.Cs >> 6, pairs = nco * nci;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int slab = (slot / pairs) * 8 + xcd, pair = slot % pairs;
+  if (slab >= p.slabs) return;
+  const int co0 = (pair % nco) * 64, ci0 = (pair / nco) * 64;
+  const long long lo = (long long)slab * p.per;
+  const long long hi = lo + p.per < p.M ? lo + p.per : p.M;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int qa = wave >> 1, qb = wave & 1;
+  const int XO = p.g.XO, YO = p.g.YO, P1 = XO + 1;
+  const float invP1 = 1.0f / (float)P1, invXO = 1.0f / (float)XO;
+  typedef const void __attribute__((address_space(1)))* gptr_t;
+  typedef void __attribute__((address_space(3)))* lptr_t;
+
+  // (y0, x0): position of row mstep
+  auto issue = [&](long long mstep, auto stc, int y0, int x0) __attribute__((always_inline)) {   // only called with mstep < hi
+    constexpr int ST = decltype(stc)::value;
+    bf16* sa = ST == 0 ? sg0 : ST == 1 ? sg1 : ST == 2 ? sg2 : sg3;
+#pragma unroll
+    for (int i = 0; i < (NINST + 3) / 4; ++i) {
+      const int q = i * 4 + wave;   // uniform
+      if (q >= NINST) break;
+      const bf16* gp;
+      bf16* dst;
+      if (q < WBK / 8) {
+        const int r = q * 8 + (lane >> 3);
+        const int cl = ((lane & 7) ^ (((r >> 1) & 1) << 2)) * 8;
+        const long long m = mstep + r;
+        gp = m < hi ? p.dout + m * p.Co + co0 + cl : g_zero_row + cl;
+        dst = sa + q * 8 * 64;
+      } else {
+        const int b = (q - WBK / 8) / (WBAND / 8), i5 = (q - WBK / 8) - b * (WBAND / 8);
+        const int r = i5 * 8 + (lane >> 3);   // band row; band row 1 is the source row in the column of row mstep
+        const int cl = ((lane & 7) ^ (((r >> 1) & 1) << 2)) * 8;
+        // padded column of the band row, one padded image row ahead so that it is not negative
+        const int up = x0 + r - 1 + P1;
+        const int wq = (int)(((float)up + 0.5f) * invP1);   // exact: up < 200, the half keeps multiples of P1 off the edge
+        const int rem = up - wq * P1, w = wq - 1;            // image rows after the step's first one (-1 only for a gap)
+        const long long f = mstep + (long long)(b - 1) * XO + (r - 1 - w);
+        int yo = y0 + w;
+        yo = yo >= YO ? yo - YO : yo;                         // the image row of the output rows this source row serves
+        const bool ok = (rem != XO) & ((unsigned)(yo + b - 1) < (unsigned)YO) & (f >= 0) & (f < p.M);
+        gp = ok ? p.src + f * p.Cs + ci0 + cl : g_zero_row + cl;
+        dst = sa + DOUT + b * BAND + i5 * 8 * 64;
+      }
+      __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)dst, 16, 0, 0);
+    }
+  };
+
+  f32x16 acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+
+  // positions (wave-uniform) of the step being worked on and of the one being fetched
+  int cy, cx, iy, ix;
+  {
+    int n;
+    row_pos(lo < p.M ? lo : p.M - 1, p.M, p.g, n, cy, cx);
+    iy = cy; ix = cx;
+  }
+  auto adv32 = [&](int& y, int& x) __attribute__((always_inline)) {
+    x += WBK;
+    while (x >= XO) { x -= XO; y = y + 1 == YO ? 0 : y + 1; }
+  };
+  // this lane's contraction rows in a transpose read: k = kk + 8 (g / 2) + s / 4 (+ 4 for the second read of a pair)
+  const int g16 = lane >> 4, s16 = lane & 15;
+  const int kl = 8 * (g16 >> 1) + (s16 >> 2);
+  const int col = qb * 32 + 16 * (g16 & 1) + (s16 & 3) * 4, cb = col >> 3, c7 = col & 7;
+
+  // the first WSTAGES - 1 steps are requested up front; step s then requests step s + WSTAGES - 1 into the stage that
+  // step s - 1 has just left
+  if (lo < hi) { issue(lo, std::integral_constant<int, 0>{}, iy, ix); adv32(iy, ix); }
+  if (lo + WBK < hi) { issue(lo + WBK, std::integral_constant<int, 1>{}, iy, ix); adv32(iy, ix); }
+  if (lo + 2 * WBK < hi) { issue(lo + 2 * WBK, std::integral_constant<int, 2>{}, iy, ix); adv32(iy, ix); }
+  auto step = [&](long long mstep, auto stc) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stc)::value;
+    // this step's rows have landed: at most the requests of the later steps are pending (waves 0..2 issue five
+    // instructions per step, wave 3 four) ...
+    const long long later = (hi - mstep - 1) / WBK;   // steps after this one
+    if (later >= WSTAGES - 2) { if (wave < 3) wait_vm<10>(); else wait_vm<8>(); }
+    else if (later == 1) { if (wave < 3) wait_vm<5>(); else wait_vm<4>(); }
+    else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();     // ... for every wavefront, and the stage of the previous step is no longer read
+    if (mstep + (WSTAGES - 1) * WBK < hi) {
+      issue(mstep + (WSTAGES - 1) * WBK, std::integral_constant<int, (ST + WSTAGES - 1) % WSTAGES>{}, iy, ix);
+      adv32(iy, ix);
+    }
+    const bf16* sb = ST == 0 ? sg0 : ST == 1 ? sg1 : ST == 2 ? sg2 : sg3;
+    // element offsets inside a band of the rows this lane addresses, per (kk, read of the pair) and kw
+    int off[4][3];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+      const int k = (a >> 1) * 16 + (a & 1) * 4 + kl;
+      const int jb = k + (int)(((float)(cx + k) + 0.5f) * invXO);
+#pragma unroll
+      for (int kw = 0; kw < 3; ++kw) {
+        const int j = jb + kw;
+        off[a][kw] = j * 64 + ((cb ^ ((j & 2) << 1)) << 3) + c7;
+      }
+    }
+    adv32(cy, cx);
+#pragma unroll
+    for (int kk = 0; kk < WBK; kk += 16) {
+      const bf16x8 fa = frag_tr_dl(sb, qa * 32, kk, lane);
+#pragma unroll
+      for (int t = 0; t < 9; ++t) {
+        const int kh = t / 3, kw = t % 3;
+        const bf16* bp = sb + DOUT + kh * BAND;
+        s16x4 u0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + off[(kk >> 4) * 2][kw]));
+        s16x4 u1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(bp + off[(kk >> 4) * 2 + 1][kw]));
+        s16x8 r8 = {u0[0], u0[1], u0[2], u0[3], u1[0], u1[1], u1[2], u1[3]};
+        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, __builtin_bit_cast(bf16x8, r8), acc[t], 0, 0, 0);
+      }
+    }
+  };
+  for (long long mstep = lo; mstep < hi; mstep += WSTAGES * WBK) {
+    step(mstep, std::integral_constant<int, 0>{});
+    if (mstep + WBK < hi) step(mstep + WBK, std::integral_constant<int, 1>{});
+    if (mstep + 2 * WBK < hi) step(mstep + 2 * WBK, std::integral_constant<int, 2>{});
+    if (mstep + 3 * WBK < hi) step(mstep + 3 * WBK, std::integral_constant<int, 3>{});
+  }
+  const long long ldk = 9LL * p.Cs;
+  float* P = p.part + (long long)slab * p.Co * ldk;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int co = co0 + qa * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+      P[(long long)co * ldk + (long long)t * p.Cs + ci0 + qb * 32 + (lane & 31)] = acc[t][e];
+    }
+}
+
 __global__ void __launch_bounds__(256) wgrad_reduce_k(const float* __restrict__ part, int slabs, int Co, int Cin, int taps,
                                                        int ldk, float* __restrict__ dW, int accumulate) {
   const int K = taps * Cin;
@@ -933,6 +1099,11 @@ hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s) {
                                        (int)lds_of(9));
     if (e != hipSuccess) return e;
     attr_done = true;
+  }
+  // 3x3 stride-1 pad-1 layers on a grid at least 8 wide: the kernel that fetches a step's source rows once
+  if (!p.g.stem && taps == 9 && p.g.stride == 1 && p.g.pad == 1 && p.g.YS == p.g.YO && p.g.XS == p.g.XO && p.g.XO >= 8) {
+    hipLaunchKernelGGL(conv_wgrad_win_k, grid, dim3(256), 0, s, p);   // (its stages are static LDS arrays)
+    return hipGetLastError();
   }
   if (p.g.stem) hipLaunchKernelGGL((conv_wgrad_k<4, true>), grid, dim3(256), lds_of(4), s, p);
   else if (taps == 1) hipLaunchKernelGGL((conv_wgrad_k<1, false>), grid, dim3(256), lds_of(1), s, p);
