@@ -747,7 +747,6 @@ constexpr int WSTAGES = 4;
 
 __global__ void __launch_bounds__(256, 2) conv_wgrad_win_k(ConvWG p) {
   constexpr int DOUT = WBK * 64, BAND = WBAND * 64, STAGE = DOUT + 3 * BAND;   // bf16 elements
-  constexpr int NINST = WBK / 8 + 3 * (WBAND / 8);                             // 1 KB load instructions per step: 19
   // one array per stage: the compiler waits for every load in flight into an LDS array before it reads that array,
   // so stages that share an array cannot have loads pending while another stage is read
   __shared__ __attribute__((aligned(128))) bf16 sg0[STAGE];
@@ -771,38 +770,46 @@ __global__ void __launch_bounds__(256, 2) conv_wgrad_win_k(ConvWG p) {
   typedef void __attribute__((address_space(3)))* lptr_t;
 
   // (y0, x0): position of row mstep
+  // Load instructions of a step (1 KB each): wavefront w takes rows 8 w .. of the output gradient, band rows 8 w .. of
+  // all three bands (what decides a band row -- gap, image row, source row -- is the same in the three, only the
+  // image-row test and the base differ) and, w < 3, band rows 32 .. 39 of band w: five instructions (wavefront 3: four).
+  const int lr = lane >> 3;
+  const int rA = wave * 8 + lr, rB = 32 + lr;                       // band rows of the two row groups of this lane
+  const int clA = ((lane & 7) ^ (((rA >> 1) & 1) << 2)) * 8, clB = ((lane & 7) ^ (((rB >> 1) & 1) << 2)) * 8;
   auto issue = [&](long long mstep, auto stc, int y0, int x0) __attribute__((always_inline)) {   // only called with mstep < hi
     constexpr int ST = decltype(stc)::value;
     bf16* sa = ST == 0 ? sg0 : ST == 1 ? sg1 : ST == 2 ? sg2 : sg3;
-#pragma unroll
-    for (int i = 0; i < (NINST + 3) / 4; ++i) {
-      const int q = i * 4 + wave;   // uniform
-      if (q >= NINST) break;
-      const bf16* gp;
-      bf16* dst;
-      if (q < WBK / 8) {
-        const int r = q * 8 + (lane >> 3);
-        const int cl = ((lane & 7) ^ (((r >> 1) & 1) << 2)) * 8;
-        const long long m = mstep + r;
-        gp = m < hi ? p.dout + m * p.Co + co0 + cl : g_zero_row + cl;
-        dst = sa + q * 8 * 64;
-      } else {
-        const int b = (q - WBK / 8) / (WBAND / 8), i5 = (q - WBK / 8) - b * (WBAND / 8);
-        const int r = i5 * 8 + (lane >> 3);   // band row; band row 1 is the source row in the column of row mstep
-        const int cl = ((lane & 7) ^ (((r >> 1) & 1) << 2)) * 8;
-        // padded column of the band row, one padded image row ahead so that it is not negative
-        const int up = x0 + r - 1 + P1;
-        const int wq = (int)(((float)up + 0.5f) * invP1);   // exact: up < 200, the half keeps multiples of P1 off the edge
-        const int rem = up - wq * P1, w = wq - 1;            // image rows after the step's first one (-1 only for a gap)
-        const long long f = mstep + (long long)(b - 1) * XO + (r - 1 - w);
-        int yo = y0 + w;
-        yo = yo >= YO ? yo - YO : yo;                         // the image row of the output rows this source row serves
-        const bool ok = (rem != XO) & ((unsigned)(yo + b - 1) < (unsigned)YO) & (f >= 0) & (f < p.M);
-        gp = ok ? p.src + f * p.Cs + ci0 + cl : g_zero_row + cl;
-        dst = sa + DOUT + b * BAND + i5 * 8 * 64;
-      }
-      __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)dst, 16, 0, 0);
+    {
+      const long long m = mstep + rA;   // (rA is also this lane's output-gradient row)
+      const bf16* gp = m < hi ? p.dout + m * p.Co + co0 + clA : g_zero_row + clA;
+      __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(sa + wave * 8 * 64), 16, 0, 0);
     }
+    // band row r of band b: padded column (one padded image row ahead so that it is not negative), image rows after
+    // the step's first one (-1 only for a gap), source row relative to the row in the column of row mstep
+    auto band_row = [&](int r, int cl, auto bc) __attribute__((always_inline)) {
+      const int up = x0 + r - 1 + P1;
+      const int wq = (int)(((float)up + 0.5f) * invP1);   // exact: up < 200, the half keeps multiples of P1 off the edge
+      const int rem = up - wq * P1, w = wq - 1;
+      int yo = y0 + w;
+      yo = yo >= YO ? yo - YO : yo;                        // the image row of the output rows this source row serves
+      const bool okx = rem != XO;
+      const int rel = r - 1 - w;
+      auto one = [&](int b, bf16* dst) __attribute__((always_inline)) {
+        const long long f = mstep + (long long)((b - 1) * XO + rel);
+        const bool ok = okx & ((unsigned)(yo + b - 1) < (unsigned)YO) & (f >= 0) & (f < p.M);
+        const bf16* gp = ok ? p.src + f * p.Cs + ci0 + cl : g_zero_row + cl;
+        __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)dst, 16, 0, 0);
+      };
+      constexpr int B = decltype(bc)::value;
+      if constexpr (B < 0) {
+#pragma unroll
+        for (int b = 0; b < 3; ++b) one(b, sa + DOUT + b * BAND + wave * 8 * 64);
+      } else {
+        one(wave, sa + DOUT + wave * BAND + 4 * 8 * 64);
+      }
+    };
+    band_row(rA, clA, std::integral_constant<int, -1>{});
+    if (wave < 3) band_row(rB, clB, std::integral_constant<int, 0>{});
   };
 
   f32x16 acc[9];
@@ -826,6 +833,7 @@ __global__ void __launch_bounds__(256, 2) conv_wgrad_win_k(ConvWG p) {
   const int g16 = lane >> 4, s16 = lane & 15;
   const int kl = 8 * (g16 >> 1) + (s16 >> 2);
   const int col = qb * 32 + 16 * (g16 & 1) + (s16 & 3) * 4, cb = col >> 3, c7 = col & 7;
+  const int swz0 = (cb << 3) + c7, swz1 = ((cb ^ 4) << 3) + c7;
 
   // the first WSTAGES - 1 steps are requested up front; step s then requests step s + WSTAGES - 1 into the stage that
   // step s - 1 has just left
@@ -855,7 +863,7 @@ __global__ void __launch_bounds__(256, 2) conv_wgrad_win_k(ConvWG p) {
 #pragma unroll
       for (int kw = 0; kw < 3; ++kw) {
         const int j = jb + kw;
-        off[a][kw] = j * 64 + ((cb ^ ((j & 2) << 1)) << 3) + c7;
+        off[a][kw] = j * 64 + ((j & 2) ? swz1 : swz0);   // rows 2, 3, 6, 7, ... hold their pieces in the other half
       }
     }
     adv32(cy, cx);
