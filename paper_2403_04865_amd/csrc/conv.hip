@@ -233,7 +233,10 @@ __device__ __forceinline__ void conv_tile_out(const ConvNT& p, const f32x16 (&ac
   }
 }
 
-template <int BM, int BN, int NST, bool STEM>
+// PW: a pointwise (1x1, stride 1) layer: produced row m reads source row m, so none of the position arithmetic below
+// is needed (a tile of such a layer is one to eight K steps long, and what a wavefront spends per tile outside the
+// MFMAs -- some 1000 vector instructions in the general form -- is what bounds it)
+template <int BM, int BN, int NST, bool STEM, bool PW = false>
 __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int col_tiles) {
   constexpr int STAGE = (BM + BN) * CBK;   // bf16 elements per stage
   constexpr int WN = BN / 64, WM = 4 / WN;
@@ -272,8 +275,13 @@ __global__ void __launch_bounds__(256) conv_nt_dl_k(ConvNT p, int row_tiles, int
 #pragma unroll
   for (int j = 0; j < AG; ++j) {
     const int R = (j * 4 + wave) * 8 + lr;
-    launch_pos(m0 + R, p.M, p.g, pn[j], py[j], px[j]);
     pc[j] = (ls ^ ((R >> 1) & 7)) * 8;
+    if (PW) {
+      rb[j] = p.src + (m0 + R) * p.Cs + pc[j];
+      rm[j] = m0 + R < p.M ? 1u : 0u;
+      continue;
+    }
+    launch_pos(m0 + R, p.M, p.g, pn[j], py[j], px[j]);
     if (!STEM) {
       const int yb = p.g.transposed ? (py[j] + p.g.pad) >> sh : py[j] * p.g.stride - p.g.pad;
       const int xb = p.g.transposed ? (px[j] + p.g.pad) >> sh : px[j] * p.g.stride - p.g.pad;
@@ -631,7 +639,8 @@ __device__ __forceinline__ bf16x8 frag_tr_dl(const bf16* B, int c0, int k0, int 
   return __builtin_bit_cast(bf16x8, r);
 }
 
-template <int TAPS, bool STEM>
+// PW: a pointwise (1x1, stride 1) layer: the source row of output row m is row m (no position arithmetic per step)
+template <int TAPS, bool STEM, bool PW = false>
 __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
   constexpr int SL = 1 + TAPS, SLICE = WBK * 64, STAGE = SL * SLICE;   // bf16 elements
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -656,11 +665,16 @@ __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
   auto issue = [&](long long mstep, int st) {   // only called with mstep < hi
     const long long m = mstep + r;
     const bool ok = m < hi;
-    int n, y, x;
-    row_pos(ok ? m : hi - 1, p.M, p.g, n, y, x);
     bf16* sa = S + st * STAGE + wave * 8 * 64;
     const bf16* gd = ok ? p.dout + m * p.Co + co0 + cl : g_zero_row + cl;
     __builtin_amdgcn_global_load_lds((gptr_t)gd, (lptr_t)sa, 16, 0, 0);
+    if (PW) {
+      const bf16* gp = ok ? p.src + m * p.Cs + ci0 + cl : g_zero_row + cl;
+      __builtin_amdgcn_global_load_lds((gptr_t)gp, (lptr_t)(sa + SLICE), 16, 0, 0);
+      return;
+    }
+    int n, y, x;
+    row_pos(ok ? m : hi - 1, p.M, p.g, n, y, x);
     if (STEM) {   // the four 64-column groups of the stem's 256 contraction columns stand where the taps stand
 #pragma unroll
       for (int t = 0; t < TAPS; ++t) {
@@ -1077,8 +1091,20 @@ hipError_t launch_conv_nt(const ConvNT& p, hipStream_t s) {
       e = hipFuncSetAttribute((const void*)conv_nt_dl_k<128, 128, NST, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
     if (e == hipSuccess)
       e = hipFuncSetAttribute((const void*)conv_nt_dl_k<256, 64, NST, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_n);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)conv_nt_dl_k<128, 128, NST, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_w);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)conv_nt_dl_k<256, 64, NST, false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_n);
     if (e != hipSuccess) return e;
     attr_done = true;
+  }
+  // pointwise layers (and their input gradients): produced row m reads source row m
+  const bool pw = !p.g.stem && !p.g.cls && p.g.KH == 1 && p.g.KW == 1 && p.g.stride == 1 && p.g.pad == 0 && p.g.YS == p.g.YO &&
+                  p.g.XS == p.g.XO;
+  if (pw) {
+    if (wide) hipLaunchKernelGGL((conv_nt_dl_k<128, 128, NST, false, true>), dim3(grid), dim3(256), lds_w, s, p, row_tiles, col_tiles);
+    else hipLaunchKernelGGL((conv_nt_dl_k<256, 64, NST, false, true>), dim3(grid), dim3(256), lds_n, s, p, row_tiles, col_tiles);
+    return hipGetLastError();
   }
   if (wide && p.g.stem) hipLaunchKernelGGL((conv_nt_dl_k<128, 128, NST, true>), dim3(grid), dim3(256), lds_w, s, p, row_tiles, col_tiles);
   else if (wide) hipLaunchKernelGGL((conv_nt_dl_k<128, 128, NST, false>), dim3(grid), dim3(256), lds_w, s, p, row_tiles, col_tiles);
@@ -1114,6 +1140,8 @@ hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s) {
     return hipGetLastError();
   }
   if (p.g.stem) hipLaunchKernelGGL((conv_wgrad_k<4, true>), grid, dim3(256), lds_of(4), s, p);
+  else if (taps == 1 && p.g.stride == 1 && p.g.pad == 0 && p.g.YS == p.g.YO && p.g.XS == p.g.XO)
+    hipLaunchKernelGGL((conv_wgrad_k<1, false, true>), grid, dim3(256), lds_of(1), s, p);
   else if (taps == 1) hipLaunchKernelGGL((conv_wgrad_k<1, false>), grid, dim3(256), lds_of(1), s, p);
   else hipLaunchKernelGGL((conv_wgrad_k<9, false>), grid, dim3(256), lds_of(9), s, p);
   return hipGetLastError();
