@@ -738,6 +738,98 @@ __global__ void __launch_bounds__(256) conv_wgrad_k(ConvWG p) {
     }
 }
 
+// Weight gradient of the pointwise (1x1, stride 1) layers.  With 64 x 64 blocks a step of 32 rows is two MFMAs per
+// wavefront between two barriers, and the Co / 64 x Cs / 64 workgroups of a slab each fetch their operands' slices
+// again.  Here a workgroup owns BO x BI = 128 x 128, 256 x 64 or 64 x 256 of (c_out, c_in), a wavefront 64 x 64 of it
+// (eight MFMAs per step), the source row of output row m is row m, three stages in separate LDS arrays, loads two
+// steps ahead.
+template <int BO, int BI>
+__global__ void __launch_bounds__(256, 2) conv_wgrad_pw_k(ConvWG p) {
+  constexpr int SA = BO / 64, SB = BI / 64, SL = SA + SB, SLICE = WBK * 64, STAGE = SL * SLICE;   // bf16 elements
+  constexpr int WI = SB >= 4 ? 4 : SB >= 2 ? 2 : 1;   // wavefronts along c_in, the others along c_out
+  static_assert(SA * SB == 4, "four 64 x 64 blocks, one per wavefront");
+  __shared__ __attribute__((aligned(128))) bf16 sg0[STAGE];
+  __shared__ __attribute__((aligned(128))) bf16 sg1[STAGE];
+  __shared__ __attribute__((aligned(128))) bf16 sg2[STAGE];
+  const int nco = p.Co / BO, nci = p.Cs / BI, pairs = nco * nci;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int slab = (slot / pairs) * 8 + xcd, pair = slot % pairs;
+  if (slab >= p.slabs) return;
+  const int co0 = (pair % nco) * BO, ci0 = (pair / nco) * BI;
+  const long long lo = (long long)slab * p.per;
+  const long long hi = lo + p.per < p.M ? lo + p.per : p.M;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wi = wave % WI, wo = wave / WI;
+  const int r = wave * 8 + (lane >> 3);                          // this lane's row of every slice
+  const int cl = ((lane & 7) ^ (((r >> 1) & 1) << 2)) * 8;       // the piece it fetches (its slot holds piece slot ^ ...)
+  typedef const void __attribute__((address_space(1)))* gptr_t;
+  typedef void __attribute__((address_space(3)))* lptr_t;
+
+  auto issue = [&](long long mstep, auto stc) __attribute__((always_inline)) {   // only called with mstep < hi
+    constexpr int ST = decltype(stc)::value;
+    bf16* sa = (ST == 0 ? sg0 : ST == 1 ? sg1 : sg2) + wave * 8 * 64;
+    const long long m = mstep + r;
+    const bool ok = m < hi;
+    const bf16* gd = ok ? p.dout + m * p.Co + co0 + cl : g_zero_row + cl;
+    const bf16* gs = ok ? p.src + m * p.Cs + ci0 + cl : g_zero_row + cl;
+    const int so = ok ? 64 : 0;   // the zero row has one slice
+#pragma unroll
+    for (int sl = 0; sl < SA; ++sl) __builtin_amdgcn_global_load_lds((gptr_t)(gd + sl * so), (lptr_t)(sa + sl * SLICE), 16, 0, 0);
+#pragma unroll
+    for (int sl = 0; sl < SB; ++sl) __builtin_amdgcn_global_load_lds((gptr_t)(gs + sl * so), (lptr_t)(sa + (SA + sl) * SLICE), 16, 0, 0);
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+  if (lo < hi) issue(lo, std::integral_constant<int, 0>{});
+  if (lo + WBK < hi) issue(lo + WBK, std::integral_constant<int, 1>{});
+  auto step = [&](long long mstep, auto stc) __attribute__((always_inline)) {
+    constexpr int ST = decltype(stc)::value;
+    // this step's rows have landed (the next step's SL requests may be pending) ...
+    if (mstep + WBK < hi) wait_vm<SL>(); else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();     // ... for every wavefront, and the stage of the previous step is no longer read
+    if (mstep + 2 * WBK < hi) issue(mstep + 2 * WBK, std::integral_constant<int, (ST + 2) % 3>{});
+    const bf16* sb = ST == 0 ? sg0 : ST == 1 ? sg1 : sg2;
+#pragma unroll
+    for (int kk = 0; kk < WBK; kk += 16) {
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) fa[a] = frag_tr_dl(sb + wo * SLICE, a * 32, kk, lane);
+#pragma unroll
+      for (int b = 0; b < 2; ++b) fb[b] = frag_tr_dl(sb + (SA + wi) * SLICE, b * 32, kk, lane);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    }
+  };
+  for (long long mstep = lo; mstep < hi; mstep += 3 * WBK) {
+    step(mstep, std::integral_constant<int, 0>{});
+    if (mstep + WBK < hi) step(mstep + WBK, std::integral_constant<int, 1>{});
+    if (mstep + 2 * WBK < hi) step(mstep + 2 * WBK, std::integral_constant<int, 2>{});
+  }
+  // block rows = output channels (e / 4) * 8 + (l / 32) * 4 + e % 4, block columns = input channels l % 32.  A slab
+  // without rows still writes its zeros: the reduction adds every slab.
+  const long long ldk = p.Cs;
+  float* P = p.part + (long long)slab * p.Co * ldk;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int co = co0 + wo * 64 + a * 32 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
+        P[(long long)co * ldk + ci0 + wi * 64 + b * 32 + (lane & 31)] = acc[a][b][e];
+      }
+}
+
 // Weight gradient of the 3x3 stride-1 pad-1 layers with the step's source rows fetched once.  In the flattened row
 // order (n, y, x) the source row of tap (kh, kw) for output row m is m + (kh - 1) XO + (kw - 1) wherever it exists,
 // so the nine slices the kernel above gathers for a step of 32 rows are three bands of consecutive rows, one per
@@ -1140,8 +1232,17 @@ hipError_t launch_conv_wgrad(const ConvWG& p, hipStream_t s) {
     return hipGetLastError();
   }
   if (p.g.stem) hipLaunchKernelGGL((conv_wgrad_k<4, true>), grid, dim3(256), lds_of(4), s, p);
-  else if (taps == 1 && p.g.stride == 1 && p.g.pad == 0 && p.g.YS == p.g.YO && p.g.XS == p.g.XO)
-    hipLaunchKernelGGL((conv_wgrad_k<1, false, true>), grid, dim3(256), lds_of(1), s, p);
+  else if (taps == 1 && p.g.stride == 1 && p.g.pad == 0 && p.g.YS == p.g.YO && p.g.XS == p.g.XO) {
+    const unsigned g8 = (unsigned)((p.slabs + 7) / 8 * 8);
+    if (p.Co % 128 == 0 && p.Cs % 128 == 0)
+      hipLaunchKernelGGL((conv_wgrad_pw_k<128, 128>), dim3(g8 * (p.Co / 128) * (p.Cs / 128)), dim3(256), 0, s, p);
+    else if (p.Co % 256 == 0)
+      hipLaunchKernelGGL((conv_wgrad_pw_k<256, 64>), dim3(g8 * (p.Co / 256) * (p.Cs / 64)), dim3(256), 0, s, p);
+    else if (p.Cs % 256 == 0)
+      hipLaunchKernelGGL((conv_wgrad_pw_k<64, 256>), dim3(g8 * (p.Co / 64) * (p.Cs / 256)), dim3(256), 0, s, p);
+    else
+      hipLaunchKernelGGL((conv_wgrad_k<1, false, true>), grid, dim3(256), lds_of(1), s, p);
+  }
   else if (taps == 1) hipLaunchKernelGGL((conv_wgrad_k<1, false>), grid, dim3(256), lds_of(1), s, p);
   else hipLaunchKernelGGL((conv_wgrad_k<9, false>), grid, dim3(256), lds_of(9), s, p);
   return hipGetLastError();
